@@ -1,0 +1,170 @@
+"""ctypes binding of libpi0_hip.so: the same names as include/pi0.h, argument marshalling only.
+
+PyTorch is used for what it is good at here: owning device memory and streams.  Every step of
+the forward pass runs in the library's HIP kernels; there is no fallback path, and loading
+fails loudly if the shared library has not been built.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpi0_hip.so")
+
+EXPORTS = ["pi0_create", "pi0_destroy", "pi0_weights_bytes", "pi0_workspace_bytes", "pi0_load_weights",
+           "pi0_prefill", "pi0_denoise", "pi0_infer", "pi0_debug_taps_elems", "pi0_debug_forward",
+           "pi0_set_graph_mode", "pi0_kernel_count", "pi0_strerror", "pi0_last_hip_error"]
+
+PI0_OK, PI0_EINVAL, PI0_ESTATE, PI0_ENOMEM, PI0_EFORMAT, PI0_EHIP = 0, -1, -2, -3, -4, -5
+
+_FIELDS = ["vis_layers", "vis_width", "vis_heads", "vis_mlp", "img_size", "patch", "llm_layers", "llm_width",
+           "llm_q_heads", "head_dim", "llm_mlp", "exp_layers", "exp_width", "exp_mlp", "state_dim", "action_dim",
+           "chunk", "steps", "vocab", "max_views", "max_prompt"]
+
+
+class Pi0ConfigC(ctypes.Structure):
+    _fields_ = [(f, ctypes.c_int32) for f in _FIELDS]
+
+
+def to_c_config(cfg) -> Pi0ConfigC:
+    """Any object with the pi0_config field names (e.g. synth.Pi0Config) -> C struct."""
+    return Pi0ConfigC(**{f: int(getattr(cfg, f)) for f in _FIELDS})
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                               "(there is no CPU fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+        cfgp = ctypes.POINTER(Pi0ConfigC)
+        L.pi0_create.argtypes = [cfgp, ctypes.POINTER(vp)]
+        L.pi0_create.restype = i32
+        L.pi0_destroy.argtypes = [vp]
+        L.pi0_destroy.restype = None
+        L.pi0_weights_bytes.argtypes = [cfgp]
+        L.pi0_weights_bytes.restype = sz
+        L.pi0_workspace_bytes.argtypes = [cfgp]
+        L.pi0_workspace_bytes.restype = sz
+        L.pi0_load_weights.argtypes = [vp, vp, sz, vp, sz, vp]
+        L.pi0_load_weights.restype = i32
+        L.pi0_prefill.argtypes = [vp, vp, i32, vp, i32, vp]
+        L.pi0_prefill.restype = i32
+        L.pi0_denoise.argtypes = [vp, vp, vp, vp, vp]
+        L.pi0_denoise.restype = i32
+        L.pi0_infer.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp, vp]
+        L.pi0_infer.restype = i32
+        L.pi0_debug_taps_elems.argtypes = [cfgp, i32, i32]
+        L.pi0_debug_taps_elems.restype = sz
+        L.pi0_debug_forward.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp, vp, sz, vp]
+        L.pi0_debug_forward.restype = i32
+        L.pi0_set_graph_mode.argtypes = [vp, i32]
+        L.pi0_set_graph_mode.restype = i32
+        L.pi0_kernel_count.argtypes = [vp, i32, i32]
+        L.pi0_kernel_count.restype = i32
+        L.pi0_strerror.argtypes = [i32]
+        L.pi0_strerror.restype = ctypes.c_char_p
+        L.pi0_last_hip_error.argtypes = [vp]
+        L.pi0_last_hip_error.restype = i32
+        _lib = L
+    return _lib
+
+
+class Pi0Error(RuntimeError):
+    def __init__(self, code: int, hip: int = 0):
+        self.code = code
+        self.hip = hip
+        msg = lib().pi0_strerror(code).decode()
+        super().__init__(f"pi0 error {code}: {msg}" + (f" (hipError_t {hip})" if hip else ""))
+
+
+def pi0_weights_bytes(cfg) -> int:
+    c = to_c_config(cfg)
+    return int(lib().pi0_weights_bytes(ctypes.byref(c)))
+
+
+def pi0_workspace_bytes(cfg) -> int:
+    c = to_c_config(cfg)
+    return int(lib().pi0_workspace_bytes(ctypes.byref(c)))
+
+
+def pi0_debug_taps_elems(cfg, n_views: int, n_prompt: int) -> int:
+    c = to_c_config(cfg)
+    return int(lib().pi0_debug_taps_elems(ctypes.byref(c), n_views, n_prompt))
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+class Pi0:
+    """Thin handle over pi0_ctx.  All tensor arguments are torch CUDA tensors (device memory)."""
+
+    def __init__(self, cfg):
+        self.cfg = cfg
+        self._c = to_c_config(cfg)
+        self._ctx = ctypes.c_void_p()
+        rc = lib().pi0_create(ctypes.byref(self._c), ctypes.byref(self._ctx))
+        if rc != PI0_OK:
+            raise Pi0Error(rc)
+        self.workspace = None
+
+    def close(self):
+        if self._ctx:
+            lib().pi0_destroy(self._ctx)
+            self._ctx = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc: int):
+        if rc != PI0_OK:
+            raise Pi0Error(rc, lib().pi0_last_hip_error(self._ctx) if rc == PI0_EHIP else 0)
+
+    @staticmethod
+    def _stream(stream) -> Optional[int]:
+        if stream is None:
+            return None
+        return int(stream.cuda_stream) or None
+
+    def pi0_load_weights(self, d_blob, stream=None):
+        """d_blob: uint16/bfloat16 CUDA tensor holding the canonical blob.  Allocates the workspace
+        through torch (the caller-owned memory of the C ABI) and keeps it alive on this object."""
+        import torch
+        need = pi0_workspace_bytes(self.cfg)
+        self.workspace = torch.empty(need + 256, dtype=torch.uint8, device=d_blob.device)
+        base = self.workspace.data_ptr()
+        self._ws_ptr = (base + 255) // 256 * 256
+        nbytes = d_blob.numel() * d_blob.element_size()
+        self._check(lib().pi0_load_weights(self._ctx, _ptr(d_blob), nbytes, self._ws_ptr, need, self._stream(stream)))
+
+    def pi0_prefill(self, d_images, n_views, d_prompt_ids=None, n_prompt=0, stream=None):
+        self._check(lib().pi0_prefill(self._ctx, _ptr(d_images), n_views, _ptr(d_prompt_ids), n_prompt, self._stream(stream)))
+
+    def pi0_denoise(self, d_state, d_noise, d_actions, stream=None):
+        self._check(lib().pi0_denoise(self._ctx, _ptr(d_state), _ptr(d_noise), _ptr(d_actions), self._stream(stream)))
+
+    def pi0_infer(self, d_images, n_views, d_prompt_ids, n_prompt, d_state, d_noise, d_actions, stream=None):
+        self._check(lib().pi0_infer(self._ctx, _ptr(d_images), n_views, _ptr(d_prompt_ids), n_prompt, _ptr(d_state),
+                                    _ptr(d_noise), _ptr(d_actions), self._stream(stream)))
+
+    def pi0_debug_forward(self, d_images, n_views, d_prompt_ids, n_prompt, d_state, d_noise, d_actions, d_taps, stream=None):
+        self._check(lib().pi0_debug_forward(self._ctx, _ptr(d_images), n_views, _ptr(d_prompt_ids), n_prompt, _ptr(d_state),
+                                            _ptr(d_noise), _ptr(d_actions), _ptr(d_taps), d_taps.numel(),
+                                            self._stream(stream)))
+
+    def pi0_set_graph_mode(self, enabled: bool):
+        self._check(lib().pi0_set_graph_mode(self._ctx, 1 if enabled else 0))
+
+    def pi0_kernel_count(self, n_views: int, n_prompt: int) -> int:
+        return int(lib().pi0_kernel_count(self._ctx, n_views, n_prompt))

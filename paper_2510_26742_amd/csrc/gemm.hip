@@ -1,0 +1,430 @@
+// bf16 MFMA GEMM family for gfx950 with fused prologue statistics and epilogues.
+//
+// Orientation: the packed weights are the MFMA A operand (32 output features x 16 k per
+// fragment, read straight from HBM in fragment order, one coalesced 1 KiB read per wave), the
+// activations are the B operand (32 tokens x 16 k, staged through LDS).  The accumulator of
+// v_mfma_f32_32x32x16_bf16 then holds C^T: lane l owns token (l % 32) and, in register r, output
+// feature 8*(r/4) + 4*(l/32) + r%4.  Per-token quantities (norm statistics, RoPE position) are
+// per-lane scalars and partner features (RoPE pairs, gate/up pairs) sit in neighbouring
+// registers of one lane, so every epilogue of Table 2 (bias, residual, activation, RMS / LN applied
+// after accumulation as in Section 4.4, RoPE of Section 3.2, gated MLP of Section 4.2) is lane-local.
+#include "pi0_internal.h"
+
+#define LDS_PAD 8
+
+__device__ __forceinline__ float gelu_tanh_f(float x) {
+  float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
+  float t = 1.0f - 2.0f / (1.0f + __expf(2.0f * u));
+  return 0.5f * x * (1.0f + t);
+}
+
+__device__ __forceinline__ bf16x8 zero8() {
+  bf16x8 z;
+#pragma unroll
+  for (int j = 0; j < 8; j++) z[j] = (bf16)0.0f;
+  return z;
+}
+
+template <int MB, int WN, int WK, int PRO, int EPI>
+__global__ __launch_bounds__(64 * WN * WK) void gemm_kernel(GemmParams p) {
+  constexpr int NT = 64 * WN * WK;        // threads
+  constexpr int CHUNK_K = 64 * WK;        // k extent of one block chunk
+  constexpr int LDX = CHUNK_K + LDS_PAD;  // LDS row stride (elements)
+  constexpr int ROWS = MB * 32;
+  constexpr int PPR = WK * 8;             // 16-byte pieces per row per chunk
+  constexpr int RPP = NT / PPR;           // rows staged per pass
+  constexpr int NP = ROWS / RPP;          // passes
+  constexpr int RING = 8;                 // weight fragments in flight per wave (2 sub-chunks)
+  static_assert(ROWS % RPP == 0, "staging must tile the rows");
+
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16* xs = reinterpret_cast<bf16*>(smem_raw);                       // [2][ROWS][LDX]
+  float* stat = reinterpret_cast<float*>(smem_raw + (size_t)2 * ROWS * LDX * sizeof(bf16));  // [2][ROWS]
+
+  const int t = threadIdx.x;
+  const int lane = t & 63;
+  const int wave = t >> 6;
+  const int wn = wave % WN;
+  const int wk = wave / WN;
+
+  // XCD-aware tile order: consecutive block ids go to different XCDs (separate L2s), so the
+  // m-tiles that share one weight panel are given ids with equal (id % 8).
+  const int nblocks_n = (p.n_tiles + WN - 1) / WN;
+  const int id = blockIdx.x;
+  const int slot = id >> 3;
+  const int nb = (id & 7) + 8 * (slot / p.m_tiles);
+  const int mt = slot % p.m_tiles;
+  if (nb >= nblocks_n) return;
+  const int m0 = mt * ROWS;
+  const int nt = nb * WN + wn;
+  const bool wave_active = nt < p.n_tiles;
+
+  const int k_pad = p.W.k_pad;
+  const int kbeg = blockIdx.y * p.k_per_split;
+  const int kend = min(kbeg + p.k_per_split, k_pad);
+  const int NC = (kend - kbeg + CHUNK_K - 1) / CHUNK_K;
+  const int KC16 = k_pad >> 4;
+
+  // ---- staging helpers -------------------------------------------------------------------
+  const int st_row = t / PPR;
+  const int st_kp = t % PPR;
+  bf16x8 xr[NP];
+  float s1[NP], s2[NP];
+#pragma unroll
+  for (int i = 0; i < NP; i++) { s1[i] = 0.f; s2[i] = 0.f; }
+
+  auto load_x = [&](int c) {
+    const int gk = kbeg + c * CHUNK_K + st_kp * 8;
+#pragma unroll
+    for (int i = 0; i < NP; i++) {
+      const int row = m0 + st_row + i * RPP;
+      if (row < p.M && gk < kend) {
+        xr[i] = *reinterpret_cast<const bf16x8*>(p.X + (size_t)row * p.ldx + gk);
+      } else {
+        xr[i] = zero8();
+      }
+    }
+  };
+  auto store_x = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < NP; i++) {
+      const int row = st_row + i * RPP;
+      *reinterpret_cast<bf16x8*>(xs + ((size_t)buf * ROWS + row) * LDX + st_kp * 8) = xr[i];
+      if (PRO != PRO_NONE) {
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+          float v = (float)xr[i][j];
+          s1[i] += v;
+          s2[i] += v * v;
+        }
+      }
+    }
+  };
+
+  // ---- weight stream -----------------------------------------------------------------------
+  const bf16* wbase = p.W.w + ((size_t)(wave_active ? nt : 0) * KC16) * 512 + lane * 8;
+  auto load_w = [&](int f) -> bf16x8 {   // f = running fragment number of this wave
+    int kc16 = (kbeg >> 4) + (f >> 2) * (CHUNK_K >> 4) + wk * 4 + (f & 3);
+    kc16 = min(kc16, KC16 - 1);
+    return *reinterpret_cast<const bf16x8*>(wbase + (size_t)kc16 * 512);
+  };
+
+  f32x16 acc[MB];
+#pragma unroll
+  for (int mb = 0; mb < MB; mb++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) acc[mb][r] = 0.f;
+
+  bf16x8 wring[RING];
+#pragma unroll
+  for (int i = 0; i < RING; i++) wring[i] = load_w(i);
+  load_x(0);
+  store_x(0);
+  __syncthreads();
+
+  const int lq = lane & 31;
+  const int lh = lane >> 5;
+  int cur = 0;
+  for (int c0 = 0; c0 < NC; c0 += RING / 4) {
+#pragma unroll
+    for (int u = 0; u < RING / 4; u++) {
+      const int c = c0 + u;
+      if (c < NC) {
+        const bool more = (c + 1) < NC;
+        if (more) load_x(c + 1);
+        const bool sub_in = (kbeg + c * CHUNK_K + wk * 64) < kend;
+#pragma unroll
+        for (int s = 0; s < 4; s++) {
+          const bf16x8 a = wring[u * 4 + s];
+          wring[u * 4 + s] = load_w(c * 4 + s + RING);
+          if (wave_active && sub_in) {
+#pragma unroll
+            for (int mb = 0; mb < MB; mb++) {
+              const bf16x8 b = *reinterpret_cast<const bf16x8*>(
+                  xs + ((size_t)cur * ROWS + mb * 32 + lq) * LDX + wk * 64 + s * 16 + lh * 8);
+              acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[mb], 0, 0, 0);
+            }
+          }
+        }
+        if (more) store_x(cur ^ 1);
+        __syncthreads();
+        cur ^= 1;
+      }
+    }
+  }
+
+  // ---- row statistics ----------------------------------------------------------------------
+  if (PRO != PRO_NONE) {
+#pragma unroll
+    for (int i = 0; i < NP; i++) {
+      float a = s1[i], b = s2[i];
+#pragma unroll
+      for (int off = 1; off < PPR; off <<= 1) {
+        a += __shfl_xor(a, off, 64);
+        b += __shfl_xor(b, off, 64);
+      }
+      if (st_kp == 0) {
+        stat[st_row + i * RPP] = a;
+        stat[ROWS + st_row + i * RPP] = b;
+      }
+    }
+  }
+
+  // ---- reduction across the waves that split K -------------------------------------------
+  if (WK > 1) {
+    float* red = reinterpret_cast<float*>(smem_raw);   // aliases the X buffers (all reads done)
+    if (wk > 0) {
+#pragma unroll
+      for (int mb = 0; mb < MB; mb++)
+#pragma unroll
+        for (int r = 0; r < 16; r++)
+          red[((((size_t)(wk - 1) * WN + wn) * MB + mb) * 16 + r) * 64 + lane] = acc[mb][r];
+    }
+    __syncthreads();
+    if (wk == 0) {
+#pragma unroll
+      for (int w = 1; w < WK; w++)
+#pragma unroll
+        for (int mb = 0; mb < MB; mb++)
+#pragma unroll
+          for (int r = 0; r < 16; r++)
+            acc[mb][r] += red[((((size_t)(w - 1) * WN + wn) * MB + mb) * 16 + r) * 64 + lane];
+    }
+  } else {
+    __syncthreads();
+  }
+  if (wk != 0 || !wave_active) return;
+
+  // ---- epilogue --------------------------------------------------------------------------------
+  const float inv_k = 1.0f / (float)p.k_true;
+#pragma unroll
+  for (int mb = 0; mb < MB; mb++) {
+    const int ml = mb * 32 + lq;
+    const int m = m0 + ml;
+    if (m >= p.M) continue;
+    float rs = 1.f, mu = 0.f;
+    if (PRO == PRO_RMS) {
+      rs = rsqrtf(stat[ROWS + ml] * inv_k + 1e-6f);
+    } else if (PRO == PRO_LN) {
+      mu = stat[ml] * inv_k;
+      float var = stat[ROWS + ml] * inv_k - mu * mu;
+      rs = rsqrtf(fmaxf(var, 0.f) + 1e-6f);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      const int n4 = nt * 32 + 8 * i + 4 * lh;
+      float v[4];
+#pragma unroll
+      for (int j = 0; j < 4; j++) v[j] = acc[mb][4 * i + j];
+      if (EPI == EPI_PARTIAL) {
+        f32x4 o = {v[0], v[1], v[2], v[3]};
+        *reinterpret_cast<f32x4*>(p.out_f32 + ((size_t)blockIdx.y * p.M + m) * p.ldo + n4) = o;
+        continue;
+      }
+      if (PRO == PRO_RMS) {
+#pragma unroll
+        for (int j = 0; j < 4; j++) v[j] *= rs;
+      } else if (PRO == PRO_LN) {
+        const f32x4 cs = *reinterpret_cast<const f32x4*>(p.colsum + n4);
+#pragma unroll
+        for (int j = 0; j < 4; j++) v[j] = rs * (v[j] - mu * cs[j]);
+      }
+      if (p.bias != nullptr) {
+        const f32x4 bb = *reinterpret_cast<const f32x4*>(p.bias + n4);
+#pragma unroll
+        for (int j = 0; j < 4; j++) v[j] += bb[j];
+      }
+      if (EPI == EPI_RESID) {
+        if (n4 < p.n_valid) {
+          if (p.resid != nullptr) {
+            const int rr = p.resid_mod > 0 ? (m % p.resid_mod) : m;
+            const f32x4 r4 = *reinterpret_cast<const f32x4*>(p.resid + (size_t)rr * p.ldo + n4);
+#pragma unroll
+            for (int j = 0; j < 4; j++) v[j] += r4[j];
+          }
+          const int mo = m + p.row_offset;
+          f32x4 o = {v[0], v[1], v[2], v[3]};
+          *reinterpret_cast<f32x4*>(p.out_f32 + (size_t)mo * p.ldo + n4) = o;
+          bf16x4 ob = {(bf16)v[0], (bf16)v[1], (bf16)v[2], (bf16)v[3]};
+          *reinterpret_cast<bf16x4*>(p.out_bf16 + (size_t)mo * p.ldo2 + n4) = ob;
+        }
+      } else if (EPI == EPI_BF16) {
+        if (n4 < p.n_valid) {
+          if (p.act == ACT_GELU) {
+#pragma unroll
+            for (int j = 0; j < 4; j++) v[j] = gelu_tanh_f(v[j]);
+          }
+          bf16x4 ob = {(bf16)v[0], (bf16)v[1], (bf16)v[2], (bf16)v[3]};
+          *reinterpret_cast<bf16x4*>(p.out_bf16 + (size_t)m * p.ldo + n4) = ob;
+        }
+      } else if (EPI == EPI_GEGLU) {
+        bf16x2 ob = {(bf16)(gelu_tanh_f(v[0]) * v[1]), (bf16)(gelu_tanh_f(v[2]) * v[3])};
+        *reinterpret_cast<bf16x2*>(p.out_bf16 + (size_t)m * p.ldo + (n4 >> 1)) = ob;
+      } else if (EPI == EPI_EULER) {
+        if (m >= 1) {
+#pragma unroll
+          for (int j = 0; j < 4; j++) {
+            if (n4 + j < p.n_valid) p.out_f32[(size_t)(m - 1) * p.ldo + n4 + j] += p.dt * v[j];
+          }
+        }
+      } else if (EPI == EPI_QKV) {
+        const int S16 = p.dqk_pad >> 4;
+        const int key = m;
+        const int kc = key >> 5, kk = key & 31;
+        if (n4 < p.q_cols + p.k_cols) {
+          const bool is_q = n4 < p.q_cols;
+          const int nl = is_q ? n4 : n4 - p.q_cols;
+          if (p.rope != nullptr) {
+            // packed head layout: row 2i = dim i, row 2i+1 = dim i + 128
+            const int head = nl >> 8;
+            const int i0 = (nl & 255) >> 1;          // even
+            const float* cs = p.rope + ((size_t)(p.pos0 + m) * 128 + i0) * 2;
+            const f32x4 c4 = *reinterpret_cast<const f32x4*>(cs);   // cos i0, sin i0, cos i0+1, sin i0+1
+            const float lo0 = v[0] * c4[0] - v[1] * c4[1], hi0 = v[1] * c4[0] + v[0] * c4[1];
+            const float lo1 = v[2] * c4[2] - v[3] * c4[3], hi1 = v[3] * c4[2] + v[2] * c4[3];
+            const bf16x2 lo = {(bf16)lo0, (bf16)lo1};
+            const bf16x2 hi = {(bf16)hi0, (bf16)hi1};
+            if (is_q) {
+              bf16* dst = p.out_bf16 + (size_t)m * p.ldo + head * 256 + i0;
+              *reinterpret_cast<bf16x2*>(dst) = lo;
+              *reinterpret_cast<bf16x2*>(dst + 128) = hi;
+            } else {
+              bf16* dst = p.kfrag + ((size_t)kc * S16) * 512 + kk * 8;
+              const int d0 = i0, d1 = i0 + 128;
+              *reinterpret_cast<bf16x2*>(dst + (size_t)(d0 >> 4) * 512 + ((d0 & 15) >> 3) * 256 + (d0 & 7)) = lo;
+              *reinterpret_cast<bf16x2*>(dst + (size_t)(d1 >> 4) * 512 + ((d1 & 15) >> 3) * 256 + (d1 & 7)) = hi;
+            }
+          } else {
+            const int head = nl / p.head_dim;
+            const int d = nl - head * p.head_dim;    // multiple of 4
+            const bf16x4 ob = {(bf16)v[0], (bf16)v[1], (bf16)v[2], (bf16)v[3]};
+            if (is_q) {
+              *reinterpret_cast<bf16x4*>(p.out_bf16 + (size_t)m * p.ldo + head * p.dqk_pad + d) = ob;
+            } else {
+              bf16* dst = p.kfrag + ((size_t)head * p.kv_chunks + kc) * S16 * 512 + kk * 8;
+              *reinterpret_cast<bf16x4*>(dst + (size_t)(d >> 4) * 512 + ((d & 15) >> 3) * 256 + (d & 7)) = ob;
+            }
+          }
+        } else {
+          const int nl = n4 - p.q_cols - p.k_cols;
+          const int head = nl / p.head_dim;
+          const int d = nl - head * p.head_dim;
+          if (head < p.kv_heads) {
+            const int s2 = kk >> 4, g = (kk & 15) >> 3, hh = (kk & 7) >> 2, jp = kk & 3;
+            bf16* dst = p.vfrag + (((size_t)head * p.kv_chunks + kc) * p.nvb) * 1024 + s2 * 512 + hh * 256 + 4 * g + jp;
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+              const int dd = d + j;
+              dst[(size_t)(dd >> 5) * 1024 + (dd & 31) * 8] = (bf16)v[j];
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+template <int MB, int WN, int WK>
+static constexpr int smem_bytes_for() {
+  return 2 * (MB * 32) * (64 * WK + LDS_PAD) * 2 + 2 * (MB * 32) * 4;
+}
+
+int gemm_smem_bytes(int tile) {
+  switch (tile) {
+    case TILE_M256_N128: return smem_bytes_for<8, 4, 1>();
+    case TILE_M64_K4: return smem_bytes_for<2, 1, 4>();
+    case TILE_M64_K8: return smem_bytes_for<2, 1, 8>();
+    case TILE_M64_N4: return smem_bytes_for<2, 4, 1>();
+    default: return -1;
+  }
+}
+
+template <int MB, int WN, int WK, int PRO, int EPI>
+static hipError_t launch_one(hipStream_t s, const GemmParams& p, int z) {
+  const int nblocks_n = (p.n_tiles + WN - 1) / WN;
+  dim3 grid(8 * ((nblocks_n + 7) / 8) * p.m_tiles, z, 1);
+  dim3 block(64 * WN * WK, 1, 1);
+  constexpr int smem = smem_bytes_for<MB, WN, WK>();
+  gemm_kernel<MB, WN, WK, PRO, EPI><<<grid, block, smem, s>>>(p);
+  return hipGetLastError();
+}
+
+template <int MB, int WN, int WK, int PRO, int EPI>
+static hipError_t set_attr() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<MB, WN, WK, PRO, EPI>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes_for<MB, WN, WK>());
+}
+
+// The instantiations that exist.  X(tile id, MB, WN, WK, PRO, EPI)
+#define GEMM_VARIANTS(X)                                   \
+  X(TILE_M256_N128, 8, 4, 1, PRO_NONE, EPI_RESID)          \
+  X(TILE_M256_N128, 8, 4, 1, PRO_NONE, EPI_PARTIAL)        \
+  X(TILE_M256_N128, 8, 4, 1, PRO_LN, EPI_QKV)              \
+  X(TILE_M256_N128, 8, 4, 1, PRO_LN, EPI_BF16)             \
+  X(TILE_M256_N128, 8, 4, 1, PRO_LN, EPI_RESID)            \
+  X(TILE_M256_N128, 8, 4, 1, PRO_RMS, EPI_QKV)             \
+  X(TILE_M256_N128, 8, 4, 1, PRO_RMS, EPI_GEGLU)           \
+  X(TILE_M64_K4, 2, 1, 4, PRO_NONE, EPI_RESID)             \
+  X(TILE_M64_K4, 2, 1, 4, PRO_RMS, EPI_QKV)                \
+  X(TILE_M64_K4, 2, 1, 4, PRO_RMS, EPI_GEGLU)              \
+  X(TILE_M64_K8, 2, 1, 8, PRO_NONE, EPI_RESID)             \
+  X(TILE_M64_K8, 2, 1, 8, PRO_RMS, EPI_EULER)
+
+hipError_t gemm_init_attributes() {
+#define X(T, MB, WN, WK, PRO, EPI)                                    \
+  {                                                                   \
+    hipError_t e = set_attr<MB, WN, WK, PRO, EPI>();                  \
+    if (e != hipSuccess) return e;                                    \
+  }
+  GEMM_VARIANTS(X)
+#undef X
+  return hipSuccess;
+}
+
+hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmParams& p, int z_splits) {
+  // Host-side shape checks: everything the kernel's indexing assumes.
+  if (p.X == nullptr || p.W.w == nullptr || p.M <= 0 || z_splits < 1) return hipErrorInvalidValue;
+  if (p.W.k_pad % 64 != 0 || p.W.n_pad % 32 != 0 || p.n_tiles * 32 != p.W.n_pad) return hipErrorInvalidValue;
+  if (p.ldx < p.W.k_pad || p.ldx % 8 != 0) return hipErrorInvalidValue;
+  if (p.k_per_split % 64 != 0 || (long)p.k_per_split * z_splits < p.W.k_pad) return hipErrorInvalidValue;
+  if (pro != PRO_NONE && z_splits != 1) return hipErrorInvalidValue;
+  if (epi != EPI_PARTIAL && z_splits != 1) return hipErrorInvalidValue;
+  if (p.m_tiles < 1) return hipErrorInvalidValue;
+#define X(T, MB, WN, WK, PRO, EPI)                                             \
+  if (tile == T && pro == PRO && epi == EPI) {                                  \
+    if (p.m_tiles * MB * 32 < p.M) return hipErrorInvalidValue;                 \
+    return launch_one<MB, WN, WK, PRO, EPI>(s, p, z_splits);                    \
+  }
+  GEMM_VARIANTS(X)
+#undef X
+  return hipErrorInvalidValue;
+}
+
+// ------------------------------------------------------------------------------------------------
+// split-K reduction (fixed summation order -> run-to-run bitwise determinism)
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(ReduceParams p) {
+  const int n4s = p.N >> 2;
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (size_t)p.M * n4s) return;
+  const int m = (int)(idx / n4s);
+  const int n = (int)(idx % n4s) * 4;
+  f32x4 a = {0.f, 0.f, 0.f, 0.f};
+  for (int z = 0; z < p.Z; z++) {
+    const f32x4 v = *reinterpret_cast<const f32x4*>(p.part + ((size_t)z * p.M + m) * p.ldp + n);
+    a += v;
+  }
+  if (p.bias != nullptr) a += *reinterpret_cast<const f32x4*>(p.bias + n);
+  if (p.resid != nullptr) a += *reinterpret_cast<const f32x4*>(p.resid + (size_t)m * p.ldo + n);
+  *reinterpret_cast<f32x4*>(p.out_f32 + (size_t)m * p.ldo + n) = a;
+  const bf16x4 ob = {(bf16)a[0], (bf16)a[1], (bf16)a[2], (bf16)a[3]};
+  *reinterpret_cast<bf16x4*>(p.out_bf16 + (size_t)m * p.ldo2 + n) = ob;
+}
+
+hipError_t launch_splitk_reduce(hipStream_t s, const ReduceParams& p) {
+  if (p.N % 4 != 0 || p.ldp < p.N || p.ldo < p.N || p.ldo2 < p.N || p.M <= 0 || p.Z < 1) return hipErrorInvalidValue;
+  const size_t total = (size_t)p.M * (p.N / 4);
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, p);
+  return hipGetLastError();
+}

@@ -1,0 +1,307 @@
+// Load-time weight packing (the graph simplifications of Section 3.2 applied to the weights) and
+// the small non-GEMM kernels of the pass (patch extraction, prompt embedding, state token,
+// folded action/time embedding of Table 2 rows 1x32x1024 and 63x32x1024).
+#include "pi0_internal.h"
+
+// ------------------------------------------------------------------------------------------------
+// packed row n -> (source matrix, source column); returns false for padding rows
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ bool map_row(const PackSrc& s, int n, int& which, int& col) {
+  if (n >= s.n_true) return false;
+  if (s.rowmap == ROWMAP_PAIR) {
+    which = n & 1;
+    col = n >> 1;
+    return true;
+  }
+  if (s.rowmap == ROWMAP_ROPE_QKV) {
+    const int qc = s.q_heads * 256;
+    if (n < qc + 256) {
+      const bool is_q = n < qc;
+      const int nl = is_q ? n : n - qc;
+      const int head = nl >> 8, pp = nl & 255;
+      const int d = (pp >> 1) + 128 * (pp & 1);
+      which = is_q ? 0 : 1;
+      col = head * 256 + d;
+      return true;
+    }
+    which = 2;
+    col = n - qc - 256;
+    return true;
+  }
+  int c = n;
+  for (int i = 0; i < 3; i++) {
+    if (c < s.cols[i]) {
+      which = i;
+      col = c;
+      return true;
+    }
+    c -= s.cols[i];
+  }
+  return false;
+}
+
+__device__ __forceinline__ float k_scale(const PackSrc& s, int k) {
+  if (s.kscale == KSCALE_GAIN) return (float)s.gain[k];
+  if (s.kscale == KSCALE_ONE_PLUS) return 1.0f + (float)s.gain[k];
+  return 1.0f;
+}
+
+// one thread per 16-byte fragment piece: (n-tile, k-step, lane)
+__global__ __launch_bounds__(256) void pack_weights_kernel(PackSrc s, bf16* dst, int n_pad, int k_pad) {
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t total = (size_t)(n_pad >> 5) * (k_pad >> 4) * 64;
+  if (idx >= total) return;
+  const int lane = (int)(idx & 63);
+  const size_t f = idx >> 6;
+  const int kc = (int)(f % (size_t)(k_pad >> 4));
+  const int nt = (int)(f / (size_t)(k_pad >> 4));
+  const int n = nt * 32 + (lane & 31);
+  const int k0 = kc * 16 + (lane >> 5) * 8;
+  int which = 0, col = 0;
+  const bool live = map_row(s, n, which, col);
+  bf16x8 out;
+#pragma unroll
+  for (int j = 0; j < 8; j++) {
+    const int k = k0 + j;
+    float v = 0.f;
+    if (live && k < s.K) v = (float)s.src[which][(size_t)k * s.cols[which] + col] * k_scale(s, k);
+    out[j] = (bf16)v;
+  }
+  *reinterpret_cast<bf16x8*>(dst + idx * 8) = out;
+}
+
+hipError_t launch_pack_weights(hipStream_t st, const PackSrc& s, bf16* dst, int n_pad, int k_pad) {
+  if (n_pad % 32 != 0 || k_pad % 64 != 0 || s.n_true > n_pad || s.K > k_pad || dst == nullptr) return hipErrorInvalidValue;
+  const size_t total = (size_t)(n_pad >> 5) * (k_pad >> 4) * 64;
+  hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, s, dst, n_pad, k_pad);
+  return hipGetLastError();
+}
+
+// colsum[n] = sum_k bf16(scale_k * W[k][col])   (exactly the values the GEMM multiplies)
+// bias_out[n] = sum_k ln_bias[k] * W[k][col] + bias_src[which][col]
+struct FoldArgs {
+  PackSrc s;
+  const bf16* ln_bias;
+  const bf16* bias_src[3];
+  float* colsum;
+  float* bias_out;
+  int n_pad;
+};
+__global__ __launch_bounds__(256) void fold_vectors_kernel(FoldArgs a) {
+  const int n = blockIdx.x * 256 + threadIdx.x;
+  if (n >= a.n_pad) return;
+  int which = 0, col = 0;
+  const bool live = map_row(a.s, n, which, col);
+  float cs = 0.f, bo = 0.f;
+  if (live) {
+    if (a.colsum != nullptr || a.ln_bias != nullptr) {
+      for (int k = 0; k < a.s.K; k++) {
+        const float w = (float)a.s.src[which][(size_t)k * a.s.cols[which] + col];
+        cs += (float)(bf16)(w * k_scale(a.s, k));
+        if (a.ln_bias != nullptr) bo += (float)a.ln_bias[k] * w;
+      }
+    }
+    if (a.bias_src[which] != nullptr) bo += (float)a.bias_src[which][col];
+  }
+  if (a.colsum != nullptr) a.colsum[n] = cs;
+  if (a.bias_out != nullptr) a.bias_out[n] = bo;
+}
+
+hipError_t launch_fold_vectors(hipStream_t st, const PackSrc& s, const bf16* ln_bias, const bf16* const bias_src[3],
+                               float* colsum, float* bias_out, int n_pad) {
+  if (n_pad <= 0 || s.n_true > n_pad) return hipErrorInvalidValue;
+  FoldArgs a;
+  a.s = s;
+  a.ln_bias = ln_bias;
+  for (int i = 0; i < 3; i++) a.bias_src[i] = bias_src ? bias_src[i] : nullptr;
+  a.colsum = colsum;
+  a.bias_out = bias_out;
+  a.n_pad = n_pad;
+  hipLaunchKernelGGL(fold_vectors_kernel, dim3((n_pad + 255) / 256), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void bf16_to_f32_kernel(const bf16* src, float* dst, size_t n) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) dst[i] = (float)src[i];
+}
+hipError_t launch_bf16_to_f32(hipStream_t st, const bf16* src, float* dst, size_t n) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(bf16_to_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, src, dst, n);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void copy_u16_kernel(const uint16_t* src, uint16_t* dst, size_t n) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (; i < n; i += stride) dst[i] = src[i];
+}
+hipError_t launch_copy_bf16(hipStream_t st, const bf16* src, bf16* dst, size_t n) {
+  if (n == 0) return hipSuccess;
+  const unsigned blocks = (unsigned)((n + 255) / 256 < 65536 ? (n + 255) / 256 : 65536);
+  hipLaunchKernelGGL(copy_u16_kernel, dim3(blocks), dim3(256), 0, st, reinterpret_cast<const uint16_t*>(src),
+                     reinterpret_cast<uint16_t*>(dst), n);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void copy_f32_kernel(const float* src, float* dst, size_t n) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) dst[i] = src[i];
+}
+hipError_t launch_copy_f32(hipStream_t st, const float* src, float* dst, size_t n) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(copy_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, src, dst, n);
+  return hipGetLastError();
+}
+
+// bytes must be a multiple of 16, dst 16-byte aligned
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint4* dst, size_t n16) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * 256;
+  const uint4 z = {0u, 0u, 0u, 0u};
+  for (; i < n16; i += stride) dst[i] = z;
+}
+hipError_t launch_fill_zero(hipStream_t st, void* dst, size_t bytes) {
+  if (bytes == 0) return hipSuccess;
+  if (bytes % 16 != 0 || (reinterpret_cast<uintptr_t>(dst) & 15) != 0) return hipErrorInvalidValue;
+  const size_t n16 = bytes / 16;
+  const unsigned blocks = (unsigned)((n16 + 255) / 256 < 16384 ? (n16 + 255) / 256 : 16384);
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, st, reinterpret_cast<uint4*>(dst), n16);
+  return hipGetLastError();
+}
+
+// Folded action/time encoder (Section 3.2): rows r < A:  W_fold[r][n] = sum_j wa[r][j] * wt1[j][n];
+// rows r = A + k: bias_k[n] = sum_j ba[j] * wt1[j][n] + sum_j tau_k[j] * wt1[X + j][n] + bt1[n].
+__global__ __launch_bounds__(256) void time_fold_kernel(const bf16* wa, const bf16* ba, const bf16* wt1, const bf16* bt1,
+                                                        const float* tau, int A, int X, int steps, float* wfold,
+                                                        float* bias_tab) {
+  const int n = blockIdx.x * 256 + threadIdx.x;
+  const int r = blockIdx.y;
+  if (n >= X) return;
+  float acc = 0.f;
+  if (r < A) {
+    for (int j = 0; j < X; j++) acc += (float)wa[(size_t)r * X + j] * (float)wt1[(size_t)j * X + n];
+    wfold[(size_t)r * X + n] = acc;
+  } else {
+    const int k = r - A;
+    for (int j = 0; j < X; j++) acc += (float)ba[j] * (float)wt1[(size_t)j * X + n];
+    for (int j = 0; j < X; j++) acc += tau[(size_t)k * X + j] * (float)wt1[(size_t)(X + j) * X + n];
+    bias_tab[(size_t)k * X + n] = acc + (float)bt1[n];
+  }
+}
+hipError_t launch_time_fold(hipStream_t st, const bf16* wa, const bf16* ba, const bf16* wt1, const bf16* bt1,
+                            const float* tau, int action_dim, int X, int steps, float* wfold, float* bias_tab) {
+  hipLaunchKernelGGL(time_fold_kernel, dim3((X + 255) / 256, action_dim + steps), dim3(256), 0, st, wa, ba, wt1, bt1, tau,
+                     action_dim, X, steps, wfold, bias_tab);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// images [V][img][img][3] fp32 -> patch vectors bf16 [V*T][ld], order (dy, dx, c); columns
+// >= patch*patch*3 are left untouched (they are zero from load time).
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void patchify_kernel(const float* images, int n_views, int img, int patch, bf16* out,
+                                                       int ld) {
+  const int per_side = img / patch;
+  const int T = per_side * per_side;
+  const int pd = patch * patch * 3;
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (size_t)n_views * T * pd) return;
+  const int e = (int)(idx % pd);
+  const int tok = (int)(idx / pd);
+  const int v = tok / T, tt = tok % T;
+  const int py = tt / per_side, px = tt % per_side;
+  const int c = e % 3, dx = (e / 3) % patch, dy = e / (3 * patch);
+  const float val = images[(((size_t)v * img + (py * patch + dy)) * img + (px * patch + dx)) * 3 + c];
+  out[(size_t)tok * ld + e] = (bf16)val;
+}
+hipError_t launch_patchify(hipStream_t st, const float* images, int n_views, int img, int patch, bf16* out, int ld) {
+  const int per_side = img / patch;
+  const size_t total = (size_t)n_views * per_side * per_side * patch * patch * 3;
+  if (ld < patch * patch * 3) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(patchify_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, images, n_views, img, patch,
+                     out, ld);
+  return hipGetLastError();
+}
+
+// prompt rows: out[row0 + i][:] = scale * table[clamp(ids[i])][:]
+__global__ __launch_bounds__(256) void embed_prompt_kernel(const int32_t* ids, int n, const bf16* table, int vocab, int E,
+                                                           float scale, float* out_f32, bf16* out_bf16, int row0) {
+  const int i = blockIdx.y;
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (i >= n || c >= E) return;
+  int id = ids[i];
+  id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);   // out-of-range ids are clamped, never read out of bounds
+  const float v = scale * (float)table[(size_t)id * E + c];
+  out_f32[(size_t)(row0 + i) * E + c] = v;
+  out_bf16[(size_t)(row0 + i) * E + c] = (bf16)v;
+}
+hipError_t launch_embed_prompt(hipStream_t st, const int32_t* ids, int n, const bf16* table, int vocab, int E, float scale,
+                               float* out_f32, bf16* out_bf16, int row0) {
+  if (n <= 0) return hipSuccess;
+  if (ids == nullptr || table == nullptr || vocab <= 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(embed_prompt_kernel, dim3((E + 255) / 256, n), dim3(256), 0, st, ids, n, table, vocab, E, scale,
+                     out_f32, out_bf16, row0);
+  return hipGetLastError();
+}
+
+// state token: out[n] = sum_j state[j] * ws[j][n] + bs[n]   (Table 2 row 1x32x1024)
+__global__ __launch_bounds__(256) void state_token_kernel(const float* state, int sd, const float* ws, const float* bs, int X,
+                                                          float* out) {
+  const int n = blockIdx.x * 256 + threadIdx.x;
+  if (n >= X) return;
+  float acc = bs[n];
+  for (int j = 0; j < sd; j++) acc += state[j] * ws[(size_t)j * X + n];
+  out[n] = acc;
+}
+hipError_t launch_state_token(hipStream_t st, const float* state, int state_dim, const float* ws, const float* bs, int X,
+                              float* out) {
+  hipLaunchKernelGGL(state_token_kernel, dim3((X + 255) / 256), dim3(256), 0, st, state, state_dim, ws, bs, X, out);
+  return hipGetLastError();
+}
+
+// Table 2 row 63x32x1024 (bias, silu) with the folded weights; also re-seeds suffix row 0 of the
+// expert's residual stream with the state token at the start of every Euler step.
+// grid.y = chunk + 1: row r < chunk -> z[r]; row chunk -> state token copy and zero z[chunk].
+__global__ __launch_bounds__(256) void action_embed_kernel(const float* x, int chunk, int A, const float* wfold,
+                                                           const float* bias_k, int X, bf16* z, const float* state_tok,
+                                                           float* y_f32, bf16* y_bf16) {
+  const int n = blockIdx.x * 256 + threadIdx.x;
+  const int r = blockIdx.y;
+  if (n >= X) return;
+  if (r < chunk) {
+    float acc = bias_k[n];
+    for (int j = 0; j < A; j++) acc += x[(size_t)r * A + j] * wfold[(size_t)j * X + n];
+    const float sv = acc / (1.0f + __expf(-acc));
+    z[(size_t)r * X + n] = (bf16)sv;
+  } else {
+    z[(size_t)chunk * X + n] = (bf16)0.0f;
+    const float s = state_tok[n];
+    y_f32[n] = s;
+    y_bf16[n] = (bf16)s;
+  }
+}
+hipError_t launch_action_embed(hipStream_t st, const float* x, int chunk, int action_dim, const float* wfold,
+                               const float* bias_k, int X, bf16* z, const float* state_tok, float* y_f32, bf16* y_bf16) {
+  hipLaunchKernelGGL(action_embed_kernel, dim3((X + 255) / 256, chunk + 1), dim3(256), 0, st, x, chunk, action_dim, wfold,
+                     bias_k, X, z, state_tok, y_f32, y_bf16);
+  return hipGetLastError();
+}
+
+// natural-order fp32 dump of one layer's fragment-ordered key / value cache (head dim 256)
+__global__ __launch_bounds__(256) void unpack_kv_kernel(const bf16* kfrag, const bf16* vfrag, int P, float* k_out,
+                                                        float* v_out) {
+  const int d = threadIdx.x;
+  const int key = blockIdx.x;
+  if (key >= P) return;
+  const int kc = key >> 5, kk = key & 31;
+  const size_t ka = ((size_t)kc * 16 + (d >> 4)) * 512 + (((d & 15) >> 3) * 32 + kk) * 8 + (d & 7);
+  k_out[(size_t)key * 256 + d] = (float)kfrag[ka];
+  const int s2 = kk >> 4, g = (kk & 15) >> 3, hh = (kk & 7) >> 2, jp = kk & 3;
+  const size_t va = ((((size_t)kc * 8 + (d >> 5)) * 2 + s2) * 64 + hh * 32 + (d & 31)) * 8 + 4 * g + jp;
+  v_out[(size_t)key * 256 + d] = (float)vfrag[va];
+}
+hipError_t launch_unpack_kv(hipStream_t st, const bf16* kfrag, const bf16* vfrag, int P, float* k_out, float* v_out) {
+  hipLaunchKernelGGL(unpack_kv_kernel, dim3(P), dim3(256), 0, st, kfrag, vfrag, P, k_out, v_out);
+  return hipGetLastError();
+}

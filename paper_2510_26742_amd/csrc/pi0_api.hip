@@ -1,0 +1,945 @@
+// Host side of the pi0 library: geometry checks, workspace layout, load-time packing, the kernel
+// sequence of one inference (Table 2 of the paper, top to bottom) and its HIP-graph capture/replay
+// (Section 3.1: record the kernel stream once, replay it with constant kernels and pointers).
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <map>
+#include <new>
+#include <vector>
+
+#include "pi0_internal.h"
+
+namespace {
+
+struct Dims {
+  int T, PD, PDp, Dv, Hv, hdv, Fv, Fv_np, Fv_kp;
+  int E, H, F, X, Fx;
+  int S, A, SD, steps;
+  int maxI, maxP, maxPc, maxpos;
+  int Lv, Ll, Le;
+};
+
+bool derive_dims(const pi0_config& c, Dims& d) {
+  if (c.vis_layers < 1 || c.llm_layers < 2 || c.exp_layers != c.llm_layers) return false;
+  if (c.patch < 1 || c.img_size < c.patch || c.img_size % c.patch != 0) return false;
+  d.T = (c.img_size / c.patch) * (c.img_size / c.patch);
+  if (d.T % 32 != 0) return false;
+  d.PD = c.patch * c.patch * 3;
+  d.PDp = round_up(d.PD, 64);
+  d.Dv = c.vis_width;
+  d.Hv = c.vis_heads;
+  if (d.Dv < 64 || d.Dv % 64 != 0 || d.Hv < 1 || d.Dv % d.Hv != 0) return false;
+  d.hdv = d.Dv / d.Hv;
+  if (d.hdv % 4 != 0 || d.hdv <= 64 || d.hdv > 80) return false;
+  d.Fv = c.vis_mlp;
+  if (d.Fv < 32 || d.Fv % 4 != 0) return false;
+  d.Fv_np = round_up(d.Fv, 32);
+  d.Fv_kp = round_up(d.Fv, 64);
+  d.E = c.llm_width;
+  d.H = c.llm_q_heads;
+  d.F = c.llm_mlp;
+  d.X = c.exp_width;
+  d.Fx = c.exp_mlp;
+  if (c.head_dim != 256 || d.H < 1 || d.H > 64) return false;
+  if (d.E < 64 || d.E % 64 != 0 || d.F < 64 || d.F % 64 != 0) return false;
+  if (d.X < 64 || d.X % 64 != 0 || d.Fx < 64 || d.Fx % 64 != 0) return false;
+  if (c.chunk + 1 != 64) return false;
+  d.S = 64;
+  d.A = c.action_dim;
+  d.SD = c.state_dim;
+  if (d.A < 1 || d.A > 32 || d.SD < 1 || d.SD > 32) return false;
+  d.steps = c.steps;
+  if (d.steps < 1 || d.steps > 1000) return false;
+  if (c.max_views < 1 || c.max_views > 8 || c.max_prompt < 0 || c.max_prompt > 4096) return false;
+  if (c.vocab < 0) return false;
+  d.maxI = c.max_views * d.T;
+  d.maxP = d.maxI + c.max_prompt;
+  d.maxPc = ceil_div(d.maxP, 32);
+  d.maxpos = d.maxPc * 32 + d.S;
+  d.Lv = c.vis_layers;
+  d.Ll = c.llm_layers;
+  d.Le = c.exp_layers;
+  return true;
+}
+
+// ---- canonical blob layout (element offsets), in the order documented in pi0.h -------------------
+struct BlobVis { size_t ln1g, ln1b, wq, bq, wk, bk, wv, bv, wo, bo, ln2g, ln2b, w1, b1, w2, b2; };
+struct BlobTr { size_t g_attn, wq, wk, wv, wo, g_mlp, wg, wu, wd; };
+struct BlobLayout {
+  size_t patch_w, patch_b, pos;
+  std::vector<BlobVis> vis;
+  size_t lnfg, lnfb, proj_w, proj_b;
+  size_t embed;
+  std::vector<BlobTr> llm, exp;
+  size_t state_w, state_b, ain_w, ain_b, tin_w, tin_b, tout_w, tout_b, g_final, out_w, out_b;
+  size_t total;
+};
+
+struct Cursor {
+  size_t off = 0;
+  size_t take(size_t n) {
+    size_t o = off;
+    off += round_up_sz(n, 128);
+    return o;
+  }
+};
+
+void blob_layout(const pi0_config& c, const Dims& d, BlobLayout& b) {
+  Cursor cur;
+  b.patch_w = cur.take((size_t)d.PD * d.Dv);
+  b.patch_b = cur.take(d.Dv);
+  b.pos = cur.take((size_t)d.T * d.Dv);
+  b.vis.resize(d.Lv);
+  for (int l = 0; l < d.Lv; l++) {
+    BlobVis& v = b.vis[l];
+    v.ln1g = cur.take(d.Dv); v.ln1b = cur.take(d.Dv);
+    v.wq = cur.take((size_t)d.Dv * d.Dv); v.bq = cur.take(d.Dv);
+    v.wk = cur.take((size_t)d.Dv * d.Dv); v.bk = cur.take(d.Dv);
+    v.wv = cur.take((size_t)d.Dv * d.Dv); v.bv = cur.take(d.Dv);
+    v.wo = cur.take((size_t)d.Dv * d.Dv); v.bo = cur.take(d.Dv);
+    v.ln2g = cur.take(d.Dv); v.ln2b = cur.take(d.Dv);
+    v.w1 = cur.take((size_t)d.Dv * d.Fv); v.b1 = cur.take(d.Fv);
+    v.w2 = cur.take((size_t)d.Fv * d.Dv); v.b2 = cur.take(d.Dv);
+  }
+  b.lnfg = cur.take(d.Dv); b.lnfb = cur.take(d.Dv);
+  b.proj_w = cur.take((size_t)d.Dv * d.E); b.proj_b = cur.take(d.E);
+  b.embed = 0;
+  if (c.vocab > 0) b.embed = cur.take((size_t)c.vocab * d.E);
+  auto tr = [&](std::vector<BlobTr>& v, int L, int W, int M) {
+    v.resize(L);
+    for (int l = 0; l < L; l++) {
+      BlobTr& t = v[l];
+      t.g_attn = cur.take(W);
+      t.wq = cur.take((size_t)W * d.H * 256); t.wk = cur.take((size_t)W * 256); t.wv = cur.take((size_t)W * 256);
+      t.wo = cur.take((size_t)d.H * 256 * W);
+      t.g_mlp = cur.take(W);
+      t.wg = cur.take((size_t)W * M); t.wu = cur.take((size_t)W * M); t.wd = cur.take((size_t)M * W);
+    }
+  };
+  tr(b.llm, d.Ll, d.E, d.F);
+  tr(b.exp, d.Le, d.X, d.Fx);
+  b.state_w = cur.take((size_t)d.SD * d.X); b.state_b = cur.take(d.X);
+  b.ain_w = cur.take((size_t)d.A * d.X); b.ain_b = cur.take(d.X);
+  b.tin_w = cur.take((size_t)2 * d.X * d.X); b.tin_b = cur.take(d.X);
+  b.tout_w = cur.take((size_t)d.X * d.X); b.tout_b = cur.take(d.X);
+  b.g_final = cur.take(d.X);
+  b.out_w = cur.take((size_t)d.X * d.A); b.out_b = cur.take(d.A);
+  b.total = cur.off;
+}
+
+// ---- workspace layout (byte offsets) ----------------------------------------------------------------
+struct PW { size_t w; int n_pad, k_pad; size_t colsum, bias; };   // packed weight + optional vectors
+struct WsVis { PW qkv, o, up, down; };
+struct WsTr { PW qkv, o, gu, down; };
+struct WsLayout {
+  PW patch; size_t pos;
+  std::vector<WsVis> vis;
+  PW proj;
+  size_t embed;
+  std::vector<WsTr> llm, exp;
+  size_t state_w, state_b, wfold, bias_tab, tau;
+  PW tout, outp;
+  size_t rope;
+  size_t act_begin;   // everything from here on is zero-filled at load time
+  size_t st_images, st_ids, st_state, st_noise, xa;
+  size_t xpatch, vh, vh_b, vq, vk, vv, vattn, vmid, part;
+  size_t lx, lx_b, lq, kcache, vcache, lattn, lmid;
+  size_t stok, z, y, y_b, eq, ek, ev, eattn, emid;
+  size_t total;
+  size_t kcache_layer, vcache_layer;   // bytes per layer
+  int zmax;
+};
+
+struct WsCursor {
+  size_t off = 0;
+  size_t take(size_t bytes) {
+    size_t o = off;
+    off += round_up_sz(bytes, 256);
+    return o;
+  }
+};
+
+const int Z_VIS_O = 6, Z_LLM_O = 8, Z_LLM_DOWN = 16;
+
+int z_vis_down(const Dims& d) { return ceil_div(d.Fv_kp / 64, 4); }   // 4 chunks of 64 per split
+
+void ws_layout(const pi0_config& c, const Dims& d, WsLayout& w) {
+  WsCursor cur;
+  auto pw = [&](int n_true, int k_true, bool colsum, bool bias) {
+    PW p;
+    p.n_pad = round_up(n_true, 32);
+    p.k_pad = round_up(k_true, 64);
+    p.w = cur.take((size_t)p.n_pad * p.k_pad * 2);
+    p.colsum = colsum ? cur.take((size_t)p.n_pad * 4) : 0;
+    p.bias = bias ? cur.take((size_t)p.n_pad * 4) : 0;
+    return p;
+  };
+  w.patch = pw(d.Dv, d.PD, false, true);
+  w.pos = cur.take((size_t)d.T * d.Dv * 4);
+  w.vis.resize(d.Lv);
+  for (int l = 0; l < d.Lv; l++) {
+    w.vis[l].qkv = pw(3 * d.Dv, d.Dv, true, true);
+    w.vis[l].o = pw(d.Dv, d.Dv, false, true);
+    w.vis[l].up = pw(d.Fv, d.Dv, true, true);
+    w.vis[l].down = pw(d.Dv, d.Fv, false, true);
+  }
+  w.proj = pw(d.E, d.Dv, true, true);
+  w.embed = c.vocab > 0 ? cur.take((size_t)c.vocab * d.E * 2) : 0;
+  w.llm.resize(d.Ll);
+  for (int l = 0; l < d.Ll; l++) {
+    const bool last = l == d.Ll - 1;
+    w.llm[l].qkv = pw(last ? 512 : (d.H + 2) * 256, d.E, false, false);
+    if (!last) {
+      w.llm[l].o = pw(d.E, d.H * 256, false, false);
+      w.llm[l].gu = pw(2 * d.F, d.E, false, false);
+      w.llm[l].down = pw(d.E, d.F, false, false);
+    } else {
+      w.llm[l].o = PW{0, 0, 0, 0, 0};
+      w.llm[l].gu = w.llm[l].o;
+      w.llm[l].down = w.llm[l].o;
+    }
+  }
+  w.exp.resize(d.Le);
+  for (int l = 0; l < d.Le; l++) {
+    w.exp[l].qkv = pw((d.H + 2) * 256, d.X, false, false);
+    w.exp[l].o = pw(d.X, d.H * 256, false, false);
+    w.exp[l].gu = pw(2 * d.Fx, d.X, false, false);
+    w.exp[l].down = pw(d.X, d.Fx, false, false);
+  }
+  w.state_w = cur.take((size_t)d.SD * d.X * 4);
+  w.state_b = cur.take((size_t)d.X * 4);
+  w.wfold = cur.take((size_t)d.A * d.X * 4);
+  w.bias_tab = cur.take((size_t)d.steps * d.X * 4);
+  w.tau = cur.take((size_t)d.steps * d.X * 4);
+  w.tout = pw(d.X, d.X, false, true);
+  w.outp = pw(d.A, d.X, false, true);
+  w.rope = cur.take((size_t)d.maxpos * 128 * 2 * 4);
+  // ---- activations ----
+  w.act_begin = cur.off;
+  w.st_images = cur.take((size_t)c.max_views * c.img_size * c.img_size * 3 * 4);
+  w.st_ids = cur.take((size_t)(c.max_prompt > 0 ? c.max_prompt : 1) * 4);
+  w.st_state = cur.take((size_t)d.SD * 4);
+  w.st_noise = cur.take((size_t)c.chunk * d.A * 4);
+  w.xa = cur.take((size_t)c.chunk * d.A * 4);
+  w.xpatch = cur.take((size_t)d.maxI * d.PDp * 2);
+  w.vh = cur.take((size_t)d.maxI * d.Dv * 4);
+  w.vh_b = cur.take((size_t)d.maxI * d.Dv * 2);
+  w.vq = cur.take((size_t)d.maxI * d.Hv * 80 * 2);
+  w.vk = cur.take((size_t)d.Hv * (d.maxI / 32) * 5 * 512 * 2);
+  w.vv = cur.take((size_t)d.Hv * (d.maxI / 32) * 3 * 1024 * 2);
+  w.vattn = cur.take((size_t)d.maxI * d.Dv * 2);
+  w.vmid = cur.take((size_t)d.maxI * d.Fv_kp * 2);
+  w.zmax = Z_LLM_DOWN;
+  if (z_vis_down(d) > w.zmax) w.zmax = z_vis_down(d);
+  {
+    size_t a = (size_t)w.zmax * d.maxI * round_up(d.Dv, 32) * 4;
+    size_t b = (size_t)w.zmax * d.maxP * d.E * 4;
+    w.part = cur.take(a > b ? a : b);
+  }
+  w.lx = cur.take((size_t)d.maxP * d.E * 4);
+  w.lx_b = cur.take((size_t)d.maxP * d.E * 2);
+  w.lq = cur.take((size_t)d.maxP * d.H * 256 * 2);
+  w.kcache_layer = (size_t)d.maxPc * 16 * 512 * 2;
+  w.vcache_layer = (size_t)d.maxPc * 8 * 1024 * 2;
+  w.kcache = cur.take(w.kcache_layer * d.Ll);
+  w.vcache = cur.take(w.vcache_layer * d.Ll);
+  w.lattn = cur.take((size_t)d.maxP * d.H * 256 * 2);
+  w.lmid = cur.take((size_t)d.maxP * d.F * 2);
+  w.stok = cur.take((size_t)d.X * 4);
+  w.z = cur.take((size_t)64 * d.X * 2);
+  w.y = cur.take((size_t)64 * d.X * 4);
+  w.y_b = cur.take((size_t)64 * d.X * 2);
+  w.eq = cur.take((size_t)64 * d.H * 256 * 2);
+  w.ek = cur.take((size_t)2 * 16 * 512 * 2);
+  w.ev = cur.take((size_t)2 * 8 * 1024 * 2);
+  w.eattn = cur.take((size_t)64 * d.H * 256 * 2);
+  w.emid = cur.take((size_t)64 * d.Fx * 2);
+  w.total = cur.off;
+}
+
+struct GraphKey {
+  int kind, n_views, n_prompt;
+  bool operator<(const GraphKey& o) const {
+    if (kind != o.kind) return kind < o.kind;
+    if (n_views != o.n_views) return n_views < o.n_views;
+    return n_prompt < o.n_prompt;
+  }
+};
+enum { KIND_PREFILL = 0, KIND_DENOISE = 1, KIND_INFER = 2 };
+
+}  // namespace
+
+struct pi0_ctx {
+  pi0_config cfg;
+  Dims d;
+  BlobLayout bl;
+  WsLayout wl;
+  unsigned char* ws = nullptr;
+  bool loaded = false;
+  bool attrs_set = false;
+  bool graph_mode = true;
+  int cur_views = 0, cur_prompt = 0;   // shape of the valid prefill (0 views = none)
+  int last_hip = 0;
+  std::map<GraphKey, hipGraphExec_t> graphs;
+  std::vector<float> h_rope, h_tau;
+};
+
+namespace {
+
+// Launch recorder: either launches or only counts.
+struct Run {
+  pi0_ctx* c;
+  hipStream_t s;
+  bool count_only;
+  int launches = 0;
+  hipError_t err = hipSuccess;
+  bool ok() const { return err == hipSuccess; }
+  void did(hipError_t e) {
+    launches++;
+    if (err == hipSuccess && e != hipSuccess) err = e;
+  }
+};
+
+template <typename T>
+T* at(pi0_ctx* c, size_t off) { return reinterpret_cast<T*>(c->ws + off); }
+
+PackedW packed(pi0_ctx* c, const PW& p) {
+  PackedW w;
+  w.w = at<bf16>(c, p.w);
+  w.n_pad = p.n_pad;
+  w.k_pad = p.k_pad;
+  return w;
+}
+
+GemmParams gp_base(pi0_ctx* c, const PW& pw, const bf16* X, int ldx, int M, int rows_per_tile, int k_true) {
+  GemmParams p;
+  memset(&p, 0, sizeof(p));
+  p.X = X;
+  p.ldx = ldx;
+  p.M = M;
+  p.W = packed(c, pw);
+  p.n_tiles = pw.n_pad / 32;
+  p.k_per_split = pw.k_pad;
+  p.k_true = k_true;
+  p.m_tiles = ceil_div(M, rows_per_tile);
+  p.n_valid = pw.n_pad;
+  return p;
+}
+
+#define RUN_GEMM(r, tile, pro, epi, p, z) \
+  do { if ((r).count_only) (r).launches++; else if ((r).ok()) (r).did(launch_gemm((r).s, tile, pro, epi, p, z)); } while (0)
+#define RUN(r, call) \
+  do { if ((r).count_only) (r).launches++; else if ((r).ok()) (r).did(call); } while (0)
+
+// split-K GEMM into the partial buffer followed by the fixed-order reduction with bias/residual
+void gemm_splitk_resid(Run& r, const PW& pw, const bf16* X, int ldx, int M, int k_true, int z, int k_per_split,
+                       const float* bias, float* resid_io, bf16* shadow, int n_true) {
+  pi0_ctx* c = r.c;
+  GemmParams p = gp_base(c, pw, X, ldx, M, 256, k_true);
+  p.k_per_split = k_per_split;
+  p.out_f32 = at<float>(c, c->wl.part);
+  p.ldo = pw.n_pad;
+  RUN_GEMM(r, TILE_M256_N128, PRO_NONE, EPI_PARTIAL, p, z);
+  ReduceParams q;
+  q.part = p.out_f32;
+  q.Z = z; q.M = M; q.N = n_true; q.ldp = pw.n_pad;
+  q.bias = bias;
+  q.resid = resid_io;
+  q.out_f32 = resid_io;
+  q.out_bf16 = shadow;
+  q.ldo = n_true; q.ldo2 = n_true;
+  RUN(r, launch_splitk_reduce(r.s, q));
+}
+
+struct Taps {
+  float* base = nullptr;
+  size_t off = 0;
+  void put(Run& r, const float* src, size_t n) {
+    if (base == nullptr) return;
+    if (!r.count_only && r.ok()) r.did(launch_copy_f32(r.s, src, base + off, n));
+    off += n;
+  }
+};
+
+void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
+  pi0_ctx* c = r.c;
+  const Dims& d = c->d;
+  const WsLayout& w = c->wl;
+  const int I = n_views * d.T, P = I + n_prompt;
+  // A0: patches -> tokens (+bias, +position embedding)
+  RUN(r, launch_patchify(r.s, at<float>(c, w.st_images), n_views, c->cfg.img_size, c->cfg.patch, at<bf16>(c, w.xpatch), d.PDp));
+  {
+    GemmParams p = gp_base(c, w.patch, at<bf16>(c, w.xpatch), d.PDp, I, 256, d.PD);
+    p.bias = at<float>(c, w.patch.bias);
+    p.resid = at<float>(c, w.pos);
+    p.resid_mod = d.T;
+    p.out_f32 = at<float>(c, w.vh);
+    p.out_bf16 = at<bf16>(c, w.vh_b);
+    p.ldo = d.Dv; p.ldo2 = d.Dv; p.n_valid = d.Dv;
+    RUN_GEMM(r, TILE_M256_N128, PRO_NONE, EPI_RESID, p, 1);
+  }
+  const int vchunks = I / 32;
+  for (int l = 0; l < d.Lv; l++) {
+    const WsVis& L = w.vis[l];
+    {  // A1: LN -> QKV (+bias), keys/values straight into attention fragment order
+      GemmParams p = gp_base(c, L.qkv, at<bf16>(c, w.vh_b), d.Dv, I, 256, d.Dv);
+      p.bias = at<float>(c, L.qkv.bias);
+      p.colsum = at<float>(c, L.qkv.colsum);
+      p.out_bf16 = at<bf16>(c, w.vq);
+      p.ldo = d.Hv * 80;
+      p.kfrag = at<bf16>(c, w.vk);
+      p.vfrag = at<bf16>(c, w.vv);
+      p.rope = nullptr;
+      p.q_cols = d.Dv; p.k_cols = d.Dv;
+      p.head_dim = d.hdv; p.dqk_pad = 80; p.nvb = 3; p.kv_heads = d.Hv; p.kv_chunks = vchunks;
+      RUN_GEMM(r, TILE_M256_N128, PRO_LN, EPI_QKV, p, 1);
+    }
+    {  // A2: attention inside each view
+      AttnParams a;
+      memset(&a, 0, sizeof(a));
+      a.q = at<bf16>(c, w.vq); a.q_ld = d.Hv * 80; a.q_head_stride = 80;
+      a.Tq = I; a.heads = d.Hv;
+      a.k0 = at<bf16>(c, w.vk); a.v0 = at<bf16>(c, w.vv);
+      a.chunks0 = vchunks; a.valid0 = I;
+      a.kv_head_stride0 = vchunks * 5 * 512; a.v_head_stride0 = vchunks * 3 * 1024;
+      a.view_tokens = d.T;
+      a.scale = 1.0f / sqrtf((float)d.hdv);
+      a.out = at<bf16>(c, w.vattn); a.out_ld = d.Dv; a.head_dim = d.hdv;
+      RUN(r, launch_attention(r.s, a));
+    }
+    // A3: O-projection + bias + residual
+    gemm_splitk_resid(r, L.o, at<bf16>(c, w.vattn), d.Dv, I, d.Dv, Z_VIS_O, round_up(ceil_div(L.o.k_pad, Z_VIS_O), 64),
+                      at<float>(c, L.o.bias), at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv);
+    {  // A4: LN -> up (+bias, GELU)
+      GemmParams p = gp_base(c, L.up, at<bf16>(c, w.vh_b), d.Dv, I, 256, d.Dv);
+      p.bias = at<float>(c, L.up.bias);
+      p.colsum = at<float>(c, L.up.colsum);
+      p.out_bf16 = at<bf16>(c, w.vmid);
+      p.ldo = d.Fv_kp; p.n_valid = L.up.n_pad; p.act = ACT_GELU;
+      RUN_GEMM(r, TILE_M256_N128, PRO_LN, EPI_BF16, p, 1);
+    }
+    // A5: down (+bias, residual)
+    gemm_splitk_resid(r, L.down, at<bf16>(c, w.vmid), d.Fv_kp, I, d.Fv, z_vis_down(d), 256, at<float>(c, L.down.bias),
+                      at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv);
+    if (taps) taps->put(r, at<float>(c, w.vh), (size_t)I * d.Dv);
+  }
+  {  // A6: final LN -> projector (+bias) = prefix image embeddings
+    GemmParams p = gp_base(c, w.proj, at<bf16>(c, w.vh_b), d.Dv, I, 256, d.Dv);
+    p.bias = at<float>(c, w.proj.bias);
+    p.colsum = at<float>(c, w.proj.colsum);
+    p.out_f32 = at<float>(c, w.lx);
+    p.out_bf16 = at<bf16>(c, w.lx_b);
+    p.ldo = d.E; p.ldo2 = d.E; p.n_valid = d.E;
+    RUN_GEMM(r, TILE_M256_N128, PRO_LN, EPI_RESID, p, 1);
+  }
+  if (taps) taps->put(r, at<float>(c, w.lx), (size_t)I * d.E);
+  if (n_prompt > 0) {  // B0: prompt embeddings after the image tokens
+    RUN(r, launch_embed_prompt(r.s, at<int32_t>(c, w.st_ids), n_prompt, at<bf16>(c, w.embed), c->cfg.vocab, d.E,
+                               sqrtf((float)d.E), at<float>(c, w.lx), at<bf16>(c, w.lx_b), I));
+  }
+  const int pchunks = ceil_div(P, 32);
+  for (int l = 0; l < d.Ll; l++) {
+    const WsTr& L = w.llm[l];
+    const bool last = l == d.Ll - 1;
+    bf16* kc = reinterpret_cast<bf16*>(c->ws + w.kcache + (size_t)l * w.kcache_layer);
+    bf16* vc = reinterpret_cast<bf16*>(c->ws + w.vcache + (size_t)l * w.vcache_layer);
+    {  // B1: RMS -> QKV, RoPE, keys/values into the cache (last layer: keys/values only)
+      GemmParams p = gp_base(c, L.qkv, at<bf16>(c, w.lx_b), d.E, P, 256, d.E);
+      p.out_bf16 = at<bf16>(c, w.lq);
+      p.ldo = d.H * 256;
+      p.kfrag = kc; p.vfrag = vc;
+      p.rope = at<float>(c, w.rope);
+      p.pos0 = 0;
+      p.q_cols = last ? 0 : d.H * 256; p.k_cols = 256;
+      p.head_dim = 256; p.dqk_pad = 256; p.nvb = 8; p.kv_heads = 1; p.kv_chunks = d.maxPc;
+      RUN_GEMM(r, TILE_M256_N128, PRO_RMS, EPI_QKV, p, 1);
+    }
+    if (last) break;
+    {  // B2: attention, whole prefix visible
+      AttnParams a;
+      memset(&a, 0, sizeof(a));
+      a.q = at<bf16>(c, w.lq); a.q_ld = d.H * 256; a.q_head_stride = 256;
+      a.Tq = P; a.heads = d.H;
+      a.k0 = kc; a.v0 = vc; a.chunks0 = pchunks; a.valid0 = P;
+      a.scale = 1.0f / 16.0f;
+      a.out = at<bf16>(c, w.lattn); a.out_ld = d.H * 256; a.head_dim = 256;
+      RUN(r, launch_attention(r.s, a));
+    }
+    // B3: O-projection + residual
+    gemm_splitk_resid(r, L.o, at<bf16>(c, w.lattn), d.H * 256, P, d.H * 256, Z_LLM_O,
+                      round_up(ceil_div(L.o.k_pad, Z_LLM_O), 64), nullptr, at<float>(c, w.lx), at<bf16>(c, w.lx_b), d.E);
+    {  // B4: RMS -> gate||up with fused GELU gate
+      GemmParams p = gp_base(c, L.gu, at<bf16>(c, w.lx_b), d.E, P, 256, d.E);
+      p.out_bf16 = at<bf16>(c, w.lmid);
+      p.ldo = d.F;
+      RUN_GEMM(r, TILE_M256_N128, PRO_RMS, EPI_GEGLU, p, 1);
+    }
+    // B5: down + residual
+    gemm_splitk_resid(r, L.down, at<bf16>(c, w.lmid), d.F, P, d.F, Z_LLM_DOWN,
+                      round_up(ceil_div(L.down.k_pad, Z_LLM_DOWN), 64), nullptr, at<float>(c, w.lx), at<bf16>(c, w.lx_b),
+                      d.E);
+    if (taps) taps->put(r, at<float>(c, w.lx), (size_t)P * d.E);
+  }
+  if (taps && taps->base) {
+    for (int l = 0; l < d.Ll; l++) {
+      bf16* kc = reinterpret_cast<bf16*>(c->ws + w.kcache + (size_t)l * w.kcache_layer);
+      bf16* vc = reinterpret_cast<bf16*>(c->ws + w.vcache + (size_t)l * w.vcache_layer);
+      float* kout = taps->base + taps->off + (size_t)l * P * 256;
+      float* vout = kout + (size_t)d.Ll * P * 256;
+      if (!r.count_only && r.ok()) r.did(launch_unpack_kv(r.s, kc, vc, P, kout, vout));
+    }
+    taps->off += (size_t)2 * d.Ll * P * 256;
+  }
+}
+
+void run_denoise(Run& r, int P, Taps* taps) {
+  pi0_ctx* c = r.c;
+  const Dims& d = c->d;
+  const WsLayout& w = c->wl;
+  const int chunk = c->cfg.chunk;
+  const int pchunks = ceil_div(P, 32);
+  float* xa = at<float>(c, w.xa);
+  RUN(r, launch_copy_f32(r.s, at<float>(c, w.st_noise), xa, (size_t)chunk * d.A));
+  // C0: state token
+  RUN(r, launch_state_token(r.s, at<float>(c, w.st_state), d.SD, at<float>(c, w.state_w), at<float>(c, w.state_b), d.X,
+                            at<float>(c, w.stok)));
+  const float dt = -1.0f / (float)d.steps;
+  size_t tap_step_base = taps ? taps->off : 0;
+  for (int k = 0; k < d.steps; k++) {
+    // C1: folded action/time embedding, SiLU; suffix row 0 <- state token
+    RUN(r, launch_action_embed(r.s, xa, chunk, d.A, at<float>(c, w.wfold), at<float>(c, w.bias_tab) + (size_t)k * d.X, d.X,
+                               at<bf16>(c, w.z), at<float>(c, w.stok), at<float>(c, w.y), at<bf16>(c, w.y_b)));
+    {  // C2: second linear of the action/time MLP -> suffix rows 1..chunk
+      GemmParams p = gp_base(c, w.tout, at<bf16>(c, w.z), d.X, chunk, 64, d.X);
+      p.bias = at<float>(c, w.tout.bias);
+      p.out_f32 = at<float>(c, w.y);
+      p.out_bf16 = at<bf16>(c, w.y_b);
+      p.ldo = d.X; p.ldo2 = d.X; p.n_valid = d.X; p.row_offset = 1;
+      RUN_GEMM(r, TILE_M64_K4, PRO_NONE, EPI_RESID, p, 1);
+    }
+    const bool tap_this = taps && (k == 0 || k == d.steps - 1);
+    for (int l = 0; l < d.Le; l++) {
+      const WsTr& L = w.exp[l];
+      bf16* kc = reinterpret_cast<bf16*>(c->ws + w.kcache + (size_t)l * w.kcache_layer);
+      bf16* vc = reinterpret_cast<bf16*>(c->ws + w.vcache + (size_t)l * w.vcache_layer);
+      {  // C3: RMS -> QKV, RoPE at positions P..P+63
+        GemmParams p = gp_base(c, L.qkv, at<bf16>(c, w.y_b), d.X, 64, 64, d.X);
+        p.out_bf16 = at<bf16>(c, w.eq);
+        p.ldo = d.H * 256;
+        p.kfrag = at<bf16>(c, w.ek); p.vfrag = at<bf16>(c, w.ev);
+        p.rope = at<float>(c, w.rope);
+        p.pos0 = P;
+        p.q_cols = d.H * 256; p.k_cols = 256;
+        p.head_dim = 256; p.dqk_pad = 256; p.nvb = 8; p.kv_heads = 1; p.kv_chunks = 2;
+        RUN_GEMM(r, TILE_M64_K4, PRO_RMS, EPI_QKV, p, 1);
+      }
+      {  // C4 + C5: scores, block mask, softmax, PV over [cache ; own keys]
+        AttnParams a;
+        memset(&a, 0, sizeof(a));
+        a.q = at<bf16>(c, w.eq); a.q_ld = d.H * 256; a.q_head_stride = 256;
+        a.Tq = 64; a.heads = d.H;
+        a.k0 = kc; a.v0 = vc; a.chunks0 = pchunks; a.valid0 = P;
+        a.k1 = at<bf16>(c, w.ek); a.v1 = at<bf16>(c, w.ev); a.chunks1 = 2;
+        a.suffix_mask = 1;
+        a.scale = 1.0f / 16.0f;
+        a.out = at<bf16>(c, w.eattn); a.out_ld = d.H * 256; a.head_dim = 256;
+        RUN(r, launch_attention(r.s, a));
+      }
+      {  // C6: O-projection + residual
+        GemmParams p = gp_base(c, L.o, at<bf16>(c, w.eattn), d.H * 256, 64, 64, d.H * 256);
+        p.resid = at<float>(c, w.y);
+        p.out_f32 = at<float>(c, w.y); p.out_bf16 = at<bf16>(c, w.y_b);
+        p.ldo = d.X; p.ldo2 = d.X; p.n_valid = d.X;
+        RUN_GEMM(r, TILE_M64_K8, PRO_NONE, EPI_RESID, p, 1);
+      }
+      {  // C7: RMS -> gate||up, fused gate
+        GemmParams p = gp_base(c, L.gu, at<bf16>(c, w.y_b), d.X, 64, 64, d.X);
+        p.out_bf16 = at<bf16>(c, w.emid);
+        p.ldo = d.Fx;
+        RUN_GEMM(r, TILE_M64_K4, PRO_RMS, EPI_GEGLU, p, 1);
+      }
+      {  // C8: down + residual
+        GemmParams p = gp_base(c, L.down, at<bf16>(c, w.emid), d.Fx, 64, 64, d.Fx);
+        p.resid = at<float>(c, w.y);
+        p.out_f32 = at<float>(c, w.y); p.out_bf16 = at<bf16>(c, w.y_b);
+        p.ldo = d.X; p.ldo2 = d.X; p.n_valid = d.X;
+        RUN_GEMM(r, TILE_M64_K8, PRO_NONE, EPI_RESID, p, 1);
+      }
+      if (tap_this) {
+        // step 0 taps first, last-step taps after them
+        const size_t slot = (k == 0 ? 0 : (size_t)d.Le) + l;
+        if (taps->base && !r.count_only && r.ok())
+          r.did(launch_copy_f32(r.s, at<float>(c, w.y), taps->base + tap_step_base + slot * 64 * d.X, (size_t)64 * d.X));
+      }
+    }
+    {  // C9: final RMS -> out-projection (+bias), Euler update x <- x + dt * v
+      GemmParams p = gp_base(c, w.outp, at<bf16>(c, w.y_b), d.X, 64, 64, d.X);
+      p.bias = at<float>(c, w.outp.bias);
+      p.out_f32 = xa;
+      p.ldo = d.A; p.n_valid = d.A; p.dt = dt;
+      RUN_GEMM(r, TILE_M64_K8, PRO_RMS, EPI_EULER, p, 1);
+    }
+    if (taps && taps->base && !r.count_only && r.ok()) {
+      const size_t xoff = tap_step_base + (size_t)2 * d.Le * 64 * d.X + (size_t)k * chunk * d.A;
+      r.did(launch_copy_f32(r.s, xa, taps->base + xoff, (size_t)chunk * d.A));
+    }
+  }
+  if (taps) taps->off = tap_step_base + (size_t)2 * d.Le * 64 * d.X + (size_t)d.steps * chunk * d.A;
+}
+
+// inputs -> static staging buffers (replayed graphs read constant addresses)
+struct CopySeg { const uint32_t* src; uint32_t* dst; unsigned n; };
+struct CopyArgs { CopySeg seg[4]; };
+__global__ __launch_bounds__(256) void copy_segments_kernel(CopyArgs a) {
+  const CopySeg s = a.seg[blockIdx.y];
+  for (unsigned i = blockIdx.x * 256 + threadIdx.x; i < s.n; i += gridDim.x * 256) s.dst[i] = s.src[i];
+}
+
+hipError_t stage_inputs(pi0_ctx* c, hipStream_t s, const float* images, int n_views, const int32_t* ids, int n_prompt,
+                        const float* state, const float* noise) {
+  CopyArgs a;
+  memset(&a, 0, sizeof(a));
+  int n = 0;
+  if (images) {
+    a.seg[n++] = CopySeg{reinterpret_cast<const uint32_t*>(images), at<uint32_t>(c, c->wl.st_images),
+                         (unsigned)((size_t)n_views * c->cfg.img_size * c->cfg.img_size * 3)};
+  }
+  if (ids && n_prompt > 0) {
+    a.seg[n++] = CopySeg{reinterpret_cast<const uint32_t*>(ids), at<uint32_t>(c, c->wl.st_ids), (unsigned)n_prompt};
+  }
+  if (state) a.seg[n++] = CopySeg{reinterpret_cast<const uint32_t*>(state), at<uint32_t>(c, c->wl.st_state), (unsigned)c->d.SD};
+  if (noise) {
+    a.seg[n++] = CopySeg{reinterpret_cast<const uint32_t*>(noise), at<uint32_t>(c, c->wl.st_noise),
+                         (unsigned)(c->cfg.chunk * c->d.A)};
+  }
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(copy_segments_kernel, dim3(64, n), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+int fail_hip(pi0_ctx* c, hipError_t e) {
+  c->last_hip = (int)e;
+  return PI0_EHIP;
+}
+
+// Runs `kind` either through a cached graph or eagerly.
+int execute(pi0_ctx* c, int kind, int n_views, int n_prompt, hipStream_t s) {
+  const int P = n_views * c->d.T + n_prompt;
+  auto body = [&](Run& r) {
+    if (kind == KIND_PREFILL || kind == KIND_INFER) run_prefill(r, n_views, n_prompt, nullptr);
+    if (kind == KIND_DENOISE || kind == KIND_INFER) run_denoise(r, P, nullptr);
+  };
+  if (!c->graph_mode || s == nullptr) {   // the legacy default stream cannot be captured
+    Run r{c, s, false};
+    body(r);
+    return r.ok() ? PI0_OK : fail_hip(c, r.err);
+  }
+  GraphKey key{kind, n_views, n_prompt};
+  auto it = c->graphs.find(key);
+  if (it == c->graphs.end()) {
+    hipError_t e = hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal);
+    if (e != hipSuccess) return fail_hip(c, e);
+    Run r{c, s, false};
+    body(r);
+    hipGraph_t g = nullptr;
+    e = hipStreamEndCapture(s, &g);
+    if (!r.ok() || e != hipSuccess || g == nullptr) {
+      if (g) (void)hipGraphDestroy(g);
+      return fail_hip(c, r.ok() ? e : r.err);
+    }
+    hipGraphExec_t ge = nullptr;
+    e = hipGraphInstantiate(&ge, g, nullptr, nullptr, 0);
+    (void)hipGraphDestroy(g);
+    if (e != hipSuccess) return fail_hip(c, e);
+    it = c->graphs.emplace(key, ge).first;
+  }
+  hipError_t e = hipGraphLaunch(it->second, s);
+  return e == hipSuccess ? PI0_OK : fail_hip(c, e);
+}
+
+bool check_prefill_args(const pi0_ctx* c, const float* images, int n_views, const int32_t* ids, int n_prompt) {
+  if (images == nullptr) return false;
+  if (n_views < 1 || n_views > c->cfg.max_views) return false;
+  if (n_prompt < 0 || n_prompt > c->cfg.max_prompt) return false;
+  if (n_prompt > 0 && (ids == nullptr || c->cfg.vocab <= 0)) return false;
+  return true;
+}
+
+}  // namespace
+
+// ==================================================================================================
+// C ABI
+// ==================================================================================================
+extern "C" {
+
+const char* pi0_strerror(int code) {
+  switch (code) {
+    case PI0_OK: return "ok";
+    case PI0_EINVAL: return "invalid argument";
+    case PI0_ESTATE: return "invalid state (weights not loaded or no valid prefill)";
+    case PI0_ENOMEM: return "buffer too small or out of host memory";
+    case PI0_EFORMAT: return "weight blob size does not match the configuration";
+    case PI0_EHIP: return "HIP runtime error";
+    default: return "unknown error code";
+  }
+}
+
+int pi0_create(const pi0_config* cfg, pi0_ctx** out) {
+  if (cfg == nullptr || out == nullptr) return PI0_EINVAL;
+  Dims d;
+  if (!derive_dims(*cfg, d)) return PI0_EINVAL;
+  pi0_ctx* c = new (std::nothrow) pi0_ctx();
+  if (c == nullptr) return PI0_ENOMEM;
+  c->cfg = *cfg;
+  c->d = d;
+  blob_layout(*cfg, d, c->bl);
+  ws_layout(*cfg, d, c->wl);
+  // RoPE table (Section 3.2: precomputed): angle = pos * 10000^(-i/128), pairs (i, i+128)
+  c->h_rope.resize((size_t)d.maxpos * 128 * 2);
+  for (int pos = 0; pos < d.maxpos; pos++) {
+    for (int i = 0; i < 128; i++) {
+      const double ang = (double)pos * pow(10000.0, -(double)i / 128.0);
+      c->h_rope[((size_t)pos * 128 + i) * 2] = (float)cos(ang);
+      c->h_rope[((size_t)pos * 128 + i) * 2 + 1] = (float)sin(ang);
+    }
+  }
+  // time encodings of the Euler steps: sin || cos, periods log-spaced from 4e-3 to 4
+  c->h_tau.resize((size_t)d.steps * d.X);
+  const int half = d.X / 2;
+  for (int k = 0; k < d.steps; k++) {
+    const double t = 1.0 - (double)k / d.steps;
+    for (int j = 0; j < half; j++) {
+      const double frac = half > 1 ? (double)j / (half - 1) : 0.0;
+      const double period = 4e-3 * pow(4.0 / 4e-3, frac);
+      const double ang = 2.0 * M_PI * t / period;
+      c->h_tau[(size_t)k * d.X + j] = (float)sin(ang);
+      c->h_tau[(size_t)k * d.X + half + j] = (float)cos(ang);
+    }
+  }
+  *out = c;
+  return PI0_OK;
+}
+
+void pi0_destroy(pi0_ctx* c) {
+  if (c == nullptr) return;
+  for (auto& kv : c->graphs) (void)hipGraphExecDestroy(kv.second);
+  delete c;
+}
+
+size_t pi0_weights_bytes(const pi0_config* cfg) {
+  Dims d;
+  if (cfg == nullptr || !derive_dims(*cfg, d)) return 0;
+  BlobLayout b;
+  blob_layout(*cfg, d, b);
+  return b.total * 2;
+}
+
+size_t pi0_workspace_bytes(const pi0_config* cfg) {
+  Dims d;
+  if (cfg == nullptr || !derive_dims(*cfg, d)) return 0;
+  WsLayout w;
+  ws_layout(*cfg, d, w);
+  return w.total;
+}
+
+int pi0_set_graph_mode(pi0_ctx* c, int enabled) {
+  if (c == nullptr) return PI0_EINVAL;
+  c->graph_mode = enabled != 0;
+  return PI0_OK;
+}
+
+int pi0_last_hip_error(const pi0_ctx* c) { return c ? c->last_hip : 0; }
+
+int pi0_kernel_count(const pi0_ctx* c, int n_views, int n_prompt) {
+  if (c == nullptr || n_views < 1 || n_views > c->cfg.max_views || n_prompt < 0 || n_prompt > c->cfg.max_prompt) return 0;
+  Run r{const_cast<pi0_ctx*>(c), nullptr, true};
+  run_prefill(r, n_views, n_prompt, nullptr);
+  run_denoise(r, n_views * c->d.T + n_prompt, nullptr);
+  return r.launches;
+}
+
+int pi0_load_weights(pi0_ctx* c, const void* d_blob, size_t blob_bytes, void* d_workspace, size_t ws_bytes, void* hip_stream) {
+  if (c == nullptr || d_blob == nullptr || d_workspace == nullptr) return PI0_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(d_workspace) & 255) != 0 || (reinterpret_cast<uintptr_t>(d_blob) & 15) != 0) return PI0_EINVAL;
+  if (blob_bytes != c->bl.total * 2) return PI0_EFORMAT;
+  if (ws_bytes < c->wl.total) return PI0_ENOMEM;
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  const Dims& d = c->d;
+  const BlobLayout& b = c->bl;
+  const WsLayout& w = c->wl;
+  for (auto& kv : c->graphs) (void)hipGraphExecDestroy(kv.second);
+  c->graphs.clear();
+  c->loaded = false;
+  c->cur_views = 0;
+  c->ws = reinterpret_cast<unsigned char*>(d_workspace);
+  const bf16* B = reinterpret_cast<const bf16*>(d_blob);
+  hipError_t e;
+  if (!c->attrs_set) {
+    e = gemm_init_attributes();
+    if (e != hipSuccess) return fail_hip(c, e);
+    e = attention_init_attributes();
+    if (e != hipSuccess) return fail_hip(c, e);
+    c->attrs_set = true;
+  }
+#define TRY(call) do { e = (call); if (e != hipSuccess) return fail_hip(c, e); } while (0)
+  TRY(launch_fill_zero(s, c->ws + w.act_begin, w.total - w.act_begin));
+  TRY(hipMemcpyAsync(c->ws + w.rope, c->h_rope.data(), c->h_rope.size() * 4, hipMemcpyHostToDevice, s));
+  TRY(hipMemcpyAsync(c->ws + w.tau, c->h_tau.data(), c->h_tau.size() * 4, hipMemcpyHostToDevice, s));
+
+  auto pack = [&](const PW& pw, PackSrc src, const bf16* ln_bias, const bf16* b0, const bf16* b1, const bf16* b2) -> hipError_t {
+    hipError_t ee = launch_pack_weights(s, src, at<bf16>(c, pw.w), pw.n_pad, pw.k_pad);
+    if (ee != hipSuccess) return ee;
+    if (pw.colsum != 0 || pw.bias != 0) {
+      const bf16* bs[3] = {b0, b1, b2};
+      ee = launch_fold_vectors(s, src, ln_bias, bs, pw.colsum ? at<float>(c, pw.colsum) : nullptr,
+                               pw.bias ? at<float>(c, pw.bias) : nullptr, pw.n_pad);
+    }
+    return ee;
+  };
+  auto src1 = [&](size_t off, int K, int N, int kscale, size_t gain_off) {
+    PackSrc p;
+    memset(&p, 0, sizeof(p));
+    p.src[0] = B + off; p.cols[0] = N;
+    p.K = K; p.n_true = N; p.rowmap = ROWMAP_CONCAT; p.kscale = kscale;
+    p.gain = kscale != KSCALE_NONE ? B + gain_off : nullptr;
+    return p;
+  };
+  // vision
+  TRY(pack(w.patch, src1(b.patch_w, d.PD, d.Dv, KSCALE_NONE, 0), nullptr, B + b.patch_b, nullptr, nullptr));
+  TRY(launch_bf16_to_f32(s, B + b.pos, at<float>(c, w.pos), (size_t)d.T * d.Dv));
+  for (int l = 0; l < d.Lv; l++) {
+    const BlobVis& v = b.vis[l];
+    PackSrc q = src1(v.wq, d.Dv, d.Dv, KSCALE_GAIN, v.ln1g);
+    q.src[1] = B + v.wk; q.cols[1] = d.Dv;
+    q.src[2] = B + v.wv; q.cols[2] = d.Dv;
+    q.n_true = 3 * d.Dv;
+    TRY(pack(w.vis[l].qkv, q, B + v.ln1b, B + v.bq, B + v.bk, B + v.bv));
+    TRY(pack(w.vis[l].o, src1(v.wo, d.Dv, d.Dv, KSCALE_NONE, 0), nullptr, B + v.bo, nullptr, nullptr));
+    TRY(pack(w.vis[l].up, src1(v.w1, d.Dv, d.Fv, KSCALE_GAIN, v.ln2g), B + v.ln2b, B + v.b1, nullptr, nullptr));
+    TRY(pack(w.vis[l].down, src1(v.w2, d.Fv, d.Dv, KSCALE_NONE, 0), nullptr, B + v.b2, nullptr, nullptr));
+  }
+  TRY(pack(w.proj, src1(b.proj_w, d.Dv, d.E, KSCALE_GAIN, b.lnfg), B + b.lnfb, B + b.proj_b, nullptr, nullptr));
+  if (c->cfg.vocab > 0) TRY(launch_copy_bf16(s, B + b.embed, at<bf16>(c, w.embed), (size_t)c->cfg.vocab * d.E));
+  // prefix and expert transformers
+  auto pack_tr = [&](const std::vector<BlobTr>& bt, const std::vector<WsTr>& wt, int L, int W, int M, bool skip_last) -> hipError_t {
+    for (int l = 0; l < L; l++) {
+      const BlobTr& t = bt[l];
+      const bool last = skip_last && l == L - 1;
+      PackSrc q;
+      memset(&q, 0, sizeof(q));
+      q.src[0] = B + t.wq; q.cols[0] = d.H * 256;
+      q.src[1] = B + t.wk; q.cols[1] = 256;
+      q.src[2] = B + t.wv; q.cols[2] = 256;
+      q.K = W; q.rowmap = ROWMAP_ROPE_QKV; q.kscale = KSCALE_ONE_PLUS; q.gain = B + t.g_attn;
+      q.q_heads = last ? 0 : d.H;
+      q.n_true = (q.q_heads + 2) * 256;
+      hipError_t ee = launch_pack_weights(s, q, at<bf16>(c, wt[l].qkv.w), wt[l].qkv.n_pad, wt[l].qkv.k_pad);
+      if (ee != hipSuccess) return ee;
+      if (last) continue;
+      ee = launch_pack_weights(s, src1(t.wo, d.H * 256, W, KSCALE_NONE, 0), at<bf16>(c, wt[l].o.w), wt[l].o.n_pad, wt[l].o.k_pad);
+      if (ee != hipSuccess) return ee;
+      PackSrc g;
+      memset(&g, 0, sizeof(g));
+      g.src[0] = B + t.wg; g.cols[0] = M;
+      g.src[1] = B + t.wu; g.cols[1] = M;
+      g.K = W; g.n_true = 2 * M; g.rowmap = ROWMAP_PAIR; g.kscale = KSCALE_ONE_PLUS; g.gain = B + t.g_mlp;
+      ee = launch_pack_weights(s, g, at<bf16>(c, wt[l].gu.w), wt[l].gu.n_pad, wt[l].gu.k_pad);
+      if (ee != hipSuccess) return ee;
+      ee = launch_pack_weights(s, src1(t.wd, M, W, KSCALE_NONE, 0), at<bf16>(c, wt[l].down.w), wt[l].down.n_pad, wt[l].down.k_pad);
+      if (ee != hipSuccess) return ee;
+    }
+    return hipSuccess;
+  };
+  TRY(pack_tr(b.llm, w.llm, d.Ll, d.E, d.F, true));
+  TRY(pack_tr(b.exp, w.exp, d.Le, d.X, d.Fx, false));
+  // expert input / output heads
+  TRY(launch_bf16_to_f32(s, B + b.state_w, at<float>(c, w.state_w), (size_t)d.SD * d.X));
+  TRY(launch_bf16_to_f32(s, B + b.state_b, at<float>(c, w.state_b), (size_t)d.X));
+  TRY(launch_time_fold(s, B + b.ain_w, B + b.ain_b, B + b.tin_w, B + b.tin_b, at<float>(c, w.tau), d.A, d.X, d.steps,
+                       at<float>(c, w.wfold), at<float>(c, w.bias_tab)));
+  TRY(pack(w.tout, src1(b.tout_w, d.X, d.X, KSCALE_NONE, 0), nullptr, B + b.tout_b, nullptr, nullptr));
+  TRY(pack(w.outp, src1(b.out_w, d.X, d.A, KSCALE_ONE_PLUS, b.g_final), nullptr, B + b.out_b, nullptr, nullptr));
+#undef TRY
+  c->loaded = true;
+  return PI0_OK;
+}
+
+int pi0_prefill(pi0_ctx* c, const float* d_images, int n_views, const int32_t* d_prompt_ids, int n_prompt, void* hip_stream) {
+  if (c == nullptr) return PI0_EINVAL;
+  if (!check_prefill_args(c, d_images, n_views, d_prompt_ids, n_prompt)) return PI0_EINVAL;
+  if (!c->loaded) return PI0_ESTATE;
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  c->cur_views = 0;
+  hipError_t e = stage_inputs(c, s, d_images, n_views, d_prompt_ids, n_prompt, nullptr, nullptr);
+  if (e != hipSuccess) return fail_hip(c, e);
+  int rc = execute(c, KIND_PREFILL, n_views, n_prompt, s);
+  if (rc != PI0_OK) return rc;
+  c->cur_views = n_views;
+  c->cur_prompt = n_prompt;
+  return PI0_OK;
+}
+
+int pi0_denoise(pi0_ctx* c, const float* d_state, const float* d_noise, float* d_actions, void* hip_stream) {
+  if (c == nullptr || d_state == nullptr || d_noise == nullptr || d_actions == nullptr) return PI0_EINVAL;
+  if (!c->loaded || c->cur_views == 0) return PI0_ESTATE;
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  hipError_t e = stage_inputs(c, s, nullptr, 0, nullptr, 0, d_state, d_noise);
+  if (e != hipSuccess) return fail_hip(c, e);
+  int rc = execute(c, KIND_DENOISE, c->cur_views, c->cur_prompt, s);
+  if (rc != PI0_OK) return rc;
+  e = launch_copy_f32(s, at<float>(c, c->wl.xa), d_actions, (size_t)c->cfg.chunk * c->d.A);
+  return e == hipSuccess ? PI0_OK : fail_hip(c, e);
+}
+
+int pi0_infer(pi0_ctx* c, const float* d_images, int n_views, const int32_t* d_prompt_ids, int n_prompt, const float* d_state,
+              const float* d_noise, float* d_actions, void* hip_stream) {
+  if (c == nullptr || d_state == nullptr || d_noise == nullptr || d_actions == nullptr) return PI0_EINVAL;
+  if (!check_prefill_args(c, d_images, n_views, d_prompt_ids, n_prompt)) return PI0_EINVAL;
+  if (!c->loaded) return PI0_ESTATE;
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  c->cur_views = 0;
+  hipError_t e = stage_inputs(c, s, d_images, n_views, d_prompt_ids, n_prompt, d_state, d_noise);
+  if (e != hipSuccess) return fail_hip(c, e);
+  int rc = execute(c, KIND_INFER, n_views, n_prompt, s);
+  if (rc != PI0_OK) return rc;
+  c->cur_views = n_views;
+  c->cur_prompt = n_prompt;
+  e = launch_copy_f32(s, at<float>(c, c->wl.xa), d_actions, (size_t)c->cfg.chunk * c->d.A);
+  return e == hipSuccess ? PI0_OK : fail_hip(c, e);
+}
+
+size_t pi0_debug_taps_elems(const pi0_config* cfg, int n_views, int n_prompt) {
+  Dims d;
+  if (cfg == nullptr || !derive_dims(*cfg, d)) return 0;
+  if (n_views < 1 || n_views > cfg->max_views || n_prompt < 0 || n_prompt > cfg->max_prompt) return 0;
+  const size_t I = (size_t)n_views * d.T, P = I + n_prompt;
+  return (size_t)d.Lv * I * d.Dv + I * d.E + (size_t)(d.Ll - 1) * P * d.E + (size_t)2 * d.Ll * P * 256 +
+         (size_t)2 * d.Le * 64 * d.X + (size_t)d.steps * cfg->chunk * d.A;
+}
+
+int pi0_debug_forward(pi0_ctx* c, const float* d_images, int n_views, const int32_t* d_prompt_ids, int n_prompt,
+                      const float* d_state, const float* d_noise, float* d_actions, float* d_taps, size_t cap_elems,
+                      void* hip_stream) {
+  if (c == nullptr || d_state == nullptr || d_noise == nullptr || d_actions == nullptr || d_taps == nullptr) return PI0_EINVAL;
+  if (!check_prefill_args(c, d_images, n_views, d_prompt_ids, n_prompt)) return PI0_EINVAL;
+  if (!c->loaded) return PI0_ESTATE;
+  if (cap_elems < pi0_debug_taps_elems(&c->cfg, n_views, n_prompt)) return PI0_ENOMEM;
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  c->cur_views = 0;
+  hipError_t e = stage_inputs(c, s, d_images, n_views, d_prompt_ids, n_prompt, d_state, d_noise);
+  if (e != hipSuccess) return fail_hip(c, e);
+  Run r{c, s, false};
+  Taps taps;
+  taps.base = d_taps;
+  run_prefill(r, n_views, n_prompt, &taps);
+  run_denoise(r, n_views * c->d.T + n_prompt, &taps);
+  if (!r.ok()) return fail_hip(c, r.err);
+  c->cur_views = n_views;
+  c->cur_prompt = n_prompt;
+  e = launch_copy_f32(s, at<float>(c, c->wl.xa), d_actions, (size_t)c->cfg.chunk * c->d.A);
+  return e == hipSuccess ? PI0_OK : fail_hip(c, e);
+}
+
+}  // extern "C"

@@ -1,0 +1,182 @@
+// Internal declarations shared by the host code and the HIP kernels of the pi0 library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/pi0.h"
+
+typedef __bf16 bf16;
+typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+static inline int round_up(int a, int b) { return ceil_div(a, b) * b; }
+static inline size_t round_up_sz(size_t a, size_t b) { return (a + b - 1) / b * b; }
+
+// ------------------------------------------------------------------------------------------
+// Packed weight matrix: MFMA "A operand" fragment order.
+// Logical matrix W'[n][k] (n = output feature, k = input feature), zero padded to n_pad x k_pad.
+// Element (n, k) lives at  ((n/32 * (k_pad/16) + k/16) * 64 + ((k%16)/8)*32 + n%32) * 8 + k%8,
+// so one wave reads the 32x16 fragment of n-tile nt, k-step kc as 64 consecutive 16-byte pieces.
+// ------------------------------------------------------------------------------------------
+struct PackedW {
+  const bf16* w;  // fragment-ordered weights
+  int n_pad;      // multiple of 32
+  int k_pad;      // multiple of 64
+};
+
+enum RowMap { ROWMAP_CONCAT = 0, ROWMAP_ROPE_QKV = 1, ROWMAP_PAIR = 2 };
+enum KScale { KSCALE_NONE = 0, KSCALE_GAIN = 1, KSCALE_ONE_PLUS = 2 };
+
+// Source description for packing: up to three [K][cols_i] row-major bf16 matrices that are
+// concatenated along the output axis (ROWMAP_CONCAT), concatenated with the q and k blocks
+// re-ordered so that RoPE partners (d, d + 128) become neighbours (ROWMAP_ROPE_QKV), or
+// interleaved pairwise src0/src1 (ROWMAP_PAIR: packed row 2i = src0 col i, 2i+1 = src1 col i).
+struct PackSrc {
+  const bf16* src[3];
+  int cols[3];
+  int K;              // true input features
+  int n_true;         // true number of packed rows
+  int rowmap;
+  int kscale;         // per-k scale folded into the weights
+  const bf16* gain;   // [K] (KSCALE_GAIN: g, KSCALE_ONE_PLUS: 1 + g)
+  int q_heads;        // ROWMAP_ROPE_QKV: number of 256-wide q heads in src0
+};
+
+// ------------------------------------------------------------------------------------------
+// GEMM:  C^T[n][m] = sum_k W'[n][k] * X[m][k]   (weights are the MFMA A operand, tokens the B
+// operand; each lane of the accumulator owns one token and groups of 4 consecutive n).
+// ------------------------------------------------------------------------------------------
+enum Prologue { PRO_NONE = 0, PRO_RMS = 1, PRO_LN = 2 };
+enum Epilogue {
+  EPI_PARTIAL = 0,   // fp32 partial sums [z][M][n_pad] for a later split-K reduction
+  EPI_RESID = 1,     // out_f32 = acc (+bias) (+resid[row % resid_mod]); bf16 shadow
+  EPI_BF16 = 2,      // out_bf16 = act(norm(acc) + bias)
+  EPI_QKV = 3,       // q natural, K / V in attention fragment order; optional RoPE / bias
+  EPI_GEGLU = 4,     // out_bf16[m][n/2] = gelu(gate) * up
+  EPI_EULER = 5      // x[m-1][n] += dt * (norm(acc) + bias), rows m >= 1
+};
+enum Act { ACT_NONE = 0, ACT_GELU = 1, ACT_SILU = 2 };
+
+struct GemmParams {
+  const bf16* X;      // [M][ldx] activations, ldx >= k_pad, pad columns finite (zero)
+  int ldx;
+  int M;              // valid rows
+  PackedW W;
+  int n_tiles;        // n_pad / 32
+  int k_per_split;    // k range of one blockIdx.z slice, multiple of 64 * WK
+  int k_true;         // divisor of the row statistics
+  int m_tiles;        // number of MB*32 row tiles
+  // statistics / affine
+  const float* bias;    // [n_pad] or null
+  const float* colsum;  // [n_pad], PRO_LN only: sum_k W'[n][k]
+  // outputs
+  float* out_f32;     // EPI_RESID / EPI_PARTIAL / EPI_EULER
+  bf16* out_bf16;     // EPI_RESID shadow, EPI_BF16, EPI_GEGLU, EPI_QKV q
+  int ldo;            // leading dimension of out_f32 / out_bf16 (elements)
+  int ldo2;           // leading dimension of out_bf16 shadow in EPI_RESID
+  int n_valid;        // columns >= n_valid are not stored (EPI_RESID / EPI_BF16 / EPI_EULER)
+  const float* resid; // EPI_RESID: residual input [*][ldo] or null
+  int resid_mod;      // row index of resid taken modulo this (0 = no modulo)
+  int row_offset;     // EPI_RESID: output row = m + row_offset
+  int act;
+  // EPI_QKV
+  bf16* kfrag;        // key fragments
+  bf16* vfrag;        // value fragments (transposed)
+  const float* rope;  // [pos][128][2] (cos, sin) or null
+  int pos0;           // position of row 0
+  int q_cols;         // packed rows belonging to q  (heads * head_dim)
+  int k_cols;         // packed rows belonging to k
+  int head_dim;       // true head dim (72 or 256)
+  int dqk_pad;        // head dim padded for QK^T (80 or 256)
+  int nvb;            // value blocks of 32 (3 or 8)
+  int kv_heads;       // 16 (vision) or 1
+  int kv_chunks;      // key chunks (of 32) per head in kfrag / vfrag
+  // EPI_EULER
+  float dt;
+};
+
+// Tile configuration ids (template instantiations that exist)
+enum GemmTile {
+  TILE_M256_N128 = 0,  // MB=8, WN=4, WK=1 : 256 tokens x 128 features per block, 256 threads
+  TILE_M64_K4 = 1,     // MB=2, WN=1, WK=4 : 64 tokens x 32 features, 4 waves split K
+  TILE_M64_K8 = 2,     // MB=2, WN=1, WK=8
+  TILE_M64_N4 = 3,     // MB=2, WN=4, WK=1
+  TILE_M256_K4 = 4     // MB=8, WN=1, WK=4
+};
+
+hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmParams& p, int z_splits);
+int gemm_smem_bytes(int tile);
+hipError_t gemm_init_attributes();
+
+// Split-K reduction: out[m][n] = sum_z part[z][m][n] (+bias[n]) (+resid[m][n]); bf16 shadow.
+struct ReduceParams {
+  const float* part;  // [Z][M][ldp]
+  int Z, M, N, ldp;
+  const float* bias;
+  const float* resid;
+  float* out_f32;
+  bf16* out_bf16;
+  int ldo, ldo2;
+};
+hipError_t launch_splitk_reduce(hipStream_t s, const ReduceParams& p);
+
+// ------------------------------------------------------------------------------------------
+// Attention over fragment-ordered keys / values.
+// Key fragments:   [head][chunk][s = d/16][lane = ((d%16)/8)*32 + key%32][d%8]
+// Value fragments: [head][chunk][vb = d/32][s2 = (key%32)/16][lane = ((key%8)/4)*32 + d%32]
+//                  [j = ((key%16)/8)*4 + key%4]
+// ------------------------------------------------------------------------------------------
+struct AttnParams {
+  const bf16* q;       // [Tq][q_ld], head h at column h * q_head_stride
+  int q_ld, q_head_stride;
+  int Tq;              // query rows per head
+  int heads;
+  const bf16* k0;      // first key segment (prefix cache or the layer's own keys)
+  const bf16* v0;
+  int chunks0;         // chunks in segment 0 (per head)
+  int valid0;          // valid keys in segment 0 (keys >= valid0 are masked)
+  int kv_head_stride0; // elements between heads in k0 (0 = shared head); v uses v_head_stride0
+  int v_head_stride0;
+  const bf16* k1;      // optional second segment (the suffix's own keys), 0 or 2 chunks
+  const bf16* v1;
+  int chunks1;
+  int view_tokens;     // > 0: query row m only sees keys of its own view [m/vt*vt, +vt)
+  int suffix_mask;     // 1: row 0 sees only key 0 of segment 1; other rows see all of segment 1
+  float scale;
+  bf16* out;           // [Tq][out_ld], head h at column h * head_dim
+  int out_ld;
+  int head_dim;        // 72 or 256
+};
+hipError_t launch_attention(hipStream_t s, const AttnParams& p);
+hipError_t attention_init_attributes();
+
+// ------------------------------------------------------------------------------------------
+// small kernels
+// ------------------------------------------------------------------------------------------
+hipError_t launch_pack_weights(hipStream_t s, const PackSrc& src, bf16* dst, int n_pad, int k_pad);
+// colsum[n] = sum_k packed(n,k) as stored (bf16-rounded, scaled); bias_out[n] = sum_k ln_bias[k]*W[k][col] + bias_cat[n]
+hipError_t launch_fold_vectors(hipStream_t s, const PackSrc& src, const bf16* ln_bias, const bf16* const bias_src[3],
+                               float* colsum, float* bias_out, int n_pad);
+hipError_t launch_bf16_to_f32(hipStream_t s, const bf16* src, float* dst, size_t n);
+hipError_t launch_copy_bf16(hipStream_t s, const bf16* src, bf16* dst, size_t n);
+hipError_t launch_fill_zero(hipStream_t s, void* dst, size_t bytes);
+// W_fold[r][n] (r < action_dim) and bias table rows (r = action_dim + step)
+hipError_t launch_time_fold(hipStream_t s, const bf16* wa, const bf16* ba, const bf16* wt1, const bf16* bt1,
+                            const float* tau, int action_dim, int X, int steps, float* wfold, float* bias_tab);
+
+hipError_t launch_patchify(hipStream_t s, const float* images, int n_views, int img, int patch, bf16* out, int ld);
+hipError_t launch_embed_prompt(hipStream_t s, const int32_t* ids, int n, const bf16* table, int vocab, int E, float scale,
+                               float* out_f32, bf16* out_bf16, int row0);
+hipError_t launch_state_token(hipStream_t s, const float* state, int state_dim, const float* ws, const float* bs, int X,
+                              float* out);
+// z = silu(x @ W_fold + bias_k) -> bf16 [64][X] (row chunk.. zero);  Y row 0 = state token
+hipError_t launch_action_embed(hipStream_t s, const float* x, int chunk, int action_dim, const float* wfold,
+                               const float* bias_k, int X, bf16* z, const float* state_tok, float* y_f32, bf16* y_bf16);
+hipError_t launch_copy_f32(hipStream_t s, const float* src, float* dst, size_t n);
+// natural-order dump of fragment-ordered caches (debug taps)
+hipError_t launch_unpack_kv(hipStream_t s, const bf16* kfrag, const bf16* vfrag, int P, float* k_out, float* v_out);

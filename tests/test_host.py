@@ -1,0 +1,144 @@
+"""Host-side checks that need no GPU: the library loads, exports what the header declares,
+rejects bad arguments before touching the GPU, and agrees with the generators on blob size.
+Also pins the roofline calculator to the numbers the paper prints in Table 2 / Section 5.1."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2510_26742_amd import binding, roofline, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(binding.LIB_PATH):
+        import __graft_entry__ as g
+        g.build()
+    return binding.lib()
+
+
+def test_header_symbols_are_exported(L):
+    hdr = open(os.path.join(ROOT, "include", "pi0.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = sorted(set(re.findall(r"\b(pi0_[a-z_0-9]+)\s*\(", hdr)))
+    assert declared, "no declarations found"
+    assert sorted(binding.EXPORTS) == declared
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_strerror(L):
+    for code in (0, -1, -2, -3, -4, -5, -99):
+        s = L.pi0_strerror(code)
+        assert s and len(s) > 1
+
+
+@pytest.mark.parametrize("cfg", [synth.reduced_config(), synth.full_config(), synth.full_config(vocab=257152)])
+def test_blob_size_matches_generator_layout(L, cfg):
+    _, total = synth.blob_layout(cfg)
+    assert binding.pi0_weights_bytes(cfg) == total * 2
+    assert binding.pi0_workspace_bytes(cfg) > total * 2 * 0.9
+
+
+def test_full_model_sizes_are_plausible(L):
+    cfg = synth.full_config()
+    gb = binding.pi0_weights_bytes(cfg) / 1e9
+    assert 5.0 < gb < 6.5          # ~2.7-3.2 B parameters in bf16 (SigLIP 0.4 B, Gemma 2 B+, expert 0.3 B)
+    assert binding.pi0_workspace_bytes(cfg) < 8e9
+
+
+def test_create_rejects_bad_geometry(L):
+    good = synth.reduced_config()
+    bad = [dict(head_dim=128), dict(chunk=31), dict(vis_width=1150), dict(exp_layers=3), dict(steps=0),
+           dict(max_views=0), dict(patch=15), dict(state_dim=33), dict(vis_heads=7), dict(llm_layers=1)]
+    for kw in bad:
+        c = binding.to_c_config(synth.dataclasses.replace(good, **kw))
+        ctx = ctypes.c_void_p()
+        assert L.pi0_create(ctypes.byref(c), ctypes.byref(ctx)) == binding.PI0_EINVAL, kw
+        assert not ctx
+        assert L.pi0_weights_bytes(ctypes.byref(c)) == 0
+        assert L.pi0_workspace_bytes(ctypes.byref(c)) == 0
+    ctx = ctypes.c_void_p()
+    assert L.pi0_create(None, ctypes.byref(ctx)) == binding.PI0_EINVAL
+    c = binding.to_c_config(good)
+    assert L.pi0_create(ctypes.byref(c), None) == binding.PI0_EINVAL
+
+
+def test_error_paths_before_any_gpu_call(L):
+    cfg = synth.reduced_config()
+    c = binding.to_c_config(cfg)
+    ctx = ctypes.c_void_p()
+    assert L.pi0_create(ctypes.byref(c), ctypes.byref(ctx)) == 0
+    fake = 0x10000                       # never dereferenced: every call below fails its checks first
+    nbytes = binding.pi0_weights_bytes(cfg)
+    ws = binding.pi0_workspace_bytes(cfg)
+    assert L.pi0_load_weights(ctx, None, nbytes, fake, ws, None) == binding.PI0_EINVAL
+    assert L.pi0_load_weights(ctx, fake, nbytes, None, ws, None) == binding.PI0_EINVAL
+    assert L.pi0_load_weights(ctx, fake, nbytes, fake + 8, ws, None) == binding.PI0_EINVAL      # misaligned
+    assert L.pi0_load_weights(ctx, fake, nbytes - 2, fake, ws, None) == binding.PI0_EFORMAT
+    assert L.pi0_load_weights(ctx, fake, nbytes, fake, ws - 1, None) == binding.PI0_ENOMEM
+    assert L.pi0_load_weights(None, fake, nbytes, fake, ws, None) == binding.PI0_EINVAL
+    # not loaded yet
+    assert L.pi0_prefill(ctx, fake, 1, None, 0, None) == binding.PI0_ESTATE
+    assert L.pi0_denoise(ctx, fake, fake, fake, None) == binding.PI0_ESTATE
+    assert L.pi0_infer(ctx, fake, 1, None, 0, fake, fake, fake, None) == binding.PI0_ESTATE
+    # argument checks win over state checks
+    assert L.pi0_prefill(ctx, None, 1, None, 0, None) == binding.PI0_EINVAL
+    assert L.pi0_prefill(ctx, fake, 0, None, 0, None) == binding.PI0_EINVAL
+    assert L.pi0_prefill(ctx, fake, 4, None, 0, None) == binding.PI0_EINVAL
+    assert L.pi0_prefill(ctx, fake, 1, None, 3, None) == binding.PI0_EINVAL         # ids missing
+    assert L.pi0_prefill(ctx, fake, 1, fake, 3, None) == binding.PI0_EINVAL         # no embedding table (vocab 0)
+    assert L.pi0_prefill(ctx, fake, 1, fake, 49, None) == binding.PI0_EINVAL
+    assert L.pi0_denoise(ctx, None, fake, fake, None) == binding.PI0_EINVAL
+    assert L.pi0_infer(ctx, fake, 1, None, 0, fake, fake, None, None) == binding.PI0_EINVAL
+    assert L.pi0_debug_forward(ctx, fake, 1, None, 0, fake, fake, fake, None, 0, None) == binding.PI0_EINVAL
+    assert L.pi0_last_hip_error(ctx) == 0
+    L.pi0_destroy(ctx)
+    L.pi0_destroy(None)
+
+
+def test_kernel_count_and_taps(L):
+    cfg = synth.full_config()
+    c = binding.to_c_config(cfg)
+    ctx = ctypes.c_void_p()
+    assert L.pi0_create(ctypes.byref(c), ctypes.byref(ctx)) == 0
+    n1 = L.pi0_kernel_count(ctx, 1, 0)
+    n2 = L.pi0_kernel_count(ctx, 2, 0)
+    assert n1 == n2 and 900 < n1 < 2000
+    assert L.pi0_kernel_count(ctx, 0, 0) == 0
+    assert L.pi0_kernel_count(ctx, 1, 5) == n1 + 1     # one extra launch: the prompt embedding gather
+    assert L.pi0_kernel_count(ctx, 1, 49) == 0
+    L.pi0_destroy(ctx)
+    I, P = 256, 256
+    exp = (27 * I * 1152 + I * 2048 + 17 * P * 2048 + 2 * 18 * P * 256 + 2 * 18 * 64 * 1024 + 10 * 63 * 32)
+    assert binding.pi0_debug_taps_elems(cfg, 1, 0) == exp
+
+
+# ---------------------------------------------------------------------------- roofline pins
+def test_roofline_reproduces_table2_and_section5():
+    cfg = synth.full_config()
+    ops = roofline.table2_ops(cfg, 2, 0)
+    b = roofline.stage_bounds_ms(ops, roofline.RTX4090_BW, roofline.RTX4090_MACS)
+    # bold totals of Table 2 (two views)
+    assert abs(b["vision"] - 2.485) < 2e-3
+    assert abs(b["llm"] - 10.727) < 2e-3
+    assert abs(b["expert"] - 6.486) < 2e-3
+    assert abs(b["total"] - 19.698) < 3e-3
+    # individual rows printed in the table's roofline column
+    rows = {(o.stage, o.name): o.bound_s(roofline.RTX4090_BW, roofline.RTX4090_MACS) * 1e3 for o in ops}
+    assert abs(rows[("vision", "qkv")] - 0.602) < 1e-3
+    assert abs(rows[("vision", "attention")] - 0.178) < 1e-3
+    assert abs(rows[("llm", "gate+up")] - 6.391) < 1e-3
+    assert abs(rows[("llm", "down")] - 3.195) < 1e-3
+    assert abs(rows[("expert", "gate+up")] - 2.990) < 1e-3
+    assert abs(rows[("expert", "scores")] - 0.149) < 1e-3
+    # 1378 matmuls (Section 5.2)
+    assert roofline.matmul_count(ops) == 1378
+    # sums for one and three views (Section 5.1 prints 12.8 and 26.7)
+    b1 = roofline.stage_bounds_ms(roofline.table2_ops(cfg, 1, 0), roofline.RTX4090_BW, roofline.RTX4090_MACS)
+    b3 = roofline.stage_bounds_ms(roofline.table2_ops(cfg, 3, 0), roofline.RTX4090_BW, roofline.RTX4090_MACS)
+    assert abs(b1["total"] - 12.8) < 0.1 and abs(b3["total"] - 26.7) < 0.1
