@@ -4,44 +4,48 @@
 // state/action block mask.
 //
 // Keys and values arrive already in MFMA fragment order (written that way by the QKV GEMM's
-// epilogue), so every operand fetch is one coalesced 16-byte-per-lane read from L2 and the kernel
-// needs no LDS staging.  Per 32-key chunk a wave computes S^T = K Q^T (keys x queries) so that a
-// lane owns one query row: the running max / sum of the online softmax are per-lane scalars, and
-// the probabilities in the accumulator registers are, without any data movement, the B operand
-// of O^T = V^T P^T.  The four waves of a block take every fourth chunk of the same 32 query rows
-// and merge their partial results through LDS in a fixed order.
+// epilogue), so every operand fetch is one coalesced 16-byte-per-lane read from L2.
+//
+// One block of 8 waves owns 32 query rows of one head.  The kernels of this pass are short and
+// bound by memory round trips, not by arithmetic, so the block is organised to need one round
+// trip when the keys fit (<= 8 chunks of 32 keys per wave-round): at entry every wave issues its
+// loads of Q (to LDS), of the key fragments of "its" chunks (chunk index = wave, wave + 8, ...)
+// and of the value fragments of "its" 32-wide slice of the head dimension, all at once.
+//   phase 1  S^T = K Q^T per chunk (keys x queries): a lane owns one query row, so max and sum
+//            are per-lane scalars; the probabilities in the accumulator registers are, without
+//            any data movement, B-operand fragments of the second product and go to LDS as such;
+//   phase 2  O^T = V^T P^T: wave w accumulates head-dimension slice w over ALL chunks, reading
+//            the probability fragments of every wave from LDS.  No cross-wave merge of O.
+// The softmax uses the exact row maximum (two LDS exchanges), so results do not depend on the
+// chunk-to-wave assignment.
 #include "pi0_internal.h"
 
 #define NEG_BIG (-1.0e30f)
+#define ATT_WAVES 8
+#define ATT_MAXR 4          // key rounds per wave: up to 8 * 4 = 32 chunks = 1024 keys
+#define ATT_VRING 8         // value chunks in flight per wave
 
 template <int DQK, int NVB>
-__global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
+__global__ __launch_bounds__(512) void attention_kernel(AttnParams p) {
   constexpr int S16 = DQK / 16;
+  constexpr int PPR = DQK / 8;                 // 16-byte pieces per query row
+  constexpr int NPQ = 32 * PPR;                // pieces of the Q tile
+  constexpr int QP = (NPQ + 511) / 512;        // pieces per thread
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  float* mw = reinterpret_cast<float*>(smem_raw);          // [4][32]
-  float* lw = mw + 4 * 32;                                 // [4][32]
-  float* ored = lw + 4 * 32;                               // [3][NVB][16][64]
+  bf16* qs = reinterpret_cast<bf16*>(smem_raw);                               // [S16][64][8]
+  float* mw = reinterpret_cast<float*>(smem_raw + (size_t)S16 * 1024);         // [8][32]
+  float* lw = mw + ATT_WAVES * 32;                                             // [8][32]
+  bf16* pf = reinterpret_cast<bf16*>(lw + ATT_WAVES * 32);                     // [ntot][2][64][8]
 
-  const int lane = threadIdx.x & 63;
-  const int w = threadIdx.x >> 6;
+  const int t = threadIdx.x;
+  const int lane = t & 63;
+  const int w = t >> 6;
   const int lq = lane & 31;
   const int lh = lane >> 5;
   const int tile = blockIdx.x;
   const int head = blockIdx.y;
   const int row = tile * 32 + lq;
   const bool row_ok = row < p.Tq;
-
-  // query fragments (B operand): lane (query lq, half lh) holds d = 16 s + 8 lh .. + 8
-  bf16x8 qf[S16];
-#pragma unroll
-  for (int s = 0; s < S16; s++) {
-    if (row_ok) {
-      qf[s] = *reinterpret_cast<const bf16x8*>(p.q + (size_t)row * p.q_ld + head * p.q_head_stride + s * 16 + lh * 8);
-    } else {
-#pragma unroll
-      for (int j = 0; j < 8; j++) qf[s][j] = (bf16)0.0f;
-    }
-  }
 
   int cbeg0 = 0, n0 = p.chunks0;
   if (p.view_tokens > 0) {
@@ -52,130 +56,165 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
   const int ntot = n0 + p.chunks1;
   const bf16* kbase0 = p.k0 + (size_t)head * p.kv_head_stride0;
   const bf16* vbase0 = p.v0 + (size_t)head * p.v_head_stride0;
+  auto kptr = [&](int ci) -> const bf16* {
+    return (ci >= n0 ? p.k1 + (size_t)(ci - n0) * S16 * 512 : kbase0 + (size_t)(cbeg0 + ci) * S16 * 512) + lane * 8;
+  };
+  auto vptr = [&](int ci) -> const bf16* {
+    return (ci >= n0 ? p.v1 + (size_t)(ci - n0) * NVB * 1024 : vbase0 + (size_t)(cbeg0 + ci) * NVB * 1024) + w * 1024 +
+           lane * 8;
+  };
 
-  f32x16 o[NVB];
+  // ---- issue every load of the first round ---------------------------------------------------
+  bf16x8 qreg[QP];
 #pragma unroll
-  for (int vb = 0; vb < NVB; vb++)
+  for (int i = 0; i < QP; i++) {
+    const int pc = t + i * 512;
+    const int r = pc / PPR, kp = pc % PPR;
+    if (pc < NPQ && tile * 32 + r < p.Tq) {
+      qreg[i] = *reinterpret_cast<const bf16x8*>(p.q + (size_t)(tile * 32 + r) * p.q_ld + head * p.q_head_stride + kp * 8);
+    } else {
 #pragma unroll
-    for (int r = 0; r < 16; r++) o[vb][r] = 0.f;
-  float m_run = NEG_BIG, l_run = 0.f;
-
-  for (int ci = w; ci < ntot; ci += 4) {
-    const bool seg1 = ci >= n0;
-    const int chunk = seg1 ? (ci - n0) : (cbeg0 + ci);
-    const bf16* kf = (seg1 ? p.k1 : kbase0) + (size_t)chunk * S16 * 512 + lane * 8;
-    const bf16* vf = (seg1 ? p.v1 : vbase0) + (size_t)chunk * NVB * 1024 + lane * 8;
-    f32x16 sacc;
-#pragma unroll
-    for (int r = 0; r < 16; r++) sacc[r] = 0.f;
-#pragma unroll
-    for (int s = 0; s < S16; s++) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(kf + (size_t)s * 512);
-      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[s], sacc, 0, 0, 0);
+      for (int j = 0; j < 8; j++) qreg[i][j] = (bf16)0.0f;
     }
-    // mask + online softmax (lane = query row; registers = keys 8*(r/4) + 4*lh + r%4)
-    float sv[16];
-    bool ok[16];
-    float cmax = NEG_BIG;
+  }
+  bf16x8 kf[S16];
+  if (w < ntot) {
+    const bf16* kp0 = kptr(w);
 #pragma unroll
-    for (int r = 0; r < 16; r++) {
-      const int kk = 8 * (r >> 2) + 4 * lh + (r & 3);
-      const int key = chunk * 32 + kk;
-      bool valid;
-      if (!seg1) {
-        valid = key < p.valid0;
-      } else {
-        valid = p.suffix_mask ? (row == 0 ? key == 0 : true) : true;
-      }
-      ok[r] = valid;
-      sv[r] = sacc[r] * p.scale;
-      if (valid) cmax = fmaxf(cmax, sv[r]);
-    }
-    cmax = fmaxf(cmax, __shfl_xor(cmax, 32, 64));
-    const float m_new = fmaxf(m_run, cmax);
-    const float alpha = __expf(m_run - m_new);
-    float psum = 0.f;
-    float pr[16];
+    for (int s = 0; s < S16; s++) kf[s] = *reinterpret_cast<const bf16x8*>(kp0 + (size_t)s * 512);
+  }
+  bf16x8 vf[ATT_VRING * 2];
+  const bool pv_wave = w < NVB;
+  if (pv_wave) {
 #pragma unroll
-    for (int r = 0; r < 16; r++) {
-      pr[r] = ok[r] ? __expf(sv[r] - m_new) : 0.f;
-      psum += pr[r];
-    }
-    psum += __shfl_xor(psum, 32, 64);
-    l_run = l_run * alpha + psum;
-    m_run = m_new;
-#pragma unroll
-    for (int vb = 0; vb < NVB; vb++)
-#pragma unroll
-      for (int r = 0; r < 16; r++) o[vb][r] *= alpha;
-    bf16x8 pb[2];
-#pragma unroll
-    for (int s2 = 0; s2 < 2; s2++)
-#pragma unroll
-      for (int j = 0; j < 8; j++) pb[s2][j] = (bf16)pr[8 * s2 + j];
-#pragma unroll
-    for (int vb = 0; vb < NVB; vb++) {
-#pragma unroll
-      for (int s2 = 0; s2 < 2; s2++) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(vf + (size_t)(vb * 2 + s2) * 512);
-        o[vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[s2], o[vb], 0, 0, 0);
+    for (int c = 0; c < ATT_VRING; c++) {
+      if (c < ntot) {
+        const bf16* vp = vptr(c);
+        vf[2 * c] = *reinterpret_cast<const bf16x8*>(vp);
+        vf[2 * c + 1] = *reinterpret_cast<const bf16x8*>(vp + 512);
       }
     }
   }
-
-  // merge the four waves
-  if (lh == 0) {
-    mw[w * 32 + lq] = m_run;
-    lw[w * 32 + lq] = l_run;
+#pragma unroll
+  for (int i = 0; i < QP; i++) {
+    const int pc = t + i * 512;
+    if (pc < NPQ) {
+      const int r = pc / PPR, kp = pc % PPR;
+      *reinterpret_cast<bf16x8*>(qs + ((size_t)(kp >> 1) * 64 + (kp & 1) * 32 + r) * 8) = qreg[i];
+    }
   }
+  __syncthreads();
+
+  // ---- phase 1: scores of this wave's chunks ------------------------------------------------
+  float sv[ATT_MAXR][16];
+  float m_loc = NEG_BIG;
+#pragma unroll
+  for (int r = 0; r < ATT_MAXR; r++) {
+    const int ci = w + ATT_WAVES * r;
+    if (ci < ntot) {
+      const bool more = ci + ATT_WAVES < ntot;
+      const bf16* kn = more ? kptr(ci + ATT_WAVES) : nullptr;
+      f32x16 sacc;
+#pragma unroll
+      for (int e = 0; e < 16; e++) sacc[e] = 0.f;
+#pragma unroll
+      for (int s = 0; s < S16; s++) {
+        const bf16x8 a = kf[s];
+        if (more) kf[s] = *reinterpret_cast<const bf16x8*>(kn + (size_t)s * 512);
+        const bf16x8 b = *reinterpret_cast<const bf16x8*>(qs + ((size_t)s * 64 + lane) * 8);
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, sacc, 0, 0, 0);
+      }
+      const bool seg1 = ci >= n0;
+      const int chunk = seg1 ? (ci - n0) : (cbeg0 + ci);
+#pragma unroll
+      for (int e = 0; e < 16; e++) {
+        const int key = chunk * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
+        const bool valid = seg1 ? (p.suffix_mask ? (row == 0 ? key == 0 : true) : true) : key < p.valid0;
+        sv[r][e] = valid ? sacc[e] * p.scale : NEG_BIG;
+        m_loc = fmaxf(m_loc, sv[r][e]);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 16; e++) sv[r][e] = NEG_BIG;
+    }
+  }
+  m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32, 64));
+  if (lh == 0) mw[w * 32 + lq] = m_loc;
   __syncthreads();
   float m_all = NEG_BIG;
 #pragma unroll
-  for (int i = 0; i < 4; i++) m_all = fmaxf(m_all, mw[i * 32 + lq]);
+  for (int i = 0; i < ATT_WAVES; i++) m_all = fmaxf(m_all, mw[i * 32 + lq]);
+  float l_loc = 0.f;
+#pragma unroll
+  for (int r = 0; r < ATT_MAXR; r++) {
+    const int ci = w + ATT_WAVES * r;
+    if (ci < ntot) {
+      float pr[16];
+#pragma unroll
+      for (int e = 0; e < 16; e++) {
+        pr[e] = sv[r][e] > 0.5f * NEG_BIG ? __expf(sv[r][e] - m_all) : 0.f;   // masked keys: exactly 0
+        l_loc += pr[e];
+      }
+#pragma unroll
+      for (int s2 = 0; s2 < 2; s2++) {
+        bf16x8 pb;
+#pragma unroll
+        for (int j = 0; j < 8; j++) pb[j] = (bf16)pr[8 * s2 + j];
+        *reinterpret_cast<bf16x8*>(pf + ((size_t)(ci * 2 + s2) * 64 + lane) * 8) = pb;
+      }
+    }
+  }
+  l_loc += __shfl_xor(l_loc, 32, 64);
+  if (lh == 0) lw[w * 32 + lq] = l_loc;
+  __syncthreads();
+  if (!pv_wave) return;
+
+  // ---- phase 2: this wave's 32-wide slice of the head dimension over all chunks --------------
+  f32x16 o;
+#pragma unroll
+  for (int e = 0; e < 16; e++) o[e] = 0.f;
+  for (int c0 = 0; c0 < ntot; c0 += ATT_VRING) {
+#pragma unroll
+    for (int cc = 0; cc < ATT_VRING; cc++) {
+      const int c = c0 + cc;
+      if (c < ntot) {
+        const bool more = c + ATT_VRING < ntot;
+        const bf16* vn = more ? vptr(c + ATT_VRING) : nullptr;
+#pragma unroll
+        for (int s2 = 0; s2 < 2; s2++) {
+          const bf16x8 a = vf[2 * cc + s2];
+          if (more) vf[2 * cc + s2] = *reinterpret_cast<const bf16x8*>(vn + (size_t)s2 * 512);
+          const bf16x8 b = *reinterpret_cast<const bf16x8*>(pf + ((size_t)(c * 2 + s2) * 64 + lane) * 8);
+          o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, o, 0, 0, 0);
+        }
+      }
+    }
+  }
   float l_all = 0.f;
 #pragma unroll
-  for (int i = 0; i < 4; i++) l_all += lw[i * 32 + lq] * __expf(mw[i * 32 + lq] - m_all);
-  const float f = __expf(m_run - m_all) / l_all;
+  for (int i = 0; i < ATT_WAVES; i++) l_all += lw[i * 32 + lq];
+  const float inv = 1.0f / l_all;
+  if (!row_ok) return;
 #pragma unroll
-  for (int vb = 0; vb < NVB; vb++)
-#pragma unroll
-    for (int r = 0; r < 16; r++) o[vb][r] *= f;
-  if (w > 0) {
-#pragma unroll
-    for (int vb = 0; vb < NVB; vb++)
-#pragma unroll
-      for (int r = 0; r < 16; r++) ored[(((size_t)(w - 1) * NVB + vb) * 16 + r) * 64 + lane] = o[vb][r];
-  }
-  __syncthreads();
-  if (w != 0 || !row_ok) return;
-#pragma unroll
-  for (int i = 1; i < 4; i++)
-#pragma unroll
-    for (int vb = 0; vb < NVB; vb++)
-#pragma unroll
-      for (int r = 0; r < 16; r++) o[vb][r] += ored[(((size_t)(i - 1) * NVB + vb) * 16 + r) * 64 + lane];
-#pragma unroll
-  for (int vb = 0; vb < NVB; vb++) {
-#pragma unroll
-    for (int i = 0; i < 4; i++) {
-      const int d = vb * 32 + 8 * i + 4 * lh;
-      if (d < p.head_dim) {
-        const bf16x4 ob = {(bf16)o[vb][4 * i], (bf16)o[vb][4 * i + 1], (bf16)o[vb][4 * i + 2], (bf16)o[vb][4 * i + 3]};
-        *reinterpret_cast<bf16x4*>(p.out + (size_t)row * p.out_ld + head * p.head_dim + d) = ob;
-      }
+  for (int i = 0; i < 4; i++) {
+    const int d = w * 32 + 8 * i + 4 * lh;
+    if (d < p.head_dim) {
+      const bf16x4 ob = {(bf16)(o[4 * i] * inv), (bf16)(o[4 * i + 1] * inv), (bf16)(o[4 * i + 2] * inv),
+                         (bf16)(o[4 * i + 3] * inv)};
+      *reinterpret_cast<bf16x4*>(p.out + (size_t)row * p.out_ld + head * p.head_dim + d) = ob;
     }
   }
 }
 
-template <int NVB>
-static constexpr int attn_smem() { return (2 * 4 * 32 + 3 * NVB * 16 * 64) * 4; }
+template <int DQK>
+static int attn_smem(int ntot) { return (DQK / 16) * 1024 + 2 * ATT_WAVES * 32 * 4 + ntot * 2048; }
 
 hipError_t attention_init_attributes() {
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_kernel<256, 8>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, attn_smem<8>());
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, attn_smem<256>(ATT_WAVES * ATT_MAXR));
   if (e != hipSuccess) return e;
   return hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_kernel<80, 3>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, attn_smem<3>());
+                             hipFuncAttributeMaxDynamicSharedMemorySize, attn_smem<80>(ATT_WAVES * ATT_MAXR));
 }
 
 hipError_t launch_attention(hipStream_t s, const AttnParams& p) {
@@ -185,16 +224,18 @@ hipError_t launch_attention(hipStream_t s, const AttnParams& p) {
   if (p.chunks1 != 0 && (p.k1 == nullptr || p.v1 == nullptr)) return hipErrorInvalidValue;
   if (p.chunks1 < 0 || p.chunks1 > 2) return hipErrorInvalidValue;
   if (p.suffix_mask && p.Tq > 32 * p.chunks1) return hipErrorInvalidValue;
+  int n0 = p.chunks0;
   if (p.view_tokens > 0) {
     if (p.view_tokens % 32 != 0 || p.Tq % p.view_tokens != 0 || p.chunks0 * 32 != p.Tq) return hipErrorInvalidValue;
+    n0 = p.view_tokens / 32;
   }
+  const int ntot = n0 + p.chunks1;
+  if (ntot > ATT_WAVES * ATT_MAXR) return hipErrorInvalidValue;   // at most 1024 keys per query row
   dim3 grid((p.Tq + 31) / 32, p.heads, 1);
   if (p.head_dim == 256) {
-    constexpr int smem = attn_smem<8>();
-    attention_kernel<256, 8><<<grid, dim3(256), smem, s>>>(p);
+    attention_kernel<256, 8><<<grid, dim3(512), attn_smem<256>(ntot), s>>>(p);
   } else if (p.head_dim <= 80 && p.head_dim > 64) {
-    constexpr int smem = attn_smem<3>();
-    attention_kernel<80, 3><<<grid, dim3(256), smem, s>>>(p);
+    attention_kernel<80, 3><<<grid, dim3(512), attn_smem<80>(ntot), s>>>(p);
   } else {
     return hipErrorInvalidValue;
   }

@@ -25,6 +25,136 @@ __device__ __forceinline__ bf16x8 zero8() {
   return z;
 }
 
+// One 32-token x 32-feature accumulator tile -> memory.  `acc` is the MFMA accumulator of the
+// calling lane (token = lane % 32, features nt*32 + 8*(r/4) + 4*(lane/32) + r%4), `m` the global
+// row, `ml` the row inside the block's tile (index into the statistics), stat = [sum | sum sq].
+template <int PRO, int EPI>
+__device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16& acc, int nt, int m, int ml, int lh,
+                                              const float* stat, int ROWS, int zsplit) {
+  const float inv_k = 1.0f / (float)p.k_true;
+  {
+    float rs = 1.f, mu = 0.f;
+    if (PRO == PRO_RMS) {
+      rs = rsqrtf(stat[ROWS + ml] * inv_k + 1e-6f);
+    } else if (PRO == PRO_LN) {
+      mu = stat[ml] * inv_k;
+      float var = stat[ROWS + ml] * inv_k - mu * mu;
+      rs = rsqrtf(fmaxf(var, 0.f) + 1e-6f);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      const int n4 = nt * 32 + 8 * i + 4 * lh;
+      float v[4];
+#pragma unroll
+      for (int j = 0; j < 4; j++) v[j] = acc[4 * i + j];
+      if (EPI == EPI_PARTIAL) {
+        f32x4 o = {v[0], v[1], v[2], v[3]};
+        *reinterpret_cast<f32x4*>(p.out_f32 + ((size_t)zsplit * p.M + m) * p.ldo + n4) = o;
+        continue;
+      }
+      if (PRO == PRO_RMS) {
+#pragma unroll
+        for (int j = 0; j < 4; j++) v[j] *= rs;
+      } else if (PRO == PRO_LN) {
+        const f32x4 cs = *reinterpret_cast<const f32x4*>(p.colsum + n4);
+#pragma unroll
+        for (int j = 0; j < 4; j++) v[j] = rs * (v[j] - mu * cs[j]);
+      }
+      if (p.bias != nullptr) {
+        const f32x4 bb = *reinterpret_cast<const f32x4*>(p.bias + n4);
+#pragma unroll
+        for (int j = 0; j < 4; j++) v[j] += bb[j];
+      }
+      if (EPI == EPI_RESID) {
+        if (n4 < p.n_valid) {
+          if (p.resid != nullptr) {
+            const int rr = p.resid_mod > 0 ? (m % p.resid_mod) : m;
+            const f32x4 r4 = *reinterpret_cast<const f32x4*>(p.resid + (size_t)rr * p.ldo + n4);
+#pragma unroll
+            for (int j = 0; j < 4; j++) v[j] += r4[j];
+          }
+          const int mo = m + p.row_offset;
+          f32x4 o = {v[0], v[1], v[2], v[3]};
+          *reinterpret_cast<f32x4*>(p.out_f32 + (size_t)mo * p.ldo + n4) = o;
+          bf16x4 ob = {(bf16)v[0], (bf16)v[1], (bf16)v[2], (bf16)v[3]};
+          *reinterpret_cast<bf16x4*>(p.out_bf16 + (size_t)mo * p.ldo2 + n4) = ob;
+        }
+      } else if (EPI == EPI_BF16) {
+        if (n4 < p.n_valid) {
+          if (p.act == ACT_GELU) {
+#pragma unroll
+            for (int j = 0; j < 4; j++) v[j] = gelu_tanh_f(v[j]);
+          }
+          bf16x4 ob = {(bf16)v[0], (bf16)v[1], (bf16)v[2], (bf16)v[3]};
+          *reinterpret_cast<bf16x4*>(p.out_bf16 + (size_t)m * p.ldo + n4) = ob;
+        }
+      } else if (EPI == EPI_GEGLU) {
+        bf16x2 ob = {(bf16)(gelu_tanh_f(v[0]) * v[1]), (bf16)(gelu_tanh_f(v[2]) * v[3])};
+        *reinterpret_cast<bf16x2*>(p.out_bf16 + (size_t)m * p.ldo + (n4 >> 1)) = ob;
+      } else if (EPI == EPI_EULER) {
+        if (m >= 1) {
+#pragma unroll
+          for (int j = 0; j < 4; j++) {
+            if (n4 + j < p.n_valid) p.out_f32[(size_t)(m - 1) * p.ldo + n4 + j] += p.dt * v[j];
+          }
+        }
+      } else if (EPI == EPI_QKV) {
+        const int S16 = p.dqk_pad >> 4;
+        const int key = m;
+        const int kc = key >> 5, kk = key & 31;
+        if (n4 < p.q_cols + p.k_cols) {
+          const bool is_q = n4 < p.q_cols;
+          const int nl = is_q ? n4 : n4 - p.q_cols;
+          if (p.rope != nullptr) {
+            // packed head layout: row 2i = dim i, row 2i+1 = dim i + 128
+            const int head = nl >> 8;
+            const int i0 = (nl & 255) >> 1;          // even
+            const float* cs = p.rope + ((size_t)(p.pos0 + m) * 128 + i0) * 2;
+            const f32x4 c4 = *reinterpret_cast<const f32x4*>(cs);   // cos i0, sin i0, cos i0+1, sin i0+1
+            const float lo0 = v[0] * c4[0] - v[1] * c4[1], hi0 = v[1] * c4[0] + v[0] * c4[1];
+            const float lo1 = v[2] * c4[2] - v[3] * c4[3], hi1 = v[3] * c4[2] + v[2] * c4[3];
+            const bf16x2 lo = {(bf16)lo0, (bf16)lo1};
+            const bf16x2 hi = {(bf16)hi0, (bf16)hi1};
+            if (is_q) {
+              bf16* dst = p.out_bf16 + (size_t)m * p.ldo + head * 256 + i0;
+              *reinterpret_cast<bf16x2*>(dst) = lo;
+              *reinterpret_cast<bf16x2*>(dst + 128) = hi;
+            } else {
+              bf16* dst = p.kfrag + ((size_t)kc * S16) * 512 + kk * 8;
+              const int d0 = i0, d1 = i0 + 128;
+              *reinterpret_cast<bf16x2*>(dst + (size_t)(d0 >> 4) * 512 + ((d0 & 15) >> 3) * 256 + (d0 & 7)) = lo;
+              *reinterpret_cast<bf16x2*>(dst + (size_t)(d1 >> 4) * 512 + ((d1 & 15) >> 3) * 256 + (d1 & 7)) = hi;
+            }
+          } else {
+            const int head = nl / p.head_dim;
+            const int d = nl - head * p.head_dim;    // multiple of 4
+            const bf16x4 ob = {(bf16)v[0], (bf16)v[1], (bf16)v[2], (bf16)v[3]};
+            if (is_q) {
+              *reinterpret_cast<bf16x4*>(p.out_bf16 + (size_t)m * p.ldo + head * p.dqk_pad + d) = ob;
+            } else {
+              bf16* dst = p.kfrag + ((size_t)head * p.kv_chunks + kc) * S16 * 512 + kk * 8;
+              *reinterpret_cast<bf16x4*>(dst + (size_t)(d >> 4) * 512 + ((d & 15) >> 3) * 256 + (d & 7)) = ob;
+            }
+          }
+        } else {
+          const int nl = n4 - p.q_cols - p.k_cols;
+          const int head = nl / p.head_dim;
+          const int d = nl - head * p.head_dim;
+          if (head < p.kv_heads) {
+            const int s2 = kk >> 4, g = (kk & 15) >> 3, hh = (kk & 7) >> 2, jp = kk & 3;
+            bf16* dst = p.vfrag + (((size_t)head * p.kv_chunks + kc) * p.nvb) * 1024 + s2 * 512 + hh * 256 + 4 * g + jp;
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+              const int dd = d + j;
+              dst[(size_t)(dd >> 5) * 1024 + (dd & 31) * 8] = (bf16)v[j];
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
 template <int MB, int WN, int WK, int PRO, int EPI>
 __global__ __launch_bounds__(64 * WN * WK) void gemm_kernel(GemmParams p) {
   constexpr int NT = 64 * WN * WK;        // threads
@@ -196,133 +326,130 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_kernel(GemmParams p) {
   if (wk != 0 || !wave_active) return;
 
   // ---- epilogue --------------------------------------------------------------------------------
-  const float inv_k = 1.0f / (float)p.k_true;
 #pragma unroll
   for (int mb = 0; mb < MB; mb++) {
     const int ml = mb * 32 + lq;
     const int m = m0 + ml;
-    if (m >= p.M) continue;
-    float rs = 1.f, mu = 0.f;
-    if (PRO == PRO_RMS) {
-      rs = rsqrtf(stat[ROWS + ml] * inv_k + 1e-6f);
-    } else if (PRO == PRO_LN) {
-      mu = stat[ml] * inv_k;
-      float var = stat[ROWS + ml] * inv_k - mu * mu;
-      rs = rsqrtf(fmaxf(var, 0.f) + 1e-6f);
+    if (m < p.M) epilogue_tile<PRO, EPI>(p, acc[mb], nt, m, ml, lh, stat, ROWS, blockIdx.y);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Skinny GEMM (at most 64 tokens): the action expert's projections.  These kernels move a few MB
+// of weights each and are bound by memory round trips, so a block issues ALL of its loads at entry
+// - the whole activation slice [64][k range <= 1024] (to registers, then LDS) and each wave's 8
+// weight fragments - waits once, and computes.  One block = one 32-feature tile, 8 waves splitting
+// the k range; partial tiles are summed through LDS in wave order (deterministic).
+// ------------------------------------------------------------------------------------------------
+#define SK_WAVES 8
+#define SK_KMAX 1024
+#define SK_LDX (SK_KMAX + LDS_PAD)
+
+template <int PRO, int EPI>
+__global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16* xs = reinterpret_cast<bf16*>(smem_raw);                                           // [64][SK_LDX]
+  float* stat = reinterpret_cast<float*>(smem_raw + (size_t)64 * SK_LDX * sizeof(bf16));  // [2][64]
+  const int t = threadIdx.x;
+  const int lane = t & 63;
+  const int w = t >> 6;
+  const int lq = lane & 31;
+  const int lh = lane >> 5;
+  const int nt = blockIdx.x;
+  const int k_pad = p.W.k_pad;
+  const int kbeg = blockIdx.y * p.k_per_split;
+  const int kend = min(kbeg + p.k_per_split, k_pad);
+  const int n16 = (kend - kbeg) >> 4;          // k16 steps of this block (<= 64)
+  const int KC16 = k_pad >> 4;
+
+  // weights: wave w owns steps w*8 .. w*8+7
+  bf16x8 wf[8];
+  const bf16* wbase = p.W.w + ((size_t)nt * KC16 + (kbeg >> 4)) * 512 + lane * 8;
+#pragma unroll
+  for (int i = 0; i < 8; i++) {
+    const int st = w * 8 + i;
+    if (st < n16) wf[i] = *reinterpret_cast<const bf16x8*>(wbase + (size_t)st * 512);
+    else wf[i] = zero8();
+  }
+  // activations: wave w stages rows w, w+8, ..., each lane pieces lane and lane+64 of the row
+  bf16x8 xr[16];
+#pragma unroll
+  for (int i = 0; i < 8; i++) {
+    const int row = w + 8 * i;
+#pragma unroll
+    for (int j = 0; j < 2; j++) {
+      const int gk = kbeg + (lane + 64 * j) * 8;
+      if (row < p.M && gk < kend) xr[2 * i + j] = *reinterpret_cast<const bf16x8*>(p.X + (size_t)row * p.ldx + gk);
+      else xr[2 * i + j] = zero8();
     }
+  }
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-      const int n4 = nt * 32 + 8 * i + 4 * lh;
-      float v[4];
+  for (int i = 0; i < 8; i++) {
+    const int row = w + 8 * i;
+    float a = 0.f, b = 0.f;
 #pragma unroll
-      for (int j = 0; j < 4; j++) v[j] = acc[mb][4 * i + j];
-      if (EPI == EPI_PARTIAL) {
-        f32x4 o = {v[0], v[1], v[2], v[3]};
-        *reinterpret_cast<f32x4*>(p.out_f32 + ((size_t)blockIdx.y * p.M + m) * p.ldo + n4) = o;
-        continue;
+    for (int j = 0; j < 2; j++) {
+      *reinterpret_cast<bf16x8*>(xs + (size_t)row * SK_LDX + (lane + 64 * j) * 8) = xr[2 * i + j];
+      if (PRO != PRO_NONE) {
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+          const float v = (float)xr[2 * i + j][e];
+          a += v;
+          b += v * v;
+        }
       }
-      if (PRO == PRO_RMS) {
+    }
+    if (PRO != PRO_NONE) {
 #pragma unroll
-        for (int j = 0; j < 4; j++) v[j] *= rs;
-      } else if (PRO == PRO_LN) {
-        const f32x4 cs = *reinterpret_cast<const f32x4*>(p.colsum + n4);
-#pragma unroll
-        for (int j = 0; j < 4; j++) v[j] = rs * (v[j] - mu * cs[j]);
+      for (int off = 1; off < 64; off <<= 1) {
+        a += __shfl_xor(a, off, 64);
+        b += __shfl_xor(b, off, 64);
       }
-      if (p.bias != nullptr) {
-        const f32x4 bb = *reinterpret_cast<const f32x4*>(p.bias + n4);
-#pragma unroll
-        for (int j = 0; j < 4; j++) v[j] += bb[j];
-      }
-      if (EPI == EPI_RESID) {
-        if (n4 < p.n_valid) {
-          if (p.resid != nullptr) {
-            const int rr = p.resid_mod > 0 ? (m % p.resid_mod) : m;
-            const f32x4 r4 = *reinterpret_cast<const f32x4*>(p.resid + (size_t)rr * p.ldo + n4);
-#pragma unroll
-            for (int j = 0; j < 4; j++) v[j] += r4[j];
-          }
-          const int mo = m + p.row_offset;
-          f32x4 o = {v[0], v[1], v[2], v[3]};
-          *reinterpret_cast<f32x4*>(p.out_f32 + (size_t)mo * p.ldo + n4) = o;
-          bf16x4 ob = {(bf16)v[0], (bf16)v[1], (bf16)v[2], (bf16)v[3]};
-          *reinterpret_cast<bf16x4*>(p.out_bf16 + (size_t)mo * p.ldo2 + n4) = ob;
-        }
-      } else if (EPI == EPI_BF16) {
-        if (n4 < p.n_valid) {
-          if (p.act == ACT_GELU) {
-#pragma unroll
-            for (int j = 0; j < 4; j++) v[j] = gelu_tanh_f(v[j]);
-          }
-          bf16x4 ob = {(bf16)v[0], (bf16)v[1], (bf16)v[2], (bf16)v[3]};
-          *reinterpret_cast<bf16x4*>(p.out_bf16 + (size_t)m * p.ldo + n4) = ob;
-        }
-      } else if (EPI == EPI_GEGLU) {
-        bf16x2 ob = {(bf16)(gelu_tanh_f(v[0]) * v[1]), (bf16)(gelu_tanh_f(v[2]) * v[3])};
-        *reinterpret_cast<bf16x2*>(p.out_bf16 + (size_t)m * p.ldo + (n4 >> 1)) = ob;
-      } else if (EPI == EPI_EULER) {
-        if (m >= 1) {
-#pragma unroll
-          for (int j = 0; j < 4; j++) {
-            if (n4 + j < p.n_valid) p.out_f32[(size_t)(m - 1) * p.ldo + n4 + j] += p.dt * v[j];
-          }
-        }
-      } else if (EPI == EPI_QKV) {
-        const int S16 = p.dqk_pad >> 4;
-        const int key = m;
-        const int kc = key >> 5, kk = key & 31;
-        if (n4 < p.q_cols + p.k_cols) {
-          const bool is_q = n4 < p.q_cols;
-          const int nl = is_q ? n4 : n4 - p.q_cols;
-          if (p.rope != nullptr) {
-            // packed head layout: row 2i = dim i, row 2i+1 = dim i + 128
-            const int head = nl >> 8;
-            const int i0 = (nl & 255) >> 1;          // even
-            const float* cs = p.rope + ((size_t)(p.pos0 + m) * 128 + i0) * 2;
-            const f32x4 c4 = *reinterpret_cast<const f32x4*>(cs);   // cos i0, sin i0, cos i0+1, sin i0+1
-            const float lo0 = v[0] * c4[0] - v[1] * c4[1], hi0 = v[1] * c4[0] + v[0] * c4[1];
-            const float lo1 = v[2] * c4[2] - v[3] * c4[3], hi1 = v[3] * c4[2] + v[2] * c4[3];
-            const bf16x2 lo = {(bf16)lo0, (bf16)lo1};
-            const bf16x2 hi = {(bf16)hi0, (bf16)hi1};
-            if (is_q) {
-              bf16* dst = p.out_bf16 + (size_t)m * p.ldo + head * 256 + i0;
-              *reinterpret_cast<bf16x2*>(dst) = lo;
-              *reinterpret_cast<bf16x2*>(dst + 128) = hi;
-            } else {
-              bf16* dst = p.kfrag + ((size_t)kc * S16) * 512 + kk * 8;
-              const int d0 = i0, d1 = i0 + 128;
-              *reinterpret_cast<bf16x2*>(dst + (size_t)(d0 >> 4) * 512 + ((d0 & 15) >> 3) * 256 + (d0 & 7)) = lo;
-              *reinterpret_cast<bf16x2*>(dst + (size_t)(d1 >> 4) * 512 + ((d1 & 15) >> 3) * 256 + (d1 & 7)) = hi;
-            }
-          } else {
-            const int head = nl / p.head_dim;
-            const int d = nl - head * p.head_dim;    // multiple of 4
-            const bf16x4 ob = {(bf16)v[0], (bf16)v[1], (bf16)v[2], (bf16)v[3]};
-            if (is_q) {
-              *reinterpret_cast<bf16x4*>(p.out_bf16 + (size_t)m * p.ldo + head * p.dqk_pad + d) = ob;
-            } else {
-              bf16* dst = p.kfrag + ((size_t)head * p.kv_chunks + kc) * S16 * 512 + kk * 8;
-              *reinterpret_cast<bf16x4*>(dst + (size_t)(d >> 4) * 512 + ((d & 15) >> 3) * 256 + (d & 7)) = ob;
-            }
-          }
-        } else {
-          const int nl = n4 - p.q_cols - p.k_cols;
-          const int head = nl / p.head_dim;
-          const int d = nl - head * p.head_dim;
-          if (head < p.kv_heads) {
-            const int s2 = kk >> 4, g = (kk & 15) >> 3, hh = (kk & 7) >> 2, jp = kk & 3;
-            bf16* dst = p.vfrag + (((size_t)head * p.kv_chunks + kc) * p.nvb) * 1024 + s2 * 512 + hh * 256 + 4 * g + jp;
-#pragma unroll
-            for (int j = 0; j < 4; j++) {
-              const int dd = d + j;
-              dst[(size_t)(dd >> 5) * 1024 + (dd & 31) * 8] = (bf16)v[j];
-            }
-          }
-        }
+      if (lane == 0) {
+        stat[row] = a;
+        stat[64 + row] = b;
       }
     }
   }
+  __syncthreads();
+
+  f32x16 acc[2];
+#pragma unroll
+  for (int mb = 0; mb < 2; mb++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) acc[mb][r] = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; i++) {
+    const int st = w * 8 + i;
+    if (st < n16) {
+#pragma unroll
+      for (int mb = 0; mb < 2; mb++) {
+        const bf16x8 b = *reinterpret_cast<const bf16x8*>(xs + (size_t)(mb * 32 + lq) * SK_LDX + st * 16 + lh * 8);
+        acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], b, acc[mb], 0, 0, 0);
+      }
+    }
+  }
+  __syncthreads();                                     // all reads of xs done: reuse it for the reduction
+  float* red = reinterpret_cast<float*>(smem_raw);     // [8 waves][2][16][64]
+#pragma unroll
+  for (int mb = 0; mb < 2; mb++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) red[(((size_t)w * 2 + mb) * 16 + r) * 64 + lane] = acc[mb][r];
+  __syncthreads();
+  if (w >= 2) return;
+  const int mb = w;                                    // waves 0 and 1 finish one 32-token tile each
+  f32x16 sum;
+#pragma unroll
+  for (int r = 0; r < 16; r++) sum[r] = 0.f;
+#pragma unroll
+  for (int ww = 0; ww < SK_WAVES; ww++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) sum[r] += red[(((size_t)ww * 2 + mb) * 16 + r) * 64 + lane];
+  const int ml = mb * 32 + lq;
+  if (ml < p.M) epilogue_tile<PRO, EPI>(p, sum, nt, ml, ml, lh, stat, 64, blockIdx.y);
 }
+
+static constexpr int skinny_smem_bytes() { return 64 * SK_LDX * 2 + 2 * 64 * 4; }
 
 // ------------------------------------------------------------------------------------------------
 template <int MB, int WN, int WK>
@@ -371,7 +498,22 @@ static hipError_t set_attr() {
   X(TILE_M64_K8, 2, 1, 8, PRO_NONE, EPI_RESID)             \
   X(TILE_M64_K8, 2, 1, 8, PRO_RMS, EPI_EULER)
 
+#define SKINNY_VARIANTS(X)      \
+  X(PRO_NONE, EPI_RESID)        \
+  X(PRO_NONE, EPI_PARTIAL)      \
+  X(PRO_RMS, EPI_QKV)           \
+  X(PRO_RMS, EPI_GEGLU)         \
+  X(PRO_RMS, EPI_EULER)
+
 hipError_t gemm_init_attributes() {
+#define X(PRO, EPI)                                                                                              \
+  {                                                                                                              \
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_kernel<PRO, EPI>),             \
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, skinny_smem_bytes());         \
+    if (e != hipSuccess) return e;                                                                               \
+  }
+  SKINNY_VARIANTS(X)
+#undef X
 #define X(T, MB, WN, WK, PRO, EPI)                                    \
   {                                                                   \
     hipError_t e = set_attr<MB, WN, WK, PRO, EPI>();                  \
@@ -391,6 +533,17 @@ hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmPara
   if (pro != PRO_NONE && z_splits != 1) return hipErrorInvalidValue;
   if (epi != EPI_PARTIAL && z_splits != 1) return hipErrorInvalidValue;
   if (p.m_tiles < 1) return hipErrorInvalidValue;
+  if (tile == TILE_SKINNY) {
+    if (p.M > 64 || p.m_tiles != 1 || p.k_per_split > SK_KMAX || p.k_per_split % 16 != 0) return hipErrorInvalidValue;
+#define X(PRO, EPI)                                                                                          \
+  if (pro == PRO && epi == EPI) {                                                                            \
+    gemm_skinny_kernel<PRO, EPI><<<dim3(p.n_tiles, z_splits), dim3(64 * SK_WAVES), skinny_smem_bytes(), s>>>(p); \
+    return hipGetLastError();                                                                                \
+  }
+    SKINNY_VARIANTS(X)
+#undef X
+    return hipErrorInvalidValue;
+  }
 #define X(T, MB, WN, WK, PRO, EPI)                                             \
   if (tile == T && pro == PRO && epi == EPI) {                                  \
     if (p.m_tiles * MB * 32 < p.M) return hipErrorInvalidValue;                 \

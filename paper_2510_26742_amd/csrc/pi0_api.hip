@@ -335,13 +335,14 @@ GemmParams gp_base(pi0_ctx* c, const PW& pw, const bf16* X, int ldx, int M, int 
 
 // split-K GEMM into the partial buffer followed by the fixed-order reduction with bias/residual
 void gemm_splitk_resid(Run& r, const PW& pw, const bf16* X, int ldx, int M, int k_true, int z, int k_per_split,
-                       const float* bias, float* resid_io, bf16* shadow, int n_true) {
+                       const float* bias, float* resid_io, bf16* shadow, int n_true, int tile = TILE_M256_N128,
+                       int rows_per_tile = 256) {
   pi0_ctx* c = r.c;
-  GemmParams p = gp_base(c, pw, X, ldx, M, 256, k_true);
+  GemmParams p = gp_base(c, pw, X, ldx, M, rows_per_tile, k_true);
   p.k_per_split = k_per_split;
   p.out_f32 = at<float>(c, c->wl.part);
   p.ldo = pw.n_pad;
-  RUN_GEMM(r, TILE_M256_N128, PRO_NONE, EPI_PARTIAL, p, z);
+  RUN_GEMM(r, tile, PRO_NONE, EPI_PARTIAL, p, z);
   ReduceParams q;
   q.part = p.out_f32;
   q.Z = z; q.M = M; q.N = n_true; q.ldp = pw.n_pad;
@@ -517,7 +518,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
       p.out_f32 = at<float>(c, w.y);
       p.out_bf16 = at<bf16>(c, w.y_b);
       p.ldo = d.X; p.ldo2 = d.X; p.n_valid = d.X; p.row_offset = 1;
-      RUN_GEMM(r, TILE_M64_K4, PRO_NONE, EPI_RESID, p, 1);
+      RUN_GEMM(r, TILE_SKINNY, PRO_NONE, EPI_RESID, p, 1);
     }
     const bool tap_this = taps && (k == 0 || k == d.steps - 1);
     for (int l = 0; l < d.Le; l++) {
@@ -533,7 +534,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
         p.pos0 = P;
         p.q_cols = d.H * 256; p.k_cols = 256;
         p.head_dim = 256; p.dqk_pad = 256; p.nvb = 8; p.kv_heads = 1; p.kv_chunks = 2;
-        RUN_GEMM(r, TILE_M64_K4, PRO_RMS, EPI_QKV, p, 1);
+        RUN_GEMM(r, TILE_SKINNY, PRO_RMS, EPI_QKV, p, 1);
       }
       {  // C4 + C5: scores, block mask, softmax, PV over [cache ; own keys]
         AttnParams a;
@@ -547,26 +548,18 @@ void run_denoise(Run& r, int P, Taps* taps) {
         a.out = at<bf16>(c, w.eattn); a.out_ld = d.H * 256; a.head_dim = 256;
         RUN(r, launch_attention(r.s, a));
       }
-      {  // C6: O-projection + residual
-        GemmParams p = gp_base(c, L.o, at<bf16>(c, w.eattn), d.H * 256, 64, 64, d.H * 256);
-        p.resid = at<float>(c, w.y);
-        p.out_f32 = at<float>(c, w.y); p.out_bf16 = at<bf16>(c, w.y_b);
-        p.ldo = d.X; p.ldo2 = d.X; p.n_valid = d.X;
-        RUN_GEMM(r, TILE_M64_K8, PRO_NONE, EPI_RESID, p, 1);
-      }
+      // C6: O-projection + residual (k split over blocks, fixed-order reduction)
+      gemm_splitk_resid(r, L.o, at<bf16>(c, w.eattn), d.H * 256, 64, d.H * 256, ceil_div(L.o.k_pad, 1024), 1024, nullptr,
+                        at<float>(c, w.y), at<bf16>(c, w.y_b), d.X, TILE_SKINNY, 64);
       {  // C7: RMS -> gate||up, fused gate
         GemmParams p = gp_base(c, L.gu, at<bf16>(c, w.y_b), d.X, 64, 64, d.X);
         p.out_bf16 = at<bf16>(c, w.emid);
         p.ldo = d.Fx;
-        RUN_GEMM(r, TILE_M64_K4, PRO_RMS, EPI_GEGLU, p, 1);
+        RUN_GEMM(r, TILE_SKINNY, PRO_RMS, EPI_GEGLU, p, 1);
       }
-      {  // C8: down + residual
-        GemmParams p = gp_base(c, L.down, at<bf16>(c, w.emid), d.Fx, 64, 64, d.Fx);
-        p.resid = at<float>(c, w.y);
-        p.out_f32 = at<float>(c, w.y); p.out_bf16 = at<bf16>(c, w.y_b);
-        p.ldo = d.X; p.ldo2 = d.X; p.n_valid = d.X;
-        RUN_GEMM(r, TILE_M64_K8, PRO_NONE, EPI_RESID, p, 1);
-      }
+      // C8: down + residual
+      gemm_splitk_resid(r, L.down, at<bf16>(c, w.emid), d.Fx, 64, d.Fx, ceil_div(L.down.k_pad, 1024), 1024, nullptr,
+                        at<float>(c, w.y), at<bf16>(c, w.y_b), d.X, TILE_SKINNY, 64);
       if (tap_this) {
         // step 0 taps first, last-step taps after them
         const size_t slot = (k == 0 ? 0 : (size_t)d.Le) + l;
@@ -579,7 +572,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
       p.bias = at<float>(c, w.outp.bias);
       p.out_f32 = xa;
       p.ldo = d.A; p.n_valid = d.A; p.dt = dt;
-      RUN_GEMM(r, TILE_M64_K8, PRO_RMS, EPI_EULER, p, 1);
+      RUN_GEMM(r, TILE_SKINNY, PRO_RMS, EPI_EULER, p, 1);
     }
     if (taps && taps->base && !r.count_only && r.ok()) {
       const size_t xoff = tap_step_base + (size_t)2 * d.Le * 64 * d.X + (size_t)k * chunk * d.A;

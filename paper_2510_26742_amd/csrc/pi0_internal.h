@@ -106,7 +106,8 @@ enum GemmTile {
   TILE_M64_K4 = 1,     // MB=2, WN=1, WK=4 : 64 tokens x 32 features, 4 waves split K
   TILE_M64_K8 = 2,     // MB=2, WN=1, WK=8
   TILE_M64_N4 = 3,     // MB=2, WN=4, WK=1
-  TILE_M256_K4 = 4     // MB=8, WN=1, WK=4
+  TILE_M256_K4 = 4,    // MB=8, WN=1, WK=4
+  TILE_SKINNY = 5      // <= 64 tokens, one 32-feature tile per block, 8 waves split k <= 1024, loads issued at once
 };
 
 hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmParams& p, int z_splits);
