@@ -18,6 +18,15 @@ __device__ __forceinline__ float gelu_tanh_f(float x) {
   return 0.5f * x * (1.0f + t);
 }
 
+// Sum over groups of 8 adjacent lanes with DPP (no LDS traffic): xor 1, xor 2 inside quads, then
+// the mirror inside each half row pairs quad 0 with quad 1.  Every lane of the group gets the sum.
+__device__ __forceinline__ float sum8_dpp(float v) {
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xf, 0xf, true));
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xf, 0xf, true));
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xf, 0xf, true));
+  return v;
+}
+
 __device__ __forceinline__ bf16x8 zero8() {
   bf16x8 z;
 #pragma unroll
@@ -155,16 +164,21 @@ __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16&
   }
 }
 
-template <int MB, int WN, int WK, int PRO, int EPI>
-__global__ __launch_bounds__(64 * WN * WK) void gemm_kernel(GemmParams p) {
-  constexpr int NT = 64 * WN * WK;        // threads
-  constexpr int CHUNK_K = 64 * WK;        // k extent of one block chunk
-  constexpr int LDX = CHUNK_K + LDS_PAD;  // LDS row stride (elements)
+// Tall GEMM (256 .. 816 tokens): the vision tower and the prefix transformer.
+// Block = WN waves, each owning one 32-feature tile, all sharing one MB*32-token activation tile
+// that is staged through LDS in chunks of 64 k.  A chunk ("stage") is the block's activation
+// slice plus each wave's 4 weight fragments.  D stages are kept in flight in registers and every
+// stage is issued the same distance ahead of its use: vector-memory loads complete in issue
+// order, so a weight prefetch issued far ahead does not help if the activation load behind which
+// it queues is only one chunk ahead.  With a memory round trip of 2-3 us and 0.4 us of MFMA work
+// per chunk this distance is what sets the rate.
+template <int MB, int WN, int D, int PRO, int EPI>
+__global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_kernel(GemmParams p) {
+  constexpr int NT = 64 * WN;             // threads
+  constexpr int LDX = 64 + LDS_PAD;       // LDS row stride (elements)
   constexpr int ROWS = MB * 32;
-  constexpr int PPR = WK * 8;             // 16-byte pieces per row per chunk
-  constexpr int RPP = NT / PPR;           // rows staged per pass
+  constexpr int RPP = NT / 8;             // rows staged per pass (8 sixteen-byte pieces per row)
   constexpr int NP = ROWS / RPP;          // passes
-  constexpr int RING = 8;                 // weight fragments in flight per wave (2 sub-chunks)
   static_assert(ROWS % RPP == 0, "staging must tile the rows");
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -173,9 +187,7 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_kernel(GemmParams p) {
 
   const int t = threadIdx.x;
   const int lane = t & 63;
-  const int wave = t >> 6;
-  const int wn = wave % WN;
-  const int wk = wave / WN;
+  const int wn = t >> 6;
 
   // XCD-aware tile order: consecutive block ids go to different XCDs (separate L2s), so the
   // m-tiles that share one weight panel are given ids with equal (id % 8).
@@ -192,52 +204,50 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_kernel(GemmParams p) {
   const int k_pad = p.W.k_pad;
   const int kbeg = blockIdx.y * p.k_per_split;
   const int kend = min(kbeg + p.k_per_split, k_pad);
-  const int NC = (kend - kbeg + CHUNK_K - 1) / CHUNK_K;
+  const int NC = (kend - kbeg + 63) >> 6;
   const int KC16 = k_pad >> 4;
 
-  // ---- staging helpers -------------------------------------------------------------------
-  const int st_row = t / PPR;
-  const int st_kp = t % PPR;
-  bf16x8 xr[NP];
+  const int st_row = t >> 3;
+  const int st_kp = t & 7;
+  bf16x8 xr[D][NP];
+  bf16x8 wr[D][4];
   float s1[NP], s2[NP];
 #pragma unroll
   for (int i = 0; i < NP; i++) { s1[i] = 0.f; s2[i] = 0.f; }
-
-  auto load_x = [&](int c) {
-    const int gk = kbeg + c * CHUNK_K + st_kp * 8;
-#pragma unroll
-    for (int i = 0; i < NP; i++) {
-      const int row = m0 + st_row + i * RPP;
-      if (row < p.M && gk < kend) {
-        xr[i] = *reinterpret_cast<const bf16x8*>(p.X + (size_t)row * p.ldx + gk);
-      } else {
-        xr[i] = zero8();
-      }
-    }
-  };
-  auto store_x = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < NP; i++) {
-      const int row = st_row + i * RPP;
-      *reinterpret_cast<bf16x8*>(xs + ((size_t)buf * ROWS + row) * LDX + st_kp * 8) = xr[i];
-      if (PRO != PRO_NONE) {
-#pragma unroll
-        for (int j = 0; j < 8; j++) {
-          float v = (float)xr[i][j];
-          s1[i] += v;
-          s2[i] += v * v;
-        }
-      }
-    }
-  };
-
-  // ---- weight stream -----------------------------------------------------------------------
   const bf16* wbase = p.W.w + ((size_t)(wave_active ? nt : 0) * KC16) * 512 + lane * 8;
-  auto load_w = [&](int f) -> bf16x8 {   // f = running fragment number of this wave
-    int kc16 = (kbeg >> 4) + (f >> 2) * (CHUNK_K >> 4) + wk * 4 + (f & 3);
-    kc16 = min(kc16, KC16 - 1);
-    return *reinterpret_cast<const bf16x8*>(wbase + (size_t)kc16 * 512);
-  };
+
+  // All loads are unconditional (addresses clamped into the valid range) so that the loop body is
+  // straight-line code: the compiler then keeps exact per-register wait counts and really leaves
+  // D stages in flight.  Rows beyond M re-read row M-1 (their outputs are never stored), chunks
+  // beyond the last re-read the last chunk (never computed).
+  const bf16* xrow[NP];
+#pragma unroll
+  for (int i = 0; i < NP; i++) xrow[i] = p.X + (size_t)min(m0 + st_row + i * RPP, p.M - 1) * p.ldx + kbeg + st_kp * 8;
+#define ISSUE_STAGE(c, u)                                                                             \
+  {                                                                                                   \
+    const int cc_ = min((c), NC - 1);                                                                 \
+    _Pragma("unroll") for (int i = 0; i < NP; i++)                                                    \
+      xr[u][i] = *reinterpret_cast<const bf16x8*>(xrow[i] + cc_ * 64);                                \
+    _Pragma("unroll") for (int s_ = 0; s_ < 4; s_++)                                                  \
+      wr[u][s_] = *reinterpret_cast<const bf16x8*>(wbase + (size_t)((kbeg >> 4) + cc_ * 4 + s_) * 512); \
+  }
+#define STORE_STAGE(u, buf, live)                                                                     \
+  {                                                                                                   \
+    _Pragma("unroll") for (int i = 0; i < NP; i++) {                                                  \
+      const int row_ = st_row + i * RPP;                                                              \
+      *reinterpret_cast<bf16x8*>(xs + ((size_t)(buf) * ROWS + row_) * LDX + st_kp * 8) = xr[u][i];    \
+      if (PRO != PRO_NONE) {                                                                          \
+        float a_ = 0.f, b_ = 0.f;                                                                     \
+        _Pragma("unroll") for (int j = 0; j < 8; j++) {                                               \
+          const float v_ = (float)xr[u][i][j];                                                        \
+          a_ += v_;                                                                                   \
+          b_ += v_ * v_;                                                                              \
+        }                                                                                             \
+        s1[i] += (live) ? a_ : 0.f;                                                                   \
+        s2[i] += (live) ? b_ : 0.f;                                                                   \
+      }                                                                                               \
+    }                                                                                                 \
+  }
 
   f32x16 acc[MB];
 #pragma unroll
@@ -245,85 +255,62 @@ __global__ __launch_bounds__(64 * WN * WK) void gemm_kernel(GemmParams p) {
 #pragma unroll
     for (int r = 0; r < 16; r++) acc[mb][r] = 0.f;
 
-  bf16x8 wring[RING];
 #pragma unroll
-  for (int i = 0; i < RING; i++) wring[i] = load_w(i);
-  load_x(0);
-  store_x(0);
+  for (int u = 0; u < D; u++) ISSUE_STAGE(u, u)
+  STORE_STAGE(0, 0, true)
   __syncthreads();
 
   const int lq = lane & 31;
   const int lh = lane >> 5;
   int cur = 0;
-  for (int c0 = 0; c0 < NC; c0 += RING / 4) {
+  for (int c0 = 0; c0 < NC; c0 += D) {
 #pragma unroll
-    for (int u = 0; u < RING / 4; u++) {
+    for (int u = 0; u < D; u++) {
       const int c = c0 + u;
-      if (c < NC) {
-        const bool more = (c + 1) < NC;
-        if (more) load_x(c + 1);
-        const bool sub_in = (kbeg + c * CHUNK_K + wk * 64) < kend;
+      if (wave_active && c < NC) {
+        // B fragments of step s+1 are fetched from LDS while the MFMAs of step s run
+        const bf16* xb = xs + ((size_t)cur * ROWS + lq) * LDX + lh * 8;
+        bf16x8 bq[2][MB];
+#pragma unroll
+        for (int mb = 0; mb < MB; mb++) bq[0][mb] = *reinterpret_cast<const bf16x8*>(xb + (size_t)mb * 32 * LDX);
 #pragma unroll
         for (int s = 0; s < 4; s++) {
-          const bf16x8 a = wring[u * 4 + s];
-          wring[u * 4 + s] = load_w(c * 4 + s + RING);
-          if (wave_active && sub_in) {
+          if (s < 3) {
 #pragma unroll
-            for (int mb = 0; mb < MB; mb++) {
-              const bf16x8 b = *reinterpret_cast<const bf16x8*>(
-                  xs + ((size_t)cur * ROWS + mb * 32 + lq) * LDX + wk * 64 + s * 16 + lh * 8);
-              acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[mb], 0, 0, 0);
-            }
+            for (int mb = 0; mb < MB; mb++)
+              bq[(s + 1) & 1][mb] = *reinterpret_cast<const bf16x8*>(xb + (size_t)mb * 32 * LDX + (s + 1) * 16);
           }
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int mb = 0; mb < MB; mb++)
+            acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[u][s], bq[s & 1][mb], acc[mb], 0, 0, 0);
+          // pin the order [reads of step s+1][MFMAs of step s]: with one wave per SIMD nobody else
+          // hides LDS latency, so no MFMA may wait for a read issued just before it
+          __builtin_amdgcn_sched_barrier(0);
         }
-        if (more) store_x(cur ^ 1);
-        __syncthreads();
-        cur ^= 1;
       }
+      STORE_STAGE((u + 1) % D, cur ^ 1, c + 1 < NC)
+      ISSUE_STAGE(c + D, u)
+      __syncthreads();
+      cur ^= 1;
     }
   }
+#undef ISSUE_STAGE
+#undef STORE_STAGE
 
   // ---- row statistics ----------------------------------------------------------------------
   if (PRO != PRO_NONE) {
 #pragma unroll
     for (int i = 0; i < NP; i++) {
-      float a = s1[i], b = s2[i];
-#pragma unroll
-      for (int off = 1; off < PPR; off <<= 1) {
-        a += __shfl_xor(a, off, 64);
-        b += __shfl_xor(b, off, 64);
-      }
+      const float a = sum8_dpp(s1[i]), b = sum8_dpp(s2[i]);
       if (st_kp == 0) {
         stat[st_row + i * RPP] = a;
         stat[ROWS + st_row + i * RPP] = b;
       }
     }
-  }
-
-  // ---- reduction across the waves that split K -------------------------------------------
-  if (WK > 1) {
-    float* red = reinterpret_cast<float*>(smem_raw);   // aliases the X buffers (all reads done)
-    if (wk > 0) {
-#pragma unroll
-      for (int mb = 0; mb < MB; mb++)
-#pragma unroll
-        for (int r = 0; r < 16; r++)
-          red[((((size_t)(wk - 1) * WN + wn) * MB + mb) * 16 + r) * 64 + lane] = acc[mb][r];
-    }
-    __syncthreads();
-    if (wk == 0) {
-#pragma unroll
-      for (int w = 1; w < WK; w++)
-#pragma unroll
-        for (int mb = 0; mb < MB; mb++)
-#pragma unroll
-          for (int r = 0; r < 16; r++)
-            acc[mb][r] += red[((((size_t)(w - 1) * WN + wn) * MB + mb) * 16 + r) * 64 + lane];
-    }
-  } else {
     __syncthreads();
   }
-  if (wk != 0 || !wave_active) return;
+  if (!wave_active) return;
 
   // ---- epilogue --------------------------------------------------------------------------------
 #pragma unroll
@@ -371,43 +358,38 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
     if (st < n16) wf[i] = *reinterpret_cast<const bf16x8*>(wbase + (size_t)st * 512);
     else wf[i] = zero8();
   }
-  // activations: wave w stages rows w, w+8, ..., each lane pieces lane and lane+64 of the row
+  // activations: thread t stages row t/8, pieces (t%8) + 8j: 8 adjacent lanes cover 128 contiguous
+  // bytes of a row per load, and a row's statistics live in 8 adjacent lanes.
+  const int st_row = t >> 3;
+  const int st_kp = t & 7;
   bf16x8 xr[16];
+  const bf16* xrow = p.X + (size_t)min(st_row, p.M - 1) * p.ldx + kbeg + st_kp * 8;
 #pragma unroll
-  for (int i = 0; i < 8; i++) {
-    const int row = w + 8 * i;
-#pragma unroll
-    for (int j = 0; j < 2; j++) {
-      const int gk = kbeg + (lane + 64 * j) * 8;
-      if (row < p.M && gk < kend) xr[2 * i + j] = *reinterpret_cast<const bf16x8*>(p.X + (size_t)row * p.ldx + gk);
-      else xr[2 * i + j] = zero8();
-    }
+  for (int j = 0; j < 16; j++) {
+    const int gk = kbeg + (st_kp + 8 * j) * 8;
+    if (gk < kend) xr[j] = *reinterpret_cast<const bf16x8*>(xrow + j * 64);
+    else xr[j] = zero8();
   }
-#pragma unroll
-  for (int i = 0; i < 8; i++) {
-    const int row = w + 8 * i;
+  {
     float a = 0.f, b = 0.f;
 #pragma unroll
-    for (int j = 0; j < 2; j++) {
-      *reinterpret_cast<bf16x8*>(xs + (size_t)row * SK_LDX + (lane + 64 * j) * 8) = xr[2 * i + j];
+    for (int j = 0; j < 16; j++) {
+      *reinterpret_cast<bf16x8*>(xs + (size_t)st_row * SK_LDX + (st_kp + 8 * j) * 8) = xr[j];
       if (PRO != PRO_NONE) {
 #pragma unroll
         for (int e = 0; e < 8; e++) {
-          const float v = (float)xr[2 * i + j][e];
+          const float v = (float)xr[j][e];
           a += v;
           b += v * v;
         }
       }
     }
     if (PRO != PRO_NONE) {
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        a += __shfl_xor(a, off, 64);
-        b += __shfl_xor(b, off, 64);
-      }
-      if (lane == 0) {
-        stat[row] = a;
-        stat[64 + row] = b;
+      a = sum8_dpp(a);
+      b = sum8_dpp(b);
+      if (st_kp == 0) {
+        stat[st_row] = a;
+        stat[64 + st_row] = b;
       }
     }
   }
@@ -452,51 +434,48 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
 static constexpr int skinny_smem_bytes() { return 64 * SK_LDX * 2 + 2 * 64 * 4; }
 
 // ------------------------------------------------------------------------------------------------
-template <int MB, int WN, int WK>
+template <int MB>
 static constexpr int smem_bytes_for() {
-  return 2 * (MB * 32) * (64 * WK + LDS_PAD) * 2 + 2 * (MB * 32) * 4;
+  return 2 * (MB * 32) * (64 + LDS_PAD) * 2 + 2 * (MB * 32) * 4;
 }
 
-int gemm_smem_bytes(int tile) {
+int gemm_rows_per_tile(int tile) {
   switch (tile) {
-    case TILE_M256_N128: return smem_bytes_for<8, 4, 1>();
-    case TILE_M64_K4: return smem_bytes_for<2, 1, 4>();
-    case TILE_M64_K8: return smem_bytes_for<2, 1, 8>();
-    case TILE_M64_N4: return smem_bytes_for<2, 4, 1>();
+    case TILE_BIG: return 256;
+    case TILE_MID: return 64;
+    case TILE_SKINNY: return 64;
     default: return -1;
   }
 }
 
-template <int MB, int WN, int WK, int PRO, int EPI>
+template <int MB, int WN, int D, int PRO, int EPI>
 static hipError_t launch_one(hipStream_t s, const GemmParams& p, int z) {
   const int nblocks_n = (p.n_tiles + WN - 1) / WN;
   dim3 grid(8 * ((nblocks_n + 7) / 8) * p.m_tiles, z, 1);
-  dim3 block(64 * WN * WK, 1, 1);
-  constexpr int smem = smem_bytes_for<MB, WN, WK>();
-  gemm_kernel<MB, WN, WK, PRO, EPI><<<grid, block, smem, s>>>(p);
+  dim3 block(64 * WN, 1, 1);
+  constexpr int smem = smem_bytes_for<MB>();
+  gemm_kernel<MB, WN, D, PRO, EPI><<<grid, block, smem, s>>>(p);
   return hipGetLastError();
 }
 
-template <int MB, int WN, int WK, int PRO, int EPI>
+template <int MB, int WN, int D, int PRO, int EPI>
 static hipError_t set_attr() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<MB, WN, WK, PRO, EPI>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes_for<MB, WN, WK>());
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<MB, WN, D, PRO, EPI>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes_for<MB>());
 }
 
-// The instantiations that exist.  X(tile id, MB, WN, WK, PRO, EPI)
-#define GEMM_VARIANTS(X)                                   \
-  X(TILE_M256_N128, 8, 4, 1, PRO_NONE, EPI_RESID)          \
-  X(TILE_M256_N128, 8, 4, 1, PRO_NONE, EPI_PARTIAL)        \
-  X(TILE_M256_N128, 8, 4, 1, PRO_LN, EPI_QKV)              \
-  X(TILE_M256_N128, 8, 4, 1, PRO_LN, EPI_BF16)             \
-  X(TILE_M256_N128, 8, 4, 1, PRO_LN, EPI_RESID)            \
-  X(TILE_M256_N128, 8, 4, 1, PRO_RMS, EPI_QKV)             \
-  X(TILE_M256_N128, 8, 4, 1, PRO_RMS, EPI_GEGLU)           \
-  X(TILE_M64_K4, 2, 1, 4, PRO_NONE, EPI_RESID)             \
-  X(TILE_M64_K4, 2, 1, 4, PRO_RMS, EPI_QKV)                \
-  X(TILE_M64_K4, 2, 1, 4, PRO_RMS, EPI_GEGLU)              \
-  X(TILE_M64_K8, 2, 1, 8, PRO_NONE, EPI_RESID)             \
-  X(TILE_M64_K8, 2, 1, 8, PRO_RMS, EPI_EULER)
+// The instantiations that exist.  X(tile id, MB, WN, D, PRO, EPI)
+#define TALL_EPIS(X, T, MB, WN, D)    \
+  X(T, MB, WN, D, PRO_NONE, EPI_RESID)   \
+  X(T, MB, WN, D, PRO_NONE, EPI_PARTIAL) \
+  X(T, MB, WN, D, PRO_LN, EPI_QKV)       \
+  X(T, MB, WN, D, PRO_LN, EPI_BF16)      \
+  X(T, MB, WN, D, PRO_LN, EPI_RESID)     \
+  X(T, MB, WN, D, PRO_RMS, EPI_QKV)      \
+  X(T, MB, WN, D, PRO_RMS, EPI_GEGLU)
+#define GEMM_VARIANTS(X)           \
+  TALL_EPIS(X, TILE_BIG, 8, 4, 3)  \
+  TALL_EPIS(X, TILE_MID, 2, 4, 6)
 
 #define SKINNY_VARIANTS(X)      \
   X(PRO_NONE, EPI_RESID)        \
@@ -514,9 +493,9 @@ hipError_t gemm_init_attributes() {
   }
   SKINNY_VARIANTS(X)
 #undef X
-#define X(T, MB, WN, WK, PRO, EPI)                                    \
+#define X(T, MB, WN, D, PRO, EPI)                                     \
   {                                                                   \
-    hipError_t e = set_attr<MB, WN, WK, PRO, EPI>();                  \
+    hipError_t e = set_attr<MB, WN, D, PRO, EPI>();                   \
     if (e != hipSuccess) return e;                                    \
   }
   GEMM_VARIANTS(X)
@@ -544,10 +523,10 @@ hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmPara
 #undef X
     return hipErrorInvalidValue;
   }
-#define X(T, MB, WN, WK, PRO, EPI)                                             \
+#define X(T, MB, WN, D, PRO, EPI)                                              \
   if (tile == T && pro == PRO && epi == EPI) {                                  \
     if (p.m_tiles * MB * 32 < p.M) return hipErrorInvalidValue;                 \
-    return launch_one<MB, WN, WK, PRO, EPI>(s, p, z_splits);                    \
+    return launch_one<MB, WN, D, PRO, EPI>(s, p, z_splits);                     \
   }
   GEMM_VARIANTS(X)
 #undef X

@@ -3,6 +3,7 @@
 // (Section 3.1: record the kernel stream once, replay it with constant kernels and pointers).
 #include <math.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <map>
@@ -161,9 +162,7 @@ struct WsCursor {
   }
 };
 
-const int Z_VIS_O = 6, Z_LLM_O = 8, Z_LLM_DOWN = 16;
-
-int z_vis_down(const Dims& d) { return ceil_div(d.Fv_kp / 64, 4); }   // 4 chunks of 64 per split
+const int Z_MAX = 32;   // upper bound on split-K slices (sizes the partial-sum buffer)
 
 void ws_layout(const pi0_config& c, const Dims& d, WsLayout& w) {
   WsCursor cur;
@@ -231,8 +230,7 @@ void ws_layout(const pi0_config& c, const Dims& d, WsLayout& w) {
   w.vv = cur.take((size_t)d.Hv * (d.maxI / 32) * 3 * 1024 * 2);
   w.vattn = cur.take((size_t)d.maxI * d.Dv * 2);
   w.vmid = cur.take((size_t)d.maxI * d.Fv_kp * 2);
-  w.zmax = Z_LLM_DOWN;
-  if (z_vis_down(d) > w.zmax) w.zmax = z_vis_down(d);
+  w.zmax = Z_MAX;
   {
     size_t a = (size_t)w.zmax * d.maxI * round_up(d.Dv, 32) * 4;
     size_t b = (size_t)w.zmax * d.maxP * d.E * 4;
@@ -271,8 +269,20 @@ enum { KIND_PREFILL = 0, KIND_DENOISE = 1, KIND_INFER = 2 };
 
 }  // namespace
 
+// Per-shape tile choices (Section 4.1 of the paper tunes tiles per GEMM shape; these are the
+// gfx950 counterparts).  Overridable for tuning runs through the environment variable PI0_TUNE,
+// e.g. PI0_TUNE="vis=1,lqkv=1,lgu=0,part=0,zvo=6,zlo=8,zld=16".
+struct Tune {
+  int vis = TILE_MID;     // vision QKV / up / patch / projector
+  int lqkv = TILE_MID;    // prefix QKV
+  int lgu = TILE_BIG;     // prefix gate||up
+  int part = TILE_BIG;    // split-K partial GEMMs (O, down of vision and prefix)
+  int zvo = 6, zlo = 8, zld = 16, zvd = 17;
+};
+
 struct pi0_ctx {
   pi0_config cfg;
+  Tune tune;
   Dims d;
   BlobLayout bl;
   WsLayout wl;
@@ -313,7 +323,8 @@ PackedW packed(pi0_ctx* c, const PW& p) {
   return w;
 }
 
-GemmParams gp_base(pi0_ctx* c, const PW& pw, const bf16* X, int ldx, int M, int rows_per_tile, int k_true) {
+GemmParams gp_base(pi0_ctx* c, const PW& pw, const bf16* X, int ldx, int M, int tile, int k_true) {
+  const int rows_per_tile = gemm_rows_per_tile(tile);
   GemmParams p;
   memset(&p, 0, sizeof(p));
   p.X = X;
@@ -335,10 +346,11 @@ GemmParams gp_base(pi0_ctx* c, const PW& pw, const bf16* X, int ldx, int M, int 
 
 // split-K GEMM into the partial buffer followed by the fixed-order reduction with bias/residual
 void gemm_splitk_resid(Run& r, const PW& pw, const bf16* X, int ldx, int M, int k_true, int z, int k_per_split,
-                       const float* bias, float* resid_io, bf16* shadow, int n_true, int tile = TILE_M256_N128,
-                       int rows_per_tile = 256) {
+                       const float* bias, float* resid_io, bf16* shadow, int n_true, int tile) {
   pi0_ctx* c = r.c;
-  GemmParams p = gp_base(c, pw, X, ldx, M, rows_per_tile, k_true);
+  if (z > Z_MAX) z = Z_MAX;
+  if ((long)k_per_split * z < pw.k_pad) k_per_split = round_up(ceil_div(pw.k_pad, z), 64);
+  GemmParams p = gp_base(c, pw, X, ldx, M, tile, k_true);
   p.k_per_split = k_per_split;
   p.out_f32 = at<float>(c, c->wl.part);
   p.ldo = pw.n_pad;
@@ -368,24 +380,25 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
   pi0_ctx* c = r.c;
   const Dims& d = c->d;
   const WsLayout& w = c->wl;
+  const Tune& T = c->tune;
   const int I = n_views * d.T, P = I + n_prompt;
   // A0: patches -> tokens (+bias, +position embedding)
   RUN(r, launch_patchify(r.s, at<float>(c, w.st_images), n_views, c->cfg.img_size, c->cfg.patch, at<bf16>(c, w.xpatch), d.PDp));
   {
-    GemmParams p = gp_base(c, w.patch, at<bf16>(c, w.xpatch), d.PDp, I, 256, d.PD);
+    GemmParams p = gp_base(c, w.patch, at<bf16>(c, w.xpatch), d.PDp, I, T.vis, d.PD);
     p.bias = at<float>(c, w.patch.bias);
     p.resid = at<float>(c, w.pos);
     p.resid_mod = d.T;
     p.out_f32 = at<float>(c, w.vh);
     p.out_bf16 = at<bf16>(c, w.vh_b);
     p.ldo = d.Dv; p.ldo2 = d.Dv; p.n_valid = d.Dv;
-    RUN_GEMM(r, TILE_M256_N128, PRO_NONE, EPI_RESID, p, 1);
+    RUN_GEMM(r, T.vis, PRO_NONE, EPI_RESID, p, 1);
   }
   const int vchunks = I / 32;
   for (int l = 0; l < d.Lv; l++) {
     const WsVis& L = w.vis[l];
     {  // A1: LN -> QKV (+bias), keys/values straight into attention fragment order
-      GemmParams p = gp_base(c, L.qkv, at<bf16>(c, w.vh_b), d.Dv, I, 256, d.Dv);
+      GemmParams p = gp_base(c, L.qkv, at<bf16>(c, w.vh_b), d.Dv, I, T.vis, d.Dv);
       p.bias = at<float>(c, L.qkv.bias);
       p.colsum = at<float>(c, L.qkv.colsum);
       p.out_bf16 = at<bf16>(c, w.vq);
@@ -395,7 +408,7 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
       p.rope = nullptr;
       p.q_cols = d.Dv; p.k_cols = d.Dv;
       p.head_dim = d.hdv; p.dqk_pad = 80; p.nvb = 3; p.kv_heads = d.Hv; p.kv_chunks = vchunks;
-      RUN_GEMM(r, TILE_M256_N128, PRO_LN, EPI_QKV, p, 1);
+      RUN_GEMM(r, T.vis, PRO_LN, EPI_QKV, p, 1);
     }
     {  // A2: attention inside each view
       AttnParams a;
@@ -411,29 +424,29 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
       RUN(r, launch_attention(r.s, a));
     }
     // A3: O-projection + bias + residual
-    gemm_splitk_resid(r, L.o, at<bf16>(c, w.vattn), d.Dv, I, d.Dv, Z_VIS_O, round_up(ceil_div(L.o.k_pad, Z_VIS_O), 64),
-                      at<float>(c, L.o.bias), at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv);
+    gemm_splitk_resid(r, L.o, at<bf16>(c, w.vattn), d.Dv, I, d.Dv, T.zvo, round_up(ceil_div(L.o.k_pad, T.zvo), 64),
+                      at<float>(c, L.o.bias), at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv, T.part);
     {  // A4: LN -> up (+bias, GELU)
-      GemmParams p = gp_base(c, L.up, at<bf16>(c, w.vh_b), d.Dv, I, 256, d.Dv);
+      GemmParams p = gp_base(c, L.up, at<bf16>(c, w.vh_b), d.Dv, I, T.vis, d.Dv);
       p.bias = at<float>(c, L.up.bias);
       p.colsum = at<float>(c, L.up.colsum);
       p.out_bf16 = at<bf16>(c, w.vmid);
       p.ldo = d.Fv_kp; p.n_valid = L.up.n_pad; p.act = ACT_GELU;
-      RUN_GEMM(r, TILE_M256_N128, PRO_LN, EPI_BF16, p, 1);
+      RUN_GEMM(r, T.vis, PRO_LN, EPI_BF16, p, 1);
     }
     // A5: down (+bias, residual)
-    gemm_splitk_resid(r, L.down, at<bf16>(c, w.vmid), d.Fv_kp, I, d.Fv, z_vis_down(d), 256, at<float>(c, L.down.bias),
-                      at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv);
+    gemm_splitk_resid(r, L.down, at<bf16>(c, w.vmid), d.Fv_kp, I, d.Fv, T.zvd, round_up(ceil_div(L.down.k_pad, T.zvd), 64),
+                      at<float>(c, L.down.bias), at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv, T.part);
     if (taps) taps->put(r, at<float>(c, w.vh), (size_t)I * d.Dv);
   }
   {  // A6: final LN -> projector (+bias) = prefix image embeddings
-    GemmParams p = gp_base(c, w.proj, at<bf16>(c, w.vh_b), d.Dv, I, 256, d.Dv);
+    GemmParams p = gp_base(c, w.proj, at<bf16>(c, w.vh_b), d.Dv, I, T.vis, d.Dv);
     p.bias = at<float>(c, w.proj.bias);
     p.colsum = at<float>(c, w.proj.colsum);
     p.out_f32 = at<float>(c, w.lx);
     p.out_bf16 = at<bf16>(c, w.lx_b);
     p.ldo = d.E; p.ldo2 = d.E; p.n_valid = d.E;
-    RUN_GEMM(r, TILE_M256_N128, PRO_LN, EPI_RESID, p, 1);
+    RUN_GEMM(r, T.vis, PRO_LN, EPI_RESID, p, 1);
   }
   if (taps) taps->put(r, at<float>(c, w.lx), (size_t)I * d.E);
   if (n_prompt > 0) {  // B0: prompt embeddings after the image tokens
@@ -447,7 +460,7 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
     bf16* kc = reinterpret_cast<bf16*>(c->ws + w.kcache + (size_t)l * w.kcache_layer);
     bf16* vc = reinterpret_cast<bf16*>(c->ws + w.vcache + (size_t)l * w.vcache_layer);
     {  // B1: RMS -> QKV, RoPE, keys/values into the cache (last layer: keys/values only)
-      GemmParams p = gp_base(c, L.qkv, at<bf16>(c, w.lx_b), d.E, P, 256, d.E);
+      GemmParams p = gp_base(c, L.qkv, at<bf16>(c, w.lx_b), d.E, P, T.lqkv, d.E);
       p.out_bf16 = at<bf16>(c, w.lq);
       p.ldo = d.H * 256;
       p.kfrag = kc; p.vfrag = vc;
@@ -455,7 +468,7 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
       p.pos0 = 0;
       p.q_cols = last ? 0 : d.H * 256; p.k_cols = 256;
       p.head_dim = 256; p.dqk_pad = 256; p.nvb = 8; p.kv_heads = 1; p.kv_chunks = d.maxPc;
-      RUN_GEMM(r, TILE_M256_N128, PRO_RMS, EPI_QKV, p, 1);
+      RUN_GEMM(r, T.lqkv, PRO_RMS, EPI_QKV, p, 1);
     }
     if (last) break;
     {  // B2: attention, whole prefix visible
@@ -469,18 +482,18 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
       RUN(r, launch_attention(r.s, a));
     }
     // B3: O-projection + residual
-    gemm_splitk_resid(r, L.o, at<bf16>(c, w.lattn), d.H * 256, P, d.H * 256, Z_LLM_O,
-                      round_up(ceil_div(L.o.k_pad, Z_LLM_O), 64), nullptr, at<float>(c, w.lx), at<bf16>(c, w.lx_b), d.E);
+    gemm_splitk_resid(r, L.o, at<bf16>(c, w.lattn), d.H * 256, P, d.H * 256, T.zlo,
+                      round_up(ceil_div(L.o.k_pad, T.zlo), 64), nullptr, at<float>(c, w.lx), at<bf16>(c, w.lx_b), d.E, T.part);
     {  // B4: RMS -> gate||up with fused GELU gate
-      GemmParams p = gp_base(c, L.gu, at<bf16>(c, w.lx_b), d.E, P, 256, d.E);
+      GemmParams p = gp_base(c, L.gu, at<bf16>(c, w.lx_b), d.E, P, T.lgu, d.E);
       p.out_bf16 = at<bf16>(c, w.lmid);
       p.ldo = d.F;
-      RUN_GEMM(r, TILE_M256_N128, PRO_RMS, EPI_GEGLU, p, 1);
+      RUN_GEMM(r, T.lgu, PRO_RMS, EPI_GEGLU, p, 1);
     }
     // B5: down + residual
-    gemm_splitk_resid(r, L.down, at<bf16>(c, w.lmid), d.F, P, d.F, Z_LLM_DOWN,
-                      round_up(ceil_div(L.down.k_pad, Z_LLM_DOWN), 64), nullptr, at<float>(c, w.lx), at<bf16>(c, w.lx_b),
-                      d.E);
+    gemm_splitk_resid(r, L.down, at<bf16>(c, w.lmid), d.F, P, d.F, T.zld,
+                      round_up(ceil_div(L.down.k_pad, T.zld), 64), nullptr, at<float>(c, w.lx), at<bf16>(c, w.lx_b),
+                      d.E, T.part);
     if (taps) taps->put(r, at<float>(c, w.lx), (size_t)P * d.E);
   }
   if (taps && taps->base) {
@@ -513,7 +526,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
     RUN(r, launch_action_embed(r.s, xa, chunk, d.A, at<float>(c, w.wfold), at<float>(c, w.bias_tab) + (size_t)k * d.X, d.X,
                                at<bf16>(c, w.z), at<float>(c, w.stok), at<float>(c, w.y), at<bf16>(c, w.y_b)));
     {  // C2: second linear of the action/time MLP -> suffix rows 1..chunk
-      GemmParams p = gp_base(c, w.tout, at<bf16>(c, w.z), d.X, chunk, 64, d.X);
+      GemmParams p = gp_base(c, w.tout, at<bf16>(c, w.z), d.X, chunk, TILE_SKINNY, d.X);
       p.bias = at<float>(c, w.tout.bias);
       p.out_f32 = at<float>(c, w.y);
       p.out_bf16 = at<bf16>(c, w.y_b);
@@ -526,7 +539,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
       bf16* kc = reinterpret_cast<bf16*>(c->ws + w.kcache + (size_t)l * w.kcache_layer);
       bf16* vc = reinterpret_cast<bf16*>(c->ws + w.vcache + (size_t)l * w.vcache_layer);
       {  // C3: RMS -> QKV, RoPE at positions P..P+63
-        GemmParams p = gp_base(c, L.qkv, at<bf16>(c, w.y_b), d.X, 64, 64, d.X);
+        GemmParams p = gp_base(c, L.qkv, at<bf16>(c, w.y_b), d.X, 64, TILE_SKINNY, d.X);
         p.out_bf16 = at<bf16>(c, w.eq);
         p.ldo = d.H * 256;
         p.kfrag = at<bf16>(c, w.ek); p.vfrag = at<bf16>(c, w.ev);
@@ -550,16 +563,16 @@ void run_denoise(Run& r, int P, Taps* taps) {
       }
       // C6: O-projection + residual (k split over blocks, fixed-order reduction)
       gemm_splitk_resid(r, L.o, at<bf16>(c, w.eattn), d.H * 256, 64, d.H * 256, ceil_div(L.o.k_pad, 1024), 1024, nullptr,
-                        at<float>(c, w.y), at<bf16>(c, w.y_b), d.X, TILE_SKINNY, 64);
+                        at<float>(c, w.y), at<bf16>(c, w.y_b), d.X, TILE_SKINNY);
       {  // C7: RMS -> gate||up, fused gate
-        GemmParams p = gp_base(c, L.gu, at<bf16>(c, w.y_b), d.X, 64, 64, d.X);
+        GemmParams p = gp_base(c, L.gu, at<bf16>(c, w.y_b), d.X, 64, TILE_SKINNY, d.X);
         p.out_bf16 = at<bf16>(c, w.emid);
         p.ldo = d.Fx;
         RUN_GEMM(r, TILE_SKINNY, PRO_RMS, EPI_GEGLU, p, 1);
       }
       // C8: down + residual
       gemm_splitk_resid(r, L.down, at<bf16>(c, w.emid), d.Fx, 64, d.Fx, ceil_div(L.down.k_pad, 1024), 1024, nullptr,
-                        at<float>(c, w.y), at<bf16>(c, w.y_b), d.X, TILE_SKINNY, 64);
+                        at<float>(c, w.y), at<bf16>(c, w.y_b), d.X, TILE_SKINNY);
       if (tap_this) {
         // step 0 taps first, last-step taps after them
         const size_t slot = (k == 0 ? 0 : (size_t)d.Le) + l;
@@ -568,7 +581,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
       }
     }
     {  // C9: final RMS -> out-projection (+bias), Euler update x <- x + dt * v
-      GemmParams p = gp_base(c, w.outp, at<bf16>(c, w.y_b), d.X, 64, 64, d.X);
+      GemmParams p = gp_base(c, w.outp, at<bf16>(c, w.y_b), d.X, 64, TILE_SKINNY, d.X);
       p.bias = at<float>(c, w.outp.bias);
       p.out_f32 = xa;
       p.ldo = d.A; p.n_valid = d.A; p.dt = dt;
@@ -689,6 +702,21 @@ int pi0_create(const pi0_config* cfg, pi0_ctx** out) {
   c->d = d;
   blob_layout(*cfg, d, c->bl);
   ws_layout(*cfg, d, c->wl);
+  c->tune.zvd = ceil_div(d.Fv_kp / 64, 4);
+  if (const char* env = getenv("PI0_TUNE")) {
+    struct { const char* key; int* dst; int lo, hi; } keys[] = {
+        {"vis", &c->tune.vis, 0, 1},   {"lqkv", &c->tune.lqkv, 0, 1}, {"lgu", &c->tune.lgu, 0, 1},
+        {"part", &c->tune.part, 0, 1}, {"zvo", &c->tune.zvo, 1, Z_MAX}, {"zlo", &c->tune.zlo, 1, Z_MAX},
+        {"zld", &c->tune.zld, 1, Z_MAX}, {"zvd", &c->tune.zvd, 1, Z_MAX}};
+    for (auto& k : keys) {
+      const char* f = strstr(env, k.key);
+      while (f != nullptr && !((f == env || f[-1] == ',') && f[strlen(k.key)] == '=')) f = strstr(f + 1, k.key);
+      if (f != nullptr) {
+        const int v = atoi(f + strlen(k.key) + 1);
+        if (v >= k.lo && v <= k.hi) *k.dst = v;
+      }
+    }
+  }
   // RoPE table (Section 3.2: precomputed): angle = pos * 10000^(-i/128), pairs (i, i+128)
   c->h_rope.resize((size_t)d.maxpos * 128 * 2);
   for (int pos = 0; pos < d.maxpos; pos++) {

@@ -102,16 +102,13 @@ struct GemmParams {
 
 // Tile configuration ids (template instantiations that exist)
 enum GemmTile {
-  TILE_M256_N128 = 0,  // MB=8, WN=4, WK=1 : 256 tokens x 128 features per block, 256 threads
-  TILE_M64_K4 = 1,     // MB=2, WN=1, WK=4 : 64 tokens x 32 features, 4 waves split K
-  TILE_M64_K8 = 2,     // MB=2, WN=1, WK=8
-  TILE_M64_N4 = 3,     // MB=2, WN=4, WK=1
-  TILE_M256_K4 = 4,    // MB=8, WN=1, WK=4
-  TILE_SKINNY = 5      // <= 64 tokens, one 32-feature tile per block, 8 waves split k <= 1024, loads issued at once
+  TILE_BIG = 0,     // 256 tokens x 128 features per block (4 waves), 4 stages in flight
+  TILE_MID = 1,     // 64 tokens x 128 features per block (4 waves), 8 stages in flight
+  TILE_SKINNY = 2   // <= 64 tokens, one 32-feature tile per block, 8 waves split k <= 1024, loads issued at once
 };
 
 hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmParams& p, int z_splits);
-int gemm_smem_bytes(int tile);
+int gemm_rows_per_tile(int tile);
 hipError_t gemm_init_attributes();
 
 // Split-K reduction: out[m][n] = sum_z part[z][m][n] (+bias[n]) (+resid[m][n]); bf16 shadow.
