@@ -28,8 +28,7 @@
 template <int DQK, int NVB>
 __global__ __launch_bounds__(512) void attention_kernel(AttnParams p) {
   constexpr int S16 = DQK / 16;
-  constexpr int PPR = DQK / 8;                 // 16-byte pieces per query row
-  constexpr int NPQ = 32 * PPR;                // pieces of the Q tile
+  constexpr int NPQ = 32 * DQK / 8;            // 16-byte pieces of the Q tile
   constexpr int QP = (NPQ + 511) / 512;        // pieces per thread
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16* qs = reinterpret_cast<bf16*>(smem_raw);                               // [S16][64][8]
@@ -65,17 +64,13 @@ __global__ __launch_bounds__(512) void attention_kernel(AttnParams p) {
   };
 
   // ---- issue every load of the first round ---------------------------------------------------
+  // Q tile: S16 fragments of 1 KiB, already in fragment order in global memory
+  const bf16* qsrc = p.q + (size_t)head * p.q_head_stride + (size_t)tile * S16 * 512;
   bf16x8 qreg[QP];
 #pragma unroll
   for (int i = 0; i < QP; i++) {
-    const int pc = t + i * 512;
-    const int r = pc / PPR, kp = pc % PPR;
-    if (pc < NPQ && tile * 32 + r < p.Tq) {
-      qreg[i] = *reinterpret_cast<const bf16x8*>(p.q + (size_t)(tile * 32 + r) * p.q_ld + head * p.q_head_stride + kp * 8);
-    } else {
-#pragma unroll
-      for (int j = 0; j < 8; j++) qreg[i][j] = (bf16)0.0f;
-    }
+    const int pc = min(t + i * 512, NPQ - 1);
+    qreg[i] = *reinterpret_cast<const bf16x8*>(qsrc + (size_t)pc * 8);
   }
   bf16x8 kf[S16];
   if (w < ntot) {
@@ -98,10 +93,7 @@ __global__ __launch_bounds__(512) void attention_kernel(AttnParams p) {
 #pragma unroll
   for (int i = 0; i < QP; i++) {
     const int pc = t + i * 512;
-    if (pc < NPQ) {
-      const int r = pc / PPR, kp = pc % PPR;
-      *reinterpret_cast<bf16x8*>(qs + ((size_t)(kp >> 1) * 64 + (kp & 1) * 32 + r) * 8) = qreg[i];
-    }
+    if (pc < NPQ) *reinterpret_cast<bf16x8*>(qs + (size_t)pc * 8) = qreg[i];
   }
   __syncthreads();
 
@@ -201,7 +193,9 @@ __global__ __launch_bounds__(512) void attention_kernel(AttnParams p) {
     if (d < p.head_dim) {
       const bf16x4 ob = {(bf16)(o[4 * i] * inv), (bf16)(o[4 * i + 1] * inv), (bf16)(o[4 * i + 2] * inv),
                          (bf16)(o[4 * i + 3] * inv)};
-      *reinterpret_cast<bf16x4*>(p.out + (size_t)row * p.out_ld + head * p.head_dim + d) = ob;
+      const int col = head * p.head_dim + d;
+      *reinterpret_cast<bf16x4*>(p.out + ((size_t)(row >> 5) * (p.out_ld >> 4) + (col >> 4)) * 512 +
+                                 (((col & 15) >> 3) * 32 + (row & 31)) * 8 + (col & 7)) = ob;
     }
   }
 }
@@ -220,7 +214,7 @@ hipError_t attention_init_attributes() {
 hipError_t launch_attention(hipStream_t s, const AttnParams& p) {
   if (p.q == nullptr || p.k0 == nullptr || p.v0 == nullptr || p.out == nullptr) return hipErrorInvalidValue;
   if (p.Tq <= 0 || p.heads <= 0 || p.chunks0 <= 0 || p.valid0 <= 0 || p.valid0 > p.chunks0 * 32) return hipErrorInvalidValue;
-  if (p.q_ld % 8 != 0 || p.q_head_stride % 8 != 0 || p.out_ld % 4 != 0 || p.head_dim % 4 != 0) return hipErrorInvalidValue;
+  if (p.q_head_stride % 512 != 0 || p.out_ld % 16 != 0 || p.head_dim % 4 != 0 || p.out_ld < p.heads * p.head_dim) return hipErrorInvalidValue;
   if (p.chunks1 != 0 && (p.k1 == nullptr || p.v1 == nullptr)) return hipErrorInvalidValue;
   if (p.chunks1 < 0 || p.chunks1 > 2) return hipErrorInvalidValue;
   if (p.suffix_mask && p.Tq > 32 * p.chunks1) return hipErrorInvalidValue;

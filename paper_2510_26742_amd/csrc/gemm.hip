@@ -34,20 +34,31 @@ __device__ __forceinline__ bf16x8 zero8() {
   return z;
 }
 
+// Activation matrices that feed a GEMM are stored in MFMA B-fragment order ("XF" layout):
+// element (row m, column k) of a matrix padded to kc16*16 columns lives at
+//   ((m/32 * kc16 + k/16) * 64 + ((k%16)/8)*32 + m%32) * 8 + k%8,
+// i.e. the 32-token x 16-k fragment (m/32, k/16) is 1 KiB of consecutive memory, lane-major.
+// Producers write it from their accumulator layout in 8-byte pieces that coalesce to 512-byte
+// runs; consumers copy fragments to LDS (or registers) with fully contiguous accesses, and LDS
+// fragment reads run at the full 128 B/clk (a padded row-major tile only reaches half of that).
+__device__ __forceinline__ size_t xf_index(int m, int k, int kc16) {
+  return ((size_t)(m >> 5) * kc16 + (k >> 4)) * 512 + (((k & 15) >> 3) * 32 + (m & 31)) * 8 + (k & 7);
+}
+
 // One 32-token x 32-feature accumulator tile -> memory.  `acc` is the MFMA accumulator of the
 // calling lane (token = lane % 32, features nt*32 + 8*(r/4) + 4*(lane/32) + r%4), `m` the global
-// row, `ml` the row inside the block's tile (index into the statistics), stat = [sum | sum sq].
+// row, (s_sum, s_sq) the row's sum and sum of squares over the true k columns.
 template <int PRO, int EPI>
-__device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16& acc, int nt, int m, int ml, int lh,
-                                              const float* stat, int ROWS, int zsplit) {
+__device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16& acc, int nt, int m, int lh,
+                                              float s_sum, float s_sq, int zsplit) {
   const float inv_k = 1.0f / (float)p.k_true;
   {
     float rs = 1.f, mu = 0.f;
     if (PRO == PRO_RMS) {
-      rs = rsqrtf(stat[ROWS + ml] * inv_k + 1e-6f);
+      rs = rsqrtf(s_sq * inv_k + 1e-6f);
     } else if (PRO == PRO_LN) {
-      mu = stat[ml] * inv_k;
-      float var = stat[ROWS + ml] * inv_k - mu * mu;
+      mu = s_sum * inv_k;
+      float var = s_sq * inv_k - mu * mu;
       rs = rsqrtf(fmaxf(var, 0.f) + 1e-6f);
     }
 #pragma unroll
@@ -86,7 +97,7 @@ __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16&
           f32x4 o = {v[0], v[1], v[2], v[3]};
           *reinterpret_cast<f32x4*>(p.out_f32 + (size_t)mo * p.ldo + n4) = o;
           bf16x4 ob = {(bf16)v[0], (bf16)v[1], (bf16)v[2], (bf16)v[3]};
-          *reinterpret_cast<bf16x4*>(p.out_bf16 + (size_t)mo * p.ldo2 + n4) = ob;
+          *reinterpret_cast<bf16x4*>(p.out_bf16 + xf_index(mo, n4, p.ldo2 >> 4)) = ob;
         }
       } else if (EPI == EPI_BF16) {
         if (n4 < p.n_valid) {
@@ -95,11 +106,11 @@ __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16&
             for (int j = 0; j < 4; j++) v[j] = gelu_tanh_f(v[j]);
           }
           bf16x4 ob = {(bf16)v[0], (bf16)v[1], (bf16)v[2], (bf16)v[3]};
-          *reinterpret_cast<bf16x4*>(p.out_bf16 + (size_t)m * p.ldo + n4) = ob;
+          *reinterpret_cast<bf16x4*>(p.out_bf16 + xf_index(m, n4, p.ldo >> 4)) = ob;
         }
       } else if (EPI == EPI_GEGLU) {
         bf16x2 ob = {(bf16)(gelu_tanh_f(v[0]) * v[1]), (bf16)(gelu_tanh_f(v[2]) * v[3])};
-        *reinterpret_cast<bf16x2*>(p.out_bf16 + (size_t)m * p.ldo + (n4 >> 1)) = ob;
+        *reinterpret_cast<bf16x2*>(p.out_bf16 + xf_index(m, n4 >> 1, p.ldo >> 4)) = ob;
       } else if (EPI == EPI_EULER) {
         if (m >= 1) {
 #pragma unroll
@@ -124,12 +135,9 @@ __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16&
             const float lo1 = v[2] * c4[2] - v[3] * c4[3], hi1 = v[3] * c4[2] + v[2] * c4[3];
             const bf16x2 lo = {(bf16)lo0, (bf16)lo1};
             const bf16x2 hi = {(bf16)hi0, (bf16)hi1};
-            if (is_q) {
-              bf16* dst = p.out_bf16 + (size_t)m * p.ldo + head * 256 + i0;
-              *reinterpret_cast<bf16x2*>(dst) = lo;
-              *reinterpret_cast<bf16x2*>(dst + 128) = hi;
-            } else {
-              bf16* dst = p.kfrag + ((size_t)kc * S16) * 512 + kk * 8;
+            {
+              bf16* dst = (is_q ? p.out_bf16 + ((size_t)head * p.q_mbs + kc) * S16 * 512 : p.kfrag + ((size_t)kc * S16) * 512) +
+                          kk * 8;
               const int d0 = i0, d1 = i0 + 128;
               *reinterpret_cast<bf16x2*>(dst + (size_t)(d0 >> 4) * 512 + ((d0 & 15) >> 3) * 256 + (d0 & 7)) = lo;
               *reinterpret_cast<bf16x2*>(dst + (size_t)(d1 >> 4) * 512 + ((d1 & 15) >> 3) * 256 + (d1 & 7)) = hi;
@@ -138,10 +146,9 @@ __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16&
             const int head = nl / p.head_dim;
             const int d = nl - head * p.head_dim;    // multiple of 4
             const bf16x4 ob = {(bf16)v[0], (bf16)v[1], (bf16)v[2], (bf16)v[3]};
-            if (is_q) {
-              *reinterpret_cast<bf16x4*>(p.out_bf16 + (size_t)m * p.ldo + head * p.dqk_pad + d) = ob;
-            } else {
-              bf16* dst = p.kfrag + ((size_t)head * p.kv_chunks + kc) * S16 * 512 + kk * 8;
+            {
+              bf16* dst = (is_q ? p.out_bf16 + ((size_t)head * p.q_mbs + kc) * S16 * 512
+                                : p.kfrag + ((size_t)head * p.kv_chunks + kc) * S16 * 512) + kk * 8;
               *reinterpret_cast<bf16x4*>(dst + (size_t)(d >> 4) * 512 + ((d & 15) >> 3) * 256 + (d & 7)) = ob;
             }
           }
@@ -166,24 +173,22 @@ __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16&
 
 // Tall GEMM (256 .. 816 tokens): the vision tower and the prefix transformer.
 // Block = WN waves, each owning one 32-feature tile, all sharing one MB*32-token activation tile
-// that is staged through LDS in chunks of 64 k.  A chunk ("stage") is the block's activation
-// slice plus each wave's 4 weight fragments.  D stages are kept in flight in registers and every
-// stage is issued the same distance ahead of its use: vector-memory loads complete in issue
-// order, so a weight prefetch issued far ahead does not help if the activation load behind which
-// it queues is only one chunk ahead.  With a memory round trip of 2-3 us and 0.4 us of MFMA work
-// per chunk this distance is what sets the rate.
+// that is staged through LDS in chunks of 64 k (4 fragments per 32-token block, copied 1 KiB at a
+// time from the XF layout, so global reads, LDS writes and LDS reads are all contiguous).  A
+// "stage" is the block's activation chunk plus each wave's 4 weight fragments.  D stages are kept
+// in flight in registers and every stage is issued the same distance ahead of its use:
+// vector-memory loads complete in issue order, so a weight prefetch issued far ahead does not
+// help if the activation load behind which it queues is only one chunk ahead.
 template <int MB, int WN, int D, int PRO, int EPI>
 __global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_kernel(GemmParams p) {
-  constexpr int NT = 64 * WN;             // threads
-  constexpr int LDX = 64 + LDS_PAD;       // LDS row stride (elements)
   constexpr int ROWS = MB * 32;
-  constexpr int RPP = NT / 8;             // rows staged per pass (8 sixteen-byte pieces per row)
-  constexpr int NP = ROWS / RPP;          // passes
-  static_assert(ROWS % RPP == 0, "staging must tile the rows");
+  constexpr int NFR = MB * 4;             // fragments per chunk
+  constexpr int NP = NFR / WN;            // fragments staged per wave per chunk
+  static_assert(NFR % WN == 0, "staging must tile the fragments");
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  bf16* xs = reinterpret_cast<bf16*>(smem_raw);                       // [2][ROWS][LDX]
-  float* stat = reinterpret_cast<float*>(smem_raw + (size_t)2 * ROWS * LDX * sizeof(bf16));  // [2][ROWS]
+  bf16* xs = reinterpret_cast<bf16*>(smem_raw);                                        // [2][NFR][64][8]
+  float* stat = reinterpret_cast<float*>(smem_raw + (size_t)2 * NFR * 1024);           // [2][WN][ROWS]
 
   const int t = threadIdx.x;
   const int lane = t & 63;
@@ -206,36 +211,40 @@ __global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(1, 1)))
   const int kend = min(kbeg + p.k_per_split, k_pad);
   const int NC = (kend - kbeg + 63) >> 6;
   const int KC16 = k_pad >> 4;
+  const int XKC16 = p.ldx >> 4;
+  const int mb_last = (p.M - 1) >> 5;
 
-  const int st_row = t >> 3;
-  const int st_kp = t & 7;
+  // Staging: fragment f = wn + WN*i of the chunk, f = mb*4 + s.  All loads are unconditional
+  // (block index clamped into the valid range) so that the loop body is straight-line code: the
+  // compiler then keeps exact per-register wait counts and really leaves D stages in flight.
+  // Token blocks beyond M re-read the last block (their outputs are never stored), chunks beyond
+  // the last re-read the last chunk (never computed).
   bf16x8 xr[D][NP];
   bf16x8 wr[D][4];
   float s1[NP], s2[NP];
+  const bf16* xfrag[NP];
 #pragma unroll
-  for (int i = 0; i < NP; i++) { s1[i] = 0.f; s2[i] = 0.f; }
-  const bf16* wbase = p.W.w + ((size_t)(wave_active ? nt : 0) * KC16) * 512 + lane * 8;
+  for (int i = 0; i < NP; i++) {
+    s1[i] = 0.f;
+    s2[i] = 0.f;
+    const int f = wn + WN * i;
+    const int mbg = min((m0 >> 5) + (f >> 2), mb_last);
+    xfrag[i] = p.X + ((size_t)mbg * XKC16 + (kbeg >> 4) + (f & 3)) * 512 + lane * 8;
+  }
+  const bf16* wbase = p.W.w + ((size_t)(wave_active ? nt : 0) * KC16 + (kbeg >> 4)) * 512 + lane * 8;
 
-  // All loads are unconditional (addresses clamped into the valid range) so that the loop body is
-  // straight-line code: the compiler then keeps exact per-register wait counts and really leaves
-  // D stages in flight.  Rows beyond M re-read row M-1 (their outputs are never stored), chunks
-  // beyond the last re-read the last chunk (never computed).
-  const bf16* xrow[NP];
-#pragma unroll
-  for (int i = 0; i < NP; i++) xrow[i] = p.X + (size_t)min(m0 + st_row + i * RPP, p.M - 1) * p.ldx + kbeg + st_kp * 8;
 #define ISSUE_STAGE(c, u)                                                                             \
   {                                                                                                   \
     const int cc_ = min((c), NC - 1);                                                                 \
     _Pragma("unroll") for (int i = 0; i < NP; i++)                                                    \
-      xr[u][i] = *reinterpret_cast<const bf16x8*>(xrow[i] + cc_ * 64);                                \
+      xr[u][i] = *reinterpret_cast<const bf16x8*>(xfrag[i] + (size_t)cc_ * 2048);                     \
     _Pragma("unroll") for (int s_ = 0; s_ < 4; s_++)                                                  \
-      wr[u][s_] = *reinterpret_cast<const bf16x8*>(wbase + (size_t)((kbeg >> 4) + cc_ * 4 + s_) * 512); \
+      wr[u][s_] = *reinterpret_cast<const bf16x8*>(wbase + (size_t)(cc_ * 4 + s_) * 512);             \
   }
 #define STORE_STAGE(u, buf, live)                                                                     \
   {                                                                                                   \
     _Pragma("unroll") for (int i = 0; i < NP; i++) {                                                  \
-      const int row_ = st_row + i * RPP;                                                              \
-      *reinterpret_cast<bf16x8*>(xs + ((size_t)(buf) * ROWS + row_) * LDX + st_kp * 8) = xr[u][i];    \
+      *reinterpret_cast<bf16x8*>(xs + (((size_t)(buf) * NFR + wn + WN * i) * 64 + lane) * 8) = xr[u][i]; \
       if (PRO != PRO_NONE) {                                                                          \
         float a_ = 0.f, b_ = 0.f;                                                                     \
         _Pragma("unroll") for (int j = 0; j < 8; j++) {                                               \
@@ -263,49 +272,89 @@ __global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(1, 1)))
   const int lq = lane & 31;
   const int lh = lane >> 5;
   int cur = 0;
-  for (int c0 = 0; c0 < NC; c0 += D) {
+  // One chunk: 4 k16 steps of MB MFMAs against the wave's weight fragments wr[u][*]; the B
+  // fragments of step s+1 are read from LDS while the MFMAs of step s run.  With one wave per SIMD
+  // nothing else overlaps memory instructions with the matrix pipe, so the main loop asks the
+  // scheduler for an explicit interleave: behind every MFMA one LDS read (next step's operands),
+  // one of the 12 global loads of the stage issued this iteration, or one of the LDS writes of
+  // the next chunk.
+#define COMPUTE_CHUNK(u)                                                                              \
+  {                                                                                                   \
+    const bf16* xb_ = xs + ((size_t)cur * NFR * 64 + lane) * 8;                                       \
+    bf16x8 bq_[2][MB];                                                                                \
+    _Pragma("unroll") for (int mb = 0; mb < MB; mb++)                                                 \
+      bq_[0][mb] = *reinterpret_cast<const bf16x8*>(xb_ + (size_t)(mb * 4) * 512);                    \
+    _Pragma("unroll") for (int s = 0; s < 4; s++) {                                                   \
+      if (s < 3) {                                                                                    \
+        _Pragma("unroll") for (int mb = 0; mb < MB; mb++)                                             \
+          bq_[(s + 1) & 1][mb] = *reinterpret_cast<const bf16x8*>(xb_ + (size_t)(mb * 4 + s + 1) * 512); \
+      }                                                                                               \
+      _Pragma("unroll") for (int mb = 0; mb < MB; mb++)                                               \
+        acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[u][s], bq_[s & 1][mb], acc[mb], 0, 0, 0); \
+    }                                                                                                 \
+  }
+  int c0 = 0;
+  for (; c0 + D <= NC; c0 += D) {
 #pragma unroll
     for (int u = 0; u < D; u++) {
       const int c = c0 + u;
-      if (wave_active && c < NC) {
-        // B fragments of step s+1 are fetched from LDS while the MFMAs of step s run
-        const bf16* xb = xs + ((size_t)cur * ROWS + lq) * LDX + lh * 8;
-        bf16x8 bq[2][MB];
-#pragma unroll
-        for (int mb = 0; mb < MB; mb++) bq[0][mb] = *reinterpret_cast<const bf16x8*>(xb + (size_t)mb * 32 * LDX);
-#pragma unroll
-        for (int s = 0; s < 4; s++) {
-          if (s < 3) {
-#pragma unroll
-            for (int mb = 0; mb < MB; mb++)
-              bq[(s + 1) & 1][mb] = *reinterpret_cast<const bf16x8*>(xb + (size_t)mb * 32 * LDX + (s + 1) * 16);
-          }
-          __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-          for (int mb = 0; mb < MB; mb++)
-            acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[u][s], bq[s & 1][mb], acc[mb], 0, 0, 0);
-          // pin the order [reads of step s+1][MFMAs of step s]: with one wave per SIMD nobody else
-          // hides LDS latency, so no MFMA may wait for a read issued just before it
-          __builtin_amdgcn_sched_barrier(0);
-        }
-      }
-      STORE_STAGE((u + 1) % D, cur ^ 1, c + 1 < NC)
+      COMPUTE_CHUNK(u)
       ISSUE_STAGE(c + D, u)
+      STORE_STAGE((u + 1) % D, cur ^ 1, c + 1 < NC)
+      // ---- requested instruction order (masks: 0x008 MFMA, 0x100 LDS read, 0x200 LDS write, 0x020 VMEM read)
+      __builtin_amdgcn_sched_group_barrier(0x100, MB, 0);
+#pragma unroll
+      for (int i = 0; i < MB; i++) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+      }
+#pragma unroll
+      for (int i = 0; i < MB; i++) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        if (i < NP + 4 - MB) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+      }
+#pragma unroll
+      for (int i = 0; i < MB; i++) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+#pragma unroll
+      for (int i = 0; i < MB; i++) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (i < NP) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+      }
       __syncthreads();
       cur ^= 1;
     }
   }
+  // tail: fewer than D chunks left, same steps with guards
+#pragma unroll
+  for (int u = 0; u < D - 1; u++) {
+    const int c = c0 + u;
+    if (c < NC) {
+      COMPUTE_CHUNK(u)
+      STORE_STAGE((u + 1) % D, cur ^ 1, c + 1 < NC)
+      __syncthreads();
+      cur ^= 1;
+    }
+  }
+#undef COMPUTE_CHUNK
 #undef ISSUE_STAGE
 #undef STORE_STAGE
 
-  // ---- row statistics ----------------------------------------------------------------------
+  // ---- row statistics: a row's pieces sit in both lane halves of all WN waves ----------------
   if (PRO != PRO_NONE) {
 #pragma unroll
     for (int i = 0; i < NP; i++) {
-      const float a = sum8_dpp(s1[i]), b = sum8_dpp(s2[i]);
-      if (st_kp == 0) {
-        stat[st_row + i * RPP] = a;
-        stat[ROWS + st_row + i * RPP] = b;
+      const float a = s1[i] + __shfl_xor(s1[i], 32, 64);
+      const float b = s2[i] + __shfl_xor(s2[i], 32, 64);
+      const int f = wn + WN * i;
+      // fragment f covers k16 step (f & 3) of token block (f >> 2): partial sums per (step, row)
+      if (lh == 0) {
+        stat[((f & 3) * 2 + 0) * ROWS + (f >> 2) * 32 + lq] = a;
+        stat[((f & 3) * 2 + 1) * ROWS + (f >> 2) * 32 + lq] = b;
       }
     }
     __syncthreads();
@@ -317,26 +366,37 @@ __global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(1, 1)))
   for (int mb = 0; mb < MB; mb++) {
     const int ml = mb * 32 + lq;
     const int m = m0 + ml;
-    if (m < p.M) epilogue_tile<PRO, EPI>(p, acc[mb], nt, m, ml, lh, stat, ROWS, blockIdx.y);
+    if (m < p.M) {
+      float ssum = 0.f, ssq = 0.f;
+      if (PRO != PRO_NONE) {
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+          ssum += stat[(q * 2 + 0) * ROWS + ml];
+          ssq += stat[(q * 2 + 1) * ROWS + ml];
+        }
+      }
+      epilogue_tile<PRO, EPI>(p, acc[mb], nt, m, lh, ssum, ssq, blockIdx.y);
+    }
   }
 }
 
 // ------------------------------------------------------------------------------------------------
 // Skinny GEMM (at most 64 tokens): the action expert's projections.  These kernels move a few MB
 // of weights each and are bound by memory round trips, so a block issues ALL of its loads at entry
-// - the whole activation slice [64][k range <= 1024] (to registers, then LDS) and each wave's 8
-// weight fragments - waits once, and computes.  One block = one 32-feature tile, 8 waves splitting
-// the k range; partial tiles are summed through LDS in wave order (deterministic).
+// and waits once.  One block = one 32-feature tile, 8 waves splitting a k range of at most 1024;
+// wave w owns k16 steps w*8 .. w*8+7 and reads exactly the activation fragments of those steps
+// (both 32-token blocks) from the XF layout straight into registers: no LDS staging, no barrier
+// before the MFMAs.  Partial tiles and partial row statistics are summed through LDS in wave order
+// (deterministic); waves 0 and 1 finish one 32-token tile each.
 // ------------------------------------------------------------------------------------------------
 #define SK_WAVES 8
 #define SK_KMAX 1024
-#define SK_LDX (SK_KMAX + LDS_PAD)
 
 template <int PRO, int EPI>
 __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  bf16* xs = reinterpret_cast<bf16*>(smem_raw);                                           // [64][SK_LDX]
-  float* stat = reinterpret_cast<float*>(smem_raw + (size_t)64 * SK_LDX * sizeof(bf16));  // [2][64]
+  float* red = reinterpret_cast<float*>(smem_raw);                 // [8 waves][2][16][64]
+  float* stat = red + SK_WAVES * 2 * 16 * 64;                      // [8 waves][2 (sum, sq)][64 rows]
   const int t = threadIdx.x;
   const int lane = t & 63;
   const int w = t >> 6;
@@ -348,78 +408,65 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
   const int kend = min(kbeg + p.k_per_split, k_pad);
   const int n16 = (kend - kbeg) >> 4;          // k16 steps of this block (<= 64)
   const int KC16 = k_pad >> 4;
+  const int XKC16 = p.ldx >> 4;
 
-  // weights: wave w owns steps w*8 .. w*8+7
-  bf16x8 wf[8];
+  bf16x8 wf[8], xf[2][8];
   const bf16* wbase = p.W.w + ((size_t)nt * KC16 + (kbeg >> 4)) * 512 + lane * 8;
+  const bf16* xbase = p.X + (size_t)(kbeg >> 4) * 512 + lane * 8;
+  const int mb1 = p.M > 32 ? 1 : 0;            // second token block (clamped when M <= 32)
 #pragma unroll
   for (int i = 0; i < 8; i++) {
-    const int st = w * 8 + i;
-    if (st < n16) wf[i] = *reinterpret_cast<const bf16x8*>(wbase + (size_t)st * 512);
-    else wf[i] = zero8();
+    const int st = min(w * 8 + i, n16 - 1);    // clamped: steps beyond the range are never used
+    wf[i] = *reinterpret_cast<const bf16x8*>(wbase + (size_t)st * 512);
+    xf[0][i] = *reinterpret_cast<const bf16x8*>(xbase + (size_t)st * 512);
+    xf[1][i] = *reinterpret_cast<const bf16x8*>(xbase + ((size_t)mb1 * XKC16 + st) * 512);
   }
-  // activations: thread t stages row t/8, pieces (t%8) + 8j: 8 adjacent lanes cover 128 contiguous
-  // bytes of a row per load, and a row's statistics live in 8 adjacent lanes.
-  const int st_row = t >> 3;
-  const int st_kp = t & 7;
-  bf16x8 xr[16];
-  const bf16* xrow = p.X + (size_t)min(st_row, p.M - 1) * p.ldx + kbeg + st_kp * 8;
-#pragma unroll
-  for (int j = 0; j < 16; j++) {
-    const int gk = kbeg + (st_kp + 8 * j) * 8;
-    if (gk < kend) xr[j] = *reinterpret_cast<const bf16x8*>(xrow + j * 64);
-    else xr[j] = zero8();
-  }
-  {
-    float a = 0.f, b = 0.f;
-#pragma unroll
-    for (int j = 0; j < 16; j++) {
-      *reinterpret_cast<bf16x8*>(xs + (size_t)st_row * SK_LDX + (st_kp + 8 * j) * 8) = xr[j];
-      if (PRO != PRO_NONE) {
-#pragma unroll
-        for (int e = 0; e < 8; e++) {
-          const float v = (float)xr[j][e];
-          a += v;
-          b += v * v;
-        }
-      }
-    }
-    if (PRO != PRO_NONE) {
-      a = sum8_dpp(a);
-      b = sum8_dpp(b);
-      if (st_kp == 0) {
-        stat[st_row] = a;
-        stat[64 + st_row] = b;
-      }
-    }
-  }
-  __syncthreads();
-
   f32x16 acc[2];
 #pragma unroll
   for (int mb = 0; mb < 2; mb++)
 #pragma unroll
     for (int r = 0; r < 16; r++) acc[mb][r] = 0.f;
+  float sa[2] = {0.f, 0.f}, sb[2] = {0.f, 0.f};
 #pragma unroll
   for (int i = 0; i < 8; i++) {
-    const int st = w * 8 + i;
-    if (st < n16) {
+    const bool live = w * 8 + i < n16;
+    if (live) {
+#pragma unroll
+      for (int mb = 0; mb < 2; mb++) acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[mb][i], acc[mb], 0, 0, 0);
+    }
+    if (PRO != PRO_NONE) {
 #pragma unroll
       for (int mb = 0; mb < 2; mb++) {
-        const bf16x8 b = *reinterpret_cast<const bf16x8*>(xs + (size_t)(mb * 32 + lq) * SK_LDX + st * 16 + lh * 8);
-        acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], b, acc[mb], 0, 0, 0);
+        float a = 0.f, b = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+          const float v = (float)xf[mb][i][e];
+          a += v;
+          b += v * v;
+        }
+        sa[mb] += live ? a : 0.f;
+        sb[mb] += live ? b : 0.f;
       }
     }
   }
-  __syncthreads();                                     // all reads of xs done: reuse it for the reduction
-  float* red = reinterpret_cast<float*>(smem_raw);     // [8 waves][2][16][64]
 #pragma unroll
   for (int mb = 0; mb < 2; mb++)
 #pragma unroll
     for (int r = 0; r < 16; r++) red[(((size_t)w * 2 + mb) * 16 + r) * 64 + lane] = acc[mb][r];
+  if (PRO != PRO_NONE) {
+#pragma unroll
+    for (int mb = 0; mb < 2; mb++) {
+      const float a = sa[mb] + __shfl_xor(sa[mb], 32, 64);
+      const float b = sb[mb] + __shfl_xor(sb[mb], 32, 64);
+      if (lh == 0) {
+        stat[(w * 2 + 0) * 64 + mb * 32 + lq] = a;
+        stat[(w * 2 + 1) * 64 + mb * 32 + lq] = b;
+      }
+    }
+  }
   __syncthreads();
   if (w >= 2) return;
-  const int mb = w;                                    // waves 0 and 1 finish one 32-token tile each
+  const int mb = w;
   f32x16 sum;
 #pragma unroll
   for (int r = 0; r < 16; r++) sum[r] = 0.f;
@@ -428,15 +475,25 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
 #pragma unroll
     for (int r = 0; r < 16; r++) sum[r] += red[(((size_t)ww * 2 + mb) * 16 + r) * 64 + lane];
   const int ml = mb * 32 + lq;
-  if (ml < p.M) epilogue_tile<PRO, EPI>(p, sum, nt, ml, ml, lh, stat, 64, blockIdx.y);
+  if (ml < p.M) {
+    float ssum = 0.f, ssq = 0.f;
+    if (PRO != PRO_NONE) {
+#pragma unroll
+      for (int ww = 0; ww < SK_WAVES; ww++) {
+        ssum += stat[(ww * 2 + 0) * 64 + ml];
+        ssq += stat[(ww * 2 + 1) * 64 + ml];
+      }
+    }
+    epilogue_tile<PRO, EPI>(p, sum, nt, ml, lh, ssum, ssq, blockIdx.y);
+  }
 }
 
-static constexpr int skinny_smem_bytes() { return 64 * SK_LDX * 2 + 2 * 64 * 4; }
+static constexpr int skinny_smem_bytes() { return (SK_WAVES * 2 * 16 * 64 + SK_WAVES * 2 * 64) * 4; }
 
 // ------------------------------------------------------------------------------------------------
 template <int MB>
 static constexpr int smem_bytes_for() {
-  return 2 * (MB * 32) * (64 + LDS_PAD) * 2 + 2 * (MB * 32) * 4;
+  return 2 * (MB * 4) * 1024 + 8 * (MB * 32) * 4;
 }
 
 int gemm_rows_per_tile(int tile) {
@@ -507,7 +564,7 @@ hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmPara
   // Host-side shape checks: everything the kernel's indexing assumes.
   if (p.X == nullptr || p.W.w == nullptr || p.M <= 0 || z_splits < 1) return hipErrorInvalidValue;
   if (p.W.k_pad % 64 != 0 || p.W.n_pad % 32 != 0 || p.n_tiles * 32 != p.W.n_pad) return hipErrorInvalidValue;
-  if (p.ldx < p.W.k_pad || p.ldx % 8 != 0) return hipErrorInvalidValue;
+  if (p.ldx < p.W.k_pad || p.ldx % 16 != 0) return hipErrorInvalidValue;   // X is in XF layout with ldx padded columns
   if (p.k_per_split % 64 != 0 || (long)p.k_per_split * z_splits < p.W.k_pad) return hipErrorInvalidValue;
   if (pro != PRO_NONE && z_splits != 1) return hipErrorInvalidValue;
   if (epi != EPI_PARTIAL && z_splits != 1) return hipErrorInvalidValue;
@@ -551,11 +608,11 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(ReduceParams p) {
   if (p.resid != nullptr) a += *reinterpret_cast<const f32x4*>(p.resid + (size_t)m * p.ldo + n);
   *reinterpret_cast<f32x4*>(p.out_f32 + (size_t)m * p.ldo + n) = a;
   const bf16x4 ob = {(bf16)a[0], (bf16)a[1], (bf16)a[2], (bf16)a[3]};
-  *reinterpret_cast<bf16x4*>(p.out_bf16 + (size_t)m * p.ldo2 + n) = ob;
+  *reinterpret_cast<bf16x4*>(p.out_bf16 + xf_index(m, n, p.ldo2 >> 4)) = ob;
 }
 
 hipError_t launch_splitk_reduce(hipStream_t s, const ReduceParams& p) {
-  if (p.N % 4 != 0 || p.ldp < p.N || p.ldo < p.N || p.ldo2 < p.N || p.M <= 0 || p.Z < 1) return hipErrorInvalidValue;
+  if (p.N % 4 != 0 || p.ldp < p.N || p.ldo < p.N || p.ldo2 < p.N || p.ldo2 % 16 != 0 || p.M <= 0 || p.Z < 1) return hipErrorInvalidValue;
   const size_t total = (size_t)p.M * (p.N / 4);
   hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, p);
   return hipGetLastError();

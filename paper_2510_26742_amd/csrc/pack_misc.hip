@@ -3,6 +3,11 @@
 // folded action/time embedding of Table 2 rows 1x32x1024 and 63x32x1024).
 #include "pi0_internal.h"
 
+// index of element (row m, column k) of an activation matrix in XF (MFMA B-fragment) order
+__device__ __forceinline__ size_t xf_index(int m, int k, int kc16) {
+  return ((size_t)(m >> 5) * kc16 + (k >> 4)) * 512 + (((k & 15) >> 3) * 32 + (m & 31)) * 8 + (k & 7);
+}
+
 // ------------------------------------------------------------------------------------------------
 // packed row n -> (source matrix, source column); returns false for padding rows
 // ------------------------------------------------------------------------------------------------
@@ -197,8 +202,8 @@ hipError_t launch_time_fold(hipStream_t st, const bf16* wa, const bf16* ba, cons
 }
 
 // ------------------------------------------------------------------------------------------------
-// images [V][img][img][3] fp32 -> patch vectors bf16 [V*T][ld], order (dy, dx, c); columns
-// >= patch*patch*3 are left untouched (they are zero from load time).
+// images [V][img][img][3] fp32 -> patch vectors bf16, XF layout with ld padded columns, vector
+// order (dy, dx, c); columns >= patch*patch*3 are left untouched (zero from load time).
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void patchify_kernel(const float* images, int n_views, int img, int patch, bf16* out,
                                                        int ld) {
@@ -213,12 +218,12 @@ __global__ __launch_bounds__(256) void patchify_kernel(const float* images, int 
   const int py = tt / per_side, px = tt % per_side;
   const int c = e % 3, dx = (e / 3) % patch, dy = e / (3 * patch);
   const float val = images[(((size_t)v * img + (py * patch + dy)) * img + (px * patch + dx)) * 3 + c];
-  out[(size_t)tok * ld + e] = (bf16)val;
+  out[xf_index(tok, e, ld >> 4)] = (bf16)val;
 }
 hipError_t launch_patchify(hipStream_t st, const float* images, int n_views, int img, int patch, bf16* out, int ld) {
   const int per_side = img / patch;
   const size_t total = (size_t)n_views * per_side * per_side * patch * patch * 3;
-  if (ld < patch * patch * 3) return hipErrorInvalidValue;
+  if (ld < patch * patch * 3 || ld % 16 != 0) return hipErrorInvalidValue;
   hipLaunchKernelGGL(patchify_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, images, n_views, img, patch,
                      out, ld);
   return hipGetLastError();
@@ -234,7 +239,7 @@ __global__ __launch_bounds__(256) void embed_prompt_kernel(const int32_t* ids, i
   id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);   // out-of-range ids are clamped, never read out of bounds
   const float v = scale * (float)table[(size_t)id * E + c];
   out_f32[(size_t)(row0 + i) * E + c] = v;
-  out_bf16[(size_t)(row0 + i) * E + c] = (bf16)v;
+  out_bf16[xf_index(row0 + i, c, E >> 4)] = (bf16)v;
 }
 hipError_t launch_embed_prompt(hipStream_t st, const int32_t* ids, int n, const bf16* table, int vocab, int E, float scale,
                                float* out_f32, bf16* out_bf16, int row0) {
@@ -273,12 +278,12 @@ __global__ __launch_bounds__(256) void action_embed_kernel(const float* x, int c
     float acc = bias_k[n];
     for (int j = 0; j < A; j++) acc += x[(size_t)r * A + j] * wfold[(size_t)j * X + n];
     const float sv = acc / (1.0f + __expf(-acc));
-    z[(size_t)r * X + n] = (bf16)sv;
+    z[xf_index(r, n, X >> 4)] = (bf16)sv;
   } else {
-    z[(size_t)chunk * X + n] = (bf16)0.0f;
+    z[xf_index(chunk, n, X >> 4)] = (bf16)0.0f;
     const float s = state_tok[n];
     y_f32[n] = s;
-    y_bf16[n] = (bf16)s;
+    y_bf16[xf_index(0, n, X >> 4)] = (bf16)s;
   }
 }
 hipError_t launch_action_embed(hipStream_t st, const float* x, int chunk, int action_dim, const float* wfold,

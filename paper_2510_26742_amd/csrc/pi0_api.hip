@@ -225,7 +225,7 @@ void ws_layout(const pi0_config& c, const Dims& d, WsLayout& w) {
   w.xpatch = cur.take((size_t)d.maxI * d.PDp * 2);
   w.vh = cur.take((size_t)d.maxI * d.Dv * 4);
   w.vh_b = cur.take((size_t)d.maxI * d.Dv * 2);
-  w.vq = cur.take((size_t)d.maxI * d.Hv * 80 * 2);
+  w.vq = cur.take((size_t)d.Hv * (d.maxI / 32) * 5 * 512 * 2);
   w.vk = cur.take((size_t)d.Hv * (d.maxI / 32) * 5 * 512 * 2);
   w.vv = cur.take((size_t)d.Hv * (d.maxI / 32) * 3 * 1024 * 2);
   w.vattn = cur.take((size_t)d.maxI * d.Dv * 2);
@@ -237,19 +237,19 @@ void ws_layout(const pi0_config& c, const Dims& d, WsLayout& w) {
     w.part = cur.take(a > b ? a : b);
   }
   w.lx = cur.take((size_t)d.maxP * d.E * 4);
-  w.lx_b = cur.take((size_t)d.maxP * d.E * 2);
-  w.lq = cur.take((size_t)d.maxP * d.H * 256 * 2);
+  w.lx_b = cur.take((size_t)d.maxPc * 32 * d.E * 2);
+  w.lq = cur.take((size_t)d.H * d.maxPc * 16 * 512 * 2);
   w.kcache_layer = (size_t)d.maxPc * 16 * 512 * 2;
   w.vcache_layer = (size_t)d.maxPc * 8 * 1024 * 2;
   w.kcache = cur.take(w.kcache_layer * d.Ll);
   w.vcache = cur.take(w.vcache_layer * d.Ll);
-  w.lattn = cur.take((size_t)d.maxP * d.H * 256 * 2);
-  w.lmid = cur.take((size_t)d.maxP * d.F * 2);
+  w.lattn = cur.take((size_t)d.maxPc * 32 * d.H * 256 * 2);
+  w.lmid = cur.take((size_t)d.maxPc * 32 * d.F * 2);
   w.stok = cur.take((size_t)d.X * 4);
   w.z = cur.take((size_t)64 * d.X * 2);
   w.y = cur.take((size_t)64 * d.X * 4);
   w.y_b = cur.take((size_t)64 * d.X * 2);
-  w.eq = cur.take((size_t)64 * d.H * 256 * 2);
+  w.eq = cur.take((size_t)d.H * 2 * 16 * 512 * 2);
   w.ek = cur.take((size_t)2 * 16 * 512 * 2);
   w.ev = cur.take((size_t)2 * 8 * 1024 * 2);
   w.eattn = cur.take((size_t)64 * d.H * 256 * 2);
@@ -402,7 +402,7 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
       p.bias = at<float>(c, L.qkv.bias);
       p.colsum = at<float>(c, L.qkv.colsum);
       p.out_bf16 = at<bf16>(c, w.vq);
-      p.ldo = d.Hv * 80;
+      p.q_mbs = vchunks;
       p.kfrag = at<bf16>(c, w.vk);
       p.vfrag = at<bf16>(c, w.vv);
       p.rope = nullptr;
@@ -413,7 +413,7 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
     {  // A2: attention inside each view
       AttnParams a;
       memset(&a, 0, sizeof(a));
-      a.q = at<bf16>(c, w.vq); a.q_ld = d.Hv * 80; a.q_head_stride = 80;
+      a.q = at<bf16>(c, w.vq); a.q_head_stride = vchunks * 5 * 512;
       a.Tq = I; a.heads = d.Hv;
       a.k0 = at<bf16>(c, w.vk); a.v0 = at<bf16>(c, w.vv);
       a.chunks0 = vchunks; a.valid0 = I;
@@ -462,7 +462,7 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
     {  // B1: RMS -> QKV, RoPE, keys/values into the cache (last layer: keys/values only)
       GemmParams p = gp_base(c, L.qkv, at<bf16>(c, w.lx_b), d.E, P, T.lqkv, d.E);
       p.out_bf16 = at<bf16>(c, w.lq);
-      p.ldo = d.H * 256;
+      p.q_mbs = pchunks;
       p.kfrag = kc; p.vfrag = vc;
       p.rope = at<float>(c, w.rope);
       p.pos0 = 0;
@@ -474,7 +474,7 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
     {  // B2: attention, whole prefix visible
       AttnParams a;
       memset(&a, 0, sizeof(a));
-      a.q = at<bf16>(c, w.lq); a.q_ld = d.H * 256; a.q_head_stride = 256;
+      a.q = at<bf16>(c, w.lq); a.q_head_stride = pchunks * 16 * 512;
       a.Tq = P; a.heads = d.H;
       a.k0 = kc; a.v0 = vc; a.chunks0 = pchunks; a.valid0 = P;
       a.scale = 1.0f / 16.0f;
@@ -541,7 +541,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
       {  // C3: RMS -> QKV, RoPE at positions P..P+63
         GemmParams p = gp_base(c, L.qkv, at<bf16>(c, w.y_b), d.X, 64, TILE_SKINNY, d.X);
         p.out_bf16 = at<bf16>(c, w.eq);
-        p.ldo = d.H * 256;
+        p.q_mbs = 2;
         p.kfrag = at<bf16>(c, w.ek); p.vfrag = at<bf16>(c, w.ev);
         p.rope = at<float>(c, w.rope);
         p.pos0 = P;
@@ -552,7 +552,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
       {  // C4 + C5: scores, block mask, softmax, PV over [cache ; own keys]
         AttnParams a;
         memset(&a, 0, sizeof(a));
-        a.q = at<bf16>(c, w.eq); a.q_ld = d.H * 256; a.q_head_stride = 256;
+        a.q = at<bf16>(c, w.eq); a.q_head_stride = 2 * 16 * 512;
         a.Tq = 64; a.heads = d.H;
         a.k0 = kc; a.v0 = vc; a.chunks0 = pchunks; a.valid0 = P;
         a.k1 = at<bf16>(c, w.ek); a.v1 = at<bf16>(c, w.ev); a.chunks1 = 2;

@@ -63,7 +63,7 @@ enum Epilogue {
 enum Act { ACT_NONE = 0, ACT_GELU = 1, ACT_SILU = 2 };
 
 struct GemmParams {
-  const bf16* X;      // [M][ldx] activations, ldx >= k_pad, pad columns finite (zero)
+  const bf16* X;      // activations in XF layout with ldx (padded) columns, ldx >= k_pad, pad columns zero
   int ldx;
   int M;              // valid rows
   PackedW W;
@@ -76,9 +76,9 @@ struct GemmParams {
   const float* colsum;  // [n_pad], PRO_LN only: sum_k W'[n][k]
   // outputs
   float* out_f32;     // EPI_RESID / EPI_PARTIAL / EPI_EULER
-  bf16* out_bf16;     // EPI_RESID shadow, EPI_BF16, EPI_GEGLU, EPI_QKV q
-  int ldo;            // leading dimension of out_f32 / out_bf16 (elements)
-  int ldo2;           // leading dimension of out_bf16 shadow in EPI_RESID
+  bf16* out_bf16;     // EPI_RESID shadow (XF), EPI_BF16 (XF), EPI_GEGLU (XF), EPI_QKV q (fragment order per head)
+  int ldo;            // leading dimension of out_f32; padded columns of the XF output of EPI_BF16 / EPI_GEGLU
+  int ldo2;           // padded columns of the XF shadow in EPI_RESID
   int n_valid;        // columns >= n_valid are not stored (EPI_RESID / EPI_BF16 / EPI_EULER)
   const float* resid; // EPI_RESID: residual input [*][ldo] or null
   int resid_mod;      // row index of resid taken modulo this (0 = no modulo)
@@ -96,6 +96,7 @@ struct GemmParams {
   int nvb;            // value blocks of 32 (3 or 8)
   int kv_heads;       // 16 (vision) or 1
   int kv_chunks;      // key chunks (of 32) per head in kfrag / vfrag
+  int q_mbs;          // 32-token blocks per head in the fragment-ordered q buffer
   // EPI_EULER
   float dt;
 };
@@ -118,7 +119,7 @@ struct ReduceParams {
   const float* bias;
   const float* resid;
   float* out_f32;
-  bf16* out_bf16;
+  bf16* out_bf16;     // XF layout with ldo2 padded columns
   int ldo, ldo2;
 };
 hipError_t launch_splitk_reduce(hipStream_t s, const ReduceParams& p);
@@ -130,8 +131,8 @@ hipError_t launch_splitk_reduce(hipStream_t s, const ReduceParams& p);
 //                  [j = ((key%16)/8)*4 + key%4]
 // ------------------------------------------------------------------------------------------
 struct AttnParams {
-  const bf16* q;       // [Tq][q_ld], head h at column h * q_head_stride
-  int q_ld, q_head_stride;
+  const bf16* q;       // fragment order [head][ceil(Tq/32)][dqk/16][64][8]; q_head_stride elements per head
+  int q_head_stride;
   int Tq;              // query rows per head
   int heads;
   const bf16* k0;      // first key segment (prefix cache or the layer's own keys)
@@ -146,7 +147,7 @@ struct AttnParams {
   int view_tokens;     // > 0: query row m only sees keys of its own view [m/vt*vt, +vt)
   int suffix_mask;     // 1: row 0 sees only key 0 of segment 1; other rows see all of segment 1
   float scale;
-  bf16* out;           // [Tq][out_ld], head h at column h * head_dim
+  bf16* out;           // XF layout, out_ld padded columns; head h at columns h * head_dim ..
   int out_ld;
   int head_dim;        // 72 or 256
 };
