@@ -8,9 +8,11 @@
 //
 // One block of 8 waves owns 32 query rows of one head.  The kernels of this pass are short and
 // bound by memory round trips, not by arithmetic, so the block is organised to need one round
-// trip when the keys fit (<= 8 chunks of 32 keys per wave-round): at entry every wave issues its
-// loads of Q (to LDS), of the key fragments of "its" chunks (chunk index = wave, wave + 8, ...)
-// and of the value fragments of "its" 32-wide slice of the head dimension, all at once.
+// trip when the prefix has at most 8 chunks of 32 keys: at entry every wave issues its loads of Q
+// (to LDS), of the key fragments of "its" prefix chunks (chunk index = wave, wave + 8, ...), of
+// the value fragments of "its" 32-wide slice of the head dimension, and the block copies the
+// (at most two) key chunks of the second segment - the action expert's own 64 keys - to LDS, so
+// that waves 0 and 1 can score them without a second trip to memory.
 //   phase 1  S^T = K Q^T per chunk (keys x queries): a lane owns one query row, so max and sum
 //            are per-lane scalars; the probabilities in the accumulator registers are, without
 //            any data movement, B-operand fragments of the second product and go to LDS as such;
@@ -22,19 +24,22 @@
 
 #define NEG_BIG (-1.0e30f)
 #define ATT_WAVES 8
-#define ATT_MAXR 4          // key rounds per wave: up to 8 * 4 = 32 chunks = 1024 keys
-#define ATT_VRING 8         // value chunks in flight per wave
 
-template <int DQK, int NVB>
+// MAXR: key rounds per wave over segment 0 (8 * MAXR chunks = 256 * MAXR keys); VRING: value
+// chunks in flight per wave.
+template <int DQK, int NVB, int MAXR, int VRING>
 __global__ __launch_bounds__(512) void attention_kernel(AttnParams p) {
   constexpr int S16 = DQK / 16;
   constexpr int NPQ = 32 * DQK / 8;            // 16-byte pieces of the Q tile
   constexpr int QP = (NPQ + 511) / 512;        // pieces per thread
+  constexpr int NPK1 = 2 * S16 * 64;           // 16-byte pieces of the two segment-1 key chunks
+  constexpr int KP1 = (NPK1 + 511) / 512;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16* qs = reinterpret_cast<bf16*>(smem_raw);                               // [S16][64][8]
-  float* mw = reinterpret_cast<float*>(smem_raw + (size_t)S16 * 1024);         // [8][32]
-  float* lw = mw + ATT_WAVES * 32;                                             // [8][32]
-  bf16* pf = reinterpret_cast<bf16*>(lw + ATT_WAVES * 32);                     // [ntot][2][64][8]
+  bf16* k1s = qs + S16 * 512;                                                 // [2][S16][64][8]
+  float* mw = reinterpret_cast<float*>(k1s + 2 * S16 * 512);                  // [8][32]
+  float* lw = mw + ATT_WAVES * 32;                                            // [8][32]
+  bf16* pf = reinterpret_cast<bf16*>(lw + ATT_WAVES * 32);                    // [ntot][2][64][8]
 
   const int t = threadIdx.x;
   const int lane = t & 63;
@@ -52,42 +57,39 @@ __global__ __launch_bounds__(512) void attention_kernel(AttnParams p) {
     cbeg0 = view * (p.view_tokens >> 5);
     n0 = p.view_tokens >> 5;
   }
-  const int ntot = n0 + p.chunks1;
-  const bf16* kbase0 = p.k0 + (size_t)head * p.kv_head_stride0;
-  const bf16* vbase0 = p.v0 + (size_t)head * p.v_head_stride0;
-  auto kptr = [&](int ci) -> const bf16* {
-    return (ci >= n0 ? p.k1 + (size_t)(ci - n0) * S16 * 512 : kbase0 + (size_t)(cbeg0 + ci) * S16 * 512) + lane * 8;
-  };
-  auto vptr = [&](int ci) -> const bf16* {
-    return (ci >= n0 ? p.v1 + (size_t)(ci - n0) * NVB * 1024 : vbase0 + (size_t)(cbeg0 + ci) * NVB * 1024) + w * 1024 +
-           lane * 8;
+  const int n1 = p.chunks1;
+  const int ntot = n0 + n1;
+  const bf16* kbase0 = p.k0 + ((size_t)head * p.kv_head_stride0 + (size_t)cbeg0 * S16 * 512) + lane * 8;
+  const bf16* vbase0 = p.v0 + ((size_t)head * p.v_head_stride0 + (size_t)cbeg0 * NVB * 1024);
+  auto vptr = [&](int ci) -> const bf16* {   // ci clamped by the caller
+    return (ci >= n0 ? p.v1 + (size_t)(ci - n0) * NVB * 1024 : vbase0 + (size_t)ci * NVB * 1024) + w * 1024 + lane * 8;
   };
 
-  // ---- issue every load of the first round ---------------------------------------------------
-  // Q tile: S16 fragments of 1 KiB, already in fragment order in global memory
+  // ---- issue every load of the first round (unconditional, clamped addresses) -----------------
   const bf16* qsrc = p.q + (size_t)head * p.q_head_stride + (size_t)tile * S16 * 512;
   bf16x8 qreg[QP];
 #pragma unroll
-  for (int i = 0; i < QP; i++) {
-    const int pc = min(t + i * 512, NPQ - 1);
-    qreg[i] = *reinterpret_cast<const bf16x8*>(qsrc + (size_t)pc * 8);
+  for (int i = 0; i < QP; i++) qreg[i] = *reinterpret_cast<const bf16x8*>(qsrc + (size_t)min(t + i * 512, NPQ - 1) * 8);
+  bf16x8 k1reg[KP1];
+  if (n1 > 0) {
+#pragma unroll
+    for (int i = 0; i < KP1; i++)
+      k1reg[i] = *reinterpret_cast<const bf16x8*>(p.k1 + (size_t)min(t + i * 512, n1 * S16 * 64 - 1) * 8);
   }
   bf16x8 kf[S16];
-  if (w < ntot) {
-    const bf16* kp0 = kptr(w);
+  {
+    const bf16* kp0 = kbase0 + (size_t)min(w, n0 - 1) * S16 * 512;
 #pragma unroll
     for (int s = 0; s < S16; s++) kf[s] = *reinterpret_cast<const bf16x8*>(kp0 + (size_t)s * 512);
   }
-  bf16x8 vf[ATT_VRING * 2];
+  bf16x8 vf[VRING * 2];
   const bool pv_wave = w < NVB;
   if (pv_wave) {
 #pragma unroll
-    for (int c = 0; c < ATT_VRING; c++) {
-      if (c < ntot) {
-        const bf16* vp = vptr(c);
-        vf[2 * c] = *reinterpret_cast<const bf16x8*>(vp);
-        vf[2 * c + 1] = *reinterpret_cast<const bf16x8*>(vp + 512);
-      }
+    for (int c = 0; c < VRING; c++) {
+      const bf16* vp = vptr(min(c, ntot - 1));
+      vf[2 * c] = *reinterpret_cast<const bf16x8*>(vp);
+      vf[2 * c + 1] = *reinterpret_cast<const bf16x8*>(vp + 512);
     }
   }
 #pragma unroll
@@ -95,39 +97,63 @@ __global__ __launch_bounds__(512) void attention_kernel(AttnParams p) {
     const int pc = t + i * 512;
     if (pc < NPQ) *reinterpret_cast<bf16x8*>(qs + (size_t)pc * 8) = qreg[i];
   }
+  if (n1 > 0) {
+#pragma unroll
+    for (int i = 0; i < KP1; i++) {
+      const int pc = t + i * 512;
+      if (pc < NPK1) *reinterpret_cast<bf16x8*>(k1s + (size_t)pc * 8) = k1reg[i];
+    }
+  }
   __syncthreads();
 
   // ---- phase 1: scores of this wave's chunks ------------------------------------------------
-  float sv[ATT_MAXR][16];
+  float sv[MAXR][16];
+  float sv1[16];
   float m_loc = NEG_BIG;
 #pragma unroll
-  for (int r = 0; r < ATT_MAXR; r++) {
+  for (int r = 0; r < MAXR; r++) {
     const int ci = w + ATT_WAVES * r;
-    if (ci < ntot) {
-      const bool more = ci + ATT_WAVES < ntot;
-      const bf16* kn = more ? kptr(ci + ATT_WAVES) : nullptr;
+    if (ci < n0) {
+      const bool more = ci + ATT_WAVES < n0;
+      const bf16* kn = kbase0 + (size_t)min(ci + ATT_WAVES, n0 - 1) * S16 * 512;
       f32x16 sacc;
 #pragma unroll
       for (int e = 0; e < 16; e++) sacc[e] = 0.f;
 #pragma unroll
       for (int s = 0; s < S16; s++) {
         const bf16x8 a = kf[s];
-        if (more) kf[s] = *reinterpret_cast<const bf16x8*>(kn + (size_t)s * 512);
+        if (r + 1 < MAXR && more) kf[s] = *reinterpret_cast<const bf16x8*>(kn + (size_t)s * 512);
         const bf16x8 b = *reinterpret_cast<const bf16x8*>(qs + ((size_t)s * 64 + lane) * 8);
         sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, sacc, 0, 0, 0);
       }
-      const bool seg1 = ci >= n0;
-      const int chunk = seg1 ? (ci - n0) : (cbeg0 + ci);
 #pragma unroll
       for (int e = 0; e < 16; e++) {
-        const int key = chunk * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
-        const bool valid = seg1 ? (p.suffix_mask ? (row == 0 ? key == 0 : true) : true) : key < p.valid0;
-        sv[r][e] = valid ? sacc[e] * p.scale : NEG_BIG;
+        const int key = (cbeg0 + ci) * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
+        sv[r][e] = key < p.valid0 ? sacc[e] * p.scale : NEG_BIG;
         m_loc = fmaxf(m_loc, sv[r][e]);
       }
     } else {
 #pragma unroll
       for (int e = 0; e < 16; e++) sv[r][e] = NEG_BIG;
+    }
+  }
+  const bool seg1_wave = w < n1;             // waves 0 and 1 score the second segment from LDS
+  if (seg1_wave) {
+    f32x16 sacc;
+#pragma unroll
+    for (int e = 0; e < 16; e++) sacc[e] = 0.f;
+#pragma unroll
+    for (int s = 0; s < S16; s++) {
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(k1s + (((size_t)w * S16 + s) * 64 + lane) * 8);
+      const bf16x8 b = *reinterpret_cast<const bf16x8*>(qs + ((size_t)s * 64 + lane) * 8);
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, sacc, 0, 0, 0);
+    }
+#pragma unroll
+    for (int e = 0; e < 16; e++) {
+      const int key = w * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
+      const bool valid = p.suffix_mask ? (row == 0 ? key == 0 : true) : true;
+      sv1[e] = valid ? sacc[e] * p.scale : NEG_BIG;
+      m_loc = fmaxf(m_loc, sv1[e]);
     }
   }
   m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32, 64));
@@ -137,25 +163,27 @@ __global__ __launch_bounds__(512) void attention_kernel(AttnParams p) {
 #pragma unroll
   for (int i = 0; i < ATT_WAVES; i++) m_all = fmaxf(m_all, mw[i * 32 + lq]);
   float l_loc = 0.f;
+  auto emit = [&](const float* svals, int slot) {   // probabilities -> B-operand fragments in LDS
+    float pr[16];
 #pragma unroll
-  for (int r = 0; r < ATT_MAXR; r++) {
-    const int ci = w + ATT_WAVES * r;
-    if (ci < ntot) {
-      float pr[16];
-#pragma unroll
-      for (int e = 0; e < 16; e++) {
-        pr[e] = sv[r][e] > 0.5f * NEG_BIG ? __expf(sv[r][e] - m_all) : 0.f;   // masked keys: exactly 0
-        l_loc += pr[e];
-      }
-#pragma unroll
-      for (int s2 = 0; s2 < 2; s2++) {
-        bf16x8 pb;
-#pragma unroll
-        for (int j = 0; j < 8; j++) pb[j] = (bf16)pr[8 * s2 + j];
-        *reinterpret_cast<bf16x8*>(pf + ((size_t)(ci * 2 + s2) * 64 + lane) * 8) = pb;
-      }
+    for (int e = 0; e < 16; e++) {
+      pr[e] = svals[e] > 0.5f * NEG_BIG ? __expf(svals[e] - m_all) : 0.f;   // masked keys: exactly 0
+      l_loc += pr[e];
     }
+#pragma unroll
+    for (int s2 = 0; s2 < 2; s2++) {
+      bf16x8 pb;
+#pragma unroll
+      for (int j = 0; j < 8; j++) pb[j] = (bf16)pr[8 * s2 + j];
+      *reinterpret_cast<bf16x8*>(pf + ((size_t)(slot * 2 + s2) * 64 + lane) * 8) = pb;
+    }
+  };
+#pragma unroll
+  for (int r = 0; r < MAXR; r++) {
+    const int ci = w + ATT_WAVES * r;
+    if (ci < n0) emit(sv[r], ci);
   }
+  if (seg1_wave) emit(sv1, n0 + w);
   l_loc += __shfl_xor(l_loc, 32, 64);
   if (lh == 0) lw[w * 32 + lq] = l_loc;
   __syncthreads();
@@ -165,13 +193,13 @@ __global__ __launch_bounds__(512) void attention_kernel(AttnParams p) {
   f32x16 o;
 #pragma unroll
   for (int e = 0; e < 16; e++) o[e] = 0.f;
-  for (int c0 = 0; c0 < ntot; c0 += ATT_VRING) {
+  for (int c0 = 0; c0 < ntot; c0 += VRING) {
 #pragma unroll
-    for (int cc = 0; cc < ATT_VRING; cc++) {
+    for (int cc = 0; cc < VRING; cc++) {
       const int c = c0 + cc;
       if (c < ntot) {
-        const bool more = c + ATT_VRING < ntot;
-        const bf16* vn = more ? vptr(c + ATT_VRING) : nullptr;
+        const bool more = c + VRING < ntot;
+        const bf16* vn = vptr(min(c + VRING, ntot - 1));
 #pragma unroll
         for (int s2 = 0; s2 < 2; s2++) {
           const bf16x8 a = vf[2 * cc + s2];
@@ -201,14 +229,24 @@ __global__ __launch_bounds__(512) void attention_kernel(AttnParams p) {
 }
 
 template <int DQK>
-static int attn_smem(int ntot) { return (DQK / 16) * 1024 + 2 * ATT_WAVES * 32 * 4 + ntot * 2048; }
+static int attn_smem(int ntot) { return 3 * (DQK / 16) * 1024 + 2 * ATT_WAVES * 32 * 4 + ntot * 2048; }
+
+#define ATTN_VARIANTS(X) \
+  X(256, 8, 1, 10)       \
+  X(256, 8, 2, 8)        \
+  X(256, 8, 4, 8)        \
+  X(80, 3, 1, 8)
 
 hipError_t attention_init_attributes() {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_kernel<256, 8>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, attn_smem<256>(ATT_WAVES * ATT_MAXR));
-  if (e != hipSuccess) return e;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_kernel<80, 3>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, attn_smem<80>(ATT_WAVES * ATT_MAXR));
+#define X(DQK, NVB, MAXR, VRING)                                                                              \
+  {                                                                                                           \
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_kernel<DQK, NVB, MAXR, VRING>), \
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, attn_smem<DQK>(8 * MAXR + 2)); \
+    if (e != hipSuccess) return e;                                                                            \
+  }
+  ATTN_VARIANTS(X)
+#undef X
+  return hipSuccess;
 }
 
 hipError_t launch_attention(hipStream_t s, const AttnParams& p) {
@@ -216,7 +254,7 @@ hipError_t launch_attention(hipStream_t s, const AttnParams& p) {
   if (p.Tq <= 0 || p.heads <= 0 || p.chunks0 <= 0 || p.valid0 <= 0 || p.valid0 > p.chunks0 * 32) return hipErrorInvalidValue;
   if (p.q_head_stride % 512 != 0 || p.out_ld % 16 != 0 || p.head_dim % 4 != 0 || p.out_ld < p.heads * p.head_dim) return hipErrorInvalidValue;
   if (p.chunks1 != 0 && (p.k1 == nullptr || p.v1 == nullptr)) return hipErrorInvalidValue;
-  if (p.chunks1 < 0 || p.chunks1 > 2) return hipErrorInvalidValue;
+  if (p.chunks1 != 0 && p.chunks1 != 2) return hipErrorInvalidValue;
   if (p.suffix_mask && p.Tq > 32 * p.chunks1) return hipErrorInvalidValue;
   int n0 = p.chunks0;
   if (p.view_tokens > 0) {
@@ -224,12 +262,15 @@ hipError_t launch_attention(hipStream_t s, const AttnParams& p) {
     n0 = p.view_tokens / 32;
   }
   const int ntot = n0 + p.chunks1;
-  if (ntot > ATT_WAVES * ATT_MAXR) return hipErrorInvalidValue;   // at most 1024 keys per query row
+  if (n0 > 32) return hipErrorInvalidValue;   // at most 1024 keys in segment 0 per query row
   dim3 grid((p.Tq + 31) / 32, p.heads, 1);
   if (p.head_dim == 256) {
-    attention_kernel<256, 8><<<grid, dim3(512), attn_smem<256>(ntot), s>>>(p);
+    if (n0 <= 8) attention_kernel<256, 8, 1, 10><<<grid, dim3(512), attn_smem<256>(ntot), s>>>(p);
+    else if (n0 <= 16) attention_kernel<256, 8, 2, 8><<<grid, dim3(512), attn_smem<256>(ntot), s>>>(p);
+    else attention_kernel<256, 8, 4, 8><<<grid, dim3(512), attn_smem<256>(ntot), s>>>(p);
   } else if (p.head_dim <= 80 && p.head_dim > 64) {
-    attention_kernel<80, 3><<<grid, dim3(512), attn_smem<80>(ntot), s>>>(p);
+    if (n0 > 8 || p.chunks1 != 0) return hipErrorInvalidValue;
+    attention_kernel<80, 3, 1, 8><<<grid, dim3(512), attn_smem<80>(ntot), s>>>(p);
   } else {
     return hipErrorInvalidValue;
   }

@@ -188,7 +188,6 @@ __global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(1, 1)))
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16* xs = reinterpret_cast<bf16*>(smem_raw);                                        // [2][NFR][64][8]
-  float* stat = reinterpret_cast<float*>(smem_raw + (size_t)2 * NFR * 1024);           // [2][WN][ROWS]
 
   const int t = threadIdx.x;
   const int lane = t & 63;
@@ -221,12 +220,9 @@ __global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(1, 1)))
   // the last re-read the last chunk (never computed).
   bf16x8 xr[D][NP];
   bf16x8 wr[D][4];
-  float s1[NP], s2[NP];
   const bf16* xfrag[NP];
 #pragma unroll
   for (int i = 0; i < NP; i++) {
-    s1[i] = 0.f;
-    s2[i] = 0.f;
     const int f = wn + WN * i;
     const int mbg = min((m0 >> 5) + (f >> 2), mb_last);
     xfrag[i] = p.X + ((size_t)mbg * XKC16 + (kbeg >> 4) + (f & 3)) * 512 + lane * 8;
@@ -241,21 +237,10 @@ __global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(1, 1)))
     _Pragma("unroll") for (int s_ = 0; s_ < 4; s_++)                                                  \
       wr[u][s_] = *reinterpret_cast<const bf16x8*>(wbase + (size_t)(cc_ * 4 + s_) * 512);             \
   }
-#define STORE_STAGE(u, buf, live)                                                                     \
+#define STORE_STAGE(u, buf)                                                                           \
   {                                                                                                   \
-    _Pragma("unroll") for (int i = 0; i < NP; i++) {                                                  \
+    _Pragma("unroll") for (int i = 0; i < NP; i++)                                                    \
       *reinterpret_cast<bf16x8*>(xs + (((size_t)(buf) * NFR + wn + WN * i) * 64 + lane) * 8) = xr[u][i]; \
-      if (PRO != PRO_NONE) {                                                                          \
-        float a_ = 0.f, b_ = 0.f;                                                                     \
-        _Pragma("unroll") for (int j = 0; j < 8; j++) {                                               \
-          const float v_ = (float)xr[u][i][j];                                                        \
-          a_ += v_;                                                                                   \
-          b_ += v_ * v_;                                                                              \
-        }                                                                                             \
-        s1[i] += (live) ? a_ : 0.f;                                                                   \
-        s2[i] += (live) ? b_ : 0.f;                                                                   \
-      }                                                                                               \
-    }                                                                                                 \
   }
 
   f32x16 acc[MB];
@@ -266,7 +251,7 @@ __global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(1, 1)))
 
 #pragma unroll
   for (int u = 0; u < D; u++) ISSUE_STAGE(u, u)
-  STORE_STAGE(0, 0, true)
+  STORE_STAGE(0, 0)
   __syncthreads();
 
   const int lq = lane & 31;
@@ -300,7 +285,7 @@ __global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(1, 1)))
       const int c = c0 + u;
       COMPUTE_CHUNK(u)
       ISSUE_STAGE(c + D, u)
-      STORE_STAGE((u + 1) % D, cur ^ 1, c + 1 < NC)
+      STORE_STAGE((u + 1) % D, cur ^ 1)
       // ---- requested instruction order (masks: 0x008 MFMA, 0x100 LDS read, 0x200 LDS write, 0x020 VMEM read)
       __builtin_amdgcn_sched_group_barrier(0x100, MB, 0);
 #pragma unroll
@@ -335,7 +320,7 @@ __global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(1, 1)))
     const int c = c0 + u;
     if (c < NC) {
       COMPUTE_CHUNK(u)
-      STORE_STAGE((u + 1) % D, cur ^ 1, c + 1 < NC)
+      STORE_STAGE((u + 1) % D, cur ^ 1)
       __syncthreads();
       cur ^= 1;
     }
@@ -344,21 +329,6 @@ __global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(1, 1)))
 #undef ISSUE_STAGE
 #undef STORE_STAGE
 
-  // ---- row statistics: a row's pieces sit in both lane halves of all WN waves ----------------
-  if (PRO != PRO_NONE) {
-#pragma unroll
-    for (int i = 0; i < NP; i++) {
-      const float a = s1[i] + __shfl_xor(s1[i], 32, 64);
-      const float b = s2[i] + __shfl_xor(s2[i], 32, 64);
-      const int f = wn + WN * i;
-      // fragment f covers k16 step (f & 3) of token block (f >> 2): partial sums per (step, row)
-      if (lh == 0) {
-        stat[((f & 3) * 2 + 0) * ROWS + (f >> 2) * 32 + lq] = a;
-        stat[((f & 3) * 2 + 1) * ROWS + (f >> 2) * 32 + lq] = b;
-      }
-    }
-    __syncthreads();
-  }
   if (!wave_active) return;
 
   // ---- epilogue --------------------------------------------------------------------------------
@@ -368,12 +338,9 @@ __global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(1, 1)))
     const int m = m0 + ml;
     if (m < p.M) {
       float ssum = 0.f, ssq = 0.f;
-      if (PRO != PRO_NONE) {
-#pragma unroll
-        for (int q = 0; q < 4; q++) {
-          ssum += stat[(q * 2 + 0) * ROWS + ml];
-          ssq += stat[(q * 2 + 1) * ROWS + ml];
-        }
+      if (PRO != PRO_NONE) {   // row statistics come from the kernel that produced the residual stream
+        ssum = p.rowstat[2 * m];
+        ssq = p.rowstat[2 * m + 1];
       }
       epilogue_tile<PRO, EPI>(p, acc[mb], nt, m, lh, ssum, ssq, blockIdx.y);
     }
@@ -396,7 +363,6 @@ template <int PRO, int EPI>
 __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   float* red = reinterpret_cast<float*>(smem_raw);                 // [8 waves][2][16][64]
-  float* stat = red + SK_WAVES * 2 * 16 * 64;                      // [8 waves][2 (sum, sq)][64 rows]
   const int t = threadIdx.x;
   const int lane = t & 63;
   const int w = t >> 6;
@@ -426,44 +392,17 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
   for (int mb = 0; mb < 2; mb++)
 #pragma unroll
     for (int r = 0; r < 16; r++) acc[mb][r] = 0.f;
-  float sa[2] = {0.f, 0.f}, sb[2] = {0.f, 0.f};
 #pragma unroll
   for (int i = 0; i < 8; i++) {
-    const bool live = w * 8 + i < n16;
-    if (live) {
+    if (w * 8 + i < n16) {
 #pragma unroll
       for (int mb = 0; mb < 2; mb++) acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[mb][i], acc[mb], 0, 0, 0);
-    }
-    if (PRO != PRO_NONE) {
-#pragma unroll
-      for (int mb = 0; mb < 2; mb++) {
-        float a = 0.f, b = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; e++) {
-          const float v = (float)xf[mb][i][e];
-          a += v;
-          b += v * v;
-        }
-        sa[mb] += live ? a : 0.f;
-        sb[mb] += live ? b : 0.f;
-      }
     }
   }
 #pragma unroll
   for (int mb = 0; mb < 2; mb++)
 #pragma unroll
     for (int r = 0; r < 16; r++) red[(((size_t)w * 2 + mb) * 16 + r) * 64 + lane] = acc[mb][r];
-  if (PRO != PRO_NONE) {
-#pragma unroll
-    for (int mb = 0; mb < 2; mb++) {
-      const float a = sa[mb] + __shfl_xor(sa[mb], 32, 64);
-      const float b = sb[mb] + __shfl_xor(sb[mb], 32, 64);
-      if (lh == 0) {
-        stat[(w * 2 + 0) * 64 + mb * 32 + lq] = a;
-        stat[(w * 2 + 1) * 64 + mb * 32 + lq] = b;
-      }
-    }
-  }
   __syncthreads();
   if (w >= 2) return;
   const int mb = w;
@@ -478,22 +417,19 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
   if (ml < p.M) {
     float ssum = 0.f, ssq = 0.f;
     if (PRO != PRO_NONE) {
-#pragma unroll
-      for (int ww = 0; ww < SK_WAVES; ww++) {
-        ssum += stat[(ww * 2 + 0) * 64 + ml];
-        ssq += stat[(ww * 2 + 1) * 64 + ml];
-      }
+      ssum = p.rowstat[2 * ml];
+      ssq = p.rowstat[2 * ml + 1];
     }
     epilogue_tile<PRO, EPI>(p, sum, nt, ml, lh, ssum, ssq, blockIdx.y);
   }
 }
 
-static constexpr int skinny_smem_bytes() { return (SK_WAVES * 2 * 16 * 64 + SK_WAVES * 2 * 64) * 4; }
+static constexpr int skinny_smem_bytes() { return SK_WAVES * 2 * 16 * 64 * 4; }
 
 // ------------------------------------------------------------------------------------------------
 template <int MB>
 static constexpr int smem_bytes_for() {
-  return 2 * (MB * 4) * 1024 + 8 * (MB * 32) * 4;
+  return 2 * (MB * 4) * 1024;
 }
 
 int gemm_rows_per_tile(int tile) {
@@ -566,7 +502,7 @@ hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmPara
   if (p.W.k_pad % 64 != 0 || p.W.n_pad % 32 != 0 || p.n_tiles * 32 != p.W.n_pad) return hipErrorInvalidValue;
   if (p.ldx < p.W.k_pad || p.ldx % 16 != 0) return hipErrorInvalidValue;   // X is in XF layout with ldx padded columns
   if (p.k_per_split % 64 != 0 || (long)p.k_per_split * z_splits < p.W.k_pad) return hipErrorInvalidValue;
-  if (pro != PRO_NONE && z_splits != 1) return hipErrorInvalidValue;
+  if (pro != PRO_NONE && (z_splits != 1 || p.rowstat == nullptr)) return hipErrorInvalidValue;
   if (epi != EPI_PARTIAL && z_splits != 1) return hipErrorInvalidValue;
   if (p.m_tiles < 1) return hipErrorInvalidValue;
   if (tile == TILE_SKINNY) {
@@ -593,27 +529,87 @@ hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmPara
 // ------------------------------------------------------------------------------------------------
 // split-K reduction (fixed summation order -> run-to-run bitwise determinism)
 // ------------------------------------------------------------------------------------------------
+// One block per output row.  Besides the sum it writes the bf16 shadow of the row in XF layout
+// and the row's (sum, sum of squares) over those bf16 values: the statistics that the next
+// LayerNorm / RMSNorm-folded GEMM applies after accumulation (Section 4.4).
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(ReduceParams p) {
-  const int n4s = p.N >> 2;
-  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= (size_t)p.M * n4s) return;
-  const int m = (int)(idx / n4s);
-  const int n = (int)(idx % n4s) * 4;
-  f32x4 a = {0.f, 0.f, 0.f, 0.f};
-  for (int z = 0; z < p.Z; z++) {
-    const f32x4 v = *reinterpret_cast<const f32x4*>(p.part + ((size_t)z * p.M + m) * p.ldp + n);
-    a += v;
+  __shared__ float sred[2][4];
+  const int m = blockIdx.x;
+  const int ro = m;
+  float sa = 0.f, sb = 0.f;
+  for (int n = threadIdx.x * 4; n < p.N; n += 1024) {
+    f32x4 a = {0.f, 0.f, 0.f, 0.f};
+    for (int z = 0; z < p.Z; z++) a += *reinterpret_cast<const f32x4*>(p.part + ((size_t)z * p.M + m) * p.ldp + n);
+    if (p.bias != nullptr) a += *reinterpret_cast<const f32x4*>(p.bias + n);
+    if (p.resid != nullptr) {
+      const int rr = p.resid_mod > 0 ? (m % p.resid_mod) : m;
+      a += *reinterpret_cast<const f32x4*>(p.resid + (size_t)rr * p.ldo + n);
+    }
+    *reinterpret_cast<f32x4*>(p.out_f32 + (size_t)ro * p.ldo + n) = a;
+    const bf16x4 ob = {(bf16)a[0], (bf16)a[1], (bf16)a[2], (bf16)a[3]};
+    *reinterpret_cast<bf16x4*>(p.out_bf16 + xf_index(ro, n, p.ldo2 >> 4)) = ob;
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+      const float v = (float)ob[j];
+      sa += v;
+      sb += v * v;
+    }
   }
-  if (p.bias != nullptr) a += *reinterpret_cast<const f32x4*>(p.bias + n);
-  if (p.resid != nullptr) a += *reinterpret_cast<const f32x4*>(p.resid + (size_t)m * p.ldo + n);
-  *reinterpret_cast<f32x4*>(p.out_f32 + (size_t)m * p.ldo + n) = a;
-  const bf16x4 ob = {(bf16)a[0], (bf16)a[1], (bf16)a[2], (bf16)a[3]};
-  *reinterpret_cast<bf16x4*>(p.out_bf16 + xf_index(m, n, p.ldo2 >> 4)) = ob;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    sa += __shfl_xor(sa, off, 64);
+    sb += __shfl_xor(sb, off, 64);
+  }
+  if ((threadIdx.x & 63) == 0) {
+    sred[0][threadIdx.x >> 6] = sa;
+    sred[1][threadIdx.x >> 6] = sb;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0 && p.stat_out != nullptr) {
+    p.stat_out[2 * ro] = sred[0][0] + sred[0][1] + sred[0][2] + sred[0][3];
+    p.stat_out[2 * ro + 1] = sred[1][0] + sred[1][1] + sred[1][2] + sred[1][3];
+  }
 }
 
 hipError_t launch_splitk_reduce(hipStream_t s, const ReduceParams& p) {
   if (p.N % 4 != 0 || p.ldp < p.N || p.ldo < p.N || p.ldo2 < p.N || p.ldo2 % 16 != 0 || p.M <= 0 || p.Z < 1) return hipErrorInvalidValue;
-  const size_t total = (size_t)p.M * (p.N / 4);
-  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, p);
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)p.M), dim3(256), 0, s, p);
+  return hipGetLastError();
+}
+
+// (sum, sum of squares) of every row of an XF matrix: for residual rows that were not produced by
+// the reduction kernel (projector output, prompt embeddings, first suffix tokens of a step).
+__global__ __launch_bounds__(256) void row_stats_kernel(const bf16* xf, int K, int kc16, float* stat_out) {
+  __shared__ float sred[2][4];
+  const int m = blockIdx.x;
+  float sa = 0.f, sb = 0.f;
+  for (int k = threadIdx.x * 8; k < K; k += 2048) {
+    const bf16x8 v = *reinterpret_cast<const bf16x8*>(xf + xf_index(m, k, kc16));
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+      const float f = (float)v[j];
+      sa += f;
+      sb += f * f;
+    }
+  }
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    sa += __shfl_xor(sa, off, 64);
+    sb += __shfl_xor(sb, off, 64);
+  }
+  if ((threadIdx.x & 63) == 0) {
+    sred[0][threadIdx.x >> 6] = sa;
+    sred[1][threadIdx.x >> 6] = sb;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    stat_out[2 * m] = sred[0][0] + sred[0][1] + sred[0][2] + sred[0][3];
+    stat_out[2 * m + 1] = sred[1][0] + sred[1][1] + sred[1][2] + sred[1][3];
+  }
+}
+
+hipError_t launch_row_stats(hipStream_t s, const bf16* xf, int M, int K, int k_pad, float* stat_out) {
+  if (xf == nullptr || stat_out == nullptr || M <= 0 || K % 8 != 0 || k_pad % 16 != 0 || K > k_pad) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(row_stats_kernel, dim3((unsigned)M), dim3(256), 0, s, xf, K, k_pad >> 4, stat_out);
   return hipGetLastError();
 }

@@ -148,6 +148,7 @@ struct WsLayout {
   size_t xpatch, vh, vh_b, vq, vk, vv, vattn, vmid, part;
   size_t lx, lx_b, lq, kcache, vcache, lattn, lmid;
   size_t stok, z, y, y_b, eq, ek, ev, eattn, emid;
+  size_t vstat, lstat, estat;
   size_t total;
   size_t kcache_layer, vcache_layer;   // bytes per layer
   int zmax;
@@ -254,6 +255,9 @@ void ws_layout(const pi0_config& c, const Dims& d, WsLayout& w) {
   w.ev = cur.take((size_t)2 * 8 * 1024 * 2);
   w.eattn = cur.take((size_t)64 * d.H * 256 * 2);
   w.emid = cur.take((size_t)64 * d.Fx * 2);
+  w.vstat = cur.take((size_t)d.maxI * 2 * 4);
+  w.lstat = cur.take((size_t)d.maxPc * 32 * 2 * 4);
+  w.estat = cur.take((size_t)64 * 2 * 4);
   w.total = cur.off;
 }
 
@@ -346,7 +350,8 @@ GemmParams gp_base(pi0_ctx* c, const PW& pw, const bf16* X, int ldx, int M, int 
 
 // split-K GEMM into the partial buffer followed by the fixed-order reduction with bias/residual
 void gemm_splitk_resid(Run& r, const PW& pw, const bf16* X, int ldx, int M, int k_true, int z, int k_per_split,
-                       const float* bias, float* resid_io, bf16* shadow, int n_true, int tile) {
+                       const float* bias, float* resid_io, bf16* shadow, int n_true, int tile, float* stat_out,
+                       const float* resid_in = nullptr, int resid_mod = 0, bool no_resid = false) {
   pi0_ctx* c = r.c;
   if (z > Z_MAX) z = Z_MAX;
   if ((long)k_per_split * z < pw.k_pad) k_per_split = round_up(ceil_div(pw.k_pad, z), 64);
@@ -359,7 +364,9 @@ void gemm_splitk_resid(Run& r, const PW& pw, const bf16* X, int ldx, int M, int 
   q.part = p.out_f32;
   q.Z = z; q.M = M; q.N = n_true; q.ldp = pw.n_pad;
   q.bias = bias;
-  q.resid = resid_io;
+  q.resid = no_resid ? nullptr : (resid_in ? resid_in : resid_io);
+  q.resid_mod = resid_mod;
+  q.stat_out = stat_out;
   q.out_f32 = resid_io;
   q.out_bf16 = shadow;
   q.ldo = n_true; q.ldo2 = n_true;
@@ -384,16 +391,8 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
   const int I = n_views * d.T, P = I + n_prompt;
   // A0: patches -> tokens (+bias, +position embedding)
   RUN(r, launch_patchify(r.s, at<float>(c, w.st_images), n_views, c->cfg.img_size, c->cfg.patch, at<bf16>(c, w.xpatch), d.PDp));
-  {
-    GemmParams p = gp_base(c, w.patch, at<bf16>(c, w.xpatch), d.PDp, I, T.vis, d.PD);
-    p.bias = at<float>(c, w.patch.bias);
-    p.resid = at<float>(c, w.pos);
-    p.resid_mod = d.T;
-    p.out_f32 = at<float>(c, w.vh);
-    p.out_bf16 = at<bf16>(c, w.vh_b);
-    p.ldo = d.Dv; p.ldo2 = d.Dv; p.n_valid = d.Dv;
-    RUN_GEMM(r, T.vis, PRO_NONE, EPI_RESID, p, 1);
-  }
+  gemm_splitk_resid(r, w.patch, at<bf16>(c, w.xpatch), d.PDp, I, d.PD, 1, w.patch.k_pad, at<float>(c, w.patch.bias),
+                    at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv, T.vis, at<float>(c, w.vstat), at<float>(c, w.pos), d.T);
   const int vchunks = I / 32;
   for (int l = 0; l < d.Lv; l++) {
     const WsVis& L = w.vis[l];
@@ -401,6 +400,7 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
       GemmParams p = gp_base(c, L.qkv, at<bf16>(c, w.vh_b), d.Dv, I, T.vis, d.Dv);
       p.bias = at<float>(c, L.qkv.bias);
       p.colsum = at<float>(c, L.qkv.colsum);
+      p.rowstat = at<float>(c, w.vstat);
       p.out_bf16 = at<bf16>(c, w.vq);
       p.q_mbs = vchunks;
       p.kfrag = at<bf16>(c, w.vk);
@@ -425,24 +425,26 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
     }
     // A3: O-projection + bias + residual
     gemm_splitk_resid(r, L.o, at<bf16>(c, w.vattn), d.Dv, I, d.Dv, T.zvo, round_up(ceil_div(L.o.k_pad, T.zvo), 64),
-                      at<float>(c, L.o.bias), at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv, T.part);
+                      at<float>(c, L.o.bias), at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv, T.part, at<float>(c, w.vstat));
     {  // A4: LN -> up (+bias, GELU)
       GemmParams p = gp_base(c, L.up, at<bf16>(c, w.vh_b), d.Dv, I, T.vis, d.Dv);
       p.bias = at<float>(c, L.up.bias);
       p.colsum = at<float>(c, L.up.colsum);
+      p.rowstat = at<float>(c, w.vstat);
       p.out_bf16 = at<bf16>(c, w.vmid);
       p.ldo = d.Fv_kp; p.n_valid = L.up.n_pad; p.act = ACT_GELU;
       RUN_GEMM(r, T.vis, PRO_LN, EPI_BF16, p, 1);
     }
     // A5: down (+bias, residual)
     gemm_splitk_resid(r, L.down, at<bf16>(c, w.vmid), d.Fv_kp, I, d.Fv, T.zvd, round_up(ceil_div(L.down.k_pad, T.zvd), 64),
-                      at<float>(c, L.down.bias), at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv, T.part);
+                      at<float>(c, L.down.bias), at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv, T.part, at<float>(c, w.vstat));
     if (taps) taps->put(r, at<float>(c, w.vh), (size_t)I * d.Dv);
   }
   {  // A6: final LN -> projector (+bias) = prefix image embeddings
     GemmParams p = gp_base(c, w.proj, at<bf16>(c, w.vh_b), d.Dv, I, T.vis, d.Dv);
     p.bias = at<float>(c, w.proj.bias);
     p.colsum = at<float>(c, w.proj.colsum);
+    p.rowstat = at<float>(c, w.vstat);
     p.out_f32 = at<float>(c, w.lx);
     p.out_bf16 = at<bf16>(c, w.lx_b);
     p.ldo = d.E; p.ldo2 = d.E; p.n_valid = d.E;
@@ -453,6 +455,7 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
     RUN(r, launch_embed_prompt(r.s, at<int32_t>(c, w.st_ids), n_prompt, at<bf16>(c, w.embed), c->cfg.vocab, d.E,
                                sqrtf((float)d.E), at<float>(c, w.lx), at<bf16>(c, w.lx_b), I));
   }
+  RUN(r, launch_row_stats(r.s, at<bf16>(c, w.lx_b), P, d.E, d.E, at<float>(c, w.lstat)));
   const int pchunks = ceil_div(P, 32);
   for (int l = 0; l < d.Ll; l++) {
     const WsTr& L = w.llm[l];
@@ -461,6 +464,7 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
     bf16* vc = reinterpret_cast<bf16*>(c->ws + w.vcache + (size_t)l * w.vcache_layer);
     {  // B1: RMS -> QKV, RoPE, keys/values into the cache (last layer: keys/values only)
       GemmParams p = gp_base(c, L.qkv, at<bf16>(c, w.lx_b), d.E, P, T.lqkv, d.E);
+      p.rowstat = at<float>(c, w.lstat);
       p.out_bf16 = at<bf16>(c, w.lq);
       p.q_mbs = pchunks;
       p.kfrag = kc; p.vfrag = vc;
@@ -483,9 +487,10 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
     }
     // B3: O-projection + residual
     gemm_splitk_resid(r, L.o, at<bf16>(c, w.lattn), d.H * 256, P, d.H * 256, T.zlo,
-                      round_up(ceil_div(L.o.k_pad, T.zlo), 64), nullptr, at<float>(c, w.lx), at<bf16>(c, w.lx_b), d.E, T.part);
+                      round_up(ceil_div(L.o.k_pad, T.zlo), 64), nullptr, at<float>(c, w.lx), at<bf16>(c, w.lx_b), d.E, T.part, at<float>(c, w.lstat));
     {  // B4: RMS -> gate||up with fused GELU gate
       GemmParams p = gp_base(c, L.gu, at<bf16>(c, w.lx_b), d.E, P, T.lgu, d.E);
+      p.rowstat = at<float>(c, w.lstat);
       p.out_bf16 = at<bf16>(c, w.lmid);
       p.ldo = d.F;
       RUN_GEMM(r, T.lgu, PRO_RMS, EPI_GEGLU, p, 1);
@@ -493,7 +498,7 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
     // B5: down + residual
     gemm_splitk_resid(r, L.down, at<bf16>(c, w.lmid), d.F, P, d.F, T.zld,
                       round_up(ceil_div(L.down.k_pad, T.zld), 64), nullptr, at<float>(c, w.lx), at<bf16>(c, w.lx_b),
-                      d.E, T.part);
+                      d.E, T.part, at<float>(c, w.lstat));
     if (taps) taps->put(r, at<float>(c, w.lx), (size_t)P * d.E);
   }
   if (taps && taps->base) {
@@ -533,6 +538,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
       p.ldo = d.X; p.ldo2 = d.X; p.n_valid = d.X; p.row_offset = 1;
       RUN_GEMM(r, TILE_SKINNY, PRO_NONE, EPI_RESID, p, 1);
     }
+    RUN(r, launch_row_stats(r.s, at<bf16>(c, w.y_b), 64, d.X, d.X, at<float>(c, w.estat)));
     const bool tap_this = taps && (k == 0 || k == d.steps - 1);
     for (int l = 0; l < d.Le; l++) {
       const WsTr& L = w.exp[l];
@@ -540,6 +546,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
       bf16* vc = reinterpret_cast<bf16*>(c->ws + w.vcache + (size_t)l * w.vcache_layer);
       {  // C3: RMS -> QKV, RoPE at positions P..P+63
         GemmParams p = gp_base(c, L.qkv, at<bf16>(c, w.y_b), d.X, 64, TILE_SKINNY, d.X);
+        p.rowstat = at<float>(c, w.estat);
         p.out_bf16 = at<bf16>(c, w.eq);
         p.q_mbs = 2;
         p.kfrag = at<bf16>(c, w.ek); p.vfrag = at<bf16>(c, w.ev);
@@ -563,16 +570,17 @@ void run_denoise(Run& r, int P, Taps* taps) {
       }
       // C6: O-projection + residual (k split over blocks, fixed-order reduction)
       gemm_splitk_resid(r, L.o, at<bf16>(c, w.eattn), d.H * 256, 64, d.H * 256, ceil_div(L.o.k_pad, 1024), 1024, nullptr,
-                        at<float>(c, w.y), at<bf16>(c, w.y_b), d.X, TILE_SKINNY);
+                        at<float>(c, w.y), at<bf16>(c, w.y_b), d.X, TILE_SKINNY, at<float>(c, w.estat));
       {  // C7: RMS -> gate||up, fused gate
         GemmParams p = gp_base(c, L.gu, at<bf16>(c, w.y_b), d.X, 64, TILE_SKINNY, d.X);
+        p.rowstat = at<float>(c, w.estat);
         p.out_bf16 = at<bf16>(c, w.emid);
         p.ldo = d.Fx;
         RUN_GEMM(r, TILE_SKINNY, PRO_RMS, EPI_GEGLU, p, 1);
       }
       // C8: down + residual
       gemm_splitk_resid(r, L.down, at<bf16>(c, w.emid), d.Fx, 64, d.Fx, ceil_div(L.down.k_pad, 1024), 1024, nullptr,
-                        at<float>(c, w.y), at<bf16>(c, w.y_b), d.X, TILE_SKINNY);
+                        at<float>(c, w.y), at<bf16>(c, w.y_b), d.X, TILE_SKINNY, at<float>(c, w.estat));
       if (tap_this) {
         // step 0 taps first, last-step taps after them
         const size_t slot = (k == 0 ? 0 : (size_t)d.Le) + l;
@@ -582,6 +590,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
     }
     {  // C9: final RMS -> out-projection (+bias), Euler update x <- x + dt * v
       GemmParams p = gp_base(c, w.outp, at<bf16>(c, w.y_b), d.X, 64, TILE_SKINNY, d.X);
+      p.rowstat = at<float>(c, w.estat);
       p.bias = at<float>(c, w.outp.bias);
       p.out_f32 = xa;
       p.ldo = d.A; p.n_valid = d.A; p.dt = dt;

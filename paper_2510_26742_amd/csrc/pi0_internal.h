@@ -74,6 +74,7 @@ struct GemmParams {
   // statistics / affine
   const float* bias;    // [n_pad] or null
   const float* colsum;  // [n_pad], PRO_LN only: sum_k W'[n][k]
+  const float* rowstat; // [rows][2] (sum, sum of squares) of the bf16 activations, PRO_RMS / PRO_LN
   // outputs
   float* out_f32;     // EPI_RESID / EPI_PARTIAL / EPI_EULER
   bf16* out_bf16;     // EPI_RESID shadow (XF), EPI_BF16 (XF), EPI_GEGLU (XF), EPI_QKV q (fragment order per head)
@@ -112,17 +113,21 @@ hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmPara
 int gemm_rows_per_tile(int tile);
 hipError_t gemm_init_attributes();
 
-// Split-K reduction: out[m][n] = sum_z part[z][m][n] (+bias[n]) (+resid[m][n]); bf16 shadow.
+// Split-K reduction: out[m][n] = sum_z part[z][m][n] (+bias[n]) (+resid[m % resid_mod][n]); bf16 shadow in XF
+// layout; (sum, sum sq) of each output row.
 struct ReduceParams {
   const float* part;  // [Z][M][ldp]
   int Z, M, N, ldp;
   const float* bias;
   const float* resid;
+  int resid_mod;      // row index of resid taken modulo this (0 = no modulo)
+  float* stat_out;    // [rows][2] or null
   float* out_f32;
   bf16* out_bf16;     // XF layout with ldo2 padded columns
   int ldo, ldo2;
 };
 hipError_t launch_splitk_reduce(hipStream_t s, const ReduceParams& p);
+hipError_t launch_row_stats(hipStream_t s, const bf16* xf, int M, int K, int k_pad, float* stat_out);
 
 // ------------------------------------------------------------------------------------------
 // Attention over fragment-ordered keys / values.
