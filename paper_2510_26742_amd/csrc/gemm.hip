@@ -54,6 +54,7 @@ __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16&
   const float inv_k = 1.0f / (float)p.k_true;
   {
     float rs = 1.f, mu = 0.f;
+    float st_a = 0.f, st_b = 0.f;   // EPI_RESID: sum / sum of squares of this lane's bf16 outputs
     if (PRO == PRO_RMS) {
       rs = rsqrtf(s_sq * inv_k + 1e-6f);
     } else if (PRO == PRO_LN) {
@@ -98,6 +99,12 @@ __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16&
           *reinterpret_cast<f32x4*>(p.out_f32 + (size_t)mo * p.ldo + n4) = o;
           bf16x4 ob = {(bf16)v[0], (bf16)v[1], (bf16)v[2], (bf16)v[3]};
           *reinterpret_cast<bf16x4*>(p.out_bf16 + xf_index(mo, n4, p.ldo2 >> 4)) = ob;
+#pragma unroll
+          for (int j = 0; j < 4; j++) {
+            const float q = (float)ob[j];
+            st_a += q;
+            st_b += q * q;
+          }
         }
       } else if (EPI == EPI_BF16) {
         if (n4 < p.n_valid) {
@@ -166,6 +173,16 @@ __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16&
             }
           }
         }
+      }
+    }
+    if (EPI == EPI_RESID && p.stat_out != nullptr) {
+      // partial row statistics over this tile's 32 columns: [n tile][64 rows][2]
+      st_a += __shfl_xor(st_a, 32, 64);
+      st_b += __shfl_xor(st_b, 32, 64);
+      if (lh == 0) {
+        float* dst = p.stat_out + ((size_t)nt * 64 + m + p.row_offset) * 2;
+        dst[0] = st_a;
+        dst[1] = st_b;
       }
     }
   }
@@ -376,6 +393,17 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
   const int KC16 = k_pad >> 4;
   const int XKC16 = p.ldx >> 4;
 
+  // row statistics of the input: parts partial sums per row (1, or one per 32-column tile of the
+  // producer); wave w adds parts w, w+8, ... for row `lane`, the epilogue adds the 8 wave sums
+  float* sstat = red + SK_WAVES * 2 * 16 * 64;     // [64 rows][2] after the reduction below
+  float* sstat8 = sstat + 128;                     // [8 waves][64][2]
+  float pa = 0.f, pb = 0.f;
+  if (PRO != PRO_NONE) {
+    for (int j = w; j < p.rowstat_parts; j += SK_WAVES) {
+      pa += p.rowstat[((size_t)j * 64 + lane) * 2];
+      pb += p.rowstat[((size_t)j * 64 + lane) * 2 + 1];
+    }
+  }
   bf16x8 wf[8], xf[2][8];
   const bf16* wbase = p.W.w + ((size_t)nt * KC16 + (kbeg >> 4)) * 512 + lane * 8;
   const bf16* xbase = p.X + (size_t)(kbeg >> 4) * 512 + lane * 8;
@@ -403,8 +431,23 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
   for (int mb = 0; mb < 2; mb++)
 #pragma unroll
     for (int r = 0; r < 16; r++) red[(((size_t)w * 2 + mb) * 16 + r) * 64 + lane] = acc[mb][r];
+  if (PRO != PRO_NONE) {
+    sstat8[(w * 64 + lane) * 2] = pa;
+    sstat8[(w * 64 + lane) * 2 + 1] = pb;
+  }
   __syncthreads();
   if (w >= 2) return;
+  if (PRO != PRO_NONE) {   // waves 0 and 1 each finish the statistics of the 32 rows they own (lanes 0..31 suffice)
+    const int r = w * 32 + lq;
+    float a = 0.f, b = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < SK_WAVES; ww++) {
+      a += sstat8[(ww * 64 + r) * 2];
+      b += sstat8[(ww * 64 + r) * 2 + 1];
+    }
+    sstat[r * 2] = a;       // both lane halves write the same value
+    sstat[r * 2 + 1] = b;
+  }
   const int mb = w;
   f32x16 sum;
 #pragma unroll
@@ -417,14 +460,63 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
   if (ml < p.M) {
     float ssum = 0.f, ssq = 0.f;
     if (PRO != PRO_NONE) {
-      ssum = p.rowstat[2 * ml];
-      ssq = p.rowstat[2 * ml + 1];
+      ssum = sstat[ml * 2];
+      ssq = sstat[ml * 2 + 1];
     }
     epilogue_tile<PRO, EPI>(p, sum, nt, ml, lh, ssum, ssq, blockIdx.y);
   }
 }
 
-static constexpr int skinny_smem_bytes() { return SK_WAVES * 2 * 16 * 64 * 4; }
+// Skinny GEMM over the whole k range with the residual epilogue (the expert's O and down
+// projections, k = 2048 / 4096): one block per (32-feature tile, 32-token block), 8 waves each
+// owning 1/8 of k in NB batches of 16 k16 steps.  No split across blocks, so the residual add, the
+// bf16 shadow and the per-tile row statistics are done here and no reduction kernel follows.
+template <int NB>
+__global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_fullk_kernel(GemmParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  float* red = reinterpret_cast<float*>(smem_raw);                 // [8 waves][16][64]
+  const int t = threadIdx.x;
+  const int lane = t & 63;
+  const int w = t >> 6;
+  const int lq = lane & 31;
+  const int lh = lane >> 5;
+  const int nt = blockIdx.x;
+  const int mb = blockIdx.y;
+  const int KC16 = p.W.k_pad >> 4;
+  const int XKC16 = p.ldx >> 4;
+  const int spw = 16 * NB;                     // steps per wave; host guarantees KC16 == 8 * spw
+  const bf16* wbase = p.W.w + ((size_t)nt * KC16 + (size_t)w * spw) * 512 + lane * 8;
+  const bf16* xbase = p.X + ((size_t)mb * XKC16 + (size_t)w * spw) * 512 + lane * 8;
+  f32x16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; r++) acc[r] = 0.f;
+#pragma unroll
+  for (int b = 0; b < NB; b++) {
+    bf16x8 wf[16], xf[16];
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+      wf[i] = *reinterpret_cast<const bf16x8*>(wbase + (size_t)(b * 16 + i) * 512);
+      xf[i] = *reinterpret_cast<const bf16x8*>(xbase + (size_t)(b * 16 + i) * 512);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; i++) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[i], acc, 0, 0, 0);
+  }
+#pragma unroll
+  for (int r = 0; r < 16; r++) red[((size_t)w * 16 + r) * 64 + lane] = acc[r];
+  __syncthreads();
+  if (w != 0) return;
+  f32x16 sum;
+#pragma unroll
+  for (int r = 0; r < 16; r++) sum[r] = 0.f;
+#pragma unroll
+  for (int ww = 0; ww < SK_WAVES; ww++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) sum[r] += red[((size_t)ww * 16 + r) * 64 + lane];
+  const int m = mb * 32 + lq;
+  if (m < p.M) epilogue_tile<PRO_NONE, EPI_RESID>(p, sum, nt, m, lh, 0.f, 0.f, 0);
+}
+
+static constexpr int skinny_smem_bytes() { return (SK_WAVES * 2 * 16 * 64 + 128 + SK_WAVES * 128) * 4; }
 
 // ------------------------------------------------------------------------------------------------
 template <int MB>
@@ -437,6 +529,7 @@ int gemm_rows_per_tile(int tile) {
     case TILE_BIG: return 256;
     case TILE_MID: return 64;
     case TILE_SKINNY: return 64;
+    case TILE_SKINNY_FULLK: return 64;
     default: return -1;
   }
 }
@@ -505,7 +598,16 @@ hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmPara
   if (pro != PRO_NONE && (z_splits != 1 || p.rowstat == nullptr)) return hipErrorInvalidValue;
   if (epi != EPI_PARTIAL && z_splits != 1) return hipErrorInvalidValue;
   if (p.m_tiles < 1) return hipErrorInvalidValue;
+  if (tile == TILE_SKINNY_FULLK) {
+    const int kc16 = p.W.k_pad >> 4;
+    if (p.M > 64 || pro != PRO_NONE || epi != EPI_RESID || z_splits != 1 || (kc16 != 128 && kc16 != 256)) return hipErrorInvalidValue;
+    const dim3 grid(p.n_tiles, (p.M + 31) / 32);
+    if (kc16 == 128) gemm_skinny_fullk_kernel<1><<<grid, dim3(64 * SK_WAVES), SK_WAVES * 16 * 64 * 4, s>>>(p);
+    else gemm_skinny_fullk_kernel<2><<<grid, dim3(64 * SK_WAVES), SK_WAVES * 16 * 64 * 4, s>>>(p);
+    return hipGetLastError();
+  }
   if (tile == TILE_SKINNY) {
+    if (pro != PRO_NONE && p.rowstat_parts < 1) return hipErrorInvalidValue;
     if (p.M > 64 || p.m_tiles != 1 || p.k_per_split > SK_KMAX || p.k_per_split % 16 != 0) return hipErrorInvalidValue;
 #define X(PRO, EPI)                                                                                          \
   if (pro == PRO && epi == EPI) {                                                                            \

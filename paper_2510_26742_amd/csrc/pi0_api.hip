@@ -148,7 +148,7 @@ struct WsLayout {
   size_t xpatch, vh, vh_b, vq, vk, vv, vattn, vmid, part;
   size_t lx, lx_b, lq, kcache, vcache, lattn, lmid;
   size_t stok, z, y, y_b, eq, ek, ev, eattn, emid;
-  size_t vstat, lstat, estat;
+  size_t vstat, lstat, estat, estat_parts;
   size_t total;
   size_t kcache_layer, vcache_layer;   // bytes per layer
   int zmax;
@@ -258,6 +258,7 @@ void ws_layout(const pi0_config& c, const Dims& d, WsLayout& w) {
   w.vstat = cur.take((size_t)d.maxI * 2 * 4);
   w.lstat = cur.take((size_t)d.maxPc * 32 * 2 * 4);
   w.estat = cur.take((size_t)64 * 2 * 4);
+  w.estat_parts = cur.take((size_t)(d.X / 32) * 64 * 2 * 4);
   w.total = cur.off;
 }
 
@@ -526,6 +527,29 @@ void run_denoise(Run& r, int P, Taps* taps) {
                             at<float>(c, w.stok)));
   const float dt = -1.0f / (float)d.steps;
   size_t tap_step_base = taps ? taps->off : 0;
+  // row statistics of the suffix residual stream: where the next RMS-folded GEMM finds them
+  const float* stat_ptr = at<float>(c, w.estat);
+  int stat_parts = 1;
+  // y += X @ W (expert O / down projection).  k = 2048 or 4096: one kernel with the residual
+  // epilogue that also leaves per-tile row statistics; otherwise split-K partials + reduction.
+  auto resid_gemm = [&](const PW& pw, const bf16* X, int K) {
+    if (pw.k_pad == 2048 || pw.k_pad == 4096) {
+      GemmParams p = gp_base(c, pw, X, K, 64, TILE_SKINNY_FULLK, K);
+      p.resid = at<float>(c, w.y);
+      p.out_f32 = at<float>(c, w.y);
+      p.out_bf16 = at<bf16>(c, w.y_b);
+      p.ldo = d.X; p.ldo2 = d.X; p.n_valid = d.X;
+      p.stat_out = at<float>(c, w.estat_parts);
+      RUN_GEMM(r, TILE_SKINNY_FULLK, PRO_NONE, EPI_RESID, p, 1);
+      stat_ptr = at<float>(c, w.estat_parts);
+      stat_parts = pw.n_pad / 32;
+    } else {
+      gemm_splitk_resid(r, pw, X, K, 64, K, ceil_div(pw.k_pad, 1024), 1024, nullptr, at<float>(c, w.y), at<bf16>(c, w.y_b),
+                        d.X, TILE_SKINNY, at<float>(c, w.estat));
+      stat_ptr = at<float>(c, w.estat);
+      stat_parts = 1;
+    }
+  };
   for (int k = 0; k < d.steps; k++) {
     // C1: folded action/time embedding, SiLU; suffix row 0 <- state token
     RUN(r, launch_action_embed(r.s, xa, chunk, d.A, at<float>(c, w.wfold), at<float>(c, w.bias_tab) + (size_t)k * d.X, d.X,
@@ -539,6 +563,8 @@ void run_denoise(Run& r, int P, Taps* taps) {
       RUN_GEMM(r, TILE_SKINNY, PRO_NONE, EPI_RESID, p, 1);
     }
     RUN(r, launch_row_stats(r.s, at<bf16>(c, w.y_b), 64, d.X, d.X, at<float>(c, w.estat)));
+    stat_ptr = at<float>(c, w.estat);
+    stat_parts = 1;
     const bool tap_this = taps && (k == 0 || k == d.steps - 1);
     for (int l = 0; l < d.Le; l++) {
       const WsTr& L = w.exp[l];
@@ -546,7 +572,8 @@ void run_denoise(Run& r, int P, Taps* taps) {
       bf16* vc = reinterpret_cast<bf16*>(c->ws + w.vcache + (size_t)l * w.vcache_layer);
       {  // C3: RMS -> QKV, RoPE at positions P..P+63
         GemmParams p = gp_base(c, L.qkv, at<bf16>(c, w.y_b), d.X, 64, TILE_SKINNY, d.X);
-        p.rowstat = at<float>(c, w.estat);
+        p.rowstat = stat_ptr;
+        p.rowstat_parts = stat_parts;
         p.out_bf16 = at<bf16>(c, w.eq);
         p.q_mbs = 2;
         p.kfrag = at<bf16>(c, w.ek); p.vfrag = at<bf16>(c, w.ev);
@@ -568,19 +595,18 @@ void run_denoise(Run& r, int P, Taps* taps) {
         a.out = at<bf16>(c, w.eattn); a.out_ld = d.H * 256; a.head_dim = 256;
         RUN(r, launch_attention(r.s, a));
       }
-      // C6: O-projection + residual (k split over blocks, fixed-order reduction)
-      gemm_splitk_resid(r, L.o, at<bf16>(c, w.eattn), d.H * 256, 64, d.H * 256, ceil_div(L.o.k_pad, 1024), 1024, nullptr,
-                        at<float>(c, w.y), at<bf16>(c, w.y_b), d.X, TILE_SKINNY, at<float>(c, w.estat));
+      // C6: O-projection + residual
+      resid_gemm(L.o, at<bf16>(c, w.eattn), d.H * 256);
       {  // C7: RMS -> gate||up, fused gate
         GemmParams p = gp_base(c, L.gu, at<bf16>(c, w.y_b), d.X, 64, TILE_SKINNY, d.X);
-        p.rowstat = at<float>(c, w.estat);
+        p.rowstat = stat_ptr;
+        p.rowstat_parts = stat_parts;
         p.out_bf16 = at<bf16>(c, w.emid);
         p.ldo = d.Fx;
         RUN_GEMM(r, TILE_SKINNY, PRO_RMS, EPI_GEGLU, p, 1);
       }
       // C8: down + residual
-      gemm_splitk_resid(r, L.down, at<bf16>(c, w.emid), d.Fx, 64, d.Fx, ceil_div(L.down.k_pad, 1024), 1024, nullptr,
-                        at<float>(c, w.y), at<bf16>(c, w.y_b), d.X, TILE_SKINNY, at<float>(c, w.estat));
+      resid_gemm(L.down, at<bf16>(c, w.emid), d.Fx);
       if (tap_this) {
         // step 0 taps first, last-step taps after them
         const size_t slot = (k == 0 ? 0 : (size_t)d.Le) + l;
@@ -590,7 +616,8 @@ void run_denoise(Run& r, int P, Taps* taps) {
     }
     {  // C9: final RMS -> out-projection (+bias), Euler update x <- x + dt * v
       GemmParams p = gp_base(c, w.outp, at<bf16>(c, w.y_b), d.X, 64, TILE_SKINNY, d.X);
-      p.rowstat = at<float>(c, w.estat);
+      p.rowstat = stat_ptr;
+      p.rowstat_parts = stat_parts;
       p.bias = at<float>(c, w.outp.bias);
       p.out_f32 = xa;
       p.ldo = d.A; p.n_valid = d.A; p.dt = dt;

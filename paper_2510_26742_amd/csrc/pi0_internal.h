@@ -74,7 +74,10 @@ struct GemmParams {
   // statistics / affine
   const float* bias;    // [n_pad] or null
   const float* colsum;  // [n_pad], PRO_LN only: sum_k W'[n][k]
-  const float* rowstat; // [rows][2] (sum, sum of squares) of the bf16 activations, PRO_RMS / PRO_LN
+  const float* rowstat; // (sum, sum of squares) of the bf16 activation rows, PRO_RMS / PRO_LN: [rows][2] for the tall
+                        // kernels; [rowstat_parts][64][2] partial sums for the skinny kernel
+  int rowstat_parts;
+  float* stat_out;      // EPI_RESID: partial row statistics of the output per 32-column tile, [n tile][64][2], or null
   // outputs
   float* out_f32;     // EPI_RESID / EPI_PARTIAL / EPI_EULER
   bf16* out_bf16;     // EPI_RESID shadow (XF), EPI_BF16 (XF), EPI_GEGLU (XF), EPI_QKV q (fragment order per head)
@@ -106,7 +109,8 @@ struct GemmParams {
 enum GemmTile {
   TILE_BIG = 0,     // 256 tokens x 128 features per block (4 waves), 4 stages in flight
   TILE_MID = 1,     // 64 tokens x 128 features per block (4 waves), 8 stages in flight
-  TILE_SKINNY = 2   // <= 64 tokens, one 32-feature tile per block, 8 waves split k <= 1024, loads issued at once
+  TILE_SKINNY = 2,  // <= 64 tokens, one 32-feature tile per block, 8 waves split k <= 1024, loads issued at once
+  TILE_SKINNY_FULLK = 3   // <= 64 tokens, k = 2048 or 4096 in one block per (feature tile, 32-token block), residual epilogue
 };
 
 hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmParams& p, int z_splits);
