@@ -54,7 +54,7 @@ __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16&
   const float inv_k = 1.0f / (float)p.k_true;
   {
     float rs = 1.f, mu = 0.f;
-    float st_a = 0.f, st_b = 0.f;   // EPI_RESID: sum / sum of squares of this lane's bf16 outputs
+    float st_a = 0.f, st_b = 0.f;   // EPI_RESID: sum / sum of squares of this lane's fp32 outputs
     if (PRO == PRO_RMS) {
       rs = rsqrtf(s_sq * inv_k + 1e-6f);
     } else if (PRO == PRO_LN) {
@@ -97,14 +97,18 @@ __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16&
           const int mo = m + p.row_offset;
           f32x4 o = {v[0], v[1], v[2], v[3]};
           *reinterpret_cast<f32x4*>(p.out_f32 + (size_t)mo * p.ldo + n4) = o;
-          bf16x4 ob = {(bf16)v[0], (bf16)v[1], (bf16)v[2], (bf16)v[3]};
-          *reinterpret_cast<bf16x4*>(p.out_bf16 + xf_index(mo, n4, p.ldo2 >> 4)) = ob;
 #pragma unroll
           for (int j = 0; j < 4; j++) {
-            const float q = (float)ob[j];
-            st_a += q;
-            st_b += q * q;
+            st_a += v[j];
+            st_b += v[j] * v[j];
           }
+          if (p.gain != nullptr) {
+            const f32x4 g4 = *reinterpret_cast<const f32x4*>(p.gain + n4);
+#pragma unroll
+            for (int j = 0; j < 4; j++) v[j] *= g4[j];
+          }
+          bf16x4 ob = {(bf16)v[0], (bf16)v[1], (bf16)v[2], (bf16)v[3]};
+          *reinterpret_cast<bf16x4*>(p.out_bf16 + xf_index(mo, n4, p.ldo2 >> 4)) = ob;
         }
       } else if (EPI == EPI_BF16) {
         if (n4 < p.n_valid) {
@@ -631,9 +635,11 @@ hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmPara
 // ------------------------------------------------------------------------------------------------
 // split-K reduction (fixed summation order -> run-to-run bitwise determinism)
 // ------------------------------------------------------------------------------------------------
-// One block per output row.  Besides the sum it writes the bf16 shadow of the row in XF layout
-// and the row's (sum, sum of squares) over those bf16 values: the statistics that the next
-// LayerNorm / RMSNorm-folded GEMM applies after accumulation (Section 4.4).
+// One block per output row.  Besides the fp32 sum it writes the row's (sum, sum of squares) and the
+// bf16 copy that the next GEMM reads, in XF layout.  The copy is scaled per column by the gain of
+// the normalisation that follows (g for LayerNorm, 1 + g for RMSNorm): the affine part of the norm
+// is folded into the activation cast, so the weights stay the checkpoint's bf16 values, and the
+// row statistics are applied after accumulation by the consumer (Sections 3.2 and 4.4).
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(ReduceParams p) {
   __shared__ float sred[2][4];
   const int m = blockIdx.x;
@@ -648,14 +654,14 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(ReduceParams p) {
       a += *reinterpret_cast<const f32x4*>(p.resid + (size_t)rr * p.ldo + n);
     }
     *reinterpret_cast<f32x4*>(p.out_f32 + (size_t)ro * p.ldo + n) = a;
-    const bf16x4 ob = {(bf16)a[0], (bf16)a[1], (bf16)a[2], (bf16)a[3]};
-    *reinterpret_cast<bf16x4*>(p.out_bf16 + xf_index(ro, n, p.ldo2 >> 4)) = ob;
 #pragma unroll
     for (int j = 0; j < 4; j++) {
-      const float v = (float)ob[j];
-      sa += v;
-      sb += v * v;
+      sa += a[j];
+      sb += a[j] * a[j];
     }
+    if (p.gain != nullptr) a *= *reinterpret_cast<const f32x4*>(p.gain + n);
+    const bf16x4 ob = {(bf16)a[0], (bf16)a[1], (bf16)a[2], (bf16)a[3]};
+    *reinterpret_cast<bf16x4*>(p.out_bf16 + xf_index(ro, n, p.ldo2 >> 4)) = ob;
   }
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
@@ -679,20 +685,27 @@ hipError_t launch_splitk_reduce(hipStream_t s, const ReduceParams& p) {
   return hipGetLastError();
 }
 
-// (sum, sum of squares) of every row of an XF matrix: for residual rows that were not produced by
-// the reduction kernel (projector output, prompt embeddings, first suffix tokens of a step).
-__global__ __launch_bounds__(256) void row_stats_kernel(const bf16* xf, int K, int kc16, float* stat_out) {
+// Row statistics and gain-scaled bf16 XF copy of fp32 residual rows that were not produced by a
+// GEMM epilogue or the reduction kernel (prefix embeddings, first suffix tokens of a step).
+__global__ __launch_bounds__(256) void row_stats_kernel(const float* x, int ld, int K, const float* gain, bf16* out_xf,
+                                                        int kc16, float* stat_out) {
   __shared__ float sred[2][4];
   const int m = blockIdx.x;
   float sa = 0.f, sb = 0.f;
   for (int k = threadIdx.x * 8; k < K; k += 2048) {
-    const bf16x8 v = *reinterpret_cast<const bf16x8*>(xf + xf_index(m, k, kc16));
+    f32x4 v0 = *reinterpret_cast<const f32x4*>(x + (size_t)m * ld + k);
+    f32x4 v1 = *reinterpret_cast<const f32x4*>(x + (size_t)m * ld + k + 4);
 #pragma unroll
-    for (int j = 0; j < 8; j++) {
-      const float f = (float)v[j];
-      sa += f;
-      sb += f * f;
+    for (int j = 0; j < 4; j++) {
+      sa += v0[j] + v1[j];
+      sb += v0[j] * v0[j] + v1[j] * v1[j];
     }
+    if (gain != nullptr) {
+      v0 *= *reinterpret_cast<const f32x4*>(gain + k);
+      v1 *= *reinterpret_cast<const f32x4*>(gain + k + 4);
+    }
+    const bf16x8 o = {(bf16)v0[0], (bf16)v0[1], (bf16)v0[2], (bf16)v0[3], (bf16)v1[0], (bf16)v1[1], (bf16)v1[2], (bf16)v1[3]};
+    *reinterpret_cast<bf16x8*>(out_xf + xf_index(m, k, kc16)) = o;
   }
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
@@ -710,8 +723,11 @@ __global__ __launch_bounds__(256) void row_stats_kernel(const bf16* xf, int K, i
   }
 }
 
-hipError_t launch_row_stats(hipStream_t s, const bf16* xf, int M, int K, int k_pad, float* stat_out) {
-  if (xf == nullptr || stat_out == nullptr || M <= 0 || K % 8 != 0 || k_pad % 16 != 0 || K > k_pad) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(row_stats_kernel, dim3((unsigned)M), dim3(256), 0, s, xf, K, k_pad >> 4, stat_out);
+hipError_t launch_row_stats(hipStream_t s, const float* x, int ld, int M, int K, int k_pad, const float* gain, bf16* out_xf,
+                            float* stat_out) {
+  if (x == nullptr || out_xf == nullptr || stat_out == nullptr || M <= 0 || K % 8 != 0 || ld % 4 != 0 || ld < K ||
+      k_pad % 16 != 0 || K > k_pad)
+    return hipErrorInvalidValue;
+  hipLaunchKernelGGL(row_stats_kernel, dim3((unsigned)M), dim3(256), 0, s, x, ld, K, gain, out_xf, k_pad >> 4, stat_out);
   return hipGetLastError();
 }

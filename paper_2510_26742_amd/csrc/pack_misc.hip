@@ -69,7 +69,7 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(PackSrc s, bf16* dst,
   for (int j = 0; j < 8; j++) {
     const int k = k0 + j;
     float v = 0.f;
-    if (live && k < s.K) v = (float)s.src[which][(size_t)k * s.cols[which] + col] * k_scale(s, k);
+    if (live && k < s.K) v = (float)s.src[which][(size_t)k * s.cols[which] + col];
     out[j] = (bf16)v;
   }
   *reinterpret_cast<bf16x8*>(dst + idx * 8) = out;
@@ -82,7 +82,7 @@ hipError_t launch_pack_weights(hipStream_t st, const PackSrc& s, bf16* dst, int 
   return hipGetLastError();
 }
 
-// colsum[n] = sum_k bf16(scale_k * W[k][col])   (exactly the values the GEMM multiplies)
+// colsum[n] = sum_k gain_k * W[k][col]   (the activations reach the GEMM already scaled by gain_k)
 // bias_out[n] = sum_k ln_bias[k] * W[k][col] + bias_src[which][col]
 struct FoldArgs {
   PackSrc s;
@@ -102,7 +102,7 @@ __global__ __launch_bounds__(256) void fold_vectors_kernel(FoldArgs a) {
     if (a.colsum != nullptr || a.ln_bias != nullptr) {
       for (int k = 0; k < a.s.K; k++) {
         const float w = (float)a.s.src[which][(size_t)k * a.s.cols[which] + col];
-        cs += (float)(bf16)(w * k_scale(a.s, k));
+        cs += w * k_scale(a.s, k);
         if (a.ln_bias != nullptr) bo += (float)a.ln_bias[k] * w;
       }
     }
@@ -133,6 +133,16 @@ __global__ __launch_bounds__(256) void bf16_to_f32_kernel(const bf16* src, float
 hipError_t launch_bf16_to_f32(hipStream_t st, const bf16* src, float* dst, size_t n) {
   if (n == 0) return hipSuccess;
   hipLaunchKernelGGL(bf16_to_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, src, dst, n);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void gain_vector_kernel(const bf16* src, float* dst, int n, float add) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) dst[i] = (float)src[i] + add;
+}
+hipError_t launch_gain_vector(hipStream_t st, const bf16* src, float* dst, int n, int one_plus) {
+  if (n <= 0 || src == nullptr || dst == nullptr) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(gain_vector_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, src, dst, n, one_plus ? 1.0f : 0.0f);
   return hipGetLastError();
 }
 

@@ -143,6 +143,8 @@ struct WsLayout {
   size_t state_w, state_b, wfold, bias_tab, tau;
   PW tout, outp;
   size_t rope;
+  std::vector<size_t> g_v1, g_v2, g_l1, g_l2, g_e1, g_e2;   // fp32 gain vectors of the norms (g or 1 + g)
+  size_t g_vf, g_ef;
   size_t act_begin;   // everything from here on is zero-filled at load time
   size_t st_images, st_ids, st_state, st_noise, xa;
   size_t xpatch, vh, vh_b, vq, vk, vv, vattn, vmid, part;
@@ -216,6 +218,14 @@ void ws_layout(const pi0_config& c, const Dims& d, WsLayout& w) {
   w.tout = pw(d.X, d.X, false, true);
   w.outp = pw(d.A, d.X, false, true);
   w.rope = cur.take((size_t)d.maxpos * 128 * 2 * 4);
+  w.g_v1.resize(d.Lv); w.g_v2.resize(d.Lv);
+  for (int l = 0; l < d.Lv; l++) { w.g_v1[l] = cur.take((size_t)d.Dv * 4); w.g_v2[l] = cur.take((size_t)d.Dv * 4); }
+  w.g_vf = cur.take((size_t)d.Dv * 4);
+  w.g_l1.resize(d.Ll); w.g_l2.resize(d.Ll);
+  for (int l = 0; l < d.Ll; l++) { w.g_l1[l] = cur.take((size_t)d.E * 4); w.g_l2[l] = cur.take((size_t)d.E * 4); }
+  w.g_e1.resize(d.Le); w.g_e2.resize(d.Le);
+  for (int l = 0; l < d.Le; l++) { w.g_e1[l] = cur.take((size_t)d.X * 4); w.g_e2[l] = cur.take((size_t)d.X * 4); }
+  w.g_ef = cur.take((size_t)d.X * 4);
   // ---- activations ----
   w.act_begin = cur.off;
   w.st_images = cur.take((size_t)c.max_views * c.img_size * c.img_size * 3 * 4);
@@ -352,7 +362,7 @@ GemmParams gp_base(pi0_ctx* c, const PW& pw, const bf16* X, int ldx, int M, int 
 // split-K GEMM into the partial buffer followed by the fixed-order reduction with bias/residual
 void gemm_splitk_resid(Run& r, const PW& pw, const bf16* X, int ldx, int M, int k_true, int z, int k_per_split,
                        const float* bias, float* resid_io, bf16* shadow, int n_true, int tile, float* stat_out,
-                       const float* resid_in = nullptr, int resid_mod = 0, bool no_resid = false) {
+                       const float* gain, const float* resid_in = nullptr, int resid_mod = 0, bool no_resid = false) {
   pi0_ctx* c = r.c;
   if (z > Z_MAX) z = Z_MAX;
   if ((long)k_per_split * z < pw.k_pad) k_per_split = round_up(ceil_div(pw.k_pad, z), 64);
@@ -368,6 +378,7 @@ void gemm_splitk_resid(Run& r, const PW& pw, const bf16* X, int ldx, int M, int 
   q.resid = no_resid ? nullptr : (resid_in ? resid_in : resid_io);
   q.resid_mod = resid_mod;
   q.stat_out = stat_out;
+  q.gain = gain;
   q.out_f32 = resid_io;
   q.out_bf16 = shadow;
   q.ldo = n_true; q.ldo2 = n_true;
@@ -393,7 +404,8 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
   // A0: patches -> tokens (+bias, +position embedding)
   RUN(r, launch_patchify(r.s, at<float>(c, w.st_images), n_views, c->cfg.img_size, c->cfg.patch, at<bf16>(c, w.xpatch), d.PDp));
   gemm_splitk_resid(r, w.patch, at<bf16>(c, w.xpatch), d.PDp, I, d.PD, 1, w.patch.k_pad, at<float>(c, w.patch.bias),
-                    at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv, T.vis, at<float>(c, w.vstat), at<float>(c, w.pos), d.T);
+                    at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv, T.vis, at<float>(c, w.vstat), at<float>(c, w.g_v1[0]),
+                    at<float>(c, w.pos), d.T);
   const int vchunks = I / 32;
   for (int l = 0; l < d.Lv; l++) {
     const WsVis& L = w.vis[l];
@@ -426,7 +438,8 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
     }
     // A3: O-projection + bias + residual
     gemm_splitk_resid(r, L.o, at<bf16>(c, w.vattn), d.Dv, I, d.Dv, T.zvo, round_up(ceil_div(L.o.k_pad, T.zvo), 64),
-                      at<float>(c, L.o.bias), at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv, T.part, at<float>(c, w.vstat));
+                      at<float>(c, L.o.bias), at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv, T.part, at<float>(c, w.vstat),
+                      at<float>(c, w.g_v2[l]));
     {  // A4: LN -> up (+bias, GELU)
       GemmParams p = gp_base(c, L.up, at<bf16>(c, w.vh_b), d.Dv, I, T.vis, d.Dv);
       p.bias = at<float>(c, L.up.bias);
@@ -438,7 +451,8 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
     }
     // A5: down (+bias, residual)
     gemm_splitk_resid(r, L.down, at<bf16>(c, w.vmid), d.Fv_kp, I, d.Fv, T.zvd, round_up(ceil_div(L.down.k_pad, T.zvd), 64),
-                      at<float>(c, L.down.bias), at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv, T.part, at<float>(c, w.vstat));
+                      at<float>(c, L.down.bias), at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv, T.part, at<float>(c, w.vstat),
+                      at<float>(c, l + 1 < d.Lv ? w.g_v1[l + 1] : w.g_vf));
     if (taps) taps->put(r, at<float>(c, w.vh), (size_t)I * d.Dv);
   }
   {  // A6: final LN -> projector (+bias) = prefix image embeddings
@@ -456,7 +470,8 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
     RUN(r, launch_embed_prompt(r.s, at<int32_t>(c, w.st_ids), n_prompt, at<bf16>(c, w.embed), c->cfg.vocab, d.E,
                                sqrtf((float)d.E), at<float>(c, w.lx), at<bf16>(c, w.lx_b), I));
   }
-  RUN(r, launch_row_stats(r.s, at<bf16>(c, w.lx_b), P, d.E, d.E, at<float>(c, w.lstat)));
+  RUN(r, launch_row_stats(r.s, at<float>(c, w.lx), d.E, P, d.E, d.E, at<float>(c, w.g_l1[0]), at<bf16>(c, w.lx_b),
+                          at<float>(c, w.lstat)));
   const int pchunks = ceil_div(P, 32);
   for (int l = 0; l < d.Ll; l++) {
     const WsTr& L = w.llm[l];
@@ -488,7 +503,8 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
     }
     // B3: O-projection + residual
     gemm_splitk_resid(r, L.o, at<bf16>(c, w.lattn), d.H * 256, P, d.H * 256, T.zlo,
-                      round_up(ceil_div(L.o.k_pad, T.zlo), 64), nullptr, at<float>(c, w.lx), at<bf16>(c, w.lx_b), d.E, T.part, at<float>(c, w.lstat));
+                      round_up(ceil_div(L.o.k_pad, T.zlo), 64), nullptr, at<float>(c, w.lx), at<bf16>(c, w.lx_b), d.E, T.part,
+                      at<float>(c, w.lstat), at<float>(c, w.g_l2[l]));
     {  // B4: RMS -> gate||up with fused GELU gate
       GemmParams p = gp_base(c, L.gu, at<bf16>(c, w.lx_b), d.E, P, T.lgu, d.E);
       p.rowstat = at<float>(c, w.lstat);
@@ -499,7 +515,7 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
     // B5: down + residual
     gemm_splitk_resid(r, L.down, at<bf16>(c, w.lmid), d.F, P, d.F, T.zld,
                       round_up(ceil_div(L.down.k_pad, T.zld), 64), nullptr, at<float>(c, w.lx), at<bf16>(c, w.lx_b),
-                      d.E, T.part, at<float>(c, w.lstat));
+                      d.E, T.part, at<float>(c, w.lstat), at<float>(c, w.g_l1[l + 1]));
     if (taps) taps->put(r, at<float>(c, w.lx), (size_t)P * d.E);
   }
   if (taps && taps->base) {
@@ -532,7 +548,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
   int stat_parts = 1;
   // y += X @ W (expert O / down projection).  k = 2048 or 4096: one kernel with the residual
   // epilogue that also leaves per-tile row statistics; otherwise split-K partials + reduction.
-  auto resid_gemm = [&](const PW& pw, const bf16* X, int K) {
+  auto resid_gemm = [&](const PW& pw, const bf16* X, int K, const float* gain) {
     if (pw.k_pad == 2048 || pw.k_pad == 4096) {
       GemmParams p = gp_base(c, pw, X, K, 64, TILE_SKINNY_FULLK, K);
       p.resid = at<float>(c, w.y);
@@ -540,12 +556,13 @@ void run_denoise(Run& r, int P, Taps* taps) {
       p.out_bf16 = at<bf16>(c, w.y_b);
       p.ldo = d.X; p.ldo2 = d.X; p.n_valid = d.X;
       p.stat_out = at<float>(c, w.estat_parts);
+      p.gain = gain;
       RUN_GEMM(r, TILE_SKINNY_FULLK, PRO_NONE, EPI_RESID, p, 1);
       stat_ptr = at<float>(c, w.estat_parts);
       stat_parts = pw.n_pad / 32;
     } else {
       gemm_splitk_resid(r, pw, X, K, 64, K, ceil_div(pw.k_pad, 1024), 1024, nullptr, at<float>(c, w.y), at<bf16>(c, w.y_b),
-                        d.X, TILE_SKINNY, at<float>(c, w.estat));
+                        d.X, TILE_SKINNY, at<float>(c, w.estat), gain);
       stat_ptr = at<float>(c, w.estat);
       stat_parts = 1;
     }
@@ -562,7 +579,8 @@ void run_denoise(Run& r, int P, Taps* taps) {
       p.ldo = d.X; p.ldo2 = d.X; p.n_valid = d.X; p.row_offset = 1;
       RUN_GEMM(r, TILE_SKINNY, PRO_NONE, EPI_RESID, p, 1);
     }
-    RUN(r, launch_row_stats(r.s, at<bf16>(c, w.y_b), 64, d.X, d.X, at<float>(c, w.estat)));
+    RUN(r, launch_row_stats(r.s, at<float>(c, w.y), d.X, 64, d.X, d.X, at<float>(c, w.g_e1[0]), at<bf16>(c, w.y_b),
+                            at<float>(c, w.estat)));
     stat_ptr = at<float>(c, w.estat);
     stat_parts = 1;
     const bool tap_this = taps && (k == 0 || k == d.steps - 1);
@@ -596,7 +614,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
         RUN(r, launch_attention(r.s, a));
       }
       // C6: O-projection + residual
-      resid_gemm(L.o, at<bf16>(c, w.eattn), d.H * 256);
+      resid_gemm(L.o, at<bf16>(c, w.eattn), d.H * 256, at<float>(c, w.g_e2[l]));
       {  // C7: RMS -> gate||up, fused gate
         GemmParams p = gp_base(c, L.gu, at<bf16>(c, w.y_b), d.X, 64, TILE_SKINNY, d.X);
         p.rowstat = stat_ptr;
@@ -606,7 +624,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
         RUN_GEMM(r, TILE_SKINNY, PRO_RMS, EPI_GEGLU, p, 1);
       }
       // C8: down + residual
-      resid_gemm(L.down, at<bf16>(c, w.emid), d.Fx);
+      resid_gemm(L.down, at<bf16>(c, w.emid), d.Fx, at<float>(c, l + 1 < d.Le ? w.g_e1[l + 1] : w.g_ef));
       if (tap_this) {
         // step 0 taps first, last-step taps after them
         const size_t slot = (k == 0 ? 0 : (size_t)d.Le) + l;
@@ -877,6 +895,20 @@ int pi0_load_weights(pi0_ctx* c, const void* d_blob, size_t blob_bytes, void* d_
     TRY(pack(w.vis[l].up, src1(v.w1, d.Dv, d.Fv, KSCALE_GAIN, v.ln2g), B + v.ln2b, B + v.b1, nullptr, nullptr));
     TRY(pack(w.vis[l].down, src1(v.w2, d.Fv, d.Dv, KSCALE_NONE, 0), nullptr, B + v.b2, nullptr, nullptr));
   }
+  for (int l = 0; l < d.Lv; l++) {
+    TRY(launch_gain_vector(s, B + b.vis[l].ln1g, at<float>(c, w.g_v1[l]), d.Dv, 0));
+    TRY(launch_gain_vector(s, B + b.vis[l].ln2g, at<float>(c, w.g_v2[l]), d.Dv, 0));
+  }
+  TRY(launch_gain_vector(s, B + b.lnfg, at<float>(c, w.g_vf), d.Dv, 0));
+  for (int l = 0; l < d.Ll; l++) {
+    TRY(launch_gain_vector(s, B + b.llm[l].g_attn, at<float>(c, w.g_l1[l]), d.E, 1));
+    TRY(launch_gain_vector(s, B + b.llm[l].g_mlp, at<float>(c, w.g_l2[l]), d.E, 1));
+  }
+  for (int l = 0; l < d.Le; l++) {
+    TRY(launch_gain_vector(s, B + b.exp[l].g_attn, at<float>(c, w.g_e1[l]), d.X, 1));
+    TRY(launch_gain_vector(s, B + b.exp[l].g_mlp, at<float>(c, w.g_e2[l]), d.X, 1));
+  }
+  TRY(launch_gain_vector(s, B + b.g_final, at<float>(c, w.g_ef), d.X, 1));
   TRY(pack(w.proj, src1(b.proj_w, d.Dv, d.E, KSCALE_GAIN, b.lnfg), B + b.lnfb, B + b.proj_b, nullptr, nullptr));
   if (c->cfg.vocab > 0) TRY(launch_copy_bf16(s, B + b.embed, at<bf16>(c, w.embed), (size_t)c->cfg.vocab * d.E));
   // prefix and expert transformers

@@ -42,7 +42,8 @@ struct PackSrc {
   int K;              // true input features
   int n_true;         // true number of packed rows
   int rowmap;
-  int kscale;         // per-k scale folded into the weights
+  int kscale;         // per-k gain of the preceding norm: enters the column sums only (the weights stay unscaled,
+                      // the gain is applied where the activations are cast to bf16)
   const bf16* gain;   // [K] (KSCALE_GAIN: g, KSCALE_ONE_PLUS: 1 + g)
   int q_heads;        // ROWMAP_ROPE_QKV: number of 256-wide q heads in src0
 };
@@ -74,10 +75,11 @@ struct GemmParams {
   // statistics / affine
   const float* bias;    // [n_pad] or null
   const float* colsum;  // [n_pad], PRO_LN only: sum_k W'[n][k]
-  const float* rowstat; // (sum, sum of squares) of the bf16 activation rows, PRO_RMS / PRO_LN: [rows][2] for the tall
+  const float* rowstat; // (sum, sum of squares) of the fp32 residual rows, PRO_RMS / PRO_LN: [rows][2] for the tall
                         // kernels; [rowstat_parts][64][2] partial sums for the skinny kernel
   int rowstat_parts;
   float* stat_out;      // EPI_RESID: partial row statistics of the output per 32-column tile, [n tile][64][2], or null
+  const float* gain;    // EPI_RESID: per-column scale of the bf16 shadow (gain of the norm that follows), or null
   // outputs
   float* out_f32;     // EPI_RESID / EPI_PARTIAL / EPI_EULER
   bf16* out_bf16;     // EPI_RESID shadow (XF), EPI_BF16 (XF), EPI_GEGLU (XF), EPI_QKV q (fragment order per head)
@@ -126,12 +128,17 @@ struct ReduceParams {
   const float* resid;
   int resid_mod;      // row index of resid taken modulo this (0 = no modulo)
   float* stat_out;    // [rows][2] or null
+  const float* gain;  // per-column scale of the bf16 shadow (gain of the norm that follows), or null
   float* out_f32;
   bf16* out_bf16;     // XF layout with ldo2 padded columns
   int ldo, ldo2;
 };
 hipError_t launch_splitk_reduce(hipStream_t s, const ReduceParams& p);
-hipError_t launch_row_stats(hipStream_t s, const bf16* xf, int M, int K, int k_pad, float* stat_out);
+// stat_out[m] = (sum, sum sq) of fp32 row m of x; out_xf = bf16(x * gain) in XF layout with k_pad columns
+hipError_t launch_row_stats(hipStream_t s, const float* x, int ld, int M, int K, int k_pad, const float* gain, bf16* out_xf,
+                            float* stat_out);
+// dst[i] = src[i] (+1 if one_plus): fp32 gain vectors of the norms
+hipError_t launch_gain_vector(hipStream_t s, const bf16* src, float* dst, int n, int one_plus);
 
 // ------------------------------------------------------------------------------------------
 // Attention over fragment-ordered keys / values.
@@ -167,7 +174,7 @@ hipError_t attention_init_attributes();
 // small kernels
 // ------------------------------------------------------------------------------------------
 hipError_t launch_pack_weights(hipStream_t s, const PackSrc& src, bf16* dst, int n_pad, int k_pad);
-// colsum[n] = sum_k packed(n,k) as stored (bf16-rounded, scaled); bias_out[n] = sum_k ln_bias[k]*W[k][col] + bias_cat[n]
+// colsum[n] = sum_k gain_k * W[k][col] in fp32; bias_out[n] = sum_k ln_bias[k]*W[k][col] + bias_cat[n]
 hipError_t launch_fold_vectors(hipStream_t s, const PackSrc& src, const bf16* ln_bias, const bf16* const bias_src[3],
                                float* colsum, float* bias_out, int n_pad);
 hipError_t launch_bf16_to_f32(hipStream_t s, const bf16* src, float* dst, size_t n);

@@ -243,14 +243,16 @@ def test_sharp_attention_masks():
         case.close()
 
 
-def test_full_model_one_view():
-    """The benchmark's workload (full depth, one view, empty prompt) end to end against the oracle."""
+def test_full_model_all_view_counts():
+    """The benchmark's workloads (full depth; one, two and three views; empty prompt, Table 1) end to
+    end against the oracle, in the launch configuration the benchmark times (graph replay)."""
     case = Case(synth.full_config())
     try:
-        act, ref = check_against_oracle(case, 1, 0, label="full 1 view")
-        # the graph path the benchmark times gives the same bits
-        img, st, nz, ids = case.inputs(1, 0)
-        np.testing.assert_array_equal(case.infer(img, st, nz, ids), act)
-        np.testing.assert_array_equal(case.infer(img, st, nz, ids), act)
+        for n_views in (1, 2, 3):
+            act, ref = check_against_oracle(case, n_views, 0, label=f"full {n_views} view")
+            # the graph path the benchmark times gives the same bits
+            img, st, nz, ids = case.inputs(n_views, 0)
+            np.testing.assert_array_equal(case.infer(img, st, nz, ids), act)
+            np.testing.assert_array_equal(case.infer(img, st, nz, ids), act)
     finally:
         case.close()
