@@ -46,6 +46,10 @@ __global__ __launch_bounds__(512) void attention_kernel(AttnParams p) {
   const int w = t >> 6;
   const int lq = lane & 31;
   const int lh = lane >> 5;
+  if ((int)blockIdx.y >= p.heads) {   // warm-up block; rank = linear block index (mod 8)
+    prefetch_role(p.pf, (int)blockIdx.x + (int)gridDim.x * ((int)blockIdx.y - p.heads));
+    return;
+  }
   const int tile = blockIdx.x;
   const int head = blockIdx.y;
   const int row = tile * 32 + lq;
@@ -264,6 +268,16 @@ hipError_t launch_attention(hipStream_t s, const AttnParams& p) {
   const int ntot = n0 + p.chunks1;
   if (n0 > 32) return hipErrorInvalidValue;   // at most 1024 keys in segment 0 per query row
   dim3 grid((p.Tq + 31) / 32, p.heads, 1);
+  if (p.pf.blocks != 0) {   // warm-up blocks as extra grid rows
+    const PrefetchDesc& d = p.pf;
+    if (d.blocks < 0 || d.blocks % 16 != 0 || d.blocks > 1024 || d.sink == nullptr || d.blocks % (int)grid.x != 0) return hipErrorInvalidValue;
+    for (int r = 0; r < 3; r++) {
+      if (d.ptr[r] == nullptr) continue;
+      if (d.tiles[r] <= 0 || d.tile16[r] <= 0 || (reinterpret_cast<uintptr_t>(d.ptr[r]) & 15) != 0) return hipErrorInvalidValue;
+      if ((long)((d.tiles[r] + 7) / 8) * d.tile16[r] > 0x7fffffffL) return hipErrorInvalidValue;
+    }
+    grid.y += d.blocks / grid.x;
+  }
   if (p.head_dim == 256) {
     if (n0 <= 8) attention_kernel<256, 8, 1, 10><<<grid, dim3(512), attn_smem<256>(ntot), s>>>(p);
     else if (n0 <= 16) attention_kernel<256, 8, 2, 8><<<grid, dim3(512), attn_smem<256>(ntot), s>>>(p);

@@ -389,6 +389,10 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
   const int w = t >> 6;
   const int lq = lane & 31;
   const int lh = lane >> 5;
+  if ((int)blockIdx.x >= p.n_tiles) {   // warm-up block (only launched with gridDim.y == 1)
+    prefetch_role(p.pf, (int)blockIdx.x - p.n_tiles);
+    return;
+  }
   const int nt = blockIdx.x;
   const int k_pad = p.W.k_pad;
   const int kbeg = blockIdx.y * p.k_per_split;
@@ -484,6 +488,10 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_fullk_kernel(GemmPa
   const int w = t >> 6;
   const int lq = lane & 31;
   const int lh = lane >> 5;
+  if ((int)blockIdx.x >= p.n_tiles) {   // warm-up block; rank = linear block index (mod 8)
+    prefetch_role(p.pf, (int)blockIdx.x - p.n_tiles + (int)blockIdx.y * ((int)gridDim.x - p.n_tiles));
+    return;
+  }
   const int nt = blockIdx.x;
   const int mb = blockIdx.y;
   const int KC16 = p.W.k_pad >> 4;
@@ -593,8 +601,23 @@ hipError_t gemm_init_attributes() {
   return hipSuccess;
 }
 
+// every region of a warm-up descriptor must be given completely; the caller guarantees that
+// [ptr, ptr + tiles * tile16 * 16) is readable device memory
+static bool prefetch_ok(const PrefetchDesc& d) {
+  if (d.blocks == 0) return true;
+  if (d.blocks < 0 || d.blocks % 16 != 0 || d.blocks > 1024 || d.sink == nullptr) return false;
+  for (int r = 0; r < 3; r++) {
+    if (d.ptr[r] == nullptr) continue;
+    if (d.tiles[r] <= 0 || d.tile16[r] <= 0 || (reinterpret_cast<uintptr_t>(d.ptr[r]) & 15) != 0) return false;
+    if ((long)((d.tiles[r] + 7) / 8) * d.tile16[r] > 0x7fffffffL) return false;
+  }
+  return true;
+}
+
 hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmParams& p, int z_splits) {
   // Host-side shape checks: everything the kernel's indexing assumes.
+  if (!prefetch_ok(p.pf)) return hipErrorInvalidValue;
+  if (p.pf.blocks != 0 && ((tile != TILE_SKINNY && tile != TILE_SKINNY_FULLK) || z_splits != 1)) return hipErrorInvalidValue;
   if (p.X == nullptr || p.W.w == nullptr || p.M <= 0 || z_splits < 1) return hipErrorInvalidValue;
   if (p.W.k_pad % 64 != 0 || p.W.n_pad % 32 != 0 || p.n_tiles * 32 != p.W.n_pad) return hipErrorInvalidValue;
   if (p.ldx < p.W.k_pad || p.ldx % 16 != 0) return hipErrorInvalidValue;   // X is in XF layout with ldx padded columns
@@ -605,7 +628,8 @@ hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmPara
   if (tile == TILE_SKINNY_FULLK) {
     const int kc16 = p.W.k_pad >> 4;
     if (p.M > 64 || pro != PRO_NONE || epi != EPI_RESID || z_splits != 1 || (kc16 != 128 && kc16 != 256)) return hipErrorInvalidValue;
-    const dim3 grid(p.n_tiles, (p.M + 31) / 32);
+    if (p.pf.blocks != 0 && ((p.M + 31) / 32 != 2 || p.n_tiles % 8 != 0)) return hipErrorInvalidValue;
+    const dim3 grid(p.n_tiles + p.pf.blocks / 2, (p.M + 31) / 32);
     if (kc16 == 128) gemm_skinny_fullk_kernel<1><<<grid, dim3(64 * SK_WAVES), SK_WAVES * 16 * 64 * 4, s>>>(p);
     else gemm_skinny_fullk_kernel<2><<<grid, dim3(64 * SK_WAVES), SK_WAVES * 16 * 64 * 4, s>>>(p);
     return hipGetLastError();
@@ -615,7 +639,7 @@ hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmPara
     if (p.M > 64 || p.m_tiles != 1 || p.k_per_split > SK_KMAX || p.k_per_split % 16 != 0) return hipErrorInvalidValue;
 #define X(PRO, EPI)                                                                                          \
   if (pro == PRO && epi == EPI) {                                                                            \
-    gemm_skinny_kernel<PRO, EPI><<<dim3(p.n_tiles, z_splits), dim3(64 * SK_WAVES), skinny_smem_bytes(), s>>>(p); \
+    gemm_skinny_kernel<PRO, EPI><<<dim3(p.n_tiles + p.pf.blocks, z_splits), dim3(64 * SK_WAVES), skinny_smem_bytes(), s>>>(p); \
     return hipGetLastError();                                                                                \
   }
     SKINNY_VARIANTS(X)

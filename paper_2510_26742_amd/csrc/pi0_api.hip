@@ -150,7 +150,7 @@ struct WsLayout {
   size_t xpatch, vh, vh_b, vq, vk, vv, vattn, vmid, part;
   size_t lx, lx_b, lq, kcache, vcache, lattn, lmid;
   size_t stok, z, y, y_b, eq, ek, ev, eattn, emid;
-  size_t vstat, lstat, estat, estat_parts;
+  size_t vstat, lstat, estat, estat_parts, pf_sink;
   size_t total;
   size_t kcache_layer, vcache_layer;   // bytes per layer
   int zmax;
@@ -269,6 +269,7 @@ void ws_layout(const pi0_config& c, const Dims& d, WsLayout& w) {
   w.lstat = cur.take((size_t)d.maxPc * 32 * 2 * 4);
   w.estat = cur.take((size_t)64 * 2 * 4);
   w.estat_parts = cur.take((size_t)(d.X / 32) * 64 * 2 * 4);
+  w.pf_sink = cur.take(1024 * 4);
   w.total = cur.off;
 }
 
@@ -293,6 +294,8 @@ struct Tune {
   int lgu = TILE_BIG;     // prefix gate||up
   int part = TILE_BIG;    // split-K partial GEMMs (O, down of vision and prefix)
   int zvo = 6, zlo = 8, zld = 16, zvd = 17;
+  // warm-up blocks carried by the expert's launches (0 = none): QKV, attention, O, down
+  int pfq = 64, pfa = 64, pfo = 64, pfd = 64;
 };
 
 struct pi0_ctx {
@@ -548,7 +551,27 @@ void run_denoise(Run& r, int P, Taps* taps) {
   int stat_parts = 1;
   // y += X @ W (expert O / down projection).  k = 2048 or 4096: one kernel with the residual
   // epilogue that also leaves per-tile row statistics; otherwise split-K partials + reduction.
-  auto resid_gemm = [&](const PW& pw, const bf16* X, int K, const float* gain) {
+  // warm-up descriptors: each launch reads ahead for the launches that follow it
+  auto pf_begin = [&](int blocks) {
+    PrefetchDesc f;
+    memset(&f, 0, sizeof(f));
+    f.blocks = blocks;
+    f.sink = at<unsigned>(c, w.pf_sink);
+    return f;
+  };
+  auto pf_weights = [&](PrefetchDesc& f, int r, const PW& pw) {
+    f.ptr[r] = at<bf16>(c, pw.w);
+    f.tiles[r] = pw.n_pad / 32;
+    f.tile16[r] = pw.k_pad * 4;          // one 32-feature tile = k_pad * 32 bf16
+  };
+  auto pf_cache = [&](PrefetchDesc& f, int r, int layer) {
+    f.ptr[r] = c->ws + w.kcache + (size_t)layer * w.kcache_layer;
+    f.tiles[r] = pchunks; f.tile16[r] = 1024;   // one key chunk = 16 KiB
+    f.ptr[r + 1] = c->ws + w.vcache + (size_t)layer * w.vcache_layer;
+    f.tiles[r + 1] = pchunks; f.tile16[r + 1] = 1024;
+  };
+  const Tune& T = c->tune;
+  auto resid_gemm = [&](const PW& pw, const bf16* X, int K, const float* gain, const PrefetchDesc& pf) {
     if (pw.k_pad == 2048 || pw.k_pad == 4096) {
       GemmParams p = gp_base(c, pw, X, K, 64, TILE_SKINNY_FULLK, K);
       p.resid = at<float>(c, w.y);
@@ -557,6 +580,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
       p.ldo = d.X; p.ldo2 = d.X; p.n_valid = d.X;
       p.stat_out = at<float>(c, w.estat_parts);
       p.gain = gain;
+      p.pf = pf;
       RUN_GEMM(r, TILE_SKINNY_FULLK, PRO_NONE, EPI_RESID, p, 1);
       stat_ptr = at<float>(c, w.estat_parts);
       stat_parts = pw.n_pad / 32;
@@ -599,6 +623,8 @@ void run_denoise(Run& r, int P, Taps* taps) {
         p.pos0 = P;
         p.q_cols = d.H * 256; p.k_cols = 256;
         p.head_dim = 256; p.dqk_pad = 256; p.nvb = 8; p.kv_heads = 1; p.kv_chunks = 2;
+        p.pf = pf_begin(T.pfq);
+        pf_weights(p.pf, 0, L.o);
         RUN_GEMM(r, TILE_SKINNY, PRO_RMS, EPI_QKV, p, 1);
       }
       {  // C4 + C5: scores, block mask, softmax, PV over [cache ; own keys]
@@ -611,10 +637,16 @@ void run_denoise(Run& r, int P, Taps* taps) {
         a.suffix_mask = 1;
         a.scale = 1.0f / 16.0f;
         a.out = at<bf16>(c, w.eattn); a.out_ld = d.H * 256; a.head_dim = 256;
+        a.pf = pf_begin(T.pfa);
+        pf_weights(a.pf, 0, L.gu);
         RUN(r, launch_attention(r.s, a));
       }
       // C6: O-projection + residual
-      resid_gemm(L.o, at<bf16>(c, w.eattn), d.H * 256, at<float>(c, w.g_e2[l]));
+      {
+        PrefetchDesc f = pf_begin(T.pfo);
+        pf_weights(f, 0, L.down);
+        resid_gemm(L.o, at<bf16>(c, w.eattn), d.H * 256, at<float>(c, w.g_e2[l]), f);
+      }
       {  // C7: RMS -> gate||up, fused gate
         GemmParams p = gp_base(c, L.gu, at<bf16>(c, w.y_b), d.X, 64, TILE_SKINNY, d.X);
         p.rowstat = stat_ptr;
@@ -624,7 +656,14 @@ void run_denoise(Run& r, int P, Taps* taps) {
         RUN_GEMM(r, TILE_SKINNY, PRO_RMS, EPI_GEGLU, p, 1);
       }
       // C8: down + residual
-      resid_gemm(L.down, at<bf16>(c, w.emid), d.Fx, at<float>(c, l + 1 < d.Le ? w.g_e1[l + 1] : w.g_ef));
+      {
+        // the gate||up launch fills every CU by itself, so the launch after it reads ahead for two
+        const int nl = l + 1 < d.Le ? l + 1 : 0;
+        PrefetchDesc f = pf_begin(T.pfd);
+        pf_weights(f, 0, w.exp[nl].qkv);
+        pf_cache(f, 1, nl);
+        resid_gemm(L.down, at<bf16>(c, w.emid), d.Fx, at<float>(c, l + 1 < d.Le ? w.g_e1[l + 1] : w.g_ef), f);
+      }
       if (tap_this) {
         // step 0 taps first, last-step taps after them
         const size_t slot = (k == 0 ? 0 : (size_t)d.Le) + l;
@@ -761,7 +800,9 @@ int pi0_create(const pi0_config* cfg, pi0_ctx** out) {
     struct { const char* key; int* dst; int lo, hi; } keys[] = {
         {"vis", &c->tune.vis, 0, 1},   {"lqkv", &c->tune.lqkv, 0, 1}, {"lgu", &c->tune.lgu, 0, 1},
         {"part", &c->tune.part, 0, 1}, {"zvo", &c->tune.zvo, 1, Z_MAX}, {"zlo", &c->tune.zlo, 1, Z_MAX},
-        {"zld", &c->tune.zld, 1, Z_MAX}, {"zvd", &c->tune.zvd, 1, Z_MAX}};
+        {"zld", &c->tune.zld, 1, Z_MAX}, {"zvd", &c->tune.zvd, 1, Z_MAX},
+        {"pfq", &c->tune.pfq, 0, 1024}, {"pfa", &c->tune.pfa, 0, 1024}, {"pfo", &c->tune.pfo, 0, 1024},
+        {"pfd", &c->tune.pfd, 0, 1024}};
     for (auto& k : keys) {
       const char* f = strstr(env, k.key);
       while (f != nullptr && !((f == env || f[-1] == ',') && f[strlen(k.key)] == '=')) f = strstr(f + 1, k.key);
@@ -770,6 +811,7 @@ int pi0_create(const pi0_config* cfg, pi0_ctx** out) {
         if (v >= k.lo && v <= k.hi) *k.dst = v;
       }
     }
+    for (int* v : {&c->tune.pfq, &c->tune.pfa, &c->tune.pfo, &c->tune.pfd}) *v &= ~15;
   }
   // RoPE table (Section 3.2: precomputed): angle = pos * 10000^(-i/128), pairs (i, i+128)
   c->h_rope.resize((size_t)d.maxpos * 128 * 2);

@@ -49,6 +49,46 @@ struct PackSrc {
 };
 
 // ------------------------------------------------------------------------------------------
+// Cache warm-up blocks.  The expert's kernels are short and each reads weights that were last
+// touched one Euler step (600+ MB of traffic) ago, so every kernel starts with HBM-cold misses.
+// A launch may therefore carry extra blocks that do no arithmetic: they read the weights (and
+// cache slices) of the kernels that follow, which pulls them into the memory-side cache and into
+// the L2 of the XCD that will consume them.  Regions are given as `tiles` pieces of `tile16`
+// 16-byte words; piece nt is consumed by the block with linear index nt of the later launch,
+// which the dispatcher places on XCD nt % 8, so warm-up block `rank` (placed on XCD rank % 8 when
+// the launch's compute blocks are a multiple of 8) reads the pieces nt = rank % 8 (mod 8).
+// The values are folded into a word that is compared with a constant, so the loads cannot be
+// elided; results of the pass do not depend on them in any way.
+// ------------------------------------------------------------------------------------------
+struct PrefetchDesc {
+  const void* ptr[3];
+  int tiles[3];
+  int tile16[3];
+  int blocks;        // number of warm-up blocks of the launch, multiple of 16 (0 = none)
+  unsigned* sink;    // [blocks]
+};
+
+static __device__ __forceinline__ void prefetch_role(const PrefetchDesc& d, int rank) {
+  const int xcd = rank & 7, sub = rank >> 3, nsub = d.blocks >> 3;
+  const int step = nsub * (int)blockDim.x;
+  unsigned acc = 0;
+#pragma unroll
+  for (int r = 0; r < 3; r++) {
+    if (d.ptr[r] == nullptr || d.tiles[r] <= xcd) continue;
+    const uint4* base = reinterpret_cast<const uint4*>(d.ptr[r]);
+    const int t16 = d.tile16[r];
+    const int total = ((d.tiles[r] - xcd + 7) >> 3) * t16;
+#pragma unroll 4
+    for (int i = sub * (int)blockDim.x + (int)threadIdx.x; i < total; i += step) {
+      const int j = i / t16;
+      const uint4 v = base[(size_t)(xcd + 8 * j) * t16 + (i - j * t16)];
+      acc ^= v.x ^ v.y ^ v.z ^ v.w;
+    }
+  }
+  if (acc == 0x9e3779b9u) d.sink[rank] = acc;
+}
+
+// ------------------------------------------------------------------------------------------
 // GEMM:  C^T[n][m] = sum_k W'[n][k] * X[m][k]   (weights are the MFMA A operand, tokens the B
 // operand; each lane of the accumulator owns one token and groups of 4 consecutive n).
 // ------------------------------------------------------------------------------------------
@@ -105,6 +145,8 @@ struct GemmParams {
   int q_mbs;          // 32-token blocks per head in the fragment-ordered q buffer
   // EPI_EULER
   float dt;
+  // warm-up blocks for later launches (skinny tiles only)
+  PrefetchDesc pf;
 };
 
 // Tile configuration ids (template instantiations that exist)
@@ -166,6 +208,7 @@ struct AttnParams {
   bf16* out;           // XF layout, out_ld padded columns; head h at columns h * head_dim ..
   int out_ld;
   int head_dim;        // 72 or 256
+  PrefetchDesc pf;     // warm-up blocks for later launches
 };
 hipError_t launch_attention(hipStream_t s, const AttnParams& p);
 hipError_t attention_init_attributes();
