@@ -155,6 +155,46 @@ int pi0_debug_forward(pi0_ctx* ctx, const float* d_images, int n_views, const in
                       int n_prompt, const float* d_state, const float* d_noise, float* d_actions,
                       float* d_taps, size_t cap_elems, void* hip_stream);
 
+/*
+ * Operation classes of the pass, for per-class timing (the rows of Table 2 grouped by launch).
+ */
+enum pi0_op_class {
+  PI0_OP_MISC = 0,        /* copies, patch extraction, embeddings, row statistics */
+  PI0_OP_VIS_PATCH,       /* patch embedding GEMM */
+  PI0_OP_VIS_QKV,         /* LayerNorm-folded QKV projection */
+  PI0_OP_VIS_ATTN,
+  PI0_OP_VIS_O,           /* split-K partial GEMM of the output projection */
+  PI0_OP_VIS_UP,
+  PI0_OP_VIS_DOWN,        /* split-K partial GEMM */
+  PI0_OP_VIS_PROJ,        /* final LayerNorm + projector */
+  PI0_OP_REDUCE,          /* split-K reductions (bias, residual, row statistics) of any stage */
+  PI0_OP_LLM_QKV,         /* RMSNorm-folded QKV + RoPE, writes the key/value cache */
+  PI0_OP_LLM_ATTN,
+  PI0_OP_LLM_O,
+  PI0_OP_LLM_GATEUP,
+  PI0_OP_LLM_DOWN,
+  PI0_OP_EXP_EMBED,       /* folded action/time embedding and its second linear layer */
+  PI0_OP_EXP_QKV,
+  PI0_OP_EXP_ATTN,
+  PI0_OP_EXP_O,
+  PI0_OP_EXP_GATEUP,
+  PI0_OP_EXP_DOWN,
+  PI0_OP_EXP_OUT,         /* final norm, output projection, Euler update */
+  PI0_OP_CLASSES
+};
+
+/*
+ * Timing run: `passes` complete passes (as pi0_infer) launched eagerly with a HIP event pair
+ * around every kernel launch on hip_stream.  Synchronises the stream, then adds the elapsed
+ * microseconds and the launch count of every class to the HOST arrays h_class_us[PI0_OP_CLASSES]
+ * and h_class_launches[PI0_OP_CLASSES] (both are overwritten).  Eager launches: each elapsed time
+ * is the kernel's duration as the stream's timestamps see it, without graph-launch effects.
+ * Errors as pi0_infer; ENOMEM if events cannot be created.
+ */
+int pi0_debug_profile(pi0_ctx* ctx, const float* d_images, int n_views, const int32_t* d_prompt_ids,
+                      int n_prompt, const float* d_state, const float* d_noise, float* d_actions,
+                      int passes, double* h_class_us, int* h_class_launches, void* hip_stream);
+
 /* Graph replay on (1, default) or off (0: every call launches kernels eagerly). */
 int pi0_set_graph_mode(pi0_ctx* ctx, int enabled);
 

@@ -14,8 +14,13 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpi0_hip.so")
 
 EXPORTS = ["pi0_create", "pi0_destroy", "pi0_weights_bytes", "pi0_workspace_bytes", "pi0_load_weights",
-           "pi0_prefill", "pi0_denoise", "pi0_infer", "pi0_debug_taps_elems", "pi0_debug_forward",
+           "pi0_prefill", "pi0_denoise", "pi0_infer", "pi0_debug_taps_elems", "pi0_debug_forward", "pi0_debug_profile",
            "pi0_set_graph_mode", "pi0_kernel_count", "pi0_strerror", "pi0_last_hip_error"]
+
+# enum pi0_op_class, in order
+OP_CLASSES = ["misc", "vis_patch", "vis_qkv", "vis_attn", "vis_o", "vis_up", "vis_down", "vis_proj", "reduce",
+              "llm_qkv", "llm_attn", "llm_o", "llm_gateup", "llm_down", "exp_embed", "exp_qkv", "exp_attn", "exp_o",
+              "exp_gateup", "exp_down", "exp_out"]
 
 PI0_OK, PI0_EINVAL, PI0_ESTATE, PI0_ENOMEM, PI0_EFORMAT, PI0_EHIP = 0, -1, -2, -3, -4, -5
 
@@ -65,6 +70,9 @@ def lib() -> ctypes.CDLL:
         L.pi0_debug_taps_elems.restype = sz
         L.pi0_debug_forward.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp, vp, sz, vp]
         L.pi0_debug_forward.restype = i32
+        L.pi0_debug_profile.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp, i32, ctypes.POINTER(ctypes.c_double),
+                                        ctypes.POINTER(ctypes.c_int), vp]
+        L.pi0_debug_profile.restype = i32
         L.pi0_set_graph_mode.argtypes = [vp, i32]
         L.pi0_set_graph_mode.restype = i32
         L.pi0_kernel_count.argtypes = [vp, i32, i32]
@@ -162,6 +170,14 @@ class Pi0:
         self._check(lib().pi0_debug_forward(self._ctx, _ptr(d_images), n_views, _ptr(d_prompt_ids), n_prompt, _ptr(d_state),
                                             _ptr(d_noise), _ptr(d_actions), _ptr(d_taps), d_taps.numel(),
                                             self._stream(stream)))
+
+    def pi0_debug_profile(self, d_images, n_views, d_prompt_ids, n_prompt, d_state, d_noise, d_actions, passes=1, stream=None):
+        """-> {class name: (total microseconds, launches)} over `passes` eager, event-bracketed passes."""
+        us = (ctypes.c_double * len(OP_CLASSES))()
+        n = (ctypes.c_int * len(OP_CLASSES))()
+        self._check(lib().pi0_debug_profile(self._ctx, _ptr(d_images), n_views, _ptr(d_prompt_ids), n_prompt, _ptr(d_state),
+                                            _ptr(d_noise), _ptr(d_actions), int(passes), us, n, self._stream(stream)))
+        return {name: (float(us[i]), int(n[i])) for i, name in enumerate(OP_CLASSES)}
 
     def pi0_set_graph_mode(self, enabled: bool):
         self._check(lib().pi0_set_graph_mode(self._ctx, 1 if enabled else 0))

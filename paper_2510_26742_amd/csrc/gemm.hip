@@ -670,8 +670,20 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(ReduceParams p) {
   const int ro = m;
   float sa = 0.f, sb = 0.f;
   for (int n = threadIdx.x * 4; n < p.N; n += 1024) {
+    // partial sums in batches of 8 loads in flight (clamped, unconditional), added in slice order
     f32x4 a = {0.f, 0.f, 0.f, 0.f};
-    for (int z = 0; z < p.Z; z++) a += *reinterpret_cast<const f32x4*>(p.part + ((size_t)z * p.M + m) * p.ldp + n);
+    for (int z0 = 0; z0 < p.Z; z0 += 8) {
+      f32x4 v[8];
+#pragma unroll
+      for (int j = 0; j < 8; j++) {
+        const int z = min(z0 + j, p.Z - 1);
+        v[j] = *reinterpret_cast<const f32x4*>(p.part + ((size_t)z * p.M + m) * p.ldp + n);
+      }
+#pragma unroll
+      for (int j = 0; j < 8; j++) {
+        if (z0 + j < p.Z) a += v[j];
+      }
+    }
     if (p.bias != nullptr) a += *reinterpret_cast<const f32x4*>(p.bias + n);
     if (p.resid != nullptr) {
       const int rr = p.resid_mod > 0 ? (m % p.resid_mod) : m;

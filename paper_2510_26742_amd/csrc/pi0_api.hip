@@ -287,13 +287,13 @@ enum { KIND_PREFILL = 0, KIND_DENOISE = 1, KIND_INFER = 2 };
 
 // Per-shape tile choices (Section 4.1 of the paper tunes tiles per GEMM shape; these are the
 // gfx950 counterparts).  Overridable for tuning runs through the environment variable PI0_TUNE,
-// e.g. PI0_TUNE="vis=1,lqkv=1,lgu=0,part=0,zvo=6,zlo=8,zld=16".
+// e.g. PI0_TUNE="vis=1,lqkv=1,lgu=0,vo=1,vd=1,lo=0,ld=0,zvo=6,zlo=8,zld=16".
 struct Tune {
   int vis = TILE_MID;     // vision QKV / up / patch / projector
   int lqkv = TILE_MID;    // prefix QKV
   int lgu = TILE_BIG;     // prefix gate||up
-  int part = TILE_BIG;    // split-K partial GEMMs (O, down of vision and prefix)
-  int zvo = 6, zlo = 8, zld = 16, zvd = 17;
+  int vo = TILE_MID, vd = TILE_MID, lo = TILE_MID, ld = TILE_BIG;   // split-K partial GEMMs: vision O / down, prefix O / down
+  int zvo = 2, zlo = 4, zld = 16, zvd = 4;
   // warm-up blocks carried by the expert's launches (0 = none): QKV, attention, O, down
   int pfq = 64, pfa = 64, pfo = 64, pfd = 64;
 };
@@ -317,16 +317,37 @@ struct pi0_ctx {
 namespace {
 
 // Launch recorder: either launches or only counts.
+struct OpTimer {
+  std::vector<hipEvent_t> ev;   // pairs (before, after)
+  std::vector<int> cls;
+};
 struct Run {
   pi0_ctx* c;
   hipStream_t s;
   bool count_only;
   int launches = 0;
   hipError_t err = hipSuccess;
+  int cls = PI0_OP_MISC;        // class of the launches that follow
+  OpTimer* timer = nullptr;     // when set, every RUN / RUN_GEMM launch is bracketed by an event pair
   bool ok() const { return err == hipSuccess; }
   void did(hipError_t e) {
     launches++;
     if (err == hipSuccess && e != hipSuccess) err = e;
+  }
+  void mark() {
+    if (timer == nullptr || err != hipSuccess) return;
+    hipEvent_t e;
+    hipError_t r = hipEventCreate(&e);
+    if (r == hipSuccess) {
+      timer->ev.push_back(e);
+      r = hipEventRecord(e, s);
+    }
+    if (r != hipSuccess) err = r;
+  }
+  void before() { mark(); }
+  void after() {
+    mark();
+    if (timer != nullptr) timer->cls.push_back(cls);
   }
 };
 
@@ -358,9 +379,9 @@ GemmParams gp_base(pi0_ctx* c, const PW& pw, const bf16* X, int ldx, int M, int 
 }
 
 #define RUN_GEMM(r, tile, pro, epi, p, z) \
-  do { if ((r).count_only) (r).launches++; else if ((r).ok()) (r).did(launch_gemm((r).s, tile, pro, epi, p, z)); } while (0)
+  do { if ((r).count_only) (r).launches++; else if ((r).ok()) { (r).before(); (r).did(launch_gemm((r).s, tile, pro, epi, p, z)); (r).after(); } } while (0)
 #define RUN(r, call) \
-  do { if ((r).count_only) (r).launches++; else if ((r).ok()) (r).did(call); } while (0)
+  do { if ((r).count_only) (r).launches++; else if ((r).ok()) { (r).before(); (r).did(call); (r).after(); } } while (0)
 
 // split-K GEMM into the partial buffer followed by the fixed-order reduction with bias/residual
 void gemm_splitk_resid(Run& r, const PW& pw, const bf16* X, int ldx, int M, int k_true, int z, int k_per_split,
@@ -374,6 +395,8 @@ void gemm_splitk_resid(Run& r, const PW& pw, const bf16* X, int ldx, int M, int 
   p.out_f32 = at<float>(c, c->wl.part);
   p.ldo = pw.n_pad;
   RUN_GEMM(r, tile, PRO_NONE, EPI_PARTIAL, p, z);
+  const int cls_gemm = r.cls;
+  r.cls = PI0_OP_REDUCE;
   ReduceParams q;
   q.part = p.out_f32;
   q.Z = z; q.M = M; q.N = n_true; q.ldp = pw.n_pad;
@@ -386,6 +409,7 @@ void gemm_splitk_resid(Run& r, const PW& pw, const bf16* X, int ldx, int M, int 
   q.out_bf16 = shadow;
   q.ldo = n_true; q.ldo2 = n_true;
   RUN(r, launch_splitk_reduce(r.s, q));
+  r.cls = cls_gemm;
 }
 
 struct Taps {
@@ -405,7 +429,9 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
   const Tune& T = c->tune;
   const int I = n_views * d.T, P = I + n_prompt;
   // A0: patches -> tokens (+bias, +position embedding)
+  r.cls = PI0_OP_MISC;
   RUN(r, launch_patchify(r.s, at<float>(c, w.st_images), n_views, c->cfg.img_size, c->cfg.patch, at<bf16>(c, w.xpatch), d.PDp));
+  r.cls = PI0_OP_VIS_PATCH;
   gemm_splitk_resid(r, w.patch, at<bf16>(c, w.xpatch), d.PDp, I, d.PD, 1, w.patch.k_pad, at<float>(c, w.patch.bias),
                     at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv, T.vis, at<float>(c, w.vstat), at<float>(c, w.g_v1[0]),
                     at<float>(c, w.pos), d.T);
@@ -424,6 +450,7 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
       p.rope = nullptr;
       p.q_cols = d.Dv; p.k_cols = d.Dv;
       p.head_dim = d.hdv; p.dqk_pad = 80; p.nvb = 3; p.kv_heads = d.Hv; p.kv_chunks = vchunks;
+      r.cls = PI0_OP_VIS_QKV;
       RUN_GEMM(r, T.vis, PRO_LN, EPI_QKV, p, 1);
     }
     {  // A2: attention inside each view
@@ -437,11 +464,13 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
       a.view_tokens = d.T;
       a.scale = 1.0f / sqrtf((float)d.hdv);
       a.out = at<bf16>(c, w.vattn); a.out_ld = d.Dv; a.head_dim = d.hdv;
+      r.cls = PI0_OP_VIS_ATTN;
       RUN(r, launch_attention(r.s, a));
     }
     // A3: O-projection + bias + residual
+    r.cls = PI0_OP_VIS_O;
     gemm_splitk_resid(r, L.o, at<bf16>(c, w.vattn), d.Dv, I, d.Dv, T.zvo, round_up(ceil_div(L.o.k_pad, T.zvo), 64),
-                      at<float>(c, L.o.bias), at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv, T.part, at<float>(c, w.vstat),
+                      at<float>(c, L.o.bias), at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv, T.vo, at<float>(c, w.vstat),
                       at<float>(c, w.g_v2[l]));
     {  // A4: LN -> up (+bias, GELU)
       GemmParams p = gp_base(c, L.up, at<bf16>(c, w.vh_b), d.Dv, I, T.vis, d.Dv);
@@ -450,11 +479,13 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
       p.rowstat = at<float>(c, w.vstat);
       p.out_bf16 = at<bf16>(c, w.vmid);
       p.ldo = d.Fv_kp; p.n_valid = L.up.n_pad; p.act = ACT_GELU;
+      r.cls = PI0_OP_VIS_UP;
       RUN_GEMM(r, T.vis, PRO_LN, EPI_BF16, p, 1);
     }
     // A5: down (+bias, residual)
+    r.cls = PI0_OP_VIS_DOWN;
     gemm_splitk_resid(r, L.down, at<bf16>(c, w.vmid), d.Fv_kp, I, d.Fv, T.zvd, round_up(ceil_div(L.down.k_pad, T.zvd), 64),
-                      at<float>(c, L.down.bias), at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv, T.part, at<float>(c, w.vstat),
+                      at<float>(c, L.down.bias), at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv, T.vd, at<float>(c, w.vstat),
                       at<float>(c, l + 1 < d.Lv ? w.g_v1[l + 1] : w.g_vf));
     if (taps) taps->put(r, at<float>(c, w.vh), (size_t)I * d.Dv);
   }
@@ -466,7 +497,9 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
     p.out_f32 = at<float>(c, w.lx);
     p.out_bf16 = at<bf16>(c, w.lx_b);
     p.ldo = d.E; p.ldo2 = d.E; p.n_valid = d.E;
+    r.cls = PI0_OP_VIS_PROJ;
     RUN_GEMM(r, T.vis, PRO_LN, EPI_RESID, p, 1);
+    r.cls = PI0_OP_MISC;
   }
   if (taps) taps->put(r, at<float>(c, w.lx), (size_t)I * d.E);
   if (n_prompt > 0) {  // B0: prompt embeddings after the image tokens
@@ -491,6 +524,7 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
       p.pos0 = 0;
       p.q_cols = last ? 0 : d.H * 256; p.k_cols = 256;
       p.head_dim = 256; p.dqk_pad = 256; p.nvb = 8; p.kv_heads = 1; p.kv_chunks = d.maxPc;
+      r.cls = PI0_OP_LLM_QKV;
       RUN_GEMM(r, T.lqkv, PRO_RMS, EPI_QKV, p, 1);
     }
     if (last) break;
@@ -502,23 +536,27 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
       a.k0 = kc; a.v0 = vc; a.chunks0 = pchunks; a.valid0 = P;
       a.scale = 1.0f / 16.0f;
       a.out = at<bf16>(c, w.lattn); a.out_ld = d.H * 256; a.head_dim = 256;
+      r.cls = PI0_OP_LLM_ATTN;
       RUN(r, launch_attention(r.s, a));
     }
     // B3: O-projection + residual
+    r.cls = PI0_OP_LLM_O;
     gemm_splitk_resid(r, L.o, at<bf16>(c, w.lattn), d.H * 256, P, d.H * 256, T.zlo,
-                      round_up(ceil_div(L.o.k_pad, T.zlo), 64), nullptr, at<float>(c, w.lx), at<bf16>(c, w.lx_b), d.E, T.part,
+                      round_up(ceil_div(L.o.k_pad, T.zlo), 64), nullptr, at<float>(c, w.lx), at<bf16>(c, w.lx_b), d.E, T.lo,
                       at<float>(c, w.lstat), at<float>(c, w.g_l2[l]));
     {  // B4: RMS -> gate||up with fused GELU gate
       GemmParams p = gp_base(c, L.gu, at<bf16>(c, w.lx_b), d.E, P, T.lgu, d.E);
       p.rowstat = at<float>(c, w.lstat);
       p.out_bf16 = at<bf16>(c, w.lmid);
       p.ldo = d.F;
+      r.cls = PI0_OP_LLM_GATEUP;
       RUN_GEMM(r, T.lgu, PRO_RMS, EPI_GEGLU, p, 1);
     }
     // B5: down + residual
+    r.cls = PI0_OP_LLM_DOWN;
     gemm_splitk_resid(r, L.down, at<bf16>(c, w.lmid), d.F, P, d.F, T.zld,
                       round_up(ceil_div(L.down.k_pad, T.zld), 64), nullptr, at<float>(c, w.lx), at<bf16>(c, w.lx_b),
-                      d.E, T.part, at<float>(c, w.lstat), at<float>(c, w.g_l1[l + 1]));
+                      d.E, T.ld, at<float>(c, w.lstat), at<float>(c, w.g_l1[l + 1]));
     if (taps) taps->put(r, at<float>(c, w.lx), (size_t)P * d.E);
   }
   if (taps && taps->base) {
@@ -540,6 +578,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
   const int chunk = c->cfg.chunk;
   const int pchunks = ceil_div(P, 32);
   float* xa = at<float>(c, w.xa);
+  r.cls = PI0_OP_MISC;
   RUN(r, launch_copy_f32(r.s, at<float>(c, w.st_noise), xa, (size_t)chunk * d.A));
   // C0: state token
   RUN(r, launch_state_token(r.s, at<float>(c, w.st_state), d.SD, at<float>(c, w.state_w), at<float>(c, w.state_b), d.X,
@@ -593,6 +632,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
   };
   for (int k = 0; k < d.steps; k++) {
     // C1: folded action/time embedding, SiLU; suffix row 0 <- state token
+    r.cls = PI0_OP_EXP_EMBED;
     RUN(r, launch_action_embed(r.s, xa, chunk, d.A, at<float>(c, w.wfold), at<float>(c, w.bias_tab) + (size_t)k * d.X, d.X,
                                at<bf16>(c, w.z), at<float>(c, w.stok), at<float>(c, w.y), at<bf16>(c, w.y_b)));
     {  // C2: second linear of the action/time MLP -> suffix rows 1..chunk
@@ -603,6 +643,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
       p.ldo = d.X; p.ldo2 = d.X; p.n_valid = d.X; p.row_offset = 1;
       RUN_GEMM(r, TILE_SKINNY, PRO_NONE, EPI_RESID, p, 1);
     }
+    r.cls = PI0_OP_MISC;
     RUN(r, launch_row_stats(r.s, at<float>(c, w.y), d.X, 64, d.X, d.X, at<float>(c, w.g_e1[0]), at<bf16>(c, w.y_b),
                             at<float>(c, w.estat)));
     stat_ptr = at<float>(c, w.estat);
@@ -625,6 +666,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
         p.head_dim = 256; p.dqk_pad = 256; p.nvb = 8; p.kv_heads = 1; p.kv_chunks = 2;
         p.pf = pf_begin(T.pfq);
         pf_weights(p.pf, 0, L.o);
+        r.cls = PI0_OP_EXP_QKV;
         RUN_GEMM(r, TILE_SKINNY, PRO_RMS, EPI_QKV, p, 1);
       }
       {  // C4 + C5: scores, block mask, softmax, PV over [cache ; own keys]
@@ -639,12 +681,14 @@ void run_denoise(Run& r, int P, Taps* taps) {
         a.out = at<bf16>(c, w.eattn); a.out_ld = d.H * 256; a.head_dim = 256;
         a.pf = pf_begin(T.pfa);
         pf_weights(a.pf, 0, L.gu);
+        r.cls = PI0_OP_EXP_ATTN;
         RUN(r, launch_attention(r.s, a));
       }
       // C6: O-projection + residual
       {
         PrefetchDesc f = pf_begin(T.pfo);
         pf_weights(f, 0, L.down);
+        r.cls = PI0_OP_EXP_O;
         resid_gemm(L.o, at<bf16>(c, w.eattn), d.H * 256, at<float>(c, w.g_e2[l]), f);
       }
       {  // C7: RMS -> gate||up, fused gate
@@ -653,6 +697,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
         p.rowstat_parts = stat_parts;
         p.out_bf16 = at<bf16>(c, w.emid);
         p.ldo = d.Fx;
+        r.cls = PI0_OP_EXP_GATEUP;
         RUN_GEMM(r, TILE_SKINNY, PRO_RMS, EPI_GEGLU, p, 1);
       }
       // C8: down + residual
@@ -662,6 +707,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
         PrefetchDesc f = pf_begin(T.pfd);
         pf_weights(f, 0, w.exp[nl].qkv);
         pf_cache(f, 1, nl);
+        r.cls = PI0_OP_EXP_DOWN;
         resid_gemm(L.down, at<bf16>(c, w.emid), d.Fx, at<float>(c, l + 1 < d.Le ? w.g_e1[l + 1] : w.g_ef), f);
       }
       if (tap_this) {
@@ -678,7 +724,9 @@ void run_denoise(Run& r, int P, Taps* taps) {
       p.bias = at<float>(c, w.outp.bias);
       p.out_f32 = xa;
       p.ldo = d.A; p.n_valid = d.A; p.dt = dt;
+      r.cls = PI0_OP_EXP_OUT;
       RUN_GEMM(r, TILE_SKINNY, PRO_RMS, EPI_EULER, p, 1);
+      r.cls = PI0_OP_MISC;
     }
     if (taps && taps->base && !r.count_only && r.ok()) {
       const size_t xoff = tap_step_base + (size_t)2 * d.Le * 64 * d.X + (size_t)k * chunk * d.A;
@@ -795,11 +843,11 @@ int pi0_create(const pi0_config* cfg, pi0_ctx** out) {
   c->d = d;
   blob_layout(*cfg, d, c->bl);
   ws_layout(*cfg, d, c->wl);
-  c->tune.zvd = ceil_div(d.Fv_kp / 64, 4);
+
   if (const char* env = getenv("PI0_TUNE")) {
     struct { const char* key; int* dst; int lo, hi; } keys[] = {
         {"vis", &c->tune.vis, 0, 1},   {"lqkv", &c->tune.lqkv, 0, 1}, {"lgu", &c->tune.lgu, 0, 1},
-        {"part", &c->tune.part, 0, 1}, {"zvo", &c->tune.zvo, 1, Z_MAX}, {"zlo", &c->tune.zlo, 1, Z_MAX},
+        {"vo", &c->tune.vo, 0, 1}, {"vd", &c->tune.vd, 0, 1}, {"lo", &c->tune.lo, 0, 1}, {"ld", &c->tune.ld, 0, 1}, {"zvo", &c->tune.zvo, 1, Z_MAX}, {"zlo", &c->tune.zlo, 1, Z_MAX},
         {"zld", &c->tune.zld, 1, Z_MAX}, {"zvd", &c->tune.zvd, 1, Z_MAX},
         {"pfq", &c->tune.pfq, 0, 1024}, {"pfa", &c->tune.pfa, 0, 1024}, {"pfo", &c->tune.pfo, 0, 1024},
         {"pfd", &c->tune.pfd, 0, 1024}};
@@ -1067,6 +1115,53 @@ int pi0_debug_forward(pi0_ctx* c, const float* d_images, int n_views, const int3
   run_prefill(r, n_views, n_prompt, &taps);
   run_denoise(r, n_views * c->d.T + n_prompt, &taps);
   if (!r.ok()) return fail_hip(c, r.err);
+  c->cur_views = n_views;
+  c->cur_prompt = n_prompt;
+  e = launch_copy_f32(s, at<float>(c, c->wl.xa), d_actions, (size_t)c->cfg.chunk * c->d.A);
+  return e == hipSuccess ? PI0_OK : fail_hip(c, e);
+}
+
+int pi0_debug_profile(pi0_ctx* c, const float* d_images, int n_views, const int32_t* d_prompt_ids, int n_prompt,
+                      const float* d_state, const float* d_noise, float* d_actions, int passes, double* h_class_us,
+                      int* h_class_launches, void* hip_stream) {
+  if (c == nullptr || d_state == nullptr || d_noise == nullptr || d_actions == nullptr || h_class_us == nullptr ||
+      h_class_launches == nullptr || passes < 1 || passes > 64)
+    return PI0_EINVAL;
+  if (!check_prefill_args(c, d_images, n_views, d_prompt_ids, n_prompt)) return PI0_EINVAL;
+  if (!c->loaded) return PI0_ESTATE;
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  for (int i = 0; i < PI0_OP_CLASSES; i++) {
+    h_class_us[i] = 0.0;
+    h_class_launches[i] = 0;
+  }
+  c->cur_views = 0;
+  hipError_t e = stage_inputs(c, s, d_images, n_views, d_prompt_ids, n_prompt, d_state, d_noise);
+  if (e != hipSuccess) return fail_hip(c, e);
+  OpTimer timer;
+  int rc = PI0_OK;
+  for (int pass = 0; pass < passes && rc == PI0_OK; pass++) {
+    Run r{c, s, false};
+    r.timer = &timer;
+    run_prefill(r, n_views, n_prompt, nullptr);
+    run_denoise(r, n_views * c->d.T + n_prompt, nullptr);
+    if (!r.ok()) rc = fail_hip(c, r.err);
+  }
+  e = hipStreamSynchronize(s);
+  if (e != hipSuccess && rc == PI0_OK) rc = fail_hip(c, e);
+  if (rc == PI0_OK) {
+    for (size_t i = 0; i < timer.cls.size() && 2 * i + 1 < timer.ev.size(); i++) {
+      float ms = 0.f;
+      e = hipEventElapsedTime(&ms, timer.ev[2 * i], timer.ev[2 * i + 1]);
+      if (e != hipSuccess) {
+        rc = fail_hip(c, e);
+        break;
+      }
+      h_class_us[timer.cls[i]] += (double)ms * 1000.0;
+      h_class_launches[timer.cls[i]] += 1;
+    }
+  }
+  for (hipEvent_t ev : timer.ev) (void)hipEventDestroy(ev);
+  if (rc != PI0_OK) return rc;
   c->cur_views = n_views;
   c->cur_prompt = n_prompt;
   e = launch_copy_f32(s, at<float>(c, c->wl.xa), d_actions, (size_t)c->cfg.chunk * c->d.A);

@@ -100,3 +100,78 @@ def weight_bytes(ops: List[Op], stage: str | None = None) -> float:
 
 def total_macs(ops: List[Op], stage: str | None = None) -> float:
     return sum(o.macs for o in ops if stage is None or o.stage == stage)
+
+
+MI355X_FLOPS = 2.5e15         # dense bf16 MFMA FLOP/s
+
+
+def class_work(cfg, n_views: int, n_prompt: int = 0) -> dict:
+    """Algorithmic work of ONE launch of every operation class the library times
+    (binding.OP_CLASSES): name -> (bytes, flops).
+
+    Bytes are what the operation must move if every operand crossed HBM exactly once: the bf16
+    weight matrix, the bf16 input activations, and the final outputs (fp32 residual read and
+    write plus its bf16 copy for residual projections, bf16 otherwise; keys and values for the
+    attention rows).  Split-K partial sums are an implementation artefact and are not counted;
+    the reduction launches and the small non-GEMM launches ("reduce", "misc") have no entry.
+    """
+    T = cfg.tokens_per_view
+    I = n_views * T
+    P = I + n_prompt
+    S = cfg.suffix
+    Dv, Fv = cfg.vis_width, cfg.vis_mlp
+    E, H, Dh, F = cfg.llm_width, cfg.llm_q_heads, cfg.head_dim, cfg.llm_mlp
+    X, Fx = cfg.exp_width, cfg.exp_mlp
+
+    def gemm(m, k, n, out_bytes):
+        return (2.0 * k * n + 2.0 * m * k + out_bytes, 2.0 * m * k * n)
+
+    def resid(m, n):            # fp32 residual in and out, bf16 copy
+        return m * n * (4 + 4 + 2)
+
+    qkv_n = (H + 2) * Dh
+    return {
+        "vis_patch": gemm(I, cfg.patch_dim, Dv, resid(I, Dv)),
+        "vis_qkv": gemm(I, Dv, 3 * Dv, 2.0 * I * 3 * Dv),
+        "vis_attn": (2.0 * I * Dv * 4, 2.0 * 2 * I * T * Dv),
+        "vis_o": gemm(I, Dv, Dv, resid(I, Dv)),
+        "vis_up": gemm(I, Dv, Fv, 2.0 * I * Fv),
+        "vis_down": gemm(I, Fv, Dv, resid(I, Dv)),
+        "vis_proj": gemm(I, Dv, E, I * E * 6.0),
+        "llm_qkv": gemm(P, E, qkv_n, 2.0 * P * qkv_n),
+        "llm_attn": (2.0 * P * H * Dh * 2 + 2.0 * P * Dh * 2, 2.0 * 2 * H * P * P * Dh),
+        "llm_o": gemm(P, H * Dh, E, resid(P, E)),
+        "llm_gateup": gemm(P, E, 2 * F, 2.0 * P * F),
+        "llm_down": gemm(P, F, E, resid(P, E)),
+        "exp_qkv": gemm(S, X, qkv_n, 2.0 * S * qkv_n),
+        "exp_attn": (2.0 * S * H * Dh * 2 + 2.0 * (P + S) * Dh * 2, 2.0 * 2 * H * S * (P + S) * Dh),
+        "exp_o": gemm(S, H * Dh, X, resid(S, X)),
+        "exp_gateup": gemm(S, X, 2 * Fx, 2.0 * S * Fx),
+        "exp_down": gemm(S, Fx, X, resid(S, X)),
+        "exp_out": gemm(S, X, cfg.action_dim, 8.0 * cfg.chunk * cfg.action_dim),
+    }
+
+
+def class_rooflines(work: dict, timing: dict) -> list:
+    """work: class_work(); timing: {class: (total_us, launches)} -> rows sorted by total time, each with
+    the class's bound ("hbm" or "mfma"), its achieved rate against the MI355X peak, and the fraction."""
+    rows = []
+    for name, (total_us, launches) in timing.items():
+        if launches == 0:
+            continue
+        avg_us = total_us / launches
+        row = {"class": name, "launches": launches, "avg_us": round(avg_us, 3), "total_us": round(total_us, 1)}
+        if name in work:
+            b, f = work[name]
+            t_mem, t_cmp = b / MI355X_BW, f / MI355X_FLOPS
+            if t_mem >= t_cmp:
+                ach = b / (avg_us * 1e-6) / 1e9
+                row.update(bound="hbm", achieved=round(ach, 1), peak=MI355X_BW / 1e9, unit="GB/s",
+                           frac=round(ach / (MI355X_BW / 1e9), 4), algorithmic_bytes=int(b))
+            else:
+                ach = f / (avg_us * 1e-6) / 1e12
+                row.update(bound="mfma", achieved=round(ach, 1), peak=MI355X_FLOPS / 1e12, unit="TFLOP/s",
+                           frac=round(ach / (MI355X_FLOPS / 1e12), 4), algorithmic_flops=int(f))
+        rows.append(row)
+    rows.sort(key=lambda r: -r["total_us"])
+    return rows
