@@ -42,6 +42,8 @@ def main() -> int:
     ap.add_argument("--reduced", action="store_true", help="reduced-depth model (parity config, not the metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--views", type=int, default=1, help="views of the headline workload")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 1 GiB device-to-device copy (reference point for hardware counter runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (batch-1 latency path, no sharding); use --gpus 1",
@@ -68,6 +70,15 @@ def main() -> int:
     del d_blob
     torch.cuda.empty_cache()
     log("[bench] weights packed")
+
+    if args.copy_calibration:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)          # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
 
     state = torch.from_numpy(synth.make_state(cfg)).to(dev)
     noise = torch.from_numpy(synth.make_noise(cfg)).to(dev)
