@@ -27,7 +27,10 @@ KERNEL_SYMBOL = {
     "exp_gateup": "gemm_skinny_kernel<1, 4>", "exp_qkv": "gemm_skinny_kernel<1, 3>",
     "exp_attn": "attention_kernel<256, 8, *, *>", "llm_gateup": "gemm_kernel<8, 4, 3, 1, 4>",
 }
-PMC_TRAFFIC_BYTES = {}
+PMC_TRAFFIC_BYTES = {   # profiles/counters_full_pi0_1view_eager_pass.txt (includes what the launch reads ahead)
+    "exp_down": 18929664, "exp_gateup": 18613248, "exp_o": 15499264, "exp_qkv": 11216077, "exp_attn": 20117299,
+    "llm_gateup": 151370342,
+}
 
 
 def log(*a):
@@ -42,8 +45,9 @@ def main() -> int:
     ap.add_argument("--reduced", action="store_true", help="reduced-depth model (parity config, not the metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--views", type=int, default=1, help="views of the headline workload")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run one 1 GiB device-to-device copy (reference point for hardware counter runs)")
+    ap.add_argument("--counters-pass", action="store_true",
+                    help="for hardware-counter runs: one 1 GiB device-to-device copy (calibration point) and ONE "
+                         "eager pass (no graph, no timing), then exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (batch-1 latency path, no sharding); use --gpus 1",
@@ -71,18 +75,23 @@ def main() -> int:
     torch.cuda.empty_cache()
     log("[bench] weights packed")
 
-    if args.copy_calibration:
+    state = torch.from_numpy(synth.make_state(cfg)).to(dev)
+    noise = torch.from_numpy(synth.make_noise(cfg)).to(dev)
+    actions = torch.empty((cfg.chunk, cfg.action_dim), dtype=torch.float32, device=dev)
+
+    if args.counters_pass:
         src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
         torch.cuda.synchronize()
         dst.copy_(src)          # reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
-        del src, dst
-        torch.cuda.empty_cache()
-
-    state = torch.from_numpy(synth.make_state(cfg)).to(dev)
-    noise = torch.from_numpy(synth.make_noise(cfg)).to(dev)
-    actions = torch.empty((cfg.chunk, cfg.action_dim), dtype=torch.float32, device=dev)
+        images = torch.from_numpy(synth.make_images(cfg, args.views)).to(dev)
+        m.pi0_set_graph_mode(False)
+        m.pi0_infer(images, args.views, None, 0, state, noise, actions, stream)
+        stream.synchronize()
+        print(json.dumps({"mode": "counters-pass", "views": args.views, "copy_bytes_each_way": 1 << 30}), flush=True)
+        m.close()
+        return 0
 
     def time_views(n_views: int, steps: int, warmup: int):
         images = torch.from_numpy(synth.make_images(cfg, n_views)).to(dev)

@@ -52,11 +52,11 @@ struct PackSrc {
 // Cache warm-up blocks.  The expert's kernels are short and each reads weights that were last
 // touched one Euler step (600+ MB of traffic) ago, so every kernel starts with HBM-cold misses.
 // A launch may therefore carry extra blocks that do no arithmetic: they read the weights (and
-// cache slices) of the kernels that follow, which pulls them into the memory-side cache and into
-// the L2 of the XCD that will consume them.  Regions are given as `tiles` pieces of `tile16`
-// 16-byte words; piece nt is consumed by the block with linear index nt of the later launch,
-// which the dispatcher places on XCD nt % 8, so warm-up block `rank` (placed on XCD rank % 8 when
-// the launch's compute blocks are a multiple of 8) reads the pieces nt = rank % 8 (mod 8).
+// cache slices) of the kernels that follow, which pulls them into the 256 MB memory-side cache;
+// the consumer then misses L2 (whose contents do not survive a kernel boundary) but not HBM.
+// Regions are given as `tiles` pieces of `tile16` 16-byte words; warm-up block `rank` reads the
+// pieces nt = rank % 8 (mod 8), i.e. the ones whose consumer block would run on the same XCD
+// under round-robin dispatch (that only matters if a later hardware keeps L2 across launches).
 // The values are folded into a word that is compared with a constant, so the loads cannot be
 // elided; results of the pass do not depend on them in any way.
 // ------------------------------------------------------------------------------------------
