@@ -405,13 +405,6 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
   // producer); wave w adds parts w, w+8, ... for row `lane`, the epilogue adds the 8 wave sums
   float* sstat = red + SK_WAVES * 2 * 16 * 64;     // [64 rows][2] after the reduction below
   float* sstat8 = sstat + 128;                     // [8 waves][64][2]
-  float pa = 0.f, pb = 0.f;
-  if (PRO != PRO_NONE) {
-    for (int j = w; j < p.rowstat_parts; j += SK_WAVES) {
-      pa += p.rowstat[((size_t)j * 64 + lane) * 2];
-      pb += p.rowstat[((size_t)j * 64 + lane) * 2 + 1];
-    }
-  }
   bf16x8 wf[8], xf[2][8];
   const bf16* wbase = p.W.w + ((size_t)nt * KC16 + (kbeg >> 4)) * 512 + lane * 8;
   const bf16* xbase = p.X + (size_t)(kbeg >> 4) * 512 + lane * 8;
@@ -422,6 +415,15 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
     wf[i] = *reinterpret_cast<const bf16x8*>(wbase + (size_t)st * 512);
     xf[0][i] = *reinterpret_cast<const bf16x8*>(xbase + (size_t)st * 512);
     xf[1][i] = *reinterpret_cast<const bf16x8*>(xbase + ((size_t)mb1 * XKC16 + st) * 512);
+  }
+  // statistics partials: issued behind the operand loads (same round trip), clamped and unconditional
+  float2 sp[4];
+  if (PRO != PRO_NONE) {
+#pragma unroll
+    for (int jj = 0; jj < 4; jj++) {
+      const int j = min(w + SK_WAVES * jj, p.rowstat_parts - 1);
+      sp[jj] = *reinterpret_cast<const float2*>(p.rowstat + ((size_t)j * 64 + lane) * 2);
+    }
   }
   f32x16 acc[2];
 #pragma unroll
@@ -440,6 +442,14 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
 #pragma unroll
     for (int r = 0; r < 16; r++) red[(((size_t)w * 2 + mb) * 16 + r) * 64 + lane] = acc[mb][r];
   if (PRO != PRO_NONE) {
+    float pa = 0.f, pb = 0.f;
+#pragma unroll
+    for (int jj = 0; jj < 4; jj++) {
+      if (w + SK_WAVES * jj < p.rowstat_parts) {
+        pa += sp[jj].x;
+        pb += sp[jj].y;
+      }
+    }
     sstat8[(w * 64 + lane) * 2] = pa;
     sstat8[(w * 64 + lane) * 2 + 1] = pb;
   }
@@ -635,7 +645,7 @@ hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmPara
     return hipGetLastError();
   }
   if (tile == TILE_SKINNY) {
-    if (pro != PRO_NONE && p.rowstat_parts < 1) return hipErrorInvalidValue;
+    if (pro != PRO_NONE && (p.rowstat_parts < 1 || p.rowstat_parts > 4 * SK_WAVES)) return hipErrorInvalidValue;
     if (p.M > 64 || p.m_tiles != 1 || p.k_per_split > SK_KMAX || p.k_per_split % 16 != 0) return hipErrorInvalidValue;
 #define X(PRO, EPI)                                                                                          \
   if (pro == PRO && epi == EPI) {                                                                            \
@@ -670,6 +680,14 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(ReduceParams p) {
   const int ro = m;
   float sa = 0.f, sb = 0.f;
   for (int n = threadIdx.x * 4; n < p.N; n += 1024) {
+    // bias and residual first, so that their round trip overlaps the partial sums
+    f32x4 extra = {0.f, 0.f, 0.f, 0.f};
+    if (p.bias != nullptr) extra = *reinterpret_cast<const f32x4*>(p.bias + n);
+    f32x4 rv = {0.f, 0.f, 0.f, 0.f};
+    if (p.resid != nullptr) {
+      const int rr = p.resid_mod > 0 ? (m % p.resid_mod) : m;
+      rv = *reinterpret_cast<const f32x4*>(p.resid + (size_t)rr * p.ldo + n);
+    }
     // partial sums in batches of 8 loads in flight (clamped, unconditional), added in slice order
     f32x4 a = {0.f, 0.f, 0.f, 0.f};
     for (int z0 = 0; z0 < p.Z; z0 += 8) {
@@ -684,11 +702,8 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(ReduceParams p) {
         if (z0 + j < p.Z) a += v[j];
       }
     }
-    if (p.bias != nullptr) a += *reinterpret_cast<const f32x4*>(p.bias + n);
-    if (p.resid != nullptr) {
-      const int rr = p.resid_mod > 0 ? (m % p.resid_mod) : m;
-      a += *reinterpret_cast<const f32x4*>(p.resid + (size_t)rr * p.ldo + n);
-    }
+    a += extra;    // same order of additions as ever: partial sums, bias, residual
+    a += rv;
     *reinterpret_cast<f32x4*>(p.out_f32 + (size_t)ro * p.ldo + n) = a;
 #pragma unroll
     for (int j = 0; j < 4; j++) {

@@ -285,8 +285,21 @@ __global__ __launch_bounds__(256) void action_embed_kernel(const float* x, int c
   const int r = blockIdx.y;
   if (n >= X) return;
   if (r < chunk) {
+    // loads in batches of 8 (independent), accumulated in index order
     float acc = bias_k[n];
-    for (int j = 0; j < A; j++) acc += x[(size_t)r * A + j] * wfold[(size_t)j * X + n];
+    for (int j0 = 0; j0 < A; j0 += 8) {
+      float wv[8], xv[8];
+#pragma unroll
+      for (int u = 0; u < 8; u++) {
+        const int j = min(j0 + u, A - 1);
+        wv[u] = wfold[(size_t)j * X + n];
+        xv[u] = x[(size_t)r * A + j];
+      }
+#pragma unroll
+      for (int u = 0; u < 8; u++) {
+        if (j0 + u < A) acc += xv[u] * wv[u];
+      }
+    }
     const float sv = acc / (1.0f + __expf(-acc));
     z[xf_index(r, n, X >> 4)] = (bf16)sv;
   } else {
