@@ -45,12 +45,45 @@ __device__ __forceinline__ size_t xf_index(int m, int k, int kc16) {
   return ((size_t)(m >> 5) * kc16 + (k >> 4)) * 512 + (((k & 15) >> 3) * 32 + (m & 31)) * 8 + (k & 7);
 }
 
+// Operands of the epilogue that come from memory (bias, column sums, residual / RoPE table, gain),
+// loaded ahead of time: a kernel calls epilogue_preload as early as it knows its (tile, row), so
+// that the round trip overlaps the main loop instead of following it.
+struct EpiOps {
+  f32x4 bias[4], colsum[4], aux[4], gain[4];
+};
+
+template <int PRO, int EPI>
+__device__ __forceinline__ void epilogue_preload(const GemmParams& p, int nt, int m, int lh, EpiOps& o) {
+  if (EPI == EPI_PARTIAL) return;
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    const int n4 = nt * 32 + 8 * i + 4 * lh;
+    if (PRO == PRO_LN) o.colsum[i] = *reinterpret_cast<const f32x4*>(p.colsum + n4);
+    if (p.bias != nullptr) o.bias[i] = *reinterpret_cast<const f32x4*>(p.bias + n4);
+    if (EPI == EPI_RESID) {
+      if (n4 < p.n_valid) {
+        if (p.resid != nullptr) {
+          const int rr = p.resid_mod > 0 ? (m % p.resid_mod) : m;
+          o.aux[i] = *reinterpret_cast<const f32x4*>(p.resid + (size_t)rr * p.ldo + n4);
+        }
+        if (p.gain != nullptr) o.gain[i] = *reinterpret_cast<const f32x4*>(p.gain + n4);
+      }
+    } else if (EPI == EPI_QKV) {
+      if (p.rope != nullptr && n4 < p.q_cols + p.k_cols) {
+        const int nl = n4 < p.q_cols ? n4 : n4 - p.q_cols;
+        const int i0 = (nl & 255) >> 1;
+        o.aux[i] = *reinterpret_cast<const f32x4*>(p.rope + ((size_t)(p.pos0 + m) * 128 + i0) * 2);
+      }
+    }
+  }
+}
+
 // One 32-token x 32-feature accumulator tile -> memory.  `acc` is the MFMA accumulator of the
 // calling lane (token = lane % 32, features nt*32 + 8*(r/4) + 4*(lane/32) + r%4), `m` the global
 // row, (s_sum, s_sq) the row's sum and sum of squares over the true k columns.
 template <int PRO, int EPI>
 __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16& acc, int nt, int m, int lh,
-                                              float s_sum, float s_sq, int zsplit) {
+                                              float s_sum, float s_sq, int zsplit, const EpiOps& ops) {
   const float inv_k = 1.0f / (float)p.k_true;
   {
     float rs = 1.f, mu = 0.f;
@@ -77,20 +110,19 @@ __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16&
 #pragma unroll
         for (int j = 0; j < 4; j++) v[j] *= rs;
       } else if (PRO == PRO_LN) {
-        const f32x4 cs = *reinterpret_cast<const f32x4*>(p.colsum + n4);
+        const f32x4 cs = ops.colsum[i];
 #pragma unroll
         for (int j = 0; j < 4; j++) v[j] = rs * (v[j] - mu * cs[j]);
       }
       if (p.bias != nullptr) {
-        const f32x4 bb = *reinterpret_cast<const f32x4*>(p.bias + n4);
+        const f32x4 bb = ops.bias[i];
 #pragma unroll
         for (int j = 0; j < 4; j++) v[j] += bb[j];
       }
       if (EPI == EPI_RESID) {
         if (n4 < p.n_valid) {
           if (p.resid != nullptr) {
-            const int rr = p.resid_mod > 0 ? (m % p.resid_mod) : m;
-            const f32x4 r4 = *reinterpret_cast<const f32x4*>(p.resid + (size_t)rr * p.ldo + n4);
+            const f32x4 r4 = ops.aux[i];
 #pragma unroll
             for (int j = 0; j < 4; j++) v[j] += r4[j];
           }
@@ -103,7 +135,7 @@ __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16&
             st_b += v[j] * v[j];
           }
           if (p.gain != nullptr) {
-            const f32x4 g4 = *reinterpret_cast<const f32x4*>(p.gain + n4);
+            const f32x4 g4 = ops.gain[i];
 #pragma unroll
             for (int j = 0; j < 4; j++) v[j] *= g4[j];
           }
@@ -140,8 +172,7 @@ __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16&
             // packed head layout: row 2i = dim i, row 2i+1 = dim i + 128
             const int head = nl >> 8;
             const int i0 = (nl & 255) >> 1;          // even
-            const float* cs = p.rope + ((size_t)(p.pos0 + m) * 128 + i0) * 2;
-            const f32x4 c4 = *reinterpret_cast<const f32x4*>(cs);   // cos i0, sin i0, cos i0+1, sin i0+1
+            const f32x4 c4 = ops.aux[i];   // cos i0, sin i0, cos i0+1, sin i0+1
             const float lo0 = v[0] * c4[0] - v[1] * c4[1], hi0 = v[1] * c4[0] + v[0] * c4[1];
             const float lo1 = v[2] * c4[2] - v[3] * c4[3], hi1 = v[3] * c4[2] + v[2] * c4[3];
             const bf16x2 lo = {(bf16)lo0, (bf16)lo1};
@@ -363,7 +394,9 @@ __global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(1, 1)))
         ssum = p.rowstat[2 * m];
         ssq = p.rowstat[2 * m + 1];
       }
-      epilogue_tile<PRO, EPI>(p, acc[mb], nt, m, lh, ssum, ssq, blockIdx.y);
+      EpiOps ops;
+      epilogue_preload<PRO, EPI>(p, nt, m, lh, ops);
+      epilogue_tile<PRO, EPI>(p, acc[mb], nt, m, lh, ssum, ssq, blockIdx.y, ops);
     }
   }
 }
@@ -425,6 +458,9 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
       sp[jj] = *reinterpret_cast<const float2*>(p.rowstat + ((size_t)j * 64 + lane) * 2);
     }
   }
+  // operands of the epilogue (waves 0 and 1 run it), in the same round trip
+  EpiOps ops;
+  if (w < 2 && w * 32 + lq < p.M) epilogue_preload<PRO, EPI>(p, nt, w * 32 + lq, lh, ops);
   f32x16 acc[2];
 #pragma unroll
   for (int mb = 0; mb < 2; mb++)
@@ -481,7 +517,7 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
       ssum = sstat[ml * 2];
       ssq = sstat[ml * 2 + 1];
     }
-    epilogue_tile<PRO, EPI>(p, sum, nt, ml, lh, ssum, ssq, blockIdx.y);
+    epilogue_tile<PRO, EPI>(p, sum, nt, ml, lh, ssum, ssq, blockIdx.y, ops);
   }
 }
 
@@ -509,9 +545,12 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_fullk_kernel(GemmPa
   const int spw = 16 * NB;                     // steps per wave; host guarantees KC16 == 8 * spw
   const bf16* wbase = p.W.w + ((size_t)nt * KC16 + (size_t)w * spw) * 512 + lane * 8;
   const bf16* xbase = p.X + ((size_t)mb * XKC16 + (size_t)w * spw) * 512 + lane * 8;
-  f32x16 acc;
+  // two accumulators: consecutive MFMAs do not wait for each other
+  f32x16 acc, acc1;
 #pragma unroll
-  for (int r = 0; r < 16; r++) acc[r] = 0.f;
+  for (int r = 0; r < 16; r++) acc[r] = 0.f, acc1[r] = 0.f;
+  EpiOps ops;
+  const int m = mb * 32 + lq;
 #pragma unroll
   for (int b = 0; b < NB; b++) {
     bf16x8 wf[16], xf[16];
@@ -520,11 +559,16 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_fullk_kernel(GemmPa
       wf[i] = *reinterpret_cast<const bf16x8*>(wbase + (size_t)(b * 16 + i) * 512);
       xf[i] = *reinterpret_cast<const bf16x8*>(xbase + (size_t)(b * 16 + i) * 512);
     }
+    // operands of the epilogue (wave 0 runs it), behind the first batch of operand loads
+    if (b == 0 && w == 0 && m < p.M) epilogue_preload<PRO_NONE, EPI_RESID>(p, nt, m, lh, ops);
 #pragma unroll
-    for (int i = 0; i < 16; i++) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[i], acc, 0, 0, 0);
+    for (int i = 0; i < 16; i += 2) {
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[i], acc, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i + 1], xf[i + 1], acc1, 0, 0, 0);
+    }
   }
 #pragma unroll
-  for (int r = 0; r < 16; r++) red[((size_t)w * 16 + r) * 64 + lane] = acc[r];
+  for (int r = 0; r < 16; r++) red[((size_t)w * 16 + r) * 64 + lane] = acc[r] + acc1[r];
   __syncthreads();
   if (w != 0) return;
   f32x16 sum;
@@ -534,8 +578,7 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_fullk_kernel(GemmPa
   for (int ww = 0; ww < SK_WAVES; ww++)
 #pragma unroll
     for (int r = 0; r < 16; r++) sum[r] += red[((size_t)ww * 16 + r) * 64 + lane];
-  const int m = mb * 32 + lq;
-  if (m < p.M) epilogue_tile<PRO_NONE, EPI_RESID>(p, sum, nt, m, lh, 0.f, 0.f, 0);
+  if (m < p.M) epilogue_tile<PRO_NONE, EPI_RESID>(p, sum, nt, m, lh, 0.f, 0.f, 0, ops);
 }
 
 static constexpr int skinny_smem_bytes() { return (SK_WAVES * 2 * 16 * 64 + 128 + SK_WAVES * 128) * 4; }
