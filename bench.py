@@ -150,6 +150,17 @@ def main() -> int:
             ("%s %.1f %s = %.3f of peak" % (r["bound"], r["achieved"], r["unit"], r["frac"])) if "bound" in r else ""))
     dominant = next(r for r in rows if "bound" in r)
 
+    # Table 3's experiment on this machine: 1378 dependent A+B updates under different orderings
+    sx = torch.zeros((256, 1024), dtype=torch.float32, device=dev)
+    sb = torch.ones((256, 1024), dtype=torch.float32, device=dev)
+    sstate = torch.zeros(2, dtype=torch.int32, device=dev)
+    torch.cuda.synchronize()
+    sync_ms = {}
+    for mode in ("eager", "graph", "barrier", "barrier_fence", "fused"):
+        binding.pi0_sync_bench(mode, 1378, 1, sx, sb, sstate, stream)          # warm-up
+        sync_ms[mode] = round(binding.pi0_sync_bench(mode, 1378, 5, sx, sb, sstate, stream), 4)
+    log("[bench] sync overhead, ms per 1378 updates: " + ", ".join(f"{k} {v:.3f}" for k, v in sync_ms.items()))
+
     # whole-pass roofline: algorithmic HBM bytes = every weight matrix once per use (Section 5.1)
     ops = roofline.table2_ops(cfg, headline_views, 0, joint_vision_attention=False)
     algo_bytes = roofline.weight_bytes(ops)
@@ -188,6 +199,9 @@ def main() -> int:
                      "avg_us": dominant["avg_us"], "launches_per_pass": dominant["launches"] // 3,
                      "algorithmic": dominant.get("algorithmic_bytes", dominant.get("algorithmic_flops"))},
         "roofline_classes": rows,
+        # Section 5.2: ms for 1378 dependent updates; the paper's RTX 4090 figures for the same experiment
+        "sync_overhead_ms": {"mi355x": sync_ms, "extra_per_graph_node_us": round((sync_ms["graph"] - sync_ms["fused"]) / 1.378, 3),
+                             "paper_rtx4090": {"eager": 13.81, "graph": 2.61, "barrier": 1.75, "fused": 0.89}},
         # the whole pass against the paper's roofline model (weights once per use, Section 5.1)
         "roofline_pass": {"bound": "hbm", "achieved": round(achieved, 1), "peak": 8000.0, "unit": "GB/s",
                           "frac": round(achieved / 8000.0, 4), "algorithmic_bytes": int(algo_bytes),

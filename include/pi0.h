@@ -195,6 +195,31 @@ int pi0_debug_profile(pi0_ctx* ctx, const float* d_images, int n_views, const in
                       int n_prompt, const float* d_state, const float* d_noise, float* d_actions,
                       int passes, double* h_class_us, int* h_class_launches, void* hip_stream);
 
+/*
+ * Synchronisation-overhead micro-benchmark (Section 5.2, Table 3 of the paper; no ctx needed).
+ * Applies x <- x + b to a 256 x 1024 fp32 array n_ops times per repetition, `reps` repetitions,
+ * one 256-thread block per row, with consecutive updates ordered by
+ *   PI0_SYNC_EAGER          n_ops separate kernel launches
+ *   PI0_SYNC_GRAPH          one hipGraph of n_ops kernel nodes (captured on hip_stream, which must not be NULL)
+ *   PI0_SYNC_BARRIER        one kernel, software grid barrier with relaxed atomics between updates
+ *   PI0_SYNC_BARRIER_FENCE  same with release / acquire at device scope (what dependent data would need)
+ *   PI0_SYNC_FUSED          one kernel, no synchronisation (the baseline)
+ * d_x, d_b: device, float32 [256][1024], 16-byte aligned; afterwards x = x0 + reps * n_ops * b exactly
+ * (for values that are exact in fp32).  d_state: device, 2 x uint32 scratch (cleared by the call).
+ * h_ms: HOST, receives the milliseconds of one repetition (HIP events on hip_stream, averaged over
+ * reps).  The call synchronises the stream.  Barrier waits are bounded: if one runs out, or the
+ * device has fewer compute units than blocks, the result is PI0_ESTATE.  Other errors: EINVAL, EHIP.
+ */
+enum pi0_sync_mode {
+  PI0_SYNC_EAGER = 0,
+  PI0_SYNC_GRAPH = 1,
+  PI0_SYNC_BARRIER = 2,
+  PI0_SYNC_BARRIER_FENCE = 3,
+  PI0_SYNC_FUSED = 4
+};
+int pi0_sync_bench(int mode, int n_ops, int reps, float* d_x, const float* d_b, unsigned* d_state,
+                   double* h_ms, void* hip_stream);
+
 /* Graph replay on (1, default) or off (0: every call launches kernels eagerly). */
 int pi0_set_graph_mode(pi0_ctx* ctx, int enabled);
 

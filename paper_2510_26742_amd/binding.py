@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpi0_hip.so")
 
 EXPORTS = ["pi0_create", "pi0_destroy", "pi0_weights_bytes", "pi0_workspace_bytes", "pi0_load_weights",
-           "pi0_prefill", "pi0_denoise", "pi0_infer", "pi0_debug_taps_elems", "pi0_debug_forward", "pi0_debug_profile",
+           "pi0_prefill", "pi0_denoise", "pi0_infer", "pi0_debug_taps_elems", "pi0_debug_forward", "pi0_debug_profile", "pi0_sync_bench",
            "pi0_set_graph_mode", "pi0_kernel_count", "pi0_strerror", "pi0_last_hip_error"]
 
 # enum pi0_op_class, in order
@@ -73,6 +73,8 @@ def lib() -> ctypes.CDLL:
         L.pi0_debug_profile.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp, i32, ctypes.POINTER(ctypes.c_double),
                                         ctypes.POINTER(ctypes.c_int), vp]
         L.pi0_debug_profile.restype = i32
+        L.pi0_sync_bench.argtypes = [i32, i32, i32, vp, vp, vp, ctypes.POINTER(ctypes.c_double), vp]
+        L.pi0_sync_bench.restype = i32
         L.pi0_set_graph_mode.argtypes = [vp, i32]
         L.pi0_set_graph_mode.restype = i32
         L.pi0_kernel_count.argtypes = [vp, i32, i32]
@@ -110,6 +112,20 @@ def pi0_debug_taps_elems(cfg, n_views: int, n_prompt: int) -> int:
 
 def _ptr(t) -> Optional[int]:
     return None if t is None else int(t.data_ptr())
+
+
+SYNC_MODES = {"eager": 0, "graph": 1, "barrier": 2, "barrier_fence": 3, "fused": 4}
+
+
+def pi0_sync_bench(mode: str, n_ops: int, reps: int, d_x, d_b, d_state, stream=None) -> float:
+    """Milliseconds of one repetition of n_ops dependent x += b updates under the given ordering mode."""
+    ms = ctypes.c_double(0.0)
+    s = None if stream is None else int(stream.cuda_stream)
+    rc = lib().pi0_sync_bench(SYNC_MODES[mode], int(n_ops), int(reps), _ptr(d_x), _ptr(d_b), _ptr(d_state),
+                              ctypes.byref(ms), s)
+    if rc != PI0_OK:
+        raise Pi0Error(rc)
+    return float(ms.value)
 
 
 class Pi0:

@@ -256,3 +256,26 @@ def test_full_model_all_view_counts():
             np.testing.assert_array_equal(case.infer(img, st, nz, ids), act)
     finally:
         case.close()
+
+
+def test_sync_overhead_microbenchmark():
+    """Table 3's experiment (Section 5.2): every ordering mode applies exactly n_ops updates; the software
+    barriers terminate; one unsynchronised kernel is the cheapest variant."""
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.Stream(device=dev)
+    g = torch.Generator().manual_seed(7)
+    x0 = torch.randint(-8, 8, (256, 1024), generator=g).float()
+    b = torch.randint(0, 3, (256, 1024), generator=g).float()
+    n_ops, reps = 1378, 2
+    times = {}
+    for mode in ("eager", "graph", "barrier", "barrier_fence", "fused"):
+        say(f"[gpu] pi0_sync_bench {mode}")
+        d_x, d_b = x0.to(dev), b.to(dev)
+        d_state = torch.zeros(2, dtype=torch.int32, device=dev)
+        torch.cuda.synchronize()
+        times[mode] = binding.pi0_sync_bench(mode, n_ops, reps, d_x, d_b, d_state, stream)
+        torch.testing.assert_close(d_x.cpu(), x0 + reps * n_ops * b, rtol=0, atol=0)
+        assert int(d_state[1].item()) == 0
+    say("[sync] ms per 1378 updates: " + ", ".join(f"{k} {v:.3f}" for k, v in times.items()))
+    assert times["fused"] < times["graph"] < times["eager"] * 1.5
+    assert times["fused"] < times["barrier"]
