@@ -150,6 +150,23 @@ def main() -> int:
             ("%s %.1f %s = %.3f of peak" % (r["bound"], r["achieved"], r["unit"], r["frac"])) if "bound" in r else ""))
     dominant = next(r for r in rows if "bound" in r)
 
+    # Section 6's concurrent mode: prefill of frame k beside the denoise of frame k-1 (two streams)
+    sp2, sd2 = torch.cuda.Stream(device=dev), torch.cuda.Stream(device=dev)
+    stream_ms = {}
+    for v in (1, 2, 3):
+        imgs = torch.from_numpy(synth.make_images(cfg, v)).to(dev)
+        m.pi0_prefill(imgs, v, None, 0, sp2)
+        for _ in range(5):
+            m.pi0_stream_frame(imgs, v, None, 0, state, noise, actions, sp2, sd2)
+        sp2.synchronize(); sd2.synchronize()
+        nfr = max(20, args.steps // 4)
+        t_start = time.perf_counter()
+        for _ in range(nfr):
+            m.pi0_stream_frame(imgs, v, None, 0, state, noise, actions, sp2, sd2)
+        sp2.synchronize(); sd2.synchronize()
+        stream_ms[str(v)] = round((time.perf_counter() - t_start) * 1e3 / nfr, 4)
+    log("[bench] two-stream frame interval ms by views: " + json.dumps(stream_ms))
+
     # Table 3's experiment on this machine: 1378 dependent A+B updates under different orderings
     sx = torch.zeros((256, 1024), dtype=torch.float32, device=dev)
     sb = torch.ones((256, 1024), dtype=torch.float32, device=dev)
@@ -191,6 +208,8 @@ def main() -> int:
                        "by_views_median": {k: round(v, 4) for k, v in views_ms.items()},
                        "prefill": round(prefill_ms, 4), "denoise": round(denoise_ms, 4)},
         "paper_rtx4090_ms": {"1": 20.0, "2": 27.3, "3": 36.8},
+        # frame interval when the prefill of frame k overlaps the denoise of frame k-1 (pi0_stream_frame)
+        "two_stream_frame_interval_ms": stream_ms,
         # the operation class with the largest share of the pass (event-timed, eager launches)
         "roofline": {"bound": dominant["bound"], "achieved": dominant["achieved"], "peak": dominant["peak"],
                      "unit": dominant["unit"], "frac": dominant["frac"],

@@ -137,6 +137,22 @@ int pi0_infer(pi0_ctx* ctx, const float* d_images, int n_views, const int32_t* d
               void* hip_stream);
 
 /*
+ * One frame of the two-stream mode of Section 6 (concurrent prefix and expert): enqueues, on
+ * stream_prefill, the prefill of THIS frame's images into the second copy of the key/value cache
+ * and, on stream_denoise, the denoise of d_state / d_noise against the cache that the PREVIOUS
+ * prefill (pi0_prefill, pi0_infer or the previous pi0_stream_frame) filled; the two run
+ * concurrently on the GPU.  d_actions therefore belongs to the previous frame's images, exactly as
+ * pi0_denoise after that prefill would compute them (same kernels, bit-identical).  After the call
+ * the cache filled by this frame is the current one.  Ordering between successive frames is kept
+ * with events owned by ctx: use the same two (distinct, non-NULL) streams for every frame, and
+ * enqueue the priming prefill on stream_prefill.  The results are valid once both streams are
+ * synchronised.  Errors as pi0_infer; ESTATE if there is no valid prefill to denoise against.
+ */
+int pi0_stream_frame(pi0_ctx* ctx, const float* d_images, int n_views, const int32_t* d_prompt_ids,
+                     int n_prompt, const float* d_state, const float* d_noise, float* d_actions,
+                     void* stream_prefill, void* stream_denoise);
+
+/*
  * Debug run for parity checks: the same kernels launched eagerly (no graph), copying
  * intermediate results into d_taps (float32) after each layer.  Tap layout, in order:
  *   vision residual stream after each vision layer      vis_layers x [I][Dv]

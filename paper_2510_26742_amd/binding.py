@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpi0_hip.so")
 
 EXPORTS = ["pi0_create", "pi0_destroy", "pi0_weights_bytes", "pi0_workspace_bytes", "pi0_load_weights",
-           "pi0_prefill", "pi0_denoise", "pi0_infer", "pi0_debug_taps_elems", "pi0_debug_forward", "pi0_debug_profile", "pi0_sync_bench",
+           "pi0_prefill", "pi0_denoise", "pi0_infer", "pi0_debug_taps_elems", "pi0_debug_forward", "pi0_debug_profile", "pi0_sync_bench", "pi0_stream_frame",
            "pi0_set_graph_mode", "pi0_kernel_count", "pi0_strerror", "pi0_last_hip_error"]
 
 # enum pi0_op_class, in order
@@ -73,6 +73,8 @@ def lib() -> ctypes.CDLL:
         L.pi0_debug_profile.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp, i32, ctypes.POINTER(ctypes.c_double),
                                         ctypes.POINTER(ctypes.c_int), vp]
         L.pi0_debug_profile.restype = i32
+        L.pi0_stream_frame.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp, vp, vp]
+        L.pi0_stream_frame.restype = i32
         L.pi0_sync_bench.argtypes = [i32, i32, i32, vp, vp, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.pi0_sync_bench.restype = i32
         L.pi0_set_graph_mode.argtypes = [vp, i32]
@@ -181,6 +183,12 @@ class Pi0:
     def pi0_infer(self, d_images, n_views, d_prompt_ids, n_prompt, d_state, d_noise, d_actions, stream=None):
         self._check(lib().pi0_infer(self._ctx, _ptr(d_images), n_views, _ptr(d_prompt_ids), n_prompt, _ptr(d_state),
                                     _ptr(d_noise), _ptr(d_actions), self._stream(stream)))
+
+    def pi0_stream_frame(self, d_images, n_views, d_prompt_ids, n_prompt, d_state, d_noise, d_actions, stream_prefill,
+                         stream_denoise):
+        self._check(lib().pi0_stream_frame(self._ctx, _ptr(d_images), n_views, _ptr(d_prompt_ids), n_prompt, _ptr(d_state),
+                                           _ptr(d_noise), _ptr(d_actions), int(stream_prefill.cuda_stream),
+                                           int(stream_denoise.cuda_stream)))
 
     def pi0_debug_forward(self, d_images, n_views, d_prompt_ids, n_prompt, d_state, d_noise, d_actions, d_taps, stream=None):
         self._check(lib().pi0_debug_forward(self._ctx, _ptr(d_images), n_views, _ptr(d_prompt_ids), n_prompt, _ptr(d_state),

@@ -153,6 +153,8 @@ struct WsLayout {
   size_t vstat, lstat, estat, estat_parts, pf_sink;
   size_t total;
   size_t kcache_layer, vcache_layer;   // bytes per layer
+  size_t kcache_slot, vcache_slot;     // bytes per cache copy (two copies: double buffering for pi0_stream_frame)
+  size_t epart;                        // split-K partial sums of the expert (separate from the prefix's)
   int zmax;
 };
 
@@ -252,8 +254,10 @@ void ws_layout(const pi0_config& c, const Dims& d, WsLayout& w) {
   w.lq = cur.take((size_t)d.H * d.maxPc * 16 * 512 * 2);
   w.kcache_layer = (size_t)d.maxPc * 16 * 512 * 2;
   w.vcache_layer = (size_t)d.maxPc * 8 * 1024 * 2;
-  w.kcache = cur.take(w.kcache_layer * d.Ll);
-  w.vcache = cur.take(w.vcache_layer * d.Ll);
+  w.kcache_slot = round_up_sz(w.kcache_layer * d.Ll, 256);
+  w.vcache_slot = round_up_sz(w.vcache_layer * d.Ll, 256);
+  w.kcache = cur.take(w.kcache_slot * 2);
+  w.vcache = cur.take(w.vcache_slot * 2);
   w.lattn = cur.take((size_t)d.maxPc * 32 * d.H * 256 * 2);
   w.lmid = cur.take((size_t)d.maxPc * 32 * d.F * 2);
   w.stok = cur.take((size_t)d.X * 4);
@@ -270,15 +274,21 @@ void ws_layout(const pi0_config& c, const Dims& d, WsLayout& w) {
   w.estat = cur.take((size_t)64 * 2 * 4);
   w.estat_parts = cur.take((size_t)(d.X / 32) * 64 * 2 * 4);
   w.pf_sink = cur.take(1024 * 4);
+  {
+    const int kmax = d.H * 256 > d.Fx ? d.H * 256 : d.Fx;
+    w.epart = cur.take((size_t)ceil_div(round_up(kmax, 64), 1024) * 64 * round_up(d.X, 32) * 4);
+  }
   w.total = cur.off;
 }
 
 struct GraphKey {
-  int kind, n_views, n_prompt;
+  int kind, n_views, n_prompt, slot_w, slot_r;
   bool operator<(const GraphKey& o) const {
     if (kind != o.kind) return kind < o.kind;
     if (n_views != o.n_views) return n_views < o.n_views;
-    return n_prompt < o.n_prompt;
+    if (n_prompt != o.n_prompt) return n_prompt < o.n_prompt;
+    if (slot_w != o.slot_w) return slot_w < o.slot_w;
+    return slot_r < o.slot_r;
   }
 };
 enum { KIND_PREFILL = 0, KIND_DENOISE = 1, KIND_INFER = 2 };
@@ -309,6 +319,9 @@ struct pi0_ctx {
   bool attrs_set = false;
   bool graph_mode = true;
   int cur_views = 0, cur_prompt = 0;   // shape of the valid prefill (0 views = none)
+  int cur_slot = 0;                    // cache copy that holds it
+  hipEvent_t ev_prefill[2] = {nullptr, nullptr};   // pi0_stream_frame: copy s was written / last read
+  hipEvent_t ev_denoise[2] = {nullptr, nullptr};
   int last_hip = 0;
   std::map<GraphKey, hipGraphExec_t> graphs;
   std::vector<float> h_rope, h_tau;
@@ -327,6 +340,7 @@ struct Run {
   bool count_only;
   int launches = 0;
   hipError_t err = hipSuccess;
+  int slot_w = 0, slot_r = 0;   // cache copy the prefill writes / the denoise reads
   int cls = PI0_OP_MISC;        // class of the launches that follow
   OpTimer* timer = nullptr;     // when set, every RUN / RUN_GEMM launch is bracketed by an event pair
   bool ok() const { return err == hipSuccess; }
@@ -386,13 +400,14 @@ GemmParams gp_base(pi0_ctx* c, const PW& pw, const bf16* X, int ldx, int M, int 
 // split-K GEMM into the partial buffer followed by the fixed-order reduction with bias/residual
 void gemm_splitk_resid(Run& r, const PW& pw, const bf16* X, int ldx, int M, int k_true, int z, int k_per_split,
                        const float* bias, float* resid_io, bf16* shadow, int n_true, int tile, float* stat_out,
-                       const float* gain, const float* resid_in = nullptr, int resid_mod = 0, bool no_resid = false) {
+                       const float* gain, const float* resid_in = nullptr, int resid_mod = 0, bool no_resid = false,
+                       bool expert_scratch = false) {
   pi0_ctx* c = r.c;
   if (z > Z_MAX) z = Z_MAX;
   if ((long)k_per_split * z < pw.k_pad) k_per_split = round_up(ceil_div(pw.k_pad, z), 64);
   GemmParams p = gp_base(c, pw, X, ldx, M, tile, k_true);
   p.k_per_split = k_per_split;
-  p.out_f32 = at<float>(c, c->wl.part);
+  p.out_f32 = at<float>(c, expert_scratch ? c->wl.epart : c->wl.part);
   p.ldo = pw.n_pad;
   RUN_GEMM(r, tile, PRO_NONE, EPI_PARTIAL, p, z);
   const int cls_gemm = r.cls;
@@ -512,8 +527,8 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
   for (int l = 0; l < d.Ll; l++) {
     const WsTr& L = w.llm[l];
     const bool last = l == d.Ll - 1;
-    bf16* kc = reinterpret_cast<bf16*>(c->ws + w.kcache + (size_t)l * w.kcache_layer);
-    bf16* vc = reinterpret_cast<bf16*>(c->ws + w.vcache + (size_t)l * w.vcache_layer);
+    bf16* kc = reinterpret_cast<bf16*>(c->ws + w.kcache + (size_t)r.slot_w * w.kcache_slot + (size_t)l * w.kcache_layer);
+    bf16* vc = reinterpret_cast<bf16*>(c->ws + w.vcache + (size_t)r.slot_w * w.vcache_slot + (size_t)l * w.vcache_layer);
     {  // B1: RMS -> QKV, RoPE, keys/values into the cache (last layer: keys/values only)
       GemmParams p = gp_base(c, L.qkv, at<bf16>(c, w.lx_b), d.E, P, T.lqkv, d.E);
       p.rowstat = at<float>(c, w.lstat);
@@ -561,8 +576,8 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
   }
   if (taps && taps->base) {
     for (int l = 0; l < d.Ll; l++) {
-      bf16* kc = reinterpret_cast<bf16*>(c->ws + w.kcache + (size_t)l * w.kcache_layer);
-      bf16* vc = reinterpret_cast<bf16*>(c->ws + w.vcache + (size_t)l * w.vcache_layer);
+      bf16* kc = reinterpret_cast<bf16*>(c->ws + w.kcache + (size_t)r.slot_w * w.kcache_slot + (size_t)l * w.kcache_layer);
+      bf16* vc = reinterpret_cast<bf16*>(c->ws + w.vcache + (size_t)r.slot_w * w.vcache_slot + (size_t)l * w.vcache_layer);
       float* kout = taps->base + taps->off + (size_t)l * P * 256;
       float* vout = kout + (size_t)d.Ll * P * 256;
       if (!r.count_only && r.ok()) r.did(launch_unpack_kv(r.s, kc, vc, P, kout, vout));
@@ -603,10 +618,11 @@ void run_denoise(Run& r, int P, Taps* taps) {
     f.tiles[r] = pw.n_pad / 32;
     f.tile16[r] = pw.k_pad * 4;          // one 32-feature tile = k_pad * 32 bf16
   };
+  const int this_slot = r.slot_r;
   auto pf_cache = [&](PrefetchDesc& f, int r, int layer) {
-    f.ptr[r] = c->ws + w.kcache + (size_t)layer * w.kcache_layer;
+    f.ptr[r] = c->ws + w.kcache + (size_t)this_slot * w.kcache_slot + (size_t)layer * w.kcache_layer;
     f.tiles[r] = pchunks; f.tile16[r] = 1024;   // one key chunk = 16 KiB
-    f.ptr[r + 1] = c->ws + w.vcache + (size_t)layer * w.vcache_layer;
+    f.ptr[r + 1] = c->ws + w.vcache + (size_t)this_slot * w.vcache_slot + (size_t)layer * w.vcache_layer;
     f.tiles[r + 1] = pchunks; f.tile16[r + 1] = 1024;
   };
   const Tune& T = c->tune;
@@ -625,7 +641,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
       stat_parts = pw.n_pad / 32;
     } else {
       gemm_splitk_resid(r, pw, X, K, 64, K, ceil_div(pw.k_pad, 1024), 1024, nullptr, at<float>(c, w.y), at<bf16>(c, w.y_b),
-                        d.X, TILE_SKINNY, at<float>(c, w.estat), gain);
+                        d.X, TILE_SKINNY, at<float>(c, w.estat), gain, nullptr, 0, false, true);
       stat_ptr = at<float>(c, w.estat);
       stat_parts = 1;
     }
@@ -651,8 +667,8 @@ void run_denoise(Run& r, int P, Taps* taps) {
     const bool tap_this = taps && (k == 0 || k == d.steps - 1);
     for (int l = 0; l < d.Le; l++) {
       const WsTr& L = w.exp[l];
-      bf16* kc = reinterpret_cast<bf16*>(c->ws + w.kcache + (size_t)l * w.kcache_layer);
-      bf16* vc = reinterpret_cast<bf16*>(c->ws + w.vcache + (size_t)l * w.vcache_layer);
+      bf16* kc = reinterpret_cast<bf16*>(c->ws + w.kcache + (size_t)r.slot_r * w.kcache_slot + (size_t)l * w.kcache_layer);
+      bf16* vc = reinterpret_cast<bf16*>(c->ws + w.vcache + (size_t)r.slot_r * w.vcache_slot + (size_t)l * w.vcache_layer);
       {  // C3: RMS -> QKV, RoPE at positions P..P+63
         GemmParams p = gp_base(c, L.qkv, at<bf16>(c, w.y_b), d.X, 64, TILE_SKINNY, d.X);
         p.rowstat = stat_ptr;
@@ -772,23 +788,29 @@ int fail_hip(pi0_ctx* c, hipError_t e) {
 }
 
 // Runs `kind` either through a cached graph or eagerly.
-int execute(pi0_ctx* c, int kind, int n_views, int n_prompt, hipStream_t s) {
+int execute(pi0_ctx* c, int kind, int n_views, int n_prompt, hipStream_t s, int slot_w = -1, int slot_r = -1) {
   const int P = n_views * c->d.T + n_prompt;
+  if (slot_w < 0) slot_w = c->cur_slot;
+  if (slot_r < 0) slot_r = c->cur_slot;
   auto body = [&](Run& r) {
     if (kind == KIND_PREFILL || kind == KIND_INFER) run_prefill(r, n_views, n_prompt, nullptr);
     if (kind == KIND_DENOISE || kind == KIND_INFER) run_denoise(r, P, nullptr);
   };
   if (!c->graph_mode || s == nullptr) {   // the legacy default stream cannot be captured
     Run r{c, s, false};
+    r.slot_w = slot_w;
+    r.slot_r = slot_r;
     body(r);
     return r.ok() ? PI0_OK : fail_hip(c, r.err);
   }
-  GraphKey key{kind, n_views, n_prompt};
+  GraphKey key{kind, n_views, n_prompt, kind == KIND_DENOISE ? 0 : slot_w, kind == KIND_PREFILL ? 0 : slot_r};
   auto it = c->graphs.find(key);
   if (it == c->graphs.end()) {
     hipError_t e = hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal);
     if (e != hipSuccess) return fail_hip(c, e);
     Run r{c, s, false};
+    r.slot_w = slot_w;
+    r.slot_r = slot_r;
     body(r);
     hipGraph_t g = nullptr;
     e = hipStreamEndCapture(s, &g);
@@ -890,6 +912,10 @@ int pi0_create(const pi0_config* cfg, pi0_ctx** out) {
 void pi0_destroy(pi0_ctx* c) {
   if (c == nullptr) return;
   for (auto& kv : c->graphs) (void)hipGraphExecDestroy(kv.second);
+  for (int i = 0; i < 2; i++) {
+    if (c->ev_prefill[i]) (void)hipEventDestroy(c->ev_prefill[i]);
+    if (c->ev_denoise[i]) (void)hipEventDestroy(c->ev_denoise[i]);
+  }
   delete c;
 }
 
@@ -1055,6 +1081,10 @@ int pi0_prefill(pi0_ctx* c, const float* d_images, int n_views, const int32_t* d
   if (e != hipSuccess) return fail_hip(c, e);
   int rc = execute(c, KIND_PREFILL, n_views, n_prompt, s);
   if (rc != PI0_OK) return rc;
+  if (c->ev_prefill[c->cur_slot] != nullptr) {
+    e = hipEventRecord(c->ev_prefill[c->cur_slot], s);
+    if (e != hipSuccess) return fail_hip(c, e);
+  }
   c->cur_views = n_views;
   c->cur_prompt = n_prompt;
   return PI0_OK;
@@ -1083,10 +1113,53 @@ int pi0_infer(pi0_ctx* c, const float* d_images, int n_views, const int32_t* d_p
   if (e != hipSuccess) return fail_hip(c, e);
   int rc = execute(c, KIND_INFER, n_views, n_prompt, s);
   if (rc != PI0_OK) return rc;
+  if (c->ev_prefill[c->cur_slot] != nullptr) {
+    e = hipEventRecord(c->ev_prefill[c->cur_slot], s);
+    if (e != hipSuccess) return fail_hip(c, e);
+  }
   c->cur_views = n_views;
   c->cur_prompt = n_prompt;
   e = launch_copy_f32(s, at<float>(c, c->wl.xa), d_actions, (size_t)c->cfg.chunk * c->d.A);
   return e == hipSuccess ? PI0_OK : fail_hip(c, e);
+}
+
+int pi0_stream_frame(pi0_ctx* c, const float* d_images, int n_views, const int32_t* d_prompt_ids, int n_prompt,
+                     const float* d_state, const float* d_noise, float* d_actions, void* stream_prefill, void* stream_denoise) {
+  if (c == nullptr || d_state == nullptr || d_noise == nullptr || d_actions == nullptr) return PI0_EINVAL;
+  if (stream_prefill == nullptr || stream_denoise == nullptr || stream_prefill == stream_denoise) return PI0_EINVAL;
+  if (!check_prefill_args(c, d_images, n_views, d_prompt_ids, n_prompt)) return PI0_EINVAL;
+  if (!c->loaded || c->cur_views == 0) return PI0_ESTATE;
+  hipStream_t sp = reinterpret_cast<hipStream_t>(stream_prefill), sd = reinterpret_cast<hipStream_t>(stream_denoise);
+  hipError_t e = hipSuccess;
+  const int cur = c->cur_slot, nxt = 1 - cur;
+  const bool first_use = c->ev_prefill[0] == nullptr;
+  for (int i = 0; i < 2 && e == hipSuccess; i++) {
+    if (c->ev_prefill[i] == nullptr) e = hipEventCreateWithFlags(&c->ev_prefill[i], hipEventDisableTiming);
+    if (e == hipSuccess && c->ev_denoise[i] == nullptr) e = hipEventCreateWithFlags(&c->ev_denoise[i], hipEventDisableTiming);
+  }
+  // first frame: the priming prefill was enqueued on stream_prefill before events existed
+  if (e == hipSuccess && first_use) e = hipEventRecord(c->ev_prefill[cur], sp);
+  if (e != hipSuccess) return fail_hip(c, e);
+  // prefill of this frame into the other cache copy, once the last denoise that read that copy is done
+  e = hipStreamWaitEvent(sp, c->ev_denoise[nxt], 0);
+  if (e == hipSuccess) e = stage_inputs(c, sp, d_images, n_views, d_prompt_ids, n_prompt, nullptr, nullptr);
+  if (e != hipSuccess) return fail_hip(c, e);
+  int rc = execute(c, KIND_PREFILL, n_views, n_prompt, sp, nxt, nxt);
+  if (rc != PI0_OK) return rc;
+  e = hipEventRecord(c->ev_prefill[nxt], sp);
+  // denoise against the copy the previous frame filled
+  if (e == hipSuccess) e = hipStreamWaitEvent(sd, c->ev_prefill[cur], 0);
+  if (e == hipSuccess) e = stage_inputs(c, sd, nullptr, 0, nullptr, 0, d_state, d_noise);
+  if (e != hipSuccess) return fail_hip(c, e);
+  rc = execute(c, KIND_DENOISE, c->cur_views, c->cur_prompt, sd, cur, cur);
+  if (rc != PI0_OK) return rc;
+  e = launch_copy_f32(sd, at<float>(c, c->wl.xa), d_actions, (size_t)c->cfg.chunk * c->d.A);
+  if (e == hipSuccess) e = hipEventRecord(c->ev_denoise[cur], sd);
+  if (e != hipSuccess) return fail_hip(c, e);
+  c->cur_slot = nxt;
+  c->cur_views = n_views;
+  c->cur_prompt = n_prompt;
+  return PI0_OK;
 }
 
 size_t pi0_debug_taps_elems(const pi0_config* cfg, int n_views, int n_prompt) {
@@ -1110,6 +1183,7 @@ int pi0_debug_forward(pi0_ctx* c, const float* d_images, int n_views, const int3
   hipError_t e = stage_inputs(c, s, d_images, n_views, d_prompt_ids, n_prompt, d_state, d_noise);
   if (e != hipSuccess) return fail_hip(c, e);
   Run r{c, s, false};
+  r.slot_w = r.slot_r = c->cur_slot;
   Taps taps;
   taps.base = d_taps;
   run_prefill(r, n_views, n_prompt, &taps);
@@ -1141,6 +1215,7 @@ int pi0_debug_profile(pi0_ctx* c, const float* d_images, int n_views, const int3
   int rc = PI0_OK;
   for (int pass = 0; pass < passes && rc == PI0_OK; pass++) {
     Run r{c, s, false};
+    r.slot_w = r.slot_r = c->cur_slot;
     r.timer = &timer;
     run_prefill(r, n_views, n_prompt, nullptr);
     run_denoise(r, n_views * c->d.T + n_prompt, nullptr);

@@ -279,3 +279,37 @@ def test_sync_overhead_microbenchmark():
     say("[sync] ms per 1378 updates: " + ", ".join(f"{k} {v:.3f}" for k, v in times.items()))
     assert times["fused"] < times["graph"] < times["eager"] * 1.5
     assert times["fused"] < times["barrier"]
+
+
+def test_two_stream_frames_match_sequential(reduced):
+    """Section 6's concurrent mode: frame k's prefill runs beside the denoise against frame k-1's cache
+    (double-buffered).  Same kernels, so every chunk must equal, bit for bit, what pi0_prefill +
+    pi0_denoise give sequentially; view counts change between frames; no host synchronisation
+    between frames."""
+    cfg, m, dev = reduced.cfg, reduced.m, reduced.dev
+    sp, sd = torch.cuda.Stream(device=dev), torch.cuda.Stream(device=dev)
+    views = [1, 2, 1, 3, 2]
+    frames = [reduced.inputs(v, 0, seed_shift=40 + k) for k, v in enumerate(views)]
+    dev_frames = [reduced.to_dev(*f) for f in frames]
+    torch.cuda.synchronize()
+    # sequential reference: actions of frame k use the cache of frame k-1
+    ref = []
+    for k in range(1, len(views)):
+        d_img, _, _, _ = dev_frames[k - 1]
+        _, d_st, d_nz, _ = dev_frames[k]
+        out = torch.empty((cfg.chunk, cfg.action_dim), dtype=torch.float32, device=dev)
+        m.pi0_prefill(d_img, views[k - 1], None, 0, reduced.stream)
+        m.pi0_denoise(d_st, d_nz, out, reduced.stream)
+        reduced.stream.synchronize()
+        ref.append(out.cpu().numpy())
+    for rounds in range(2):      # second round replays the captured graphs
+        outs = [torch.empty((cfg.chunk, cfg.action_dim), dtype=torch.float32, device=dev) for _ in views[1:]]
+        say(f"[gpu] pi0_stream_frame round {rounds}")
+        m.pi0_prefill(dev_frames[0][0], views[0], None, 0, sp)
+        for k in range(1, len(views)):
+            d_img, d_st, d_nz, _ = dev_frames[k]
+            m.pi0_stream_frame(d_img, views[k], None, 0, d_st, d_nz, outs[k - 1], sp, sd)
+        sp.synchronize()
+        sd.synchronize()
+        for k, (o, r) in enumerate(zip(outs, ref)):
+            np.testing.assert_array_equal(o.cpu().numpy(), r, err_msg=f"frame {k + 1}")
