@@ -450,10 +450,10 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
     xf[1][i] = *reinterpret_cast<const bf16x8*>(xbase + ((size_t)mb1 * XKC16 + st) * 512);
   }
   // statistics partials: issued behind the operand loads (same round trip), clamped and unconditional
-  float2 sp[4];
+  float2 sp[8];
   if (PRO != PRO_NONE) {
 #pragma unroll
-    for (int jj = 0; jj < 4; jj++) {
+    for (int jj = 0; jj < 8; jj++) {
       const int j = min(w + SK_WAVES * jj, p.rowstat_parts - 1);
       sp[jj] = *reinterpret_cast<const float2*>(p.rowstat + ((size_t)j * 64 + lane) * 2);
     }
@@ -480,7 +480,7 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
   if (PRO != PRO_NONE) {
     float pa = 0.f, pb = 0.f;
 #pragma unroll
-    for (int jj = 0; jj < 4; jj++) {
+    for (int jj = 0; jj < 8; jj++) {
       if (w + SK_WAVES * jj < p.rowstat_parts) {
         pa += sp[jj].x;
         pb += sp[jj].y;
@@ -581,6 +581,98 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_fullk_kernel(GemmPa
   if (m < p.M) epilogue_tile<PRO_NONE, EPI_RESID>(p, sum, nt, m, lh, 0.f, 0.f, 0, ops);
 }
 
+// Skinny GEMM over the whole k range on 16-feature x 16-token tiles (mfma_f32_16x16x32_bf16): the
+// expert's O and down projections.  A launch lasts as long as its busiest CU needs to pull its
+// operands, and a CU sustains only ~60-100 GB/s, so the 64 x 1024 output is cut into 256 blocks
+// (one per CU) of 16 x 16: each block reads 16 weight rows and 16 token rows over all of k, half of
+// what a 32 x 32 tile needs, and every CU takes part.  The 16-row operand of one 32-k step is two
+// half fragments of the 32 x 16 fragment order (weights and XF activations alike): lane (g, i),
+// g = lane / 16, i = lane % 16, takes the 16 bytes of row i at k = 32 j + 8 g .. + 7, i.e. piece
+// ((g & 1) * 32 + 16 * (tile & 1) + i) of fragment 2 j + (g >> 1); every lane of every load is
+// used.  8 waves split k; NS steps per wave, all loads issued at once; fixed-order LDS reduction;
+// wave 0 adds the residual, writes fp32, the gain-scaled bf16 copy and per-tile row statistics.
+// Accumulator: lane -> token lane % 16, features 4 * (lane / 16) + r.
+template <int NS>
+__global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny16_kernel(GemmParams p) {
+  __shared__ float red[SK_WAVES][4][64];
+  const int t = threadIdx.x;
+  const int lane = t & 63;
+  const int w = t >> 6;
+  const int li = lane & 15;
+  const int lg = lane >> 4;
+  const int ntiles16 = p.n_tiles * 2;
+  if ((int)blockIdx.x >= ntiles16) {   // warm-up block; rank = linear block index (mod 8)
+    prefetch_role(p.pf, (int)blockIdx.x - ntiles16 + (int)blockIdx.y * ((int)gridDim.x - ntiles16));
+    return;
+  }
+  const int nt16 = blockIdx.x;
+  const int mt16 = blockIdx.y;
+  const int KC16 = p.W.k_pad >> 4;
+  const int XKC16 = p.ldx >> 4;
+  const int piece_w = ((lg & 1) * 32 + (nt16 & 1) * 16 + li) * 8;
+  const int piece_x = ((lg & 1) * 32 + (mt16 & 1) * 16 + li) * 8;
+  const bf16* wbase = p.W.w + ((size_t)(nt16 >> 1) * KC16 + (size_t)w * NS * 2 + (lg >> 1)) * 512 + piece_w;
+  const bf16* xbase = p.X + ((size_t)(mt16 >> 1) * XKC16 + (size_t)w * NS * 2 + (lg >> 1)) * 512 + piece_x;
+  bf16x8 wf[NS], xf[NS];
+#pragma unroll
+  for (int j = 0; j < NS; j++) {
+    wf[j] = *reinterpret_cast<const bf16x8*>(wbase + (size_t)j * 1024);
+    xf[j] = *reinterpret_cast<const bf16x8*>(xbase + (size_t)j * 1024);
+  }
+  // operands of the epilogue (wave 0), behind the operand loads
+  const int m = mt16 * 16 + li;
+  const int n4 = nt16 * 16 + 4 * lg;
+  const bool live = w == 0 && m < p.M && n4 < p.n_valid;
+  f32x4 rv = {0.f, 0.f, 0.f, 0.f}, gv = {1.f, 1.f, 1.f, 1.f}, bv = {0.f, 0.f, 0.f, 0.f};
+  if (live) {
+    if (p.resid != nullptr) rv = *reinterpret_cast<const f32x4*>(p.resid + (size_t)m * p.ldo + n4);
+    if (p.gain != nullptr) gv = *reinterpret_cast<const f32x4*>(p.gain + n4);
+    if (p.bias != nullptr) bv = *reinterpret_cast<const f32x4*>(p.bias + n4);
+  }
+  f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int j = 0; j < NS; j += 2) {
+    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[j], xf[j], acc0, 0, 0, 0);
+    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[j + 1], xf[j + 1], acc1, 0, 0, 0);
+  }
+#pragma unroll
+  for (int r = 0; r < 4; r++) red[w][r][lane] = acc0[r] + acc1[r];
+  __syncthreads();
+  if (w != 0) return;
+  float v[4];
+#pragma unroll
+  for (int r = 0; r < 4; r++) {
+    float a = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < SK_WAVES; ww++) a += red[ww][r][lane];
+    v[r] = a + bv[r] + rv[r];
+  }
+  float st_a = 0.f, st_b = 0.f;
+  const int mo = m + p.row_offset;
+  if (live) {
+    const f32x4 o = {v[0], v[1], v[2], v[3]};
+    *reinterpret_cast<f32x4*>(p.out_f32 + (size_t)mo * p.ldo + n4) = o;
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+      st_a += v[r];
+      st_b += v[r] * v[r];
+    }
+    const bf16x4 ob = {(bf16)(v[0] * gv[0]), (bf16)(v[1] * gv[1]), (bf16)(v[2] * gv[2]), (bf16)(v[3] * gv[3])};
+    *reinterpret_cast<bf16x4*>(p.out_bf16 + xf_index(mo, n4, p.ldo2 >> 4)) = ob;
+  }
+  if (p.stat_out != nullptr) {   // partial row statistics over this tile's 16 columns: [16-column tile][64 rows][2]
+    st_a += __shfl_xor(st_a, 16, 64);
+    st_b += __shfl_xor(st_b, 16, 64);
+    st_a += __shfl_xor(st_a, 32, 64);
+    st_b += __shfl_xor(st_b, 32, 64);
+    if (lg == 0 && m < p.M) {
+      float* dst = p.stat_out + ((size_t)nt16 * 64 + mo) * 2;
+      dst[0] = st_a;
+      dst[1] = st_b;
+    }
+  }
+}
+
 static constexpr int skinny_smem_bytes() { return (SK_WAVES * 2 * 16 * 64 + 128 + SK_WAVES * 128) * 4; }
 
 // ------------------------------------------------------------------------------------------------
@@ -595,6 +687,7 @@ int gemm_rows_per_tile(int tile) {
     case TILE_MID: return 64;
     case TILE_SKINNY: return 64;
     case TILE_SKINNY_FULLK: return 64;
+    case TILE_SKINNY16: return 64;
     default: return -1;
   }
 }
@@ -670,7 +763,7 @@ static bool prefetch_ok(const PrefetchDesc& d) {
 hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmParams& p, int z_splits) {
   // Host-side shape checks: everything the kernel's indexing assumes.
   if (!prefetch_ok(p.pf)) return hipErrorInvalidValue;
-  if (p.pf.blocks != 0 && ((tile != TILE_SKINNY && tile != TILE_SKINNY_FULLK) || z_splits != 1)) return hipErrorInvalidValue;
+  if (p.pf.blocks != 0 && ((tile != TILE_SKINNY && tile != TILE_SKINNY_FULLK && tile != TILE_SKINNY16) || z_splits != 1)) return hipErrorInvalidValue;
   if (p.X == nullptr || p.W.w == nullptr || p.M <= 0 || z_splits < 1) return hipErrorInvalidValue;
   if (p.W.k_pad % 64 != 0 || p.W.n_pad % 32 != 0 || p.n_tiles * 32 != p.W.n_pad) return hipErrorInvalidValue;
   if (p.ldx < p.W.k_pad || p.ldx % 16 != 0) return hipErrorInvalidValue;   // X is in XF layout with ldx padded columns
@@ -678,6 +771,19 @@ hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmPara
   if (pro != PRO_NONE && (z_splits != 1 || p.rowstat == nullptr)) return hipErrorInvalidValue;
   if (epi != EPI_PARTIAL && z_splits != 1) return hipErrorInvalidValue;
   if (p.m_tiles < 1) return hipErrorInvalidValue;
+  if (tile == TILE_SKINNY16) {
+    // 16 x 16 tiles over the whole k range: k = 8 waves x NS steps x 32
+    const int kc16 = p.W.k_pad >> 4;
+    if (p.M > 64 || pro != PRO_NONE || epi != EPI_RESID || z_splits != 1 || (kc16 != 128 && kc16 != 256)) return hipErrorInvalidValue;
+    if (p.out_f32 == nullptr || p.out_bf16 == nullptr || p.ldo % 4 != 0 || p.ldo2 % 16 != 0) return hipErrorInvalidValue;
+    const int my = (p.M + 15) / 16;
+    if (p.pf.blocks != 0 && (p.pf.blocks % my != 0 || (p.n_tiles * 2) % 8 != 0 || ((p.n_tiles * 2 + p.pf.blocks / my) * my) % 8 != 0))
+      return hipErrorInvalidValue;
+    const dim3 grid(p.n_tiles * 2 + (p.pf.blocks != 0 ? p.pf.blocks / my : 0), my);
+    if (kc16 == 128) gemm_skinny16_kernel<8><<<grid, dim3(64 * SK_WAVES), 0, s>>>(p);
+    else gemm_skinny16_kernel<16><<<grid, dim3(64 * SK_WAVES), 0, s>>>(p);
+    return hipGetLastError();
+  }
   if (tile == TILE_SKINNY_FULLK) {
     const int kc16 = p.W.k_pad >> 4;
     if (p.M > 64 || pro != PRO_NONE || epi != EPI_RESID || z_splits != 1 || (kc16 != 128 && kc16 != 256)) return hipErrorInvalidValue;
@@ -688,7 +794,7 @@ hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmPara
     return hipGetLastError();
   }
   if (tile == TILE_SKINNY) {
-    if (pro != PRO_NONE && (p.rowstat_parts < 1 || p.rowstat_parts > 4 * SK_WAVES)) return hipErrorInvalidValue;
+    if (pro != PRO_NONE && (p.rowstat_parts < 1 || p.rowstat_parts > 8 * SK_WAVES)) return hipErrorInvalidValue;
     if (p.M > 64 || p.m_tiles != 1 || p.k_per_split > SK_KMAX || p.k_per_split % 16 != 0) return hipErrorInvalidValue;
 #define X(PRO, EPI)                                                                                          \
   if (pro == PRO && epi == EPI) {                                                                            \

@@ -272,7 +272,7 @@ void ws_layout(const pi0_config& c, const Dims& d, WsLayout& w) {
   w.vstat = cur.take((size_t)d.maxI * 2 * 4);
   w.lstat = cur.take((size_t)d.maxPc * 32 * 2 * 4);
   w.estat = cur.take((size_t)64 * 2 * 4);
-  w.estat_parts = cur.take((size_t)(d.X / 32) * 64 * 2 * 4);
+  w.estat_parts = cur.take((size_t)(d.X / 16) * 64 * 2 * 4);
   w.pf_sink = cur.take(1024 * 4);
   {
     const int kmax = d.H * 256 > d.Fx ? d.H * 256 : d.Fx;
@@ -305,7 +305,8 @@ struct Tune {
   int vo = TILE_MID, vd = TILE_MID, lo = TILE_MID, ld = TILE_BIG;   // split-K partial GEMMs: vision O / down, prefix O / down
   int zvo = 2, zlo = 4, zld = 16, zvd = 4;
   // warm-up blocks carried by the expert's launches (0 = none): QKV, attention, O, down
-  int pfq = 64, pfa = 64, pfo = 64, pfd = 64;
+  int pfq = 64, pfa = 64, pfo = 128, pfd = 128;
+  int ae16 = 1;           // expert O / down on 16 x 16 tiles (256 blocks) instead of 32 x 32 (64 blocks)
 };
 
 struct pi0_ctx {
@@ -628,7 +629,8 @@ void run_denoise(Run& r, int P, Taps* taps) {
   const Tune& T = c->tune;
   auto resid_gemm = [&](const PW& pw, const bf16* X, int K, const float* gain, const PrefetchDesc& pf) {
     if (pw.k_pad == 2048 || pw.k_pad == 4096) {
-      GemmParams p = gp_base(c, pw, X, K, 64, TILE_SKINNY_FULLK, K);
+      const int tile = T.ae16 ? TILE_SKINNY16 : TILE_SKINNY_FULLK;
+      GemmParams p = gp_base(c, pw, X, K, 64, tile, K);
       p.resid = at<float>(c, w.y);
       p.out_f32 = at<float>(c, w.y);
       p.out_bf16 = at<bf16>(c, w.y_b);
@@ -636,9 +638,9 @@ void run_denoise(Run& r, int P, Taps* taps) {
       p.stat_out = at<float>(c, w.estat_parts);
       p.gain = gain;
       p.pf = pf;
-      RUN_GEMM(r, TILE_SKINNY_FULLK, PRO_NONE, EPI_RESID, p, 1);
+      RUN_GEMM(r, tile, PRO_NONE, EPI_RESID, p, 1);
       stat_ptr = at<float>(c, w.estat_parts);
-      stat_parts = pw.n_pad / 32;
+      stat_parts = T.ae16 ? pw.n_pad / 16 : pw.n_pad / 32;
     } else {
       gemm_splitk_resid(r, pw, X, K, 64, K, ceil_div(pw.k_pad, 1024), 1024, nullptr, at<float>(c, w.y), at<bf16>(c, w.y_b),
                         d.X, TILE_SKINNY, at<float>(c, w.estat), gain, nullptr, 0, false, true);
@@ -872,7 +874,7 @@ int pi0_create(const pi0_config* cfg, pi0_ctx** out) {
         {"vo", &c->tune.vo, 0, 1}, {"vd", &c->tune.vd, 0, 1}, {"lo", &c->tune.lo, 0, 1}, {"ld", &c->tune.ld, 0, 1}, {"zvo", &c->tune.zvo, 1, Z_MAX}, {"zlo", &c->tune.zlo, 1, Z_MAX},
         {"zld", &c->tune.zld, 1, Z_MAX}, {"zvd", &c->tune.zvd, 1, Z_MAX},
         {"pfq", &c->tune.pfq, 0, 1024}, {"pfa", &c->tune.pfa, 0, 1024}, {"pfo", &c->tune.pfo, 0, 1024},
-        {"pfd", &c->tune.pfd, 0, 1024}};
+        {"pfd", &c->tune.pfd, 0, 1024}, {"ae16", &c->tune.ae16, 0, 1}};
     for (auto& k : keys) {
       const char* f = strstr(env, k.key);
       while (f != nullptr && !((f == env || f[-1] == ',') && f[strlen(k.key)] == '=')) f = strstr(f + 1, k.key);
