@@ -13,9 +13,9 @@
 #define LDS_PAD 8
 
 __device__ __forceinline__ float gelu_tanh_f(float x) {
-  float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-  float t = 1.0f - 2.0f / (1.0f + __expf(2.0f * u));
-  return 0.5f * x * (1.0f + t);
+  // 0.5 x (1 + tanh u) = x * sigmoid(2u) = x / (1 + exp(-2u)); hardware exp2 and reciprocal
+  const float u2 = -1.5957691216057308f * (x + 0.044715f * x * x * x);
+  return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(1.4426950408889634f * u2));
 }
 
 // Sum over groups of 8 adjacent lanes with DPP (no LDS traffic): xor 1, xor 2 inside quads, then
@@ -88,6 +88,7 @@ __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16&
   {
     float rs = 1.f, mu = 0.f;
     float st_a = 0.f, st_b = 0.f;   // EPI_RESID: sum / sum of squares of this lane's fp32 outputs
+    unsigned geglu_keep = 0u;       // EPI_GEGLU: the products of the even step, until the odd step pairs them
     if (PRO == PRO_RMS) {
       rs = rsqrtf(s_sq * inv_k + 1e-6f);
     } else if (PRO == PRO_LN) {
@@ -152,8 +153,22 @@ __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16&
           *reinterpret_cast<bf16x4*>(p.out_bf16 + xf_index(m, n4, p.ldo >> 4)) = ob;
         }
       } else if (EPI == EPI_GEGLU) {
-        bf16x2 ob = {(bf16)(gelu_tanh_f(v[0]) * v[1]), (bf16)(gelu_tanh_f(v[2]) * v[3])};
-        *reinterpret_cast<bf16x2*>(p.out_bf16 + xf_index(m, n4 >> 1, p.ldo >> 4)) = ob;
+        // this lane's two products of step i; steps are paired (0,1), (2,3): the lane halves swap one
+        // pair each, so that a lane stores 4 consecutive columns (8 bytes) and the two halves together
+        // fill whole 16-byte pieces of the XF layout
+        const bf16x2 ob = {(bf16)(gelu_tanh_f(v[0]) * v[1]), (bf16)(gelu_tanh_f(v[2]) * v[3])};
+        const unsigned mine = __builtin_bit_cast(unsigned, ob);
+        if ((i & 1) == 0) {
+          geglu_keep = mine;
+        } else {
+          const unsigned give = lh ? geglu_keep : mine;            // half 0 gives step i, half 1 gives step i-1
+          const unsigned got = (unsigned)__shfl_xor((int)give, 32, 64);
+          const unsigned lo = lh ? got : geglu_keep;                 // half 0: own i-1, partner's i-1
+          const unsigned hi = lh ? mine : got;                       // half 1: partner's i, own i
+          const int col = nt * 16 + 4 * (i - 1) + 4 * lh;            // (n4 >> 1) of step i-1 for half 0, +4 for half 1
+          const uint2 o2 = {lo, hi};
+          *reinterpret_cast<uint2*>(p.out_bf16 + xf_index(m, col, p.ldo >> 4)) = o2;
+        }
       } else if (EPI == EPI_EULER) {
         if (m >= 1) {
 #pragma unroll
@@ -384,15 +399,23 @@ __global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(1, 1)))
   if (!wave_active) return;
 
   // ---- epilogue --------------------------------------------------------------------------------
+  // row statistics (from the kernel that produced the residual stream) of all token blocks in one
+  // round trip, rows clamped into range
+  float2 rst[MB];
+  if (PRO != PRO_NONE) {
+#pragma unroll
+    for (int mb = 0; mb < MB; mb++)
+      rst[mb] = *reinterpret_cast<const float2*>(p.rowstat + 2 * (size_t)min(m0 + mb * 32 + lq, p.M - 1));
+  }
 #pragma unroll
   for (int mb = 0; mb < MB; mb++) {
     const int ml = mb * 32 + lq;
     const int m = m0 + ml;
     if (m < p.M) {
       float ssum = 0.f, ssq = 0.f;
-      if (PRO != PRO_NONE) {   // row statistics come from the kernel that produced the residual stream
-        ssum = p.rowstat[2 * m];
-        ssq = p.rowstat[2 * m + 1];
+      if (PRO != PRO_NONE) {
+        ssum = rst[mb].x;
+        ssq = rst[mb].y;
       }
       EpiOps ops;
       epilogue_preload<PRO, EPI>(p, nt, m, lh, ops);
