@@ -846,12 +846,12 @@ hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmPara
 // the normalisation that follows (g for LayerNorm, 1 + g for RMSNorm): the affine part of the norm
 // is folded into the activation cast, so the weights stay the checkpoint's bf16 values, and the
 // row statistics are applied after accumulation by the consumer (Sections 3.2 and 4.4).
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(ReduceParams p) {
-  __shared__ float sred[2][4];
+__global__ __launch_bounds__(512) void splitk_reduce_kernel(ReduceParams p) {
+  __shared__ float sred[2][8];
   const int m = blockIdx.x;
   const int ro = m;
   float sa = 0.f, sb = 0.f;
-  for (int n = threadIdx.x * 4; n < p.N; n += 1024) {
+  for (int n = threadIdx.x * 4; n < p.N; n += 2048) {   // one pass for rows of up to 2048 columns
     // bias and residual first, so that their round trip overlaps the partial sums
     f32x4 extra = {0.f, 0.f, 0.f, 0.f};
     if (p.bias != nullptr) extra = *reinterpret_cast<const f32x4*>(p.bias + n);
@@ -860,6 +860,8 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(ReduceParams p) {
       const int rr = p.resid_mod > 0 ? (m % p.resid_mod) : m;
       rv = *reinterpret_cast<const f32x4*>(p.resid + (size_t)rr * p.ldo + n);
     }
+    f32x4 gv = {1.f, 1.f, 1.f, 1.f};
+    if (p.gain != nullptr) gv = *reinterpret_cast<const f32x4*>(p.gain + n);
     // partial sums in batches of 8 loads in flight (clamped, unconditional), added in slice order
     f32x4 a = {0.f, 0.f, 0.f, 0.f};
     for (int z0 = 0; z0 < p.Z; z0 += 8) {
@@ -882,7 +884,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(ReduceParams p) {
       sa += a[j];
       sb += a[j] * a[j];
     }
-    if (p.gain != nullptr) a *= *reinterpret_cast<const f32x4*>(p.gain + n);
+    a *= gv;
     const bf16x4 ob = {(bf16)a[0], (bf16)a[1], (bf16)a[2], (bf16)a[3]};
     *reinterpret_cast<bf16x4*>(p.out_bf16 + xf_index(ro, n, p.ldo2 >> 4)) = ob;
   }
@@ -897,14 +899,20 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(ReduceParams p) {
   }
   __syncthreads();
   if (threadIdx.x == 0 && p.stat_out != nullptr) {
-    p.stat_out[2 * ro] = sred[0][0] + sred[0][1] + sred[0][2] + sred[0][3];
-    p.stat_out[2 * ro + 1] = sred[1][0] + sred[1][1] + sred[1][2] + sred[1][3];
+    float ta = 0.f, tb = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+      ta += sred[0][i];
+      tb += sred[1][i];
+    }
+    p.stat_out[2 * ro] = ta;
+    p.stat_out[2 * ro + 1] = tb;
   }
 }
 
 hipError_t launch_splitk_reduce(hipStream_t s, const ReduceParams& p) {
   if (p.N % 4 != 0 || p.ldp < p.N || p.ldo < p.N || p.ldo2 < p.N || p.ldo2 % 16 != 0 || p.M <= 0 || p.Z < 1) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)p.M), dim3(256), 0, s, p);
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)p.M), dim3(512), 0, s, p);
   return hipGetLastError();
 }
 
