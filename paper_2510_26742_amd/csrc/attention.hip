@@ -47,7 +47,7 @@ __global__ __launch_bounds__(512) void attention_kernel(AttnParams p) {
   const int lq = lane & 31;
   const int lh = lane >> 5;
   if ((int)blockIdx.y >= p.heads) {   // warm-up block; rank = linear block index (mod 8)
-    prefetch_role(p.pf, (int)blockIdx.x + (int)gridDim.x * ((int)blockIdx.y - p.heads));
+    if (blockIdx.z == 0) prefetch_role(p.pf, (int)blockIdx.x + (int)gridDim.x * ((int)blockIdx.y - p.heads));
     return;
   }
   const int tile = blockIdx.x;
@@ -61,7 +61,12 @@ __global__ __launch_bounds__(512) void attention_kernel(AttnParams p) {
     cbeg0 = view * (p.view_tokens >> 5);
     n0 = p.view_tokens >> 5;
   }
-  const int n1 = p.chunks1;
+  int n1 = p.chunks1;
+  if (p.key_splits > 1) {   // this block's share of segment 0; the last share also takes segment 1
+    cbeg0 = (int)blockIdx.z * p.chunks_per_split;
+    n0 = min(p.chunks_per_split, p.chunks0 - cbeg0);
+    if ((int)blockIdx.z != p.key_splits - 1) n1 = 0;
+  }
   const int ntot = n0 + n1;
   const bf16* kbase0 = p.k0 + ((size_t)head * p.kv_head_stride0 + (size_t)cbeg0 * S16 * 512) + lane * 8;
   const bf16* vbase0 = p.v0 + ((size_t)head * p.v_head_stride0 + (size_t)cbeg0 * NVB * 1024);
@@ -219,6 +224,12 @@ __global__ __launch_bounds__(512) void attention_kernel(AttnParams p) {
   for (int i = 0; i < ATT_WAVES; i++) l_all += lw[i * 32 + lq];
   const float inv = 1.0f / l_all;
   if (!row_ok) return;
+  if (p.ml_out != nullptr && w == 0 && lh == 0) {   // (row maximum, sum) of this share, for the consumer's merge
+    float* dst = p.ml_out + ((((size_t)blockIdx.z * p.heads + head) * gridDim.x * 32) + row) * 2;
+    dst[0] = m_all;
+    dst[1] = l_all;
+  }
+  bf16* outp = p.out + (size_t)blockIdx.z * p.out_split_stride;
 #pragma unroll
   for (int i = 0; i < 4; i++) {
     const int d = w * 32 + 8 * i + 4 * lh;
@@ -226,7 +237,7 @@ __global__ __launch_bounds__(512) void attention_kernel(AttnParams p) {
       const bf16x4 ob = {(bf16)(o[4 * i] * inv), (bf16)(o[4 * i + 1] * inv), (bf16)(o[4 * i + 2] * inv),
                          (bf16)(o[4 * i + 3] * inv)};
       const int col = head * p.head_dim + d;
-      *reinterpret_cast<bf16x4*>(p.out + ((size_t)(row >> 5) * (p.out_ld >> 4) + (col >> 4)) * 512 +
+      *reinterpret_cast<bf16x4*>(outp + ((size_t)(row >> 5) * (p.out_ld >> 4) + (col >> 4)) * 512 +
                                  (((col & 15) >> 3) * 32 + (row & 31)) * 8 + (col & 7)) = ob;
     }
   }
@@ -265,9 +276,17 @@ hipError_t launch_attention(hipStream_t s, const AttnParams& p) {
     if (p.view_tokens % 32 != 0 || p.Tq % p.view_tokens != 0 || p.chunks0 * 32 != p.Tq) return hipErrorInvalidValue;
     n0 = p.view_tokens / 32;
   }
+  if (p.key_splits > 1) {   // keys of segment 0 shared out over gridDim.z blocks, merged by the consumer
+    if (p.view_tokens > 0 || p.ml_out == nullptr || p.chunks_per_split < 1 || p.key_splits > 8) return hipErrorInvalidValue;
+    if ((p.key_splits - 1) * p.chunks_per_split >= p.chunks0 || p.key_splits * p.chunks_per_split < p.chunks0) return hipErrorInvalidValue;
+    if (p.out_split_stride < (size_t)((p.Tq + 31) / 32) * 32 * p.out_ld) return hipErrorInvalidValue;
+    n0 = p.chunks_per_split;
+  } else if (p.key_splits != 0 && p.key_splits != 1) {
+    return hipErrorInvalidValue;
+  }
   const int ntot = n0 + p.chunks1;
   if (n0 > 32) return hipErrorInvalidValue;   // at most 1024 keys in segment 0 per query row
-  dim3 grid((p.Tq + 31) / 32, p.heads, 1);
+  dim3 grid((p.Tq + 31) / 32, p.heads, p.key_splits > 1 ? p.key_splits : 1);
   if (p.pf.blocks != 0) {   // warm-up blocks as extra grid rows
     const PrefetchDesc& d = p.pf;
     if (d.blocks < 0 || d.blocks % 16 != 0 || d.blocks > 1024 || d.sink == nullptr || d.blocks % (int)grid.x != 0) return hipErrorInvalidValue;

@@ -642,8 +642,50 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny16_kernel(GemmParams
     wf[j] = *reinterpret_cast<const bf16x8*>(wbase + (size_t)j * 1024);
     xf[j] = *reinterpret_cast<const bf16x8*>(xbase + (size_t)j * 1024);
   }
-  // operands of the epilogue (wave 0), behind the operand loads
   const int m = mt16 * 16 + li;
+  // X given as attention shares over disjoint key ranges (k = 8 heads x 256, so wave w holds exactly
+  // head w): merge them while they arrive.  Share z carries its normalised output and (max, sum)
+  // of its exponentials; the weights are c_z = l_z exp(m_z - max m) / sum over shares.
+  if (NS == 8 && p.xsplits > 1) {
+    bf16x8 xo[3][NS];
+    float2 ml[4];
+#pragma unroll
+    for (int z = 1; z < 4; z++) {
+      const int ze = min(z, p.xsplits - 1);
+#pragma unroll
+      for (int j = 0; j < NS; j++) xo[z - 1][j] = *reinterpret_cast<const bf16x8*>(xbase + (size_t)ze * p.xsplit_stride + (size_t)j * 1024);
+    }
+#pragma unroll
+    for (int z = 0; z < 4; z++) {
+      const int ze = min(z, p.xsplits - 1);
+      ml[z] = *reinterpret_cast<const float2*>(p.xsplit_ml + (((size_t)ze * SK_WAVES + w) * 64 + min(m, 63)) * 2);
+    }
+    float mx = ml[0].x;
+#pragma unroll
+    for (int z = 1; z < 4; z++) mx = z < p.xsplits ? fmaxf(mx, ml[z].x) : mx;
+    float c[4], den = 0.f;
+#pragma unroll
+    for (int z = 0; z < 4; z++) {
+      c[z] = z < p.xsplits ? ml[z].y * __expf(ml[z].x - mx) : 0.f;
+      den += c[z];
+    }
+    const float rden = 1.0f / den;
+#pragma unroll
+    for (int z = 0; z < 4; z++) c[z] *= rden;
+#pragma unroll
+    for (int j = 0; j < NS; j++) {
+      bf16x8 o;
+#pragma unroll
+      for (int e = 0; e < 8; e++) {
+        float a = c[0] * (float)xf[j][e];
+#pragma unroll
+        for (int z = 1; z < 4; z++) a += c[z] * (float)xo[z - 1][j][e];
+        o[e] = (bf16)a;
+      }
+      xf[j] = o;
+    }
+  }
+  // operands of the epilogue (wave 0), behind the operand loads
   const int n4 = nt16 * 16 + 4 * lg;
   const bool live = w == 0 && m < p.M && n4 < p.n_valid;
   f32x4 rv = {0.f, 0.f, 0.f, 0.f}, gv = {1.f, 1.f, 1.f, 1.f}, bv = {0.f, 0.f, 0.f, 0.f};
@@ -799,6 +841,8 @@ hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmPara
     const int kc16 = p.W.k_pad >> 4;
     if (p.M > 64 || pro != PRO_NONE || epi != EPI_RESID || z_splits != 1 || (kc16 != 128 && kc16 != 256)) return hipErrorInvalidValue;
     if (p.out_f32 == nullptr || p.out_bf16 == nullptr || p.ldo % 4 != 0 || p.ldo2 % 16 != 0) return hipErrorInvalidValue;
+    if (p.xsplits > 1 && (kc16 != 128 || p.xsplits > 4 || p.xsplit_ml == nullptr || p.xsplit_stride < (size_t)64 * p.ldx))
+      return hipErrorInvalidValue;
     const int my = (p.M + 15) / 16;
     if (p.pf.blocks != 0 && (p.pf.blocks % my != 0 || (p.n_tiles * 2) % 8 != 0 || ((p.n_tiles * 2 + p.pf.blocks / my) * my) % 8 != 0))
       return hipErrorInvalidValue;

@@ -149,7 +149,7 @@ struct WsLayout {
   size_t st_images, st_ids, st_state, st_noise, xa;
   size_t xpatch, vh, vh_b, vq, vk, vv, vattn, vmid, part;
   size_t lx, lx_b, lq, kcache, vcache, lattn, lmid;
-  size_t stok, z, y, y_b, eq, ek, ev, eattn, emid;
+  size_t stok, z, y, y_b, eq, ek, ev, eattn, eml, emid;
   size_t vstat, lstat, estat, estat_parts, pf_sink;
   size_t total;
   size_t kcache_layer, vcache_layer;   // bytes per layer
@@ -267,7 +267,8 @@ void ws_layout(const pi0_config& c, const Dims& d, WsLayout& w) {
   w.eq = cur.take((size_t)d.H * 2 * 16 * 512 * 2);
   w.ek = cur.take((size_t)2 * 16 * 512 * 2);
   w.ev = cur.take((size_t)2 * 8 * 1024 * 2);
-  w.eattn = cur.take((size_t)64 * d.H * 256 * 2);
+  w.eattn = cur.take((size_t)4 * 64 * d.H * 256 * 2);   // up to 4 key shares
+  w.eml = cur.take((size_t)4 * d.H * 64 * 2 * 4);
   w.emid = cur.take((size_t)64 * d.Fx * 2);
   w.vstat = cur.take((size_t)d.maxI * 2 * 4);
   w.lstat = cur.take((size_t)d.maxPc * 32 * 2 * 4);
@@ -303,9 +304,10 @@ struct Tune {
   int lqkv = TILE_MID;    // prefix QKV
   int lgu = TILE_BIG;     // prefix gate||up
   int vo = TILE_MID, vd = TILE_MID, lo = TILE_MID, ld = TILE_BIG;   // split-K partial GEMMs: vision O / down, prefix O / down
-  int zvo = 2, zlo = 4, zld = 16, zvd = 4;
+  int zvo = 3, zlo = 4, zld = 16, zvd = 4;
   // warm-up blocks carried by the expert's launches (0 = none): QKV, attention, O, down
   int pfq = 64, pfa = 64, pfo = 128, pfd = 128;
+  int ksplit = 1;         // expert attention: key shares for prefixes beyond 256 keys
   int ae16 = 1;           // expert O / down on 16 x 16 tiles (256 blocks) instead of 32 x 32 (64 blocks)
 };
 
@@ -627,6 +629,10 @@ void run_denoise(Run& r, int P, Taps* taps) {
     f.tiles[r + 1] = pchunks; f.tile16[r + 1] = 1024;
   };
   const Tune& T = c->tune;
+  // prefixes beyond 256 keys: the attention of the expert is shared out over ceil(chunks / 8) blocks per
+  // (query tile, head); needs the 16 x 16 O projection (which merges the shares) and 8 heads of 256
+  const int ksplits = (T.ae16 && T.ksplit && d.H == 8 && pchunks > 8) ? ceil_div(pchunks, 8) : 1;
+  int o_splits = 1;
   auto resid_gemm = [&](const PW& pw, const bf16* X, int K, const float* gain, const PrefetchDesc& pf) {
     if (pw.k_pad == 2048 || pw.k_pad == 4096) {
       const int tile = T.ae16 ? TILE_SKINNY16 : TILE_SKINNY_FULLK;
@@ -638,6 +644,12 @@ void run_denoise(Run& r, int P, Taps* taps) {
       p.stat_out = at<float>(c, w.estat_parts);
       p.gain = gain;
       p.pf = pf;
+      if (o_splits > 1) {
+        p.xsplits = o_splits;
+        p.xsplit_stride = (size_t)64 * d.H * 256;
+        p.xsplit_ml = at<float>(c, w.eml);
+        o_splits = 1;
+      }
       RUN_GEMM(r, tile, PRO_NONE, EPI_RESID, p, 1);
       stat_ptr = at<float>(c, w.estat_parts);
       stat_parts = T.ae16 ? pw.n_pad / 16 : pw.n_pad / 32;
@@ -697,6 +709,12 @@ void run_denoise(Run& r, int P, Taps* taps) {
         a.suffix_mask = 1;
         a.scale = 1.0f / 16.0f;
         a.out = at<bf16>(c, w.eattn); a.out_ld = d.H * 256; a.head_dim = 256;
+        if (ksplits > 1) {   // long prefix: key shares over more blocks, merged by the O projection
+          a.key_splits = ksplits;
+          a.chunks_per_split = 8;
+          a.out_split_stride = (size_t)64 * d.H * 256;
+          a.ml_out = at<float>(c, w.eml);
+        }
         a.pf = pf_begin(T.pfa);
         pf_weights(a.pf, 0, L.gu);
         r.cls = PI0_OP_EXP_ATTN;
@@ -707,6 +725,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
         PrefetchDesc f = pf_begin(T.pfo);
         pf_weights(f, 0, L.down);
         r.cls = PI0_OP_EXP_O;
+        o_splits = ksplits;
         resid_gemm(L.o, at<bf16>(c, w.eattn), d.H * 256, at<float>(c, w.g_e2[l]), f);
       }
       {  // C7: RMS -> gate||up, fused gate
@@ -874,7 +893,7 @@ int pi0_create(const pi0_config* cfg, pi0_ctx** out) {
         {"vo", &c->tune.vo, 0, 1}, {"vd", &c->tune.vd, 0, 1}, {"lo", &c->tune.lo, 0, 1}, {"ld", &c->tune.ld, 0, 1}, {"zvo", &c->tune.zvo, 1, Z_MAX}, {"zlo", &c->tune.zlo, 1, Z_MAX},
         {"zld", &c->tune.zld, 1, Z_MAX}, {"zvd", &c->tune.zvd, 1, Z_MAX},
         {"pfq", &c->tune.pfq, 0, 1024}, {"pfa", &c->tune.pfa, 0, 1024}, {"pfo", &c->tune.pfo, 0, 1024},
-        {"pfd", &c->tune.pfd, 0, 1024}, {"ae16", &c->tune.ae16, 0, 1}};
+        {"pfd", &c->tune.pfd, 0, 1024}, {"ae16", &c->tune.ae16, 0, 1}, {"ksplit", &c->tune.ksplit, 0, 1}};
     for (auto& k : keys) {
       const char* f = strstr(env, k.key);
       while (f != nullptr && !((f == env || f[-1] == ',') && f[strlen(k.key)] == '=')) f = strstr(f + 1, k.key);

@@ -145,6 +145,12 @@ struct GemmParams {
   int q_mbs;          // 32-token blocks per head in the fragment-ordered q buffer
   // EPI_EULER
   float dt;
+  // TILE_SKINNY16 with k = heads * 256: X is given as xsplits attention shares (each ldx-padded, xsplit_stride
+  // elements apart) with their (row maximum, sum) pairs xsplit_ml[((z * 8 + head) * 64 + row) * 2]; the
+  // kernel merges them while loading (0 / 1 = X is a plain matrix)
+  int xsplits;
+  size_t xsplit_stride;
+  const float* xsplit_ml;
   // warm-up blocks for later launches (skinny tiles only)
   PrefetchDesc pf;
 };
@@ -209,6 +215,14 @@ struct AttnParams {
   bf16* out;           // XF layout, out_ld padded columns; head h at columns h * head_dim ..
   int out_ld;
   int head_dim;        // 72 or 256
+  // keys of segment 0 shared out over key_splits blocks per (query tile, head) (0 / 1 = off): share z
+  // takes chunks [z * chunks_per_split, ...), the last one also segment 1; each share writes its own
+  // normalised output at out + z * out_split_stride and (row maximum, sum of exponentials) at
+  // ml_out[((z * heads + head) * ceil32(Tq) + row) * 2]; the consumer merges them
+  int key_splits;
+  int chunks_per_split;
+  size_t out_split_stride;
+  float* ml_out;
   PrefetchDesc pf;     // warm-up blocks for later launches
 };
 hipError_t launch_attention(hipStream_t s, const AttnParams& p);
