@@ -647,41 +647,50 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny16_kernel(GemmParams
   // head w): merge them while they arrive.  Share z carries its normalised output and (max, sum)
   // of its exponentials; the weights are c_z = l_z exp(m_z - max m) / sum over shares.
   if (NS == 8 && p.xsplits > 1) {
+    const int nz = p.xsplits;             // 2 .. 4, uniform
     bf16x8 xo[3][NS];
     float2 ml[4];
+    const int mrow = min(m, 63);
+    ml[0] = *reinterpret_cast<const float2*>(p.xsplit_ml + ((size_t)w * 64 + mrow) * 2);
 #pragma unroll
     for (int z = 1; z < 4; z++) {
-      const int ze = min(z, p.xsplits - 1);
+      if (z < nz) {
 #pragma unroll
-      for (int j = 0; j < NS; j++) xo[z - 1][j] = *reinterpret_cast<const bf16x8*>(xbase + (size_t)ze * p.xsplit_stride + (size_t)j * 1024);
-    }
-#pragma unroll
-    for (int z = 0; z < 4; z++) {
-      const int ze = min(z, p.xsplits - 1);
-      ml[z] = *reinterpret_cast<const float2*>(p.xsplit_ml + (((size_t)ze * SK_WAVES + w) * 64 + min(m, 63)) * 2);
+        for (int j = 0; j < NS; j++) xo[z - 1][j] = *reinterpret_cast<const bf16x8*>(xbase + (size_t)z * p.xsplit_stride + (size_t)j * 1024);
+        ml[z] = *reinterpret_cast<const float2*>(p.xsplit_ml + (((size_t)z * SK_WAVES + w) * 64 + mrow) * 2);
+      }
     }
     float mx = ml[0].x;
 #pragma unroll
-    for (int z = 1; z < 4; z++) mx = z < p.xsplits ? fmaxf(mx, ml[z].x) : mx;
-    float c[4], den = 0.f;
+    for (int z = 1; z < 4; z++) {
+      if (z < nz) mx = fmaxf(mx, ml[z].x);
+    }
+    float c[4] = {0.f, 0.f, 0.f, 0.f}, den = 0.f;
 #pragma unroll
     for (int z = 0; z < 4; z++) {
-      c[z] = z < p.xsplits ? ml[z].y * __expf(ml[z].x - mx) : 0.f;
-      den += c[z];
+      if (z < nz) {
+        c[z] = ml[z].y * __expf(ml[z].x - mx);
+        den += c[z];
+      }
     }
     const float rden = 1.0f / den;
 #pragma unroll
     for (int z = 0; z < 4; z++) c[z] *= rden;
 #pragma unroll
     for (int j = 0; j < NS; j++) {
+      float a[8];
+#pragma unroll
+      for (int e = 0; e < 8; e++) a[e] = c[0] * (float)xf[j][e];
+#pragma unroll
+      for (int z = 1; z < 4; z++) {
+        if (z < nz) {
+#pragma unroll
+          for (int e = 0; e < 8; e++) a[e] += c[z] * (float)xo[z - 1][j][e];
+        }
+      }
       bf16x8 o;
 #pragma unroll
-      for (int e = 0; e < 8; e++) {
-        float a = c[0] * (float)xf[j][e];
-#pragma unroll
-        for (int z = 1; z < 4; z++) a += c[z] * (float)xo[z - 1][j][e];
-        o[e] = (bf16)a;
-      }
+      for (int e = 0; e < 8; e++) o[e] = (bf16)a[e];
       xf[j] = o;
     }
   }
