@@ -96,9 +96,35 @@ def test_error_paths_before_any_gpu_call(L):
     assert L.pi0_denoise(ctx, None, fake, fake, None) == binding.PI0_EINVAL
     assert L.pi0_infer(ctx, fake, 1, None, 0, fake, fake, None, None) == binding.PI0_EINVAL
     assert L.pi0_debug_forward(ctx, fake, 1, None, 0, fake, fake, fake, None, 0, None) == binding.PI0_EINVAL
+    # two-stream frame: streams must be two different non-null streams, and a prefill must exist
+    assert L.pi0_stream_frame(ctx, fake, 1, None, 0, fake, fake, fake, None, fake) == binding.PI0_EINVAL
+    assert L.pi0_stream_frame(ctx, fake, 1, None, 0, fake, fake, fake, fake, fake) == binding.PI0_EINVAL
+    assert L.pi0_stream_frame(ctx, fake, 1, None, 0, fake, None, fake, fake, fake + 64) == binding.PI0_EINVAL
+    assert L.pi0_stream_frame(ctx, fake, 1, None, 0, fake, fake, fake, fake, fake + 64) == binding.PI0_ESTATE
+    # per-class timing run
+    us = (ctypes.c_double * len(binding.OP_CLASSES))()
+    n = (ctypes.c_int * len(binding.OP_CLASSES))()
+    assert L.pi0_debug_profile(ctx, fake, 1, None, 0, fake, fake, fake, 0, us, n, None) == binding.PI0_EINVAL
+    assert L.pi0_debug_profile(ctx, fake, 1, None, 0, fake, fake, fake, 1, None, n, None) == binding.PI0_EINVAL
+    assert L.pi0_debug_profile(ctx, fake, 1, None, 0, fake, fake, fake, 1, us, n, None) == binding.PI0_ESTATE
     assert L.pi0_last_hip_error(ctx) == 0
     L.pi0_destroy(ctx)
     L.pi0_destroy(None)
+
+
+def test_sync_bench_rejects_bad_arguments(L):
+    fake = 0x10000
+    ms = ctypes.c_double(0.0)
+    ok = (1, 10, 1, fake, fake, fake)
+    assert L.pi0_sync_bench(5, 10, 1, fake, fake, fake, ctypes.byref(ms), None) == binding.PI0_EINVAL      # unknown mode
+    assert L.pi0_sync_bench(-1, 10, 1, fake, fake, fake, ctypes.byref(ms), None) == binding.PI0_EINVAL
+    assert L.pi0_sync_bench(0, 0, 1, fake, fake, fake, ctypes.byref(ms), None) == binding.PI0_EINVAL       # no updates
+    assert L.pi0_sync_bench(0, 10, 0, fake, fake, fake, ctypes.byref(ms), None) == binding.PI0_EINVAL      # no repetitions
+    assert L.pi0_sync_bench(0, 10, 1, None, fake, fake, ctypes.byref(ms), None) == binding.PI0_EINVAL
+    assert L.pi0_sync_bench(0, 10, 1, fake + 4, fake, fake, ctypes.byref(ms), None) == binding.PI0_EINVAL  # misaligned
+    assert L.pi0_sync_bench(0, 10, 1, fake, fake, None, ctypes.byref(ms), None) == binding.PI0_EINVAL
+    assert L.pi0_sync_bench(0, 10, 1, fake, fake, fake, None, None) == binding.PI0_EINVAL
+    assert len(binding.OP_CLASSES) == 21 and binding.SYNC_MODES["fused"] == 4
 
 
 def test_kernel_count_and_taps(L):
