@@ -762,6 +762,7 @@ int gemm_rows_per_tile(int tile) {
     case TILE_SKINNY: return 64;
     case TILE_SKINNY_FULLK: return 64;
     case TILE_SKINNY16: return 64;
+    case TILE_SMALL: return 64;
     default: return -1;
   }
 }
@@ -793,7 +794,8 @@ static hipError_t set_attr() {
   X(T, MB, WN, D, PRO_RMS, EPI_GEGLU)
 #define GEMM_VARIANTS(X)           \
   TALL_EPIS(X, TILE_BIG, 8, 4, 3)  \
-  TALL_EPIS(X, TILE_MID, 2, 4, 6)
+  TALL_EPIS(X, TILE_MID, 2, 4, 6)   \
+  TALL_EPIS(X, TILE_SMALL, 2, 2, 6)
 
 #define SKINNY_VARIANTS(X)      \
   X(PRO_NONE, EPI_RESID)        \

@@ -300,14 +300,16 @@ enum { KIND_PREFILL = 0, KIND_DENOISE = 1, KIND_INFER = 2 };
 // gfx950 counterparts).  Overridable for tuning runs through the environment variable PI0_TUNE,
 // e.g. PI0_TUNE="vis=1,lqkv=1,lgu=0,vo=1,vd=1,lo=0,ld=0,zvo=6,zlo=8,zld=16".
 struct Tune {
-  int vis = TILE_MID;     // vision QKV / up / patch / projector
+  int vis = TILE_MID;     // vision patch / projector (and QKV / up unless overridden below)
+  int vqkv = -1, vup = -1; // vision QKV / up tile (-1: same as vis)
   int lqkv = TILE_MID;    // prefix QKV
   int lgu = TILE_BIG;     // prefix gate||up
   int vo = TILE_MID, vd = TILE_MID, lo = TILE_MID, ld = TILE_BIG;   // split-K partial GEMMs: vision O / down, prefix O / down
   int zvo = 3, zlo = 4, zld = 16, zvd = 4;
   // warm-up blocks carried by the expert's launches (0 = none): QKV, attention, O, down
   int pfq = 64, pfa = 64, pfo = 128, pfd = 128;
-  int ksplit = 1;         // expert attention: key shares for prefixes beyond 256 keys
+  int ksplit = 1;         // expert attention: key shares for prefixes beyond kcps chunks
+  int kcps = 8;
   int ae16 = 1;           // expert O / down on 16 x 16 tiles (256 blocks) instead of 32 x 32 (64 blocks)
 };
 
@@ -454,10 +456,12 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
                     at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv, T.vis, at<float>(c, w.vstat), at<float>(c, w.g_v1[0]),
                     at<float>(c, w.pos), d.T);
   const int vchunks = I / 32;
+  // one view: the QKV GEMM has too few 64 x 128 tiles for 256 CUs, 64 x 64 tiles spread it further
+  const int tqkv = T.vqkv >= 0 ? T.vqkv : (I <= 256 ? TILE_SMALL : T.vis), tup = T.vup >= 0 ? T.vup : T.vis;
   for (int l = 0; l < d.Lv; l++) {
     const WsVis& L = w.vis[l];
     {  // A1: LN -> QKV (+bias), keys/values straight into attention fragment order
-      GemmParams p = gp_base(c, L.qkv, at<bf16>(c, w.vh_b), d.Dv, I, T.vis, d.Dv);
+      GemmParams p = gp_base(c, L.qkv, at<bf16>(c, w.vh_b), d.Dv, I, tqkv, d.Dv);
       p.bias = at<float>(c, L.qkv.bias);
       p.colsum = at<float>(c, L.qkv.colsum);
       p.rowstat = at<float>(c, w.vstat);
@@ -469,7 +473,7 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
       p.q_cols = d.Dv; p.k_cols = d.Dv;
       p.head_dim = d.hdv; p.dqk_pad = 80; p.nvb = 3; p.kv_heads = d.Hv; p.kv_chunks = vchunks;
       r.cls = PI0_OP_VIS_QKV;
-      RUN_GEMM(r, T.vis, PRO_LN, EPI_QKV, p, 1);
+      RUN_GEMM(r, tqkv, PRO_LN, EPI_QKV, p, 1);
     }
     {  // A2: attention inside each view
       AttnParams a;
@@ -491,14 +495,14 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
                       at<float>(c, L.o.bias), at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv, T.vo, at<float>(c, w.vstat),
                       at<float>(c, w.g_v2[l]));
     {  // A4: LN -> up (+bias, GELU)
-      GemmParams p = gp_base(c, L.up, at<bf16>(c, w.vh_b), d.Dv, I, T.vis, d.Dv);
+      GemmParams p = gp_base(c, L.up, at<bf16>(c, w.vh_b), d.Dv, I, tup, d.Dv);
       p.bias = at<float>(c, L.up.bias);
       p.colsum = at<float>(c, L.up.colsum);
       p.rowstat = at<float>(c, w.vstat);
       p.out_bf16 = at<bf16>(c, w.vmid);
       p.ldo = d.Fv_kp; p.n_valid = L.up.n_pad; p.act = ACT_GELU;
       r.cls = PI0_OP_VIS_UP;
-      RUN_GEMM(r, T.vis, PRO_LN, EPI_BF16, p, 1);
+      RUN_GEMM(r, tup, PRO_LN, EPI_BF16, p, 1);
     }
     // A5: down (+bias, residual)
     r.cls = PI0_OP_VIS_DOWN;
@@ -631,7 +635,8 @@ void run_denoise(Run& r, int P, Taps* taps) {
   const Tune& T = c->tune;
   // prefixes beyond 256 keys: the attention of the expert is shared out over ceil(chunks / 8) blocks per
   // (query tile, head); needs the 16 x 16 O projection (which merges the shares) and 8 heads of 256
-  const int ksplits = (T.ae16 && T.ksplit && d.H == 8 && pchunks > 8) ? ceil_div(pchunks, 8) : 1;
+  const int kcps = T.kcps;   // key chunks per share
+  const int ksplits = (T.ae16 && T.ksplit && d.H == 8 && pchunks > kcps && ceil_div(pchunks, kcps) <= 4) ? ceil_div(pchunks, kcps) : 1;
   int o_splits = 1;
   auto resid_gemm = [&](const PW& pw, const bf16* X, int K, const float* gain, const PrefetchDesc& pf) {
     if (pw.k_pad == 2048 || pw.k_pad == 4096) {
@@ -711,7 +716,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
         a.out = at<bf16>(c, w.eattn); a.out_ld = d.H * 256; a.head_dim = 256;
         if (ksplits > 1) {   // long prefix: key shares over more blocks, merged by the O projection
           a.key_splits = ksplits;
-          a.chunks_per_split = 8;
+          a.chunks_per_split = kcps;
           a.out_split_stride = (size_t)64 * d.H * 256;
           a.ml_out = at<float>(c, w.eml);
         }
@@ -889,11 +894,12 @@ int pi0_create(const pi0_config* cfg, pi0_ctx** out) {
 
   if (const char* env = getenv("PI0_TUNE")) {
     struct { const char* key; int* dst; int lo, hi; } keys[] = {
-        {"vis", &c->tune.vis, 0, 1},   {"lqkv", &c->tune.lqkv, 0, 1}, {"lgu", &c->tune.lgu, 0, 1},
-        {"vo", &c->tune.vo, 0, 1}, {"vd", &c->tune.vd, 0, 1}, {"lo", &c->tune.lo, 0, 1}, {"ld", &c->tune.ld, 0, 1}, {"zvo", &c->tune.zvo, 1, Z_MAX}, {"zlo", &c->tune.zlo, 1, Z_MAX},
+        {"vis", &c->tune.vis, 0, 5},   {"lqkv", &c->tune.lqkv, 0, 5}, {"lgu", &c->tune.lgu, 0, 5},
+        {"vqkv", &c->tune.vqkv, -1, 5}, {"vup", &c->tune.vup, -1, 5},
+        {"vo", &c->tune.vo, 0, 5}, {"vd", &c->tune.vd, 0, 5}, {"lo", &c->tune.lo, 0, 5}, {"ld", &c->tune.ld, 0, 5}, {"zvo", &c->tune.zvo, 1, Z_MAX}, {"zlo", &c->tune.zlo, 1, Z_MAX},
         {"zld", &c->tune.zld, 1, Z_MAX}, {"zvd", &c->tune.zvd, 1, Z_MAX},
         {"pfq", &c->tune.pfq, 0, 1024}, {"pfa", &c->tune.pfa, 0, 1024}, {"pfo", &c->tune.pfo, 0, 1024},
-        {"pfd", &c->tune.pfd, 0, 1024}, {"ae16", &c->tune.ae16, 0, 1}, {"ksplit", &c->tune.ksplit, 0, 1}};
+        {"pfd", &c->tune.pfd, 0, 1024}, {"ae16", &c->tune.ae16, 0, 1}, {"ksplit", &c->tune.ksplit, 0, 1}, {"kcps", &c->tune.kcps, 2, 8}};
     for (auto& k : keys) {
       const char* f = strstr(env, k.key);
       while (f != nullptr && !((f == env || f[-1] == ',') && f[strlen(k.key)] == '=')) f = strstr(f + 1, k.key);

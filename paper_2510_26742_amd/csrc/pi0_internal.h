@@ -161,7 +161,8 @@ enum GemmTile {
   TILE_MID = 1,     // 64 tokens x 128 features per block (4 waves), 8 stages in flight
   TILE_SKINNY = 2,  // <= 64 tokens, one 32-feature tile per block, 8 waves split k <= 1024, loads issued at once
   TILE_SKINNY_FULLK = 3,  // <= 64 tokens, k = 2048 or 4096 in one block per (feature tile, 32-token block), residual epilogue
-  TILE_SKINNY16 = 4       // same on 16-feature x 16-token tiles (mfma 16x16x32): 256 blocks for the expert's O / down
+  TILE_SKINNY16 = 4,      // same on 16-feature x 16-token tiles (mfma 16x16x32): 256 blocks for the expert's O / down
+  TILE_SMALL = 5          // 64 tokens x 64 features per block (2 waves), 6 stages: small GEMMs of the vision tower
 };
 
 hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmParams& p, int z_splits);
