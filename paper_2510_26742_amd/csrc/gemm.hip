@@ -499,7 +499,10 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
 #pragma unroll
   for (int mb = 0; mb < 2; mb++)
 #pragma unroll
-    for (int r = 0; r < 16; r++) red[(((size_t)w * 2 + mb) * 16 + r) * 64 + lane] = acc[mb][r];
+    for (int q = 0; q < 4; q++) {   // 16-byte pieces: [wave][token block][q][lane][4]
+      const f32x4 v4 = {acc[mb][4 * q], acc[mb][4 * q + 1], acc[mb][4 * q + 2], acc[mb][4 * q + 3]};
+      *reinterpret_cast<f32x4*>(red + ((((size_t)w * 2 + mb) * 4 + q) * 64 + lane) * 4) = v4;
+    }
   if (PRO != PRO_NONE) {
     float pa = 0.f, pb = 0.f;
 #pragma unroll
@@ -532,7 +535,11 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
 #pragma unroll
   for (int ww = 0; ww < SK_WAVES; ww++)
 #pragma unroll
-    for (int r = 0; r < 16; r++) sum[r] += red[(((size_t)ww * 2 + mb) * 16 + r) * 64 + lane];
+    for (int q = 0; q < 4; q++) {
+      const f32x4 v4 = *reinterpret_cast<const f32x4*>(red + ((((size_t)ww * 2 + mb) * 4 + q) * 64 + lane) * 4);
+#pragma unroll
+      for (int j = 0; j < 4; j++) sum[4 * q + j] += v4[j];
+    }
   const int ml = mb * 32 + lq;
   if (ml < p.M) {
     float ssum = 0.f, ssq = 0.f;
@@ -617,7 +624,7 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_fullk_kernel(GemmPa
 // Accumulator: lane -> token lane % 16, features 4 * (lane / 16) + r.
 template <int NS>
 __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny16_kernel(GemmParams p) {
-  __shared__ float red[SK_WAVES][4][64];
+  __shared__ __attribute__((aligned(16))) float red[SK_WAVES][64][4];
   const int t = threadIdx.x;
   const int lane = t & 63;
   const int w = t >> 6;
@@ -710,16 +717,17 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny16_kernel(GemmParams
     acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[j + 1], xf[j + 1], acc1, 0, 0, 0);
   }
 #pragma unroll
-  for (int r = 0; r < 4; r++) red[w][r][lane] = acc0[r] + acc1[r];
+  for (int r = 0; r < 4; r++) acc0[r] += acc1[r];
+  *reinterpret_cast<f32x4*>(&red[w][lane][0]) = acc0;
   __syncthreads();
   if (w != 0) return;
   float v[4];
+  {
+    f32x4 a = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-  for (int r = 0; r < 4; r++) {
-    float a = 0.f;
+    for (int ww = 0; ww < SK_WAVES; ww++) a += *reinterpret_cast<const f32x4*>(&red[ww][lane][0]);
 #pragma unroll
-    for (int ww = 0; ww < SK_WAVES; ww++) a += red[ww][r][lane];
-    v[r] = a + bv[r] + rv[r];
+    for (int r = 0; r < 4; r++) v[r] = a[r] + bv[r] + rv[r];
   }
   float st_a = 0.f, st_b = 0.f;
   const int mo = m + p.row_offset;
