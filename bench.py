@@ -20,13 +20,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
-# kernel symbols of the operation classes (as rocprofv3 prints them) and, where a counter run exists,
-# the HBM bytes per launch it measured (FETCH_SIZE + WRITE_SIZE, calibrated against a copy kernel)
-KERNEL_SYMBOL = {
-    "exp_down": "gemm_skinny_fullk_kernel<2>", "exp_o": "gemm_skinny_fullk_kernel<1>",
-    "exp_gateup": "gemm_skinny_kernel<1, 4>", "exp_qkv": "gemm_skinny_kernel<1, 3>",
-    "exp_attn": "attention_kernel<256, 8, *, *>", "llm_gateup": "gemm_kernel<8, 4, 3, 1, 4>",
-}
+# HBM-side bytes per launch of an operation class, where a counter run exists (2 x FETCH_SIZE + WRITE_SIZE,
+# calibrated against a copy kernel)
 PMC_TRAFFIC_BYTES = {   # profiles/counters_full_pi0_1view_eager_pass.txt (includes what the launch reads ahead)
     "exp_down": 18929664, "exp_gateup": 18613248, "exp_o": 15499264, "exp_qkv": 11216077, "exp_attn": 20117299,
     "llm_gateup": 151370342,
@@ -148,7 +143,11 @@ def main() -> int:
         log("[bench] class %-10s launches %5d avg %8.2f us total %9.1f us  %s" % (
             r["class"], r["launches"], r["avg_us"], r["total_us"],
             ("%s %.1f %s = %.3f of peak" % (r["bound"], r["achieved"], r["unit"], r["frac"])) if "bound" in r else ""))
-    dominant = next(r for r in rows if "bound" in r)
+    krows = roofline.kernel_rooflines(roofline.class_work(cfg, headline_views, 0), timing, PMC_TRAFFIC_BYTES)
+    for r in krows:
+        log("[bench] kernel %-22s launches %5d avg %8.2f us total %9.1f us  %s %.1f %s = %.3f of peak" % (
+            r["kernel"], r["launches"], r["avg_us"], r["total_us"], r["bound"], r["achieved"], r["unit"], r["frac"]))
+    dominant = krows[0]
 
     # Section 6's concurrent mode: prefill of frame k beside the denoise of frame k-1 (two streams)
     sp2, sd2 = torch.cuda.Stream(device=dev), torch.cuda.Stream(device=dev)
@@ -210,13 +209,15 @@ def main() -> int:
         "paper_rtx4090_ms": {"1": 20.0, "2": 27.3, "3": 36.8},
         # frame interval when the prefill of frame k overlaps the denoise of frame k-1 (pi0_stream_frame)
         "two_stream_frame_interval_ms": stream_ms,
-        # the operation class with the largest share of the pass (event-timed, eager launches)
+        # the kernel (all launches of one template family) with the largest share of the pass: algorithmic
+        # bytes of its launches / their event-timed duration (eager launches, 3 passes)
         "roofline": {"bound": dominant["bound"], "achieved": dominant["achieved"], "peak": dominant["peak"],
-                     "unit": dominant["unit"], "frac": dominant["frac"],
-                     "traffic": PMC_TRAFFIC_BYTES.get(dominant["class"]),
-                     "kernel": dominant["class"], "kernel_symbol": KERNEL_SYMBOL.get(dominant["class"]),
+                     "unit": dominant["unit"], "frac": dominant["frac"], "traffic": dominant["traffic"],
+                     "kernel": dominant["kernel"], "classes": dominant["classes"],
                      "avg_us": dominant["avg_us"], "launches_per_pass": dominant["launches"] // 3,
-                     "algorithmic": dominant.get("algorithmic_bytes", dominant.get("algorithmic_flops"))},
+                     "algorithmic_bytes_per_launch": dominant["algorithmic_bytes_per_launch"],
+                     "algorithmic_flops_per_launch": dominant["algorithmic_flops_per_launch"]},
+        "roofline_kernels": krows,
         "roofline_classes": rows,
         # Section 5.2: ms for 1378 dependent updates; the paper's RTX 4090 figures for the same experiment
         "sync_overhead_ms": {"mi355x": sync_ms, "extra_per_graph_node_us": round((sync_ms["graph"] - sync_ms["fused"]) / 1.378, 3),

@@ -436,8 +436,11 @@ __global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(1, 1)))
 #define SK_WAVES 8
 #define SK_KMAX 1024
 
-template <int PRO, int EPI>
+// MS = 1: the two 32-token blocks go to separate blocks (gridDim.z = 2), which halves the activation
+// bytes per CU; used where the launch would otherwise leave most CUs idle (the expert's QKV).
+template <int PRO, int EPI, int MS = 0>
 __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p) {
+  constexpr int NMB = MS ? 1 : 2;              // token blocks per block
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   float* red = reinterpret_cast<float*>(smem_raw);                 // [8 waves][2][16][64]
   const int t = threadIdx.x;
@@ -446,7 +449,7 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
   const int lq = lane & 31;
   const int lh = lane >> 5;
   if ((int)blockIdx.x >= p.n_tiles) {   // warm-up block (only launched with gridDim.y == 1)
-    prefetch_role(p.pf, (int)blockIdx.x - p.n_tiles);
+    if (blockIdx.z == 0) prefetch_role(p.pf, (int)blockIdx.x - p.n_tiles);
     return;
   }
   const int nt = blockIdx.x;
@@ -461,16 +464,18 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
   // producer); wave w adds parts w, w+8, ... for row `lane`, the epilogue adds the 8 wave sums
   float* sstat = red + SK_WAVES * 2 * 16 * 64;     // [64 rows][2] after the reduction below
   float* sstat8 = sstat + 128;                     // [8 waves][64][2]
-  bf16x8 wf[8], xf[2][8];
+  bf16x8 wf[8], xf[NMB][8];
   const bf16* wbase = p.W.w + ((size_t)nt * KC16 + (kbeg >> 4)) * 512 + lane * 8;
   const bf16* xbase = p.X + (size_t)(kbeg >> 4) * 512 + lane * 8;
-  const int mb1 = p.M > 32 ? 1 : 0;            // second token block (clamped when M <= 32)
+  const int mb_last = p.M > 32 ? 1 : 0;        // last token block (clamps when M <= 32)
+  const int mb_first = MS ? min((int)blockIdx.z, mb_last) : 0;   // global index of local token block 0
 #pragma unroll
   for (int i = 0; i < 8; i++) {
     const int st = min(w * 8 + i, n16 - 1);    // clamped: steps beyond the range are never used
     wf[i] = *reinterpret_cast<const bf16x8*>(wbase + (size_t)st * 512);
-    xf[0][i] = *reinterpret_cast<const bf16x8*>(xbase + (size_t)st * 512);
-    xf[1][i] = *reinterpret_cast<const bf16x8*>(xbase + ((size_t)mb1 * XKC16 + st) * 512);
+#pragma unroll
+    for (int mb = 0; mb < NMB; mb++)
+      xf[mb][i] = *reinterpret_cast<const bf16x8*>(xbase + ((size_t)min(mb_first + mb, mb_last) * XKC16 + st) * 512);
   }
   // statistics partials: issued behind the operand loads (same round trip), clamped and unconditional
   float2 sp[8];
@@ -481,23 +486,24 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
       sp[jj] = *reinterpret_cast<const float2*>(p.rowstat + ((size_t)j * 64 + lane) * 2);
     }
   }
-  // operands of the epilogue (waves 0 and 1 run it), in the same round trip
+  // operands of the epilogue (wave i finishes local token block i), in the same round trip
   EpiOps ops;
-  if (w < 2 && w * 32 + lq < p.M) epilogue_preload<PRO, EPI>(p, nt, w * 32 + lq, lh, ops);
-  f32x16 acc[2];
+  const int mrow = (mb_first + w) * 32 + lq;   // the row this lane finishes if w < NMB
+  if (w < NMB && mrow < p.M) epilogue_preload<PRO, EPI>(p, nt, mrow, lh, ops);
+  f32x16 acc[NMB];
 #pragma unroll
-  for (int mb = 0; mb < 2; mb++)
+  for (int mb = 0; mb < NMB; mb++)
 #pragma unroll
     for (int r = 0; r < 16; r++) acc[mb][r] = 0.f;
 #pragma unroll
   for (int i = 0; i < 8; i++) {
     if (w * 8 + i < n16) {
 #pragma unroll
-      for (int mb = 0; mb < 2; mb++) acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[mb][i], acc[mb], 0, 0, 0);
+      for (int mb = 0; mb < NMB; mb++) acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[mb][i], acc[mb], 0, 0, 0);
     }
   }
 #pragma unroll
-  for (int mb = 0; mb < 2; mb++)
+  for (int mb = 0; mb < NMB; mb++)
 #pragma unroll
     for (int q = 0; q < 4; q++) {   // 16-byte pieces: [wave][token block][q][lane][4]
       const f32x4 v4 = {acc[mb][4 * q], acc[mb][4 * q + 1], acc[mb][4 * q + 2], acc[mb][4 * q + 3]};
@@ -516,9 +522,10 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
     sstat8[(w * 64 + lane) * 2 + 1] = pb;
   }
   __syncthreads();
-  if (w >= 2) return;
-  if (PRO != PRO_NONE) {   // waves 0 and 1 each finish the statistics of the 32 rows they own (lanes 0..31 suffice)
-    const int r = w * 32 + lq;
+  if (w >= NMB) return;
+  if (MS && (int)blockIdx.z > mb_last) return;   // M <= 32: the second block of a split launch has nothing to store
+  if (PRO != PRO_NONE) {   // each finishing wave sums the statistics of the 32 rows it owns (lanes 0..31 suffice)
+    const int r = (mb_first + w) * 32 + lq;
     float a = 0.f, b = 0.f;
 #pragma unroll
     for (int ww = 0; ww < SK_WAVES; ww++) {
@@ -540,7 +547,7 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
 #pragma unroll
       for (int j = 0; j < 4; j++) sum[4 * q + j] += v4[j];
     }
-  const int ml = mb * 32 + lq;
+  const int ml = mrow;
   if (ml < p.M) {
     float ssum = 0.f, ssq = 0.f;
     if (PRO != PRO_NONE) {
@@ -821,6 +828,11 @@ hipError_t gemm_init_attributes() {
   }
   SKINNY_VARIANTS(X)
 #undef X
+  {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_kernel<PRO_RMS, EPI_QKV, 1>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, skinny_smem_bytes());
+    if (e != hipSuccess) return e;
+  }
 #define X(T, MB, WN, D, PRO, EPI)                                     \
   {                                                                   \
     hipError_t e = set_attr<MB, WN, D, PRO, EPI>();                   \
@@ -882,6 +894,11 @@ hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmPara
   if (tile == TILE_SKINNY) {
     if (pro != PRO_NONE && (p.rowstat_parts < 1 || p.rowstat_parts > 8 * SK_WAVES)) return hipErrorInvalidValue;
     if (p.M > 64 || p.m_tiles != 1 || p.k_per_split > SK_KMAX || p.k_per_split % 16 != 0) return hipErrorInvalidValue;
+    if (p.m_split) {   // one block per (feature tile, 32-token block)
+      if (pro != PRO_RMS || epi != EPI_QKV || z_splits != 1) return hipErrorInvalidValue;
+      gemm_skinny_kernel<PRO_RMS, EPI_QKV, 1><<<dim3(p.n_tiles + p.pf.blocks, 1, 2), dim3(64 * SK_WAVES), skinny_smem_bytes(), s>>>(p);
+      return hipGetLastError();
+    }
 #define X(PRO, EPI)                                                                                          \
   if (pro == PRO && epi == EPI) {                                                                            \
     gemm_skinny_kernel<PRO, EPI><<<dim3(p.n_tiles + p.pf.blocks, z_splits), dim3(64 * SK_WAVES), skinny_smem_bytes(), s>>>(p); \

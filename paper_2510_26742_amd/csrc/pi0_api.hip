@@ -308,6 +308,7 @@ struct Tune {
   int zvo = 3, zlo = 4, zld = 16, zvd = 4;
   // warm-up blocks carried by the expert's launches (0 = none): QKV, attention, O, down
   int pfq = 64, pfa = 64, pfo = 128, pfd = 128;
+  int qms = 1;            // expert QKV: token blocks on separate blocks (160 instead of 80)
   int ksplit = 1;         // expert attention: key shares for prefixes beyond kcps chunks
   int kcps = 8;
   int ae16 = 1;           // expert O / down on 16 x 16 tiles (256 blocks) instead of 32 x 32 (64 blocks)
@@ -699,6 +700,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
         p.pos0 = P;
         p.q_cols = d.H * 256; p.k_cols = 256;
         p.head_dim = 256; p.dqk_pad = 256; p.nvb = 8; p.kv_heads = 1; p.kv_chunks = 2;
+        p.m_split = T.qms;
         p.pf = pf_begin(T.pfq);
         pf_weights(p.pf, 0, L.o);
         r.cls = PI0_OP_EXP_QKV;
@@ -899,7 +901,7 @@ int pi0_create(const pi0_config* cfg, pi0_ctx** out) {
         {"vo", &c->tune.vo, 0, 5}, {"vd", &c->tune.vd, 0, 5}, {"lo", &c->tune.lo, 0, 5}, {"ld", &c->tune.ld, 0, 5}, {"zvo", &c->tune.zvo, 1, Z_MAX}, {"zlo", &c->tune.zlo, 1, Z_MAX},
         {"zld", &c->tune.zld, 1, Z_MAX}, {"zvd", &c->tune.zvd, 1, Z_MAX},
         {"pfq", &c->tune.pfq, 0, 1024}, {"pfa", &c->tune.pfa, 0, 1024}, {"pfo", &c->tune.pfo, 0, 1024},
-        {"pfd", &c->tune.pfd, 0, 1024}, {"ae16", &c->tune.ae16, 0, 1}, {"ksplit", &c->tune.ksplit, 0, 1}, {"kcps", &c->tune.kcps, 2, 8}};
+        {"pfd", &c->tune.pfd, 0, 1024}, {"ae16", &c->tune.ae16, 0, 1}, {"ksplit", &c->tune.ksplit, 0, 1}, {"kcps", &c->tune.kcps, 2, 8}, {"qms", &c->tune.qms, 0, 1}};
     for (auto& k : keys) {
       const char* f = strstr(env, k.key);
       while (f != nullptr && !((f == env || f[-1] == ',') && f[strlen(k.key)] == '=')) f = strstr(f + 1, k.key);

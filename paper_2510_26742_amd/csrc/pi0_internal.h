@@ -112,6 +112,7 @@ struct GemmParams {
   int k_per_split;    // k range of one blockIdx.z slice, multiple of 64 * WK
   int k_true;         // divisor of the row statistics
   int m_tiles;        // number of MB*32 row tiles
+  int m_split;        // TILE_SKINNY QKV: 1 = one block per (feature tile, 32-token block)
   // statistics / affine
   const float* bias;    // [n_pad] or null
   const float* colsum;  // [n_pad], PRO_LN only: sum_k W'[n][k]

@@ -175,3 +175,58 @@ def class_rooflines(work: dict, timing: dict) -> list:
         rows.append(row)
     rows.sort(key=lambda r: -r["total_us"])
     return rows
+
+
+# which kernel (template family, as rocprofv3 names it) runs each operation class
+KERNEL_OF_CLASS = {
+    "vis_patch": "gemm_kernel", "vis_qkv": "gemm_kernel", "vis_o": "gemm_kernel", "vis_up": "gemm_kernel",
+    "vis_down": "gemm_kernel", "vis_proj": "gemm_kernel", "llm_qkv": "gemm_kernel", "llm_o": "gemm_kernel",
+    "llm_gateup": "gemm_kernel", "llm_down": "gemm_kernel",
+    "vis_attn": "attention_kernel", "llm_attn": "attention_kernel", "exp_attn": "attention_kernel",
+    "exp_qkv": "gemm_skinny_kernel", "exp_gateup": "gemm_skinny_kernel", "exp_out": "gemm_skinny_kernel",
+    "exp_o": "gemm_skinny16_kernel", "exp_down": "gemm_skinny16_kernel",
+    "reduce": "splitk_reduce_kernel",
+}
+
+
+def kernel_rooflines(work: dict, timing: dict, traffic: dict | None = None) -> list:
+    """Per kernel (all launches of one template family): total time, launches, algorithmic bytes and flops summed
+    over its launches, the bound that dominates, the achieved rate over the kernel's total time and the
+    fraction of the MI355X peak; `traffic` (measured HBM-side bytes per launch by class) is averaged over the
+    launches it covers, None if a class of the family has no counter figure."""
+    fam = {}
+    for name, (total_us, launches) in timing.items():
+        k = KERNEL_OF_CLASS.get(name)
+        if k is None or launches == 0 or name not in work:
+            continue
+        f = fam.setdefault(k, {"kernel": k, "classes": [], "launches": 0, "total_us": 0.0, "bytes": 0.0, "flops": 0.0,
+                               "traffic": 0.0, "traffic_ok": True})
+        b, fl = work[name]
+        f["classes"].append(name)
+        f["launches"] += launches
+        f["total_us"] += total_us
+        f["bytes"] += b * launches
+        f["flops"] += fl * launches
+        if traffic and name in traffic:
+            f["traffic"] += traffic[name] * launches
+        else:
+            f["traffic_ok"] = False
+    rows = []
+    for f in fam.values():
+        t = f["total_us"] * 1e-6
+        t_mem, t_cmp = f["bytes"] / MI355X_BW, f["flops"] / MI355X_FLOPS
+        row = {"kernel": f["kernel"], "classes": f["classes"], "launches": f["launches"],
+               "avg_us": round(f["total_us"] / f["launches"], 3), "total_us": round(f["total_us"], 1),
+               "algorithmic_bytes_per_launch": int(f["bytes"] / f["launches"]),
+               "algorithmic_flops_per_launch": int(f["flops"] / f["launches"]),
+               "traffic": int(f["traffic"] / f["launches"]) if f["traffic_ok"] else None}
+        if t_mem >= t_cmp:
+            ach = f["bytes"] / t / 1e9
+            row.update(bound="hbm", achieved=round(ach, 1), peak=MI355X_BW / 1e9, unit="GB/s", frac=round(ach / (MI355X_BW / 1e9), 4))
+        else:
+            ach = f["flops"] / t / 1e12
+            row.update(bound="mfma", achieved=round(ach, 1), peak=MI355X_FLOPS / 1e12, unit="TFLOP/s",
+                       frac=round(ach / (MI355X_FLOPS / 1e12), 4))
+        rows.append(row)
+    rows.sort(key=lambda r: -r["total_us"])
+    return rows
