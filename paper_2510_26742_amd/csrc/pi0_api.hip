@@ -304,8 +304,8 @@ struct Tune {
   int vqkv = -1, vup = -1; // vision QKV / up tile (-1: same as vis)
   int lqkv = TILE_MID;    // prefix QKV
   int lgu = TILE_BIG;     // prefix gate||up
-  int vo = TILE_MID, vd = TILE_MID, lo = TILE_MID, ld = TILE_BIG;   // split-K partial GEMMs: vision O / down, prefix O / down
-  int zvo = 3, zlo = 4, zld = 16, zvd = 4;
+  int vo = TILE_MID, vd = -1, lo = TILE_MID, ld = TILE_BIG;   // split-K partial GEMMs: vision O / down, prefix O / down
+  int zvo = -1, zlo = 4, zld = -1, zvd = 4;   // -1: chosen from the number of image tokens (measured optima at 1 / 2 / 3 views)
   // warm-up blocks carried by the expert's launches (0 = none): QKV, attention, O, down
   int pfq = 64, pfa = 64, pfo = 128, pfd = 128;
   int qms = 1;            // expert QKV: token blocks on separate blocks (160 instead of 80)
@@ -457,6 +457,9 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
                     at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv, T.vis, at<float>(c, w.vstat), at<float>(c, w.g_v1[0]),
                     at<float>(c, w.pos), d.T);
   const int vchunks = I / 32;
+  const int zvo = T.zvo > 0 ? T.zvo : (I <= 256 ? 3 : I <= 512 ? 2 : 1);
+  const int tvd = T.vd >= 0 ? T.vd : (I <= 256 ? TILE_MID : TILE_BIG);
+  const int zld = T.zld > 0 ? T.zld : (I <= 256 ? 16 : 8);
   // one view: the QKV GEMM has too few 64 x 128 tiles for 256 CUs, 64 x 64 tiles spread it further
   const int tqkv = T.vqkv >= 0 ? T.vqkv : (I <= 256 ? TILE_SMALL : T.vis), tup = T.vup >= 0 ? T.vup : T.vis;
   for (int l = 0; l < d.Lv; l++) {
@@ -492,7 +495,7 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
     }
     // A3: O-projection + bias + residual
     r.cls = PI0_OP_VIS_O;
-    gemm_splitk_resid(r, L.o, at<bf16>(c, w.vattn), d.Dv, I, d.Dv, T.zvo, round_up(ceil_div(L.o.k_pad, T.zvo), 64),
+    gemm_splitk_resid(r, L.o, at<bf16>(c, w.vattn), d.Dv, I, d.Dv, zvo, round_up(ceil_div(L.o.k_pad, zvo), 64),
                       at<float>(c, L.o.bias), at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv, T.vo, at<float>(c, w.vstat),
                       at<float>(c, w.g_v2[l]));
     {  // A4: LN -> up (+bias, GELU)
@@ -508,7 +511,7 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
     // A5: down (+bias, residual)
     r.cls = PI0_OP_VIS_DOWN;
     gemm_splitk_resid(r, L.down, at<bf16>(c, w.vmid), d.Fv_kp, I, d.Fv, T.zvd, round_up(ceil_div(L.down.k_pad, T.zvd), 64),
-                      at<float>(c, L.down.bias), at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv, T.vd, at<float>(c, w.vstat),
+                      at<float>(c, L.down.bias), at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv, tvd, at<float>(c, w.vstat),
                       at<float>(c, l + 1 < d.Lv ? w.g_v1[l + 1] : w.g_vf));
     if (taps) taps->put(r, at<float>(c, w.vh), (size_t)I * d.Dv);
   }
@@ -577,8 +580,8 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
     }
     // B5: down + residual
     r.cls = PI0_OP_LLM_DOWN;
-    gemm_splitk_resid(r, L.down, at<bf16>(c, w.lmid), d.F, P, d.F, T.zld,
-                      round_up(ceil_div(L.down.k_pad, T.zld), 64), nullptr, at<float>(c, w.lx), at<bf16>(c, w.lx_b),
+    gemm_splitk_resid(r, L.down, at<bf16>(c, w.lmid), d.F, P, d.F, zld,
+                      round_up(ceil_div(L.down.k_pad, zld), 64), nullptr, at<float>(c, w.lx), at<bf16>(c, w.lx_b),
                       d.E, T.ld, at<float>(c, w.lstat), at<float>(c, w.g_l1[l + 1]));
     if (taps) taps->put(r, at<float>(c, w.lx), (size_t)P * d.E);
   }
