@@ -23,8 +23,8 @@ if ROOT not in sys.path:
 # HBM-side bytes per launch of an operation class, where a counter run exists (2 x FETCH_SIZE + WRITE_SIZE,
 # calibrated against a copy kernel)
 PMC_TRAFFIC_BYTES = {   # profiles/counters_full_pi0_1view_eager_pass.txt (includes what the launch reads ahead)
-    "exp_down": 18929664, "exp_gateup": 18613248, "exp_o": 15499264, "exp_qkv": 11216077, "exp_attn": 20117299,
-    "llm_gateup": 151370342,
+    "exp_down": 19167232, "exp_gateup": 18717696, "exp_o": 15729664, "exp_qkv": 11335680, "exp_attn": 20119552,
+    "exp_out": 259789, "llm_gateup": 151338394,
 }
 
 
