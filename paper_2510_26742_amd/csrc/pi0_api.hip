@@ -302,7 +302,7 @@ enum { KIND_PREFILL = 0, KIND_DENOISE = 1, KIND_INFER = 2 };
 struct Tune {
   int vis = TILE_MID;     // vision patch / projector (and QKV / up unless overridden below)
   int vqkv = -1, vup = -1; // vision QKV / up tile (-1: same as vis)
-  int lqkv = TILE_MID;    // prefix QKV
+  int lqkv = -1;          // prefix QKV (-1: 64 x 64 tiles up to 256 tokens, 64 x 128 beyond)
   int lgu = TILE_BIG;     // prefix gate||up
   int vo = TILE_MID, vd = -1, lo = TILE_MID, ld = TILE_BIG;   // split-K partial GEMMs: vision O / down, prefix O / down
   int zvo = -1, zlo = 4, zld = -1, zvd = 4;   // -1: chosen from the number of image tokens (measured optima at 1 / 2 / 3 views)
@@ -535,13 +535,14 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
   RUN(r, launch_row_stats(r.s, at<float>(c, w.lx), d.E, P, d.E, d.E, at<float>(c, w.g_l1[0]), at<bf16>(c, w.lx_b),
                           at<float>(c, w.lstat)));
   const int pchunks = ceil_div(P, 32);
+  const int tlqkv = T.lqkv >= 0 ? T.lqkv : (P <= 256 ? TILE_SMALL : TILE_MID);
   for (int l = 0; l < d.Ll; l++) {
     const WsTr& L = w.llm[l];
     const bool last = l == d.Ll - 1;
     bf16* kc = reinterpret_cast<bf16*>(c->ws + w.kcache + (size_t)r.slot_w * w.kcache_slot + (size_t)l * w.kcache_layer);
     bf16* vc = reinterpret_cast<bf16*>(c->ws + w.vcache + (size_t)r.slot_w * w.vcache_slot + (size_t)l * w.vcache_layer);
     {  // B1: RMS -> QKV, RoPE, keys/values into the cache (last layer: keys/values only)
-      GemmParams p = gp_base(c, L.qkv, at<bf16>(c, w.lx_b), d.E, P, T.lqkv, d.E);
+      GemmParams p = gp_base(c, L.qkv, at<bf16>(c, w.lx_b), d.E, P, tlqkv, d.E);
       p.rowstat = at<float>(c, w.lstat);
       p.out_bf16 = at<bf16>(c, w.lq);
       p.q_mbs = pchunks;
@@ -551,7 +552,7 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
       p.q_cols = last ? 0 : d.H * 256; p.k_cols = 256;
       p.head_dim = 256; p.dqk_pad = 256; p.nvb = 8; p.kv_heads = 1; p.kv_chunks = d.maxPc;
       r.cls = PI0_OP_LLM_QKV;
-      RUN_GEMM(r, T.lqkv, PRO_RMS, EPI_QKV, p, 1);
+      RUN_GEMM(r, tlqkv, PRO_RMS, EPI_QKV, p, 1);
     }
     if (last) break;
     {  // B2: attention, whole prefix visible
