@@ -313,3 +313,23 @@ def test_two_stream_frames_match_sequential(reduced):
         sd.synchronize()
         for k, (o, r) in enumerate(zip(outs, ref)):
             np.testing.assert_array_equal(o.cpu().numpy(), r, err_msg=f"frame {k + 1}")
+
+
+@pytest.mark.parametrize("tune", [
+    "ae16=0,qms=0,ksplit=0,pfq=0,pfa=0,pfo=0,pfd=0",                                   # 32x32 expert tiles, no warm-up, no key shares
+    "vis=0,vqkv=0,vup=0,lqkv=0,lgu=1,vo=0,vd=0,lo=0,ld=1,zvo=6,zvd=17,zlo=8,zld=4",    # the other tile of every prefill GEMM
+    "vis=5,vqkv=5,vup=5,lqkv=5,vo=5,vd=5,lo=5,zvo=1,zvd=2,zlo=1,kcps=4",               # 64x64 tiles, few splits, small key shares
+])
+def test_alternative_kernel_choices(tune):
+    """Every tile / split / warm-up choice the tuning variable can select computes the same function."""
+    import os
+    os.environ["PI0_TUNE"] = tune
+    try:
+        case = Case(synth.reduced_config(vocab=1024))
+    finally:
+        del os.environ["PI0_TUNE"]
+    try:
+        check_against_oracle(case, 3, 48, label=f"tune {tune}")
+        check_against_oracle(case, 1, 0, label=f"tune {tune} (1 view)")
+    finally:
+        case.close()
