@@ -10,7 +10,6 @@
 // after accumulation as in Section 4.4, RoPE of Section 3.2, gated MLP of Section 4.2) is lane-local.
 #include "pi0_internal.h"
 
-#define LDS_PAD 8
 
 __device__ __forceinline__ float gelu_tanh_f(float x) {
   // 0.5 x (1 + tanh u) = x * sigmoid(2u) = x / (1 + exp(-2u)); hardware exp2 and reciprocal
