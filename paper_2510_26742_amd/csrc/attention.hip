@@ -30,6 +30,8 @@
 template <int DQK, int NVB, int MAXR, int VRING>
 __global__ __launch_bounds__(512) void attention_kernel(AttnParams p) {
   constexpr int S16 = DQK / 16;
+  constexpr bool DUAL = MAXR == 1;             // second accumulators (register room permitting)
+  constexpr int QB = (MAXR == 1 && S16 % 8 == 0) ? 8 : 1;   // Q fragments read from LDS per batch (register room permitting)
   constexpr int NPQ = 32 * DQK / 8;            // 16-byte pieces of the Q tile
   constexpr int QP = (NPQ + 511) / 512;        // pieces per thread
   constexpr int NPK1 = 2 * S16 * 64;           // 16-byte pieces of the two segment-1 key chunks
@@ -125,15 +127,28 @@ __global__ __launch_bounds__(512) void attention_kernel(AttnParams p) {
     if (ci < n0) {
       const bool more = ci + ATT_WAVES < n0;
       const bf16* kn = kbase0 + (size_t)min(ci + ATT_WAVES, n0 - 1) * S16 * 512;
-      f32x16 sacc;
+      f32x16 sacc, sacc1;      // two accumulators where registers allow: a dependent MFMA waits ~64 clocks
 #pragma unroll
-      for (int e = 0; e < 16; e++) sacc[e] = 0.f;
+      for (int e = 0; e < 16; e++) sacc[e] = 0.f, sacc1[e] = 0.f;
+      // the Q fragments come from LDS in batches of QB reads issued together: a read that is only
+      // issued when its MFMA is next costs a full LDS round trip per step
 #pragma unroll
-      for (int s = 0; s < S16; s++) {
-        const bf16x8 a = kf[s];
-        if (r + 1 < MAXR && more) kf[s] = *reinterpret_cast<const bf16x8*>(kn + (size_t)s * 512);
-        const bf16x8 b = *reinterpret_cast<const bf16x8*>(qs + ((size_t)s * 64 + lane) * 8);
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, sacc, 0, 0, 0);
+      for (int s0 = 0; s0 < S16; s0 += QB) {
+        bf16x8 qb[QB];
+#pragma unroll
+        for (int j = 0; j < QB; j++) qb[j] = *reinterpret_cast<const bf16x8*>(qs + ((size_t)(s0 + j) * 64 + lane) * 8);
+#pragma unroll
+        for (int j = 0; j < QB; j++) {
+          const int s = s0 + j;
+          const bf16x8 a = kf[s];
+          if (r + 1 < MAXR && more) kf[s] = *reinterpret_cast<const bf16x8*>(kn + (size_t)s * 512);
+          if (DUAL && (s & 1)) sacc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qb[j], sacc1, 0, 0, 0);
+          else sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qb[j], sacc, 0, 0, 0);
+        }
+      }
+      if (DUAL) {
+#pragma unroll
+        for (int e = 0; e < 16; e++) sacc[e] += sacc1[e];
       }
 #pragma unroll
       for (int e = 0; e < 16; e++) {
@@ -148,14 +163,30 @@ __global__ __launch_bounds__(512) void attention_kernel(AttnParams p) {
   }
   const bool seg1_wave = w < n1;             // waves 0 and 1 score the second segment from LDS
   if (seg1_wave) {
-    f32x16 sacc;
+    f32x16 sacc, sacc1;
 #pragma unroll
-    for (int e = 0; e < 16; e++) sacc[e] = 0.f;
+    for (int e = 0; e < 16; e++) sacc[e] = 0.f, sacc1[e] = 0.f;
 #pragma unroll
-    for (int s = 0; s < S16; s++) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(k1s + (((size_t)w * S16 + s) * 64 + lane) * 8);
-      const bf16x8 b = *reinterpret_cast<const bf16x8*>(qs + ((size_t)s * 64 + lane) * 8);
-      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, sacc, 0, 0, 0);
+    for (int s0 = 0; s0 < S16; s0 += 4) {
+      bf16x8 ka[4], qb[4];
+#pragma unroll
+      for (int j = 0; j < 4; j++) {
+        if (s0 + j < S16) {
+          ka[j] = *reinterpret_cast<const bf16x8*>(k1s + (((size_t)w * S16 + s0 + j) * 64 + lane) * 8);
+          qb[j] = *reinterpret_cast<const bf16x8*>(qs + ((size_t)(s0 + j) * 64 + lane) * 8);
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < 4; j++) {
+        if (s0 + j < S16) {
+          if (DUAL && (j & 1)) sacc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[j], qb[j], sacc1, 0, 0, 0);
+          else sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[j], qb[j], sacc, 0, 0, 0);
+        }
+      }
+    }
+    if (DUAL) {
+#pragma unroll
+      for (int e = 0; e < 16; e++) sacc[e] += sacc1[e];
     }
 #pragma unroll
     for (int e = 0; e < 16; e++) {
@@ -199,25 +230,39 @@ __global__ __launch_bounds__(512) void attention_kernel(AttnParams p) {
   if (!pv_wave) return;
 
   // ---- phase 2: this wave's 32-wide slice of the head dimension over all chunks --------------
-  f32x16 o;
+  f32x16 o, o1;
 #pragma unroll
-  for (int e = 0; e < 16; e++) o[e] = 0.f;
+  for (int e = 0; e < 16; e++) o[e] = 0.f, o1[e] = 0.f;
+  // One ring of VRING chunks per round: the probability fragments of the whole round are read
+  // from LDS up front (clamped, unconditional), chunks beyond the end multiply zeros; the value
+  // fragments of the next round are requested (whole round, one uniform branch) as the registers
+  // of this round are consumed.
+  const bf16x8 zero8v = {(bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f};
   for (int c0 = 0; c0 < ntot; c0 += VRING) {
+    bf16x8 bp[2 * VRING];
 #pragma unroll
     for (int cc = 0; cc < VRING; cc++) {
-      const int c = c0 + cc;
-      if (c < ntot) {
-        const bool more = c + VRING < ntot;
-        const bf16* vn = vptr(min(c + VRING, ntot - 1));
+      const int c = min(c0 + cc, ntot - 1);
 #pragma unroll
-        for (int s2 = 0; s2 < 2; s2++) {
-          const bf16x8 a = vf[2 * cc + s2];
-          if (more) vf[2 * cc + s2] = *reinterpret_cast<const bf16x8*>(vn + (size_t)s2 * 512);
-          const bf16x8 b = *reinterpret_cast<const bf16x8*>(pf + ((size_t)(c * 2 + s2) * 64 + lane) * 8);
-          o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, o, 0, 0, 0);
-        }
+      for (int s2 = 0; s2 < 2; s2++)
+        bp[2 * cc + s2] = *reinterpret_cast<const bf16x8*>(pf + ((size_t)(c * 2 + s2) * 64 + lane) * 8);
+    }
+    const bool more_round = c0 + VRING < ntot;
+#pragma unroll
+    for (int cc = 0; cc < VRING; cc++) {
+      const bool live = c0 + cc < ntot;
+#pragma unroll
+      for (int s2 = 0; s2 < 2; s2++) {
+        const bf16x8 a = vf[2 * cc + s2];
+        if (more_round) vf[2 * cc + s2] = *reinterpret_cast<const bf16x8*>(vptr(min(c0 + cc + VRING, ntot - 1)) + (size_t)s2 * 512);
+        if (DUAL && s2) o1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, live ? bp[2 * cc + s2] : zero8v, o1, 0, 0, 0);
+        else o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, live ? bp[2 * cc + s2] : zero8v, o, 0, 0, 0);
       }
     }
+  }
+  if (DUAL) {
+#pragma unroll
+    for (int e = 0; e < 16; e++) o[e] += o1[e];
   }
   float l_all = 0.f;
 #pragma unroll
