@@ -22,9 +22,11 @@ if ROOT not in sys.path:
 
 # HBM-side bytes per launch of an operation class, where a counter run exists (2 x FETCH_SIZE + WRITE_SIZE,
 # calibrated against a copy kernel)
-PMC_TRAFFIC_BYTES = {   # profiles/counters_full_pi0_1view_eager_pass.txt (includes what the launch reads ahead)
+PMC_TRAFFIC_BYTES = {   # profiles/counters_full_pi0_1view_eager_pass.txt (expert launches: includes what they read ahead)
     "exp_down": 19167232, "exp_gateup": 18717696, "exp_o": 15729664, "exp_qkv": 11335680, "exp_attn": 20119552,
-    "exp_out": 259789, "llm_gateup": 151338394,
+    "exp_out": 259789,
+    "llm_gateup": 151338393, "llm_down": 167949721, "vis_down": 29837414, "llm_o": 29837414, "vis_up": 17199923,
+    "vis_qkv": 14818304, "llm_qkv": 21565849, "vis_o": 11017216, "vis_proj": 12856320, "vis_patch": 5409792,
 }
 
 
