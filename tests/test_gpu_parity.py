@@ -313,6 +313,17 @@ def test_two_stream_frames_match_sequential(reduced):
         sd.synchronize()
         for k, (o, r) in enumerate(zip(outs, ref)):
             np.testing.assert_array_equal(o.cpu().numpy(), r, err_msg=f"frame {k + 1}")
+    # the plain entry points keep working on whichever cache copy is current after streaming
+    k = 2
+    d_img, _, _, _ = dev_frames[k - 1]
+    _, d_st, d_nz, _ = dev_frames[k]
+    out = torch.empty((cfg.chunk, cfg.action_dim), dtype=torch.float32, device=dev)
+    m.pi0_infer(d_img, views[k - 1], None, 0, d_st, d_nz, out, reduced.stream)
+    reduced.stream.synchronize()
+    np.testing.assert_array_equal(out.cpu().numpy(), ref[k - 1])
+    m.pi0_denoise(d_st, d_nz, out, reduced.stream)
+    reduced.stream.synchronize()
+    np.testing.assert_array_equal(out.cpu().numpy(), ref[k - 1])
 
 
 @pytest.mark.parametrize("tune", [
