@@ -5,8 +5,9 @@
  * camera views, a Gemma-style prefix transformer that fills a per-layer key/value cache, and an
  * action expert that integrates a flow with `steps` Euler steps against that cache and returns a
  * chunk of `chunk` actions.  The sequence of GEMMs and fused scalar ops is the one listed in the
- * paper's Table 2; the algebraic rewrites of Section 3.2 (norm gains folded into the next
- * linear, action/time encoder folded, fused QKV with RoPE in the epilogue), Section 4.1 (last
+ * paper's Table 2; the algebraic rewrites of Section 3.2 (norm gains folded out of the norm - here
+ * into the bf16 cast of the activations that the next linear reads -, action/time encoder
+ * folded, fused QKV with RoPE in the epilogue), Section 4.1 (last
  * prefix layer only produces keys/values), Section 4.2 (fused gated MLP) and Section 4.4 (norm
  * statistics applied after accumulation) are done inside the library at load time / in kernels.
  * Section 3.1's graph replay: pi0_prefill / pi0_denoise / pi0_infer record their kernel
@@ -20,7 +21,8 @@
  *    stream); results are valid after the caller synchronises that stream.
  *  - Return value: 0 on success, a negative PI0_E* code otherwise.  Argument checks happen before
  *    any GPU call, so error paths touch no GPU state.  Nothing throws or aborts across the ABI.
- *  - Calls on one ctx must not overlap in time (one workspace, one set of activations).
+ *  - Calls on one ctx must not overlap in time (one workspace, one set of activations); the only
+ *    concurrency is the one pi0_stream_frame arranges itself between its two streams.
  */
 #ifndef PI0_H
 #define PI0_H

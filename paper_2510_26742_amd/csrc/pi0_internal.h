@@ -97,7 +97,7 @@ enum Epilogue {
   EPI_PARTIAL = 0,   // fp32 partial sums [z][M][n_pad] for a later split-K reduction
   EPI_RESID = 1,     // out_f32 = acc (+bias) (+resid[row % resid_mod]); bf16 shadow
   EPI_BF16 = 2,      // out_bf16 = act(norm(acc) + bias)
-  EPI_QKV = 3,       // q natural, K / V in attention fragment order; optional RoPE / bias
+  EPI_QKV = 3,       // q, K, V in the attention kernel's fragment orders (K / V straight into the cache); optional RoPE / bias
   EPI_GEGLU = 4,     // out_bf16[m][n/2] = gelu(gate) * up
   EPI_EULER = 5      // x[m-1][n] += dt * (norm(acc) + bias), rows m >= 1
 };
@@ -158,8 +158,8 @@ struct GemmParams {
 
 // Tile configuration ids (template instantiations that exist)
 enum GemmTile {
-  TILE_BIG = 0,     // 256 tokens x 128 features per block (4 waves), 4 stages in flight
-  TILE_MID = 1,     // 64 tokens x 128 features per block (4 waves), 8 stages in flight
+  TILE_BIG = 0,     // 256 tokens x 128 features per block (4 waves), 3 register stages in flight
+  TILE_MID = 1,     // 64 tokens x 128 features per block (4 waves), 6 register stages in flight
   TILE_SKINNY = 2,  // <= 64 tokens, one 32-feature tile per block, 8 waves split k <= 1024, loads issued at once
   TILE_SKINNY_FULLK = 3,  // <= 64 tokens, k = 2048 or 4096 in one block per (feature tile, 32-token block), residual epilogue
   TILE_SKINNY16 = 4,      // same on 16-feature x 16-token tiles (mfma 16x16x32): 256 blocks for the expert's O / down
