@@ -238,6 +238,24 @@ enum pi0_sync_mode {
 int pi0_sync_bench(int mode, int n_ops, int reps, float* d_x, const float* d_b, unsigned* d_state,
                    double* h_ms, void* hip_stream);
 
+/*
+ * Attainable-peak micro-benchmarks (no ctx needed): what this device sustains on the two resources
+ * the roofline of Section 5.1 prices operations by.
+ *   PI0_PEAK_HBM_READ   streams `bytes` bytes at d_buf (device, 16-byte aligned, bytes a multiple of
+ *                       16; give far more than the 256 MB last-level cache) through all compute units
+ *                       with 16-byte loads; *h_result = GB/s (1e9 bytes per second).  iters unused.
+ *   PI0_PEAK_MFMA_BF16  runs `iters` (1 .. 2^22) rounds of 4 independent 32x32x16 bf16 MFMAs per wave,
+ *                       2 waves per SIMD on 256 compute units' worth of blocks, operands and
+ *                       accumulators in registers, non-zero operands; *h_result = TFLOP/s.
+ *                       d_buf / bytes unused.
+ * One untimed launch, then `reps` (1 .. 1000) launches timed with HIP events on hip_stream; the call
+ * synchronises the stream.  d_sink: device, one uint32 the kernels may write (never read back).
+ * h_result: HOST.  Nothing is allocated on the device.  Errors: EINVAL, EHIP.
+ */
+enum pi0_peak_kind { PI0_PEAK_HBM_READ = 0, PI0_PEAK_MFMA_BF16 = 1 };
+int pi0_peak_bench(int kind, const void* d_buf, size_t bytes, int iters, int reps, unsigned* d_sink,
+                   double* h_result, void* hip_stream);
+
 /* Graph replay on (1, default) or off (0: every call launches kernels eagerly). */
 int pi0_set_graph_mode(pi0_ctx* ctx, int enabled);
 

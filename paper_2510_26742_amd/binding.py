@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpi0_hip.so")
 
 EXPORTS = ["pi0_create", "pi0_destroy", "pi0_weights_bytes", "pi0_workspace_bytes", "pi0_load_weights",
-           "pi0_prefill", "pi0_denoise", "pi0_infer", "pi0_debug_taps_elems", "pi0_debug_forward", "pi0_debug_profile", "pi0_sync_bench", "pi0_stream_frame",
+           "pi0_prefill", "pi0_denoise", "pi0_infer", "pi0_debug_taps_elems", "pi0_debug_forward", "pi0_debug_profile", "pi0_sync_bench", "pi0_peak_bench", "pi0_stream_frame",
            "pi0_set_graph_mode", "pi0_kernel_count", "pi0_strerror", "pi0_last_hip_error"]
 
 # enum pi0_op_class, in order
@@ -77,6 +77,8 @@ def lib() -> ctypes.CDLL:
         L.pi0_stream_frame.restype = i32
         L.pi0_sync_bench.argtypes = [i32, i32, i32, vp, vp, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.pi0_sync_bench.restype = i32
+        L.pi0_peak_bench.argtypes = [i32, vp, sz, i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
+        L.pi0_peak_bench.restype = i32
         L.pi0_set_graph_mode.argtypes = [vp, i32]
         L.pi0_set_graph_mode.restype = i32
         L.pi0_kernel_count.argtypes = [vp, i32, i32]
@@ -128,6 +130,20 @@ def pi0_sync_bench(mode: str, n_ops: int, reps: int, d_x, d_b, d_state, stream=N
     if rc != PI0_OK:
         raise Pi0Error(rc)
     return float(ms.value)
+
+
+PEAK_KINDS = {"hbm_read": 0, "mfma_bf16": 1}
+
+
+def pi0_peak_bench(kind: str, d_buf, nbytes: int, iters: int, reps: int, d_sink, stream=None) -> float:
+    """GB/s of a streaming read of nbytes at d_buf ("hbm_read") or TFLOP/s of a register-resident bf16 MFMA loop."""
+    out = ctypes.c_double(0.0)
+    s = None if stream is None else int(stream.cuda_stream)
+    rc = lib().pi0_peak_bench(PEAK_KINDS[kind], _ptr(d_buf), int(nbytes), int(iters), int(reps), _ptr(d_sink),
+                              ctypes.byref(out), s)
+    if rc != PI0_OK:
+        raise Pi0Error(rc)
+    return float(out.value)
 
 
 class Pi0:

@@ -281,6 +281,30 @@ def test_sync_overhead_microbenchmark():
     assert times["fused"] < times["barrier"]
 
 
+def test_attainable_peak_microbenchmarks():
+    """The two device micro-benchmarks behind the roofline fractions (Section 5.1): a streaming read and a
+    register-resident bf16 MFMA loop finish, leave their input alone and land between a floor that any
+    working MI355X exceeds and the published peak."""
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.Stream(device=dev)
+    g = torch.Generator().manual_seed(11)
+    n = (512 << 20) // 4 + 12                                  # 512 MiB and a ragged tail of 3 sixteen-byte words
+    host = torch.randint(-2 ** 31, 2 ** 31 - 1, (n,), dtype=torch.int32, generator=g)
+    buf = host.to(dev)
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    torch.cuda.synchronize()
+    say("[gpu] pi0_peak_bench hbm_read")
+    gbps = binding.pi0_peak_bench("hbm_read", buf, n * 4, 0, 10, sink, stream)
+    say("[gpu] pi0_peak_bench mfma_bf16")
+    tflops = binding.pi0_peak_bench("mfma_bf16", None, 0, 2048, 10, sink, stream)
+    say(f"[peak] HBM read {gbps:.0f} GB/s, bf16 MFMA {tflops:.0f} TFLOP/s")
+    assert 1500.0 < gbps < 8000.0
+    assert 500.0 < tflops < 2600.0
+    assert torch.equal(buf.cpu(), host)
+    with pytest.raises(binding.Pi0Error):
+        binding.pi0_peak_bench("hbm_read", buf, n * 4 + 4, 0, 1, sink, stream)
+
+
 def test_two_stream_frames_match_sequential(reduced):
     """Section 6's concurrent mode: frame k's prefill runs beside the denoise against frame k-1's cache
     (double-buffered).  Same kernels, so every chunk must equal, bit for bit, what pi0_prefill +

@@ -127,6 +127,23 @@ def test_sync_bench_rejects_bad_arguments(L):
     assert len(binding.OP_CLASSES) == 21 and binding.SYNC_MODES["fused"] == 4
 
 
+def test_peak_bench_rejects_bad_arguments(L):
+    fake = 0x10000
+    out = ctypes.c_double(0.0)
+    r = ctypes.byref(out)
+    assert L.pi0_peak_bench(2, fake, 1 << 20, 16, 1, fake, r, None) == binding.PI0_EINVAL          # unknown kind
+    assert L.pi0_peak_bench(0, None, 1 << 20, 0, 1, fake, r, None) == binding.PI0_EINVAL            # no buffer
+    assert L.pi0_peak_bench(0, fake, 0, 0, 1, fake, r, None) == binding.PI0_EINVAL                  # nothing to read
+    assert L.pi0_peak_bench(0, fake, (1 << 20) + 8, 0, 1, fake, r, None) == binding.PI0_EINVAL      # not whole 16-byte words
+    assert L.pi0_peak_bench(0, fake + 8, 1 << 20, 0, 1, fake, r, None) == binding.PI0_EINVAL        # misaligned
+    assert L.pi0_peak_bench(1, None, 0, 0, 1, fake, r, None) == binding.PI0_EINVAL                  # no rounds
+    assert L.pi0_peak_bench(1, None, 0, (1 << 22) + 1, 1, fake, r, None) == binding.PI0_EINVAL      # too many rounds
+    assert L.pi0_peak_bench(1, None, 0, 16, 0, fake, r, None) == binding.PI0_EINVAL                 # no repetitions
+    assert L.pi0_peak_bench(1, None, 0, 16, 1, None, r, None) == binding.PI0_EINVAL                 # no sink
+    assert L.pi0_peak_bench(1, None, 0, 16, 1, fake, None, None) == binding.PI0_EINVAL              # no result
+    assert binding.PEAK_KINDS == {"hbm_read": 0, "mfma_bf16": 1}
+
+
 def test_kernel_count_and_taps(L):
     cfg = synth.full_config()
     c = binding.to_c_config(cfg)
