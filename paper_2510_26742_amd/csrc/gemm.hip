@@ -245,7 +245,10 @@ __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16&
 // in flight in registers and every stage is issued the same distance ahead of its use:
 // vector-memory loads complete in issue order, so a weight prefetch issued far ahead does not
 // help if the activation load behind which it queues is only one chunk ahead.
-template <int MB, int WN, int D, int PRO, int EPI>
+// NT > 1: every wave owns NT adjacent feature tiles, so that an activation fragment read from LDS
+// feeds NT MFMAs (with NT = 1 and 32-feature wave tiles the LDS read rate, one 1 KiB fragment per
+// MFMA per wave, is exactly the LDS peak, and the matrix pipe cannot be kept busy).
+template <int MB, int WN, int D, int PRO, int EPI, int NT = 1>
 __global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_kernel(GemmParams p) {
   constexpr int ROWS = MB * 32;
   constexpr int NFR = MB * 4;             // fragments per chunk
@@ -261,14 +264,14 @@ __global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(1, 1)))
 
   // XCD-aware tile order: consecutive block ids go to different XCDs (separate L2s), so the
   // m-tiles that share one weight panel are given ids with equal (id % 8).
-  const int nblocks_n = (p.n_tiles + WN - 1) / WN;
+  const int nblocks_n = (p.n_tiles + WN * NT - 1) / (WN * NT);
   const int id = blockIdx.x;
   const int slot = id >> 3;
   const int nb = (id & 7) + 8 * (slot / p.m_tiles);
   const int mt = slot % p.m_tiles;
   if (nb >= nblocks_n) return;
   const int m0 = mt * ROWS;
-  const int nt = nb * WN + wn;
+  const int nt = (nb * WN + wn) * NT;          // first of the wave's NT feature tiles (n_tiles is a multiple of NT)
   const bool wave_active = nt < p.n_tiles;
 
   const int k_pad = p.W.k_pad;
@@ -285,7 +288,7 @@ __global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(1, 1)))
   // Token blocks beyond M re-read the last block (their outputs are never stored), chunks beyond
   // the last re-read the last chunk (never computed).
   bf16x8 xr[D][NP];
-  bf16x8 wr[D][4];
+  bf16x8 wr[D][NT][4];
   const bf16* xfrag[NP];
 #pragma unroll
   for (int i = 0; i < NP; i++) {
@@ -294,14 +297,16 @@ __global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(1, 1)))
     xfrag[i] = p.X + ((size_t)mbg * XKC16 + (kbeg >> 4) + (f & 3)) * 512 + lane * 8;
   }
   const bf16* wbase = p.W.w + ((size_t)(wave_active ? nt : 0) * KC16 + (kbeg >> 4)) * 512 + lane * 8;
+  const size_t wtile = (size_t)KC16 * 512;     // elements between adjacent feature tiles
 
 #define ISSUE_STAGE(c, u)                                                                             \
   {                                                                                                   \
     const int cc_ = min((c), NC - 1);                                                                 \
     _Pragma("unroll") for (int i = 0; i < NP; i++)                                                    \
       xr[u][i] = *reinterpret_cast<const bf16x8*>(xfrag[i] + (size_t)cc_ * 2048);                     \
-    _Pragma("unroll") for (int s_ = 0; s_ < 4; s_++)                                                  \
-      wr[u][s_] = *reinterpret_cast<const bf16x8*>(wbase + (size_t)(cc_ * 4 + s_) * 512);             \
+    _Pragma("unroll") for (int j_ = 0; j_ < NT; j_++)                                                 \
+      _Pragma("unroll") for (int s_ = 0; s_ < 4; s_++)                                                \
+        wr[u][j_][s_] = *reinterpret_cast<const bf16x8*>(wbase + j_ * wtile + (size_t)(cc_ * 4 + s_) * 512); \
   }
 #define STORE_STAGE(u, buf)                                                                           \
   {                                                                                                   \
@@ -309,11 +314,13 @@ __global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(1, 1)))
       *reinterpret_cast<bf16x8*>(xs + (((size_t)(buf) * NFR + wn + WN * i) * 64 + lane) * 8) = xr[u][i]; \
   }
 
-  f32x16 acc[MB];
+  f32x16 acc[NT][MB];
 #pragma unroll
-  for (int mb = 0; mb < MB; mb++)
+  for (int j = 0; j < NT; j++)
 #pragma unroll
-    for (int r = 0; r < 16; r++) acc[mb][r] = 0.f;
+    for (int mb = 0; mb < MB; mb++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) acc[j][mb][r] = 0.f;
 
 #pragma unroll
   for (int u = 0; u < D; u++) ISSUE_STAGE(u, u)
@@ -341,7 +348,8 @@ __global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(1, 1)))
           bq_[(s + 1) & 1][mb] = *reinterpret_cast<const bf16x8*>(xb_ + (size_t)(mb * 4 + s + 1) * 512); \
       }                                                                                               \
       _Pragma("unroll") for (int mb = 0; mb < MB; mb++)                                               \
-        acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[u][s], bq_[s & 1][mb], acc[mb], 0, 0, 0); \
+        _Pragma("unroll") for (int j_ = 0; j_ < NT; j_++)                                             \
+          acc[j_][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[u][j_][s], bq_[s & 1][mb], acc[j_][mb], 0, 0, 0); \
     }                                                                                                 \
   }
   int c0 = 0;
@@ -354,27 +362,46 @@ __global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(1, 1)))
       STORE_STAGE((u + 1) % D, cur ^ 1)
       // ---- requested instruction order (masks: 0x008 MFMA, 0x100 LDS read, 0x200 LDS write, 0x020 VMEM read)
       __builtin_amdgcn_sched_group_barrier(0x100, MB, 0);
+      if (NT == 1) {
 #pragma unroll
-      for (int i = 0; i < MB; i++) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-      }
+        for (int i = 0; i < MB; i++) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
 #pragma unroll
-      for (int i = 0; i < MB; i++) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        if (i < NP + 4 - MB) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-      }
+        for (int i = 0; i < MB; i++) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          if (i < NP + 4 - MB) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
 #pragma unroll
-      for (int i = 0; i < MB; i++) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      }
+        for (int i = 0; i < MB; i++) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
 #pragma unroll
-      for (int i = 0; i < MB; i++) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        if (i < NP) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+        for (int i = 0; i < MB; i++) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          if (i < NP) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+        }
+      } else {
+        // NT MFMAs per LDS read; the NP + 4 NT global loads of the new stage behind the first ones
+        // of steps 0..2, the NP LDS writes of the next chunk inside step 3
+#pragma unroll
+        for (int st = 0; st < 3; st++) {
+#pragma unroll
+          for (int i = 0; i < MB; i++) {
+            __builtin_amdgcn_sched_group_barrier(0x008, NT, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            if (st * MB + i < NP + 4 * NT) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < MB; i++) {
+          __builtin_amdgcn_sched_group_barrier(0x008, NT, 0);
+          if (i < NP) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+        }
       }
       __syncthreads();
       cur ^= 1;
@@ -416,9 +443,12 @@ __global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(1, 1)))
         ssum = rst[mb].x;
         ssq = rst[mb].y;
       }
-      EpiOps ops;
-      epilogue_preload<PRO, EPI>(p, nt, m, lh, ops);
-      epilogue_tile<PRO, EPI>(p, acc[mb], nt, m, lh, ssum, ssq, blockIdx.y, ops);
+#pragma unroll
+      for (int j = 0; j < NT; j++) {
+        EpiOps ops;
+        epilogue_preload<PRO, EPI>(p, nt + j, m, lh, ops);
+        epilogue_tile<PRO, EPI>(p, acc[j][mb], nt + j, m, lh, ssum, ssq, blockIdx.y, ops);
+      }
     }
   }
 }
@@ -777,39 +807,46 @@ int gemm_rows_per_tile(int tile) {
     case TILE_SKINNY_FULLK: return 64;
     case TILE_SKINNY16: return 64;
     case TILE_SMALL: return 64;
+    case TILE_WIDE: return 256;
+    case TILE_WIDE128: return 128;
     default: return -1;
   }
 }
 
-template <int MB, int WN, int D, int PRO, int EPI>
+template <int MB, int WN, int D, int PRO, int EPI, int NT>
 static hipError_t launch_one(hipStream_t s, const GemmParams& p, int z) {
-  const int nblocks_n = (p.n_tiles + WN - 1) / WN;
+  if (p.n_tiles % NT != 0) return hipErrorInvalidValue;
+  const int nblocks_n = (p.n_tiles + WN * NT - 1) / (WN * NT);
   dim3 grid(8 * ((nblocks_n + 7) / 8) * p.m_tiles, z, 1);
   dim3 block(64 * WN, 1, 1);
   constexpr int smem = smem_bytes_for<MB>();
-  gemm_kernel<MB, WN, D, PRO, EPI><<<grid, block, smem, s>>>(p);
+  gemm_kernel<MB, WN, D, PRO, EPI, NT><<<grid, block, smem, s>>>(p);
   return hipGetLastError();
 }
 
-template <int MB, int WN, int D, int PRO, int EPI>
+template <int MB, int WN, int D, int PRO, int EPI, int NT>
 static hipError_t set_attr() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<MB, WN, D, PRO, EPI>),
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<MB, WN, D, PRO, EPI, NT>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes_for<MB>());
 }
 
-// The instantiations that exist.  X(tile id, MB, WN, D, PRO, EPI)
+// The instantiations that exist.  X(tile id, MB, WN, D, PRO, EPI, NT)
 #define TALL_EPIS(X, T, MB, WN, D)    \
-  X(T, MB, WN, D, PRO_NONE, EPI_RESID)   \
-  X(T, MB, WN, D, PRO_NONE, EPI_PARTIAL) \
-  X(T, MB, WN, D, PRO_LN, EPI_QKV)       \
-  X(T, MB, WN, D, PRO_LN, EPI_BF16)      \
-  X(T, MB, WN, D, PRO_LN, EPI_RESID)     \
-  X(T, MB, WN, D, PRO_RMS, EPI_QKV)      \
-  X(T, MB, WN, D, PRO_RMS, EPI_GEGLU)
+  X(T, MB, WN, D, PRO_NONE, EPI_RESID, 1)   \
+  X(T, MB, WN, D, PRO_NONE, EPI_PARTIAL, 1) \
+  X(T, MB, WN, D, PRO_LN, EPI_QKV, 1)       \
+  X(T, MB, WN, D, PRO_LN, EPI_BF16, 1)      \
+  X(T, MB, WN, D, PRO_LN, EPI_RESID, 1)     \
+  X(T, MB, WN, D, PRO_RMS, EPI_QKV, 1)      \
+  X(T, MB, WN, D, PRO_RMS, EPI_GEGLU, 1)
 #define GEMM_VARIANTS(X)           \
   TALL_EPIS(X, TILE_BIG, 8, 4, 3)  \
   TALL_EPIS(X, TILE_MID, 2, 4, 6)   \
-  TALL_EPIS(X, TILE_SMALL, 2, 2, 6)
+  TALL_EPIS(X, TILE_SMALL, 2, 2, 6) \
+  X(TILE_WIDE, 8, 4, 2, PRO_RMS, EPI_GEGLU, 2)   \
+  X(TILE_WIDE, 8, 4, 2, PRO_NONE, EPI_PARTIAL, 2) \
+  X(TILE_WIDE128, 4, 4, 3, PRO_RMS, EPI_GEGLU, 2)   \
+  X(TILE_WIDE128, 4, 4, 3, PRO_NONE, EPI_PARTIAL, 2)
 
 #define SKINNY_VARIANTS(X)      \
   X(PRO_NONE, EPI_RESID)        \
@@ -832,9 +869,9 @@ hipError_t gemm_init_attributes() {
                                        hipFuncAttributeMaxDynamicSharedMemorySize, skinny_smem_bytes());
     if (e != hipSuccess) return e;
   }
-#define X(T, MB, WN, D, PRO, EPI)                                     \
+#define X(T, MB, WN, D, PRO, EPI, NT)                                 \
   {                                                                   \
-    hipError_t e = set_attr<MB, WN, D, PRO, EPI>();                   \
+    hipError_t e = set_attr<MB, WN, D, PRO, EPI, NT>();               \
     if (e != hipSuccess) return e;                                    \
   }
   GEMM_VARIANTS(X)
@@ -907,10 +944,10 @@ hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmPara
 #undef X
     return hipErrorInvalidValue;
   }
-#define X(T, MB, WN, D, PRO, EPI)                                              \
+#define X(T, MB, WN, D, PRO, EPI, NT)                                          \
   if (tile == T && pro == PRO && epi == EPI) {                                  \
     if (p.m_tiles * MB * 32 < p.M) return hipErrorInvalidValue;                 \
-    return launch_one<MB, WN, D, PRO, EPI>(s, p, z_splits);                     \
+    return launch_one<MB, WN, D, PRO, EPI, NT>(s, p, z_splits);                 \
   }
   GEMM_VARIANTS(X)
 #undef X

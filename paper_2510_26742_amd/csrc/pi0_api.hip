@@ -303,8 +303,8 @@ struct Tune {
   int vis = TILE_MID;     // vision patch / projector (and QKV / up unless overridden below)
   int vqkv = -1, vup = -1; // vision QKV / up tile (-1: same as vis)
   int lqkv = -1;          // prefix QKV (-1: 64 x 64 tiles up to 256 tokens, 64 x 128 beyond)
-  int lgu = TILE_BIG;     // prefix gate||up
-  int vo = TILE_MID, vd = -1, lo = TILE_MID, ld = TILE_BIG;   // split-K partial GEMMs: vision O / down, prefix O / down
+  int lgu = -1;           // prefix gate||up (-1: 128 x 256 or 256 x 256 tiles, whichever fills the 256 CUs in fewer rounds)
+  int vo = TILE_MID, vd = -1, lo = TILE_MID, ld = TILE_WIDE128;   // split-K partial GEMMs: vision O / down, prefix O / down
   int zvo = -1, zlo = 4, zld = -1, zvd = 4;   // -1: chosen from the number of image tokens (measured optima at 1 / 2 / 3 views)
   // warm-up blocks carried by the expert's launches (0 = none): QKV, attention, O, down
   int pfq = 64, pfa = 64, pfo = 128, pfd = 128;
@@ -459,7 +459,6 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
   const int vchunks = I / 32;
   const int zvo = T.zvo > 0 ? T.zvo : (I <= 256 ? 3 : I <= 512 ? 2 : 1);
   const int tvd = T.vd >= 0 ? T.vd : (I <= 256 ? TILE_MID : TILE_BIG);
-  const int zld = T.zld > 0 ? T.zld : (I <= 256 ? 16 : 8);
   // one view: the QKV GEMM has too few 64 x 128 tiles for 256 CUs, 64 x 64 tiles spread it further
   const int tqkv = T.vqkv >= 0 ? T.vqkv : (I <= 256 ? TILE_SMALL : T.vis), tup = T.vup >= 0 ? T.vup : T.vis;
   for (int l = 0; l < d.Lv; l++) {
@@ -536,6 +535,14 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
                           at<float>(c, w.lstat)));
   const int pchunks = ceil_div(P, 32);
   const int tlqkv = T.lqkv >= 0 ? T.lqkv : (P <= 256 ? TILE_SMALL : TILE_MID);
+  // gate||up: 128 blocks of 256 features per token tile.  A 256-token tile costs two 128-token tiles; take the
+  // tile height whose block count needs fewer rounds on 256 compute units (ties: the taller tile).
+  const int gu_cols = ceil_div(w.llm[0].gu.n_pad, 256);
+  const int rounds128 = ceil_div(ceil_div(P, 128) * gu_cols, 256), rounds256 = 2 * ceil_div(ceil_div(P, 256) * gu_cols, 256);
+  const int tlgu = T.lgu >= 0 ? T.lgu : (rounds256 <= rounds128 ? TILE_WIDE : TILE_WIDE128);
+  // down: as many k slices as keep all blocks in one round (measured optima 16 / 8 / 5 at 256 / 512 / 768 tokens)
+  const int down_tiles = ceil_div(P, gemm_rows_per_tile(T.ld)) * ceil_div(w.llm[0].down.n_pad, T.ld == TILE_WIDE || T.ld == TILE_WIDE128 ? 256 : 128);
+  const int zld = T.zld > 0 ? T.zld : std::max(1, std::min(16, 256 / std::max(1, down_tiles)));
   for (int l = 0; l < d.Ll; l++) {
     const WsTr& L = w.llm[l];
     const bool last = l == d.Ll - 1;
@@ -572,12 +579,12 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
                       round_up(ceil_div(L.o.k_pad, T.zlo), 64), nullptr, at<float>(c, w.lx), at<bf16>(c, w.lx_b), d.E, T.lo,
                       at<float>(c, w.lstat), at<float>(c, w.g_l2[l]));
     {  // B4: RMS -> gate||up with fused GELU gate
-      GemmParams p = gp_base(c, L.gu, at<bf16>(c, w.lx_b), d.E, P, T.lgu, d.E);
+      GemmParams p = gp_base(c, L.gu, at<bf16>(c, w.lx_b), d.E, P, tlgu, d.E);
       p.rowstat = at<float>(c, w.lstat);
       p.out_bf16 = at<bf16>(c, w.lmid);
       p.ldo = d.F;
       r.cls = PI0_OP_LLM_GATEUP;
-      RUN_GEMM(r, T.lgu, PRO_RMS, EPI_GEGLU, p, 1);
+      RUN_GEMM(r, tlgu, PRO_RMS, EPI_GEGLU, p, 1);
     }
     // B5: down + residual
     r.cls = PI0_OP_LLM_DOWN;
@@ -900,9 +907,9 @@ int pi0_create(const pi0_config* cfg, pi0_ctx** out) {
 
   if (const char* env = getenv("PI0_TUNE")) {
     struct { const char* key; int* dst; int lo, hi; } keys[] = {
-        {"vis", &c->tune.vis, 0, 5},   {"lqkv", &c->tune.lqkv, 0, 5}, {"lgu", &c->tune.lgu, 0, 5},
+        {"vis", &c->tune.vis, 0, 5},   {"lqkv", &c->tune.lqkv, 0, 5}, {"lgu", &c->tune.lgu, 0, 7},
         {"vqkv", &c->tune.vqkv, -1, 5}, {"vup", &c->tune.vup, -1, 5},
-        {"vo", &c->tune.vo, 0, 5}, {"vd", &c->tune.vd, 0, 5}, {"lo", &c->tune.lo, 0, 5}, {"ld", &c->tune.ld, 0, 5}, {"zvo", &c->tune.zvo, 1, Z_MAX}, {"zlo", &c->tune.zlo, 1, Z_MAX},
+        {"vo", &c->tune.vo, 0, 5}, {"vd", &c->tune.vd, 0, 5}, {"lo", &c->tune.lo, 0, 5}, {"ld", &c->tune.ld, 0, 7}, {"zvo", &c->tune.zvo, 1, Z_MAX}, {"zlo", &c->tune.zlo, 1, Z_MAX},
         {"zld", &c->tune.zld, 1, Z_MAX}, {"zvd", &c->tune.zvd, 1, Z_MAX},
         {"pfq", &c->tune.pfq, 0, 1024}, {"pfa", &c->tune.pfa, 0, 1024}, {"pfo", &c->tune.pfo, 0, 1024},
         {"pfd", &c->tune.pfd, 0, 1024}, {"ae16", &c->tune.ae16, 0, 1}, {"ksplit", &c->tune.ksplit, 0, 1}, {"kcps", &c->tune.kcps, 2, 16}, {"qms", &c->tune.qms, 0, 1}};

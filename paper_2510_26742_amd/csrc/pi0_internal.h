@@ -163,7 +163,10 @@ enum GemmTile {
   TILE_SKINNY = 2,  // <= 64 tokens, one 32-feature tile per block, 8 waves split k <= 1024, loads issued at once
   TILE_SKINNY_FULLK = 3,  // <= 64 tokens, k = 2048 or 4096 in one block per (feature tile, 32-token block), residual epilogue
   TILE_SKINNY16 = 4,      // same on 16-feature x 16-token tiles (mfma 16x16x32): 256 blocks for the expert's O / down
-  TILE_SMALL = 5          // 64 tokens x 64 features per block (2 waves), 6 stages: small GEMMs of the vision tower
+  TILE_SMALL = 5,         // 64 tokens x 64 features per block (2 waves), 6 stages: small GEMMs of the vision tower
+  // two feature tiles per wave: an activation fragment read from LDS feeds two MFMAs (prefix gate||up / down only)
+  TILE_WIDE = 6,          // 256 tokens x 256 features per block (4 waves x 2 feature tiles), 2 stages
+  TILE_WIDE128 = 7        // 128 tokens x 256 features per block, 3 stages
 };
 
 hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmParams& p, int z_splits);

@@ -351,9 +351,11 @@ def test_two_stream_frames_match_sequential(reduced):
 
 
 @pytest.mark.parametrize("tune", [
-    "ae16=0,qms=0,ksplit=0,pfq=0,pfa=0,pfo=0,pfd=0",                                   # 32x32 expert tiles, no warm-up, no key shares
+    "ae16=0,qms=0,ksplit=0,pfq=0,pfa=0,pfo=0,pfd=0,lgu=0,ld=0",                        # 32x32 expert tiles, no warm-up, no key shares, 256x128 gate||up and down
     "vis=0,vqkv=0,vup=0,lqkv=0,lgu=1,vo=0,vd=0,lo=0,ld=1,zvo=6,zvd=17,zlo=8,zld=4",    # the other tile of every prefill GEMM
     "vis=5,vqkv=5,vup=5,lqkv=5,vo=5,vd=5,lo=5,zvo=1,zvd=2,zlo=1,kcps=4",               # 64x64 tiles, few splits, small key shares
+    "lgu=6,ld=7,zld=4",                                                                # two feature tiles per wave: 256x256 gate||up, 128x256 down
+    "lgu=7,ld=6,zld=8",                                                                # ... and the other way round
 ])
 def test_alternative_kernel_choices(tune):
     """Every tile / split / warm-up choice the tuning variable can select computes the same function."""
