@@ -145,7 +145,8 @@ def main() -> int:
         log("[bench] class %-10s launches %5d avg %8.2f us total %9.1f us  %s" % (
             r["class"], r["launches"], r["avg_us"], r["total_us"],
             ("%s %.1f %s = %.3f of peak" % (r["bound"], r["achieved"], r["unit"], r["frac"])) if "bound" in r else ""))
-    krows = roofline.kernel_rooflines(roofline.class_work(cfg, headline_views, 0), timing, PMC_TRAFFIC_BYTES)
+    krows = roofline.kernel_rooflines(roofline.class_work(cfg, headline_views, 0), timing, PMC_TRAFFIC_BYTES,
+                                      prefix_tokens=headline_views * cfg.tokens_per_view)
     for r in krows:
         log("[bench] kernel %-22s launches %5d avg %8.2f us total %9.1f us  %s %.1f %s = %.3f of peak" % (
             r["kernel"], r["launches"], r["avg_us"], r["total_us"], r["bound"], r["achieved"], r["unit"], r["frac"]))

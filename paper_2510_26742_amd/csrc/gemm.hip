@@ -225,11 +225,11 @@ __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16&
       }
     }
     if (EPI == EPI_RESID && p.stat_out != nullptr) {
-      // partial row statistics over this tile's 32 columns: [n tile][64 rows][2]
+      // partial row statistics over this tile's 32 columns: [n tile][stat_rows (64 if not given)][2]
       st_a += __shfl_xor(st_a, 32, 64);
       st_b += __shfl_xor(st_b, 32, 64);
       if (lh == 0) {
-        float* dst = p.stat_out + ((size_t)nt * 64 + m + p.row_offset) * 2;
+        float* dst = p.stat_out + ((size_t)nt * (p.stat_rows > 0 ? p.stat_rows : 64) + m + p.row_offset) * 2;
         dst[0] = st_a;
         dst[1] = st_b;
       }
@@ -245,6 +245,7 @@ __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16&
 // in flight in registers and every stage is issued the same distance ahead of its use:
 // vector-memory loads complete in issue order, so a weight prefetch issued far ahead does not
 // help if the activation load behind which it queues is only one chunk ahead.
+#define STAT_PARTS_MAX 64   // most partial-statistics planes a tall kernel accepts (2048 columns / 32)
 // NT > 1: every wave owns NT adjacent feature tiles, so that an activation fragment read from LDS
 // feeds NT MFMAs (with NT = 1 and 32-feature wave tiles the LDS read rate, one 1 KiB fragment per
 // MFMA per wave, is exactly the LDS peak, and the matrix pipe cannot be kept busy).
@@ -324,6 +325,34 @@ __global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(1, 1)))
 
 #pragma unroll
   for (int u = 0; u < D; u++) ISSUE_STAGE(u, u)
+  // Row statistics given as partial sums (the producer was a GEMM over the whole k range that left
+  // one sum per 32-column tile): thread (g, row) adds planes g * pg .. g * pg + pg - 1 of its row.
+  // The loads are issued together behind the first stages (no extra round trip) and the SG group
+  // sums per row are kept in LDS until the epilogue adds them, always in the same order.
+  constexpr int SG = (64 * WN) / ROWS > 0 ? (64 * WN) / ROWS : 1;      // thread groups per row
+  constexpr int SPG = STAT_PARTS_MAX / SG;                             // planes per group, at most
+  static_assert(ROWS <= 64 * WN, "one thread per row at least");
+  float2* sstat = reinterpret_cast<float2*>(smem_raw + 2 * NFR * 1024);   // [SG][ROWS]
+  if (PRO != PRO_NONE && p.rowstat_parts > 1) {
+    const int row = t % ROWS, g = t / ROWS;
+    const int pg = (p.rowstat_parts + SG - 1) / SG;
+    const size_t rowg = (size_t)min(m0 + row, p.M - 1);
+    float2 v[SPG];
+#pragma unroll
+    for (int jj = 0; jj < SPG; jj++) {
+      const int j = min(g * pg + min(jj, pg - 1), p.rowstat_parts - 1);   // clamped, unconditional
+      v[jj] = *reinterpret_cast<const float2*>(p.rowstat + 2 * ((size_t)j * p.stat_rows + rowg));
+    }
+    float a = 0.f, b = 0.f;
+#pragma unroll
+    for (int jj = 0; jj < SPG; jj++) {
+      if (jj < pg && g * pg + jj < p.rowstat_parts) {
+        a += v[jj].x;
+        b += v[jj].y;
+      }
+    }
+    if (g < SG) sstat[g * ROWS + row] = make_float2(a, b);
+  }
   STORE_STAGE(0, 0)
   __syncthreads();
 
@@ -422,17 +451,31 @@ __global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(1, 1)))
 #undef ISSUE_STAGE
 #undef STORE_STAGE
 
-  if (!wave_active) return;
-
   // ---- epilogue --------------------------------------------------------------------------------
   // row statistics (from the kernel that produced the residual stream) of all token blocks in one
   // round trip, rows clamped into range
   float2 rst[MB];
   if (PRO != PRO_NONE) {
+    if (p.rowstat_parts <= 1) {
 #pragma unroll
-    for (int mb = 0; mb < MB; mb++)
-      rst[mb] = *reinterpret_cast<const float2*>(p.rowstat + 2 * (size_t)min(m0 + mb * 32 + lq, p.M - 1));
+      for (int mb = 0; mb < MB; mb++)
+        rst[mb] = *reinterpret_cast<const float2*>(p.rowstat + 2 * (size_t)min(m0 + mb * 32 + lq, p.M - 1));
+    } else {
+      // partial statistics were added up at entry (see above): one sum per thread group in LDS
+#pragma unroll
+      for (int mb = 0; mb < MB; mb++) {
+        float a = 0.f, b = 0.f;
+#pragma unroll
+        for (int g = 0; g < SG; g++) {
+          const float2 v = sstat[g * ROWS + mb * 32 + lq];
+          a += v.x;
+          b += v.y;
+        }
+        rst[mb] = make_float2(a, b);
+      }
+    }
   }
+  if (!wave_active) return;
 #pragma unroll
   for (int mb = 0; mb < MB; mb++) {
     const int ml = mb * 32 + lq;
@@ -585,6 +628,99 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
     }
     epilogue_tile<PRO, EPI>(p, sum, nt, ml, lh, ssum, ssq, blockIdx.y, ops);
   }
+}
+
+// ------------------------------------------------------------------------------------------------
+// "Entry" GEMM: the skinny kernels' plan (every load of the block issued at entry, one wait, no
+// LDS staging) for the O projections of the vision tower (k = 1152) and of the prefix at one view
+// (k = 2048).  As split-K partial GEMMs these need a reduction launch behind them; as one tall
+// GEMM over the whole k range they spend their time on consecutive memory round trips (18 or 32
+// chunks at 6 in flight).  Here one block = 64 tokens x NT feature tiles; 8 waves split the k16
+// steps (at most EN_SPW each) and hold their slice of both operands in registers, so the block
+// pays one round trip, and the residual epilogue runs in the same launch.  Partial tiles meet in
+// LDS, one 32-token block at a time, and are added in wave order; wave mb * NT + j finishes tile
+// (mb, j).  Input row statistics (unused by the residual epilogue) would be whole-row sums.
+// ------------------------------------------------------------------------------------------------
+template <int PRO, int EPI, int NT, int EN_SPW>
+__global__ __launch_bounds__(64 * SK_WAVES) void gemm_entry_kernel(GemmParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  float* red = reinterpret_cast<float*>(smem_raw);                 // [8 waves][NT][4][64][4]
+  const int t = threadIdx.x;
+  const int lane = t & 63;
+  const int w = t >> 6;
+  const int lq = lane & 31;
+  const int lh = lane >> 5;
+  const int nt0 = blockIdx.x * NT;
+  const int m0 = blockIdx.y * 64;
+  const int KC16 = p.W.k_pad >> 4;
+  const int XKC16 = p.ldx >> 4;
+  const int spw = (KC16 + SK_WAVES - 1) / SK_WAVES;        // host picks the instantiation with spw <= EN_SPW
+  const int s_beg = w * spw, s_end = min(s_beg + spw, KC16);
+  const int mb_last = (p.M - 1) >> 5;
+  bf16x8 wf[NT][EN_SPW], xf[2][EN_SPW];
+#pragma unroll
+  for (int i = 0; i < EN_SPW; i++) {
+    const int st = min(s_beg + i, KC16 - 1);   // clamped: steps beyond the wave's range are never used
+#pragma unroll
+    for (int j = 0; j < NT; j++)
+      wf[j][i] = *reinterpret_cast<const bf16x8*>(p.W.w + ((size_t)min(nt0 + j, p.n_tiles - 1) * KC16 + st) * 512 + lane * 8);
+#pragma unroll
+    for (int mb = 0; mb < 2; mb++)
+      xf[mb][i] = *reinterpret_cast<const bf16x8*>(p.X + ((size_t)min((m0 >> 5) + mb, mb_last) * XKC16 + st) * 512 + lane * 8);
+  }
+  const int fin_mb = w / NT, fin_j = w - fin_mb * NT;
+  const bool finisher = w < 2 * NT && nt0 + fin_j < p.n_tiles;
+  const int mrow = m0 + fin_mb * 32 + lq;
+  f32x16 acc[2][NT];
+#pragma unroll
+  for (int mb = 0; mb < 2; mb++)
+#pragma unroll
+    for (int j = 0; j < NT; j++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) acc[mb][j][r] = 0.f;
+#pragma unroll
+  for (int i = 0; i < EN_SPW; i++) {
+    if (s_beg + i < s_end) {
+#pragma unroll
+      for (int mb = 0; mb < 2; mb++)
+#pragma unroll
+        for (int j = 0; j < NT; j++) acc[mb][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j][i], xf[mb][i], acc[mb][j], 0, 0, 0);
+    }
+  }
+  // The finishing waves fetch what their epilogue needs once the operand registers are free; the
+  // round trip overlaps the reduction through LDS.
+  EpiOps ops;
+  float2 rst = make_float2(0.f, 0.f);
+  if (finisher && mrow < p.M) {
+    if (PRO != PRO_NONE) rst = *reinterpret_cast<const float2*>(p.rowstat + 2 * (size_t)mrow);
+    epilogue_preload<PRO, EPI>(p, nt0 + fin_j, mrow, lh, ops);
+  }
+  f32x16 sum;
+#pragma unroll
+  for (int r = 0; r < 16; r++) sum[r] = 0.f;
+#pragma unroll
+  for (int mb = 0; mb < 2; mb++) {
+    if (mb) __syncthreads();   // the readers of the first round are done
+#pragma unroll
+    for (int j = 0; j < NT; j++)
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        const f32x4 v4 = {acc[mb][j][4 * q], acc[mb][j][4 * q + 1], acc[mb][j][4 * q + 2], acc[mb][j][4 * q + 3]};
+        *reinterpret_cast<f32x4*>(red + ((((size_t)w * NT + j) * 4 + q) * 64 + lane) * 4) = v4;
+      }
+    __syncthreads();
+    if (fin_mb == mb && w < 2 * NT) {
+#pragma unroll
+      for (int ww = 0; ww < SK_WAVES; ww++)
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+          const f32x4 v4 = *reinterpret_cast<const f32x4*>(red + ((((size_t)ww * NT + fin_j) * 4 + q) * 64 + lane) * 4);
+#pragma unroll
+          for (int jj = 0; jj < 4; jj++) sum[4 * q + jj] += v4[jj];
+        }
+    }
+  }
+  if (finisher && mrow < p.M) epilogue_tile<PRO, EPI>(p, sum, nt0 + fin_j, mrow, lh, rst.x, rst.y, 0, ops);
 }
 
 // Skinny GEMM over the whole k range with the residual epilogue (the expert's O and down
@@ -794,9 +930,10 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny16_kernel(GemmParams
 static constexpr int skinny_smem_bytes() { return (SK_WAVES * 2 * 16 * 64 + 128 + SK_WAVES * 128) * 4; }
 
 // ------------------------------------------------------------------------------------------------
-template <int MB>
+// two staging buffers of MB * 4 fragments, then one (sum, sum of squares) pair per thread
+template <int MB, int WN>
 static constexpr int smem_bytes_for() {
-  return 2 * (MB * 4) * 1024;
+  return 2 * (MB * 4) * 1024 + 64 * WN * 8;
 }
 
 int gemm_rows_per_tile(int tile) {
@@ -809,6 +946,7 @@ int gemm_rows_per_tile(int tile) {
     case TILE_SMALL: return 64;
     case TILE_WIDE: return 256;
     case TILE_WIDE128: return 128;
+    case TILE_ENTRY: return 64;
     default: return -1;
   }
 }
@@ -819,7 +957,7 @@ static hipError_t launch_one(hipStream_t s, const GemmParams& p, int z) {
   const int nblocks_n = (p.n_tiles + WN * NT - 1) / (WN * NT);
   dim3 grid(8 * ((nblocks_n + 7) / 8) * p.m_tiles, z, 1);
   dim3 block(64 * WN, 1, 1);
-  constexpr int smem = smem_bytes_for<MB>();
+  constexpr int smem = smem_bytes_for<MB, WN>();
   gemm_kernel<MB, WN, D, PRO, EPI, NT><<<grid, block, smem, s>>>(p);
   return hipGetLastError();
 }
@@ -827,7 +965,7 @@ static hipError_t launch_one(hipStream_t s, const GemmParams& p, int z) {
 template <int MB, int WN, int D, int PRO, int EPI, int NT>
 static hipError_t set_attr() {
   return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<MB, WN, D, PRO, EPI, NT>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes_for<MB>());
+                             hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes_for<MB, WN>());
 }
 
 // The instantiations that exist.  X(tile id, MB, WN, D, PRO, EPI, NT)
@@ -847,6 +985,14 @@ static hipError_t set_attr() {
   X(TILE_WIDE, 8, 4, 2, PRO_NONE, EPI_PARTIAL, 2) \
   X(TILE_WIDE128, 4, 4, 3, PRO_RMS, EPI_GEGLU, 2)   \
   X(TILE_WIDE128, 4, 4, 3, PRO_NONE, EPI_PARTIAL, 2)
+
+// X(PRO, EPI, feature tiles per block, k16 steps per wave), ascending steps: vision O (k = 1152), prefix O
+// (k = 2048), vision QKV (k = 1152, 64 x 64 tiles)
+#define ENTRY_VARIANTS(X)       \
+  X(PRO_NONE, EPI_RESID, 1, 9)  \
+  X(PRO_NONE, EPI_RESID, 1, 16) \
+  X(PRO_LN, EPI_QKV, 2, 9)
+static constexpr int entry_smem_bytes(int nt) { return SK_WAVES * nt * 16 * 64 * 4; }
 
 #define SKINNY_VARIANTS(X)      \
   X(PRO_NONE, EPI_RESID)        \
@@ -869,6 +1015,14 @@ hipError_t gemm_init_attributes() {
                                        hipFuncAttributeMaxDynamicSharedMemorySize, skinny_smem_bytes());
     if (e != hipSuccess) return e;
   }
+#define X(PRO, EPI, NT, SPW)                                                                                     \
+  {                                                                                                              \
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_entry_kernel<PRO, EPI, NT, SPW>),     \
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, entry_smem_bytes(NT));        \
+    if (e != hipSuccess) return e;                                                                               \
+  }
+  ENTRY_VARIANTS(X)
+#undef X
 #define X(T, MB, WN, D, PRO, EPI, NT)                                 \
   {                                                                   \
     hipError_t e = set_attr<MB, WN, D, PRO, EPI, NT>();               \
@@ -903,6 +1057,11 @@ hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmPara
   if (pro != PRO_NONE && (z_splits != 1 || p.rowstat == nullptr)) return hipErrorInvalidValue;
   if (epi != EPI_PARTIAL && z_splits != 1) return hipErrorInvalidValue;
   if (p.m_tiles < 1) return hipErrorInvalidValue;
+  if (tile == TILE_BIG || tile == TILE_MID || tile == TILE_SMALL || tile == TILE_WIDE || tile == TILE_WIDE128 || tile == TILE_ENTRY) {
+    // partial row statistics: planes of stat_rows rows, every row a block touches inside a plane
+    if (pro != PRO_NONE && p.rowstat_parts > 1 && (p.stat_rows < p.M || p.rowstat_parts > STAT_PARTS_MAX)) return hipErrorInvalidValue;
+    if (epi == EPI_RESID && p.stat_out != nullptr && p.stat_rows < p.M + p.row_offset) return hipErrorInvalidValue;
+  }
   if (tile == TILE_SKINNY16) {
     // 16 x 16 tiles over the whole k range: k = 8 waves x NS steps x 32
     const int kc16 = p.W.k_pad >> 4;
@@ -917,6 +1076,23 @@ hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmPara
     if (kc16 == 128) gemm_skinny16_kernel<8><<<grid, dim3(64 * SK_WAVES), 0, s>>>(p);
     else gemm_skinny16_kernel<16><<<grid, dim3(64 * SK_WAVES), 0, s>>>(p);
     return hipGetLastError();
+  }
+  if (tile == TILE_ENTRY) {
+    // 64 tokens x NT feature tiles per block, the k16 steps split over 8 waves, at most EN_SPW each
+    const int kc16 = p.W.k_pad >> 4;
+    const int spw = (kc16 + SK_WAVES - 1) / SK_WAVES;
+    if (z_splits != 1 || p.m_tiles * 64 < p.M) return hipErrorInvalidValue;
+    if (pro != PRO_NONE && p.rowstat_parts > 1) return hipErrorInvalidValue;   // whole-row statistics only
+    if (epi == EPI_RESID && (p.out_f32 == nullptr || p.out_bf16 == nullptr)) return hipErrorInvalidValue;
+#define X(PRO, EPI, NT, SPW)                                                                                   \
+  if (pro == PRO && epi == EPI && spw <= SPW) {                                                                \
+    gemm_entry_kernel<PRO, EPI, NT, SPW><<<dim3((p.n_tiles + NT - 1) / NT, p.m_tiles), dim3(64 * SK_WAVES),    \
+                                           entry_smem_bytes(NT), s>>>(p);                                      \
+    return hipGetLastError();                                                                                  \
+  }
+    ENTRY_VARIANTS(X)
+#undef X
+    return hipErrorInvalidValue;
   }
   if (tile == TILE_SKINNY_FULLK) {
     const int kc16 = p.W.k_pad >> 4;

@@ -150,7 +150,7 @@ struct WsLayout {
   size_t xpatch, vh, vh_b, vq, vk, vv, vattn, vmid, part;
   size_t lx, lx_b, lq, kcache, vcache, lattn, lmid;
   size_t stok, z, y, y_b, eq, ek, ev, eattn, eml, emid;
-  size_t vstat, lstat, estat, estat_parts, pf_sink;
+  size_t vstat, lstat, estat, estat_parts, pf_sink, vstat_parts, lstat_parts;
   size_t total;
   size_t kcache_layer, vcache_layer;   // bytes per layer
   size_t kcache_slot, vcache_slot;     // bytes per cache copy (two copies: double buffering for pi0_stream_frame)
@@ -272,6 +272,8 @@ void ws_layout(const pi0_config& c, const Dims& d, WsLayout& w) {
   w.emid = cur.take((size_t)64 * d.Fx * 2);
   w.vstat = cur.take((size_t)d.maxI * 2 * 4);
   w.lstat = cur.take((size_t)d.maxPc * 32 * 2 * 4);
+  w.vstat_parts = cur.take((size_t)(d.Dv / 32) * d.maxI * 2 * 4);                     // [32-column tile][maxI][2]
+  w.lstat_parts = cur.take((size_t)(d.E / 32) * d.maxPc * 32 * 2 * 4);                // [32-column tile][maxPc * 32][2]
   w.estat = cur.take((size_t)64 * 2 * 4);
   w.estat_parts = cur.take((size_t)(d.X / 16) * 64 * 2 * 4);
   w.pf_sink = cur.take(1024 * 4);
@@ -301,7 +303,7 @@ enum { KIND_PREFILL = 0, KIND_DENOISE = 1, KIND_INFER = 2 };
 // e.g. PI0_TUNE="vis=1,lqkv=1,lgu=0,vo=1,vd=1,lo=0,ld=0,zvo=6,zlo=8,zld=16".
 struct Tune {
   int vis = TILE_MID;     // vision patch / projector (and QKV / up unless overridden below)
-  int vqkv = -1, vup = -1; // vision QKV / up tile (-1: same as vis)
+  int vqkv = -1, vup = -1; // vision QKV / up tile (-1: QKV on the entry kernel up to 256 tokens, else same as vis)
   int lqkv = -1;          // prefix QKV (-1: 64 x 64 tiles up to 256 tokens, 64 x 128 beyond)
   int lgu = -1;           // prefix gate||up (-1: 128 x 256 or 256 x 256 tiles, whichever fills the 256 CUs in fewer rounds)
   int vo = TILE_MID, vd = -1, lo = TILE_MID, ld = TILE_WIDE128;   // split-K partial GEMMs: vision O / down, prefix O / down
@@ -312,6 +314,10 @@ struct Tune {
   int ksplit = 1;         // expert attention: key shares for prefixes beyond kcps chunks
   int kcps = 8;
   int ae16 = 1;           // expert O / down on 16 x 16 tiles (256 blocks) instead of 32 x 32 (64 blocks)
+  // O projections as one launch over the whole k range (TILE_ENTRY: residual epilogue in the GEMM, no partial
+  // buffer, no reduction launch): vision O, prefix O.  -1: up to 256 tokens (measured: -0.06 ms at one view,
+  // nothing or a loss beyond, where the blocks' operand reads add up to more than the reduction launch costs)
+  int fko = -1, fkl = -1;
 };
 
 struct pi0_ctx {
@@ -433,6 +439,22 @@ void gemm_splitk_resid(Run& r, const PW& pw, const bf16* X, int ldx, int M, int 
   r.cls = cls_gemm;
 }
 
+// the same operation as one GEMM over the whole k range: bias / residual / gain-scaled shadow in the
+// GEMM's epilogue, row statistics left as one partial sum per 32-column tile in parts[n tile][stat_rows][2]
+void gemm_fullk_resid(Run& r, const PW& pw, const bf16* X, int ldx, int M, int k_true, const float* bias, float* resid_io,
+                      bf16* shadow, int n_true, float* parts, int stat_rows, const float* gain) {
+  GemmParams p = gp_base(r.c, pw, X, ldx, M, TILE_ENTRY, k_true);
+  p.bias = bias;
+  p.resid = resid_io;
+  p.out_f32 = resid_io;
+  p.out_bf16 = shadow;
+  p.ldo = n_true; p.ldo2 = n_true; p.n_valid = n_true;
+  p.gain = gain;
+  p.stat_out = parts;
+  p.stat_rows = stat_rows;
+  RUN_GEMM(r, TILE_ENTRY, PRO_NONE, EPI_RESID, p, 1);
+}
+
 struct Taps {
   float* base = nullptr;
   size_t off = 0;
@@ -459,8 +481,9 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
   const int vchunks = I / 32;
   const int zvo = T.zvo > 0 ? T.zvo : (I <= 256 ? 3 : I <= 512 ? 2 : 1);
   const int tvd = T.vd >= 0 ? T.vd : (I <= 256 ? TILE_MID : TILE_BIG);
-  // one view: the QKV GEMM has too few 64 x 128 tiles for 256 CUs, 64 x 64 tiles spread it further
-  const int tqkv = T.vqkv >= 0 ? T.vqkv : (I <= 256 ? TILE_SMALL : T.vis), tup = T.vup >= 0 ? T.vup : T.vis;
+  // one view: the QKV GEMM has too few 64 x 128 tiles for 256 CUs; 64 x 64 tiles with every load issued at entry
+  const int tqkv = T.vqkv >= 0 ? T.vqkv : (I <= 256 ? TILE_ENTRY : T.vis), tup = T.vup >= 0 ? T.vup : T.vis;
+  const bool fko = T.fko >= 0 ? T.fko != 0 : I <= 256;
   for (int l = 0; l < d.Lv; l++) {
     const WsVis& L = w.vis[l];
     {  // A1: LN -> QKV (+bias), keys/values straight into attention fragment order
@@ -494,14 +517,19 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
     }
     // A3: O-projection + bias + residual
     r.cls = PI0_OP_VIS_O;
-    gemm_splitk_resid(r, L.o, at<bf16>(c, w.vattn), d.Dv, I, d.Dv, zvo, round_up(ceil_div(L.o.k_pad, zvo), 64),
-                      at<float>(c, L.o.bias), at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv, T.vo, at<float>(c, w.vstat),
-                      at<float>(c, w.g_v2[l]));
+    if (fko)
+      gemm_fullk_resid(r, L.o, at<bf16>(c, w.vattn), d.Dv, I, d.Dv, at<float>(c, L.o.bias), at<float>(c, w.vh),
+                       at<bf16>(c, w.vh_b), d.Dv, at<float>(c, w.vstat_parts), d.maxI, at<float>(c, w.g_v2[l]));
+    else
+      gemm_splitk_resid(r, L.o, at<bf16>(c, w.vattn), d.Dv, I, d.Dv, zvo, round_up(ceil_div(L.o.k_pad, zvo), 64),
+                        at<float>(c, L.o.bias), at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv, T.vo, at<float>(c, w.vstat),
+                        at<float>(c, w.g_v2[l]));
     {  // A4: LN -> up (+bias, GELU)
       GemmParams p = gp_base(c, L.up, at<bf16>(c, w.vh_b), d.Dv, I, tup, d.Dv);
       p.bias = at<float>(c, L.up.bias);
       p.colsum = at<float>(c, L.up.colsum);
       p.rowstat = at<float>(c, w.vstat);
+      if (fko) { p.rowstat = at<float>(c, w.vstat_parts); p.rowstat_parts = L.o.n_pad / 32; p.stat_rows = d.maxI; }
       p.out_bf16 = at<bf16>(c, w.vmid);
       p.ldo = d.Fv_kp; p.n_valid = L.up.n_pad; p.act = ACT_GELU;
       r.cls = PI0_OP_VIS_UP;
@@ -535,6 +563,7 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
                           at<float>(c, w.lstat)));
   const int pchunks = ceil_div(P, 32);
   const int tlqkv = T.lqkv >= 0 ? T.lqkv : (P <= 256 ? TILE_SMALL : TILE_MID);
+  const bool fkl = T.fkl >= 0 ? T.fkl != 0 : P <= 256;
   // gate||up: 128 blocks of 256 features per token tile.  A 256-token tile costs two 128-token tiles; take the
   // tile height whose block count needs fewer rounds on 256 compute units (ties: the taller tile).
   const int gu_cols = ceil_div(w.llm[0].gu.n_pad, 256);
@@ -575,12 +604,17 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
     }
     // B3: O-projection + residual
     r.cls = PI0_OP_LLM_O;
-    gemm_splitk_resid(r, L.o, at<bf16>(c, w.lattn), d.H * 256, P, d.H * 256, T.zlo,
-                      round_up(ceil_div(L.o.k_pad, T.zlo), 64), nullptr, at<float>(c, w.lx), at<bf16>(c, w.lx_b), d.E, T.lo,
-                      at<float>(c, w.lstat), at<float>(c, w.g_l2[l]));
+    if (fkl)
+      gemm_fullk_resid(r, L.o, at<bf16>(c, w.lattn), d.H * 256, P, d.H * 256, nullptr, at<float>(c, w.lx), at<bf16>(c, w.lx_b),
+                       d.E, at<float>(c, w.lstat_parts), d.maxPc * 32, at<float>(c, w.g_l2[l]));
+    else
+      gemm_splitk_resid(r, L.o, at<bf16>(c, w.lattn), d.H * 256, P, d.H * 256, T.zlo,
+                        round_up(ceil_div(L.o.k_pad, T.zlo), 64), nullptr, at<float>(c, w.lx), at<bf16>(c, w.lx_b), d.E, T.lo,
+                        at<float>(c, w.lstat), at<float>(c, w.g_l2[l]));
     {  // B4: RMS -> gate||up with fused GELU gate
       GemmParams p = gp_base(c, L.gu, at<bf16>(c, w.lx_b), d.E, P, tlgu, d.E);
       p.rowstat = at<float>(c, w.lstat);
+      if (fkl) { p.rowstat = at<float>(c, w.lstat_parts); p.rowstat_parts = L.o.n_pad / 32; p.stat_rows = d.maxPc * 32; }
       p.out_bf16 = at<bf16>(c, w.lmid);
       p.ldo = d.F;
       r.cls = PI0_OP_LLM_GATEUP;
@@ -908,11 +942,12 @@ int pi0_create(const pi0_config* cfg, pi0_ctx** out) {
   if (const char* env = getenv("PI0_TUNE")) {
     struct { const char* key; int* dst; int lo, hi; } keys[] = {
         {"vis", &c->tune.vis, 0, 5},   {"lqkv", &c->tune.lqkv, 0, 5}, {"lgu", &c->tune.lgu, 0, 7},
-        {"vqkv", &c->tune.vqkv, -1, 5}, {"vup", &c->tune.vup, -1, 5},
+        {"vqkv", &c->tune.vqkv, -1, 8}, {"vup", &c->tune.vup, -1, 5},
         {"vo", &c->tune.vo, 0, 5}, {"vd", &c->tune.vd, 0, 5}, {"lo", &c->tune.lo, 0, 5}, {"ld", &c->tune.ld, 0, 7}, {"zvo", &c->tune.zvo, 1, Z_MAX}, {"zlo", &c->tune.zlo, 1, Z_MAX},
         {"zld", &c->tune.zld, 1, Z_MAX}, {"zvd", &c->tune.zvd, 1, Z_MAX},
         {"pfq", &c->tune.pfq, 0, 1024}, {"pfa", &c->tune.pfa, 0, 1024}, {"pfo", &c->tune.pfo, 0, 1024},
-        {"pfd", &c->tune.pfd, 0, 1024}, {"ae16", &c->tune.ae16, 0, 1}, {"ksplit", &c->tune.ksplit, 0, 1}, {"kcps", &c->tune.kcps, 2, 16}, {"qms", &c->tune.qms, 0, 1}};
+        {"pfd", &c->tune.pfd, 0, 1024}, {"ae16", &c->tune.ae16, 0, 1}, {"ksplit", &c->tune.ksplit, 0, 1}, {"kcps", &c->tune.kcps, 2, 16}, {"qms", &c->tune.qms, 0, 1},
+        {"fko", &c->tune.fko, 0, 1}, {"fkl", &c->tune.fkl, 0, 1}};
     for (auto& k : keys) {
       const char* f = strstr(env, k.key);
       while (f != nullptr && !((f == env || f[-1] == ',') && f[strlen(k.key)] == '=')) f = strstr(f + 1, k.key);

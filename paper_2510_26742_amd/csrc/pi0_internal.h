@@ -118,8 +118,9 @@ struct GemmParams {
   const float* colsum;  // [n_pad], PRO_LN only: sum_k W'[n][k]
   const float* rowstat; // (sum, sum of squares) of the fp32 residual rows, PRO_RMS / PRO_LN: [rows][2] for the tall
                         // kernels; [rowstat_parts][64][2] partial sums for the skinny kernel
-  int rowstat_parts;
-  float* stat_out;      // EPI_RESID: partial row statistics of the output per 32-column tile, [n tile][64][2], or null
+  int rowstat_parts;    // tall kernels: 0 / 1 = rowstat holds whole-row sums, > 1 = [rowstat_parts][stat_rows][2] partial sums
+  float* stat_out;      // EPI_RESID: partial row statistics of the output per 32-column tile, [n tile][stat_rows][2], or null
+  int stat_rows;        // rows per plane of stat_out (producer) / of a partial rowstat (tall consumer); 0 = 64
   const float* gain;    // EPI_RESID: per-column scale of the bf16 shadow (gain of the norm that follows), or null
   // outputs
   float* out_f32;     // EPI_RESID / EPI_PARTIAL / EPI_EULER
@@ -166,7 +167,8 @@ enum GemmTile {
   TILE_SMALL = 5,         // 64 tokens x 64 features per block (2 waves), 6 stages: small GEMMs of the vision tower
   // two feature tiles per wave: an activation fragment read from LDS feeds two MFMAs (prefix gate||up / down only)
   TILE_WIDE = 6,          // 256 tokens x 256 features per block (4 waves x 2 feature tiles), 2 stages
-  TILE_WIDE128 = 7        // 128 tokens x 256 features per block, 3 stages
+  TILE_WIDE128 = 7,       // 128 tokens x 256 features per block, 3 stages
+  TILE_ENTRY = 8          // 64 tokens x 32 features per block, k <= 2048 split over 8 waves, every load issued at entry; residual epilogue
 };
 
 hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmParams& p, int z_splits);

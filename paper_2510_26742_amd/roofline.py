@@ -189,14 +189,23 @@ KERNEL_OF_CLASS = {
 }
 
 
-def kernel_rooflines(work: dict, timing: dict, traffic: dict | None = None) -> list:
+def kernel_of_class(name: str, prefix_tokens: int | None = None):
+    """Kernel template family that runs an operation class.  Up to 256 tokens the library's default schedule runs
+    the vision QKV projection and the vision and prefix O projections on gemm_entry_kernel (every load issued at
+    entry; the O projections over the whole k range with the residual epilogue in the GEMM)."""
+    if prefix_tokens is not None and prefix_tokens <= 256 and name in ("vis_qkv", "vis_o", "llm_o"):
+        return "gemm_entry_kernel"
+    return KERNEL_OF_CLASS.get(name)
+
+
+def kernel_rooflines(work: dict, timing: dict, traffic: dict | None = None, prefix_tokens: int | None = None) -> list:
     """Per kernel (all launches of one template family): total time, launches, algorithmic bytes and flops summed
     over its launches, the bound that dominates, the achieved rate over the kernel's total time and the
     fraction of the MI355X peak; `traffic` (measured HBM-side bytes per launch by class) is averaged over the
     launches it covers, None if a class of the family has no counter figure."""
     fam = {}
     for name, (total_us, launches) in timing.items():
-        k = KERNEL_OF_CLASS.get(name)
+        k = kernel_of_class(name, prefix_tokens)
         if k is None or launches == 0 or name not in work:
             continue
         f = fam.setdefault(k, {"kernel": k, "classes": [], "launches": 0, "total_us": 0.0, "bytes": 0.0, "flops": 0.0,
