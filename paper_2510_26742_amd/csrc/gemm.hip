@@ -947,6 +947,7 @@ int gemm_rows_per_tile(int tile) {
     case TILE_WIDE: return 256;
     case TILE_WIDE128: return 128;
     case TILE_ENTRY: return 64;
+    case TILE_SQ128: return 128;
     default: return -1;
   }
 }
@@ -981,6 +982,7 @@ static hipError_t set_attr() {
   TALL_EPIS(X, TILE_BIG, 8, 4, 3)  \
   TALL_EPIS(X, TILE_MID, 2, 4, 6)   \
   TALL_EPIS(X, TILE_SMALL, 2, 2, 6) \
+  TALL_EPIS(X, TILE_SQ128, 4, 4, 5) \
   X(TILE_WIDE, 8, 4, 2, PRO_RMS, EPI_GEGLU, 2)   \
   X(TILE_WIDE, 8, 4, 2, PRO_NONE, EPI_PARTIAL, 2) \
   X(TILE_WIDE128, 4, 4, 3, PRO_RMS, EPI_GEGLU, 2)   \

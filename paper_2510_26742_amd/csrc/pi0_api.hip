@@ -306,8 +306,8 @@ struct Tune {
   int vqkv = -1, vup = -1; // vision QKV / up tile (-1: QKV on the entry kernel up to 256 tokens, else same as vis)
   int lqkv = -1;          // prefix QKV (-1: 64 x 64 tiles up to 256 tokens, 64 x 128 beyond)
   int lgu = -1;           // prefix gate||up (-1: 128 x 256 or 256 x 256 tiles, whichever fills the 256 CUs in fewer rounds)
-  int vo = TILE_MID, vd = -1, lo = TILE_MID, ld = TILE_WIDE128;   // split-K partial GEMMs: vision O / down, prefix O / down
-  int zvo = -1, zlo = 4, zld = -1, zvd = 4;   // -1: chosen from the number of image tokens (measured optima at 1 / 2 / 3 views)
+  int vo = TILE_MID, vd = -1, lo = -1, ld = TILE_WIDE128;   // split-K partial GEMMs: vision O / down, prefix O / down
+  int zvo = -1, zlo = -1, zld = -1, zvd = -1;   // -1: chosen from the number of tokens (measured optima at 1 / 2 / 3 views)
   // warm-up blocks carried by the expert's launches (0 = none): QKV, attention, O, down
   int pfq = 64, pfa = 64, pfo = 128, pfd = 128;
   int qms = 1;            // expert QKV: token blocks on separate blocks (160 instead of 80)
@@ -480,9 +480,12 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
                     at<float>(c, w.pos), d.T);
   const int vchunks = I / 32;
   const int zvo = T.zvo > 0 ? T.zvo : (I <= 256 ? 3 : I <= 512 ? 2 : 1);
-  const int tvd = T.vd >= 0 ? T.vd : (I <= 256 ? TILE_MID : TILE_BIG);
+  const int tvd = T.vd >= 0 ? T.vd : (I <= 256 ? TILE_MID : TILE_SQ128);
+  const int zvd = T.zvd > 0 ? T.zvd : (I <= 512 ? 4 : 2);
   // one view: the QKV GEMM has too few 64 x 128 tiles for 256 CUs; 64 x 64 tiles with every load issued at entry
-  const int tqkv = T.vqkv >= 0 ? T.vqkv : (I <= 256 ? TILE_ENTRY : T.vis), tup = T.vup >= 0 ? T.vup : T.vis;
+  // two and three views: 128 x 128 tiles need fewer operand bytes per CU than 64 x 128 once they still fill the chip
+  const int tqkv = T.vqkv >= 0 ? T.vqkv : (I <= 256 ? TILE_ENTRY : I <= 512 ? T.vis : TILE_SQ128);
+  const int tup = T.vup >= 0 ? T.vup : (I <= 256 ? T.vis : TILE_SQ128);
   const bool fko = T.fko >= 0 ? T.fko != 0 : I <= 256;
   for (int l = 0; l < d.Lv; l++) {
     const WsVis& L = w.vis[l];
@@ -537,7 +540,7 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
     }
     // A5: down (+bias, residual)
     r.cls = PI0_OP_VIS_DOWN;
-    gemm_splitk_resid(r, L.down, at<bf16>(c, w.vmid), d.Fv_kp, I, d.Fv, T.zvd, round_up(ceil_div(L.down.k_pad, T.zvd), 64),
+    gemm_splitk_resid(r, L.down, at<bf16>(c, w.vmid), d.Fv_kp, I, d.Fv, zvd, round_up(ceil_div(L.down.k_pad, zvd), 64),
                       at<float>(c, L.down.bias), at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv, tvd, at<float>(c, w.vstat),
                       at<float>(c, l + 1 < d.Lv ? w.g_v1[l + 1] : w.g_vf));
     if (taps) taps->put(r, at<float>(c, w.vh), (size_t)I * d.Dv);
@@ -562,7 +565,9 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
   RUN(r, launch_row_stats(r.s, at<float>(c, w.lx), d.E, P, d.E, d.E, at<float>(c, w.g_l1[0]), at<bf16>(c, w.lx_b),
                           at<float>(c, w.lstat)));
   const int pchunks = ceil_div(P, 32);
-  const int tlqkv = T.lqkv >= 0 ? T.lqkv : (P <= 256 ? TILE_SMALL : TILE_MID);
+  const int tlqkv = T.lqkv >= 0 ? T.lqkv : (P <= 256 ? TILE_SMALL : P <= 512 ? TILE_MID : TILE_SQ128);
+  const int tlo = T.lo >= 0 ? T.lo : (P <= 512 ? TILE_MID : TILE_SQ128);
+  const int zlo = T.zlo > 0 ? T.zlo : (P <= 256 ? 4 : 2);
   const bool fkl = T.fkl >= 0 ? T.fkl != 0 : P <= 256;
   // gate||up: 128 blocks of 256 features per token tile.  A 256-token tile costs two 128-token tiles; take the
   // tile height whose block count needs fewer rounds on 256 compute units (ties: the taller tile).
@@ -608,8 +613,8 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
       gemm_fullk_resid(r, L.o, at<bf16>(c, w.lattn), d.H * 256, P, d.H * 256, nullptr, at<float>(c, w.lx), at<bf16>(c, w.lx_b),
                        d.E, at<float>(c, w.lstat_parts), d.maxPc * 32, at<float>(c, w.g_l2[l]));
     else
-      gemm_splitk_resid(r, L.o, at<bf16>(c, w.lattn), d.H * 256, P, d.H * 256, T.zlo,
-                        round_up(ceil_div(L.o.k_pad, T.zlo), 64), nullptr, at<float>(c, w.lx), at<bf16>(c, w.lx_b), d.E, T.lo,
+      gemm_splitk_resid(r, L.o, at<bf16>(c, w.lattn), d.H * 256, P, d.H * 256, zlo,
+                        round_up(ceil_div(L.o.k_pad, zlo), 64), nullptr, at<float>(c, w.lx), at<bf16>(c, w.lx_b), d.E, tlo,
                         at<float>(c, w.lstat), at<float>(c, w.g_l2[l]));
     {  // B4: RMS -> gate||up with fused GELU gate
       GemmParams p = gp_base(c, L.gu, at<bf16>(c, w.lx_b), d.E, P, tlgu, d.E);
@@ -941,9 +946,9 @@ int pi0_create(const pi0_config* cfg, pi0_ctx** out) {
 
   if (const char* env = getenv("PI0_TUNE")) {
     struct { const char* key; int* dst; int lo, hi; } keys[] = {
-        {"vis", &c->tune.vis, 0, 5},   {"lqkv", &c->tune.lqkv, 0, 5}, {"lgu", &c->tune.lgu, 0, 7},
-        {"vqkv", &c->tune.vqkv, -1, 8}, {"vup", &c->tune.vup, -1, 5},
-        {"vo", &c->tune.vo, 0, 5}, {"vd", &c->tune.vd, 0, 5}, {"lo", &c->tune.lo, 0, 5}, {"ld", &c->tune.ld, 0, 7}, {"zvo", &c->tune.zvo, 1, Z_MAX}, {"zlo", &c->tune.zlo, 1, Z_MAX},
+        {"vis", &c->tune.vis, 0, 9},   {"lqkv", &c->tune.lqkv, 0, 9}, {"lgu", &c->tune.lgu, 0, 9},
+        {"vqkv", &c->tune.vqkv, -1, 9}, {"vup", &c->tune.vup, -1, 9},
+        {"vo", &c->tune.vo, 0, 9}, {"vd", &c->tune.vd, 0, 9}, {"lo", &c->tune.lo, 0, 9}, {"ld", &c->tune.ld, 0, 9}, {"zvo", &c->tune.zvo, 1, Z_MAX}, {"zlo", &c->tune.zlo, 1, Z_MAX},
         {"zld", &c->tune.zld, 1, Z_MAX}, {"zvd", &c->tune.zvd, 1, Z_MAX},
         {"pfq", &c->tune.pfq, 0, 1024}, {"pfa", &c->tune.pfa, 0, 1024}, {"pfo", &c->tune.pfo, 0, 1024},
         {"pfd", &c->tune.pfd, 0, 1024}, {"ae16", &c->tune.ae16, 0, 1}, {"ksplit", &c->tune.ksplit, 0, 1}, {"kcps", &c->tune.kcps, 2, 16}, {"qms", &c->tune.qms, 0, 1},

@@ -168,7 +168,8 @@ enum GemmTile {
   // two feature tiles per wave: an activation fragment read from LDS feeds two MFMAs (prefix gate||up / down only)
   TILE_WIDE = 6,          // 256 tokens x 256 features per block (4 waves x 2 feature tiles), 2 stages
   TILE_WIDE128 = 7,       // 128 tokens x 256 features per block, 3 stages
-  TILE_ENTRY = 8          // 64 tokens x 32 features per block, k <= 2048 split over 8 waves, every load issued at entry; residual epilogue
+  TILE_ENTRY = 8,         // 64 tokens x 32 / 64 features per block, k <= 2048 split over 8 waves, every load issued at entry
+  TILE_SQ128 = 9          // 128 tokens x 128 features per block (4 waves), 5 stages: the mid-size GEMMs at three views
 };
 
 hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmParams& p, int z_splits);
