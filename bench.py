@@ -23,10 +23,10 @@ if ROOT not in sys.path:
 # HBM-side bytes per launch of an operation class, where a counter run exists (2 x FETCH_SIZE + WRITE_SIZE,
 # calibrated against a copy kernel)
 PMC_TRAFFIC_BYTES = {   # profiles/counters_full_pi0_1view_eager_pass.txt (expert launches: includes what they read ahead)
-    "exp_down": 19167232, "exp_gateup": 18717696, "exp_o": 15729664, "exp_qkv": 11335680, "exp_attn": 20119552,
-    "exp_out": 259789,
-    "llm_gateup": 151338393, "llm_down": 167949721, "vis_down": 29837414, "llm_o": 29837414, "vis_up": 17199923,
-    "vis_qkv": 14818304, "llm_qkv": 21565849, "vis_o": 11017216, "vis_proj": 12856320, "vis_patch": 5409792,
+    "exp_down": 19167232, "exp_gateup": 18705408, "exp_o": 15749120, "exp_qkv": 11334656, "exp_attn": 20127129,
+    "exp_out": 259788,
+    "llm_gateup": 152385331, "llm_down": 167919001, "llm_qkv": 21047296, "llm_o": 22289612, "vis_qkv": 38654156,
+    "vis_o": 13193216, "vis_up": 17787699, "vis_down": 32711680, "vis_proj": 12871680, "vis_patch": 5421056,
 }
 
 

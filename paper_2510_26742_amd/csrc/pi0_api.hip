@@ -442,8 +442,8 @@ void gemm_splitk_resid(Run& r, const PW& pw, const bf16* X, int ldx, int M, int 
 // the same operation as one GEMM over the whole k range: bias / residual / gain-scaled shadow in the
 // GEMM's epilogue, row statistics left as one partial sum per 32-column tile in parts[n tile][stat_rows][2]
 void gemm_fullk_resid(Run& r, const PW& pw, const bf16* X, int ldx, int M, int k_true, const float* bias, float* resid_io,
-                      bf16* shadow, int n_true, float* parts, int stat_rows, const float* gain) {
-  GemmParams p = gp_base(r.c, pw, X, ldx, M, TILE_ENTRY, k_true);
+                      bf16* shadow, int n_true, float* parts, int stat_rows, const float* gain, int tile = TILE_ENTRY) {
+  GemmParams p = gp_base(r.c, pw, X, ldx, M, tile, k_true);
   p.bias = bias;
   p.resid = resid_io;
   p.out_f32 = resid_io;
@@ -452,7 +452,7 @@ void gemm_fullk_resid(Run& r, const PW& pw, const bf16* X, int ldx, int M, int k
   p.gain = gain;
   p.stat_out = parts;
   p.stat_rows = stat_rows;
-  RUN_GEMM(r, TILE_ENTRY, PRO_NONE, EPI_RESID, p, 1);
+  RUN_GEMM(r, tile, PRO_NONE, EPI_RESID, p, 1);
 }
 
 struct Taps {
@@ -522,7 +522,8 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
     r.cls = PI0_OP_VIS_O;
     if (fko)
       gemm_fullk_resid(r, L.o, at<bf16>(c, w.vattn), d.Dv, I, d.Dv, at<float>(c, L.o.bias), at<float>(c, w.vh),
-                       at<bf16>(c, w.vh_b), d.Dv, at<float>(c, w.vstat_parts), d.maxI, at<float>(c, w.g_v2[l]));
+                       at<bf16>(c, w.vh_b), d.Dv, at<float>(c, w.vstat_parts), d.maxI, at<float>(c, w.g_v2[l]),
+                       I <= 256 ? TILE_ENTRY : T.vo);
     else
       gemm_splitk_resid(r, L.o, at<bf16>(c, w.vattn), d.Dv, I, d.Dv, zvo, round_up(ceil_div(L.o.k_pad, zvo), 64),
                         at<float>(c, L.o.bias), at<float>(c, w.vh), at<bf16>(c, w.vh_b), d.Dv, T.vo, at<float>(c, w.vstat),
@@ -611,7 +612,7 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
     r.cls = PI0_OP_LLM_O;
     if (fkl)
       gemm_fullk_resid(r, L.o, at<bf16>(c, w.lattn), d.H * 256, P, d.H * 256, nullptr, at<float>(c, w.lx), at<bf16>(c, w.lx_b),
-                       d.E, at<float>(c, w.lstat_parts), d.maxPc * 32, at<float>(c, w.g_l2[l]));
+                       d.E, at<float>(c, w.lstat_parts), d.maxPc * 32, at<float>(c, w.g_l2[l]), P <= 256 ? TILE_ENTRY : tlo);
     else
       gemm_splitk_resid(r, L.o, at<bf16>(c, w.lattn), d.H * 256, P, d.H * 256, zlo,
                         round_up(ceil_div(L.o.k_pad, zlo), 64), nullptr, at<float>(c, w.lx), at<bf16>(c, w.lx_b), d.E, tlo,
