@@ -30,6 +30,8 @@ from typing import Dict, Optional
 
 import numpy as np
 
+from . import mxfp8
+
 EPS = 1e-6
 
 
@@ -121,6 +123,11 @@ class Weights:
     def __getitem__(self, name):
         return widen_bf16(self.t[name], self.dtype)
 
+    def mx(self, name):
+        """Weight matrix [k, n] rounded through MXFP8 with blocks of 32 along k (its contraction axis)."""
+        w = widen_bf16(self.t[name], np.float64)
+        return np.ascontiguousarray(mxfp8.mx_round(w.T, np.float64).T).astype(self.dtype)
+
 
 def patchify(cfg, images, dtype):
     """[V, H, W, 3] -> [V * T, patch*patch*3]; patch vector order (dy, dx, channel)."""
@@ -177,8 +184,23 @@ def _gemma_mlp(W, p, x):
     return (gelu_tanh(m @ W[p + "wg"]) * (m @ W[p + "wu"])) @ W[p + "wd"]
 
 
+def _gemma_mlp_mxfp8(W, p, x):
+    """The same feed-forward block with every GEMM operand rounded through MXFP8 (blocks of 32 along the
+    contraction axis).  A convention of this build, not of the paper: the gain-scaled input x * (1 + g) is
+    what gets quantised and the row's 1 / rms is applied to the products (power-of-two block scales do not
+    commute with an arbitrary row factor, so the order is part of the definition); the gated product
+    gelu(gate) * up is quantised before the down projection."""
+    dt = x.dtype
+    rstd = dt.type(1.0) / np.sqrt((x * x).mean(axis=-1, keepdims=True) + dt.type(EPS))
+    xq = mxfp8.mx_round(x * (dt.type(1.0) + W[p + "g_mlp"]))
+    gate = rstd * (xq @ W.mx(p + "wg"))
+    up = rstd * (xq @ W.mx(p + "wu"))
+    hq = mxfp8.mx_round(gelu_tanh(gate) * up)
+    return hq @ W.mx(p + "wd")
+
+
 def prefix_forward(cfg, W: Weights, images, prompt_ids=None, taps: Optional[dict] = None,
-                   run_last_layer: bool = False):
+                   run_last_layer: bool = False, mlp_mxfp8: bool = False):
     """Vision tower, prompt embedding, and the prefix transformer.  Returns the per-layer
     key and value caches ([L, P, head_dim] each).  The last layer only produces its keys and
     values (Section 4.1: its attention and FFN feed nothing downstream) unless
@@ -203,7 +225,7 @@ def prefix_forward(cfg, W: Weights, images, prompt_ids=None, taps: Optional[dict
             break
         o = attention(q, k, v, allowed).transpose(1, 0, 2).reshape(P, -1)
         x = x + o @ W[p + "wo"]
-        x = x + _gemma_mlp(W, p, x)
+        x = x + (_gemma_mlp_mxfp8(W, p, x) if mlp_mxfp8 else _gemma_mlp(W, p, x))
         if taps is not None:
             taps[f"llm.x.{l}"] = x.copy()
     return Ks, Vs
@@ -267,10 +289,11 @@ def denoise(cfg, W: Weights, Ks, Vs, state, noise, taps: Optional[dict] = None, 
 
 
 def pi0_forward(cfg, tensors: Dict[str, np.ndarray], images, state, noise, prompt_ids=None,
-                dtype=np.float32, taps: Optional[dict] = None):
-    """images [V,H,W,3], state [state_dim], noise [chunk, action_dim] -> action chunk."""
+                dtype=np.float32, taps: Optional[dict] = None, prefix_mlp_mxfp8: bool = False):
+    """images [V,H,W,3], state [state_dim], noise [chunk, action_dim] -> action chunk.
+    prefix_mlp_mxfp8: the prefix transformer's feed-forward GEMMs take MXFP8-rounded operands."""
     W = Weights(tensors, dtype)
-    Ks, Vs = prefix_forward(cfg, W, images, prompt_ids, taps)
+    Ks, Vs = prefix_forward(cfg, W, images, prompt_ids, taps, mlp_mxfp8=prefix_mlp_mxfp8)
     if taps is not None:
         taps["kcache"], taps["vcache"] = Ks.copy(), Vs.copy()
     return denoise(cfg, W, Ks, Vs, state, noise, taps, tap_steps=(0, cfg.steps - 1))
