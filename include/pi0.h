@@ -256,6 +256,22 @@ enum pi0_peak_kind { PI0_PEAK_HBM_READ = 0, PI0_PEAK_MFMA_BF16 = 1 };
 int pi0_peak_bench(int kind, const void* d_buf, size_t bytes, int iters, int reps, unsigned* d_sink,
                    double* h_result, void* hip_stream);
 
+/*
+ * Arithmetic of the prefix transformer's feed-forward GEMMs (gate||up and down; everything else stays bf16).
+ * The paper runs everything in bf16 and names 8-bit multiplication as a direction (Section 9.1); the
+ * reduced-precision mode is this library's reading of it and changes the numerics contract:
+ *   PI0_PRECISION_BF16 (default)        bf16 operands, fp32 accumulation
+ *   PI0_PRECISION_MXFP8_PREFIX_MLP      OCP MXFP8 operands (FP8 E4M3 elements, one power-of-two E8M0 scale per 32
+ *                                       consecutive elements of the contraction axis), fp32 accumulation, block
+ *                                       scales applied by the MFMA.  Quantised: the weights (at load time, both
+ *                                       copies are kept), the gain-scaled input x * (1 + g) of gate||up (1 / rms is
+ *                                       applied to the products), and gelu(gate) * up before the down projection.
+ * Takes effect from the next pi0_prefill / pi0_infer / pi0_stream_frame; may be changed at any time between calls
+ * (graphs are kept per mode).  EINVAL for an unknown mode, or if llm_width / llm_mlp are not multiples of 256.
+ */
+enum pi0_precision { PI0_PRECISION_BF16 = 0, PI0_PRECISION_MXFP8_PREFIX_MLP = 1 };
+int pi0_set_precision(pi0_ctx* ctx, int precision);
+
 /* Graph replay on (1, default) or off (0: every call launches kernels eagerly). */
 int pi0_set_graph_mode(pi0_ctx* ctx, int enabled);
 

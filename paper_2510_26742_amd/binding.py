@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libpi0_hip.so")
 
 EXPORTS = ["pi0_create", "pi0_destroy", "pi0_weights_bytes", "pi0_workspace_bytes", "pi0_load_weights",
            "pi0_prefill", "pi0_denoise", "pi0_infer", "pi0_debug_taps_elems", "pi0_debug_forward", "pi0_debug_profile", "pi0_sync_bench", "pi0_peak_bench", "pi0_stream_frame",
-           "pi0_set_graph_mode", "pi0_kernel_count", "pi0_strerror", "pi0_last_hip_error"]
+           "pi0_set_graph_mode", "pi0_set_precision", "pi0_kernel_count", "pi0_strerror", "pi0_last_hip_error"]
 
 # enum pi0_op_class, in order
 OP_CLASSES = ["misc", "vis_patch", "vis_qkv", "vis_attn", "vis_o", "vis_up", "vis_down", "vis_proj", "reduce",
@@ -81,6 +81,8 @@ def lib() -> ctypes.CDLL:
         L.pi0_peak_bench.restype = i32
         L.pi0_set_graph_mode.argtypes = [vp, i32]
         L.pi0_set_graph_mode.restype = i32
+        L.pi0_set_precision.argtypes = [vp, i32]
+        L.pi0_set_precision.restype = i32
         L.pi0_kernel_count.argtypes = [vp, i32, i32]
         L.pi0_kernel_count.restype = i32
         L.pi0_strerror.argtypes = [i32]
@@ -133,6 +135,7 @@ def pi0_sync_bench(mode: str, n_ops: int, reps: int, d_x, d_b, d_state, stream=N
 
 
 PEAK_KINDS = {"hbm_read": 0, "mfma_bf16": 1}
+PRECISIONS = {"bf16": 0, "mxfp8_prefix_mlp": 1}
 
 
 def pi0_peak_bench(kind: str, d_buf, nbytes: int, iters: int, reps: int, d_sink, stream=None) -> float:
@@ -221,6 +224,9 @@ class Pi0:
 
     def pi0_set_graph_mode(self, enabled: bool):
         self._check(lib().pi0_set_graph_mode(self._ctx, 1 if enabled else 0))
+
+    def pi0_set_precision(self, precision: str):
+        self._check(lib().pi0_set_precision(self._ctx, PRECISIONS[precision]))
 
     def pi0_kernel_count(self, n_views: int, n_prompt: int) -> int:
         return int(lib().pi0_kernel_count(self._ctx, n_views, n_prompt))

@@ -133,7 +133,7 @@ void blob_layout(const pi0_config& c, const Dims& d, BlobLayout& b) {
 // ---- workspace layout (byte offsets) ----------------------------------------------------------------
 struct PW { size_t w; int n_pad, k_pad; size_t colsum, bias; };   // packed weight + optional vectors
 struct WsVis { PW qkv, o, up, down; };
-struct WsTr { PW qkv, o, gu, down; };
+struct WsTr { PW qkv, o, gu, down; size_t gu8 = 0, gu8s = 0, down8 = 0, down8s = 0; };   // *8 / *8s: MXFP8 copy and its scales (prefix only)
 struct WsLayout {
   PW patch; size_t pos;
   std::vector<WsVis> vis;
@@ -151,6 +151,8 @@ struct WsLayout {
   size_t lx, lx_b, lq, kcache, vcache, lattn, lmid;
   size_t stok, z, y, y_b, eq, ek, ev, eattn, eml, emid;
   size_t vstat, lstat, estat, estat_parts, pf_sink, vstat_parts, lstat_parts;
+  size_t lx8, lx8s, lmid8, lmid8s;   // MXFP8 copies of the prefix feed-forward inputs
+  bool mx_ok = false;                // the prefix feed-forward shapes fit the MXFP8 kernels (multiples of 256)
   size_t total;
   size_t kcache_layer, vcache_layer;   // bytes per layer
   size_t kcache_slot, vcache_slot;     // bytes per cache copy (two copies: double buffering for pi0_stream_frame)
@@ -203,6 +205,15 @@ void ws_layout(const pi0_config& c, const Dims& d, WsLayout& w) {
       w.llm[l].o = PW{0, 0, 0, 0, 0};
       w.llm[l].gu = w.llm[l].o;
       w.llm[l].down = w.llm[l].o;
+    }
+  }
+  w.mx_ok = d.E % 256 == 0 && d.F % 256 == 0;
+  if (w.mx_ok) {
+    for (int l = 0; l + 1 < d.Ll; l++) {
+      w.llm[l].gu8 = cur.take((size_t)2 * d.F * d.E);
+      w.llm[l].gu8s = cur.take((size_t)2 * d.F * d.E / 32);
+      w.llm[l].down8 = cur.take((size_t)d.E * d.F);
+      w.llm[l].down8s = cur.take((size_t)d.E * d.F / 32);
     }
   }
   w.exp.resize(d.Le);
@@ -272,6 +283,10 @@ void ws_layout(const pi0_config& c, const Dims& d, WsLayout& w) {
   w.emid = cur.take((size_t)64 * d.Fx * 2);
   w.vstat = cur.take((size_t)d.maxI * 2 * 4);
   w.lstat = cur.take((size_t)d.maxPc * 32 * 2 * 4);
+  w.lx8 = cur.take((size_t)d.maxPc * 32 * d.E);
+  w.lx8s = cur.take((size_t)d.maxPc * 32 * d.E / 32 + 256);
+  w.lmid8 = cur.take((size_t)d.maxPc * 32 * d.F);
+  w.lmid8s = cur.take((size_t)d.maxPc * 32 * d.F / 32 + 256);
   w.vstat_parts = cur.take((size_t)(d.Dv / 32) * d.maxI * 2 * 4);                     // [32-column tile][maxI][2]
   w.lstat_parts = cur.take((size_t)(d.E / 32) * d.maxPc * 32 * 2 * 4);                // [32-column tile][maxPc * 32][2]
   w.estat = cur.take((size_t)64 * 2 * 4);
@@ -285,9 +300,10 @@ void ws_layout(const pi0_config& c, const Dims& d, WsLayout& w) {
 }
 
 struct GraphKey {
-  int kind, n_views, n_prompt, slot_w, slot_r;
+  int kind, n_views, n_prompt, slot_w, slot_r, precision;
   bool operator<(const GraphKey& o) const {
     if (kind != o.kind) return kind < o.kind;
+    if (precision != o.precision) return precision < o.precision;
     if (n_views != o.n_views) return n_views < o.n_views;
     if (n_prompt != o.n_prompt) return n_prompt < o.n_prompt;
     if (slot_w != o.slot_w) return slot_w < o.slot_w;
@@ -330,6 +346,7 @@ struct pi0_ctx {
   bool loaded = false;
   bool attrs_set = false;
   bool graph_mode = true;
+  int precision = PI0_PRECISION_BF16;   // PI0_PRECISION_MXFP8_PREFIX_MLP: prefix gate||up / down on MXFP8 operands
   int cur_views = 0, cur_prompt = 0;   // shape of the valid prefill (0 views = none)
   int cur_slot = 0;                    // cache copy that holds it
   hipEvent_t ev_prefill[2] = {nullptr, nullptr};   // pi0_stream_frame: copy s was written / last read
@@ -569,7 +586,9 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
   const int tlqkv = T.lqkv >= 0 ? T.lqkv : (P <= 256 ? TILE_SMALL : P <= 512 ? TILE_MID : TILE_SQ128);
   const int tlo = T.lo >= 0 ? T.lo : (P <= 512 ? TILE_MID : TILE_SQ128);
   const int zlo = T.zlo > 0 ? T.zlo : (P <= 256 ? 4 : 2);
-  const bool fkl = T.fkl >= 0 ? T.fkl != 0 : P <= 256;
+  const bool mx = c->precision == PI0_PRECISION_MXFP8_PREFIX_MLP;
+  // reduced precision: the GeGLU epilogue takes whole-row statistics, so the O projection keeps its reduction launch
+  const bool fkl = mx ? false : (T.fkl >= 0 ? T.fkl != 0 : P <= 256);
   // gate||up: 128 blocks of 256 features per token tile.  A 256-token tile costs two 128-token tiles; take the
   // tile height whose block count needs fewer rounds on 256 compute units (ties: the taller tile).
   const int gu_cols = ceil_div(w.llm[0].gu.n_pad, 256);
@@ -617,6 +636,46 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
       gemm_splitk_resid(r, L.o, at<bf16>(c, w.lattn), d.H * 256, P, d.H * 256, zlo,
                         round_up(ceil_div(L.o.k_pad, zlo), 64), nullptr, at<float>(c, w.lx), at<bf16>(c, w.lx_b), d.E, tlo,
                         at<float>(c, w.lstat), at<float>(c, w.g_l2[l]));
+    if (mx) {
+      // B4 / B5 on MXFP8 operands: x * (1 + g) quantised per 32 columns, gate||up with the GeGLU product quantised
+      // in the epilogue, down as split-K partials into the usual reduction
+      r.cls = PI0_OP_LLM_GATEUP;
+      RUN(r, launch_quant_rows_mx(r.s, at<float>(c, w.lx), d.E, P, d.E, at<float>(c, w.g_l2[l]), c->ws + w.lx8, c->ws + w.lx8s));
+      MxGemmParams q;
+      memset(&q, 0, sizeof(q));
+      q.X8 = c->ws + w.lx8; q.XS = c->ws + w.lx8s; q.ldx = d.E; q.M = P;
+      q.W8 = c->ws + L.gu8; q.WS = c->ws + L.gu8s; q.n_pad = L.gu.n_pad; q.k_pad = L.gu.k_pad;
+      q.m_tiles = ceil_div(P, 128); q.k_per_split = L.gu.k_pad; q.k_true = d.E;
+      q.rowstat = at<float>(c, w.lstat);
+      q.out8 = c->ws + w.lmid8; q.out_scales = c->ws + w.lmid8s; q.ldo8 = d.F;
+      RUN(r, launch_gemm_mx(r.s, MX_EPI_GEGLU, q, 1));
+      r.cls = PI0_OP_LLM_DOWN;
+      const int zmx = std::max(1, std::min(16, 256 / std::max(1, ceil_div(P, 128) * ceil_div(L.down.n_pad, 256))));
+      const int kps = round_up(ceil_div(L.down.k_pad, zmx), 256);
+      const int zeff = ceil_div(L.down.k_pad, kps);
+      MxGemmParams u;
+      memset(&u, 0, sizeof(u));
+      u.X8 = c->ws + w.lmid8; u.XS = c->ws + w.lmid8s; u.ldx = d.F; u.M = P;
+      u.W8 = c->ws + L.down8; u.WS = c->ws + L.down8s; u.n_pad = L.down.n_pad; u.k_pad = L.down.k_pad;
+      u.m_tiles = ceil_div(P, 128); u.k_per_split = kps; u.k_true = d.F;
+      u.out_f32 = at<float>(c, w.part); u.ldo = L.down.n_pad;
+      RUN(r, launch_gemm_mx(r.s, MX_EPI_PARTIAL, u, zeff));
+      r.cls = PI0_OP_REDUCE;
+      ReduceParams rq;
+      rq.part = u.out_f32;
+      rq.Z = zeff; rq.M = P; rq.N = d.E; rq.ldp = L.down.n_pad;
+      rq.bias = nullptr;
+      rq.resid = at<float>(c, w.lx);
+      rq.resid_mod = 0;
+      rq.stat_out = at<float>(c, w.lstat);
+      rq.gain = at<float>(c, w.g_l1[l + 1]);
+      rq.out_f32 = at<float>(c, w.lx);
+      rq.out_bf16 = at<bf16>(c, w.lx_b);
+      rq.ldo = d.E; rq.ldo2 = d.E;
+      RUN(r, launch_splitk_reduce(r.s, rq));
+      if (taps) taps->put(r, at<float>(c, w.lx), (size_t)P * d.E);
+      continue;
+    }
     {  // B4: RMS -> gate||up with fused GELU gate
       GemmParams p = gp_base(c, L.gu, at<bf16>(c, w.lx_b), d.E, P, tlgu, d.E);
       p.rowstat = at<float>(c, w.lstat);
@@ -882,7 +941,8 @@ int execute(pi0_ctx* c, int kind, int n_views, int n_prompt, hipStream_t s, int 
     body(r);
     return r.ok() ? PI0_OK : fail_hip(c, r.err);
   }
-  GraphKey key{kind, n_views, n_prompt, kind == KIND_DENOISE ? 0 : slot_w, kind == KIND_PREFILL ? 0 : slot_r};
+  GraphKey key{kind, n_views, n_prompt, kind == KIND_DENOISE ? 0 : slot_w, kind == KIND_PREFILL ? 0 : slot_r,
+               kind == KIND_DENOISE ? 0 : c->precision};
   auto it = c->graphs.find(key);
   if (it == c->graphs.end()) {
     hipError_t e = hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal);
@@ -1022,6 +1082,13 @@ int pi0_set_graph_mode(pi0_ctx* c, int enabled) {
   return PI0_OK;
 }
 
+int pi0_set_precision(pi0_ctx* c, int precision) {
+  if (c == nullptr || (precision != PI0_PRECISION_BF16 && precision != PI0_PRECISION_MXFP8_PREFIX_MLP)) return PI0_EINVAL;
+  if (precision == PI0_PRECISION_MXFP8_PREFIX_MLP && !c->wl.mx_ok) return PI0_EINVAL;   // widths not multiples of 256
+  c->precision = precision;
+  return PI0_OK;
+}
+
 int pi0_last_hip_error(const pi0_ctx* c) { return c ? c->last_hip : 0; }
 
 int pi0_kernel_count(const pi0_ctx* c, int n_views, int n_prompt) {
@@ -1052,6 +1119,8 @@ int pi0_load_weights(pi0_ctx* c, const void* d_blob, size_t blob_bytes, void* d_
     e = gemm_init_attributes();
     if (e != hipSuccess) return fail_hip(c, e);
     e = attention_init_attributes();
+    if (e != hipSuccess) return fail_hip(c, e);
+    e = gemm_mx_init_attributes();
     if (e != hipSuccess) return fail_hip(c, e);
     c->attrs_set = true;
   }
@@ -1135,6 +1204,13 @@ int pi0_load_weights(pi0_ctx* c, const void* d_blob, size_t blob_bytes, void* d_
       if (ee != hipSuccess) return ee;
       ee = launch_pack_weights(s, src1(t.wd, M, W, KSCALE_NONE, 0), at<bf16>(c, wt[l].down.w), wt[l].down.n_pad, wt[l].down.k_pad);
       if (ee != hipSuccess) return ee;
+      if (wt[l].gu8 != 0) {   // MXFP8 copies for the reduced-precision mode (same row maps)
+        ee = launch_pack_weights_mx(s, g, c->ws + wt[l].gu8, c->ws + wt[l].gu8s, wt[l].gu.n_pad, wt[l].gu.k_pad);
+        if (ee != hipSuccess) return ee;
+        ee = launch_pack_weights_mx(s, src1(t.wd, M, W, KSCALE_NONE, 0), c->ws + wt[l].down8, c->ws + wt[l].down8s, wt[l].down.n_pad,
+                                    wt[l].down.k_pad);
+        if (ee != hipSuccess) return ee;
+      }
     }
     return hipSuccess;
   };

@@ -172,6 +172,58 @@ enum GemmTile {
   TILE_SQ128 = 9          // 128 tokens x 128 features per block (4 waves), 5 stages: the mid-size GEMMs at three views
 };
 
+// ------------------------------------------------------------------------------------------
+// MXFP8 (OCP Microscaling: FP8 E4M3 elements, one power-of-two E8M0 scale per 32 consecutive k) operands
+// of the reduced-precision prefix feed-forward GEMMs.  A 32-row x 64-k fragment is 2 KiB:
+//   [piece k/16 (4)][row (32)][16 bytes]
+// which is what mfma_scale_f32_32x32x64_f8f6f4 takes when lane (h, i) loads pieces h and h + 2 of row i
+// (two 16-byte loads, each contiguous over the wave).  Fragments are ordered [row block][k / 64].  The scale
+// of (row i, 32-k block b of a fragment) is supplied to the MFMA by lane b * 32 + i, so scales are stored as
+// one dword per lane for four consecutive fragments: [row block][k / 256][lane (64)][fragment % 4].
+// ------------------------------------------------------------------------------------------
+static __device__ __forceinline__ int mx_scale_code(float amax) {   // floor(log2 amax) - 8 + 127, clamped at 0
+  const int ef = (int)((__builtin_bit_cast(unsigned, amax) >> 23) & 0xffu);
+  return ef > 8 ? ef - 8 : 0;
+}
+static __device__ __forceinline__ float mx_inv_scale(int code) {    // 2^(127 - code), exact
+  return __builtin_bit_cast(float, (unsigned)(254 - code) << 23);
+}
+// two values scaled, saturated at +-448 (the conversion alone would give NaN beyond 464) and rounded to nearest
+// even E4M3: codes in bits 0..7 and 8..15
+static __device__ __forceinline__ unsigned mx_encode2(float a, float b, float inv) {
+  a = fminf(fmaxf(a * inv, -448.f), 448.f);
+  b = fminf(fmaxf(b * inv, -448.f), 448.f);
+  return (unsigned)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, 0, false) & 0xffffu;
+}
+
+struct MxGemmParams {
+  const unsigned char* X8;   // activations, MX fragment order, ldx (multiple of 256) k columns, rows padded to 32
+  const unsigned char* XS;   // their scales
+  int ldx;
+  int M;                     // valid rows
+  const unsigned char* W8;   // weights, MX fragment order [n / 32][k / 64]
+  const unsigned char* WS;   // their scales [n / 32][k / 256][64][4]
+  int n_pad, k_pad;          // n_pad multiple of 256, k_pad multiple of 256
+  int m_tiles;               // 128-row tiles
+  int k_per_split;           // multiple of 256
+  int k_true;                // divisor of the row statistics (GEGLU epilogue: RMS)
+  const float* rowstat;      // [rows][2] whole-row (sum, sum of squares) of the fp32 input rows
+  float* out_f32;            // partial epilogue: [split][M][ldo]
+  int ldo;
+  unsigned char* out8;       // GeGLU epilogue: gelu(gate) * up in MX fragment order, ldo8 (multiple of 256) columns
+  unsigned char* out_scales;
+  int ldo8;
+};
+enum MxEpi { MX_EPI_PARTIAL = 0, MX_EPI_GEGLU = 1 };
+// 128 x 256 block tiles; grid = (n_pad / 256 rounded up to 8) x m_tiles blocks, z_splits in y
+hipError_t launch_gemm_mx(hipStream_t s, int epi, const MxGemmParams& p, int z_splits);
+hipError_t gemm_mx_init_attributes();
+// weights -> MX fragments + scales (same row maps as launch_pack_weights)
+hipError_t launch_pack_weights_mx(hipStream_t s, const PackSrc& src, unsigned char* dst, unsigned char* scales, int n_pad, int k_pad);
+// rows of x * gain (fp32 [M][ld], K multiple of 256 columns used) -> MX fragments + scales; rows M .. round_up(M, 32) are zeroed
+hipError_t launch_quant_rows_mx(hipStream_t s, const float* x, int ld, int M, int K, const float* gain, unsigned char* out8,
+                                unsigned char* out_scales);
+
 hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmParams& p, int z_splits);
 int gemm_rows_per_tile(int tile);
 hipError_t gemm_init_attributes();

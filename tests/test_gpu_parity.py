@@ -20,6 +20,13 @@ pytestmark = pytest.mark.gpu
 
 ACTION_TOL = 2e-2
 COS_MIN = 0.999
+# MXFP8 mode against the MXFP8 oracle.  Both sides quantise by the same rule, but their inputs differ by the bf16
+# path's own error (~2^-9 relative), so a few percent of the elements land on neighbouring FP8 codes (one code =
+# 2^-4 .. 2^-3 relative): the per-layer agreement is looser than in bf16 (measured worst cosine 0.9995), the
+# actions stay within the bf16 bar (measured 6e-3 of their RMS).
+MX_ACTION_TOL = 2e-2
+MX_COS_MIN = 0.998
+MX_ROW_COS_MIN = 0.99
 
 
 def say(*a):
@@ -118,12 +125,13 @@ def split_taps(cfg, taps, n_views, n_prompt):
     return out
 
 
-def check_against_oracle(case, n_views, n_prompt, seed_shift=0, label="", action_tol=ACTION_TOL):
+def check_against_oracle(case, n_views, n_prompt, seed_shift=0, label="", action_tol=ACTION_TOL, mxfp8=False, cos_min=COS_MIN,
+                         row_cos_min=0.995):
     cfg = case.cfg
     img, st, nz, ids = case.inputs(n_views, n_prompt, seed_shift)
     say(f"[oracle] forward {label}")
     ref_taps = {}
-    ref = O.pi0_forward(cfg, case.tensors, img, st, nz, ids, dtype=np.float32, taps=ref_taps)
+    ref = O.pi0_forward(cfg, case.tensors, img, st, nz, ids, dtype=np.float32, taps=ref_taps, prefix_mlp_mxfp8=mxfp8)
     act, taps = case.debug_forward(img, st, nz, ids)
     got = split_taps(cfg, taps, n_views, n_prompt)
     assert np.isfinite(act).all() and np.isfinite(taps).all()
@@ -134,14 +142,14 @@ def check_against_oracle(case, n_views, n_prompt, seed_shift=0, label="", action
             for l in range(cfg.llm_layers):
                 c = cosine(g[l], r[l])
                 worst = min(worst, (c, f"{name}[{l}]"))
-                assert c >= COS_MIN, (label, name, l, c)
+                assert c >= cos_min, (label, name, l, c)
         else:
             c = cosine(g, r)
             worst = min(worst, (c, name))
-            assert c >= COS_MIN, (label, name, c)
+            assert c >= cos_min, (label, name, c)
             if name.startswith(("vis.h", "llm.x", "exp.y")):      # per-token cosine, catches single bad rows
                 rows = [cosine(g[i], r[i]) for i in range(g.shape[0])]
-                assert min(rows) >= 0.995, (label, name, int(np.argmin(rows)), min(rows))
+                assert min(rows) >= row_cos_min, (label, name, int(np.argmin(rows)), min(rows))
     rms = math.sqrt(float((ref.astype(np.float64) ** 2).mean()))
     err = float(np.abs(act - ref).max()) / rms
     say(f"[parity] {label}: actions max|d|/rms = {err:.3e}, worst cosine {worst[0]:.6f} at {worst[1]}")
@@ -303,6 +311,39 @@ def test_attainable_peak_microbenchmarks():
     assert torch.equal(buf.cpu(), host)
     with pytest.raises(binding.Pi0Error):
         binding.pi0_peak_bench("hbm_read", buf, n * 4 + 4, 0, 1, sink, stream)
+
+
+def test_mxfp8_prefix_mlp_against_mxfp8_oracle(reduced):
+    """Reduced-precision mode (prefix gate||up / down on MXFP8 operands) against the oracle that rounds the same
+    operands through MXFP8 by the format's definition; the mode really changes the numbers; switching back
+    restores the bf16 results bit for bit."""
+    img, st, nz, ids = reduced.inputs(1, 0)
+    before = reduced.infer(img, st, nz, ids)
+    reduced.m.pi0_set_precision("mxfp8_prefix_mlp")
+    try:
+        act1, ref1 = check_against_oracle(reduced, 1, 0, label="mxfp8 1 view", mxfp8=True, action_tol=MX_ACTION_TOL,
+                                          cos_min=MX_COS_MIN, row_cos_min=MX_ROW_COS_MIN)
+        check_against_oracle(reduced, 3, 48, label="mxfp8 3 views + 48 prompt", mxfp8=True, action_tol=MX_ACTION_TOL,
+                             cos_min=MX_COS_MIN, row_cos_min=MX_ROW_COS_MIN)
+        # graph replays of the mode equal its eager debug pass
+        np.testing.assert_array_equal(reduced.infer(img, st, nz, ids), act1)
+        np.testing.assert_array_equal(reduced.infer(img, st, nz, ids), act1)
+        # not the bf16 path under another name: the prefix hidden state is much closer to the MXFP8 oracle than to
+        # the plain one
+        taps_plain, taps_mx = {}, {}
+        O.pi0_forward(reduced.cfg, reduced.tensors, img, st, nz, ids, taps=taps_plain)
+        O.pi0_forward(reduced.cfg, reduced.tensors, img, st, nz, ids, taps=taps_mx, prefix_mlp_mxfp8=True)
+        _, taps = reduced.debug_forward(img, st, nz, ids)
+        x0 = split_taps(reduced.cfg, taps, 1, 0)["llm.x.0"]
+        d_mx, d_plain = 1 - cosine(x0, taps_mx["llm.x.0"]), 1 - cosine(x0, taps_plain["llm.x.0"])
+        say(f"[mxfp8] 1 - cos of llm.x.0: {d_mx:.2e} to the MXFP8 oracle, {d_plain:.2e} to the plain oracle")
+        assert d_mx < 0.5 * d_plain
+        assert np.abs(act1 - before).max() > 0
+    finally:
+        reduced.m.pi0_set_precision("bf16")
+    np.testing.assert_array_equal(reduced.infer(img, st, nz, ids), before)
+    with pytest.raises(binding.Pi0Error):
+        reduced.m._check(binding.lib().pi0_set_precision(reduced.m._ctx, 2))
 
 
 def test_two_stream_frames_match_sequential(reduced):

@@ -127,6 +127,28 @@ def test_sync_bench_rejects_bad_arguments(L):
     assert len(binding.OP_CLASSES) == 21 and binding.SYNC_MODES["fused"] == 4
 
 
+def test_set_precision_arguments(L):
+    cfg = synth.reduced_config(vocab=16)
+    c = binding.to_c_config(cfg)
+    ctx = ctypes.c_void_p()
+    assert L.pi0_create(ctypes.byref(c), ctypes.byref(ctx)) == 0
+    n_bf16 = L.pi0_kernel_count(ctx, 1, 0)
+    assert L.pi0_set_precision(None, 0) == binding.PI0_EINVAL
+    assert L.pi0_set_precision(ctx, 2) == binding.PI0_EINVAL and L.pi0_set_precision(ctx, -1) == binding.PI0_EINVAL
+    assert L.pi0_set_precision(ctx, 1) == binding.PI0_OK
+    # per prefix layer with a feed-forward block: one quantisation launch more, and the O projection keeps its reduction
+    assert L.pi0_kernel_count(ctx, 1, 0) == n_bf16 + 2 * (cfg.llm_layers - 1)
+    assert L.pi0_set_precision(ctx, 0) == binding.PI0_OK and L.pi0_kernel_count(ctx, 1, 0) == n_bf16
+    L.pi0_destroy(ctx)
+    # widths that are not multiples of 256 cannot use the MXFP8 kernels
+    import dataclasses
+    odd = binding.to_c_config(dataclasses.replace(cfg, llm_width=2048 + 64))
+    ctx2 = ctypes.c_void_p()
+    if L.pi0_create(ctypes.byref(odd), ctypes.byref(ctx2)) == 0:
+        assert L.pi0_set_precision(ctx2, 1) == binding.PI0_EINVAL
+        L.pi0_destroy(ctx2)
+
+
 def test_peak_bench_rejects_bad_arguments(L):
     fake = 0x10000
     out = ctypes.c_double(0.0)
