@@ -1181,6 +1181,23 @@ __global__ __launch_bounds__(512) void splitk_reduce_kernel(ReduceParams p) {
     a *= gv;
     const bf16x4 ob = {(bf16)a[0], (bf16)a[1], (bf16)a[2], (bf16)a[3]};
     *reinterpret_cast<bf16x4*>(p.out_bf16 + xf_index(ro, n, p.ldo2 >> 4)) = ob;
+    if (p.out8 != nullptr) {
+      // MXFP8 copy of the same gain-scaled values: 8 threads hold one 32-column scale block (N is a multiple of
+      // 256, so a block's threads are all inside the loop)
+      float amax = fmaxf(fmaxf(fabsf(a[0]), fabsf(a[1])), fmaxf(fabsf(a[2]), fabsf(a[3])));
+      amax = fmaxf(amax, __shfl_xor(amax, 1, 64));
+      amax = fmaxf(amax, __shfl_xor(amax, 2, 64));
+      amax = fmaxf(amax, __shfl_xor(amax, 4, 64));
+      const int code = mx_scale_code(amax);
+      const float inv = mx_inv_scale(code);
+      const unsigned word = mx_encode2(a[0], a[1], inv) | (mx_encode2(a[2], a[3], inv) << 16);
+      const int kc64 = p.N >> 6, kc = n >> 6;
+      unsigned char* frag = p.out8 + ((size_t)(ro >> 5) * kc64 + kc) * 2048;
+      *reinterpret_cast<unsigned*>(frag + ((size_t)((n & 63) >> 4) * 32 + (ro & 31)) * 16 + (n & 15)) = word;
+      if ((threadIdx.x & 7) == 0)
+        p.out8_scales[(((size_t)(ro >> 5) * (kc64 >> 2) + (kc >> 2)) * 64 + ((n & 63) >> 5) * 32 + (ro & 31)) * 4 + (kc & 3)] =
+            (unsigned char)code;
+    }
   }
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
@@ -1206,6 +1223,7 @@ __global__ __launch_bounds__(512) void splitk_reduce_kernel(ReduceParams p) {
 
 hipError_t launch_splitk_reduce(hipStream_t s, const ReduceParams& p) {
   if (p.N % 4 != 0 || p.ldp < p.N || p.ldo < p.N || p.ldo2 < p.N || p.ldo2 % 16 != 0 || p.M <= 0 || p.Z < 1) return hipErrorInvalidValue;
+  if (p.out8 != nullptr && (p.N % 256 != 0 || p.out8_scales == nullptr)) return hipErrorInvalidValue;
   hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)p.M), dim3(512), 0, s, p);
   return hipGetLastError();
 }

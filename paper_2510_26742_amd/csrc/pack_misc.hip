@@ -126,56 +126,6 @@ hipError_t launch_pack_weights_mx(hipStream_t st, const PackSrc& s, unsigned cha
   return hipGetLastError();
 }
 
-// MXFP8 copy of activation rows x * gain: one block per row, 8 consecutive columns per thread per pass, the 4
-// threads of a 32-column block share their maximum.  Rows beyond M (up to the next multiple of 32) are zeroed.
-__global__ __launch_bounds__(256) void quant_rows_mx_kernel(const float* x, int ld, int M, int K, const float* gain,
-                                                            unsigned char* out8, unsigned char* out_scales) {
-  const int m = blockIdx.x;
-  const int kc64 = K >> 6;
-  for (int k = threadIdx.x * 8; k < K; k += 2048) {
-    float v[8];
-    if (m < M) {
-      const f32x4 a = *reinterpret_cast<const f32x4*>(x + (size_t)m * ld + k);
-      const f32x4 b = *reinterpret_cast<const f32x4*>(x + (size_t)m * ld + k + 4);
-      const f32x4 ga = *reinterpret_cast<const f32x4*>(gain + k);
-      const f32x4 gb = *reinterpret_cast<const f32x4*>(gain + k + 4);
-#pragma unroll
-      for (int j = 0; j < 4; j++) {
-        v[j] = a[j] * ga[j];
-        v[4 + j] = b[j] * gb[j];
-      }
-    } else {
-#pragma unroll
-      for (int j = 0; j < 8; j++) v[j] = 0.f;
-    }
-    float amax = 0.f;
-#pragma unroll
-    for (int j = 0; j < 8; j++) amax = fmaxf(amax, fabsf(v[j]));
-    amax = fmaxf(amax, __shfl_xor(amax, 1, 64));
-    amax = fmaxf(amax, __shfl_xor(amax, 2, 64));
-    const int code = mx_scale_code(amax);
-    const float inv = mx_inv_scale(code);
-    const unsigned lo = mx_encode2(v[0], v[1], inv) | (mx_encode2(v[2], v[3], inv) << 16);
-    const unsigned hi = mx_encode2(v[4], v[5], inv) | (mx_encode2(v[6], v[7], inv) << 16);
-    const int kc = k >> 6, piece = (k & 63) >> 4, byte = k & 15;
-    unsigned char* frag = out8 + ((size_t)(m >> 5) * kc64 + kc) * 2048;
-    *reinterpret_cast<uint2*>(frag + ((size_t)piece * 32 + (m & 31)) * 16 + byte) = make_uint2(lo, hi);
-    if ((threadIdx.x & 3) == 0) {
-      const int b = (k & 63) >> 5;
-      out_scales[(((size_t)(m >> 5) * (kc64 >> 2) + (kc >> 2)) * 64 + b * 32 + (m & 31)) * 4 + (kc & 3)] = (unsigned char)code;
-    }
-  }
-}
-
-hipError_t launch_quant_rows_mx(hipStream_t st, const float* x, int ld, int M, int K, const float* gain, unsigned char* out8,
-                                unsigned char* out_scales) {
-  if (x == nullptr || gain == nullptr || out8 == nullptr || out_scales == nullptr || M <= 0 || K <= 0 || K % 256 != 0 || ld < K ||
-      ld % 4 != 0)
-    return hipErrorInvalidValue;
-  hipLaunchKernelGGL(quant_rows_mx_kernel, dim3((unsigned)((M + 31) / 32 * 32)), dim3(256), 0, st, x, ld, M, K, gain, out8, out_scales);
-  return hipGetLastError();
-}
-
 // colsum[n] = sum_k gain_k * W[k][col]   (the activations reach the GEMM already scaled by gain_k)
 // bias_out[n] = sum_k ln_bias[k] * W[k][col] + bias_src[which][col]
 struct FoldArgs {

@@ -430,7 +430,7 @@ GemmParams gp_base(pi0_ctx* c, const PW& pw, const bf16* X, int ldx, int M, int 
 void gemm_splitk_resid(Run& r, const PW& pw, const bf16* X, int ldx, int M, int k_true, int z, int k_per_split,
                        const float* bias, float* resid_io, bf16* shadow, int n_true, int tile, float* stat_out,
                        const float* gain, const float* resid_in = nullptr, int resid_mod = 0, bool no_resid = false,
-                       bool expert_scratch = false) {
+                       bool expert_scratch = false, unsigned char* out8 = nullptr, unsigned char* out8_scales = nullptr) {
   pi0_ctx* c = r.c;
   if (z > Z_MAX) z = Z_MAX;
   if ((long)k_per_split * z < pw.k_pad) k_per_split = round_up(ceil_div(pw.k_pad, z), 64);
@@ -452,6 +452,7 @@ void gemm_splitk_resid(Run& r, const PW& pw, const bf16* X, int ldx, int M, int 
   q.out_f32 = resid_io;
   q.out_bf16 = shadow;
   q.ldo = n_true; q.ldo2 = n_true;
+  q.out8 = out8; q.out8_scales = out8_scales;
   RUN(r, launch_splitk_reduce(r.s, q));
   r.cls = cls_gemm;
 }
@@ -635,12 +636,12 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
     else
       gemm_splitk_resid(r, L.o, at<bf16>(c, w.lattn), d.H * 256, P, d.H * 256, zlo,
                         round_up(ceil_div(L.o.k_pad, zlo), 64), nullptr, at<float>(c, w.lx), at<bf16>(c, w.lx_b), d.E, tlo,
-                        at<float>(c, w.lstat), at<float>(c, w.g_l2[l]));
+                        at<float>(c, w.lstat), at<float>(c, w.g_l2[l]), nullptr, 0, false, false,
+                        mx ? c->ws + w.lx8 : nullptr, mx ? c->ws + w.lx8s : nullptr);   // MXFP8 copy for gate||up
     if (mx) {
-      // B4 / B5 on MXFP8 operands: x * (1 + g) quantised per 32 columns, gate||up with the GeGLU product quantised
-      // in the epilogue, down as split-K partials into the usual reduction
+      // B4 / B5 on MXFP8 operands: x * (1 + g) was quantised per 32 columns by the O projection's reduction, gate||up
+      // quantises the GeGLU product in its epilogue, down goes as split-K partials into the usual reduction
       r.cls = PI0_OP_LLM_GATEUP;
-      RUN(r, launch_quant_rows_mx(r.s, at<float>(c, w.lx), d.E, P, d.E, at<float>(c, w.g_l2[l]), c->ws + w.lx8, c->ws + w.lx8s));
       MxGemmParams q;
       memset(&q, 0, sizeof(q));
       q.X8 = c->ws + w.lx8; q.XS = c->ws + w.lx8s; q.ldx = d.E; q.M = P;
@@ -672,6 +673,7 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
       rq.out_f32 = at<float>(c, w.lx);
       rq.out_bf16 = at<bf16>(c, w.lx_b);
       rq.ldo = d.E; rq.ldo2 = d.E;
+      rq.out8 = nullptr; rq.out8_scales = nullptr;
       RUN(r, launch_splitk_reduce(r.s, rq));
       if (taps) taps->put(r, at<float>(c, w.lx), (size_t)P * d.E);
       continue;

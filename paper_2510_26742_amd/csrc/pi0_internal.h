@@ -220,9 +220,6 @@ hipError_t launch_gemm_mx(hipStream_t s, int epi, const MxGemmParams& p, int z_s
 hipError_t gemm_mx_init_attributes();
 // weights -> MX fragments + scales (same row maps as launch_pack_weights)
 hipError_t launch_pack_weights_mx(hipStream_t s, const PackSrc& src, unsigned char* dst, unsigned char* scales, int n_pad, int k_pad);
-// rows of x * gain (fp32 [M][ld], K multiple of 256 columns used) -> MX fragments + scales; rows M .. round_up(M, 32) are zeroed
-hipError_t launch_quant_rows_mx(hipStream_t s, const float* x, int ld, int M, int K, const float* gain, unsigned char* out8,
-                                unsigned char* out_scales);
 
 hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmParams& p, int z_splits);
 int gemm_rows_per_tile(int tile);
@@ -241,6 +238,8 @@ struct ReduceParams {
   float* out_f32;
   bf16* out_bf16;     // XF layout with ldo2 padded columns
   int ldo, ldo2;
+  unsigned char* out8;         // optional MXFP8 copy of the gain-scaled row (N multiple of 256) in MX fragment order, or null
+  unsigned char* out8_scales;
 };
 hipError_t launch_splitk_reduce(hipStream_t s, const ReduceParams& p);
 // stat_out[m] = (sum, sum sq) of fp32 row m of x; out_xf = bf16(x * gain) in XF layout with k_pad columns
