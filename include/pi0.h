@@ -95,8 +95,9 @@ void pi0_destroy(pi0_ctx* ctx);
  */
 size_t pi0_weights_bytes(const pi0_config* cfg);
 
-/* Bytes of caller-provided device workspace needed (packed weights, tables, key/value cache,
- * activations).  0 if cfg is invalid. */
+/* Bytes of caller-provided device workspace needed (packed weights - with llm_width and llm_mlp multiples of 256
+ * also the MXFP8 copies of the prefix feed-forward weights, 1.5 bytes per such weight in all -, tables, both copies
+ * of the key/value cache, activations, split-K partial sums).  0 if cfg is invalid. */
 size_t pi0_workspace_bytes(const pi0_config* cfg);
 
 /*
