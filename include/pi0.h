@@ -95,9 +95,9 @@ void pi0_destroy(pi0_ctx* ctx);
  */
 size_t pi0_weights_bytes(const pi0_config* cfg);
 
-/* Bytes of caller-provided device workspace needed (packed weights - with llm_width and llm_mlp multiples of 256
- * also the MXFP8 copies of the prefix feed-forward weights, 1.5 bytes per such weight in all -, tables, both copies
- * of the key/value cache, activations, split-K partial sums).  0 if cfg is invalid. */
+/* Bytes of caller-provided device workspace needed: packed bf16 weights (and, if llm_width and llm_mlp are
+ * multiples of 256, an MXFP8 copy of the prefix feed-forward weights, about 1.03 bytes per weight), tables, both
+ * copies of the key/value cache, activations, split-K partial sums.  0 if cfg is invalid. */
 size_t pi0_workspace_bytes(const pi0_config* cfg);
 
 /*
