@@ -309,12 +309,24 @@ __global__ __launch_bounds__(256) void state_token_kernel(const float* state, in
                                                           float* out) {
   const int n = blockIdx.x * 256 + threadIdx.x;
   if (n >= X) return;
+  // all (at most 32) loads issued together (clamped, unconditional), added in index order
+  float wv[32], sv[32];
+#pragma unroll
+  for (int j = 0; j < 32; j++) {
+    const int jj = min(j, sd - 1);
+    wv[j] = ws[(size_t)jj * X + n];
+    sv[j] = state[jj];
+  }
   float acc = bs[n];
-  for (int j = 0; j < sd; j++) acc += state[j] * ws[(size_t)j * X + n];
+#pragma unroll
+  for (int j = 0; j < 32; j++) {
+    if (j < sd) acc += sv[j] * wv[j];
+  }
   out[n] = acc;
 }
 hipError_t launch_state_token(hipStream_t st, const float* state, int state_dim, const float* ws, const float* bs, int X,
                               float* out) {
+  if (state_dim < 1 || state_dim > 32) return hipErrorInvalidValue;
   hipLaunchKernelGGL(state_token_kernel, dim3((X + 255) / 256), dim3(256), 0, st, state, state_dim, ws, bs, X, out);
   return hipGetLastError();
 }
