@@ -39,8 +39,11 @@ __device__ __forceinline__ float gelu_tanh_mx(float x) {
   return x * __builtin_amdgcn_rcpf(1.0f + exp2f(-2.885390081777927f * u));
 }
 
-template <int EPI>
-__global__ __launch_bounds__(64 * MX_WN) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_mx_kernel(MxGemmParams p) {
+// OCC = blocks per CU the register budget is cut for: with more blocks than CUs, two resident blocks hide each
+// other's waits (measured -16 % at 512 / 768 tokens, at the price of a few spilled registers); with one block per
+// CU the full register file is the better use (+20 % the other way at 256 tokens).
+template <int EPI, int OCC>
+__global__ __launch_bounds__(64 * MX_WN) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) void gemm_mx_kernel(MxGemmParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char xs[];     // [2][MB * 2][1024]
   const int t = threadIdx.x;
   const int lane = t & 63;
@@ -233,10 +236,13 @@ __global__ __launch_bounds__(64 * MX_WN) __attribute__((amdgpu_waves_per_eu(1, 1
 }  // namespace
 
 hipError_t gemm_mx_init_attributes() {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mx_kernel<MX_EPI_PARTIAL>),
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mx_kernel<MX_EPI_PARTIAL, 1>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, MX_SMEM);
   if (e != hipSuccess) return e;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mx_kernel<MX_EPI_GEGLU>),
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mx_kernel<MX_EPI_GEGLU, 1>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, MX_SMEM);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mx_kernel<MX_EPI_GEGLU, 2>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, MX_SMEM);
 }
 
@@ -257,7 +263,8 @@ hipError_t launch_gemm_mx(hipStream_t s, int epi, const MxGemmParams& p, int z_s
   }
   const int nblocks_n = (p.n_pad >> 5) / (MX_WN * MX_NT);
   const dim3 grid(8 * ((nblocks_n + 7) / 8) * p.m_tiles, z_splits);
-  if (epi == MX_EPI_PARTIAL) gemm_mx_kernel<MX_EPI_PARTIAL><<<grid, dim3(64 * MX_WN), MX_SMEM, s>>>(p);
-  else gemm_mx_kernel<MX_EPI_GEGLU><<<grid, dim3(64 * MX_WN), MX_SMEM, s>>>(p);
+  if (epi == MX_EPI_PARTIAL) gemm_mx_kernel<MX_EPI_PARTIAL, 1><<<grid, dim3(64 * MX_WN), MX_SMEM, s>>>(p);
+  else if (nblocks_n * p.m_tiles > 256) gemm_mx_kernel<MX_EPI_GEGLU, 2><<<grid, dim3(64 * MX_WN), MX_SMEM, s>>>(p);
+  else gemm_mx_kernel<MX_EPI_GEGLU, 1><<<grid, dim3(64 * MX_WN), MX_SMEM, s>>>(p);
   return hipGetLastError();
 }
