@@ -334,9 +334,11 @@ hipError_t launch_state_token(hipStream_t st, const float* state, int state_dim,
 // Table 2 row 63x32x1024 (bias, silu) with the folded weights; also re-seeds suffix row 0 of the
 // expert's residual stream with the state token at the start of every Euler step.
 // grid.y = chunk + 1: row r < chunk -> z[r]; row chunk -> state token copy and zero z[chunk].
+// The state row also gets its gain-scaled bf16 copy and, per 32 columns, its (sum, sum of squares) in
+// stat_parts[tile][64 rows][2] (row 0), the form the first QKV GEMM of the step reads.
 __global__ __launch_bounds__(256) void action_embed_kernel(const float* x, int chunk, int A, const float* wfold,
                                                            const float* bias_k, int X, bf16* z, const float* state_tok,
-                                                           float* y_f32, bf16* y_bf16) {
+                                                           float* y_f32, bf16* y_bf16, const float* gain, float* stat_parts) {
   const int n = blockIdx.x * 256 + threadIdx.x;
   const int r = blockIdx.y;
   if (n >= X) return;
@@ -362,13 +364,25 @@ __global__ __launch_bounds__(256) void action_embed_kernel(const float* x, int c
     z[xf_index(chunk, n, X >> 4)] = (bf16)0.0f;
     const float s = state_tok[n];
     y_f32[n] = s;
-    y_bf16[xf_index(0, n, X >> 4)] = (bf16)s;
+    y_bf16[xf_index(0, n, X >> 4)] = (bf16)(s * gain[n]);
+    float a = s, b = s * s;     // X is a multiple of 32: a 32-lane group is here completely or not at all
+#pragma unroll
+    for (int off = 1; off < 32; off <<= 1) {
+      a += __shfl_xor(a, off, 64);
+      b += __shfl_xor(b, off, 64);
+    }
+    if ((threadIdx.x & 31) == 0) {
+      stat_parts[(size_t)(n >> 5) * 128] = a;
+      stat_parts[(size_t)(n >> 5) * 128 + 1] = b;
+    }
   }
 }
 hipError_t launch_action_embed(hipStream_t st, const float* x, int chunk, int action_dim, const float* wfold,
-                               const float* bias_k, int X, bf16* z, const float* state_tok, float* y_f32, bf16* y_bf16) {
+                               const float* bias_k, int X, bf16* z, const float* state_tok, float* y_f32, bf16* y_bf16,
+                               const float* gain, float* stat_parts) {
+  if (X % 32 != 0 || gain == nullptr || stat_parts == nullptr) return hipErrorInvalidValue;
   hipLaunchKernelGGL(action_embed_kernel, dim3((X + 255) / 256, chunk + 1), dim3(256), 0, st, x, chunk, action_dim, wfold,
-                     bias_k, X, z, state_tok, y_f32, y_bf16);
+                     bias_k, X, z, state_tok, y_f32, y_bf16, gain, stat_parts);
   return hipGetLastError();
 }
 

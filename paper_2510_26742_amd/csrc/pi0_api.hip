@@ -782,20 +782,21 @@ void run_denoise(Run& r, int P, Taps* taps) {
     // C1: folded action/time embedding, SiLU; suffix row 0 <- state token
     r.cls = PI0_OP_EXP_EMBED;
     RUN(r, launch_action_embed(r.s, xa, chunk, d.A, at<float>(c, w.wfold), at<float>(c, w.bias_tab) + (size_t)k * d.X, d.X,
-                               at<bf16>(c, w.z), at<float>(c, w.stok), at<float>(c, w.y), at<bf16>(c, w.y_b)));
-    {  // C2: second linear of the action/time MLP -> suffix rows 1..chunk
+                               at<bf16>(c, w.z), at<float>(c, w.stok), at<float>(c, w.y), at<bf16>(c, w.y_b),
+                               at<float>(c, w.g_e1[0]), at<float>(c, w.estat_parts)));
+    {  // C2: second linear of the action/time MLP -> suffix rows 1..chunk; gain-scaled copy and per-tile row
+       // statistics for the first layer's QKV come out of the same epilogue (row 0: from the kernel above)
       GemmParams p = gp_base(c, w.tout, at<bf16>(c, w.z), d.X, chunk, TILE_SKINNY, d.X);
       p.bias = at<float>(c, w.tout.bias);
       p.out_f32 = at<float>(c, w.y);
       p.out_bf16 = at<bf16>(c, w.y_b);
       p.ldo = d.X; p.ldo2 = d.X; p.n_valid = d.X; p.row_offset = 1;
+      p.gain = at<float>(c, w.g_e1[0]);
+      p.stat_out = at<float>(c, w.estat_parts);
       RUN_GEMM(r, TILE_SKINNY, PRO_NONE, EPI_RESID, p, 1);
     }
-    r.cls = PI0_OP_MISC;
-    RUN(r, launch_row_stats(r.s, at<float>(c, w.y), d.X, 64, d.X, d.X, at<float>(c, w.g_e1[0]), at<bf16>(c, w.y_b),
-                            at<float>(c, w.estat)));
-    stat_ptr = at<float>(c, w.estat);
-    stat_parts = 1;
+    stat_ptr = at<float>(c, w.estat_parts);
+    stat_parts = w.tout.n_pad / 32;
     const bool tap_this = taps && (k == 0 || k == d.steps - 1);
     for (int l = 0; l < d.Le; l++) {
       const WsTr& L = w.exp[l];

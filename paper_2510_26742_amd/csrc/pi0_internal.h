@@ -308,7 +308,8 @@ hipError_t launch_state_token(hipStream_t s, const float* state, int state_dim, 
                               float* out);
 // z = silu(x @ W_fold + bias_k) -> bf16 [64][X] (row chunk.. zero);  Y row 0 = state token
 hipError_t launch_action_embed(hipStream_t s, const float* x, int chunk, int action_dim, const float* wfold,
-                               const float* bias_k, int X, bf16* z, const float* state_tok, float* y_f32, bf16* y_bf16);
+                               const float* bias_k, int X, bf16* z, const float* state_tok, float* y_f32, bf16* y_bf16,
+                               const float* gain, float* stat_parts);
 hipError_t launch_copy_f32(hipStream_t s, const float* src, float* dst, size_t n);
 // natural-order dump of fragment-ordered caches (debug taps)
 hipError_t launch_unpack_kv(hipStream_t s, const bf16* kfrag, const bf16* vfrag, int P, float* k_out, float* v_out);
