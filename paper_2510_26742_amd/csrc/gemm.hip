@@ -238,10 +238,10 @@ __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16&
 }
 
 // Tall GEMM (256 .. 816 tokens): the vision tower and the prefix transformer.
-// Block = WN waves, each owning one 32-feature tile, all sharing one MB*32-token activation tile
-// that is staged through LDS in chunks of 64 k (4 fragments per 32-token block, copied 1 KiB at a
-// time from the XF layout, so global reads, LDS writes and LDS reads are all contiguous).  A
-// "stage" is the block's activation chunk plus each wave's 4 weight fragments.  D stages are kept
+// Block = WN waves, each owning NT adjacent 32-feature tiles, all sharing one MB*32-token activation
+// tile that is staged through LDS in chunks of 64 k (4 fragments per 32-token block, copied 1 KiB at
+// a time from the XF layout, so global reads, LDS writes and LDS reads are all contiguous).  A
+// "stage" is the block's activation chunk plus each wave's 4 * NT weight fragments.  D stages are kept
 // in flight in registers and every stage is issued the same distance ahead of its use:
 // vector-memory loads complete in issue order, so a weight prefetch issued far ahead does not
 // help if the activation load behind which it queues is only one chunk ahead.
