@@ -273,6 +273,17 @@ int pi0_peak_bench(int kind, const void* d_buf, size_t bytes, int iters, int rep
 enum pi0_precision { PI0_PRECISION_BF16 = 0, PI0_PRECISION_MXFP8_PREFIX_MLP = 1 };
 int pi0_set_precision(pi0_ctx* ctx, int precision);
 
+/*
+ * Clock sample (no ctx needed): enqueues one single-lane kernel on hip_stream that writes d_out[0] = the shader
+ * cycle counter and d_out[1] = the constant 100 MHz counter (d_out: device, 2 x int64, 8-byte aligned).  Two
+ * samples around a piece of work on the same stream give the shader clock the device actually ran at:
+ * (cycles_1 - cycles_0) / ((ticks_1 - ticks_0) * 10 ns) - the figure the published peaks (quoted at 2.4 GHz)
+ * have to be scaled by.  The cycle counters of the chip's dies are not aligned with each other and the two sample
+ * kernels may run on different dies, so the interval has to be long (>= 100 ms) for the offset not to matter.
+ * Errors: EINVAL, EHIP.
+ */
+int pi0_clock_sample(long long* d_out, void* hip_stream);
+
 /* Graph replay on (1, default) or off (0: every call launches kernels eagerly). */
 int pi0_set_graph_mode(pi0_ctx* ctx, int enabled);
 

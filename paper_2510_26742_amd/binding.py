@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpi0_hip.so")
 
 EXPORTS = ["pi0_create", "pi0_destroy", "pi0_weights_bytes", "pi0_workspace_bytes", "pi0_load_weights",
-           "pi0_prefill", "pi0_denoise", "pi0_infer", "pi0_debug_taps_elems", "pi0_debug_forward", "pi0_debug_profile", "pi0_sync_bench", "pi0_peak_bench", "pi0_stream_frame",
+           "pi0_prefill", "pi0_denoise", "pi0_infer", "pi0_debug_taps_elems", "pi0_debug_forward", "pi0_debug_profile", "pi0_sync_bench", "pi0_peak_bench", "pi0_clock_sample", "pi0_stream_frame",
            "pi0_set_graph_mode", "pi0_set_precision", "pi0_kernel_count", "pi0_strerror", "pi0_last_hip_error"]
 
 # enum pi0_op_class, in order
@@ -79,6 +79,8 @@ def lib() -> ctypes.CDLL:
         L.pi0_sync_bench.restype = i32
         L.pi0_peak_bench.argtypes = [i32, vp, sz, i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.pi0_peak_bench.restype = i32
+        L.pi0_clock_sample.argtypes = [vp, vp]
+        L.pi0_clock_sample.restype = i32
         L.pi0_set_graph_mode.argtypes = [vp, i32]
         L.pi0_set_graph_mode.restype = i32
         L.pi0_set_precision.argtypes = [vp, i32]
@@ -132,6 +134,20 @@ def pi0_sync_bench(mode: str, n_ops: int, reps: int, d_x, d_b, d_state, stream=N
     if rc != PI0_OK:
         raise Pi0Error(rc)
     return float(ms.value)
+
+
+def pi0_clock_sample(d_out, stream=None):
+    """Enqueue a sample of (shader cycle counter, 100 MHz counter) into the int64[2] device tensor d_out."""
+    s = None if stream is None else int(stream.cuda_stream)
+    rc = lib().pi0_clock_sample(_ptr(d_out), s)
+    if rc != PI0_OK:
+        raise Pi0Error(rc)
+
+
+def shader_clock_ghz(sample0, sample1) -> float:
+    """Average shader clock between two pi0_clock_sample results (host tensors / sequences of 2 ints)."""
+    cyc, ticks = int(sample1[0]) - int(sample0[0]), int(sample1[1]) - int(sample0[1])
+    return cyc / (ticks * 10.0) if ticks > 0 else float("nan")
 
 
 PEAK_KINDS = {"hbm_read": 0, "mfma_bf16": 1}

@@ -61,7 +61,20 @@ __global__ __launch_bounds__(PEAK_THREADS) void peak_mfma_kernel(int iters, unsi
   if (__builtin_bit_cast(unsigned, s) == NEVER) sink[0] = NEVER;
 }
 
+// the shader's cycle counter (moves with the clock the power management currently grants) and the constant
+// 100 MHz counter, read back to back by one lane
+__global__ void clock_pair_kernel(long long* out) {
+  out[0] = (long long)__builtin_amdgcn_s_memtime();
+  out[1] = (long long)wall_clock64();
+}
+
 }  // namespace
+
+extern "C" int pi0_clock_sample(long long* d_out, void* hip_stream) {
+  if (d_out == nullptr || (reinterpret_cast<uintptr_t>(d_out) & 7) != 0) return PI0_EINVAL;
+  clock_pair_kernel<<<1, 1, 0, reinterpret_cast<hipStream_t>(hip_stream)>>>(d_out);
+  return hipGetLastError() == hipSuccess ? PI0_OK : PI0_EHIP;
+}
 
 extern "C" int pi0_peak_bench(int kind, const void* d_buf, size_t bytes, int iters, int reps, unsigned* d_sink,
                               double* h_result, void* hip_stream) {

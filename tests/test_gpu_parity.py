@@ -311,6 +311,17 @@ def test_attainable_peak_microbenchmarks():
     assert torch.equal(buf.cpu(), host)
     with pytest.raises(binding.Pi0Error):
         binding.pi0_peak_bench("hbm_read", buf, n * 4 + 4, 0, 1, sink, stream)
+    # clock samples around ~0.2 s of streaming reads: a plausible shader clock
+    c0 = torch.zeros(2, dtype=torch.int64, device=dev)
+    c1 = torch.zeros(2, dtype=torch.int64, device=dev)
+    binding.pi0_clock_sample(c0, stream)
+    binding.pi0_peak_bench("hbm_read", buf, n * 4, 0, 1000, sink, stream)
+    binding.pi0_peak_bench("hbm_read", buf, n * 4, 0, 1000, sink, stream)
+    binding.pi0_clock_sample(c1, stream)
+    stream.synchronize()
+    ghz = binding.shader_clock_ghz(c0.cpu().tolist(), c1.cpu().tolist())
+    say(f"[peak] shader clock {ghz:.3f} GHz")
+    assert 0.5 < ghz < 3.0
 
 
 def test_mxfp8_prefix_mlp_against_mxfp8_oracle(reduced):

@@ -166,6 +166,12 @@ def test_peak_bench_rejects_bad_arguments(L):
     assert binding.PEAK_KINDS == {"hbm_read": 0, "mfma_bf16": 1}
 
 
+def test_clock_sample_rejects_bad_arguments(L):
+    assert L.pi0_clock_sample(None, None) == binding.PI0_EINVAL
+    assert L.pi0_clock_sample(0x10004, None) == binding.PI0_EINVAL        # not 8-byte aligned
+    assert binding.shader_clock_ghz([100, 10], [2500, 110]) == 2.4        # 2400 cycles in 100 ticks of 10 ns
+
+
 def test_kernel_count_and_taps(L):
     cfg = synth.full_config()
     c = binding.to_c_config(cfg)
