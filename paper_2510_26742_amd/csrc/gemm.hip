@@ -823,8 +823,13 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny16_kernel(GemmParams
   }
   const int m = mt16 * 16 + li;
   // X given as attention shares over disjoint key ranges (k = 8 heads x 256, so wave w holds exactly
-  // head w): merge them while they arrive.  Share z carries its normalised output and (max, sum)
-  // of its exponentials; the weights are c_z = l_z exp(m_z - max m) / sum over shares.
+  // head w).  Share z carries its normalised output and (max, sum) of its exponentials; the merged
+  // row is sum_z c_z x_z with c_z = l_z exp(m_z - max m) / sum over shares.  The product is linear
+  // in x and a lane of the accumulator belongs to one token, so every share is multiplied on its
+  // own and the 4 accumulator values per lane are combined with the lane's c_z: no element-wise
+  // merge of the operand fragments.
+  f32x4 acc_merged = {0.f, 0.f, 0.f, 0.f};
+  const bool merge = NS == 8 && p.xsplits > 1;
   if (NS == 8 && p.xsplits > 1) {
     const int nz = p.xsplits;             // 2 .. 4, uniform
     bf16x8 xo[3][NS];
@@ -856,21 +861,17 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny16_kernel(GemmParams
 #pragma unroll
     for (int z = 0; z < 4; z++) c[z] *= rden;
 #pragma unroll
-    for (int j = 0; j < NS; j++) {
-      float a[8];
+    for (int z = 0; z < 4; z++) {
+      if (z < nz) {
+        f32x4 az = {0.f, 0.f, 0.f, 0.f}, az1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int e = 0; e < 8; e++) a[e] = c[0] * (float)xf[j][e];
-#pragma unroll
-      for (int z = 1; z < 4; z++) {
-        if (z < nz) {
-#pragma unroll
-          for (int e = 0; e < 8; e++) a[e] += c[z] * (float)xo[z - 1][j][e];
+        for (int j = 0; j < NS; j += 2) {
+          az = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[j], z == 0 ? xf[j] : xo[z == 0 ? 0 : z - 1][j], az, 0, 0, 0);
+          az1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[j + 1], z == 0 ? xf[j + 1] : xo[z == 0 ? 0 : z - 1][j + 1], az1, 0, 0, 0);
         }
-      }
-      bf16x8 o;
 #pragma unroll
-      for (int e = 0; e < 8; e++) o[e] = (bf16)a[e];
-      xf[j] = o;
+        for (int r = 0; r < 4; r++) acc_merged[r] += c[z] * (az[r] + az1[r]);
+      }
     }
   }
   // operands of the epilogue (wave 0), behind the operand loads
@@ -883,13 +884,17 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny16_kernel(GemmParams
     if (p.bias != nullptr) bv = *reinterpret_cast<const f32x4*>(p.bias + n4);
   }
   f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+  if (!merge) {
 #pragma unroll
-  for (int j = 0; j < NS; j += 2) {
-    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[j], xf[j], acc0, 0, 0, 0);
-    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[j + 1], xf[j + 1], acc1, 0, 0, 0);
+    for (int j = 0; j < NS; j += 2) {
+      acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[j], xf[j], acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[j + 1], xf[j + 1], acc1, 0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; r++) acc0[r] += acc1[r];
+  } else {
+    acc0 = acc_merged;
   }
-#pragma unroll
-  for (int r = 0; r < 4; r++) acc0[r] += acc1[r];
   *reinterpret_cast<f32x4*>(&red[w][lane][0]) = acc0;
   __syncthreads();
   if (w != 0) return;
