@@ -46,6 +46,10 @@ def main() -> int:
                     help="for hardware-counter runs: one 1 GiB device-to-device copy (calibration point) and ONE "
                          "eager pass (no graph, no timing), then exit")
     args = ap.parse_args()
+    if args.counters_pass:
+        # counter collection runs one kernel at a time, so the expert's read-ahead kernel (a second stream beside
+        # the compute launches) would only wait out its bound: this pass uses the warm-up blocks inside the launches
+        os.environ["PI0_TUNE"] = ",".join(x for x in (os.environ.get("PI0_TUNE", ""), "ras=0") if x)
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (batch-1 latency path, no sharding); use --gpus 1",
               file=sys.stderr)

@@ -18,7 +18,11 @@
  *    The caller owns all device memory: weight blob, workspace, inputs, outputs, and the stream.
  *    The library allocates no device memory; it owns only the host-side pi0_ctx.
  *  - Every call only enqueues work on `hip_stream` (a hipStream_t, may be NULL for the default
- *    stream); results are valid after the caller synchronises that stream.
+ *    stream); results are valid after the caller synchronises that stream.  One exception that the
+ *    caller never sees: pi0_denoise / pi0_infer fork one read-ahead kernel (it only loads the
+ *    expert's weights ahead of the compute launches, Section 5.2) onto a stream the ctx owns and
+ *    join it back into `hip_stream` before the call's last launch, with events, also inside the
+ *    captured graph; work enqueued on `hip_stream` after the call is ordered after both.
  *  - Return value: 0 on success, a negative PI0_E* code otherwise.  Argument checks happen before
  *    any GPU call, so error paths touch no GPU state.  Nothing throws or aborts across the ABI.
  *  - Calls on one ctx must not overlap in time (one workspace, one set of activations); the only
@@ -287,7 +291,8 @@ int pi0_clock_sample(long long* d_out, void* hip_stream);
 /* Graph replay on (1, default) or off (0: every call launches kernels eagerly). */
 int pi0_set_graph_mode(pi0_ctx* ctx, int enabled);
 
-/* Number of kernel launches one pi0_infer issues for the given shape (0 on bad arguments). */
+/* Number of kernel launches one pi0_infer issues on hip_stream for the given shape (0 on bad
+ * arguments); the read-ahead kernel on the ctx's own stream is not counted. */
 int pi0_kernel_count(const pi0_ctx* ctx, int n_views, int n_prompt);
 
 /* Static, never-NULL description of an error code. */

@@ -524,6 +524,8 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
     if (blockIdx.z == 0) prefetch_role(p.pf, (int)blockIdx.x - p.n_tiles);
     return;
   }
+  if (p.progress != nullptr && t == 0 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0)
+    __hip_atomic_store(p.progress, p.progress_value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   const int nt = blockIdx.x;
   const int k_pad = p.W.k_pad;
   const int kbeg = blockIdx.y * p.k_per_split;

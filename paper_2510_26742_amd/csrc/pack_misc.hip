@@ -306,8 +306,10 @@ hipError_t launch_embed_prompt(hipStream_t st, const int32_t* ids, int n, const 
 
 // state token: out[n] = sum_j state[j] * ws[j][n] + bs[n]   (Table 2 row 1x32x1024)
 __global__ __launch_bounds__(256) void state_token_kernel(const float* state, int sd, const float* ws, const float* bs, int X,
-                                                          float* out) {
+                                                          float* out, int* progress) {
   const int n = blockIdx.x * 256 + threadIdx.x;
+  // first launch of the action expert: no layer has started yet (read by the read-ahead kernel)
+  if (n == 0 && progress != nullptr) __hip_atomic_store(progress, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   if (n >= X) return;
   // all (at most 32) loads issued together (clamped, unconditional), added in index order
   float wv[32], sv[32];
@@ -325,9 +327,88 @@ __global__ __launch_bounds__(256) void state_token_kernel(const float* state, in
   out[n] = acc;
 }
 hipError_t launch_state_token(hipStream_t st, const float* state, int state_dim, const float* ws, const float* bs, int X,
-                              float* out) {
+                              float* out, int* progress) {
   if (state_dim < 1 || state_dim > 32) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(state_token_kernel, dim3((X + 255) / 256), dim3(256), 0, st, state, state_dim, ws, bs, X, out);
+  hipLaunchKernelGGL(state_token_kernel, dim3((X + 255) / 256), dim3(256), 0, st, state, state_dim, ws, bs, X, out, progress);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Read-ahead kernel of the action expert (the prefetch-across-synchronisation-points idea of
+// Section 5.2, as a kernel of its own beside the compute launches instead of extra blocks inside
+// them).  It runs on a second stream for the whole denoise loop and reads the weights and cache
+// slices of layer-step i (i = step * layers + layer) once the compute stream has started
+// layer-step i - lead + 1, which it learns from a counter the QKV launch of every layer stores.
+// The loads only pull the bytes into the memory-side cache; their values are xor-folded into a
+// word compared with a constant so they cannot be elided, and no result depends on them.
+// Every wait is bounded: a block that does not see the counter move within `wait_ticks` of the
+// 100 MHz wall clock stops reading ahead altogether and exits (so a machine that runs the two
+// streams one after the other only loses that one wait).
+// ------------------------------------------------------------------------------------------------
+// Register budget: the expert's compute launches keep two waves of up to 224 registers on every SIMD, so a
+// wave of this kernel only fits beside them with at most 64 (asked for through the occupancy attribute).
+template <int RA_DEPTH>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8, 8))) void read_ahead_kernel(ReadAheadParams p) {
+  __shared__ int s_go;
+  const unsigned tid = blockIdx.x * blockDim.x + threadIdx.x;
+  const unsigned nth = gridDim.x * blockDim.x;
+  unsigned acc = 0;
+  const int total = p.steps * p.layers;
+  for (int i = 0; i < total; i++) {
+    const int need = i + 1 - p.lead;
+    if (need > 0) {
+      if (threadIdx.x == 0) {
+        const long long t0 = wall_clock64();
+        int go = 1;
+        while (__hip_atomic_load(p.progress, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < need) {
+          if (wall_clock64() - t0 > p.wait_ticks) {
+            go = 0;
+            break;
+          }
+          __builtin_amdgcn_s_sleep(16);
+        }
+        s_go = go;
+      }
+      __syncthreads();
+      const int go = s_go;
+      __syncthreads();
+      if (!go) break;
+    }
+    const int layer = i % p.layers;
+#pragma unroll
+    for (int r = 0; r < RA_REGIONS; r++) {
+      // uniform base + 32-bit byte offset per lane (a region is far below 4 GiB); RA_DEPTH loads in flight
+      // per lane, offsets past the end clamped to the last word (a repeated load, no branch)
+      const unsigned char* base = p.base[r] + (size_t)layer * p.layer_stride[r];
+      const unsigned end = p.n16[r] * 16u;
+      if (end == 0u) continue;
+      for (unsigned o0 = tid * 16u; o0 < end; o0 += RA_DEPTH * nth * 16u) {
+        uint4 v[RA_DEPTH];
+#pragma unroll
+        for (int k = 0; k < RA_DEPTH; k++)
+          v[k] = *reinterpret_cast<const uint4*>(base + min(o0 + (unsigned)k * nth * 16u, end - 16u));
+#pragma unroll
+        for (int k = 0; k < RA_DEPTH; k++) acc ^= v[k].x ^ v[k].y ^ v[k].z ^ v[k].w;
+      }
+    }
+  }
+  if (acc == 0x9e3779b9u) p.sink[tid & 1023] = acc;
+}
+hipError_t launch_read_ahead(hipStream_t st, const ReadAheadParams& p, int blocks, int threads, int depth) {
+  if (blocks < 1 || blocks > 4096 || (threads != 64 && threads != 128 && threads != 256) || p.progress == nullptr ||
+      p.sink == nullptr || p.lead < 1 || p.layers < 1 || p.steps < 1 || p.wait_ticks < 1)
+    return hipErrorInvalidValue;
+  for (int r = 0; r < RA_REGIONS; r++) {
+    if (p.n16[r] >= (1u << 27)) return hipErrorInvalidValue;   // byte offsets are 32-bit in the kernel
+    if (p.n16[r] != 0 && (p.base[r] == nullptr || (reinterpret_cast<uintptr_t>(p.base[r]) & 15) != 0 || p.layer_stride[r] % 16 != 0))
+      return hipErrorInvalidValue;
+  }
+  switch (depth) {
+#define X(D) case D: hipLaunchKernelGGL(read_ahead_kernel<D>, dim3(blocks), dim3(threads), 0, st, p); break;
+    X(1) X(2) X(3) X(4) X(5) X(6) X(8)
+#undef X
+    default: return hipErrorInvalidValue;
+  }
   return hipGetLastError();
 }
 

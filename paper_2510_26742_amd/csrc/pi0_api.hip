@@ -150,7 +150,7 @@ struct WsLayout {
   size_t xpatch, vh, vh_b, vq, vk, vv, vattn, vmid, part;
   size_t lx, lx_b, lq, kcache, vcache, lattn, lmid;
   size_t stok, z, y, y_b, eq, ek, ev, eattn, eml, emid;
-  size_t vstat, lstat, estat, estat_parts, pf_sink, vstat_parts, lstat_parts;
+  size_t vstat, lstat, estat, estat_parts, pf_sink, vstat_parts, lstat_parts, progress;
   size_t lx8, lx8s, lmid8, lmid8s;   // MXFP8 copies of the prefix feed-forward inputs
   bool mx_ok = false;                // the prefix feed-forward shapes fit the MXFP8 kernels (multiples of 256)
   size_t total;
@@ -292,6 +292,7 @@ void ws_layout(const pi0_config& c, const Dims& d, WsLayout& w) {
   w.estat = cur.take((size_t)64 * 2 * 4);
   w.estat_parts = cur.take((size_t)(d.X / 16) * 64 * 2 * 4);
   w.pf_sink = cur.take(1024 * 4);
+  w.progress = cur.take(256);
   {
     const int kmax = d.H * 256 > d.Fx ? d.H * 256 : d.Fx;
     w.epart = cur.take((size_t)ceil_div(round_up(kmax, 64), 1024) * 64 * round_up(d.X, 32) * 4);
@@ -300,13 +301,14 @@ void ws_layout(const pi0_config& c, const Dims& d, WsLayout& w) {
 }
 
 struct GraphKey {
-  int kind, n_views, n_prompt, slot_w, slot_r, precision;
+  int kind, n_views, n_prompt, slot_w, slot_r, precision, read_ahead;
   bool operator<(const GraphKey& o) const {
     if (kind != o.kind) return kind < o.kind;
     if (precision != o.precision) return precision < o.precision;
     if (n_views != o.n_views) return n_views < o.n_views;
     if (n_prompt != o.n_prompt) return n_prompt < o.n_prompt;
     if (slot_w != o.slot_w) return slot_w < o.slot_w;
+    if (read_ahead != o.read_ahead) return read_ahead < o.read_ahead;
     return slot_r < o.slot_r;
   }
 };
@@ -334,6 +336,12 @@ struct Tune {
   // buffer, no reduction launch): vision O, prefix O.  -1: up to 256 tokens (measured: -0.06 ms at one view,
   // nothing or a loss beyond, where the blocks' operand reads add up to more than the reduction launch costs)
   int fko = -1, fkl = -1;
+  // read-ahead for the expert as one kernel on a second stream beside the compute launches: number of its
+  // blocks (0 = warm-up blocks inside the launches instead, see pfq .. pfd), layer-steps it runs ahead,
+  // threads per block, loads in flight per lane.  Measured optimum: one 4-wave block per CU (a second wave
+  // per SIMD no longer fits beside the compute kernels' registers), 4 loads in flight (more reads the
+  // layer in a shorter burst that disturbs the compute launches, fewer arrives late), one layer ahead.
+  int ras = 256, ral = 1, rat = 256, rad = 4;
 };
 
 struct pi0_ctx {
@@ -351,6 +359,8 @@ struct pi0_ctx {
   int cur_slot = 0;                    // cache copy that holds it
   hipEvent_t ev_prefill[2] = {nullptr, nullptr};   // pi0_stream_frame: copy s was written / last read
   hipEvent_t ev_denoise[2] = {nullptr, nullptr};
+  hipStream_t ra_stream = nullptr;                 // read-ahead kernel of the expert (created on first use)
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   int last_hip = 0;
   std::map<GraphKey, hipGraphExec_t> graphs;
   std::vector<float> h_rope, h_tau;
@@ -370,6 +380,7 @@ struct Run {
   int launches = 0;
   hipError_t err = hipSuccess;
   int slot_w = 0, slot_r = 0;   // cache copy the prefill writes / the denoise reads
+  bool read_ahead = true;       // expert: read-ahead kernel on a second stream (else warm-up blocks inside the launches)
   int cls = PI0_OP_MISC;        // class of the launches that follow
   OpTimer* timer = nullptr;     // when set, every RUN / RUN_GEMM launch is bracketed by an event pair
   bool ok() const { return err == hipSuccess; }
@@ -717,7 +728,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
   RUN(r, launch_copy_f32(r.s, at<float>(c, w.st_noise), xa, (size_t)chunk * d.A));
   // C0: state token
   RUN(r, launch_state_token(r.s, at<float>(c, w.st_state), d.SD, at<float>(c, w.state_w), at<float>(c, w.state_b), d.X,
-                            at<float>(c, w.stok)));
+                            at<float>(c, w.stok), at<int>(c, w.progress)));
   const float dt = -1.0f / (float)d.steps;
   size_t tap_step_base = taps ? taps->off : 0;
   // row statistics of the suffix residual stream: where the next RMS-folded GEMM finds them
@@ -751,6 +762,44 @@ void run_denoise(Run& r, int P, Taps* taps) {
   const int kcps = T.kcps;   // key chunks per share
   const int ksplits = (T.ae16 && T.ksplit && d.H == 8 && pchunks > kcps && ceil_div(pchunks, kcps) <= 4) ? ceil_div(pchunks, kcps) : 1;
   int o_splits = 1;
+  // read-ahead kernel on its own stream, forked here and joined after the last Euler step (in a captured graph:
+  // a branch beside the chain of compute launches); it replaces the warm-up blocks inside the launches
+  bool ras = T.ras > 0 && r.read_ahead;
+  for (int l = 1; ras && l < d.Le; l++) {   // one stride between layers for every region
+    const WsTr &A = w.exp[l - 1], &B = w.exp[l];
+    const size_t st = w.exp[1].qkv.w - w.exp[0].qkv.w;
+    ras = B.qkv.w - A.qkv.w == st && B.o.w - A.o.w == st && B.gu.w - A.gu.w == st && B.down.w - A.down.w == st && st % 16 == 0;
+  }
+  const int pfq = ras ? 0 : T.pfq, pfa = ras ? 0 : T.pfa, pfo = ras ? 0 : T.pfo, pfd = ras ? 0 : T.pfd;
+  if (ras && !r.count_only && r.ok()) {
+    ReadAheadParams ra;
+    memset(&ra, 0, sizeof(ra));
+    const WsTr& L0 = w.exp[0];
+    const PW* pws[4] = {&L0.qkv, &L0.o, &L0.gu, &L0.down};
+    const int cslot = 4;
+    const size_t st = d.Le > 1 ? w.exp[1].qkv.w - w.exp[0].qkv.w : 0;
+    for (int i = 0; i < 4; i++) {
+      ra.base[i] = c->ws + pws[i]->w;
+      ra.layer_stride[i] = st;
+      ra.n16[i] = (unsigned)((size_t)pws[i]->n_pad * pws[i]->k_pad * 2 / 16);
+    }
+    ra.base[cslot] = c->ws + w.kcache + (size_t)this_slot * w.kcache_slot;
+    ra.layer_stride[cslot] = w.kcache_layer;
+    ra.n16[cslot] = (unsigned)pchunks * 1024;
+    ra.base[cslot + 1] = c->ws + w.vcache + (size_t)this_slot * w.vcache_slot;
+    ra.layer_stride[cslot + 1] = w.vcache_layer;
+    ra.n16[cslot + 1] = (unsigned)pchunks * 1024;
+    ra.layers = d.Le; ra.steps = d.steps; ra.lead = T.ral;
+    ra.progress = at<int>(c, w.progress);
+    ra.wait_ticks = 50000;   // 0.5 ms
+    ra.sink = at<unsigned>(c, w.pf_sink);
+    hipError_t e = c->ra_stream != nullptr ? hipSuccess : hipErrorNotReady;   // made by ensure_read_ahead, outside any capture
+    if (e == hipSuccess) e = hipEventRecord(c->ev_fork, r.s);
+    if (e == hipSuccess) e = hipStreamWaitEvent(c->ra_stream, c->ev_fork, 0);
+    if (e == hipSuccess) e = launch_read_ahead(c->ra_stream, ra, T.ras, T.rat, T.rad);
+    if (e == hipSuccess) e = hipEventRecord(c->ev_join, c->ra_stream);
+    if (e != hipSuccess) r.err = e;
+  }
   auto resid_gemm = [&](const PW& pw, const bf16* X, int K, const float* gain, const PrefetchDesc& pf) {
     if (pw.k_pad == 2048 || pw.k_pad == 4096) {
       const int tile = T.ae16 ? TILE_SKINNY16 : TILE_SKINNY_FULLK;
@@ -814,7 +863,8 @@ void run_denoise(Run& r, int P, Taps* taps) {
         p.q_cols = d.H * 256; p.k_cols = 256;
         p.head_dim = 256; p.dqk_pad = 256; p.nvb = 8; p.kv_heads = 1; p.kv_chunks = 2;
         p.m_split = T.qms;
-        p.pf = pf_begin(T.pfq);
+        p.pf = pf_begin(pfq);
+        if (ras) { p.progress = at<int>(c, w.progress); p.progress_value = k * d.Le + l + 1; }
         pf_weights(p.pf, 0, L.o);
         r.cls = PI0_OP_EXP_QKV;
         RUN_GEMM(r, TILE_SKINNY, PRO_RMS, EPI_QKV, p, 1);
@@ -835,14 +885,14 @@ void run_denoise(Run& r, int P, Taps* taps) {
           a.out_split_stride = (size_t)64 * d.H * 256;
           a.ml_out = at<float>(c, w.eml);
         }
-        a.pf = pf_begin(T.pfa);
+        a.pf = pf_begin(pfa);
         pf_weights(a.pf, 0, L.gu);
         r.cls = PI0_OP_EXP_ATTN;
         RUN(r, launch_attention(r.s, a));
       }
       // C6: O-projection + residual
       {
-        PrefetchDesc f = pf_begin(T.pfo);
+        PrefetchDesc f = pf_begin(pfo);
         pf_weights(f, 0, L.down);
         r.cls = PI0_OP_EXP_O;
         o_splits = ksplits;
@@ -861,7 +911,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
       {
         // the gate||up launch fills every CU by itself, so the launch after it reads ahead for two
         const int nl = l + 1 < d.Le ? l + 1 : 0;
-        PrefetchDesc f = pf_begin(T.pfd);
+        PrefetchDesc f = pf_begin(pfd);
         pf_weights(f, 0, w.exp[nl].qkv);
         pf_cache(f, 1, nl);
         r.cls = PI0_OP_EXP_DOWN;
@@ -889,6 +939,10 @@ void run_denoise(Run& r, int P, Taps* taps) {
       const size_t xoff = tap_step_base + (size_t)2 * d.Le * 64 * d.X + (size_t)k * chunk * d.A;
       r.did(launch_copy_f32(r.s, xa, taps->base + xoff, (size_t)chunk * d.A));
     }
+  }
+  if (ras && !r.count_only && r.ok()) {
+    const hipError_t e = hipStreamWaitEvent(r.s, c->ev_join, 0);
+    if (e != hipSuccess) r.err = e;
   }
   if (taps) taps->off = tap_step_base + (size_t)2 * d.Le * 64 * d.X + (size_t)d.steps * chunk * d.A;
 }
@@ -928,11 +982,22 @@ int fail_hip(pi0_ctx* c, hipError_t e) {
   return PI0_EHIP;
 }
 
+// stream and events of the read-ahead kernel (not created while a stream is being captured)
+hipError_t ensure_read_ahead(pi0_ctx* c) {
+  if (c->tune.ras <= 0) return hipSuccess;
+  hipError_t e = hipSuccess;
+  if (c->ra_stream == nullptr) e = hipStreamCreateWithFlags(&c->ra_stream, hipStreamNonBlocking);
+  if (e == hipSuccess && c->ev_fork == nullptr) e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming);
+  if (e == hipSuccess && c->ev_join == nullptr) e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming);
+  return e;
+}
+
 // Runs `kind` either through a cached graph or eagerly.
-int execute(pi0_ctx* c, int kind, int n_views, int n_prompt, hipStream_t s, int slot_w = -1, int slot_r = -1) {
+int execute(pi0_ctx* c, int kind, int n_views, int n_prompt, hipStream_t s, int slot_w = -1, int slot_r = -1, bool read_ahead = true) {
   const int P = n_views * c->d.T + n_prompt;
   if (slot_w < 0) slot_w = c->cur_slot;
   if (slot_r < 0) slot_r = c->cur_slot;
+  if (const hipError_t e = ensure_read_ahead(c); e != hipSuccess) return fail_hip(c, e);
   auto body = [&](Run& r) {
     if (kind == KIND_PREFILL || kind == KIND_INFER) run_prefill(r, n_views, n_prompt, nullptr);
     if (kind == KIND_DENOISE || kind == KIND_INFER) run_denoise(r, P, nullptr);
@@ -941,11 +1006,12 @@ int execute(pi0_ctx* c, int kind, int n_views, int n_prompt, hipStream_t s, int 
     Run r{c, s, false};
     r.slot_w = slot_w;
     r.slot_r = slot_r;
+    r.read_ahead = read_ahead;
     body(r);
     return r.ok() ? PI0_OK : fail_hip(c, r.err);
   }
   GraphKey key{kind, n_views, n_prompt, kind == KIND_DENOISE ? 0 : slot_w, kind == KIND_PREFILL ? 0 : slot_r,
-               kind == KIND_DENOISE ? 0 : c->precision};
+               kind == KIND_DENOISE ? 0 : c->precision, kind == KIND_PREFILL ? 0 : (int)read_ahead};
   auto it = c->graphs.find(key);
   if (it == c->graphs.end()) {
     hipError_t e = hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal);
@@ -953,6 +1019,7 @@ int execute(pi0_ctx* c, int kind, int n_views, int n_prompt, hipStream_t s, int 
     Run r{c, s, false};
     r.slot_w = slot_w;
     r.slot_r = slot_r;
+    r.read_ahead = read_ahead;
     body(r);
     hipGraph_t g = nullptr;
     e = hipStreamEndCapture(s, &g);
@@ -1016,7 +1083,7 @@ int pi0_create(const pi0_config* cfg, pi0_ctx** out) {
         {"zld", &c->tune.zld, 1, Z_MAX}, {"zvd", &c->tune.zvd, 1, Z_MAX},
         {"pfq", &c->tune.pfq, 0, 1024}, {"pfa", &c->tune.pfa, 0, 1024}, {"pfo", &c->tune.pfo, 0, 1024},
         {"pfd", &c->tune.pfd, 0, 1024}, {"ae16", &c->tune.ae16, 0, 1}, {"ksplit", &c->tune.ksplit, 0, 1}, {"kcps", &c->tune.kcps, 2, 16}, {"qms", &c->tune.qms, 0, 1},
-        {"fko", &c->tune.fko, 0, 1}, {"fkl", &c->tune.fkl, 0, 1}};
+        {"fko", &c->tune.fko, 0, 1}, {"fkl", &c->tune.fkl, 0, 1}, {"ras", &c->tune.ras, 0, 4096}, {"ral", &c->tune.ral, 1, 8}, {"rat", &c->tune.rat, 64, 256}, {"rad", &c->tune.rad, 1, 8}};
     for (auto& k : keys) {
       const char* f = strstr(env, k.key);
       while (f != nullptr && !((f == env || f[-1] == ',') && f[strlen(k.key)] == '=')) f = strstr(f + 1, k.key);
@@ -1060,6 +1127,9 @@ void pi0_destroy(pi0_ctx* c) {
     if (c->ev_prefill[i]) (void)hipEventDestroy(c->ev_prefill[i]);
     if (c->ev_denoise[i]) (void)hipEventDestroy(c->ev_denoise[i]);
   }
+  if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+  if (c->ev_join) (void)hipEventDestroy(c->ev_join);
+  if (c->ra_stream) (void)hipStreamDestroy(c->ra_stream);
   delete c;
 }
 
@@ -1271,6 +1341,8 @@ int pi0_infer(pi0_ctx* c, const float* d_images, int n_views, const int32_t* d_p
   c->cur_views = 0;
   hipError_t e = stage_inputs(c, s, d_images, n_views, d_prompt_ids, n_prompt, d_state, d_noise);
   if (e != hipSuccess) return fail_hip(c, e);
+  e = ensure_read_ahead(c);
+  if (e != hipSuccess) return fail_hip(c, e);
   int rc = execute(c, KIND_INFER, n_views, n_prompt, s);
   if (rc != PI0_OK) return rc;
   if (c->ev_prefill[c->cur_slot] != nullptr) {
@@ -1311,7 +1383,10 @@ int pi0_stream_frame(pi0_ctx* c, const float* d_images, int n_views, const int32
   if (e == hipSuccess) e = hipStreamWaitEvent(sd, c->ev_prefill[cur], 0);
   if (e == hipSuccess) e = stage_inputs(c, sd, nullptr, 0, nullptr, 0, d_state, d_noise);
   if (e != hipSuccess) return fail_hip(c, e);
-  rc = execute(c, KIND_DENOISE, c->cur_views, c->cur_prompt, sd, cur, cur);
+  // no read-ahead kernel here: it keeps a wave on every SIMD for the whole loop, and the prefill that runs beside
+  // this denoise has kernels whose waves take a SIMD's whole register file (they would wait for the loop's end;
+  // measured with it: frame interval +0.8 .. +1.2 ms)
+  rc = execute(c, KIND_DENOISE, c->cur_views, c->cur_prompt, sd, cur, cur, false);
   if (rc != PI0_OK) return rc;
   e = launch_copy_f32(sd, at<float>(c, c->wl.xa), d_actions, (size_t)c->cfg.chunk * c->d.A);
   if (e == hipSuccess) e = hipEventRecord(c->ev_denoise[cur], sd);
@@ -1342,6 +1417,8 @@ int pi0_debug_forward(pi0_ctx* c, const float* d_images, int n_views, const int3
   c->cur_views = 0;
   hipError_t e = stage_inputs(c, s, d_images, n_views, d_prompt_ids, n_prompt, d_state, d_noise);
   if (e != hipSuccess) return fail_hip(c, e);
+  e = ensure_read_ahead(c);
+  if (e != hipSuccess) return fail_hip(c, e);
   Run r{c, s, false};
   r.slot_w = r.slot_r = c->cur_slot;
   Taps taps;
@@ -1370,6 +1447,8 @@ int pi0_debug_profile(pi0_ctx* c, const float* d_images, int n_views, const int3
   }
   c->cur_views = 0;
   hipError_t e = stage_inputs(c, s, d_images, n_views, d_prompt_ids, n_prompt, d_state, d_noise);
+  if (e != hipSuccess) return fail_hip(c, e);
+  e = ensure_read_ahead(c);
   if (e != hipSuccess) return fail_hip(c, e);
   OpTimer timer;
   int rc = PI0_OK;

@@ -113,6 +113,8 @@ struct GemmParams {
   int k_true;         // divisor of the row statistics
   int m_tiles;        // number of MB*32 row tiles
   int m_split;        // TILE_SKINNY QKV: 1 = one block per (feature tile, 32-token block)
+  int* progress;      // TILE_SKINNY: when set, the launch stores progress_value there on entry (read-ahead kernel's pace)
+  int progress_value;
   // statistics / affine
   const float* bias;    // [n_pad] or null
   const float* colsum;  // [n_pad], PRO_LN only: sum_k W'[n][k]
@@ -305,7 +307,21 @@ hipError_t launch_patchify(hipStream_t s, const float* images, int n_views, int 
 hipError_t launch_embed_prompt(hipStream_t s, const int32_t* ids, int n, const bf16* table, int vocab, int E, float scale,
                                float* out_f32, bf16* out_bf16, int row0);
 hipError_t launch_state_token(hipStream_t s, const float* state, int state_dim, const float* ws, const float* bs, int X,
-                              float* out);
+                              float* out, int* progress);
+// read-ahead kernel of the action expert: per layer RA_REGIONS byte ranges (weights of the four GEMMs, the
+// layer's slice of the key and of the value cache), region r of layer l at base[r] + l * layer_stride[r]
+enum { RA_REGIONS = 6 };
+struct ReadAheadParams {
+  const unsigned char* base[RA_REGIONS];
+  size_t layer_stride[RA_REGIONS];   // bytes, multiples of 16
+  unsigned n16[RA_REGIONS];          // 16-byte words per layer (0 = region unused)
+  int layers, steps;
+  int lead;                          // layer-steps read ahead of the compute stream (>= 1)
+  const int* progress;               // number of layer-steps the compute stream has started
+  long long wait_ticks;              // bound of one wait, 100 MHz wall-clock ticks
+  unsigned* sink;                    // [1024]
+};
+hipError_t launch_read_ahead(hipStream_t s, const ReadAheadParams& p, int blocks, int threads, int depth);
 // z = silu(x @ W_fold + bias_k) -> bf16 [64][X] (row chunk.. zero);  Y row 0 = state token
 hipError_t launch_action_embed(hipStream_t s, const float* x, int chunk, int action_dim, const float* wfold,
                                const float* bias_k, int X, bf16* z, const float* state_tok, float* y_f32, bf16* y_bf16,

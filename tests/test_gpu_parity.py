@@ -411,6 +411,8 @@ def test_two_stream_frames_match_sequential(reduced):
     "vis=9,vqkv=9,vup=9,lqkv=9,vo=9,vd=9,lo=9,zvo=2,zvd=3,zlo=2,fko=0,fkl=0",          # 128x128 tiles everywhere they exist
     "fko=1,fkl=1",                                                                     # O projections over the whole k range, residual epilogue in the GEMM
     "fko=0,fkl=0",                                                                     # ... and as split-K partial GEMMs + reduction
+    "ras=64,ral=2,rat=128,rad=8",                                                      # expert read-ahead kernel: other shape, two layers ahead
+    "ras=0",                                                                           # ... and none: warm-up blocks inside the expert's launches
 ])
 def test_alternative_kernel_choices(tune):
     """Every tile / split / warm-up choice the tuning variable can select computes the same function."""
