@@ -288,6 +288,23 @@ int pi0_set_precision(pi0_ctx* ctx, int precision);
  */
 int pi0_clock_sample(long long* d_out, void* hip_stream);
 
+/*
+ * The read-ahead kernel that pi0_denoise runs beside the expert's compute launches (Section 5.2: prefetch across
+ * synchronisation points), alone on hip_stream, over a caller's buffer (no ctx needed).  The buffer is cut into
+ * `layers` equal slices; the kernel reads slice i % layers for i = 0 .. steps * layers - 1, each once the int32
+ * counter *d_progress is >= i + 1 - lead (lead >= 1; nothing in this call ever writes the counter: whoever
+ * sets it - the caller beforehand, or a kernel on another stream - sets the pace).  A block that waits longer than
+ * wait_ticks (100 MHz wall-clock ticks) for the counter gives up and exits, which is what keeps the kernel from
+ * hanging when its partner stream does not run: with a counter that never moves the call returns after about one
+ * bound.  The loads change nothing anywhere.
+ *   d_buf      device, 16-byte aligned, bytes a multiple of layers * 16, a slice below 2 GiB
+ *   d_progress device int32      d_sink device, 1024 x uint32 (never written in practice)
+ *   blocks     1 .. 1024 blocks of 256 threads      h_ms  HOST, elapsed milliseconds (the call synchronises)
+ * Errors: EINVAL, EHIP.
+ */
+int pi0_read_ahead_probe(const void* d_buf, size_t bytes, int layers, int steps, int lead, const int* d_progress,
+                         long long wait_ticks, int blocks, unsigned* d_sink, double* h_ms, void* hip_stream);
+
 /* Graph replay on (1, default) or off (0: every call launches kernels eagerly). */
 int pi0_set_graph_mode(pi0_ctx* ctx, int enabled);
 

@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpi0_hip.so")
 
 EXPORTS = ["pi0_create", "pi0_destroy", "pi0_weights_bytes", "pi0_workspace_bytes", "pi0_load_weights",
-           "pi0_prefill", "pi0_denoise", "pi0_infer", "pi0_debug_taps_elems", "pi0_debug_forward", "pi0_debug_profile", "pi0_sync_bench", "pi0_peak_bench", "pi0_clock_sample", "pi0_stream_frame",
+           "pi0_prefill", "pi0_denoise", "pi0_infer", "pi0_debug_taps_elems", "pi0_debug_forward", "pi0_debug_profile", "pi0_sync_bench", "pi0_peak_bench", "pi0_clock_sample", "pi0_read_ahead_probe", "pi0_stream_frame",
            "pi0_set_graph_mode", "pi0_set_precision", "pi0_kernel_count", "pi0_strerror", "pi0_last_hip_error"]
 
 # enum pi0_op_class, in order
@@ -81,6 +81,8 @@ def lib() -> ctypes.CDLL:
         L.pi0_peak_bench.restype = i32
         L.pi0_clock_sample.argtypes = [vp, vp]
         L.pi0_clock_sample.restype = i32
+        L.pi0_read_ahead_probe.argtypes = [vp, sz, i32, i32, i32, vp, ctypes.c_longlong, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
+        L.pi0_read_ahead_probe.restype = i32
         L.pi0_set_graph_mode.argtypes = [vp, i32]
         L.pi0_set_graph_mode.restype = i32
         L.pi0_set_precision.argtypes = [vp, i32]
@@ -142,6 +144,19 @@ def pi0_clock_sample(d_out, stream=None):
     rc = lib().pi0_clock_sample(_ptr(d_out), s)
     if rc != PI0_OK:
         raise Pi0Error(rc)
+
+
+def pi0_read_ahead_probe(d_buf, layers: int, steps: int, lead: int, d_progress, wait_ticks: int, blocks: int, d_sink,
+                         stream=None) -> float:
+    """Milliseconds one read-ahead kernel takes over d_buf (cut into `layers` slices) at the pace *d_progress allows."""
+    ms = ctypes.c_double(0.0)
+    s = None if stream is None else int(stream.cuda_stream)
+    nbytes = 0 if d_buf is None else int(d_buf.numel() * d_buf.element_size())
+    rc = lib().pi0_read_ahead_probe(_ptr(d_buf), nbytes, int(layers), int(steps), int(lead), _ptr(d_progress),
+                                    int(wait_ticks), int(blocks), _ptr(d_sink), ctypes.byref(ms), s)
+    if rc != PI0_OK:
+        raise Pi0Error(rc)
+    return float(ms.value)
 
 
 def shader_clock_ghz(sample0, sample1) -> float:

@@ -5,8 +5,9 @@
 // peaks, so that a roofline fraction can be read against either.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <string.h>
 
-#include "../../include/pi0.h"
+#include "pi0_internal.h"
 
 namespace {
 
@@ -117,6 +118,41 @@ extern "C" int pi0_peak_bench(int kind, const void* d_buf, size_t bytes, int ite
       }
     }
   }
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  return e == hipSuccess ? PI0_OK : PI0_EHIP;
+}
+
+// One read-ahead kernel over a caller's buffer, alone on the stream: the buffer is cut into `layers` equal
+// slices (one range per layer), the kernel walks steps * layers of them at the pace d_progress allows.
+extern "C" int pi0_read_ahead_probe(const void* d_buf, size_t bytes, int layers, int steps, int lead, const int* d_progress,
+                                    long long wait_ticks, int blocks, unsigned* d_sink, double* h_ms, void* hip_stream) {
+  if (d_buf == nullptr || d_progress == nullptr || d_sink == nullptr || h_ms == nullptr) return PI0_EINVAL;
+  if (layers < 1 || layers > 4096 || steps < 1 || steps > 4096 || lead < 1 || wait_ticks < 1 || blocks < 1 || blocks > 1024)
+    return PI0_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(d_buf) & 15) != 0 || bytes < (size_t)layers * 16 || bytes % ((size_t)layers * 16) != 0 ||
+      bytes / layers >= ((size_t)1 << 31))
+    return PI0_EINVAL;
+  ReadAheadParams p;
+  memset(&p, 0, sizeof(p));
+  p.base[0] = reinterpret_cast<const unsigned char*>(d_buf);
+  p.layer_stride[0] = bytes / layers;
+  p.n16[0] = (unsigned)(bytes / layers / 16);
+  p.layers = layers; p.steps = steps; p.lead = lead;
+  p.progress = d_progress;
+  p.wait_ticks = wait_ticks;
+  p.sink = d_sink;
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  hipError_t e = hipEventCreate(&e0);
+  if (e == hipSuccess) e = hipEventCreate(&e1);
+  if (e == hipSuccess) e = hipEventRecord(e0, s);
+  if (e == hipSuccess) e = launch_read_ahead(s, p, blocks, 256, 4);
+  if (e == hipSuccess) e = hipEventRecord(e1, s);
+  if (e == hipSuccess) e = hipEventSynchronize(e1);
+  float ms = 0.f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+  if (e == hipSuccess) *h_ms = (double)ms;
   if (e0) (void)hipEventDestroy(e0);
   if (e1) (void)hipEventDestroy(e1);
   return e == hipSuccess ? PI0_OK : PI0_EHIP;

@@ -324,6 +324,48 @@ def test_attainable_peak_microbenchmarks():
     assert 0.5 < ghz < 3.0
 
 
+def test_read_ahead_kernel_follows_its_counter_and_gives_up_when_it_stalls():
+    """The expert's read-ahead kernel (Section 5.2's prefetch across synchronisation points) alone on a stream:
+    with the counter ahead of it, it walks the whole buffer; with a counter that never moves, every block gives
+    up after one bound instead of waiting for a partner stream that is not there; it writes nothing."""
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.Stream(device=dev)
+    g = torch.Generator().manual_seed(5)
+    host = torch.randint(-2 ** 31, 2 ** 31 - 1, ((64 << 20) // 4,), dtype=torch.int32, generator=g)
+    buf = host.to(dev)
+    sink = torch.zeros(1024, dtype=torch.int32, device=dev)
+    prog = torch.full((1,), 1 << 20, dtype=torch.int32, device=dev)
+    torch.cuda.synchronize()
+    say("[gpu] pi0_read_ahead_probe, counter ahead")
+    ms_free = binding.pi0_read_ahead_probe(buf, 8, 4, 1, prog, 100000, 256, sink, stream)     # 4 x 64 MiB
+    say(f"[read-ahead] 256 MiB unpaced: {ms_free:.3f} ms ({0.268 / ms_free:.2f} TB/s)")
+    assert 0.03 < ms_free < 20.0
+    prog.zero_()
+    torch.cuda.synchronize()
+    say("[gpu] pi0_read_ahead_probe, counter never moves, bound 1 ms")
+    ms_1 = binding.pi0_read_ahead_probe(buf, 8, 4, 1, prog, 100000, 256, sink, stream)        # slice 0, then one wait of 1 ms
+    say("[gpu] pi0_read_ahead_probe, counter never moves, bound 20 us")
+    ms_2 = binding.pi0_read_ahead_probe(buf, 8, 4, 1, prog, 2000, 256, sink, stream)
+    say(f"[read-ahead] stalled: {ms_1:.3f} ms with a 1 ms bound, {ms_2:.3f} ms with a 20 us bound")
+    assert 0.9 < ms_1 < 3.0
+    assert ms_2 < 0.5
+    # the counter lets it through 3 of 8 slices (lead 1: slice i needs counter >= i), then it stalls for one bound
+    prog.fill_(2)
+    torch.cuda.synchronize()
+    say("[gpu] pi0_read_ahead_probe, counter at 2, bound 1 ms")
+    ms_3 = binding.pi0_read_ahead_probe(buf, 8, 1, 1, prog, 100000, 256, sink, stream)
+    assert 0.9 < ms_3 < 3.0
+    # two slices ahead of the counter instead of one: slice i needs counter >= i - 1, so a counter of 6 lets all 8 through
+    prog.fill_(6)
+    torch.cuda.synchronize()
+    say("[gpu] pi0_read_ahead_probe, counter at 6, two ahead")
+    ms_4 = binding.pi0_read_ahead_probe(buf, 8, 1, 2, prog, 100000, 256, sink, stream)
+    assert ms_4 < 0.9
+    assert torch.equal(buf.cpu(), host) and int(sink.abs().sum()) == 0 and int(prog.item()) == 6
+    with pytest.raises(binding.Pi0Error):
+        binding.pi0_read_ahead_probe(buf, 7, 1, 1, prog, 1000, 256, sink, stream)               # 64 MiB is not 7 * 16 * n
+
+
 def test_mxfp8_prefix_mlp_against_mxfp8_oracle(reduced):
     """Reduced-precision mode (prefix gate||up / down on MXFP8 operands) against the oracle that rounds the same
     operands through MXFP8 by the format's definition; the mode really changes the numbers; switching back

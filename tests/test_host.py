@@ -172,6 +172,23 @@ def test_clock_sample_rejects_bad_arguments(L):
     assert binding.shader_clock_ghz([100, 10], [2500, 110]) == 2.4        # 2400 cycles in 100 ticks of 10 ns
 
 
+def test_read_ahead_probe_rejects_bad_arguments(L):
+    fake = 0x10000
+    out = ctypes.c_double(0.0)
+    r = ctypes.byref(out)
+    ok = dict(buf=fake, nbytes=1 << 20, layers=4, steps=2, lead=1, prog=fake, ticks=1000, blocks=64, sink=fake)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return L.pi0_read_ahead_probe(a["buf"], a["nbytes"], a["layers"], a["steps"], a["lead"], a["prog"], a["ticks"], a["blocks"],
+                                      a["sink"], kw.get("res", r), None)
+    for bad in (dict(buf=None), dict(prog=None), dict(sink=None), dict(res=None), dict(buf=fake + 8),     # null / misaligned
+                dict(layers=0), dict(steps=0), dict(lead=0), dict(ticks=0), dict(blocks=0), dict(blocks=1025),
+                dict(nbytes=0), dict(nbytes=(1 << 20) + 16),                                               # not layers * 16
+                dict(nbytes=1 << 33, layers=2)):                                                           # slice of 4 GiB
+        assert call(**bad) == binding.PI0_EINVAL, bad
+
+
 def test_kernel_count_and_taps(L):
     cfg = synth.full_config()
     c = binding.to_c_config(cfg)
