@@ -293,7 +293,9 @@ int pi0_clock_sample(long long* d_out, void* hip_stream);
  * synchronisation points), alone on hip_stream, over a caller's buffer (no ctx needed).  The buffer is cut into
  * `layers` equal slices; the kernel reads slice i % layers for i = 0 .. steps * layers - 1, each once the int32
  * counter *d_progress is >= i + 1 - lead (lead >= 1; nothing in this call ever writes the counter: whoever
- * sets it - the caller beforehand, or a kernel on another stream - sets the pace).  A block that waits longer than
+ * sets it - the caller beforehand, or a kernel on another stream - sets the pace), and skips slice i when the
+ * counter is already >= i + 2 (too late to be of use).  lead >= steps * layers reads everything without waiting;
+ * a counter far ahead makes the kernel skip everything.  A block that waits longer than
  * wait_ticks (100 MHz wall-clock ticks) for the counter gives up and exits, which is what keeps the kernel from
  * hanging when its partner stream does not run: with a counter that never moves the call returns after about one
  * bound.  The loads change nothing anywhere.

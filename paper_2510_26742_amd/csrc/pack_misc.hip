@@ -343,7 +343,9 @@ hipError_t launch_state_token(hipStream_t st, const float* state, int state_dim,
 // word compared with a constant so they cannot be elided, and no result depends on them.
 // Every wait is bounded: a block that does not see the counter move within `wait_ticks` of the
 // 100 MHz wall clock stops reading ahead altogether and exits (so a machine that runs the two
-// streams one after the other only loses that one wait).
+// streams one after the other only loses that one wait).  A block that finds the compute stream
+// already past layer-step i skips that slice, so a kernel that has fallen behind catches up and
+// the join at the end of the loop never waits for reads nobody needs any more.
 // ------------------------------------------------------------------------------------------------
 // Register budget: the expert's compute launches keep two waves of up to 224 registers on every SIMD, so a
 // wave of this kernel only fits beside them with at most 64 (asked for through the occupancy attribute).
@@ -355,25 +357,31 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
   unsigned acc = 0;
   const int total = p.steps * p.layers;
   for (int i = 0; i < total; i++) {
+    // thread 0 decides for the block: 1 read slice i, 2 skip it (the compute stream is already past layer-step
+    // i, so its bytes would come too late: a read-ahead kernel that has fallen behind catches up instead of
+    // holding the join back), 0 give up (the counter did not move within the bound)
     const int need = i + 1 - p.lead;
-    if (need > 0) {
-      if (threadIdx.x == 0) {
+    if (threadIdx.x == 0) {
+      int seen = __hip_atomic_load(p.progress, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      int go = 1;
+      if (seen < need) {
         const long long t0 = wall_clock64();
-        int go = 1;
-        while (__hip_atomic_load(p.progress, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < need) {
+        while ((seen = __hip_atomic_load(p.progress, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) < need) {
           if (wall_clock64() - t0 > p.wait_ticks) {
             go = 0;
             break;
           }
           __builtin_amdgcn_s_sleep(16);
         }
-        s_go = go;
       }
-      __syncthreads();
-      const int go = s_go;
-      __syncthreads();
-      if (!go) break;
+      if (go && seen >= i + 2) go = 2;
+      s_go = go;
     }
+    __syncthreads();
+    const int go = s_go;
+    __syncthreads();
+    if (go == 0) break;
+    if (go == 2) continue;
     const int layer = i % p.layers;
 #pragma unroll
     for (int r = 0; r < RA_REGIONS; r++) {
@@ -382,6 +390,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
       const unsigned char* base = p.base[r] + (size_t)layer * p.layer_stride[r];
       const unsigned end = p.n16[r] * 16u;
       if (end == 0u) continue;
+      // overtaken in the middle of the slice: leave the rest of it (every lane of the wave reads the same word)
+      if (r > 0 && __hip_atomic_load(p.progress, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= i + 2) break;
       for (unsigned o0 = tid * 16u; o0 < end; o0 += RA_DEPTH * nth * 16u) {
         uint4 v[RA_DEPTH];
 #pragma unroll

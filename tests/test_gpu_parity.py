@@ -334,12 +334,20 @@ def test_read_ahead_kernel_follows_its_counter_and_gives_up_when_it_stalls():
     host = torch.randint(-2 ** 31, 2 ** 31 - 1, ((64 << 20) // 4,), dtype=torch.int32, generator=g)
     buf = host.to(dev)
     sink = torch.zeros(1024, dtype=torch.int32, device=dev)
-    prog = torch.full((1,), 1 << 20, dtype=torch.int32, device=dev)
+    prog = torch.zeros(1, dtype=torch.int32, device=dev)
     torch.cuda.synchronize()
-    say("[gpu] pi0_read_ahead_probe, counter ahead")
-    ms_free = binding.pi0_read_ahead_probe(buf, 8, 4, 1, prog, 100000, 256, sink, stream)     # 4 x 64 MiB
+    say("[gpu] pi0_read_ahead_probe, unpaced")
+    binding.pi0_read_ahead_probe(buf, 8, 4, 32, prog, 100000, 256, sink, stream)              # first launch: code upload
+    ms_free = binding.pi0_read_ahead_probe(buf, 8, 4, 32, prog, 100000, 256, sink, stream)    # lead 32 of 32: 4 x 64 MiB, no waits
     say(f"[read-ahead] 256 MiB unpaced: {ms_free:.3f} ms ({0.268 / ms_free:.2f} TB/s)")
     assert 0.03 < ms_free < 20.0
+    # a compute stream that is far ahead: every slice is skipped
+    prog.fill_(1 << 20)
+    torch.cuda.synchronize()
+    say("[gpu] pi0_read_ahead_probe, counter far ahead")
+    ms_skip = binding.pi0_read_ahead_probe(buf, 8, 4, 1, prog, 100000, 256, sink, stream)
+    say(f"[read-ahead] all 32 slices skipped: {ms_skip:.3f} ms")
+    assert ms_skip < 0.5 * ms_free
     prog.zero_()
     torch.cuda.synchronize()
     say("[gpu] pi0_read_ahead_probe, counter never moves, bound 1 ms")
@@ -349,13 +357,14 @@ def test_read_ahead_kernel_follows_its_counter_and_gives_up_when_it_stalls():
     say(f"[read-ahead] stalled: {ms_1:.3f} ms with a 1 ms bound, {ms_2:.3f} ms with a 20 us bound")
     assert 0.9 < ms_1 < 3.0
     assert ms_2 < 0.5
-    # the counter lets it through 3 of 8 slices (lead 1: slice i needs counter >= i), then it stalls for one bound
+    # the counter lets it through slices 1 and 2 of 8 (lead 1: slice i needs counter >= i; slice 0 is skipped as stale),
+    # then it stalls for one bound
     prog.fill_(2)
     torch.cuda.synchronize()
     say("[gpu] pi0_read_ahead_probe, counter at 2, bound 1 ms")
     ms_3 = binding.pi0_read_ahead_probe(buf, 8, 1, 1, prog, 100000, 256, sink, stream)
     assert 0.9 < ms_3 < 3.0
-    # two slices ahead of the counter instead of one: slice i needs counter >= i - 1, so a counter of 6 lets all 8 through
+    # two slices ahead of the counter instead of one: slice i needs counter >= i - 1, so a counter of 6 lets it reach the end
     prog.fill_(6)
     torch.cuda.synchronize()
     say("[gpu] pi0_read_ahead_probe, counter at 6, two ahead")
