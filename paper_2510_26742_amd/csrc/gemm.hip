@@ -955,6 +955,7 @@ int gemm_rows_per_tile(int tile) {
     case TILE_WIDE128: return 128;
     case TILE_ENTRY: return 64;
     case TILE_SQ128: return 128;
+    case TILE_T192: return 192;
     default: return -1;
   }
 }
@@ -993,7 +994,9 @@ static hipError_t set_attr() {
   X(TILE_WIDE, 8, 4, 2, PRO_RMS, EPI_GEGLU, 2)   \
   X(TILE_WIDE, 8, 4, 2, PRO_NONE, EPI_PARTIAL, 2) \
   X(TILE_WIDE128, 4, 4, 3, PRO_RMS, EPI_GEGLU, 2)   \
-  X(TILE_WIDE128, 4, 4, 3, PRO_NONE, EPI_PARTIAL, 2)
+  X(TILE_WIDE128, 4, 4, 3, PRO_NONE, EPI_PARTIAL, 2) \
+  X(TILE_T192, 6, 4, 3, PRO_RMS, EPI_GEGLU, 2)   \
+  X(TILE_T192, 6, 4, 2, PRO_NONE, EPI_PARTIAL, 2)
 
 // X(PRO, EPI, feature tiles per block, k16 steps per wave), ascending steps: vision O (k = 1152), prefix O
 // (k = 2048), vision QKV (k = 1152, 64 x 64 tiles)
@@ -1066,7 +1069,7 @@ hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmPara
   if (pro != PRO_NONE && (z_splits != 1 || p.rowstat == nullptr)) return hipErrorInvalidValue;
   if (epi != EPI_PARTIAL && z_splits != 1) return hipErrorInvalidValue;
   if (p.m_tiles < 1) return hipErrorInvalidValue;
-  if (tile == TILE_BIG || tile == TILE_MID || tile == TILE_SMALL || tile == TILE_WIDE || tile == TILE_WIDE128 || tile == TILE_ENTRY) {
+  if (tile == TILE_BIG || tile == TILE_MID || tile == TILE_SMALL || tile == TILE_WIDE || tile == TILE_WIDE128 || tile == TILE_T192 || tile == TILE_ENTRY) {
     // partial row statistics: planes of stat_rows rows, every row a block touches inside a plane
     if (pro != PRO_NONE && p.rowstat_parts > 1 && (p.stat_rows < p.M || p.rowstat_parts > STAT_PARTS_MAX)) return hipErrorInvalidValue;
     if (epi == EPI_RESID && p.stat_out != nullptr && p.stat_rows < p.M + p.row_offset) return hipErrorInvalidValue;

@@ -323,10 +323,11 @@ struct Tune {
   int vis = TILE_MID;     // vision patch / projector (and QKV / up unless overridden below)
   int vqkv = -1, vup = -1; // vision QKV / up tile (-1: QKV on the entry kernel up to 256 tokens, else same as vis)
   int lqkv = -1;          // prefix QKV (-1: 64 x 64 tiles up to 256 tokens, 64 x 128 beyond)
-  int lgu = -1;           // prefix gate||up (-1: 128 x 256 or 256 x 256 tiles, whichever fills the 256 CUs in fewer rounds)
+  int lgu = -1;           // prefix gate||up (-1: 128, 192 or 256 tokens x 256 features, whichever fills the 256 CUs at the least cost)
   int vo = TILE_MID, vd = -1, lo = -1, ld = TILE_WIDE128;   // split-K partial GEMMs: vision O / down, prefix O / down
   int zvo = -1, zlo = -1, zld = -1, zvd = -1;   // -1: chosen from the number of tokens (measured optima at 1 / 2 / 3 views)
-  // warm-up blocks carried by the expert's launches (0 = none): QKV, attention, O, down
+  // warm-up blocks carried by the expert's launches (0 = none): QKV, attention, O, down.  Used where the read-ahead
+  // kernel below is not (two-stream frames, ras=0)
   int pfq = 64, pfa = 64, pfo = 128, pfd = 128;
   int qms = 1;            // expert QKV: token blocks on separate blocks (160 instead of 80)
   int ksplit = 1;         // expert attention: key shares for prefixes beyond kcps chunks
@@ -601,13 +602,21 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
   const bool mx = c->precision == PI0_PRECISION_MXFP8_PREFIX_MLP;
   // reduced precision: the GeGLU epilogue takes whole-row statistics, so the O projection keeps its reduction launch
   const bool fkl = mx ? false : (T.fkl >= 0 ? T.fkl != 0 : P <= 256);
-  // gate||up: 128 blocks of 256 features per token tile.  A 256-token tile costs two 128-token tiles; take the
-  // tile height whose block count needs fewer rounds on 256 compute units (ties: the taller tile).
+  // gate||up: 128 blocks of 256 features per token tile of 128, 192 or 256 tokens.  A block's time goes with its
+  // height, so a choice costs height x rounds on 256 compute units; take the cheapest, the taller tile on ties
+  // (fewer operand bytes per CU and flop).  256 / 512 / 768 / 816 tokens -> 128 / 256 / 192 / 256.
   const int gu_cols = ceil_div(w.llm[0].gu.n_pad, 256);
-  const int rounds128 = ceil_div(ceil_div(P, 128) * gu_cols, 256), rounds256 = 2 * ceil_div(ceil_div(P, 256) * gu_cols, 256);
-  const int tlgu = T.lgu >= 0 ? T.lgu : (rounds256 <= rounds128 ? TILE_WIDE : TILE_WIDE128);
+  int tlgu = T.lgu;
+  if (tlgu < 0) {
+    const int heights[3] = {128, 192, 256}, ids[3] = {TILE_WIDE128, TILE_T192, TILE_WIDE};
+    int best = 0;
+    for (int i = 0; i < 3; i++) {
+      const int cost = heights[i] * ceil_div(ceil_div(P, heights[i]) * gu_cols, 256);
+      if (tlgu < 0 || cost <= best) { best = cost; tlgu = ids[i]; }
+    }
+  }
   // down: as many k slices as keep all blocks in one round (measured optima 16 / 8 / 5 at 256 / 512 / 768 tokens)
-  const int down_tiles = ceil_div(P, gemm_rows_per_tile(T.ld)) * ceil_div(w.llm[0].down.n_pad, T.ld == TILE_WIDE || T.ld == TILE_WIDE128 ? 256 : 128);
+  const int down_tiles = ceil_div(P, gemm_rows_per_tile(T.ld)) * ceil_div(w.llm[0].down.n_pad, T.ld == TILE_WIDE || T.ld == TILE_WIDE128 || T.ld == TILE_T192 ? 256 : 128);
   const int zld = T.zld > 0 ? T.zld : std::max(1, std::min(16, 256 / std::max(1, down_tiles)));
   for (int l = 0; l < d.Ll; l++) {
     const WsTr& L = w.llm[l];
@@ -1077,9 +1086,9 @@ int pi0_create(const pi0_config* cfg, pi0_ctx** out) {
 
   if (const char* env = getenv("PI0_TUNE")) {
     struct { const char* key; int* dst; int lo, hi; } keys[] = {
-        {"vis", &c->tune.vis, 0, 9},   {"lqkv", &c->tune.lqkv, 0, 9}, {"lgu", &c->tune.lgu, 0, 9},
+        {"vis", &c->tune.vis, 0, 9},   {"lqkv", &c->tune.lqkv, 0, 9}, {"lgu", &c->tune.lgu, 0, 10},
         {"vqkv", &c->tune.vqkv, -1, 9}, {"vup", &c->tune.vup, -1, 9},
-        {"vo", &c->tune.vo, 0, 9}, {"vd", &c->tune.vd, 0, 9}, {"lo", &c->tune.lo, 0, 9}, {"ld", &c->tune.ld, 0, 9}, {"zvo", &c->tune.zvo, 1, Z_MAX}, {"zlo", &c->tune.zlo, 1, Z_MAX},
+        {"vo", &c->tune.vo, 0, 9}, {"vd", &c->tune.vd, 0, 9}, {"lo", &c->tune.lo, 0, 9}, {"ld", &c->tune.ld, 0, 10}, {"zvo", &c->tune.zvo, 1, Z_MAX}, {"zlo", &c->tune.zlo, 1, Z_MAX},
         {"zld", &c->tune.zld, 1, Z_MAX}, {"zvd", &c->tune.zvd, 1, Z_MAX},
         {"pfq", &c->tune.pfq, 0, 1024}, {"pfa", &c->tune.pfa, 0, 1024}, {"pfo", &c->tune.pfo, 0, 1024},
         {"pfd", &c->tune.pfd, 0, 1024}, {"ae16", &c->tune.ae16, 0, 1}, {"ksplit", &c->tune.ksplit, 0, 1}, {"kcps", &c->tune.kcps, 2, 16}, {"qms", &c->tune.qms, 0, 1},

@@ -459,6 +459,7 @@ def test_two_stream_frames_match_sequential(reduced):
     "vis=5,vqkv=5,vup=5,lqkv=5,vo=5,vd=5,lo=5,zvo=1,zvd=2,zlo=1,kcps=4",               # 64x64 tiles, few splits, small key shares
     "lgu=6,ld=7,zld=4",                                                                # two feature tiles per wave: 256x256 gate||up, 128x256 down
     "lgu=7,ld=6,zld=8",                                                                # ... and the other way round
+    "lgu=10,ld=10,zld=8",                                                              # 192-token tiles (768 tokens in four)
     "vis=9,vqkv=9,vup=9,lqkv=9,vo=9,vd=9,lo=9,zvo=2,zvd=3,zlo=2,fko=0,fkl=0",          # 128x128 tiles everywhere they exist
     "fko=1,fkl=1",                                                                     # O projections over the whole k range, residual epilogue in the GEMM
     "fko=0,fkl=0",                                                                     # ... and as split-K partial GEMMs + reduction
