@@ -51,11 +51,13 @@ struct EpiOps {
   f32x4 bias[4], colsum[4], aux[4], gain[4];
 };
 
-template <int PRO, int EPI>
+// Steps I0 .. I1-1 of the tile's four 8-feature steps (all of them unless a kernel shares a tile's epilogue out
+// over several waves; the residual epilogue's row statistics need the whole tile, the GeGLU one whole pairs).
+template <int PRO, int EPI, int I0 = 0, int I1 = 4>
 __device__ __forceinline__ void epilogue_preload(const GemmParams& p, int nt, int m, int lh, EpiOps& o) {
   if (EPI == EPI_PARTIAL) return;
 #pragma unroll
-  for (int i = 0; i < 4; i++) {
+  for (int i = I0; i < I1; i++) {
     const int n4 = nt * 32 + 8 * i + 4 * lh;
     if (PRO == PRO_LN) o.colsum[i] = *reinterpret_cast<const f32x4*>(p.colsum + n4);
     if (p.bias != nullptr) o.bias[i] = *reinterpret_cast<const f32x4*>(p.bias + n4);
@@ -80,9 +82,11 @@ __device__ __forceinline__ void epilogue_preload(const GemmParams& p, int nt, in
 // One 32-token x 32-feature accumulator tile -> memory.  `acc` is the MFMA accumulator of the
 // calling lane (token = lane % 32, features nt*32 + 8*(r/4) + 4*(lane/32) + r%4), `m` the global
 // row, (s_sum, s_sq) the row's sum and sum of squares over the true k columns.
-template <int PRO, int EPI>
+template <int PRO, int EPI, int I0 = 0, int I1 = 4>
 __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16& acc, int nt, int m, int lh,
                                               float s_sum, float s_sq, int zsplit, const EpiOps& ops) {
+  static_assert(EPI != EPI_RESID || (I0 == 0 && I1 == 4), "row statistics are taken over the whole tile");
+  static_assert(EPI != EPI_GEGLU || (I0 % 2 == 0 && I1 % 2 == 0), "gate / up steps are stored in pairs");
   const float inv_k = 1.0f / (float)p.k_true;
   {
     float rs = 1.f, mu = 0.f;
@@ -96,7 +100,7 @@ __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16&
       rs = rsqrtf(fmaxf(var, 0.f) + 1e-6f);
     }
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
+    for (int i = I0; i < I1; i++) {
       const int n4 = nt * 32 + 8 * i + 4 * lh;
       float v[4];
 #pragma unroll
@@ -510,6 +514,25 @@ __global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(1, 1)))
 
 // MS = 1: the two 32-token blocks go to separate blocks (gridDim.z = 2), which halves the activation
 // bytes per CU; used where the launch would otherwise leave most CUs idle (the expert's QKV).
+// Steps I0 .. I1-1 of one token block's tile: the 8 waves' partial tiles [wave][token block][step][lane][4] are
+// added in wave order, then the epilogue runs on those steps.
+template <int PRO, int EPI, int I0, int I1>
+__device__ __forceinline__ void skinny_finish(const GemmParams& p, const float* red, int mb, int lane, int nt, int ml, int lh,
+                                              float ssum, float ssq, const EpiOps& ops) {
+  f32x16 sum;
+#pragma unroll
+  for (int r = 0; r < 16; r++) sum[r] = 0.f;
+#pragma unroll
+  for (int ww = 0; ww < SK_WAVES; ww++)
+#pragma unroll
+    for (int q = I0; q < I1; q++) {
+      const f32x4 v4 = *reinterpret_cast<const f32x4*>(red + ((((size_t)ww * 2 + mb) * 4 + q) * 64 + lane) * 4);
+#pragma unroll
+      for (int j = 0; j < 4; j++) sum[4 * q + j] += v4[j];
+    }
+  if (ml < p.M) epilogue_tile<PRO, EPI, I0, I1>(p, sum, nt, ml, lh, ssum, ssq, blockIdx.y, ops);
+}
+
 template <int PRO, int EPI, int MS = 0>
 __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p) {
   constexpr int NMB = MS ? 1 : 2;              // token blocks per block
@@ -536,8 +559,7 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
 
   // row statistics of the input: parts partial sums per row (1, or one per 32-column tile of the
   // producer); wave w adds parts w, w+8, ... for row `lane`, the epilogue adds the 8 wave sums
-  float* sstat = red + SK_WAVES * 2 * 16 * 64;     // [64 rows][2] after the reduction below
-  float* sstat8 = sstat + 128;                     // [8 waves][64][2]
+  float* sstat8 = red + SK_WAVES * 2 * 16 * 64 + 128;   // [8 waves][64][2]
   bf16x8 wf[8], xf[NMB][8];
   const bf16* wbase = p.W.w + ((size_t)nt * KC16 + (kbeg >> 4)) * 512 + lane * 8;
   const bf16* xbase = p.X + (size_t)(kbeg >> 4) * 512 + lane * 8;
@@ -560,10 +582,28 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
       sp[jj] = *reinterpret_cast<const float2*>(p.rowstat + ((size_t)j * 64 + lane) * 2);
     }
   }
-  // operands of the epilogue (wave i finishes local token block i), in the same round trip
+  // operands of the epilogue, in the same round trip.  The tile of a token block is finished by PIECES waves, each
+  // taking 4 / PIECES of its four 8-feature steps (finishing wave f: token block f / PIECES, piece f % PIECES): the
+  // sum over the 8 waves' partial tiles and the epilogue arithmetic are the tail of the launch, and one wave alone
+  // took 3.8 k cycles over them for the QKV epilogue (2.2 k for GeGLU)
+  constexpr int PIECES = EPI == EPI_QKV ? 4 : EPI == EPI_GEGLU ? 2 : 1;
+  constexpr int NFIN = NMB * PIECES;
+  static_assert(NFIN <= SK_WAVES, "finishing waves");
   EpiOps ops;
-  const int mrow = (mb_first + w) * 32 + lq;   // the row this lane finishes if w < NMB
-  if (w < NMB && mrow < p.M) epilogue_preload<PRO, EPI>(p, nt, mrow, lh, ops);
+  const int fmb = w / PIECES, fpc = w % PIECES;
+  const int mrow = (mb_first + fmb) * 32 + lq;   // the row this lane finishes if w < NFIN
+  if (w < NFIN && mrow < p.M) {
+    if constexpr (PIECES == 1) epilogue_preload<PRO, EPI>(p, nt, mrow, lh, ops);
+    else if constexpr (PIECES == 2) {
+      if (fpc == 0) epilogue_preload<PRO, EPI, 0, 2>(p, nt, mrow, lh, ops);
+      else epilogue_preload<PRO, EPI, 2, 4>(p, nt, mrow, lh, ops);
+    } else {
+      if (fpc == 0) epilogue_preload<PRO, EPI, 0, 1>(p, nt, mrow, lh, ops);
+      else if (fpc == 1) epilogue_preload<PRO, EPI, 1, 2>(p, nt, mrow, lh, ops);
+      else if (fpc == 2) epilogue_preload<PRO, EPI, 2, 3>(p, nt, mrow, lh, ops);
+      else epilogue_preload<PRO, EPI, 3, 4>(p, nt, mrow, lh, ops);
+    }
+  }
   f32x16 acc[NMB];
 #pragma unroll
   for (int mb = 0; mb < NMB; mb++)
@@ -596,39 +636,26 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
     sstat8[(w * 64 + lane) * 2 + 1] = pb;
   }
   __syncthreads();
-  if (w >= NMB) return;
+  if (w >= NFIN) return;
   if (MS && (int)blockIdx.z > mb_last) return;   // M <= 32: the second block of a split launch has nothing to store
-  if (PRO != PRO_NONE) {   // each finishing wave sums the statistics of the 32 rows it owns (lanes 0..31 suffice)
-    const int r = (mb_first + w) * 32 + lq;
-    float a = 0.f, b = 0.f;
+  const int ml = mrow;
+  float ssum = 0.f, ssq = 0.f;
+  if (PRO != PRO_NONE) {   // statistics of the lane's own row: the 8 waves' partial sums, in wave order
 #pragma unroll
     for (int ww = 0; ww < SK_WAVES; ww++) {
-      a += sstat8[(ww * 64 + r) * 2];
-      b += sstat8[(ww * 64 + r) * 2 + 1];
+      ssum += sstat8[(ww * 64 + ml) * 2];
+      ssq += sstat8[(ww * 64 + ml) * 2 + 1];
     }
-    sstat[r * 2] = a;       // both lane halves write the same value
-    sstat[r * 2 + 1] = b;
   }
-  const int mb = w;
-  f32x16 sum;
-#pragma unroll
-  for (int r = 0; r < 16; r++) sum[r] = 0.f;
-#pragma unroll
-  for (int ww = 0; ww < SK_WAVES; ww++)
-#pragma unroll
-    for (int q = 0; q < 4; q++) {
-      const f32x4 v4 = *reinterpret_cast<const f32x4*>(red + ((((size_t)ww * 2 + mb) * 4 + q) * 64 + lane) * 4);
-#pragma unroll
-      for (int j = 0; j < 4; j++) sum[4 * q + j] += v4[j];
-    }
-  const int ml = mrow;
-  if (ml < p.M) {
-    float ssum = 0.f, ssq = 0.f;
-    if (PRO != PRO_NONE) {
-      ssum = sstat[ml * 2];
-      ssq = sstat[ml * 2 + 1];
-    }
-    epilogue_tile<PRO, EPI>(p, sum, nt, ml, lh, ssum, ssq, blockIdx.y, ops);
+  if constexpr (PIECES == 1) skinny_finish<PRO, EPI, 0, 4>(p, red, fmb, lane, nt, ml, lh, ssum, ssq, ops);
+  else if constexpr (PIECES == 2) {
+    if (fpc == 0) skinny_finish<PRO, EPI, 0, 2>(p, red, fmb, lane, nt, ml, lh, ssum, ssq, ops);
+    else skinny_finish<PRO, EPI, 2, 4>(p, red, fmb, lane, nt, ml, lh, ssum, ssq, ops);
+  } else {
+    if (fpc == 0) skinny_finish<PRO, EPI, 0, 1>(p, red, fmb, lane, nt, ml, lh, ssum, ssq, ops);
+    else if (fpc == 1) skinny_finish<PRO, EPI, 1, 2>(p, red, fmb, lane, nt, ml, lh, ssum, ssq, ops);
+    else if (fpc == 2) skinny_finish<PRO, EPI, 2, 3>(p, red, fmb, lane, nt, ml, lh, ssum, ssq, ops);
+    else skinny_finish<PRO, EPI, 3, 4>(p, red, fmb, lane, nt, ml, lh, ssum, ssq, ops);
   }
 }
 
