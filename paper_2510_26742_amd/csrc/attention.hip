@@ -52,7 +52,13 @@ __global__ __launch_bounds__(512) void attention_kernel(AttnParams p) {
     if (blockIdx.z == 0) prefetch_role(p.pf, (int)blockIdx.x + (int)gridDim.x * ((int)blockIdx.y - p.heads));
     return;
   }
-  const int tile = blockIdx.x;
+  // v_split > 1: the head dimension of the values (and of the output) is shared out over v_split blocks per
+  // (query tile, head); each repeats phase 1 on all keys and runs phase 2 on its NVB / v_split slices only
+  const int vs = p.v_split > 1 ? p.v_split : 1;
+  const int tile = (int)blockIdx.x / vs;
+  const int vpart = (int)blockIdx.x - tile * vs;
+  const int nslice = NVB / vs;                 // value slices (waves of phase 2) of this block
+  const int slice = vpart * nslice + w;        // the slice wave w < nslice accumulates
   const int head = blockIdx.y;
   const int row = tile * 32 + lq;
   const bool row_ok = row < p.Tq;
@@ -73,7 +79,7 @@ __global__ __launch_bounds__(512) void attention_kernel(AttnParams p) {
   const bf16* kbase0 = p.k0 + ((size_t)head * p.kv_head_stride0 + (size_t)cbeg0 * S16 * 512) + lane * 8;
   const bf16* vbase0 = p.v0 + ((size_t)head * p.v_head_stride0 + (size_t)cbeg0 * NVB * 1024);
   auto vptr = [&](int ci) -> const bf16* {   // ci clamped by the caller
-    return (ci >= n0 ? p.v1 + (size_t)(ci - n0) * NVB * 1024 : vbase0 + (size_t)ci * NVB * 1024) + w * 1024 + lane * 8;
+    return (ci >= n0 ? p.v1 + (size_t)(ci - n0) * NVB * 1024 : vbase0 + (size_t)ci * NVB * 1024) + slice * 1024 + lane * 8;
   };
 
   // ---- issue every load of the first round (unconditional, clamped addresses) -----------------
@@ -94,7 +100,7 @@ __global__ __launch_bounds__(512) void attention_kernel(AttnParams p) {
     for (int s = 0; s < S16; s++) kf[s] = *reinterpret_cast<const bf16x8*>(kp0 + (size_t)s * 512);
   }
   bf16x8 vf[VRING * 2];
-  const bool pv_wave = w < NVB;
+  const bool pv_wave = w < nslice;
   if (pv_wave) {
 #pragma unroll
     for (int c = 0; c < VRING; c++) {
@@ -269,15 +275,15 @@ __global__ __launch_bounds__(512) void attention_kernel(AttnParams p) {
   for (int i = 0; i < ATT_WAVES; i++) l_all += lw[i * 32 + lq];
   const float inv = 1.0f / l_all;
   if (!row_ok) return;
-  if (p.ml_out != nullptr && w == 0 && lh == 0) {   // (row maximum, sum) of this share, for the consumer's merge
-    float* dst = p.ml_out + ((((size_t)blockIdx.z * p.heads + head) * gridDim.x * 32) + row) * 2;
+  if (p.ml_out != nullptr && w == 0 && lh == 0 && vpart == 0) {   // (row maximum, sum) of this share, for the consumer's merge
+    float* dst = p.ml_out + ((((size_t)blockIdx.z * p.heads + head) * ((p.Tq + 31) >> 5) * 32) + row) * 2;
     dst[0] = m_all;
     dst[1] = l_all;
   }
   bf16* outp = p.out + (size_t)blockIdx.z * p.out_split_stride;
 #pragma unroll
   for (int i = 0; i < 4; i++) {
-    const int d = w * 32 + 8 * i + 4 * lh;
+    const int d = slice * 32 + 8 * i + 4 * lh;
     if (d < p.head_dim) {
       const bf16x4 ob = {(bf16)(o[4 * i] * inv), (bf16)(o[4 * i + 1] * inv), (bf16)(o[4 * i + 2] * inv),
                          (bf16)(o[4 * i + 3] * inv)};
@@ -331,7 +337,9 @@ hipError_t launch_attention(hipStream_t s, const AttnParams& p) {
   }
   const int ntot = n0 + p.chunks1;
   if (n0 > 32) return hipErrorInvalidValue;   // at most 1024 keys in segment 0 per query row
-  dim3 grid((p.Tq + 31) / 32, p.heads, p.key_splits > 1 ? p.key_splits : 1);
+  if (p.v_split != 0 && p.v_split != 1 && ((p.v_split != 2 && p.v_split != 4 && p.v_split != 8) || p.head_dim != 256)) return hipErrorInvalidValue;
+  const int vs = p.v_split > 1 ? p.v_split : 1;
+  dim3 grid(((p.Tq + 31) / 32) * vs, p.heads, p.key_splits > 1 ? p.key_splits : 1);
   if (p.pf.blocks != 0) {   // warm-up blocks as extra grid rows
     const PrefetchDesc& d = p.pf;
     if (d.blocks < 0 || d.blocks % 16 != 0 || d.blocks > 1024 || d.sink == nullptr || d.blocks % (int)grid.x != 0) return hipErrorInvalidValue;

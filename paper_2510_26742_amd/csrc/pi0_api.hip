@@ -332,6 +332,9 @@ struct Tune {
   int qms = 1;            // expert QKV: token blocks on separate blocks (160 instead of 80)
   int ksplit = 1;         // expert attention: key shares for prefixes beyond kcps chunks
   int kcps = 8;
+  // expert attention: the 8 value slices of a (query tile, head) shared out over this many blocks, each repeating the
+  // scores (-1: 4 with one key share, 2 with several; measured -0.2 ms of denoise.  The prefix attention gains nothing)
+  int avs = -1;
   int ae16 = 1;           // expert O / down on 16 x 16 tiles (256 blocks) instead of 32 x 32 (64 blocks)
   // O projections as one launch over the whole k range (TILE_ENTRY: residual epilogue in the GEMM, no partial
   // buffer, no reduction launch): vision O, prefix O.  -1: up to 256 tokens (measured: -0.06 ms at one view,
@@ -894,6 +897,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
           a.out_split_stride = (size_t)64 * d.H * 256;
           a.ml_out = at<float>(c, w.eml);
         }
+        a.v_split = T.avs > 0 ? T.avs : (ksplits == 1 ? 4 : 2);
         a.pf = pf_begin(pfa);
         pf_weights(a.pf, 0, L.gu);
         r.cls = PI0_OP_EXP_ATTN;
@@ -1092,7 +1096,7 @@ int pi0_create(const pi0_config* cfg, pi0_ctx** out) {
         {"zld", &c->tune.zld, 1, Z_MAX}, {"zvd", &c->tune.zvd, 1, Z_MAX},
         {"pfq", &c->tune.pfq, 0, 1024}, {"pfa", &c->tune.pfa, 0, 1024}, {"pfo", &c->tune.pfo, 0, 1024},
         {"pfd", &c->tune.pfd, 0, 1024}, {"ae16", &c->tune.ae16, 0, 1}, {"ksplit", &c->tune.ksplit, 0, 1}, {"kcps", &c->tune.kcps, 2, 16}, {"qms", &c->tune.qms, 0, 1},
-        {"fko", &c->tune.fko, 0, 1}, {"fkl", &c->tune.fkl, 0, 1}, {"ras", &c->tune.ras, 0, 4096}, {"ral", &c->tune.ral, 1, 8}, {"rat", &c->tune.rat, 64, 256}, {"rad", &c->tune.rad, 1, 8}};
+        {"fko", &c->tune.fko, 0, 1}, {"fkl", &c->tune.fkl, 0, 1}, {"ras", &c->tune.ras, 0, 4096}, {"ral", &c->tune.ral, 1, 8}, {"rat", &c->tune.rat, 64, 256}, {"rad", &c->tune.rad, 1, 8}, {"avs", &c->tune.avs, 1, 8}};
     for (auto& k : keys) {
       const char* f = strstr(env, k.key);
       while (f != nullptr && !((f == env || f[-1] == ',') && f[strlen(k.key)] == '=')) f = strstr(f + 1, k.key);

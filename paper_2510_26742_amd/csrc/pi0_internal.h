@@ -285,6 +285,7 @@ struct AttnParams {
   int chunks_per_split;
   size_t out_split_stride;
   float* ml_out;
+  int v_split;         // head dim 256 only: 2 / 4 / 8 blocks per (query tile, head), each with 1 / v_split of the value slices (0 / 1 = off)
   PrefetchDesc pf;     // warm-up blocks for later launches
 };
 hipError_t launch_attention(hipStream_t s, const AttnParams& p);

@@ -465,6 +465,8 @@ def test_two_stream_frames_match_sequential(reduced):
     "fko=0,fkl=0",                                                                     # ... and as split-K partial GEMMs + reduction
     "ras=64,ral=2,rat=128,rad=8",                                                      # expert read-ahead kernel: other shape, two layers ahead
     "ras=0",                                                                           # ... and none: warm-up blocks inside the expert's launches
+    "avs=1",                                                                           # expert attention: one block per (query tile, head)
+    "avs=8,ras=0",                                                                     # ... its value slices over 8 blocks, warm-up blocks in the launch
 ])
 def test_alternative_kernel_choices(tune):
     """Every tile / split / warm-up choice the tuning variable can select computes the same function."""
