@@ -331,15 +331,15 @@ def test_read_ahead_kernel_follows_its_counter_and_gives_up_when_it_stalls():
     dev = torch.device("cuda:0")
     stream = torch.cuda.Stream(device=dev)
     g = torch.Generator().manual_seed(5)
-    host = torch.randint(-2 ** 31, 2 ** 31 - 1, ((64 << 20) // 4,), dtype=torch.int32, generator=g)
+    host = torch.randint(-2 ** 31, 2 ** 31 - 1, ((256 << 20) // 4,), dtype=torch.int32, generator=g)
     buf = host.to(dev)
     sink = torch.zeros(1024, dtype=torch.int32, device=dev)
     prog = torch.zeros(1, dtype=torch.int32, device=dev)
     torch.cuda.synchronize()
     say("[gpu] pi0_read_ahead_probe, unpaced")
     binding.pi0_read_ahead_probe(buf, 8, 4, 32, prog, 100000, 256, sink, stream)              # first launch: code upload
-    ms_free = binding.pi0_read_ahead_probe(buf, 8, 4, 32, prog, 100000, 256, sink, stream)    # lead 32 of 32: 4 x 64 MiB, no waits
-    say(f"[read-ahead] 256 MiB unpaced: {ms_free:.3f} ms ({0.268 / ms_free:.2f} TB/s)")
+    ms_free = binding.pi0_read_ahead_probe(buf, 8, 4, 32, prog, 100000, 256, sink, stream)    # lead 32 of 32: 4 x 256 MiB, no waits
+    say(f"[read-ahead] 1 GiB unpaced: {ms_free:.3f} ms ({1.074 / ms_free:.2f} TB/s)")
     assert 0.03 < ms_free < 20.0
     # a compute stream that is far ahead: every slice is skipped
     prog.fill_(1 << 20)
@@ -372,7 +372,7 @@ def test_read_ahead_kernel_follows_its_counter_and_gives_up_when_it_stalls():
     assert ms_4 < 0.9
     assert torch.equal(buf.cpu(), host) and int(sink.abs().sum()) == 0 and int(prog.item()) == 6
     with pytest.raises(binding.Pi0Error):
-        binding.pi0_read_ahead_probe(buf, 7, 1, 1, prog, 1000, 256, sink, stream)               # 64 MiB is not 7 * 16 * n
+        binding.pi0_read_ahead_probe(buf, 7, 1, 1, prog, 1000, 256, sink, stream)               # 256 MiB is not 7 * 16 * n
 
 
 def test_mxfp8_prefix_mlp_against_mxfp8_oracle(reduced):
