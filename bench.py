@@ -22,9 +22,9 @@ if ROOT not in sys.path:
 
 # HBM-side bytes per launch of an operation class, where a counter run exists (2 x FETCH_SIZE + WRITE_SIZE,
 # calibrated against a copy kernel)
-PMC_TRAFFIC_BYTES = {   # profiles/counters_full_pi0_1view_eager_pass.txt (expert launches: includes what they read ahead)
-    "exp_down": 19167232, "exp_gateup": 18705408, "exp_o": 15749120, "exp_qkv": 11334656, "exp_attn": 20127129,
-    "exp_out": 259788,
+PMC_TRAFFIC_BYTES = {   # profiles/counters_full_pi0_1view_eager_pass.txt
+    "exp_down": 13596672, "exp_gateup": 18720768, "exp_o": 7324672, "exp_qkv": 7132160, "exp_attn": 3123200,
+    "exp_out": 257126,
     "llm_gateup": 152385331, "llm_down": 167919001, "llm_qkv": 21047296, "llm_o": 22289612, "vis_qkv": 38654156,
     "vis_o": 13193216, "vis_up": 17787699, "vis_down": 32711680, "vis_proj": 12871680, "vis_patch": 5421056,
 }
@@ -48,8 +48,9 @@ def main() -> int:
     args = ap.parse_args()
     if args.counters_pass:
         # counter collection runs one kernel at a time, so the expert's read-ahead kernel (a second stream beside
-        # the compute launches) would only wait out its bound: this pass uses the warm-up blocks inside the launches
-        os.environ["PI0_TUNE"] = ",".join(x for x in (os.environ.get("PI0_TUNE", ""), "ras=0") if x)
+        # the compute launches) would only wait out its bound: this pass runs without it and without warm-up blocks
+        # inside the launches, so that every launch's counters are its own traffic
+        os.environ["PI0_TUNE"] = ",".join(x for x in (os.environ.get("PI0_TUNE", ""), "ras=0,pfq=0,pfa=0,pfo=0,pfd=0") if x)
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (batch-1 latency path, no sharding); use --gpus 1",
               file=sys.stderr)
