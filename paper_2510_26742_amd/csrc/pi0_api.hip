@@ -343,9 +343,9 @@ struct Tune {
   // read-ahead for the expert as one kernel on a second stream beside the compute launches: number of its
   // blocks (0 = warm-up blocks inside the launches instead, see pfq .. pfd), layer-steps it runs ahead,
   // threads per block, loads in flight per lane.  Measured optimum: one 4-wave block per CU (a second wave
-  // per SIMD no longer fits beside the compute kernels' registers), 4 loads in flight (more reads the
+  // per SIMD no longer fits beside the compute kernels' registers), 6 loads in flight (more reads the
   // layer in a shorter burst that disturbs the compute launches, fewer arrives late), one layer ahead.
-  int ras = 256, ral = 1, rat = 256, rad = 4;
+  int ras = 256, ral = 1, rat = 256, rad = 6;
 };
 
 struct pi0_ctx {
