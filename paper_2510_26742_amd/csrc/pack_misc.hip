@@ -383,23 +383,34 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
     if (go == 0) break;
     if (go == 2) continue;
     const int layer = i % p.layers;
+    // The layer's ranges as one virtual range of `total` bytes (below 4 GiB, checked by the host), walked in batches
+    // of RA_DEPTH loads per lane: the word at virtual offset v lies in the last range r with cum[r] <= v.  Offsets past
+    // the end are clamped to the last word (a repeated load, no branch).
+    const unsigned char* lbase[RA_REGIONS];
+    unsigned cum[RA_REGIONS + 1];
+    cum[0] = 0u;
 #pragma unroll
     for (int r = 0; r < RA_REGIONS; r++) {
-      // uniform base + 32-bit byte offset per lane (a region is far below 4 GiB); RA_DEPTH loads in flight
-      // per lane, offsets past the end clamped to the last word (a repeated load, no branch)
-      const unsigned char* base = p.base[r] + (size_t)layer * p.layer_stride[r];
-      const unsigned end = p.n16[r] * 16u;
-      if (end == 0u) continue;
-      // overtaken in the middle of the slice: leave the rest of it (every lane of the wave reads the same word)
-      if (r > 0 && __hip_atomic_load(p.progress, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= i + 2) break;
-      for (unsigned o0 = tid * 16u; o0 < end; o0 += RA_DEPTH * nth * 16u) {
-        uint4 v[RA_DEPTH];
+      lbase[r] = p.base[r] + (size_t)layer * p.layer_stride[r];
+      cum[r + 1] = cum[r] + p.n16[r] * 16u;
+    }
+    const unsigned total = cum[RA_REGIONS];
+    for (unsigned o0 = tid * 16u; o0 < total; o0 += RA_DEPTH * nth * 16u) {
+      // overtaken in the middle of the layer: leave the rest of it (every lane of the wave reads the same word)
+      if (o0 != tid * 16u && __hip_atomic_load(p.progress, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= i + 2) break;
+      uint4 v[RA_DEPTH];
 #pragma unroll
-        for (int k = 0; k < RA_DEPTH; k++)
-          v[k] = *reinterpret_cast<const uint4*>(base + min(o0 + (unsigned)k * nth * 16u, end - 16u));
+      for (int k = 0; k < RA_DEPTH; k++) {
+        const unsigned vo = min(o0 + (unsigned)k * nth * 16u, total - 16u);
+        const unsigned char* ptr = lbase[0] + vo;
 #pragma unroll
-        for (int k = 0; k < RA_DEPTH; k++) acc ^= v[k].x ^ v[k].y ^ v[k].z ^ v[k].w;
+        for (int r = 1; r < RA_REGIONS; r++) {
+          if (vo >= cum[r]) ptr = lbase[r] + (vo - cum[r]);
+        }
+        v[k] = *reinterpret_cast<const uint4*>(ptr);
       }
+#pragma unroll
+      for (int k = 0; k < RA_DEPTH; k++) acc ^= v[k].x ^ v[k].y ^ v[k].z ^ v[k].w;
     }
   }
   if (acc == 0x9e3779b9u) p.sink[tid & 1023] = acc;
@@ -408,8 +419,10 @@ hipError_t launch_read_ahead(hipStream_t st, const ReadAheadParams& p, int block
   if (blocks < 1 || blocks > 4096 || (threads != 64 && threads != 128 && threads != 256) || p.progress == nullptr ||
       p.sink == nullptr || p.lead < 1 || p.layers < 1 || p.steps < 1 || p.wait_ticks < 1)
     return hipErrorInvalidValue;
+  size_t words = 0;
+  for (int r = 0; r < RA_REGIONS; r++) words += p.n16[r];
+  if (words == 0 || words >= ((size_t)1 << 27)) return hipErrorInvalidValue;   // byte offsets over a whole layer are 32-bit in the kernel
   for (int r = 0; r < RA_REGIONS; r++) {
-    if (p.n16[r] >= (1u << 27)) return hipErrorInvalidValue;   // byte offsets are 32-bit in the kernel
     if (p.n16[r] != 0 && (p.base[r] == nullptr || (reinterpret_cast<uintptr_t>(p.base[r]) & 15) != 0 || p.layer_stride[r] % 16 != 0))
       return hipErrorInvalidValue;
   }
