@@ -453,6 +453,33 @@ def test_two_stream_frames_match_sequential(reduced):
     np.testing.assert_array_equal(out.cpu().numpy(), ref[k - 1])
 
 
+def test_reading_ahead_changes_no_bit():
+    """The expert's read-ahead kernel and the warm-up blocks only load: the actions of a pass with either of them,
+    with neither, and with another shape of the read-ahead kernel are the same bits (graph replay and eager)."""
+    import os
+    outs = {}
+    for tune in ("", "ras=0", "ras=0,pfq=0,pfa=0,pfo=0,pfd=0", "ras=128,rat=128,rad=3,ral=2"):
+        if tune:
+            os.environ["PI0_TUNE"] = tune
+        try:
+            case = Case(synth.reduced_config(vocab=1024))
+        finally:
+            os.environ.pop("PI0_TUNE", None)
+        try:
+            img, st, nz, ids = case.inputs(2, 16)
+            a = case.infer(img, st, nz, ids)
+            b = case.infer(img, st, nz, ids)          # replay
+            case.m.pi0_set_graph_mode(False)
+            c = case.infer(img, st, nz, ids)          # eager
+            np.testing.assert_array_equal(a, b)
+            np.testing.assert_array_equal(a, c)
+            outs[tune] = a
+        finally:
+            case.close()
+    for tune, a in outs.items():
+        np.testing.assert_array_equal(a, outs[""], err_msg=f"PI0_TUNE={tune}")
+
+
 @pytest.mark.parametrize("tune", [
     "ae16=0,qms=0,ksplit=0,pfq=0,pfa=0,pfo=0,pfd=0,lgu=0,ld=0",                        # 32x32 expert tiles, no warm-up, no key shares, 256x128 gate||up and down
     "vis=0,vqkv=0,vup=0,lqkv=0,lgu=1,vo=0,vd=0,lo=0,ld=1,zvo=6,zvd=17,zlo=8,zld=4",    # the other tile of every prefill GEMM
