@@ -455,10 +455,11 @@ def test_two_stream_frames_match_sequential(reduced):
 
 def test_reading_ahead_changes_no_bit():
     """The expert's read-ahead kernel and the warm-up blocks only load: the actions of a pass with either of them,
-    with neither, and with another shape of the read-ahead kernel are the same bits (graph replay and eager)."""
+    with neither, and with another shape of the read-ahead kernel are the same bits (graph replay and eager).  So are
+    they with the value slices of the expert attention on one block or on eight: every block repeats the same scores."""
     import os
     outs = {}
-    for tune in ("", "ras=0", "ras=0,pfq=0,pfa=0,pfo=0,pfd=0", "ras=128,rat=128,rad=3,ral=2"):
+    for tune in ("", "ras=0", "ras=0,pfq=0,pfa=0,pfo=0,pfd=0", "ras=128,rat=128,rad=3,ral=2", "avs=1", "avs=8"):
         if tune:
             os.environ["PI0_TUNE"] = tune
         try:
