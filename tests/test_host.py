@@ -210,6 +210,36 @@ def test_kernel_count_and_taps(L):
     assert binding.pi0_debug_taps_elems(cfg, 1, 0) == exp
 
 
+def test_tuning_variable_is_parsed_by_key_and_range(L):
+    """PI0_TUNE is read at pi0_create: whole keys only (`vo` is not found inside `zvo`), values outside a key's range
+    are ignored, unknown keys do nothing.  Seen through the launch count: a one-launch O projection drops a reduction
+    launch per layer, the plain expert QKV / 32 x 32 expert tiles change nothing in the count."""
+    import os
+    cfg = synth.full_config()
+    c = binding.to_c_config(cfg)
+
+    def count(tune, views=1):
+        if tune is not None:
+            os.environ["PI0_TUNE"] = tune
+        try:
+            ctx = ctypes.c_void_p()
+            assert L.pi0_create(ctypes.byref(c), ctypes.byref(ctx)) == 0
+        finally:
+            os.environ.pop("PI0_TUNE", None)
+        n = L.pi0_kernel_count(ctx, views, 0)
+        L.pi0_destroy(ctx)
+        return n
+    base = count(None)
+    vis, llm = cfg.vis_layers, cfg.llm_layers - 1
+    assert count("") == base and count("nonsense=3,,=,x") == base
+    assert count("fko=0") == base + vis and count("fkl=0") == base + llm and count("fko=0,fkl=0") == base + vis + llm
+    assert count("fko=7") == base and count("fko=-1") == base            # out of range: ignored
+    assert count("xfko=0") == base and count("fko0=0") == base           # not the key
+    assert count("zvo=1,fko=0") == base + vis                            # a key after another one
+    assert count("fko=1,fkl=1", views=2) == count(None, views=2) - vis - llm
+    assert count("ras=0") == base and count("ras=4096,rad=8,ral=8,avs=8,qms=0,ae16=0") == base
+
+
 # ---------------------------------------------------------------------------- roofline pins
 def test_roofline_reproduces_table2_and_section5():
     cfg = synth.full_config()
