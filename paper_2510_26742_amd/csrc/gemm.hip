@@ -565,15 +565,7 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
   const bf16* xbase = p.X + (size_t)(kbeg >> 4) * 512 + lane * 8;
   const int mb_last = p.M > 32 ? 1 : 0;        // last token block (clamps when M <= 32)
   const int mb_first = MS ? min((int)blockIdx.z, mb_last) : 0;   // global index of local token block 0
-#pragma unroll
-  for (int i = 0; i < 8; i++) {
-    const int st = min(w * 8 + i, n16 - 1);    // clamped: steps beyond the range are never used
-    wf[i] = *reinterpret_cast<const bf16x8*>(wbase + (size_t)st * 512);
-#pragma unroll
-    for (int mb = 0; mb < NMB; mb++)
-      xf[mb][i] = *reinterpret_cast<const bf16x8*>(xbase + ((size_t)min(mb_first + mb, mb_last) * XKC16 + st) * 512);
-  }
-  // statistics partials: issued behind the operand loads (same round trip), clamped and unconditional
+  // statistics partials: issued ahead of the operand loads (same round trip), clamped and unconditional
   float2 sp[8];
   if (PRO != PRO_NONE) {
 #pragma unroll
@@ -581,6 +573,14 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
       const int j = min(w + SK_WAVES * jj, p.rowstat_parts - 1);
       sp[jj] = *reinterpret_cast<const float2*>(p.rowstat + ((size_t)j * 64 + lane) * 2);
     }
+  }
+#pragma unroll
+  for (int i = 0; i < 8; i++) {
+    const int st = min(w * 8 + i, n16 - 1);    // clamped: steps beyond the range are never used
+    wf[i] = *reinterpret_cast<const bf16x8*>(wbase + (size_t)st * 512);
+#pragma unroll
+    for (int mb = 0; mb < NMB; mb++)
+      xf[mb][i] = *reinterpret_cast<const bf16x8*>(xbase + ((size_t)min(mb_first + mb, mb_last) * XKC16 + st) * 512);
   }
   // operands of the epilogue, in the same round trip.  The tile of a token block is finished by PIECES waves, each
   // taking 4 / PIECES of its four 8-feature steps (finishing wave f: token block f / PIECES, piece f % PIECES): the
