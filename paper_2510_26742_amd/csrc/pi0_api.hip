@@ -326,8 +326,8 @@ struct Tune {
   int lgu = -1;           // prefix gate||up (-1: 128, 192 or 256 tokens x 256 features, whichever fills the 256 CUs at the least cost)
   int vo = TILE_MID, vd = -1, lo = -1, ld = TILE_WIDE128;   // split-K partial GEMMs: vision O / down, prefix O / down
   int zvo = -1, zlo = -1, zld = -1, zvd = -1;   // -1: chosen from the number of tokens (measured optima at 1 / 2 / 3 views)
-  // warm-up blocks carried by the expert's launches (0 = none): QKV, attention, O, down.  Used where the read-ahead
-  // kernel below is not (two-stream frames, ras=0)
+  // warm-up blocks carried by the expert's launches (0 = none): QKV, attention, O, down.  Used instead of the read-ahead
+  // kernel below with ras=0
   int pfq = 64, pfa = 64, pfo = 128, pfd = 128;
   int qms = 1;            // expert QKV: token blocks on separate blocks (160 instead of 80)
   int ksplit = 1;         // expert attention: key shares for prefixes beyond kcps chunks
@@ -384,7 +384,8 @@ struct Run {
   int launches = 0;
   hipError_t err = hipSuccess;
   int slot_w = 0, slot_r = 0;   // cache copy the prefill writes / the denoise reads
-  bool read_ahead = true;       // expert: read-ahead kernel on a second stream (else warm-up blocks inside the launches)
+  bool read_ahead = true;       // expert: read ahead of the compute launches (read-ahead kernel on a second stream, or warm-up
+                                // blocks inside the launches with PI0_TUNE=ras=0); false: neither
   int cls = PI0_OP_MISC;        // class of the launches that follow
   OpTimer* timer = nullptr;     // when set, every RUN / RUN_GEMM launch is bracketed by an event pair
   bool ok() const { return err == hipSuccess; }
@@ -782,7 +783,9 @@ void run_denoise(Run& r, int P, Taps* taps) {
     const size_t st = w.exp[1].qkv.w - w.exp[0].qkv.w;
     ras = B.qkv.w - A.qkv.w == st && B.o.w - A.o.w == st && B.gu.w - A.gu.w == st && B.down.w - A.down.w == st && st % 16 == 0;
   }
-  const int pfq = ras ? 0 : T.pfq, pfa = ras ? 0 : T.pfa, pfo = ras ? 0 : T.pfo, pfd = ras ? 0 : T.pfd;
+  // warm-up blocks inside the launches only where the read-ahead kernel was asked for but is not used (ras=0)
+  const bool pfb = r.read_ahead && !ras;
+  const int pfq = pfb ? T.pfq : 0, pfa = pfb ? T.pfa : 0, pfo = pfb ? T.pfo : 0, pfd = pfb ? T.pfd : 0;
   if (ras && !r.count_only && r.ok()) {
     ReadAheadParams ra;
     memset(&ra, 0, sizeof(ra));
@@ -1396,9 +1399,10 @@ int pi0_stream_frame(pi0_ctx* c, const float* d_images, int n_views, const int32
   if (e == hipSuccess) e = hipStreamWaitEvent(sd, c->ev_prefill[cur], 0);
   if (e == hipSuccess) e = stage_inputs(c, sd, nullptr, 0, nullptr, 0, d_state, d_noise);
   if (e != hipSuccess) return fail_hip(c, e);
-  // no read-ahead kernel here: it keeps a wave on every SIMD for the whole loop, and the prefill that runs beside
-  // this denoise has kernels whose waves take a SIMD's whole register file (they would wait for the loop's end;
-  // measured with it: frame interval +0.8 .. +1.2 ms)
+  // no reading ahead here.  The read-ahead kernel keeps a wave on every SIMD for the whole loop, and the prefill that
+  // runs beside this denoise has kernels whose waves take a SIMD's whole register file (they would wait for the loop's
+  // end; measured with it: frame interval +0.8 .. +1.2 ms); warm-up blocks inside the launches cost +0.2 .. +0.3 ms:
+  // the prefill already keeps the memory busy, and the expert's cold starts hide behind it
   rc = execute(c, KIND_DENOISE, c->cur_views, c->cur_prompt, sd, cur, cur, false);
   if (rc != PI0_OK) return rc;
   e = launch_copy_f32(sd, at<float>(c, c->wl.xa), d_actions, (size_t)c->cfg.chunk * c->d.A);
