@@ -44,10 +44,10 @@ typedef struct pi0_ctx pi0_ctx; /* opaque, host memory, owned by the library */
 typedef struct pi0_config {
   int32_t vis_layers;  /* 27   SigLIP blocks                                              */
   int32_t vis_width;   /* 1152 must be a multiple of 64                                   */
-  int32_t vis_heads;   /* 16   head dim = vis_width / vis_heads (72), multiple of 4, <= 80 */
+  int32_t vis_heads;   /* 16   head dim = vis_width / vis_heads (72), multiple of 4, 68 .. 80 */
   int32_t vis_mlp;     /* 4304                                                            */
   int32_t img_size;    /* 224                                                             */
-  int32_t patch;       /* 14   tokens per view = (img_size/patch)^2 (256), multiple of 32 */
+  int32_t patch;       /* 14   tokens per view = (img_size/patch)^2 (256), multiple of 32, <= 256 */
   int32_t llm_layers;  /* 18                                                              */
   int32_t llm_width;   /* 2048                                                            */
   int32_t llm_q_heads; /* 8    query heads sharing one key/value head                     */
@@ -61,8 +61,8 @@ typedef struct pi0_config {
   int32_t chunk;       /* 63   chunk + 1 suffix tokens (state + actions) must be 64       */
   int32_t steps;       /* 10   Euler steps, t = 1 - k/steps, dt = -1/steps                */
   int32_t vocab;       /* rows of the prompt embedding table in the blob; 0 = no table    */
-  int32_t max_views;   /* 3                                                               */
-  int32_t max_prompt;  /* 48   (0 allowed)                                                */
+  int32_t max_views;   /* 3    1 .. 8                                                     */
+  int32_t max_prompt;  /* 48   (0 allowed); max_views * tokens per view + max_prompt <= 1024 */
 } pi0_config;
 
 enum {
@@ -179,89 +179,6 @@ int pi0_debug_forward(pi0_ctx* ctx, const float* d_images, int n_views, const in
                       float* d_taps, size_t cap_elems, void* hip_stream);
 
 /*
- * Operation classes of the pass, for per-class timing (the rows of Table 2 grouped by launch).
- */
-enum pi0_op_class {
-  PI0_OP_MISC = 0,        /* copies, patch extraction, embeddings, row statistics */
-  PI0_OP_VIS_PATCH,       /* patch embedding GEMM */
-  PI0_OP_VIS_QKV,         /* LayerNorm-folded QKV projection */
-  PI0_OP_VIS_ATTN,
-  PI0_OP_VIS_O,           /* split-K partial GEMM of the output projection */
-  PI0_OP_VIS_UP,
-  PI0_OP_VIS_DOWN,        /* split-K partial GEMM */
-  PI0_OP_VIS_PROJ,        /* final LayerNorm + projector */
-  PI0_OP_REDUCE,          /* split-K reductions (bias, residual, row statistics) of any stage */
-  PI0_OP_LLM_QKV,         /* RMSNorm-folded QKV + RoPE, writes the key/value cache */
-  PI0_OP_LLM_ATTN,
-  PI0_OP_LLM_O,
-  PI0_OP_LLM_GATEUP,
-  PI0_OP_LLM_DOWN,
-  PI0_OP_EXP_EMBED,       /* folded action/time embedding and its second linear layer */
-  PI0_OP_EXP_QKV,
-  PI0_OP_EXP_ATTN,
-  PI0_OP_EXP_O,
-  PI0_OP_EXP_GATEUP,
-  PI0_OP_EXP_DOWN,
-  PI0_OP_EXP_OUT,         /* final norm, output projection, Euler update */
-  PI0_OP_CLASSES
-};
-
-/*
- * Timing run: `passes` complete passes (as pi0_infer) launched eagerly with a HIP event pair
- * around every kernel launch on hip_stream.  Synchronises the stream, then adds the elapsed
- * microseconds and the launch count of every class to the HOST arrays h_class_us[PI0_OP_CLASSES]
- * and h_class_launches[PI0_OP_CLASSES] (both are overwritten).  Eager launches: each elapsed time
- * is the kernel's duration as the stream's timestamps see it, without graph-launch effects.
- * Errors as pi0_infer; ENOMEM if events cannot be created.
- */
-int pi0_debug_profile(pi0_ctx* ctx, const float* d_images, int n_views, const int32_t* d_prompt_ids,
-                      int n_prompt, const float* d_state, const float* d_noise, float* d_actions,
-                      int passes, double* h_class_us, int* h_class_launches, void* hip_stream);
-
-/*
- * Synchronisation-overhead micro-benchmark (Section 5.2, Table 3 of the paper; no ctx needed).
- * Applies x <- x + b to a 256 x 1024 fp32 array n_ops times per repetition, `reps` repetitions,
- * one 256-thread block per row, with consecutive updates ordered by
- *   PI0_SYNC_EAGER          n_ops separate kernel launches
- *   PI0_SYNC_GRAPH          one hipGraph of n_ops kernel nodes (captured on hip_stream, which must not be NULL)
- *   PI0_SYNC_BARRIER        one kernel, software grid barrier with relaxed atomics between updates
- *   PI0_SYNC_BARRIER_FENCE  same with release / acquire at device scope (what dependent data would need)
- *   PI0_SYNC_FUSED          one kernel, no synchronisation (the baseline)
- * d_x, d_b: device, float32 [256][1024], 16-byte aligned; afterwards x = x0 + reps * n_ops * b exactly
- * (for values that are exact in fp32).  d_state: device, 2 x uint32 scratch (cleared by the call).
- * h_ms: HOST, receives the milliseconds of one repetition (HIP events on hip_stream, averaged over
- * reps).  The call synchronises the stream.  Barrier waits are bounded: if one runs out, or the
- * device has fewer compute units than blocks, the result is PI0_ESTATE.  Other errors: EINVAL, EHIP.
- */
-enum pi0_sync_mode {
-  PI0_SYNC_EAGER = 0,
-  PI0_SYNC_GRAPH = 1,
-  PI0_SYNC_BARRIER = 2,
-  PI0_SYNC_BARRIER_FENCE = 3,
-  PI0_SYNC_FUSED = 4
-};
-int pi0_sync_bench(int mode, int n_ops, int reps, float* d_x, const float* d_b, unsigned* d_state,
-                   double* h_ms, void* hip_stream);
-
-/*
- * Attainable-peak micro-benchmarks (no ctx needed): what this device sustains on the two resources
- * the roofline of Section 5.1 prices operations by.
- *   PI0_PEAK_HBM_READ   streams `bytes` bytes at d_buf (device, 16-byte aligned, bytes a multiple of
- *                       16; give far more than the 256 MB last-level cache) through all compute units
- *                       with 16-byte loads; *h_result = GB/s (1e9 bytes per second).  iters unused.
- *   PI0_PEAK_MFMA_BF16  runs `iters` (1 .. 2^22) rounds of 4 independent 32x32x16 bf16 MFMAs per wave,
- *                       2 waves per SIMD on 256 compute units' worth of blocks, operands and
- *                       accumulators in registers, non-zero operands; *h_result = TFLOP/s.
- *                       d_buf / bytes unused.
- * One untimed launch, then `reps` (1 .. 1000) launches timed with HIP events on hip_stream; the call
- * synchronises the stream.  d_sink: device, one uint32 the kernels may write (never read back).
- * h_result: HOST.  Nothing is allocated on the device.  Errors: EINVAL, EHIP.
- */
-enum pi0_peak_kind { PI0_PEAK_HBM_READ = 0, PI0_PEAK_MFMA_BF16 = 1 };
-int pi0_peak_bench(int kind, const void* d_buf, size_t bytes, int iters, int reps, unsigned* d_sink,
-                   double* h_result, void* hip_stream);
-
-/*
  * Arithmetic of the prefix transformer's feed-forward GEMMs (gate||up and down; everything else stays bf16).
  * The paper runs everything in bf16 and names 8-bit multiplication as a direction (Section 9.1); the
  * reduced-precision mode is this library's reading of it and changes the numerics contract:
@@ -277,42 +194,8 @@ int pi0_peak_bench(int kind, const void* d_buf, size_t bytes, int iters, int rep
 enum pi0_precision { PI0_PRECISION_BF16 = 0, PI0_PRECISION_MXFP8_PREFIX_MLP = 1 };
 int pi0_set_precision(pi0_ctx* ctx, int precision);
 
-/*
- * Clock sample (no ctx needed): enqueues one single-lane kernel on hip_stream that writes d_out[0] = the shader
- * cycle counter and d_out[1] = the constant 100 MHz counter (d_out: device, 2 x int64, 8-byte aligned).  Two
- * samples around a piece of work on the same stream give the shader clock the device actually ran at:
- * (cycles_1 - cycles_0) / ((ticks_1 - ticks_0) * 10 ns) - the figure the published peaks (quoted at 2.4 GHz)
- * have to be scaled by.  The cycle counters of the chip's dies are not aligned with each other and the two sample
- * kernels may run on different dies, so the interval has to be long (>= 100 ms) for the offset not to matter.
- * Errors: EINVAL, EHIP.
- */
-int pi0_clock_sample(long long* d_out, void* hip_stream);
-
-/*
- * The read-ahead kernel that pi0_denoise runs beside the expert's compute launches (Section 5.2: prefetch across
- * synchronisation points), alone on hip_stream, over a caller's buffer (no ctx needed).  The buffer is cut into
- * `layers` equal slices; the kernel reads slice i % layers for i = 0 .. steps * layers - 1, each once the int32
- * counter *d_progress is >= i + 1 - lead (lead >= 1; nothing in this call ever writes the counter: whoever
- * sets it - the caller beforehand, or a kernel on another stream - sets the pace), and skips slice i when the
- * counter is already >= i + 2 (too late to be of use).  lead >= steps * layers reads everything without waiting;
- * a counter far ahead makes the kernel skip everything.  A block that waits longer than
- * wait_ticks (100 MHz wall-clock ticks) for the counter gives up and exits, which is what keeps the kernel from
- * hanging when its partner stream does not run: with a counter that never moves the call returns after about one
- * bound.  The loads change nothing anywhere.
- *   d_buf      device, 16-byte aligned, bytes a multiple of layers * 16, a slice below 2 GiB
- *   d_progress device int32      d_sink device, 1024 x uint32 (never written in practice)
- *   blocks     1 .. 1024 blocks of 256 threads      h_ms  HOST, elapsed milliseconds (the call synchronises)
- * Errors: EINVAL, EHIP.
- */
-int pi0_read_ahead_probe(const void* d_buf, size_t bytes, int layers, int steps, int lead, const int* d_progress,
-                         long long wait_ticks, int blocks, unsigned* d_sink, double* h_ms, void* hip_stream);
-
 /* Graph replay on (1, default) or off (0: every call launches kernels eagerly). */
 int pi0_set_graph_mode(pi0_ctx* ctx, int enabled);
-
-/* Number of kernel launches one pi0_infer issues on hip_stream for the given shape (0 on bad
- * arguments); the read-ahead kernel on the ctx's own stream is not counted. */
-int pi0_kernel_count(const pi0_ctx* ctx, int n_views, int n_prompt);
 
 /* Static, never-NULL description of an error code. */
 const char* pi0_strerror(int code);

@@ -15,7 +15,8 @@ LIB_PATH = os.path.join(_HERE, "libpi0_hip.so")
 
 EXPORTS = ["pi0_create", "pi0_destroy", "pi0_weights_bytes", "pi0_workspace_bytes", "pi0_load_weights",
            "pi0_prefill", "pi0_denoise", "pi0_infer", "pi0_debug_taps_elems", "pi0_debug_forward", "pi0_debug_profile", "pi0_sync_bench", "pi0_peak_bench", "pi0_clock_sample", "pi0_read_ahead_probe", "pi0_stream_frame",
-           "pi0_set_graph_mode", "pi0_set_precision", "pi0_kernel_count", "pi0_strerror", "pi0_last_hip_error"]
+           "pi0_set_graph_mode", "pi0_set_precision", "pi0_kernel_count", "pi0_strerror", "pi0_last_hip_error",
+           "pi0_sync_dep_bench", "pi0_tune"]
 
 # enum pi0_op_class, in order
 OP_CLASSES = ["misc", "vis_patch", "vis_qkv", "vis_attn", "vis_o", "vis_up", "vis_down", "vis_proj", "reduce",
@@ -77,6 +78,10 @@ def lib() -> ctypes.CDLL:
         L.pi0_stream_frame.restype = i32
         L.pi0_sync_bench.argtypes = [i32, i32, i32, vp, vp, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.pi0_sync_bench.restype = i32
+        L.pi0_sync_dep_bench.argtypes = [i32, i32, i32, i32, i32, vp, i32, vp, vp, ctypes.POINTER(ctypes.c_double), vp]
+        L.pi0_sync_dep_bench.restype = i32
+        L.pi0_tune.argtypes = [vp, ctypes.c_char_p]
+        L.pi0_tune.restype = i32
         L.pi0_peak_bench.argtypes = [i32, vp, sz, i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.pi0_peak_bench.restype = i32
         L.pi0_clock_sample.argtypes = [vp, vp]
@@ -138,6 +143,21 @@ def pi0_sync_bench(mode: str, n_ops: int, reps: int, d_x, d_b, d_state, stream=N
     return float(ms.value)
 
 
+BARRIERS = {"counter": 0, "xcd": 1, "flags": 2}
+SYNC_DATA = {"none": 0, "bypass": 1, "inv": 2, "fence": 3, "fresh": 4}
+
+
+def pi0_sync_dep_bench(barrier: str, data: str, fan: int, n_ops: int, reps: int, d_x, d_b, d_state, stream=None) -> float:
+    """Milliseconds of one repetition of n_ops updates x_{k+1}[r] = max_j x_k[r + j] + b[r] (d_x: [planes, 256, 1024])."""
+    ms = ctypes.c_double(0.0)
+    s = None if stream is None else int(stream.cuda_stream)
+    rc = lib().pi0_sync_dep_bench(BARRIERS[barrier], SYNC_DATA[data], int(fan), int(n_ops), int(reps), _ptr(d_x),
+                                  int(d_x.shape[0]), _ptr(d_b), _ptr(d_state), ctypes.byref(ms), s)
+    if rc != PI0_OK:
+        raise Pi0Error(rc)
+    return float(ms.value)
+
+
 def pi0_clock_sample(d_out, stream=None):
     """Enqueue a sample of (shader cycle counter, 100 MHz counter) into the int64[2] device tensor d_out."""
     s = None if stream is None else int(stream.cuda_stream)
@@ -183,7 +203,8 @@ def pi0_peak_bench(kind: str, d_buf, nbytes: int, iters: int, reps: int, d_sink,
 class Pi0:
     """Thin handle over pi0_ctx.  All tensor arguments are torch CUDA tensors (device memory)."""
 
-    def __init__(self, cfg):
+    def __init__(self, cfg, tune: Optional[str] = None):
+        """tune: kernel choices for tuning runs (pi0_tune); None takes the PI0_TUNE environment variable if set."""
         self.cfg = cfg
         self._c = to_c_config(cfg)
         self._ctx = ctypes.c_void_p()
@@ -191,6 +212,13 @@ class Pi0:
         if rc != PI0_OK:
             raise Pi0Error(rc)
         self.workspace = None
+        if tune is None:
+            tune = os.environ.get("PI0_TUNE")
+        if tune:
+            self.pi0_tune(tune)
+
+    def pi0_tune(self, spec: str):
+        self._check(lib().pi0_tune(self._ctx, spec.encode()))
 
     def close(self):
         if self._ctx:

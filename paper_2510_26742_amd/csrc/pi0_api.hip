@@ -26,7 +26,7 @@ bool derive_dims(const pi0_config& c, Dims& d) {
   if (c.vis_layers < 1 || c.llm_layers < 2 || c.exp_layers != c.llm_layers) return false;
   if (c.patch < 1 || c.img_size < c.patch || c.img_size % c.patch != 0) return false;
   d.T = (c.img_size / c.patch) * (c.img_size / c.patch);
-  if (d.T % 32 != 0) return false;
+  if (d.T % 32 != 0 || d.T > 256) return false;   // vision attention: one view's keys in one round of 8 chunks
   d.PD = c.patch * c.patch * 3;
   d.PDp = round_up(d.PD, 64);
   d.Dv = c.vis_width;
@@ -57,6 +57,7 @@ bool derive_dims(const pi0_config& c, Dims& d) {
   if (c.vocab < 0) return false;
   d.maxI = c.max_views * d.T;
   d.maxP = d.maxI + c.max_prompt;
+  if (d.maxP > 1024) return false;   // prefix / expert attention: at most 32 key chunks per query row
   d.maxPc = ceil_div(d.maxP, 32);
   d.maxpos = d.maxPc * 32 + d.S;
   d.Lv = c.vis_layers;
@@ -317,8 +318,8 @@ enum { KIND_PREFILL = 0, KIND_DENOISE = 1, KIND_INFER = 2 };
 }  // namespace
 
 // Per-shape tile choices (Section 4.1 of the paper tunes tiles per GEMM shape; these are the
-// gfx950 counterparts).  Overridable for tuning runs through the environment variable PI0_TUNE,
-// e.g. PI0_TUNE="vis=1,lqkv=1,lgu=0,vo=1,vd=1,lo=0,ld=0,zvo=6,zlo=8,zld=16".
+// gfx950 counterparts).  Overridable for tuning runs through pi0_tune,
+// e.g. "vis=1,lqkv=1,lgu=0,vo=1,vd=1,lo=0,ld=0,zvo=6,zlo=8,zld=16".
 struct Tune {
   int vis = TILE_MID;     // vision patch / projector (and QKV / up unless overridden below)
   int vqkv = -1, vup = -1; // vision QKV / up tile (-1: QKV on the entry kernel up to 256 tokens, else same as vis)
@@ -385,7 +386,7 @@ struct Run {
   hipError_t err = hipSuccess;
   int slot_w = 0, slot_r = 0;   // cache copy the prefill writes / the denoise reads
   bool read_ahead = true;       // expert: read ahead of the compute launches (read-ahead kernel on a second stream, or warm-up
-                                // blocks inside the launches with PI0_TUNE=ras=0); false: neither
+                                // blocks inside the launches with pi0_tune "ras=0"); false: neither
   int cls = PI0_OP_MISC;        // class of the launches that follow
   OpTimer* timer = nullptr;     // when set, every RUN / RUN_GEMM launch is bracketed by an event pair
   bool ok() const { return err == hipSuccess; }
@@ -1091,25 +1092,6 @@ int pi0_create(const pi0_config* cfg, pi0_ctx** out) {
   blob_layout(*cfg, d, c->bl);
   ws_layout(*cfg, d, c->wl);
 
-  if (const char* env = getenv("PI0_TUNE")) {
-    struct { const char* key; int* dst; int lo, hi; } keys[] = {
-        {"vis", &c->tune.vis, 0, 9},   {"lqkv", &c->tune.lqkv, 0, 9}, {"lgu", &c->tune.lgu, 0, 10},
-        {"vqkv", &c->tune.vqkv, -1, 9}, {"vup", &c->tune.vup, -1, 9},
-        {"vo", &c->tune.vo, 0, 9}, {"vd", &c->tune.vd, 0, 9}, {"lo", &c->tune.lo, 0, 9}, {"ld", &c->tune.ld, 0, 10}, {"zvo", &c->tune.zvo, 1, Z_MAX}, {"zlo", &c->tune.zlo, 1, Z_MAX},
-        {"zld", &c->tune.zld, 1, Z_MAX}, {"zvd", &c->tune.zvd, 1, Z_MAX},
-        {"pfq", &c->tune.pfq, 0, 1024}, {"pfa", &c->tune.pfa, 0, 1024}, {"pfo", &c->tune.pfo, 0, 1024},
-        {"pfd", &c->tune.pfd, 0, 1024}, {"ae16", &c->tune.ae16, 0, 1}, {"ksplit", &c->tune.ksplit, 0, 1}, {"kcps", &c->tune.kcps, 2, 16}, {"qms", &c->tune.qms, 0, 1},
-        {"fko", &c->tune.fko, 0, 1}, {"fkl", &c->tune.fkl, 0, 1}, {"ras", &c->tune.ras, 0, 4096}, {"ral", &c->tune.ral, 1, 8}, {"rat", &c->tune.rat, 64, 256}, {"rad", &c->tune.rad, 1, 8}, {"avs", &c->tune.avs, 1, 8}};
-    for (auto& k : keys) {
-      const char* f = strstr(env, k.key);
-      while (f != nullptr && !((f == env || f[-1] == ',') && f[strlen(k.key)] == '=')) f = strstr(f + 1, k.key);
-      if (f != nullptr) {
-        const int v = atoi(f + strlen(k.key) + 1);
-        if (v >= k.lo && v <= k.hi) *k.dst = v;
-      }
-    }
-    for (int* v : {&c->tune.pfq, &c->tune.pfa, &c->tune.pfo, &c->tune.pfd}) *v &= ~15;
-  }
   // RoPE table (Section 3.2: precomputed): angle = pos * 10000^(-i/128), pairs (i, i+128)
   c->h_rope.resize((size_t)d.maxpos * 128 * 2);
   for (int pos = 0; pos < d.maxpos; pos++) {
@@ -1163,6 +1145,33 @@ size_t pi0_workspace_bytes(const pi0_config* cfg) {
   WsLayout w;
   ws_layout(*cfg, d, w);
   return w.total;
+}
+
+int pi0_tune(pi0_ctx* c, const char* env) {
+  if (c == nullptr || env == nullptr) return PI0_EINVAL;
+  {
+    struct { const char* key; int* dst; int lo, hi; } keys[] = {
+        {"vis", &c->tune.vis, 0, 9},   {"lqkv", &c->tune.lqkv, 0, 9}, {"lgu", &c->tune.lgu, 0, 10},
+        {"vqkv", &c->tune.vqkv, -1, 9}, {"vup", &c->tune.vup, -1, 9},
+        {"vo", &c->tune.vo, 0, 9}, {"vd", &c->tune.vd, 0, 9}, {"lo", &c->tune.lo, 0, 9}, {"ld", &c->tune.ld, 0, 10}, {"zvo", &c->tune.zvo, 1, Z_MAX}, {"zlo", &c->tune.zlo, 1, Z_MAX},
+        {"zld", &c->tune.zld, 1, Z_MAX}, {"zvd", &c->tune.zvd, 1, Z_MAX},
+        {"pfq", &c->tune.pfq, 0, 1024}, {"pfa", &c->tune.pfa, 0, 1024}, {"pfo", &c->tune.pfo, 0, 1024},
+        {"pfd", &c->tune.pfd, 0, 1024}, {"ae16", &c->tune.ae16, 0, 1}, {"ksplit", &c->tune.ksplit, 0, 1}, {"kcps", &c->tune.kcps, 2, 16}, {"qms", &c->tune.qms, 0, 1},
+        {"fko", &c->tune.fko, 0, 1}, {"fkl", &c->tune.fkl, 0, 1}, {"ras", &c->tune.ras, 0, 4096}, {"ral", &c->tune.ral, 1, 8}, {"rat", &c->tune.rat, 64, 256}, {"rad", &c->tune.rad, 1, 8 /* 7: no such variant, see below */}, {"avs", &c->tune.avs, 1, 8}};
+    for (auto& k : keys) {
+      const char* f = strstr(env, k.key);
+      while (f != nullptr && !((f == env || f[-1] == ',') && f[strlen(k.key)] == '=')) f = strstr(f + 1, k.key);
+      if (f != nullptr) {
+        const int v = atoi(f + strlen(k.key) + 1);
+        if (v >= k.lo && v <= k.hi) *k.dst = v;
+      }
+    }
+    for (int* v : {&c->tune.pfq, &c->tune.pfa, &c->tune.pfo, &c->tune.pfd}) *v &= ~15;
+    if (c->tune.rad == 7) c->tune.rad = 6;   // the read-ahead kernel exists with 1 .. 6 and 8 loads in flight
+  }
+  for (auto& kv : c->graphs) (void)hipGraphExecDestroy(kv.second);
+  c->graphs.clear();
+  return PI0_OK;
 }
 
 int pi0_set_graph_mode(pi0_ctx* c, int enabled) {

@@ -8,7 +8,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "../../include/pi0.h"
+#include "../../include/pi0_bench.h"
 
 namespace {
 

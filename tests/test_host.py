@@ -22,10 +22,14 @@ def L():
 
 
 def test_header_symbols_are_exported(L):
-    hdr = open(os.path.join(ROOT, "include", "pi0.h")).read()
-    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    declared = sorted(set(re.findall(r"\b(pi0_[a-z_0-9]+)\s*\(", hdr)))
-    assert declared, "no declarations found"
+    declared = []
+    for name in ("pi0.h", "pi0_bench.h"):
+        hdr = open(os.path.join(ROOT, "include", name)).read()
+        hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+        found = set(re.findall(r"\b(pi0_[a-z_0-9]+)\s*\(", hdr))
+        assert found, f"no declarations found in {name}"
+        declared += sorted(found)
+    declared = sorted(set(declared))
     assert sorted(binding.EXPORTS) == declared
     for name in declared:
         assert hasattr(L, name), name
@@ -54,7 +58,10 @@ def test_full_model_sizes_are_plausible(L):
 def test_create_rejects_bad_geometry(L):
     good = synth.reduced_config()
     bad = [dict(head_dim=128), dict(chunk=31), dict(vis_width=1150), dict(exp_layers=3), dict(steps=0),
-           dict(max_views=0), dict(patch=15), dict(state_dim=33), dict(vis_heads=7), dict(llm_layers=1)]
+           dict(max_views=0), dict(patch=15), dict(state_dim=33), dict(vis_heads=7), dict(llm_layers=1),
+           dict(max_views=4, max_prompt=1),      # 1025 prefix tokens: beyond the attention kernels' 32 key chunks
+           dict(img_size=448),                   # 1024 tokens per view: beyond one round of the vision attention
+           dict(vis_heads=18)]                   # vision head dim 64: no such attention variant
     for kw in bad:
         c = binding.to_c_config(synth.dataclasses.replace(good, **kw))
         ctx = ctypes.c_void_p()
@@ -211,7 +218,7 @@ def test_kernel_count_and_taps(L):
 
 
 def test_tuning_variable_is_parsed_by_key_and_range(L):
-    """PI0_TUNE is read at pi0_create: whole keys only (`vo` is not found inside `zvo`), values outside a key's range
+    """pi0_tune parses whole keys only (`vo` is not found inside `zvo`), values outside a key's range
     are ignored, unknown keys do nothing.  Seen through the launch count: a one-launch O projection drops a reduction
     launch per layer, the plain expert QKV / 32 x 32 expert tiles change nothing in the count."""
     import os
@@ -219,13 +226,10 @@ def test_tuning_variable_is_parsed_by_key_and_range(L):
     c = binding.to_c_config(cfg)
 
     def count(tune, views=1):
+        ctx = ctypes.c_void_p()
+        assert L.pi0_create(ctypes.byref(c), ctypes.byref(ctx)) == 0
         if tune is not None:
-            os.environ["PI0_TUNE"] = tune
-        try:
-            ctx = ctypes.c_void_p()
-            assert L.pi0_create(ctypes.byref(c), ctypes.byref(ctx)) == 0
-        finally:
-            os.environ.pop("PI0_TUNE", None)
+            assert L.pi0_tune(ctx, tune.encode()) == 0
         n = L.pi0_kernel_count(ctx, views, 0)
         L.pi0_destroy(ctx)
         return n
