@@ -143,27 +143,44 @@ int pi0_kernel_count(const pi0_ctx* ctx, int n_views, int n_prompt);
  *                                 epoch published in one word per group and polled with back-off
  *            PI0_BARRIER_FLAGS    block i stores the epoch in word i; one wave per block polls all 256 words with
  *                                 one 16-byte load per lane; no read-modify-write
+ *            PI0_BARRIER_FLAGS8   the same with 8 copies of the flag array 4 KiB apart: a block stores into all of
+ *                                 them and polls copy (block index mod 8) only
+ *            PI0_BARRIER_GROUPADD one add without return value per block on its group's counter; everyone polls
+ *                                 the 8 group counters
+ *            PI0_BARRIER_XCC      as XCD with the real dies as groups (hardware die id): arrivals counted in the
+ *                                 die's own L2, one device-scope release per die instead of one per block
  *   data     PI0_SYNCDATA_NONE    no dependency: x[r] += b[r] in place (fan, planes ignored beyond validation)
  *            PI0_SYNCDATA_BYPASS  write-through stores, loads that bypass the L2 (device-scope instruction bits)
  *            PI0_SYNCDATA_INV     write-through stores, one cache invalidate per block after the wait, cached loads
  *            PI0_SYNCDATA_FENCE   ordinary stores / loads with device-scope release / acquire fences
  *            PI0_SYNCDATA_FRESH   write-through stores, cached loads, a never-read plane per update
  *                                 (needs planes >= n_ops + 1 and reps == 1)
+ *            PI0_SYNCDATA_WBACK   ordinary stores, loads that bypass the L2
+ *            (every dependent path releases at device scope between a block's stores and its arrival: without it
+ *            an arrival was observed to overtake the write-through data it announces)
  *   d_x      device, float32 [planes][256][1024], 16-byte aligned; update k reads plane k mod planes and writes
  *            plane (k + 1) mod planes, k counting on across repetitions (data NONE uses plane 0 only).  planes >= 2
  *            for the dependent data paths, at most 4096.
- *   d_b      device, float32 [256][1024].   d_state  device, 1024 x uint32 scratch, 16-byte aligned (cleared by the call).
+ *   d_b      device, float32 [256][1024].   d_state  device, 9216 x uint32 scratch, 16-byte aligned (cleared by the call).
  *   h_ms     HOST, milliseconds of one repetition of n_ops updates (HIP events on hip_stream; the call synchronises).
  * Every wait is bounded; PI0_ESTATE if one ran out or the device has fewer than 256 compute units.  Other
  * errors: EINVAL, EHIP.
  */
-enum pi0_barrier_kind { PI0_BARRIER_COUNTER = 0, PI0_BARRIER_XCD = 1, PI0_BARRIER_FLAGS = 2 };
+enum pi0_barrier_kind {
+  PI0_BARRIER_COUNTER = 0,
+  PI0_BARRIER_XCD = 1,
+  PI0_BARRIER_FLAGS = 2,
+  PI0_BARRIER_FLAGS8 = 3,
+  PI0_BARRIER_GROUPADD = 4,
+  PI0_BARRIER_XCC = 5
+};
 enum pi0_syncdata_kind {
   PI0_SYNCDATA_NONE = 0,
   PI0_SYNCDATA_BYPASS = 1,
   PI0_SYNCDATA_INV = 2,
   PI0_SYNCDATA_FENCE = 3,
-  PI0_SYNCDATA_FRESH = 4
+  PI0_SYNCDATA_FRESH = 4,
+  PI0_SYNCDATA_WBACK = 5
 };
 int pi0_sync_dep_bench(int barrier, int data, int fan, int n_ops, int reps, float* d_x, int planes, const float* d_b,
                        unsigned* d_state, double* h_ms, void* hip_stream);

@@ -143,8 +143,8 @@ def pi0_sync_bench(mode: str, n_ops: int, reps: int, d_x, d_b, d_state, stream=N
     return float(ms.value)
 
 
-BARRIERS = {"counter": 0, "xcd": 1, "flags": 2}
-SYNC_DATA = {"none": 0, "bypass": 1, "inv": 2, "fence": 3, "fresh": 4}
+BARRIERS = {"counter": 0, "xcd": 1, "flags": 2, "flags8": 3, "groupadd": 4, "xcc": 5}
+SYNC_DATA = {"none": 0, "bypass": 1, "inv": 2, "fence": 3, "fresh": 4, "wback": 5}
 
 
 def pi0_sync_dep_bench(barrier: str, data: str, fan: int, n_ops: int, reps: int, d_x, d_b, d_state, stream=None) -> float:

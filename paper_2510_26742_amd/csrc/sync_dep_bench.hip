@@ -16,6 +16,10 @@
 //            epoch in one word per group, which the group polls with s_sleep back-off
 //   FLAGS    no read-modify-write at all: block i stores the epoch in word i of a 1 KiB array, one
 //            wave per block polls the whole array with one 16-byte load per lane
+//   FLAGS8   the same with 8 copies of the array 4 KiB apart: a block stores into all 8 and polls one
+//   GROUPADD one add without return value per block on its group's counter, everyone polls the 8 counters
+//   XCC      as XCD, but the groups are the real dies (hardware register XCC_ID): arrivals are counted in
+//            the die's own L2, and only the last block of a die performs the device-scope release
 // Data paths (how update k+1 is made to see update k's rows)
 //   NONE     no dependency (own row, in place): the barrier alone, comparable with Table 3
 //   BYPASS   write-through stores and loads that bypass the die's L2 (device-scope bits on the
@@ -26,6 +30,10 @@
 //            language memory model (cache write-back + invalidate)
 //   FRESH    write-through stores, ordinary loads, and every update writes a plane that nobody has
 //            read before (planes >= n_ops + 1), so no cache can hold a stale copy
+//   WBACK    ordinary (write-back) stores, loads that bypass the L2; the release writes the lines back
+// Every dependent data path performs a device-scope release (cache write-back, which also waits for
+// write-through stores in flight) between a block's stores and its arrival: one per block, or - XCC - one
+// per die.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -47,8 +55,10 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsig
 }
 
 // state layout (unsigned words): [0] error flag, [32] counter, [64 + 32 g] group counters, [320] root counter,
-// [352 + 32 g] group epochs, [768 .. 1023] per-block flags
-enum { ST_ERR = 0, ST_CNT = 32, ST_GCNT = 64, ST_ROOT = 320, ST_GEPOCH = 352, ST_FLAGS = 768, ST_WORDS = 1024 };
+// [352 + 32 g] group epochs, [768 .. 1023] per-block flags,
+// [1024 + 1024 g + i] copy g of block i's flag (FLAGS8)
+enum { ST_ERR = 0, ST_CNT = 32, ST_GCNT = 64, ST_ROOT = 320, ST_GEPOCH = 352, ST_FLAGS = 768, ST_WORDS = 1024,
+       ST_MEMBERS = 640 /* + 32 x: blocks on die x */, ST_REP = 1024, ST_REP_STRIDE = 1024 /* words: 8 copies of the 256 flags, 4 KiB apart */, ST_ALL_WORDS = 1024 + 8 * 1024 };
 
 __device__ __forceinline__ unsigned ld_relaxed(const unsigned* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -59,8 +69,12 @@ __device__ __forceinline__ void st_relaxed(unsigned* p, unsigned v) {
 
 // Called by wave 0 of the block after the block's stores have completed (s_barrier behind vmcnt(0)).
 // epoch = number of the barrier, 1-based.  Returns when every block has arrived or the bound ran out.
-template <int BAR>
-__device__ __forceinline__ void grid_wait(unsigned* state, unsigned epoch, unsigned spin_limit) {
+// die (XCC) the calling wave runs on: bits 3:0 of hardware register XCC_ID (id 20)
+__device__ __forceinline__ unsigned xcc_id() { return (unsigned)__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 15u; }
+
+template <int BAR, int DATA>
+__device__ __forceinline__ void grid_wait(unsigned* state, unsigned epoch, unsigned spin_limit, unsigned xcc, unsigned members,
+                                          unsigned n_xcc) {
   const int lane = threadIdx.x & 63;
   const unsigned nblk = gridDim.x;
   if (BAR == PI0_BARRIER_COUNTER) {
@@ -90,6 +104,61 @@ __device__ __forceinline__ void grid_wait(unsigned* state, unsigned epoch, unsig
         if (++spins > spin_limit || ld_relaxed(&state[ST_ERR]) != 0u) { st_relaxed(&state[ST_ERR], 1u); break; }
       }
     }
+  } else if (BAR == PI0_BARRIER_XCC) {
+    // arrivals are counted inside the die (an atomic without device scope is performed in the die's own L2); the
+    // last block of a die releases the die's writes to memory ONCE for all of them, adds to the root counter at
+    // device scope, and the last die publishes the epoch per die
+    if (lane == 0) {
+      const unsigned old = __hip_atomic_fetch_add(&state[ST_GCNT + 32 * xcc], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      if (old + 1u == epoch * members) {
+        if (DATA != PI0_SYNCDATA_NONE) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        const unsigned oldr = __hip_atomic_fetch_add(&state[ST_ROOT], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (oldr + 1u == epoch * n_xcc) {
+          for (unsigned k = 0; k < 8u; k++) st_relaxed(&state[ST_GEPOCH + 32 * k], epoch);
+        }
+      }
+      unsigned spins = 0;
+      while (ld_relaxed(&state[ST_GEPOCH + 32 * xcc]) < epoch) {
+        __builtin_amdgcn_s_sleep(1);
+        if (++spins > spin_limit || ld_relaxed(&state[ST_ERR]) != 0u) { st_relaxed(&state[ST_ERR], 1u); break; }
+      }
+    }
+  } else if (BAR == PI0_BARRIER_GROUPADD) {
+    // arrivals: one fire-and-forget add per block on its group's counter; everybody polls the 8 counters
+    const unsigned g = blockIdx.x & 7u;
+    if (lane == 0) (void)__hip_atomic_fetch_add(&state[ST_GCNT + 32 * g], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned spins = 0;
+    while (true) {
+      bool ok = true;
+      if (lane < 8 && (unsigned)lane < nblk) {
+        const unsigned gsize = (nblk + 7u - (unsigned)lane) >> 3;
+        ok = ld_relaxed(&state[ST_GCNT + 32 * lane]) >= epoch * gsize;
+      }
+      if (__builtin_amdgcn_ballot_w64(!ok) == 0ull) break;
+      __builtin_amdgcn_s_sleep(1);
+      if (++spins > spin_limit || ld_relaxed(&state[ST_ERR]) != 0u) {
+        if (lane == 0) st_relaxed(&state[ST_ERR], 1u);
+        break;
+      }
+    }
+  } else if (BAR == PI0_BARRIER_FLAGS8) {
+    // block i stores the epoch in word i of 8 copies of the flag array (lanes 0..7, one store instruction); the
+    // blocks of group g = i mod 8 poll copy g only, so a copy has 32 pollers instead of 256
+    if (lane < 8) st_relaxed(&state[ST_REP + ST_REP_STRIDE * lane + blockIdx.x], epoch);
+    const __amdgpu_buffer_rsrc_t fr = make_rsrc(state + ST_REP + ST_REP_STRIDE * (blockIdx.x & 7u), 256 * 4);
+    unsigned spins = 0;
+    while (true) {
+      const u32x4 f = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(fr, lane * 16, 0, AUX_SC1));
+      bool ok = true;
+#pragma unroll
+      for (int j = 0; j < 4; j++) ok = ok && (f[j] >= epoch || (unsigned)(4 * lane + j) >= nblk);
+      if (__builtin_amdgcn_ballot_w64(!ok) == 0ull) break;
+      __builtin_amdgcn_s_sleep(1);
+      if (++spins > spin_limit || ld_relaxed(&state[ST_ERR]) != 0u) {
+        if (lane == 0) st_relaxed(&state[ST_ERR], 1u);
+        break;
+      }
+    }
   } else {   // FLAGS
     if (lane == 0) st_relaxed(&state[ST_FLAGS + blockIdx.x], epoch);
     const __amdgpu_buffer_rsrc_t fr = make_rsrc(state + ST_FLAGS, 256 * 4);
@@ -115,6 +184,23 @@ __global__ __launch_bounds__(256) void sync_dep_kernel(float* x, int planes, con
                                                        unsigned* state, unsigned spin_limit, unsigned epoch0) {
   const int r = blockIdx.x, t = threadIdx.x;
   const f32x4 bv = *reinterpret_cast<const f32x4*>(b + (size_t)r * COLS + 4 * t);
+  unsigned xcc = 0, members = 0, n_xcc = 0;
+  if (BAR == PI0_BARRIER_XCC) {
+    // who shares a die with whom: every block registers on its die's member counter (cleared by the host before each
+    // launch); one counter barrier later the counts are final
+    xcc = xcc_id() & 7u;
+    if (t == 0) {
+      __hip_atomic_fetch_add(&state[ST_MEMBERS + 32 * xcc], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_fetch_add(&state[ST_CNT], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      unsigned spins = 0;
+      while (ld_relaxed(&state[ST_CNT]) < gridDim.x) {
+        if (++spins > spin_limit || ld_relaxed(&state[ST_ERR]) != 0u) { st_relaxed(&state[ST_ERR], 1u); break; }
+      }
+    }
+    __syncthreads();
+    members = ld_relaxed(&state[ST_MEMBERS + 32 * xcc]);
+    for (unsigned k = 0; k < 8u; k++) n_xcc += ld_relaxed(&state[ST_MEMBERS + 32 * k]) != 0u ? 1u : 0u;
+  }
   for (int op = 0; op < n_ops; op++) {
     const int ps = (op0 + op) % planes, pd = (op0 + op + 1) % planes;
     const float* src = x + (size_t)ps * PLANE;
@@ -127,7 +213,7 @@ __global__ __launch_bounds__(256) void sync_dep_kernel(float* x, int planes, con
     } else {
       f32x4 in[MAX_FAN];
       const f32x4 ninf = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-      if (DATA == PI0_SYNCDATA_BYPASS) {
+      if (DATA == PI0_SYNCDATA_BYPASS || DATA == PI0_SYNCDATA_WBACK) {
         const __amdgpu_buffer_rsrc_t sr = make_rsrc(src, PLANE * 4);
 #pragma unroll
         for (int j = 0; j < MAX_FAN; j++) {
@@ -150,7 +236,7 @@ __global__ __launch_bounds__(256) void sync_dep_kernel(float* x, int planes, con
         for (int e = 0; e < 4; e++) v[e] = fmaxf(v[e], in[j][e]);
       }
       v += bv;
-      if (DATA == PI0_SYNCDATA_FENCE) {
+      if (DATA == PI0_SYNCDATA_FENCE || DATA == PI0_SYNCDATA_WBACK) {
         *reinterpret_cast<f32x4*>(dst + (size_t)r * COLS + 4 * t) = v;
       } else {
         const __amdgpu_buffer_rsrc_t dr = make_rsrc(dst, PLANE * 4);
@@ -162,8 +248,11 @@ __global__ __launch_bounds__(256) void sync_dep_kernel(float* x, int planes, con
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
       __syncthreads();
       if (t < 64) {
-        if (DATA == PI0_SYNCDATA_FENCE) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");   // write the die's dirty lines back
-        grid_wait<BAR>(state, epoch0 + (unsigned)op + 1u, spin_limit);
+        // device-scope release: the die's dirty lines are written back (FENCE) and - for every dependent data path -
+        // the write-through stores issued before are complete, not merely accepted, before the arrival is announced
+        // (without it an arrival was seen to overtake the data it announces)
+        if (DATA != PI0_SYNCDATA_NONE && BAR != PI0_BARRIER_XCC) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        grid_wait<BAR, DATA>(state, epoch0 + (unsigned)op + 1u, spin_limit, xcc, members, n_xcc);
         if (DATA == PI0_SYNCDATA_INV || DATA == PI0_SYNCDATA_FENCE) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
       }
       __syncthreads();
@@ -171,8 +260,8 @@ __global__ __launch_bounds__(256) void sync_dep_kernel(float* x, int planes, con
   }
 }
 
-__global__ void sync_dep_clear_kernel(unsigned* state) {
-  for (int i = threadIdx.x; i < ST_WORDS; i += blockDim.x) state[i] = 0u;
+__global__ void sync_dep_clear_kernel(unsigned* state, int first) {   // first = 1 keeps the error flag
+  for (int i = first + threadIdx.x; i < ST_ALL_WORDS; i += blockDim.x) state[i] = 0u;
 }
 
 template <int BAR>
@@ -184,6 +273,7 @@ void launch_dep(int data, hipStream_t s, float* x, int planes, const float* b, i
     case PI0_SYNCDATA_BYPASS: sync_dep_kernel<BAR, PI0_SYNCDATA_BYPASS><<<grid, block, 0, s>>>(x, planes, b, n_ops, op0, fan, state, spin_limit, epoch0); break;
     case PI0_SYNCDATA_INV: sync_dep_kernel<BAR, PI0_SYNCDATA_INV><<<grid, block, 0, s>>>(x, planes, b, n_ops, op0, fan, state, spin_limit, epoch0); break;
     case PI0_SYNCDATA_FENCE: sync_dep_kernel<BAR, PI0_SYNCDATA_FENCE><<<grid, block, 0, s>>>(x, planes, b, n_ops, op0, fan, state, spin_limit, epoch0); break;
+    case PI0_SYNCDATA_WBACK: sync_dep_kernel<BAR, PI0_SYNCDATA_WBACK><<<grid, block, 0, s>>>(x, planes, b, n_ops, op0, fan, state, spin_limit, epoch0); break;
     default: sync_dep_kernel<BAR, PI0_SYNCDATA_FRESH><<<grid, block, 0, s>>>(x, planes, b, n_ops, op0, fan, state, spin_limit, epoch0); break;
   }
 }
@@ -193,7 +283,7 @@ void launch_dep(int data, hipStream_t s, float* x, int planes, const float* b, i
 extern "C" int pi0_sync_dep_bench(int barrier, int data, int fan, int n_ops, int reps, float* d_x, int planes, const float* d_b,
                                   unsigned* d_state, double* h_ms, void* hip_stream) {
   if (d_x == nullptr || d_b == nullptr || d_state == nullptr || h_ms == nullptr) return PI0_EINVAL;
-  if (barrier < PI0_BARRIER_COUNTER || barrier > PI0_BARRIER_FLAGS || data < PI0_SYNCDATA_NONE || data > PI0_SYNCDATA_FRESH) return PI0_EINVAL;
+  if (barrier < PI0_BARRIER_COUNTER || barrier > PI0_BARRIER_XCC || data < PI0_SYNCDATA_NONE || data > PI0_SYNCDATA_WBACK) return PI0_EINVAL;
   if (n_ops < 1 || n_ops > 100000 || reps < 1 || reps > 1000 || fan < 1 || fan > MAX_FAN) return PI0_EINVAL;
   if (planes < 1 || planes > 4096) return PI0_EINVAL;
   if (data != PI0_SYNCDATA_NONE && planes < 2) return PI0_EINVAL;
@@ -212,15 +302,22 @@ extern "C" int pi0_sync_dep_bench(int barrier, int data, int fan, int n_ops, int
   const unsigned spin_limit = 1u << 20;
   int rc = PI0_OK;
   if (e == hipSuccess) {
-    sync_dep_clear_kernel<<<1, 256, 0, s>>>(d_state);
+    sync_dep_clear_kernel<<<1, 256, 0, s>>>(d_state, 0);
     e = hipEventRecord(e0, s);
     for (int r = 0; r < reps && e == hipSuccess; r++) {
-      // epochs keep counting across repetitions, so the counters and flags need no clearing in between
-      const unsigned epoch0 = (unsigned)r * (unsigned)n_ops;
+      // epochs keep counting across repetitions (n_ops - 1 barriers each), so the counters and flags need no clearing in between
+      const unsigned epoch0 = (unsigned)r * (unsigned)(n_ops - 1);
       const int op0 = (int)(((long long)r * n_ops) % planes);
       if (barrier == PI0_BARRIER_COUNTER) launch_dep<PI0_BARRIER_COUNTER>(data, s, d_x, planes, d_b, n_ops, op0, fan, d_state, spin_limit, epoch0);
       else if (barrier == PI0_BARRIER_XCD) launch_dep<PI0_BARRIER_XCD>(data, s, d_x, planes, d_b, n_ops, op0, fan, d_state, spin_limit, epoch0);
-      else launch_dep<PI0_BARRIER_FLAGS>(data, s, d_x, planes, d_b, n_ops, op0, fan, d_state, spin_limit, epoch0);
+      else if (barrier == PI0_BARRIER_FLAGS) launch_dep<PI0_BARRIER_FLAGS>(data, s, d_x, planes, d_b, n_ops, op0, fan, d_state, spin_limit, epoch0);
+      else if (barrier == PI0_BARRIER_FLAGS8) launch_dep<PI0_BARRIER_FLAGS8>(data, s, d_x, planes, d_b, n_ops, op0, fan, d_state, spin_limit, epoch0);
+      else if (barrier == PI0_BARRIER_GROUPADD) launch_dep<PI0_BARRIER_GROUPADD>(data, s, d_x, planes, d_b, n_ops, op0, fan, d_state, spin_limit, epoch0);
+      else {
+        // the member registration restarts with every launch: its counter and the die counters are cleared, epochs restart
+        sync_dep_clear_kernel<<<1, 256, 0, s>>>(d_state, 1);
+        launch_dep<PI0_BARRIER_XCC>(data, s, d_x, planes, d_b, n_ops, op0, fan, d_state, spin_limit, 0u);
+      }
       e = hipGetLastError();
     }
     if (e == hipSuccess) e = hipEventRecord(e1, s);

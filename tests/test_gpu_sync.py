@@ -28,8 +28,8 @@ def simulate(x0, b, fan, n_ops):
     return x
 
 
-@pytest.mark.parametrize("barrier", ["counter", "xcd", "flags"])
-@pytest.mark.parametrize("data", ["bypass", "inv", "fence", "fresh"])
+@pytest.mark.parametrize("barrier", ["counter", "xcd", "flags", "flags8", "groupadd", "xcc"])
+@pytest.mark.parametrize("data", ["bypass", "inv", "fence", "fresh", "wback"])
 def test_dependent_updates_are_exact(barrier, data):
     dev = torch.device("cuda:0")
     stream = torch.cuda.Stream(device=dev)
@@ -42,7 +42,7 @@ def test_dependent_updates_are_exact(barrier, data):
     d_x = torch.zeros((planes, 256, 1024), dtype=torch.float32, device=dev)
     d_x[0] = torch.from_numpy(x0).to(dev)
     d_b = torch.from_numpy(b).to(dev)
-    d_state = torch.zeros(1024, dtype=torch.int32, device=dev)
+    d_state = torch.zeros(9216, dtype=torch.int32, device=dev)
     torch.cuda.synchronize()
     ms = binding.pi0_sync_dep_bench(barrier, data, fan, n_ops, 1, d_x, d_b, d_state, stream)
     want = simulate(x0, b, fan, n_ops)
@@ -57,8 +57,8 @@ def test_independent_updates_and_argument_checks():
     x0 = torch.arange(256 * 1024, dtype=torch.float32).reshape(256, 1024) % 17
     b = torch.ones(256, 1024)
     d_b = b.to(dev)
-    d_state = torch.zeros(1024, dtype=torch.int32, device=dev)
-    for barrier in ("counter", "xcd", "flags"):
+    d_state = torch.zeros(9216, dtype=torch.int32, device=dev)
+    for barrier in ("counter", "xcd", "flags", "flags8", "groupadd", "xcc"):
         say(f"[gpu] pi0_sync_dep_bench {barrier} none")
         d_x = x0.clone().reshape(1, 256, 1024).to(dev)
         torch.cuda.synchronize()
