@@ -22,276 +22,12 @@
 // chunk-to-wave assignment.
 #include "pi0_internal.h"
 
-#define NEG_BIG (-1.0e30f)
-#define ATT_WAVES 8
+#include "attention_body.h"
 
-// MAXR: key rounds per wave over segment 0 (8 * MAXR chunks = 256 * MAXR keys); VRING: value
-// chunks in flight per wave.
 template <int DQK, int NVB, int MAXR, int VRING>
 __global__ __launch_bounds__(512) void attention_kernel(AttnParams p) {
-  constexpr int S16 = DQK / 16;
-  constexpr bool DUAL = MAXR == 1;             // second accumulators (register room permitting)
-  constexpr int QB = (MAXR == 1 && S16 % 8 == 0) ? 8 : 1;   // Q fragments read from LDS per batch (register room permitting)
-  constexpr int NPQ = 32 * DQK / 8;            // 16-byte pieces of the Q tile
-  constexpr int QP = (NPQ + 511) / 512;        // pieces per thread
-  constexpr int NPK1 = 2 * S16 * 64;           // 16-byte pieces of the two segment-1 key chunks
-  constexpr int KP1 = (NPK1 + 511) / 512;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  bf16* qs = reinterpret_cast<bf16*>(smem_raw);                               // [S16][64][8]
-  bf16* k1s = qs + S16 * 512;                                                 // [2][S16][64][8]
-  float* mw = reinterpret_cast<float*>(k1s + 2 * S16 * 512);                  // [8][32]
-  float* lw = mw + ATT_WAVES * 32;                                            // [8][32]
-  bf16* pf = reinterpret_cast<bf16*>(lw + ATT_WAVES * 32);                    // [ntot][2][64][8]
-
-  const int t = threadIdx.x;
-  const int lane = t & 63;
-  const int w = t >> 6;
-  const int lq = lane & 31;
-  const int lh = lane >> 5;
-  if ((int)blockIdx.y >= p.heads) {   // warm-up block; rank = linear block index (mod 8)
-    if (blockIdx.z == 0) prefetch_role(p.pf, (int)blockIdx.x + (int)gridDim.x * ((int)blockIdx.y - p.heads));
-    return;
-  }
-  // v_split > 1: the head dimension of the values (and of the output) is shared out over v_split blocks per
-  // (query tile, head); each repeats phase 1 on all keys and runs phase 2 on its NVB / v_split slices only
-  const int vs = p.v_split > 1 ? p.v_split : 1;
-  const int tile = (int)blockIdx.x / vs;
-  const int vpart = (int)blockIdx.x - tile * vs;
-  const int nslice = NVB / vs;                 // value slices (waves of phase 2) of this block
-  const int slice = vpart * nslice + w;        // the slice wave w < nslice accumulates
-  const int head = blockIdx.y;
-  const int row = tile * 32 + lq;
-  const bool row_ok = row < p.Tq;
-
-  int cbeg0 = 0, n0 = p.chunks0;
-  if (p.view_tokens > 0) {
-    const int view = (tile * 32) / p.view_tokens;
-    cbeg0 = view * (p.view_tokens >> 5);
-    n0 = p.view_tokens >> 5;
-  }
-  int n1 = p.chunks1;
-  if (p.key_splits > 1) {   // this block's share of segment 0; the last share also takes segment 1
-    cbeg0 = (int)blockIdx.z * p.chunks_per_split;
-    n0 = min(p.chunks_per_split, p.chunks0 - cbeg0);
-    if ((int)blockIdx.z != p.key_splits - 1) n1 = 0;
-  }
-  const int ntot = n0 + n1;
-  const bf16* kbase0 = p.k0 + ((size_t)head * p.kv_head_stride0 + (size_t)cbeg0 * S16 * 512) + lane * 8;
-  const bf16* vbase0 = p.v0 + ((size_t)head * p.v_head_stride0 + (size_t)cbeg0 * NVB * 1024);
-  auto vptr = [&](int ci) -> const bf16* {   // ci clamped by the caller
-    return (ci >= n0 ? p.v1 + (size_t)(ci - n0) * NVB * 1024 : vbase0 + (size_t)ci * NVB * 1024) + slice * 1024 + lane * 8;
-  };
-
-  // ---- issue every load of the first round (unconditional, clamped addresses) -----------------
-  const bf16* qsrc = p.q + (size_t)head * p.q_head_stride + (size_t)tile * S16 * 512;
-  bf16x8 qreg[QP];
-#pragma unroll
-  for (int i = 0; i < QP; i++) qreg[i] = *reinterpret_cast<const bf16x8*>(qsrc + (size_t)min(t + i * 512, NPQ - 1) * 8);
-  bf16x8 k1reg[KP1];
-  if (n1 > 0) {
-#pragma unroll
-    for (int i = 0; i < KP1; i++)
-      k1reg[i] = *reinterpret_cast<const bf16x8*>(p.k1 + (size_t)min(t + i * 512, n1 * S16 * 64 - 1) * 8);
-  }
-  bf16x8 kf[S16];
-  {
-    const bf16* kp0 = kbase0 + (size_t)min(w, n0 - 1) * S16 * 512;
-#pragma unroll
-    for (int s = 0; s < S16; s++) kf[s] = *reinterpret_cast<const bf16x8*>(kp0 + (size_t)s * 512);
-  }
-  bf16x8 vf[VRING * 2];
-  const bool pv_wave = w < nslice;
-  if (pv_wave) {
-#pragma unroll
-    for (int c = 0; c < VRING; c++) {
-      const bf16* vp = vptr(min(c, ntot - 1));
-      vf[2 * c] = *reinterpret_cast<const bf16x8*>(vp);
-      vf[2 * c + 1] = *reinterpret_cast<const bf16x8*>(vp + 512);
-    }
-  }
-#pragma unroll
-  for (int i = 0; i < QP; i++) {
-    const int pc = t + i * 512;
-    if (pc < NPQ) *reinterpret_cast<bf16x8*>(qs + (size_t)pc * 8) = qreg[i];
-  }
-  if (n1 > 0) {
-#pragma unroll
-    for (int i = 0; i < KP1; i++) {
-      const int pc = t + i * 512;
-      if (pc < NPK1) *reinterpret_cast<bf16x8*>(k1s + (size_t)pc * 8) = k1reg[i];
-    }
-  }
-  __syncthreads();
-
-  // ---- phase 1: scores of this wave's chunks ------------------------------------------------
-  float sv[MAXR][16];
-  float sv1[16];
-  float m_loc = NEG_BIG;
-#pragma unroll
-  for (int r = 0; r < MAXR; r++) {
-    const int ci = w + ATT_WAVES * r;
-    if (ci < n0) {
-      const bool more = ci + ATT_WAVES < n0;
-      const bf16* kn = kbase0 + (size_t)min(ci + ATT_WAVES, n0 - 1) * S16 * 512;
-      f32x16 sacc, sacc1;      // two accumulators where registers allow: a dependent MFMA waits ~64 clocks
-#pragma unroll
-      for (int e = 0; e < 16; e++) sacc[e] = 0.f, sacc1[e] = 0.f;
-      // the Q fragments come from LDS in batches of QB reads issued together: a read that is only
-      // issued when its MFMA is next costs a full LDS round trip per step
-#pragma unroll
-      for (int s0 = 0; s0 < S16; s0 += QB) {
-        bf16x8 qb[QB];
-#pragma unroll
-        for (int j = 0; j < QB; j++) qb[j] = *reinterpret_cast<const bf16x8*>(qs + ((size_t)(s0 + j) * 64 + lane) * 8);
-#pragma unroll
-        for (int j = 0; j < QB; j++) {
-          const int s = s0 + j;
-          const bf16x8 a = kf[s];
-          if (r + 1 < MAXR && more) kf[s] = *reinterpret_cast<const bf16x8*>(kn + (size_t)s * 512);
-          if (DUAL && (s & 1)) sacc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qb[j], sacc1, 0, 0, 0);
-          else sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qb[j], sacc, 0, 0, 0);
-        }
-      }
-      if (DUAL) {
-#pragma unroll
-        for (int e = 0; e < 16; e++) sacc[e] += sacc1[e];
-      }
-#pragma unroll
-      for (int e = 0; e < 16; e++) {
-        const int key = (cbeg0 + ci) * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
-        sv[r][e] = key < p.valid0 ? sacc[e] * p.scale : NEG_BIG;
-        m_loc = fmaxf(m_loc, sv[r][e]);
-      }
-    } else {
-#pragma unroll
-      for (int e = 0; e < 16; e++) sv[r][e] = NEG_BIG;
-    }
-  }
-  const bool seg1_wave = w < n1;             // waves 0 and 1 score the second segment from LDS
-  if (seg1_wave) {
-    f32x16 sacc, sacc1;
-#pragma unroll
-    for (int e = 0; e < 16; e++) sacc[e] = 0.f, sacc1[e] = 0.f;
-#pragma unroll
-    for (int s0 = 0; s0 < S16; s0 += 4) {
-      bf16x8 ka[4], qb[4];
-#pragma unroll
-      for (int j = 0; j < 4; j++) {
-        if (s0 + j < S16) {
-          ka[j] = *reinterpret_cast<const bf16x8*>(k1s + (((size_t)w * S16 + s0 + j) * 64 + lane) * 8);
-          qb[j] = *reinterpret_cast<const bf16x8*>(qs + ((size_t)(s0 + j) * 64 + lane) * 8);
-        }
-      }
-#pragma unroll
-      for (int j = 0; j < 4; j++) {
-        if (s0 + j < S16) {
-          if (DUAL && (j & 1)) sacc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[j], qb[j], sacc1, 0, 0, 0);
-          else sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[j], qb[j], sacc, 0, 0, 0);
-        }
-      }
-    }
-    if (DUAL) {
-#pragma unroll
-      for (int e = 0; e < 16; e++) sacc[e] += sacc1[e];
-    }
-#pragma unroll
-    for (int e = 0; e < 16; e++) {
-      const int key = w * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
-      const bool valid = p.suffix_mask ? (row == 0 ? key == 0 : true) : true;
-      sv1[e] = valid ? sacc[e] * p.scale : NEG_BIG;
-      m_loc = fmaxf(m_loc, sv1[e]);
-    }
-  }
-  m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32, 64));
-  if (lh == 0) mw[w * 32 + lq] = m_loc;
-  __syncthreads();
-  float m_all = NEG_BIG;
-#pragma unroll
-  for (int i = 0; i < ATT_WAVES; i++) m_all = fmaxf(m_all, mw[i * 32 + lq]);
-  float l_loc = 0.f;
-  auto emit = [&](const float* svals, int slot) {   // probabilities -> B-operand fragments in LDS
-    float pr[16];
-#pragma unroll
-    for (int e = 0; e < 16; e++) {
-      pr[e] = svals[e] > 0.5f * NEG_BIG ? __expf(svals[e] - m_all) : 0.f;   // masked keys: exactly 0
-      l_loc += pr[e];
-    }
-#pragma unroll
-    for (int s2 = 0; s2 < 2; s2++) {
-      bf16x8 pb;
-#pragma unroll
-      for (int j = 0; j < 8; j++) pb[j] = (bf16)pr[8 * s2 + j];
-      *reinterpret_cast<bf16x8*>(pf + ((size_t)(slot * 2 + s2) * 64 + lane) * 8) = pb;
-    }
-  };
-#pragma unroll
-  for (int r = 0; r < MAXR; r++) {
-    const int ci = w + ATT_WAVES * r;
-    if (ci < n0) emit(sv[r], ci);
-  }
-  if (seg1_wave) emit(sv1, n0 + w);
-  l_loc += __shfl_xor(l_loc, 32, 64);
-  if (lh == 0) lw[w * 32 + lq] = l_loc;
-  __syncthreads();
-  if (!pv_wave) return;
-
-  // ---- phase 2: this wave's 32-wide slice of the head dimension over all chunks --------------
-  f32x16 o, o1;
-#pragma unroll
-  for (int e = 0; e < 16; e++) o[e] = 0.f, o1[e] = 0.f;
-  // One ring of VRING chunks per round: the probability fragments of the whole round are read
-  // from LDS up front (clamped, unconditional), chunks beyond the end multiply zeros; the value
-  // fragments of the next round are requested (whole round, one uniform branch) as the registers
-  // of this round are consumed.
-  const bf16x8 zero8v = {(bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f};
-  for (int c0 = 0; c0 < ntot; c0 += VRING) {
-    bf16x8 bp[2 * VRING];
-#pragma unroll
-    for (int cc = 0; cc < VRING; cc++) {
-      const int c = min(c0 + cc, ntot - 1);
-#pragma unroll
-      for (int s2 = 0; s2 < 2; s2++)
-        bp[2 * cc + s2] = *reinterpret_cast<const bf16x8*>(pf + ((size_t)(c * 2 + s2) * 64 + lane) * 8);
-    }
-    const bool more_round = c0 + VRING < ntot;
-#pragma unroll
-    for (int cc = 0; cc < VRING; cc++) {
-      const bool live = c0 + cc < ntot;
-#pragma unroll
-      for (int s2 = 0; s2 < 2; s2++) {
-        const bf16x8 a = vf[2 * cc + s2];
-        if (more_round) vf[2 * cc + s2] = *reinterpret_cast<const bf16x8*>(vptr(min(c0 + cc + VRING, ntot - 1)) + (size_t)s2 * 512);
-        if (DUAL && s2) o1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, live ? bp[2 * cc + s2] : zero8v, o1, 0, 0, 0);
-        else o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, live ? bp[2 * cc + s2] : zero8v, o, 0, 0, 0);
-      }
-    }
-  }
-  if (DUAL) {
-#pragma unroll
-    for (int e = 0; e < 16; e++) o[e] += o1[e];
-  }
-  float l_all = 0.f;
-#pragma unroll
-  for (int i = 0; i < ATT_WAVES; i++) l_all += lw[i * 32 + lq];
-  const float inv = 1.0f / l_all;
-  if (!row_ok) return;
-  if (p.ml_out != nullptr && w == 0 && lh == 0 && vpart == 0) {   // (row maximum, sum) of this share, for the consumer's merge
-    float* dst = p.ml_out + ((((size_t)blockIdx.z * p.heads + head) * ((p.Tq + 31) >> 5) * 32) + row) * 2;
-    dst[0] = m_all;
-    dst[1] = l_all;
-  }
-  bf16* outp = p.out + (size_t)blockIdx.z * p.out_split_stride;
-#pragma unroll
-  for (int i = 0; i < 4; i++) {
-    const int d = slice * 32 + 8 * i + 4 * lh;
-    if (d < p.head_dim) {
-      const bf16x4 ob = {(bf16)(o[4 * i] * inv), (bf16)(o[4 * i + 1] * inv), (bf16)(o[4 * i + 2] * inv),
-                         (bf16)(o[4 * i + 3] * inv)};
-      const int col = head * p.head_dim + d;
-      *reinterpret_cast<bf16x4*>(outp + ((size_t)(row >> 5) * (p.out_ld >> 4) + (col >> 4)) * 512 +
-                                 (((col & 15) >> 3) * 32 + (row & 31)) * 8 + (col & 7)) = ob;
-    }
-  }
+  attention_body<DQK, NVB, MAXR, VRING>(p, LaunchCtx::from_block_idx(), smem_raw);
 }
 
 template <int DQK>

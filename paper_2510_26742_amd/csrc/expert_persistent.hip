@@ -1,0 +1,198 @@
+// The action expert's whole denoise loop as ONE persistent kernel (Section 5.2 of the paper: software barriers
+// in place of kernel boundaries, operands requested across the synchronisation points; Section 6.2 names the
+// persistent megakernel as the way to take the expert's per-kernel overhead out).
+//
+// 256 blocks of 8 waves, one per compute unit, walk the operation list of Table 2's action-expert rows - state
+// token; per Euler step the folded action/time embedding and its second linear layer; per layer QKV + RoPE,
+// attention over [prefix cache ; own keys], O projection + residual, gate||up GeGLU, down + residual; final norm,
+// output projection and the Euler update - with one grid barrier between consecutive operations.  Every operation
+// is the same body that the per-operation launches run (gemm_common.h, attention_body.h, embed_bodies.h), cut
+// into the same work items, so the results agree with that path bit for bit; a block takes the work items
+// block index, block index + 256, ... of each operation and then arrives at the barrier.
+// What the persistent form buys: a body requests its weights (constant during the kernel, ordinary loads) and
+// the other constants BEFORE it waits for the operation before to complete everywhere, so the weights' trip
+// from HBM overlaps the barrier; and there is no dispatch, no cold instruction / argument fetch, no end-of-kernel
+// cache write-back per operation.  What it costs: data that crosses blocks must be written through to memory
+// and read past the per-die L2 (exec_ctx.h), and a barrier costs two dependent atomics plus a poll.
+#include "attention_body.h"
+#include "expert_loop.h"
+
+namespace {
+
+constexpr int PK_THREADS = 512;
+
+template <class F>
+__device__ __forceinline__ void for_items(int n_items, F&& f) {
+  bool first = true;
+  for (int it = (int)blockIdx.x; it < n_items; it += (int)gridDim.x) {
+    if (!first) __syncthreads();   // shared memory of the item before is free
+    f(it);
+    first = false;
+  }
+}
+
+__global__ __launch_bounds__(PK_THREADS) void expert_loop_kernel(ExpertLoopParams P) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  GridBarrier bar;
+  bar.init(P.sync, P.spin_limit);
+  PersistCtx cx;
+  cx.arena = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(P.arena), 0, (int)P.arena_bytes, 0x00020000);
+  cx.arena_base = P.arena;
+  cx.bar = &bar;
+  cx.bx = cx.by = cx.bz = 0;
+  auto item = [&](int bx, int by, int bz) {
+    PersistCtx c = cx;
+    c.bx = bx; c.by = by; c.bz = bz;
+    return c;
+  };
+
+  // ---- C0: state token; x <- noise ---------------------------------------------------------------
+  for_items((P.stok.X + 255) / 256, [&](int it) { state_token_body(P.stok, item(it, 0, 0)); });
+  if ((int)blockIdx.x == (int)gridDim.x - 1) {
+    for (int i = threadIdx.x; i < P.x_elems; i += PK_THREADS) cx.st(P.emb.x_rw + i, P.noise[i]);
+  }
+  bar.arrive();
+
+  const int emb_cols = (P.emb.a.X + 255) / 256;
+  const int att_gx = P.att_gx, att_gxy = P.att_gx * P.att.heads;
+  for (int k = 0; k < P.steps; k++) {
+    {  // ---- C1: folded action/time embedding + SiLU; suffix row 0 <- state token ----------------
+      ActionEmbedArgs a = P.emb.a;
+      a.bias_k += (size_t)k * a.X;
+      bool waited = false;
+      for_items(emb_cols * (a.chunk + 1), [&](int it) {
+        if (!waited) { bar.wait(); waited = true; }
+        action_embed_body(a, item(it % emb_cols, it / emb_cols, 0));
+      });
+      bar.arrive();
+    }
+    // ---- C2: second linear of the action/time MLP -> suffix rows 1 .. chunk --------------------------
+    for_items(P.tout.n_tiles, [&](int it) { gemm_skinny_body<PRO_NONE, EPI_RESID, 0>(P.tout, item(it, 0, 0), smem_raw); });
+    bar.arrive();
+    for (int l = 0; l < P.layers; l++) {
+      {  // ---- C3: RMS -> QKV, RoPE at positions P .. P + 63 -------------------------------------
+        GemmParams q = P.qkv;
+        q.W.w += (size_t)l * P.w_stride;
+        q.rowstat_parts = l == 0 ? P.parts_first : P.parts_rest;
+        for_items(q.n_tiles * 2, [&](int it) { gemm_skinny_body<PRO_RMS, EPI_QKV, 1>(q, item(it % q.n_tiles, 0, it / q.n_tiles), smem_raw); });
+        bar.arrive();
+      }
+      {  // ---- C4 + C5: scores, block mask, softmax, PV over [cache ; own keys] ---------------------
+        AttnParams a = P.att;
+        a.k0 += (size_t)l * P.kcache_stride;
+        a.v0 += (size_t)l * P.vcache_stride;
+        for_items(P.att_items, [&](int it) {
+          attention_body<256, 8, 1, 10>(a, item(it % att_gx, (it % att_gxy) / att_gx, it / att_gxy), smem_raw);
+        });
+        bar.arrive();
+      }
+      {  // ---- C6: O projection + residual ------------------------------------------------------
+        GemmParams o = P.o;
+        o.W.w += (size_t)l * P.w_stride;
+        o.gain = P.g_mlp0 + (size_t)l * P.gain_stride;
+        const int nx = o.n_tiles * 2;
+        for_items(nx * P.m16, [&](int it) { gemm_skinny16_body<8>(o, item(it % nx, it / nx, 0), smem_raw); });
+        bar.arrive();
+      }
+      {  // ---- C7: RMS -> gate||up, fused gate -----------------------------------------------------
+        GemmParams g = P.gu;
+        g.W.w += (size_t)l * P.w_stride;
+        for_items(g.n_tiles, [&](int it) { gemm_skinny_body<PRO_RMS, EPI_GEGLU, 0>(g, item(it, 0, 0), smem_raw); });
+        bar.arrive();
+      }
+      {  // ---- C8: down + residual -----------------------------------------------------------------
+        GemmParams d = P.dn;
+        d.W.w += (size_t)l * P.w_stride;
+        d.gain = l + 1 < P.layers ? P.g_attn0 + (size_t)(l + 1) * P.gain_stride : P.g_final;
+        const int nx = d.n_tiles * 2;
+        if (P.dn_ns == 16) for_items(nx * P.m16, [&](int it) { gemm_skinny16_body<16>(d, item(it % nx, it / nx, 0), smem_raw); });
+        else for_items(nx * P.m16, [&](int it) { gemm_skinny16_body<8>(d, item(it % nx, it / nx, 0), smem_raw); });
+        bar.arrive();
+      }
+    }
+    // ---- C9: final RMS -> out-projection (+bias), Euler update x <- x + dt * v ----------------------
+    for_items(P.outp.n_tiles, [&](int it) { gemm_skinny_body<PRO_RMS, EPI_EULER, 0>(P.outp, item(it, 0, 0), smem_raw); });
+    bar.arrive();
+  }
+  // ---- actions out (the caller's buffer is outside the arena: ordinary stores, visible at the kernel's end)
+  if ((int)blockIdx.x == 0) {
+    bar.wait();
+    for (int i = threadIdx.x; i < P.x_elems; i += PK_THREADS) P.actions[i] = cx.ld(P.emb.x_rw + i);
+  }
+}
+
+}  // namespace
+
+int expert_loop_smem_bytes() {
+  const int sk = (SK_WAVES * 2 * 16 * 64 + 128 + SK_WAVES * 128) * 4;
+  const int at = attn_smem_bytes<256>(8 + 2);
+  return sk > at ? sk : at;
+}
+
+hipError_t expert_loop_init_attributes() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&expert_loop_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             expert_loop_smem_bytes());
+}
+
+hipError_t expert_loop_max_blocks_per_cu(int* out) {
+  return hipOccupancyMaxActiveBlocksPerMultiprocessor(out, reinterpret_cast<const void*>(&expert_loop_kernel), PK_THREADS,
+                                                      expert_loop_smem_bytes());
+}
+
+// Host-side checks of everything the kernel's indexing assumes; the caller has zeroed the barrier words.
+hipError_t launch_expert_loop(hipStream_t s, const ExpertLoopParams& P, int blocks) {
+  if (blocks < 1 || blocks > 1024 || P.sync == nullptr || P.arena == nullptr || P.arena_bytes == 0 || P.spin_limit == 0)
+    return hipErrorInvalidValue;
+  if (P.layers < 1 || P.steps < 1 || P.x_elems < 1 || P.noise == nullptr || P.actions == nullptr || P.emb.x_rw == nullptr)
+    return hipErrorInvalidValue;
+  // every buffer that blocks exchange lies inside the arena (offsets are 32-bit)
+  auto in_arena = [&](const void* p, size_t bytes) {
+    const char* c = reinterpret_cast<const char*>(p);
+    return p != nullptr && c >= P.arena && c + bytes <= P.arena + P.arena_bytes;
+  };
+  const GemmParams* gs[6] = {&P.qkv, &P.o, &P.gu, &P.dn, &P.tout, &P.outp};
+  for (const GemmParams* g : gs) {
+    if (g->X == nullptr || g->W.w == nullptr || g->M < 1 || g->M > 64 || g->W.k_pad % 64 != 0 || g->n_tiles * 32 != g->W.n_pad)
+      return hipErrorInvalidValue;
+    if (g->ldx < g->W.k_pad || g->ldx % 16 != 0 || !in_arena(g->X, (size_t)64 * g->ldx * 2)) return hipErrorInvalidValue;
+    if (g->pf.blocks != 0 || g->progress != nullptr) return hipErrorInvalidValue;
+  }
+  const GemmParams* sk[4] = {&P.qkv, &P.gu, &P.tout, &P.outp};   // 32-feature tiles, k <= 1024 split over 8 waves
+  for (const GemmParams* g : sk) {
+    if (g->k_per_split != g->W.k_pad || g->W.k_pad > SK_KMAX || g->m_tiles != 1) return hipErrorInvalidValue;
+  }
+  if (P.qkv.rowstat == nullptr || P.gu.rowstat == nullptr || P.outp.rowstat == nullptr) return hipErrorInvalidValue;
+  if (P.parts_first < 1 || P.parts_first > 8 * SK_WAVES || P.parts_rest < 1 || P.parts_rest > 8 * SK_WAVES) return hipErrorInvalidValue;
+  if (P.gu.rowstat_parts < 1 || P.gu.rowstat_parts > 8 * SK_WAVES || P.outp.rowstat_parts < 1 || P.outp.rowstat_parts > 8 * SK_WAVES)
+    return hipErrorInvalidValue;
+  if (!in_arena(P.qkv.rowstat, (size_t)8 * SK_WAVES * 64 * 8)) return hipErrorInvalidValue;
+  if (P.qkv.rope == nullptr || P.qkv.out_bf16 == nullptr || P.qkv.kfrag == nullptr || P.qkv.vfrag == nullptr) return hipErrorInvalidValue;
+  const GemmParams* s16[2] = {&P.o, &P.dn};   // 16 x 16 tiles over the whole k range
+  for (const GemmParams* g : s16) {
+    const int kc16 = g->W.k_pad >> 4;
+    if ((kc16 != 128 && kc16 != 256) || g->out_f32 == nullptr || g->out_bf16 == nullptr || g->resid == nullptr || g->ldo % 4 != 0 ||
+        g->ldo2 % 16 != 0 || g->stat_out == nullptr)
+      return hipErrorInvalidValue;
+  }
+  if ((P.o.W.k_pad >> 4) != 128 || P.dn_ns != ((P.dn.W.k_pad >> 4) == 256 ? 16 : 8) || P.m16 != (P.o.M + 15) / 16) return hipErrorInvalidValue;
+  if (P.o.xsplits > 1 && (P.o.xsplits > 4 || P.o.xsplit_ml == nullptr || P.o.xsplit_stride < (size_t)64 * P.o.ldx)) return hipErrorInvalidValue;
+  // attention: head dim 256, at most 8 prefix chunks per share, the suffix's own 2 chunks as second segment
+  const AttnParams& a = P.att;
+  if (a.q == nullptr || a.k0 == nullptr || a.v0 == nullptr || a.k1 == nullptr || a.v1 == nullptr || a.out == nullptr) return hipErrorInvalidValue;
+  if (a.head_dim != 256 || a.Tq != 64 || a.chunks1 != 2 || a.heads < 1 || a.chunks0 < 1 || a.valid0 < 1 || a.valid0 > a.chunks0 * 32)
+    return hipErrorInvalidValue;
+  const int shares = a.key_splits > 1 ? a.key_splits : 1;
+  const int n0 = shares > 1 ? a.chunks_per_split : a.chunks0;
+  if (n0 < 1 || n0 > 8 || shares > 4 || (shares > 1 && (a.ml_out == nullptr || (shares - 1) * a.chunks_per_split >= a.chunks0 ||
+                                                        shares * a.chunks_per_split < a.chunks0)))
+    return hipErrorInvalidValue;
+  const int vs = a.v_split > 1 ? a.v_split : 1;
+  if (vs != 1 && vs != 2 && vs != 4 && vs != 8) return hipErrorInvalidValue;
+  if (P.att_gx != 2 * vs || P.att_items != 2 * vs * a.heads * shares || a.pf.blocks != 0) return hipErrorInvalidValue;
+  if (!in_arena(a.q, 2) || !in_arena(a.k1, 2) || !in_arena(a.v1, 2) || !in_arena(a.out, 2)) return hipErrorInvalidValue;
+  if (P.emb.a.X % 32 != 0 || P.emb.a.gain == nullptr || P.emb.a.stat_parts == nullptr || P.emb.a.x != P.emb.x_rw) return hipErrorInvalidValue;
+  if (!in_arena(P.emb.x_rw, (size_t)P.x_elems * 4) || !in_arena(P.stok.out, (size_t)P.stok.X * 4)) return hipErrorInvalidValue;
+  if (P.stok.sd < 1 || P.stok.sd > 32) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(expert_loop_kernel, dim3(blocks), dim3(PK_THREADS), expert_loop_smem_bytes(), s, P);
+  return hipGetLastError();
+}

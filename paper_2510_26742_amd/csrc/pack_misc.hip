@@ -2,11 +2,7 @@
 // the small non-GEMM kernels of the pass (patch extraction, prompt embedding, state token,
 // folded action/time embedding of Table 2 rows 1x32x1024 and 63x32x1024).
 #include "pi0_internal.h"
-
-// index of element (row m, column k) of an activation matrix in XF (MFMA B-fragment) order
-__device__ __forceinline__ size_t xf_index(int m, int k, int kc16) {
-  return ((size_t)(m >> 5) * kc16 + (k >> 4)) * 512 + (((k & 15) >> 3) * 32 + (m & 31)) * 8 + (k & 7);
-}
+#include "embed_bodies.h"
 
 // ------------------------------------------------------------------------------------------------
 // packed row n -> (source matrix, source column); returns false for padding rows
@@ -304,32 +300,13 @@ hipError_t launch_embed_prompt(hipStream_t st, const int32_t* ids, int n, const 
   return hipGetLastError();
 }
 
-// state token: out[n] = sum_j state[j] * ws[j][n] + bs[n]   (Table 2 row 1x32x1024)
-__global__ __launch_bounds__(256) void state_token_kernel(const float* state, int sd, const float* ws, const float* bs, int X,
-                                                          float* out, int* progress) {
-  const int n = blockIdx.x * 256 + threadIdx.x;
-  // first launch of the action expert: no layer has started yet (read by the read-ahead kernel)
-  if (n == 0 && progress != nullptr) __hip_atomic_store(progress, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  if (n >= X) return;
-  // all (at most 32) loads issued together (clamped, unconditional), added in index order
-  float wv[32], sv[32];
-#pragma unroll
-  for (int j = 0; j < 32; j++) {
-    const int jj = min(j, sd - 1);
-    wv[j] = ws[(size_t)jj * X + n];
-    sv[j] = state[jj];
-  }
-  float acc = bs[n];
-#pragma unroll
-  for (int j = 0; j < 32; j++) {
-    if (j < sd) acc += sv[j] * wv[j];
-  }
-  out[n] = acc;
+__global__ __launch_bounds__(256) void state_token_kernel(StateTokenArgs a) {
+  state_token_body(a, LaunchCtx::from_block_idx());
 }
 hipError_t launch_state_token(hipStream_t st, const float* state, int state_dim, const float* ws, const float* bs, int X,
                               float* out, int* progress) {
   if (state_dim < 1 || state_dim > 32) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(state_token_kernel, dim3((X + 255) / 256), dim3(256), 0, st, state, state_dim, ws, bs, X, out, progress);
+  hipLaunchKernelGGL(state_token_kernel, dim3((X + 255) / 256), dim3(256), 0, st, StateTokenArgs{state, state_dim, ws, bs, X, out, progress});
   return hipGetLastError();
 }
 
@@ -435,58 +412,15 @@ hipError_t launch_read_ahead(hipStream_t st, const ReadAheadParams& p, int block
   return hipGetLastError();
 }
 
-// Table 2 row 63x32x1024 (bias, silu) with the folded weights; also re-seeds suffix row 0 of the
-// expert's residual stream with the state token at the start of every Euler step.
-// grid.y = chunk + 1: row r < chunk -> z[r]; row chunk -> state token copy and zero z[chunk].
-// The state row also gets its gain-scaled bf16 copy and, per 32 columns, its (sum, sum of squares) in
-// stat_parts[tile][64 rows][2] (row 0), the form the first QKV GEMM of the step reads.
-__global__ __launch_bounds__(256) void action_embed_kernel(const float* x, int chunk, int A, const float* wfold,
-                                                           const float* bias_k, int X, bf16* z, const float* state_tok,
-                                                           float* y_f32, bf16* y_bf16, const float* gain, float* stat_parts) {
-  const int n = blockIdx.x * 256 + threadIdx.x;
-  const int r = blockIdx.y;
-  if (n >= X) return;
-  if (r < chunk) {
-    // loads in batches of 8 (independent), accumulated in index order
-    float acc = bias_k[n];
-    for (int j0 = 0; j0 < A; j0 += 8) {
-      float wv[8], xv[8];
-#pragma unroll
-      for (int u = 0; u < 8; u++) {
-        const int j = min(j0 + u, A - 1);
-        wv[u] = wfold[(size_t)j * X + n];
-        xv[u] = x[(size_t)r * A + j];
-      }
-#pragma unroll
-      for (int u = 0; u < 8; u++) {
-        if (j0 + u < A) acc += xv[u] * wv[u];
-      }
-    }
-    const float sv = acc / (1.0f + __expf(-acc));
-    z[xf_index(r, n, X >> 4)] = (bf16)sv;
-  } else {
-    z[xf_index(chunk, n, X >> 4)] = (bf16)0.0f;
-    const float s = state_tok[n];
-    y_f32[n] = s;
-    y_bf16[xf_index(0, n, X >> 4)] = (bf16)(s * gain[n]);
-    float a = s, b = s * s;     // X is a multiple of 32: a 32-lane group is here completely or not at all
-#pragma unroll
-    for (int off = 1; off < 32; off <<= 1) {
-      a += __shfl_xor(a, off, 64);
-      b += __shfl_xor(b, off, 64);
-    }
-    if ((threadIdx.x & 31) == 0) {
-      stat_parts[(size_t)(n >> 5) * 128] = a;
-      stat_parts[(size_t)(n >> 5) * 128 + 1] = b;
-    }
-  }
+__global__ __launch_bounds__(256) void action_embed_kernel(ActionEmbedArgs a) {
+  action_embed_body(a, LaunchCtx::from_block_idx());
 }
 hipError_t launch_action_embed(hipStream_t st, const float* x, int chunk, int action_dim, const float* wfold,
                                const float* bias_k, int X, bf16* z, const float* state_tok, float* y_f32, bf16* y_bf16,
                                const float* gain, float* stat_parts) {
   if (X % 32 != 0 || gain == nullptr || stat_parts == nullptr) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(action_embed_kernel, dim3((X + 255) / 256, chunk + 1), dim3(256), 0, st, x, chunk, action_dim, wfold,
-                     bias_k, X, z, state_tok, y_f32, y_bf16, gain, stat_parts);
+  hipLaunchKernelGGL(action_embed_kernel, dim3((X + 255) / 256, chunk + 1), dim3(256), 0, st,
+                     ActionEmbedArgs{x, chunk, action_dim, wfold, bias_k, X, z, state_tok, y_f32, y_bf16, gain, stat_parts});
   return hipGetLastError();
 }
 
