@@ -18,11 +18,15 @@
  *    The caller owns all device memory: weight blob, workspace, inputs, outputs, and the stream.
  *    The library allocates no device memory; it owns only the host-side pi0_ctx.
  *  - Every call only enqueues work on `hip_stream` (a hipStream_t, may be NULL for the default
- *    stream); results are valid after the caller synchronises that stream.  One exception that the
- *    caller never sees: pi0_denoise / pi0_infer fork one read-ahead kernel (it only loads the
- *    expert's weights ahead of the compute launches, Section 5.2) onto a stream the ctx owns and
- *    join it back into `hip_stream` before the call's last launch, with events, also inside the
- *    captured graph; work enqueued on `hip_stream` after the call is ordered after both.
+ *    stream); results are valid after the caller synchronises that stream.  pi0_denoise / pi0_infer
+ *    run the expert's loop as one persistent kernel of 256 blocks that must all be resident at once:
+ *    on a device with fewer than 256 compute units, or when the shape is outside what that kernel
+ *    covers, the loop is issued as one launch per operation instead, together with one read-ahead
+ *    kernel (it only loads the expert's weights ahead of the compute launches, Section 5.2) forked onto
+ *    a stream the ctx owns and joined back into `hip_stream` before the call's last launch, with events,
+ *    also inside the captured graph; work enqueued on `hip_stream` after the call is ordered after both.
+ *    Do not run other kernels that occupy whole compute units for long beside pi0_denoise / pi0_infer:
+ *    the persistent kernel's blocks wait for each other (bounded, see pi0_device_status).
  *  - Return value: 0 on success, a negative PI0_E* code otherwise.  Argument checks happen before
  *    any GPU call, so error paths touch no GPU state.  Nothing throws or aborts across the ABI.
  *  - Calls on one ctx must not overlap in time (one workspace, one set of activations); the only
@@ -196,6 +200,15 @@ int pi0_set_precision(pi0_ctx* ctx, int precision);
 
 /* Graph replay on (1, default) or off (0: every call launches kernels eagerly). */
 int pi0_set_graph_mode(pi0_ctx* ctx, int enabled);
+
+/*
+ * Synchronises hip_stream and reports whether a bounded wait inside a kernel of this ctx ever ran out
+ * (the denoise loop runs as one persistent kernel whose blocks synchronise with software grid barriers,
+ * Section 5.2 of the paper; a barrier that is not completed within its bound - about a second - gives up
+ * instead of hanging, and every result after that is undefined).  PI0_OK if none did, PI0_ESTATE if one
+ * did or no weights are loaded; the condition stays set until pi0_load_weights.  Errors: EINVAL, EHIP.
+ */
+int pi0_device_status(pi0_ctx* ctx, void* hip_stream);
 
 /* Static, never-NULL description of an error code. */
 const char* pi0_strerror(int code);

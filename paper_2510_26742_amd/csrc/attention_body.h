@@ -24,7 +24,7 @@ __device__ __forceinline__ void attention_body(const AttnParams& p, const Cx& cx
   float* lw = mw + ATT_WAVES * 32;                                            // [8][32]
   bf16* pf = reinterpret_cast<bf16*>(lw + ATT_WAVES * 32);                    // [ntot][2][64][8]
 
-  const int t = threadIdx.x;
+  const int t = cx.tid();
   const int lane = t & 63;
   const int w = t >> 6;
   const int lq = lane & 31;

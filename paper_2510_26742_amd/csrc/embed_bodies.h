@@ -13,8 +13,9 @@ struct StateTokenArgs {
 // state token: out[n] = sum_j state[j] * ws[j][n] + bs[n]   (Table 2 row 1x32x1024)
 template <class Cx>
 __device__ __forceinline__ void state_token_body(const StateTokenArgs& a, const Cx& cx) {
-  if (threadIdx.x >= 256) return;
-  const int n = cx.bx * 256 + threadIdx.x;
+  const int tx = cx.tid();
+  if (tx >= 256) return;
+  const int n = cx.bx * 256 + tx;
   // first launch of the action expert: no layer has started yet (read by the read-ahead kernel)
   if (!Cx::kPersistent && n == 0 && a.progress != nullptr) __hip_atomic_store(a.progress, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   if (n >= a.X) return;
@@ -46,8 +47,9 @@ struct ActionEmbedArgs {
 // stat_parts[tile][64 rows][2] (row 0), the form the first QKV GEMM of the step reads.
 template <class Cx>
 __device__ __forceinline__ void action_embed_body(const ActionEmbedArgs& a, const Cx& cx) {
-  if (threadIdx.x >= 256) return;
-  const int n = cx.bx * 256 + threadIdx.x;
+  const int tx = cx.tid();
+  if (tx >= 256) return;
+  const int n = cx.bx * 256 + tx;
   const int r = cx.by;
   const int X = a.X, A = a.A, chunk = a.chunk;
   if (n >= X) return;
@@ -80,6 +82,6 @@ __device__ __forceinline__ void action_embed_body(const ActionEmbedArgs& a, cons
       sa += __shfl_xor(sa, off, 64);
       sb += __shfl_xor(sb, off, 64);
     }
-    if ((threadIdx.x & 31) == 0) cx.st(reinterpret_cast<float2*>(a.stat_parts + (size_t)(n >> 5) * 128), make_float2(sa, sb));
+    if ((tx & 31) == 0) cx.st(reinterpret_cast<float2*>(a.stat_parts + (size_t)(n >> 5) * 128), make_float2(sa, sb));
   }
 }

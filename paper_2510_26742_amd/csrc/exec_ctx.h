@@ -31,6 +31,7 @@ struct LaunchCtx {
   template <class T>
   __device__ __forceinline__ void st(T* p, const T& v) const { *p = v; }
   __device__ __forceinline__ void wait_inputs() const {}
+  __device__ __forceinline__ int tid() const { return (int)threadIdx.x; }
 };
 
 // ------------------------------------------------------------------------------------------------
@@ -125,7 +126,10 @@ struct PersistCtx {
   __amdgpu_buffer_rsrc_t arena;    // buffer resource over the activation arena
   const char* arena_base;
   GridBarrier* bar;
+  int thread;                      // threadIdx.x, made opaque per operation: per-lane address arithmetic of one operation
+                                   // is then not hoisted out of the layer loop, where it would hold registers throughout
 
+  __device__ __forceinline__ int tid() const { return thread; }
   __device__ __forceinline__ unsigned off(const void* p) const { return (unsigned)(reinterpret_cast<const char*>(p) - arena_base); }
 
   template <class T>

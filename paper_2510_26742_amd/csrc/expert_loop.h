@@ -11,10 +11,9 @@ struct ExpertLoopParams {
   StateTokenArgs stok;
   struct {
     ActionEmbedArgs a;            // a.bias_k = row of step 0 (rows a.X floats apart); a.x == x_rw
-    float* x_rw;                  // x of the Euler integration [chunk][action_dim], inside the arena
+    float* x_rw;                  // x of the Euler integration [chunk][action_dim], inside the arena; holds the actions at the end
   } emb;
   const float* noise;             // [x_elems] initial x (staged input, constant during the kernel)
-  float* actions;                 // [x_elems] result (caller's buffer)
   int x_elems;
   int layers, steps;
   size_t w_stride;                // elements between consecutive layers, the same for the four packed matrices
@@ -37,4 +36,5 @@ struct ExpertLoopParams {
 int expert_loop_smem_bytes();
 hipError_t expert_loop_init_attributes();
 hipError_t expert_loop_max_blocks_per_cu(int* out);
-hipError_t launch_expert_loop(hipStream_t s, const ExpertLoopParams& P, int blocks);
+// d_params: device memory for one ExpertLoopParams (16-byte aligned), written by a small launch ahead of the loop kernel
+hipError_t launch_expert_loop(hipStream_t s, const ExpertLoopParams& P, ExpertLoopParams* d_params, int blocks);

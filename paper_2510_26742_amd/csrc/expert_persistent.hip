@@ -31,18 +31,34 @@ __device__ __forceinline__ void for_items(int n_items, F&& f) {
   }
 }
 
-__global__ __launch_bounds__(PK_THREADS) void expert_loop_kernel(ExpertLoopParams P) {
+// The parameter block lives in device memory and every operation reads its own part afresh: taken by value, the
+// operations' pointers and sizes stay live across the whole loop and the kernel spills hundreds of registers.
+__device__ __forceinline__ const ExpertLoopParams& fresh(const ExpertLoopParams* p) {
+  asm volatile("" : "+s"(p));   // nothing read through the pointer before this point is reused after it
+  return *p;
+}
+
+__global__ void expert_loop_params_kernel(ExpertLoopParams P, ExpertLoopParams* dst) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *dst = P;
+}
+
+__global__ __launch_bounds__(PK_THREADS) void expert_loop_kernel(const ExpertLoopParams* __restrict__ Pg) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   GridBarrier bar;
+  const ExpertLoopParams& P = *Pg;
   bar.init(P.sync, P.spin_limit);
   PersistCtx cx;
   cx.arena = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(P.arena), 0, (int)P.arena_bytes, 0x00020000);
   cx.arena_base = P.arena;
   cx.bar = &bar;
   cx.bx = cx.by = cx.bz = 0;
+  cx.thread = (int)threadIdx.x;
   auto item = [&](int bx, int by, int bz) {
     PersistCtx c = cx;
     c.bx = bx; c.by = by; c.bz = bz;
+    int t = (int)threadIdx.x;
+    asm volatile("" : "+v"(t));
+    c.thread = t;
     return c;
   };
 
@@ -54,10 +70,10 @@ __global__ __launch_bounds__(PK_THREADS) void expert_loop_kernel(ExpertLoopParam
   bar.arrive();
 
   const int emb_cols = (P.emb.a.X + 255) / 256;
-  const int att_gx = P.att_gx, att_gxy = P.att_gx * P.att.heads;
-  for (int k = 0; k < P.steps; k++) {
+  const int steps = P.steps, layers = P.layers;
+  for (int k = 0; k < steps; k++) {
     {  // ---- C1: folded action/time embedding + SiLU; suffix row 0 <- state token ----------------
-      ActionEmbedArgs a = P.emb.a;
+      ActionEmbedArgs a = fresh(Pg).emb.a;
       a.bias_k += (size_t)k * a.X;
       bool waited = false;
       for_items(emb_cols * (a.chunk + 1), [&](int it) {
@@ -67,57 +83,64 @@ __global__ __launch_bounds__(PK_THREADS) void expert_loop_kernel(ExpertLoopParam
       bar.arrive();
     }
     // ---- C2: second linear of the action/time MLP -> suffix rows 1 .. chunk --------------------------
-    for_items(P.tout.n_tiles, [&](int it) { gemm_skinny_body<PRO_NONE, EPI_RESID, 0>(P.tout, item(it, 0, 0), smem_raw); });
+    {
+      const GemmParams t = fresh(Pg).tout;
+      for_items(t.n_tiles, [&](int it) { gemm_skinny_body<PRO_NONE, EPI_RESID, 0>(t, item(it, 0, 0), smem_raw); });
+    }
     bar.arrive();
-    for (int l = 0; l < P.layers; l++) {
+    for (int l = 0; l < layers; l++) {
       {  // ---- C3: RMS -> QKV, RoPE at positions P .. P + 63 -------------------------------------
-        GemmParams q = P.qkv;
-        q.W.w += (size_t)l * P.w_stride;
-        q.rowstat_parts = l == 0 ? P.parts_first : P.parts_rest;
+        const ExpertLoopParams& F = fresh(Pg);
+        GemmParams q = F.qkv;
+        q.W.w += (size_t)l * F.w_stride;
+        q.rowstat_parts = l == 0 ? F.parts_first : F.parts_rest;
         for_items(q.n_tiles * 2, [&](int it) { gemm_skinny_body<PRO_RMS, EPI_QKV, 1>(q, item(it % q.n_tiles, 0, it / q.n_tiles), smem_raw); });
         bar.arrive();
       }
       {  // ---- C4 + C5: scores, block mask, softmax, PV over [cache ; own keys] ---------------------
-        AttnParams a = P.att;
-        a.k0 += (size_t)l * P.kcache_stride;
-        a.v0 += (size_t)l * P.vcache_stride;
-        for_items(P.att_items, [&](int it) {
-          attention_body<256, 8, 1, 10>(a, item(it % att_gx, (it % att_gxy) / att_gx, it / att_gxy), smem_raw);
+        const ExpertLoopParams& F = fresh(Pg);
+        AttnParams a = F.att;
+        a.k0 += (size_t)l * F.kcache_stride;
+        a.v0 += (size_t)l * F.vcache_stride;
+        const int att_gx = F.att_gx, att_gxy = F.att_gx * a.heads;
+        for_items(F.att_items, [&](int it) {
+          attention_body<256, 8, 1, 8>(a, item(it % att_gx, (it % att_gxy) / att_gx, it / att_gxy), smem_raw);
         });
         bar.arrive();
       }
       {  // ---- C6: O projection + residual ------------------------------------------------------
-        GemmParams o = P.o;
-        o.W.w += (size_t)l * P.w_stride;
-        o.gain = P.g_mlp0 + (size_t)l * P.gain_stride;
+        const ExpertLoopParams& F = fresh(Pg);
+        GemmParams o = F.o;
+        o.W.w += (size_t)l * F.w_stride;
+        o.gain = F.g_mlp0 + (size_t)l * F.gain_stride;
         const int nx = o.n_tiles * 2;
-        for_items(nx * P.m16, [&](int it) { gemm_skinny16_body<8>(o, item(it % nx, it / nx, 0), smem_raw); });
+        for_items(nx * F.m16, [&](int it) { gemm_skinny16_body<8>(o, item(it % nx, it / nx, 0), smem_raw); });
         bar.arrive();
       }
       {  // ---- C7: RMS -> gate||up, fused gate -----------------------------------------------------
-        GemmParams g = P.gu;
-        g.W.w += (size_t)l * P.w_stride;
+        const ExpertLoopParams& F = fresh(Pg);
+        GemmParams g = F.gu;
+        g.W.w += (size_t)l * F.w_stride;
         for_items(g.n_tiles, [&](int it) { gemm_skinny_body<PRO_RMS, EPI_GEGLU, 0>(g, item(it, 0, 0), smem_raw); });
         bar.arrive();
       }
       {  // ---- C8: down + residual -----------------------------------------------------------------
-        GemmParams d = P.dn;
-        d.W.w += (size_t)l * P.w_stride;
-        d.gain = l + 1 < P.layers ? P.g_attn0 + (size_t)(l + 1) * P.gain_stride : P.g_final;
+        const ExpertLoopParams& F = fresh(Pg);
+        GemmParams d = F.dn;
+        d.W.w += (size_t)l * F.w_stride;
+        d.gain = l + 1 < F.layers ? F.g_attn0 + (size_t)(l + 1) * F.gain_stride : F.g_final;
         const int nx = d.n_tiles * 2;
-        if (P.dn_ns == 16) for_items(nx * P.m16, [&](int it) { gemm_skinny16_body<16>(d, item(it % nx, it / nx, 0), smem_raw); });
-        else for_items(nx * P.m16, [&](int it) { gemm_skinny16_body<8>(d, item(it % nx, it / nx, 0), smem_raw); });
+        if (F.dn_ns == 16) for_items(nx * F.m16, [&](int it) { gemm_skinny16_body<16>(d, item(it % nx, it / nx, 0), smem_raw); });
+        else for_items(nx * F.m16, [&](int it) { gemm_skinny16_body<8>(d, item(it % nx, it / nx, 0), smem_raw); });
         bar.arrive();
       }
     }
     // ---- C9: final RMS -> out-projection (+bias), Euler update x <- x + dt * v ----------------------
-    for_items(P.outp.n_tiles, [&](int it) { gemm_skinny_body<PRO_RMS, EPI_EULER, 0>(P.outp, item(it, 0, 0), smem_raw); });
+    {
+      const GemmParams u = fresh(Pg).outp;
+      for_items(u.n_tiles, [&](int it) { gemm_skinny_body<PRO_RMS, EPI_EULER, 0>(u, item(it, 0, 0), smem_raw); });
+    }
     bar.arrive();
-  }
-  // ---- actions out (the caller's buffer is outside the arena: ordinary stores, visible at the kernel's end)
-  if ((int)blockIdx.x == 0) {
-    bar.wait();
-    for (int i = threadIdx.x; i < P.x_elems; i += PK_THREADS) P.actions[i] = cx.ld(P.emb.x_rw + i);
   }
 }
 
@@ -140,10 +163,11 @@ hipError_t expert_loop_max_blocks_per_cu(int* out) {
 }
 
 // Host-side checks of everything the kernel's indexing assumes; the caller has zeroed the barrier words.
-hipError_t launch_expert_loop(hipStream_t s, const ExpertLoopParams& P, int blocks) {
+hipError_t launch_expert_loop(hipStream_t s, const ExpertLoopParams& P, ExpertLoopParams* d_params, int blocks) {
+  if (d_params == nullptr || (reinterpret_cast<uintptr_t>(d_params) & 15) != 0) return hipErrorInvalidValue;
   if (blocks < 1 || blocks > 1024 || P.sync == nullptr || P.arena == nullptr || P.arena_bytes == 0 || P.spin_limit == 0)
     return hipErrorInvalidValue;
-  if (P.layers < 1 || P.steps < 1 || P.x_elems < 1 || P.noise == nullptr || P.actions == nullptr || P.emb.x_rw == nullptr)
+  if (P.layers < 1 || P.steps < 1 || P.x_elems < 1 || P.noise == nullptr || P.emb.x_rw == nullptr)
     return hipErrorInvalidValue;
   // every buffer that blocks exchange lies inside the arena (offsets are 32-bit)
   auto in_arena = [&](const void* p, size_t bytes) {
@@ -193,6 +217,9 @@ hipError_t launch_expert_loop(hipStream_t s, const ExpertLoopParams& P, int bloc
   if (P.emb.a.X % 32 != 0 || P.emb.a.gain == nullptr || P.emb.a.stat_parts == nullptr || P.emb.a.x != P.emb.x_rw) return hipErrorInvalidValue;
   if (!in_arena(P.emb.x_rw, (size_t)P.x_elems * 4) || !in_arena(P.stok.out, (size_t)P.stok.X * 4)) return hipErrorInvalidValue;
   if (P.stok.sd < 1 || P.stok.sd > 32) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(expert_loop_kernel, dim3(blocks), dim3(PK_THREADS), expert_loop_smem_bytes(), s, P);
+  hipLaunchKernelGGL(expert_loop_params_kernel, dim3(1), dim3(64), 0, s, P, d_params);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(expert_loop_kernel, dim3(blocks), dim3(PK_THREADS), expert_loop_smem_bytes(), s, d_params);
   return hipGetLastError();
 }

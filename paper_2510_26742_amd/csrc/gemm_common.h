@@ -280,7 +280,7 @@ template <int PRO, int EPI, int MS, class Cx>
 __device__ __forceinline__ void gemm_skinny_body(const GemmParams& p, const Cx& cx, unsigned char* smem_raw) {
   constexpr int NMB = MS ? 1 : 2;              // token blocks per block
   float* red = reinterpret_cast<float*>(smem_raw);                 // [8 waves][2][16][64]
-  const int t = threadIdx.x;
+  const int t = cx.tid();
   const int lane = t & 63;
   const int w = t >> 6;
   const int lq = lane & 31;
@@ -439,7 +439,7 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
 template <int NS, class Cx>
 __device__ __forceinline__ void gemm_skinny16_body(const GemmParams& p, const Cx& cx, unsigned char* smem_raw) {
   float (*red)[64][4] = reinterpret_cast<float (*)[64][4]>(smem_raw);   // [SK_WAVES][64][4]
-  const int t = threadIdx.x;
+  const int t = cx.tid();
   const int lane = t & 63;
   const int w = t >> 6;
   const int li = lane & 15;

@@ -10,6 +10,7 @@
 #include <new>
 #include <vector>
 
+#include "expert_loop.h"
 #include "pi0_internal.h"
 
 namespace {
@@ -152,6 +153,7 @@ struct WsLayout {
   size_t lx, lx_b, lq, kcache, vcache, lattn, lmid;
   size_t stok, z, y, y_b, eq, ek, ev, eattn, eml, emid;
   size_t vstat, lstat, estat, estat_parts, pf_sink, vstat_parts, lstat_parts, progress;
+  size_t esync, eparams;             // persistent denoise kernel: barrier words, parameter block
   size_t lx8, lx8s, lmid8, lmid8s;   // MXFP8 copies of the prefix feed-forward inputs
   bool mx_ok = false;                // the prefix feed-forward shapes fit the MXFP8 kernels (multiples of 256)
   size_t total;
@@ -170,6 +172,8 @@ struct WsCursor {
   }
 };
 
+const int SK_KMAX_HOST = 1024;   // widest contraction of the expert's 32-feature skinny kernels
+const int PK_BLOCKS = 256;   // blocks of the persistent denoise kernel
 const int Z_MAX = 32;   // upper bound on split-K slices (sizes the partial-sum buffer)
 
 void ws_layout(const pi0_config& c, const Dims& d, WsLayout& w) {
@@ -294,6 +298,8 @@ void ws_layout(const pi0_config& c, const Dims& d, WsLayout& w) {
   w.estat_parts = cur.take((size_t)(d.X / 16) * 64 * 2 * 4);
   w.pf_sink = cur.take(1024 * 4);
   w.progress = cur.take(256);
+  w.esync = cur.take((size_t)GB_WORDS * 4);
+  w.eparams = cur.take(sizeof(ExpertLoopParams));
   {
     const int kmax = d.H * 256 > d.Fx ? d.H * 256 : d.Fx;
     w.epart = cur.take((size_t)ceil_div(round_up(kmax, 64), 1024) * 64 * round_up(d.X, 32) * 4);
@@ -347,6 +353,8 @@ struct Tune {
   // per SIMD no longer fits beside the compute kernels' registers), 6 loads in flight (more reads the
   // layer in a shorter burst that disturbs the compute launches, fewer arrives late), one layer ahead.
   int ras = 256, ral = 1, rat = 256, rad = 6;
+  // the whole denoise loop as one persistent kernel with grid barriers (1) or one launch per operation (0)
+  int pdn = 1;
 };
 
 struct pi0_ctx {
@@ -358,6 +366,7 @@ struct pi0_ctx {
   unsigned char* ws = nullptr;
   bool loaded = false;
   bool attrs_set = false;
+  bool pk_ok = false;                  // the device can hold the persistent denoise kernel's 256 blocks at once
   bool graph_mode = true;
   int precision = PI0_PRECISION_BF16;   // PI0_PRECISION_MXFP8_PREFIX_MLP: prefix gate||up / down on MXFP8 operands
   int cur_views = 0, cur_prompt = 0;   // shape of the valid prefill (0 views = none)
@@ -389,6 +398,7 @@ struct Run {
                                 // blocks inside the launches with pi0_tune "ras=0"); false: neither
   int cls = PI0_OP_MISC;        // class of the launches that follow
   OpTimer* timer = nullptr;     // when set, every RUN / RUN_GEMM launch is bracketed by an event pair
+  bool persistent_ok = false;   // the denoise loop may run as one persistent kernel (plain pi0_denoise / pi0_infer calls)
   bool ok() const { return err == hipSuccess; }
   void did(hipError_t e) {
     launches++;
@@ -731,7 +741,162 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
   }
 }
 
+
+// The denoise loop as ONE persistent kernel (expert_persistent.hip): the operations' parameters exactly as the
+// per-operation launches below fill them for layer 0 / step 0, plus the strides between layers.  Returns false
+// (nothing launched) when the shape or the tuning choices are outside what the kernel covers; the caller then
+// issues the per-operation launches.
+bool run_denoise_persistent(Run& r, int P) {
+  pi0_ctx* c = r.c;
+  const Dims& d = c->d;
+  const WsLayout& w = c->wl;
+  const Tune& T = c->tune;
+  if (!T.pdn || !r.persistent_ok || !c->pk_ok || r.timer != nullptr) return false;
+  const int chunk = c->cfg.chunk;
+  const int pchunks = ceil_div(P, 32);
+  if (!T.ae16 || !T.qms || d.H != 8 || d.X > SK_KMAX_HOST || d.X % 256 != 0) return false;
+  const int shares = pchunks > T.kcps ? ceil_div(pchunks, T.kcps) : 1;
+  if (T.kcps > 8 || shares > 4 || (shares > 1 && !T.ksplit)) return false;
+  const WsTr& L0 = w.exp[0];
+  if (L0.o.k_pad != 2048 || (L0.down.k_pad != 2048 && L0.down.k_pad != 4096)) return false;
+  size_t wst = 0, gst = 0;
+  if (d.Le > 1) {
+    wst = w.exp[1].qkv.w - w.exp[0].qkv.w;
+    gst = w.g_e1[1] - w.g_e1[0];
+    for (int l = 1; l < d.Le; l++) {
+      const WsTr &A = w.exp[l - 1], &B = w.exp[l];
+      if (B.qkv.w - A.qkv.w != wst || B.o.w - A.o.w != wst || B.gu.w - A.gu.w != wst || B.down.w - A.down.w != wst) return false;
+      if (w.g_e1[l] - w.g_e1[l - 1] != gst || w.g_e2[l] - w.g_e2[l - 1] != gst) return false;
+    }
+    if (wst % 2 != 0 || gst % 4 != 0) return false;
+  }
+  const size_t arena_bytes = w.total - w.act_begin;
+  if (arena_bytes >= ((size_t)1 << 32)) return false;
+  if (r.count_only) {
+    r.launches += 3;   // barrier words cleared, parameter block written, the loop kernel
+    return true;
+  }
+  if (!r.ok()) return true;
+  ExpertLoopParams E;
+  memset(&E, 0, sizeof(E));
+  float* xa = at<float>(c, w.xa);
+  E.stok = StateTokenArgs{at<float>(c, w.st_state), d.SD, at<float>(c, w.state_w), at<float>(c, w.state_b), d.X, at<float>(c, w.stok), nullptr};
+  E.emb.a = ActionEmbedArgs{xa, chunk, d.A, at<float>(c, w.wfold), at<float>(c, w.bias_tab), d.X, at<bf16>(c, w.z), at<float>(c, w.stok),
+                            at<float>(c, w.y), at<bf16>(c, w.y_b), at<float>(c, w.g_e1[0]), at<float>(c, w.estat_parts)};
+  E.emb.x_rw = xa;
+  E.noise = at<float>(c, w.st_noise);
+  E.x_elems = chunk * d.A;
+  E.layers = d.Le;
+  E.steps = d.steps;
+  E.w_stride = wst / 2;
+  E.kcache_stride = w.kcache_layer / 2;
+  E.vcache_stride = w.vcache_layer / 2;
+  E.g_attn0 = at<float>(c, w.g_e1[0]);
+  E.g_mlp0 = at<float>(c, w.g_e2[0]);
+  E.g_final = at<float>(c, w.g_ef);
+  E.gain_stride = gst / 4;
+  {  // C2
+    GemmParams p = gp_base(c, w.tout, at<bf16>(c, w.z), d.X, chunk, TILE_SKINNY, d.X);
+    p.bias = at<float>(c, w.tout.bias);
+    p.out_f32 = at<float>(c, w.y);
+    p.out_bf16 = at<bf16>(c, w.y_b);
+    p.ldo = d.X; p.ldo2 = d.X; p.n_valid = d.X; p.row_offset = 1;
+    p.gain = at<float>(c, w.g_e1[0]);
+    p.stat_out = at<float>(c, w.estat_parts);
+    E.tout = p;
+  }
+  E.parts_first = w.tout.n_pad / 32;
+  E.parts_rest = L0.down.n_pad / 16;
+  {  // C3
+    GemmParams p = gp_base(c, L0.qkv, at<bf16>(c, w.y_b), d.X, 64, TILE_SKINNY, d.X);
+    p.rowstat = at<float>(c, w.estat_parts);
+    p.rowstat_parts = E.parts_first;
+    p.out_bf16 = at<bf16>(c, w.eq);
+    p.q_mbs = 2;
+    p.kfrag = at<bf16>(c, w.ek); p.vfrag = at<bf16>(c, w.ev);
+    p.rope = at<float>(c, w.rope);
+    p.pos0 = P;
+    p.q_cols = d.H * 256; p.k_cols = 256;
+    p.head_dim = 256; p.dqk_pad = 256; p.nvb = 8; p.kv_heads = 1; p.kv_chunks = 2;
+    p.m_split = 1;
+    E.qkv = p;
+  }
+  {  // C4 + C5
+    AttnParams a;
+    memset(&a, 0, sizeof(a));
+    a.q = at<bf16>(c, w.eq); a.q_head_stride = 2 * 16 * 512;
+    a.Tq = 64; a.heads = d.H;
+    a.k0 = reinterpret_cast<bf16*>(c->ws + w.kcache + (size_t)r.slot_r * w.kcache_slot);
+    a.v0 = reinterpret_cast<bf16*>(c->ws + w.vcache + (size_t)r.slot_r * w.vcache_slot);
+    a.chunks0 = pchunks; a.valid0 = P;
+    a.k1 = at<bf16>(c, w.ek); a.v1 = at<bf16>(c, w.ev); a.chunks1 = 2;
+    a.suffix_mask = 1;
+    a.scale = 1.0f / 16.0f;
+    a.out = at<bf16>(c, w.eattn); a.out_ld = d.H * 256; a.head_dim = 256;
+    if (shares > 1) {
+      a.key_splits = shares;
+      a.chunks_per_split = T.kcps;
+      a.out_split_stride = (size_t)64 * d.H * 256;
+      a.ml_out = at<float>(c, w.eml);
+    }
+    a.v_split = T.avs > 0 ? T.avs : (shares == 1 ? 4 : 2);
+    if (a.v_split != 1 && a.v_split != 2 && a.v_split != 4 && a.v_split != 8) return false;
+    E.att = a;
+    E.att_gx = 2 * a.v_split;
+    E.att_items = E.att_gx * d.H * shares;
+  }
+  auto resid = [&](const PW& pw, const bf16* X, int K, const float* gain) {
+    GemmParams p = gp_base(c, pw, X, K, 64, TILE_SKINNY16, K);
+    p.resid = at<float>(c, w.y);
+    p.out_f32 = at<float>(c, w.y);
+    p.out_bf16 = at<bf16>(c, w.y_b);
+    p.ldo = d.X; p.ldo2 = d.X; p.n_valid = d.X;
+    p.stat_out = at<float>(c, w.estat_parts);
+    p.gain = gain;
+    return p;
+  };
+  E.o = resid(L0.o, at<bf16>(c, w.eattn), d.H * 256, at<float>(c, w.g_e2[0]));   // C6
+  if (shares > 1) {
+    E.o.xsplits = shares;
+    E.o.xsplit_stride = (size_t)64 * d.H * 256;
+    E.o.xsplit_ml = at<float>(c, w.eml);
+  }
+  {  // C7
+    GemmParams p = gp_base(c, L0.gu, at<bf16>(c, w.y_b), d.X, 64, TILE_SKINNY, d.X);
+    p.rowstat = at<float>(c, w.estat_parts);
+    p.rowstat_parts = L0.o.n_pad / 16;
+    p.out_bf16 = at<bf16>(c, w.emid);
+    p.ldo = d.Fx;
+    E.gu = p;
+  }
+  E.dn = resid(L0.down, at<bf16>(c, w.emid), d.Fx, at<float>(c, d.Le > 1 ? w.g_e1[1] : w.g_ef));   // C8
+  E.m16 = 4;
+  E.dn_ns = L0.down.k_pad == 4096 ? 16 : 8;
+  {  // C9
+    GemmParams p = gp_base(c, w.outp, at<bf16>(c, w.y_b), d.X, 64, TILE_SKINNY, d.X);
+    p.rowstat = at<float>(c, w.estat_parts);
+    p.rowstat_parts = L0.down.n_pad / 16;
+    p.bias = at<float>(c, w.outp.bias);
+    p.out_f32 = xa;
+    p.ldo = d.A; p.n_valid = d.A; p.dt = -1.0f / (float)d.steps;
+    E.outp = p;
+  }
+  E.sync = at<unsigned>(c, w.esync);
+  E.arena = reinterpret_cast<const char*>(c->ws + w.act_begin);
+  E.arena_bytes = (unsigned)arena_bytes;
+  E.spin_limit = 1u << 20;
+  r.cls = PI0_OP_MISC;
+  // barrier words restart at zero (the error word, first, stays as it is)
+  RUN(r, launch_fill_zero(r.s, at<unsigned>(c, w.esync) + GB_START, (size_t)(GB_WORDS - GB_START) * 4));
+  if (r.ok()) {
+    r.did(launch_expert_loop(r.s, E, at<ExpertLoopParams>(c, w.eparams), PK_BLOCKS));
+    r.launches++;   // two launches: parameter block, loop kernel
+  }
+  return true;
+}
+
 void run_denoise(Run& r, int P, Taps* taps) {
+  if (taps == nullptr && run_denoise_persistent(r, P)) return;
   pi0_ctx* c = r.c;
   const Dims& d = c->d;
   const WsLayout& w = c->wl;
@@ -1024,6 +1189,7 @@ int execute(pi0_ctx* c, int kind, int n_views, int n_prompt, hipStream_t s, int 
     r.slot_w = slot_w;
     r.slot_r = slot_r;
     r.read_ahead = read_ahead;
+    r.persistent_ok = read_ahead;   // two-stream frames keep the per-operation launches: the prefill's blocks need the compute units too
     body(r);
     return r.ok() ? PI0_OK : fail_hip(c, r.err);
   }
@@ -1037,6 +1203,7 @@ int execute(pi0_ctx* c, int kind, int n_views, int n_prompt, hipStream_t s, int 
     r.slot_w = slot_w;
     r.slot_r = slot_r;
     r.read_ahead = read_ahead;
+    r.persistent_ok = read_ahead;   // two-stream frames keep the per-operation launches: the prefill's blocks need the compute units too
     body(r);
     hipGraph_t g = nullptr;
     e = hipStreamEndCapture(s, &g);
@@ -1157,7 +1324,7 @@ int pi0_tune(pi0_ctx* c, const char* env) {
         {"zld", &c->tune.zld, 1, Z_MAX}, {"zvd", &c->tune.zvd, 1, Z_MAX},
         {"pfq", &c->tune.pfq, 0, 1024}, {"pfa", &c->tune.pfa, 0, 1024}, {"pfo", &c->tune.pfo, 0, 1024},
         {"pfd", &c->tune.pfd, 0, 1024}, {"ae16", &c->tune.ae16, 0, 1}, {"ksplit", &c->tune.ksplit, 0, 1}, {"kcps", &c->tune.kcps, 2, 16}, {"qms", &c->tune.qms, 0, 1},
-        {"fko", &c->tune.fko, 0, 1}, {"fkl", &c->tune.fkl, 0, 1}, {"ras", &c->tune.ras, 0, 4096}, {"ral", &c->tune.ral, 1, 8}, {"rat", &c->tune.rat, 64, 256}, {"rad", &c->tune.rad, 1, 8 /* 7: no such variant, see below */}, {"avs", &c->tune.avs, 1, 8}};
+        {"fko", &c->tune.fko, 0, 1}, {"fkl", &c->tune.fkl, 0, 1}, {"ras", &c->tune.ras, 0, 4096}, {"ral", &c->tune.ral, 1, 8}, {"rat", &c->tune.rat, 64, 256}, {"rad", &c->tune.rad, 1, 8 /* 7: no such variant, see below */}, {"avs", &c->tune.avs, 1, 8}, {"pdn", &c->tune.pdn, 0, 1}};
     for (auto& k : keys) {
       const char* f = strstr(env, k.key);
       while (f != nullptr && !((f == env || f[-1] == ',') && f[strlen(k.key)] == '=')) f = strstr(f + 1, k.key);
@@ -1189,9 +1356,21 @@ int pi0_set_precision(pi0_ctx* c, int precision) {
 
 int pi0_last_hip_error(const pi0_ctx* c) { return c ? c->last_hip : 0; }
 
+int pi0_device_status(pi0_ctx* c, void* hip_stream) {
+  if (c == nullptr) return PI0_EINVAL;
+  if (!c->loaded) return PI0_ESTATE;
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  unsigned flag = 0;
+  hipError_t e = hipMemcpyAsync(&flag, at<unsigned>(c, c->wl.esync) + GB_ERR, sizeof(flag), hipMemcpyDeviceToHost, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  if (e != hipSuccess) return fail_hip(c, e);
+  return flag == 0u ? PI0_OK : PI0_ESTATE;
+}
+
 int pi0_kernel_count(const pi0_ctx* c, int n_views, int n_prompt) {
   if (c == nullptr || n_views < 1 || n_views > c->cfg.max_views || n_prompt < 0 || n_prompt > c->cfg.max_prompt) return 0;
   Run r{const_cast<pi0_ctx*>(c), nullptr, true};
+  r.persistent_ok = true;
   run_prefill(r, n_views, n_prompt, nullptr);
   run_denoise(r, n_views * c->d.T + n_prompt, nullptr);
   return r.launches;
@@ -1220,6 +1399,16 @@ int pi0_load_weights(pi0_ctx* c, const void* d_blob, size_t blob_bytes, void* d_
     if (e != hipSuccess) return fail_hip(c, e);
     e = gemm_mx_init_attributes();
     if (e != hipSuccess) return fail_hip(c, e);
+    e = expert_loop_init_attributes();
+    if (e != hipSuccess) return fail_hip(c, e);
+    {  // the persistent kernel's barrier needs all of its blocks resident: one per compute unit, 256 of them
+      int dev = 0, cus = 0, per_cu = 0;
+      e = hipGetDevice(&dev);
+      if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+      if (e == hipSuccess) e = expert_loop_max_blocks_per_cu(&per_cu);
+      if (e != hipSuccess) return fail_hip(c, e);
+      c->pk_ok = cus >= PK_BLOCKS && per_cu >= 1;
+    }
     c->attrs_set = true;
   }
 #define TRY(call) do { e = (call); if (e != hipSuccess) return fail_hip(c, e); } while (0)

@@ -43,14 +43,14 @@ def cosine(a, b):
 class Case:
     """One (config, weights) pair loaded on the GPU plus the oracle-side view of the same bytes."""
 
-    def __init__(self, cfg, seed=0, overrides=None):
+    def __init__(self, cfg, seed=0, overrides=None, tune=None):
         self.cfg = cfg
         self.dev = torch.device("cuda:0")
         say(f"[case] generating weights layers={cfg.vis_layers}/{cfg.llm_layers}/{cfg.exp_layers} vocab={cfg.vocab}")
         self.blob = synth.make_weights(cfg, seed=seed, overrides=overrides)
         self.tensors = synth.blob_views(cfg, self.blob)
         self.stream = torch.cuda.Stream(device=self.dev)
-        self.m = binding.Pi0(cfg)
+        self.m = binding.Pi0(cfg, tune=tune)
         d_blob = torch.from_numpy(self.blob.view(np.int16)).to(self.dev)
         say("[case] pi0_load_weights")
         self.m.pi0_load_weights(d_blob, self.stream)
@@ -89,6 +89,15 @@ class Case:
         d_img, d_st, d_nz, d_ids = self.to_dev(img, st, nz, ids)
         d_act = torch.empty((cfg.chunk, cfg.action_dim), dtype=torch.float32, device=self.dev)
         self.m.pi0_infer(d_img, img.shape[0], d_ids, len(ids), d_st, d_nz, d_act, self.stream)
+        self.stream.synchronize()
+        return d_act.cpu().numpy()
+
+    def denoise_only(self, st, nz):
+        """pi0_denoise on the cache of the last prefill."""
+        cfg = self.cfg
+        d_st, d_nz = torch.from_numpy(st).to(self.dev), torch.from_numpy(nz).to(self.dev)
+        d_act = torch.empty((cfg.chunk, cfg.action_dim), dtype=torch.float32, device=self.dev)
+        self.m.pi0_denoise(d_st, d_nz, d_act, self.stream)
         self.stream.synchronize()
         return d_act.cpu().numpy()
 
@@ -453,13 +462,54 @@ def test_two_stream_frames_match_sequential(reduced):
     np.testing.assert_array_equal(out.cpu().numpy(), ref[k - 1])
 
 
+def test_persistent_denoise_loop_equals_per_operation_launches():
+    """The denoise loop as one persistent kernel with software grid barriers (Section 5.2) runs the same bodies on
+    the same work items as the per-operation launches: same bits, for one prefix share (1 view), two (2 views), three
+    (3 views) and four ragged ones (3 views + 48 prompt tokens), as a graph replay and eagerly, also through
+    pi0_denoise alone on the cached prefix with fresh noise; no barrier wait runs out."""
+    cfg = synth.reduced_config(vocab=1024)
+    shapes = [(1, 0), (2, 0), (3, 0), (3, 48), (1, 7)]
+    outs = {}
+    for tune in ("pdn=0", "pdn=1"):
+        case = Case(cfg, tune=tune)
+        try:
+            for n_views, n_prompt in shapes:
+                say(f"[gpu] {tune} views={n_views} prompt={n_prompt}")
+                img, st, nz, ids = case.inputs(n_views, n_prompt)
+                a = case.infer(img, st, nz, ids)
+                b = case.infer(img, st, nz, ids)          # replay
+                case.m.pi0_set_graph_mode(False)
+                c = case.infer(img, st, nz, ids)          # eager
+                case.m.pi0_set_graph_mode(True)
+                np.testing.assert_array_equal(a, b)
+                np.testing.assert_array_equal(a, c)
+                # streaming use: denoise alone on the cache of the prefill above, other state / noise
+                _, st2, nz2, _ = case.inputs(n_views, n_prompt, seed_shift=50)
+                d = case.denoise_only(st2, nz2)
+                assert np.isfinite(d).all() and not np.array_equal(d, a)
+                outs[(tune, n_views, n_prompt)] = (a, d)
+            case.m.pi0_device_status(case.stream)
+            n_launch = case.m.pi0_kernel_count(1, 0)
+            say(f"[gpu] {tune}: {n_launch} launches per pi0_infer at 1 view")
+            outs[(tune, "launches")] = n_launch
+        finally:
+            case.close()
+    for n_views, n_prompt in shapes:
+        for i, what in enumerate(("infer", "denoise")):
+            np.testing.assert_array_equal(outs[("pdn=1", n_views, n_prompt)][i], outs[("pdn=0", n_views, n_prompt)][i],
+                                          err_msg=f"{what} views={n_views} prompt={n_prompt}")
+    # 5 launches per layer-step and 3 per Euler step become 3 launches in all
+    assert outs[("pdn=0", "launches")] - outs[("pdn=1", "launches")] >= 10 * (5 * cfg.exp_layers + 3) - 3
+
+
 def test_reading_ahead_changes_no_bit():
     """The expert's read-ahead kernel and the warm-up blocks only load: the actions of a pass with either of them,
     with neither, and with another shape of the read-ahead kernel are the same bits (graph replay and eager).  So are
     they with the value slices of the expert attention on one block or on eight: every block repeats the same scores."""
     import os
     outs = {}
-    for tune in ("", "ras=0", "ras=0,pfq=0,pfa=0,pfo=0,pfd=0", "ras=128,rat=128,rad=3,ral=2", "avs=1", "avs=8"):
+    for tune in ("", "pdn=0", "pdn=0,ras=0", "pdn=0,ras=0,pfq=0,pfa=0,pfo=0,pfd=0", "pdn=0,ras=128,rat=128,rad=3,ral=2", "pdn=0,avs=1",
+                 "pdn=0,avs=8", "avs=1", "avs=8"):
         if tune:
             os.environ["PI0_TUNE"] = tune
         try:
