@@ -61,6 +61,7 @@ struct GridBarrier {
   unsigned n_xcc;       // dies that hold at least one block
   unsigned spin_limit;
   unsigned epoch;       // barriers this block has arrived at
+  unsigned waited;      // last barrier this block has seen completed
 
   __device__ __forceinline__ static unsigned ld_dev(const unsigned* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
   __device__ __forceinline__ static void st_dev(unsigned* p, unsigned v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
@@ -70,6 +71,7 @@ struct GridBarrier {
     w = words;
     spin_limit = limit;
     epoch = 0;
+    waited = 0;
     xcc = (unsigned)__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 7u;   // XCC_ID, bits 3:0
     if (threadIdx.x == 0) {
       __hip_atomic_fetch_add(&w[GB_MEMBERS + 32 * xcc], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -88,7 +90,11 @@ struct GridBarrier {
 
   // all threads of the block, after the block's last store of the operation
   __device__ __forceinline__ void arrive() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // this wave's stores have been acknowledged
+    // A block with no work item in an operation does not wait for that operation's inputs; it must still see the
+    // barrier before completed, or its two arrivals in a row would be counted towards one barrier of its die.
+    if (waited != epoch) wait();
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's stores have been acknowledged (a workgroup-scope
+                                                        // fence does not wait for them)
     __syncthreads();
     epoch++;
     if (threadIdx.x == 0) {
@@ -113,6 +119,7 @@ struct GridBarrier {
       }
     }
     __syncthreads();
+    waited = epoch;
   }
 };
 

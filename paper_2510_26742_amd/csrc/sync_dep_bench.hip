@@ -245,7 +245,7 @@ __global__ __launch_bounds__(256) void sync_dep_kernel(float* x, int planes, con
     }
     if (op + 1 < n_ops) {
       // every store of the block has been acknowledged before anyone announces the block's arrival
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // a workgroup-scope fence does not wait for global stores
       __syncthreads();
       if (t < 64) {
         // device-scope release: the die's dirty lines are written back (FENCE) and - for every dependent data path -
