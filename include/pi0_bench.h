@@ -186,6 +186,19 @@ int pi0_sync_dep_bench(int barrier, int data, int fan, int n_ops, int reps, floa
                        unsigned* d_state, double* h_ms, void* hip_stream);
 
 /*
+ * Timeline of the persistent denoise kernel (Section 5.2: where the time between two software barriers goes).
+ * With a buffer set, thread 0 of every block notes the 100 MHz wall clock four times per operation of the loop:
+ * operation entered (its constant operands are requested next), inputs complete (the wait for the barrier of the
+ * operation before is over; 0 if the block has no work item in this operation), body done, arrival announced.
+ *   d_trace  device, int64 [ops_cap][256 blocks][4], 8-byte aligned; NULL with ops_cap 0 switches the timeline off
+ *   operations are numbered in execution order: 0 = state token; per Euler step: embed, second linear, per layer
+ *   QKV, attention, O, gate||up, down; then out-projection + Euler.  pi0_loop_trace_ops gives their number.
+ * Drops every captured graph.  Must not be called while work of this ctx is in flight.  Errors: EINVAL.
+ */
+int pi0_loop_trace_ops(const pi0_ctx* ctx);
+int pi0_set_loop_trace(pi0_ctx* ctx, long long* d_trace, int ops_cap);
+
+/*
  * Per-shape kernel choices for tuning runs (Section 4.1 of the paper tunes tiles per GEMM shape): `spec` is a
  * comma-separated list of key=value pairs, e.g. "lgu=7,zld=16,ras=0"; unknown keys and values outside a key's
  * range are ignored.  Keys: tile ids (vis, vqkv, vup, lqkv, lgu, vo, vd, lo, ld), split counts (zvo, zvd, zlo,

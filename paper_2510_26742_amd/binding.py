@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libpi0_hip.so")
 EXPORTS = ["pi0_create", "pi0_destroy", "pi0_weights_bytes", "pi0_workspace_bytes", "pi0_load_weights",
            "pi0_prefill", "pi0_denoise", "pi0_infer", "pi0_debug_taps_elems", "pi0_debug_forward", "pi0_debug_profile", "pi0_sync_bench", "pi0_peak_bench", "pi0_clock_sample", "pi0_read_ahead_probe", "pi0_stream_frame",
            "pi0_set_graph_mode", "pi0_set_precision", "pi0_kernel_count", "pi0_strerror", "pi0_last_hip_error",
-           "pi0_sync_dep_bench", "pi0_tune", "pi0_device_status"]
+           "pi0_sync_dep_bench", "pi0_tune", "pi0_device_status", "pi0_loop_trace_ops", "pi0_set_loop_trace"]
 
 # enum pi0_op_class, in order
 OP_CLASSES = ["misc", "vis_patch", "vis_qkv", "vis_attn", "vis_o", "vis_up", "vis_down", "vis_proj", "reduce",
@@ -82,6 +82,10 @@ def lib() -> ctypes.CDLL:
         L.pi0_sync_dep_bench.restype = i32
         L.pi0_device_status.argtypes = [vp, vp]
         L.pi0_device_status.restype = i32
+        L.pi0_loop_trace_ops.argtypes = [vp]
+        L.pi0_loop_trace_ops.restype = i32
+        L.pi0_set_loop_trace.argtypes = [vp, vp, i32]
+        L.pi0_set_loop_trace.restype = i32
         L.pi0_tune.argtypes = [vp, ctypes.c_char_p]
         L.pi0_tune.restype = i32
         L.pi0_peak_bench.argtypes = [i32, vp, sz, i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
@@ -286,6 +290,13 @@ class Pi0:
     def pi0_device_status(self, stream=None):
         """Synchronises the stream; raises if a bounded wait inside a kernel ran out."""
         self._check(lib().pi0_device_status(self._ctx, self._stream(stream)))
+
+    def pi0_loop_trace_ops(self) -> int:
+        return int(lib().pi0_loop_trace_ops(self._ctx))
+
+    def pi0_set_loop_trace(self, d_trace):
+        """d_trace: int64 CUDA tensor [ops, 256, 4] or None (off)."""
+        self._check(lib().pi0_set_loop_trace(self._ctx, _ptr(d_trace), 0 if d_trace is None else int(d_trace.shape[0])))
 
     def pi0_set_graph_mode(self, enabled: bool):
         self._check(lib().pi0_set_graph_mode(self._ctx, 1 if enabled else 0))

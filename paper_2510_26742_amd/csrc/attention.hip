@@ -34,7 +34,7 @@ template <int DQK>
 static int attn_smem(int ntot) { return 3 * (DQK / 16) * 1024 + 2 * ATT_WAVES * 32 * 4 + ntot * 2048; }
 
 #define ATTN_VARIANTS(X) \
-  X(256, 8, 1, 10)       \
+  X(256, 8, 1, 8)        \
   X(256, 8, 2, 8)        \
   X(256, 8, 4, 8)        \
   X(80, 3, 1, 8)
@@ -87,7 +87,7 @@ hipError_t launch_attention(hipStream_t s, const AttnParams& p) {
     grid.y += d.blocks / grid.x;
   }
   if (p.head_dim == 256) {
-    if (n0 <= 8) attention_kernel<256, 8, 1, 10><<<grid, dim3(512), attn_smem<256>(ntot), s>>>(p);
+    if (n0 <= 8) attention_kernel<256, 8, 1, 8><<<grid, dim3(512), attn_smem<256>(ntot), s>>>(p);
     else if (n0 <= 16) attention_kernel<256, 8, 2, 8><<<grid, dim3(512), attn_smem<256>(ntot), s>>>(p);
     else attention_kernel<256, 8, 4, 8><<<grid, dim3(512), attn_smem<256>(ntot), s>>>(p);
   } else if (p.head_dim <= 80 && p.head_dim > 64) {

@@ -58,61 +58,53 @@ __device__ __forceinline__ void attention_body(const AttnParams& p, const Cx& cx
     n0 = min(p.chunks_per_split, p.chunks0 - cbeg0);
     if (cx.bz != p.key_splits - 1) n1 = 0;
   }
-  const int ntot = n0 + n1;
   const bf16* kbase0 = p.k0 + ((size_t)head * p.kv_head_stride0 + (size_t)cbeg0 * S16 * 512) + lane * 8;
   const bf16* vbase0 = p.v0 + ((size_t)head * p.v_head_stride0 + (size_t)cbeg0 * NVB * 1024);
-  auto vptr = [&](int ci) -> const bf16* {   // ci clamped by the caller
-    return (ci >= n0 ? p.v1 + (size_t)(ci - n0) * NVB * 1024 : vbase0 + (size_t)ci * NVB * 1024) + slice * 1024 + lane * 8;
-  };
+  const bf16* vslice0 = vbase0 + slice * 1024 + lane * 8;   // this wave's slice of the value fragments of segment 0
 
   // ---- issue every load of the first round (unconditional, clamped addresses) -----------------
   // Keys and values of segment 0 are constants of a persistent kernel (the prefix cache): requested before the
   // wait for this operation's inputs (Q and the second segment, which the QKV projection before produced).
-  // value fragment ci of this wave's slice: chunks of the second segment come through the context
-  auto ldv = [&](int ci, int half) -> bf16x8 {   // ci clamped by the caller
-    const bf16* vp = vptr(ci) + (size_t)half * 512;
-    return ci >= n0 ? cx.ld(reinterpret_cast<const bf16x8*>(vp)) : *reinterpret_cast<const bf16x8*>(vp);
-  };
   const bf16* qsrc = p.q + (size_t)head * p.q_head_stride + (size_t)tile * S16 * 512;
   bf16x8 qreg[QP];
   bf16x8 k1reg[KP1];
   bf16x8 kf[S16];
-  bf16x8 vf[VRING * 2];
+  bf16x8 vf[VRING * 2];      // ring over the chunks of segment 0
+  bf16x8 vs1[4];             // the (at most two) chunks of segment 1
   const bool pv_wave = w < nslice;
-  auto load_k0 = [&]() {
+  auto load_seg0 = [&]() {
     const bf16* kp0 = kbase0 + (size_t)min(w, n0 - 1) * S16 * 512;
 #pragma unroll
     for (int s = 0; s < S16; s++) kf[s] = *reinterpret_cast<const bf16x8*>(kp0 + (size_t)s * 512);
-  };
-  auto load_v_ring = [&](bool seg0) {   // the ring's first round: chunks of segment 0 (seg0) or of segment 1
     if (pv_wave) {
 #pragma unroll
       for (int c = 0; c < VRING; c++) {
-        const int ci = min(c, ntot - 1);
-        if ((ci < n0) == seg0) {
-          vf[2 * c] = ldv(ci, 0);
-          vf[2 * c + 1] = ldv(ci, 1);
-        }
+        const bf16* vp = vslice0 + (size_t)min(c, n0 - 1) * NVB * 1024;
+        vf[2 * c] = *reinterpret_cast<const bf16x8*>(vp);
+        vf[2 * c + 1] = *reinterpret_cast<const bf16x8*>(vp + 512);
       }
     }
   };
   if (Cx::kPersistent) {
-    load_k0();
-    load_v_ring(true);
+    load_seg0();
     cx.wait_inputs();
   }
 #pragma unroll
-  for (int i = 0; i < QP; i++) qreg[i] = cx.ld(reinterpret_cast<const bf16x8*>(qsrc + (size_t)min(t + i * 512, NPQ - 1) * 8));
+  for (int i = 0; i < QP; i++) qreg[i] = cx.ld_bulk(reinterpret_cast<const bf16x8*>(qsrc + (size_t)min(t + i * 512, NPQ - 1) * 8));
   if (n1 > 0) {
 #pragma unroll
     for (int i = 0; i < KP1; i++)
-      k1reg[i] = cx.ld(reinterpret_cast<const bf16x8*>(p.k1 + (size_t)min(t + i * 512, n1 * S16 * 64 - 1) * 8));
+      k1reg[i] = cx.ld_bulk(reinterpret_cast<const bf16x8*>(p.k1 + (size_t)min(t + i * 512, n1 * S16 * 64 - 1) * 8));
+    if (pv_wave) {
+#pragma unroll
+      for (int c = 0; c < 2; c++) {
+        const bf16* vp = p.v1 + (size_t)min(c, n1 - 1) * NVB * 1024 + slice * 1024 + lane * 8;
+        vs1[2 * c] = cx.ld_bulk(reinterpret_cast<const bf16x8*>(vp));
+        vs1[2 * c + 1] = cx.ld_bulk(reinterpret_cast<const bf16x8*>(vp + 512));
+      }
+    }
   }
-  if (!Cx::kPersistent) {
-    load_k0();
-    load_v_ring(true);
-  }
-  load_v_ring(false);
+  if (!Cx::kPersistent) load_seg0();
 #pragma unroll
   for (int i = 0; i < QP; i++) {
     const int pc = t + i * 512;
@@ -243,30 +235,43 @@ __device__ __forceinline__ void attention_body(const AttnParams& p, const Cx& cx
   f32x16 o, o1;
 #pragma unroll
   for (int e = 0; e < 16; e++) o[e] = 0.f, o1[e] = 0.f;
-  // One ring of VRING chunks per round: the probability fragments of the whole round are read
+  // Segment 0: one ring of VRING chunks per round: the probability fragments of the whole round are read
   // from LDS up front (clamped, unconditional), chunks beyond the end multiply zeros; the value
   // fragments of the next round are requested (whole round, one uniform branch) as the registers
-  // of this round are consumed.
+  // of this round are consumed.  Then the chunks of segment 1, whose value fragments came with Q.
   const bf16x8 zero8v = {(bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f};
-  for (int c0 = 0; c0 < ntot; c0 += VRING) {
+  for (int c0 = 0; c0 < n0; c0 += VRING) {
     bf16x8 bp[2 * VRING];
 #pragma unroll
     for (int cc = 0; cc < VRING; cc++) {
-      const int c = min(c0 + cc, ntot - 1);
+      const int c = min(c0 + cc, n0 - 1);
 #pragma unroll
       for (int s2 = 0; s2 < 2; s2++)
         bp[2 * cc + s2] = *reinterpret_cast<const bf16x8*>(pf + ((size_t)(c * 2 + s2) * 64 + lane) * 8);
     }
-    const bool more_round = c0 + VRING < ntot;
+    const bool more_round = c0 + VRING < n0;
 #pragma unroll
     for (int cc = 0; cc < VRING; cc++) {
-      const bool live = c0 + cc < ntot;
+      const bool live = c0 + cc < n0;
 #pragma unroll
       for (int s2 = 0; s2 < 2; s2++) {
         const bf16x8 a = vf[2 * cc + s2];
-        if (more_round) vf[2 * cc + s2] = ldv(min(c0 + cc + VRING, ntot - 1), s2);
+        if (more_round) vf[2 * cc + s2] = *reinterpret_cast<const bf16x8*>(vslice0 + (size_t)min(c0 + cc + VRING, n0 - 1) * NVB * 1024 + (size_t)s2 * 512);
         if (DUAL && s2) o1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, live ? bp[2 * cc + s2] : zero8v, o1, 0, 0, 0);
         else o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, live ? bp[2 * cc + s2] : zero8v, o, 0, 0, 0);
+      }
+    }
+  }
+  if (n1 > 0) {
+#pragma unroll
+    for (int cc = 0; cc < 2; cc++) {
+      const bool live = cc < n1;
+      const int c = n0 + min(cc, n1 - 1);
+#pragma unroll
+      for (int s2 = 0; s2 < 2; s2++) {
+        const bf16x8 bpv = *reinterpret_cast<const bf16x8*>(pf + ((size_t)(c * 2 + s2) * 64 + lane) * 8);
+        if (DUAL && s2) o1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vs1[2 * cc + s2], live ? bpv : zero8v, o1, 0, 0, 0);
+        else o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vs1[2 * cc + s2], live ? bpv : zero8v, o, 0, 0, 0);
       }
     }
   }

@@ -29,6 +29,8 @@ struct LaunchCtx {
   template <class T>
   __device__ __forceinline__ T ld(const T* p) const { return *p; }
   template <class T>
+  __device__ __forceinline__ T ld_bulk(const T* p) const { return *p; }
+  template <class T>
   __device__ __forceinline__ void st(T* p, const T& v) const { *p = v; }
   __device__ __forceinline__ void wait_inputs() const {}
   __device__ __forceinline__ int tid() const { return (int)threadIdx.x; }
@@ -37,10 +39,10 @@ struct LaunchCtx {
 // ------------------------------------------------------------------------------------------------
 // Grid barrier of the persistent kernel.  Arrivals are counted per die (hardware register XCC_ID names
 // the die a wave runs on); the block that completes a die's count performs ONE device-scope release for
-// the whole die (cache write-back, which also waits for the write-through stores in flight: an arrival
-// announced without it was observed to overtake the data it announces), adds to a root counter, and the
-// die that completes the root count publishes the epoch in one word per die, which the die's blocks poll
-// with back-off.  Arrive and wait are separate calls, so a block requests the next operation's constant
+// the whole die (cache write-back, which also waits for the write-through stores in flight) and then tells
+// every die, in a word of that die's own cache line, that this die has completed the epoch; a block polls
+// its die's line (one 32-byte load) until all dies that hold blocks have.  One read-modify-write and one
+// store-to-poll hop per barrier; a root counter between the two cost a second read-modify-write round trip.  Arrive and wait are separate calls, so a block requests the next operation's constant
 // operands between them.  Every wait is bounded: when the bound runs out the error word is raised, every
 // later wait returns at once, and the host reports the failure.
 // Words (unsigned, 128 bytes apart so that no two are in one cache line):
@@ -49,19 +51,19 @@ enum {
   GB_START = 32,       // start-up counter: blocks registered
   GB_MEMBERS = 64,     // + 32 x: blocks resident on die x
   GB_COUNT = 320,      // + 32 x: arrivals on die x (monotonic)
-  GB_ROOT = 576,       // dies whose count completed (monotonic)
-  GB_EPOCH = 608,      // + 32 x: last epoch published to die x
-  GB_WORDS = 864
+  GB_DONE = 576,       // + 32 y + x: last epoch that die x completed, as told to die y (one cache line per reading die)
+  GB_WORDS = 832
 };
 
 struct GridBarrier {
   unsigned* w;          // GB_WORDS words, zeroed before the launch
   unsigned xcc;         // die of this block
   unsigned members;     // blocks on this die
-  unsigned n_xcc;       // dies that hold at least one block
+  unsigned present;     // bit x set: die x holds at least one block
   unsigned spin_limit;
   unsigned epoch;       // barriers this block has arrived at
   unsigned waited;      // last barrier this block has seen completed
+  long long* trace;     // optional: where thread 0 notes the wall clock (100 MHz) when a wait ends
 
   __device__ __forceinline__ static unsigned ld_dev(const unsigned* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
   __device__ __forceinline__ static void st_dev(unsigned* p, unsigned v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
@@ -72,6 +74,7 @@ struct GridBarrier {
     spin_limit = limit;
     epoch = 0;
     waited = 0;
+    trace = nullptr;
     xcc = (unsigned)__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 7u;   // XCC_ID, bits 3:0
     if (threadIdx.x == 0) {
       __hip_atomic_fetch_add(&w[GB_MEMBERS + 32 * xcc], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -84,8 +87,8 @@ struct GridBarrier {
     }
     __syncthreads();
     members = ld_dev(&w[GB_MEMBERS + 32 * xcc]);
-    n_xcc = 0;
-    for (unsigned k = 0; k < 8u; k++) n_xcc += ld_dev(&w[GB_MEMBERS + 32 * k]) != 0u ? 1u : 0u;
+    present = 0;
+    for (unsigned k = 0; k < 8u; k++) present |= ld_dev(&w[GB_MEMBERS + 32 * k]) != 0u ? 1u << k : 0u;
   }
 
   // all threads of the block, after the block's last store of the operation
@@ -101,25 +104,30 @@ struct GridBarrier {
       const unsigned old = __hip_atomic_fetch_add(&w[GB_COUNT + 32 * xcc], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if (old + 1u == epoch * members) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");   // the die's writes are in memory
-        const unsigned oldr = __hip_atomic_fetch_add(&w[GB_ROOT], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (oldr + 1u == epoch * n_xcc) {
-          for (unsigned k = 0; k < 8u; k++) st_dev(&w[GB_EPOCH + 32 * k], epoch);
-        }
+        for (unsigned k = 0; k < 8u; k++) st_dev(&w[GB_DONE + 32 * k + xcc], epoch);
       }
     }
   }
 
   // all threads of the block: returns once every block has arrived at the barrier this block arrived at last
   __device__ __forceinline__ void wait() {
-    if (threadIdx.x == 0) {
+    if (threadIdx.x < 8) {   // lane x reads what die x has told this die
+      const unsigned lane = threadIdx.x;
+      const bool counts = ((present >> lane) & 1u) != 0u;
       unsigned spins = 0;
-      while (ld_dev(&w[GB_EPOCH + 32 * xcc]) < epoch) {
+      while (true) {
+        const bool behind = counts && ld_dev(&w[GB_DONE + 32 * xcc + lane]) < epoch;
+        if (__builtin_amdgcn_ballot_w64(behind) == 0ull) break;
         __builtin_amdgcn_s_sleep(1);
-        if (++spins > spin_limit || ld_dev(&w[GB_ERR]) != 0u) { st_dev(&w[GB_ERR], 1u); break; }
+        if (++spins > spin_limit || ld_dev(&w[GB_ERR]) != 0u) {
+          if (lane == 0) st_dev(&w[GB_ERR], 1u);
+          break;
+        }
       }
     }
     __syncthreads();
     waited = epoch;
+    if (trace != nullptr && threadIdx.x == 0) *trace = (long long)wall_clock64();
   }
 };
 
@@ -127,7 +135,14 @@ struct GridBarrier {
 // not hit in the die's L2 or the compute unit's L1)
 #define PI0_AUX_DEVICE_SCOPE 16
 
-struct PersistCtx {
+// BULK_CACHED: the operation's large inputs (activation matrices, statistic partials, attention operands) are read
+// with ordinary cached loads, so that the 32 blocks of a die fetch them from memory once instead of 32 times (read
+// past the L2 by every block, an operation's inputs cross the fabric 256 times: measured 2 - 3.5 us per operation).
+// That is only coherent if no cache of the reading die can hold an older copy of those addresses, which the caller
+// guarantees by giving every operation instance of the loop its own never-read buffers whose cache lines are each
+// written by one block only ("fresh" data path of the barrier experiment).
+template <bool BULK_CACHED>
+struct PersistCtxT {
   static constexpr bool kPersistent = true;
   int bx, by, bz;                  // work item of the current operation
   __amdgpu_buffer_rsrc_t arena;    // buffer resource over the activation arena
@@ -155,5 +170,17 @@ struct PersistCtx {
     else if constexpr (sizeof(T) == 4) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), arena, off(p), 0, PI0_AUX_DEVICE_SCOPE);
     else __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, v), arena, off(p), 0, PI0_AUX_DEVICE_SCOPE);
   }
+  template <class T>
+  __device__ __forceinline__ T ld_bulk(const T* p) const {
+    if constexpr (BULK_CACHED) return *p;
+    else return ld(p);
+  }
   __device__ __forceinline__ void wait_inputs() const { bar->wait(); }
+  template <bool B>
+  __device__ __forceinline__ PersistCtxT<B> as() const {
+    PersistCtxT<B> c;
+    c.bx = bx; c.by = by; c.bz = bz; c.arena = arena; c.arena_base = arena_base; c.bar = bar; c.thread = thread;
+    return c;
+  }
 };
+using PersistCtx = PersistCtxT<false>;

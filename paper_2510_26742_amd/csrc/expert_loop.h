@@ -26,11 +26,28 @@ struct ExpertLoopParams {
   int m16;                        // 16-token tiles of the O / down projections
   int dn_ns;                      // k steps per wave of the down projection: 16 (k = 4096) or 8 (k = 2048)
   int att_gx, att_items;          // attention work items: att_gx = 2 query tiles x value parts; x heads x key shares
+  // Ring of per-layer-step buffers (slot ls = step * layers + layer at ring + ls * ring_stride).  Every activation
+  // that one operation writes and the next reads with cached loads has its own place per layer-step, which nothing
+  // has read before in this launch (exec_ctx.h, BULK_CACHED); byte offsets inside a slot:
+  //   r_yb_o / r_st_o   gain-scaled bf16 copy of the residual stream and its statistic partials after the O projection
+  //   r_yb_d / r_st_d   the same after the down projection (input of the next layer's QKV / of the out-projection)
+  //   r_q, r_k, r_v     the QKV projection's outputs;  r_attn, r_ml  attention output shares and their (max, sum)
+  //   r_mid             GeGLU product
+  // The operation parameters above name the buffers of the per-operation launches; the kernel uses them for the first
+  // QKV projection of a step (its input rows come from two operations and share cache lines: read past the L2) and
+  // for the fp32 residual stream, which only ever crosses blocks as 1 KiB tiles read past the L2.
+  char* ring;
+  size_t ring_stride;
+  unsigned r_yb_o, r_st_o, r_yb_d, r_st_d, r_q, r_k, r_v, r_attn, r_ml, r_mid;
   // synchronisation and the memory that blocks exchange
   unsigned* sync;                 // GB_WORDS words, words >= GB_START zeroed before the launch
   const char* arena;              // every buffer written by one block and read by another lies in [arena, arena + arena_bytes)
   unsigned arena_bytes;
   unsigned spin_limit;            // bound of one barrier wait, in polls
+  // optional timeline for measurements: [operation][block][4] wall-clock samples (100 MHz) taken by thread 0:
+  // operation entered, its inputs complete (wait over), body done, arrival announced; null = off
+  long long* trace;
+  int trace_ops;                  // capacity in operations
 };
 
 int expert_loop_smem_bytes();

@@ -53,6 +53,27 @@ __global__ __launch_bounds__(PK_THREADS) void expert_loop_kernel(const ExpertLoo
   cx.bar = &bar;
   cx.bx = cx.by = cx.bz = 0;
   cx.thread = (int)threadIdx.x;
+  long long* const trace = P.trace;
+  const int trace_ops = P.trace_ops;
+  int opi = 0;
+  // timeline: sample 0 at the start of an operation, 1 by the barrier when the wait ends, 2 after the body, 3 after arrive
+  auto op_begin = [&]() {
+    if (trace != nullptr && opi < trace_ops) {
+      long long* slot = trace + ((size_t)opi * gridDim.x + blockIdx.x) * 4;
+      bar.trace = slot + 1;
+      if (threadIdx.x == 0) { slot[0] = (long long)wall_clock64(); slot[1] = 0; }
+    } else {
+      bar.trace = nullptr;
+    }
+  };
+  auto op_end = [&]() {
+    long long* slot = trace != nullptr && opi < trace_ops ? trace + ((size_t)opi * gridDim.x + blockIdx.x) * 4 : nullptr;
+    if (slot != nullptr && threadIdx.x == 0) slot[2] = (long long)wall_clock64();
+    bar.trace = nullptr;
+    bar.arrive();
+    if (slot != nullptr && threadIdx.x == 0) slot[3] = (long long)wall_clock64();
+    opi++;
+  };
   auto item = [&](int bx, int by, int bz) {
     PersistCtx c = cx;
     c.bx = bx; c.by = by; c.bz = bz;
@@ -62,16 +83,18 @@ __global__ __launch_bounds__(PK_THREADS) void expert_loop_kernel(const ExpertLoo
     return c;
   };
 
+  op_begin();
   // ---- C0: state token; x <- noise ---------------------------------------------------------------
   for_items((P.stok.X + 255) / 256, [&](int it) { state_token_body(P.stok, item(it, 0, 0)); });
   if ((int)blockIdx.x == (int)gridDim.x - 1) {
     for (int i = threadIdx.x; i < P.x_elems; i += PK_THREADS) cx.st(P.emb.x_rw + i, P.noise[i]);
   }
-  bar.arrive();
+  op_end();
 
   const int emb_cols = (P.emb.a.X + 255) / 256;
   const int steps = P.steps, layers = P.layers;
   for (int k = 0; k < steps; k++) {
+    op_begin();
     {  // ---- C1: folded action/time embedding + SiLU; suffix row 0 <- state token ----------------
       ActionEmbedArgs a = fresh(Pg).emb.a;
       a.bias_k += (size_t)k * a.X;
@@ -80,67 +103,110 @@ __global__ __launch_bounds__(PK_THREADS) void expert_loop_kernel(const ExpertLoo
         if (!waited) { bar.wait(); waited = true; }
         action_embed_body(a, item(it % emb_cols, it / emb_cols, 0));
       });
-      bar.arrive();
+      op_end();
     }
+    op_begin();
     // ---- C2: second linear of the action/time MLP -> suffix rows 1 .. chunk --------------------------
     {
       const GemmParams t = fresh(Pg).tout;
       for_items(t.n_tiles, [&](int it) { gemm_skinny_body<PRO_NONE, EPI_RESID, 0>(t, item(it, 0, 0), smem_raw); });
     }
-    bar.arrive();
+    op_end();
     for (int l = 0; l < layers; l++) {
+      op_begin();
       {  // ---- C3: RMS -> QKV, RoPE at positions P .. P + 63 -------------------------------------
         const ExpertLoopParams& F = fresh(Pg);
         GemmParams q = F.qkv;
         q.W.w += (size_t)l * F.w_stride;
-        q.rowstat_parts = l == 0 ? F.parts_first : F.parts_rest;
-        for_items(q.n_tiles * 2, [&](int it) { gemm_skinny_body<PRO_RMS, EPI_QKV, 1>(q, item(it % q.n_tiles, 0, it / q.n_tiles), smem_raw); });
-        bar.arrive();
+        char* slot = F.ring + (size_t)(k * layers + l) * F.ring_stride;
+        q.out_bf16 = reinterpret_cast<bf16*>(slot + F.r_q);
+        q.kfrag = reinterpret_cast<bf16*>(slot + F.r_k);
+        q.vfrag = reinterpret_cast<bf16*>(slot + F.r_v);
+        if (l == 0) {   // input: the step's embedding (two operations wrote its rows)
+          q.rowstat_parts = F.parts_first;
+          for_items(q.n_tiles * 2, [&](int it) { gemm_skinny_body<PRO_RMS, EPI_QKV, 1>(q, item(it % q.n_tiles, 0, it / q.n_tiles), smem_raw); });
+        } else {
+          q.rowstat_parts = F.parts_rest;
+          q.X = reinterpret_cast<const bf16*>(slot - F.ring_stride + F.r_yb_d);
+          q.rowstat = reinterpret_cast<const float*>(slot - F.ring_stride + F.r_st_d);
+          for_items(q.n_tiles * 2, [&](int it) {
+            gemm_skinny_body<PRO_RMS, EPI_QKV, 1>(q, item(it % q.n_tiles, 0, it / q.n_tiles).template as<true>(), smem_raw);
+          });
+        }
+        op_end();
       }
+      op_begin();
       {  // ---- C4 + C5: scores, block mask, softmax, PV over [cache ; own keys] ---------------------
         const ExpertLoopParams& F = fresh(Pg);
         AttnParams a = F.att;
         a.k0 += (size_t)l * F.kcache_stride;
         a.v0 += (size_t)l * F.vcache_stride;
+        char* slot = F.ring + (size_t)(k * layers + l) * F.ring_stride;
+        a.q = reinterpret_cast<const bf16*>(slot + F.r_q);
+        a.k1 = reinterpret_cast<const bf16*>(slot + F.r_k);
+        a.v1 = reinterpret_cast<const bf16*>(slot + F.r_v);
+        a.out = reinterpret_cast<bf16*>(slot + F.r_attn);
+        if (a.ml_out != nullptr) a.ml_out = reinterpret_cast<float*>(slot + F.r_ml);
         const int att_gx = F.att_gx, att_gxy = F.att_gx * a.heads;
         for_items(F.att_items, [&](int it) {
-          attention_body<256, 8, 1, 8>(a, item(it % att_gx, (it % att_gxy) / att_gx, it / att_gxy), smem_raw);
+          attention_body<256, 8, 1, 8>(a, item(it % att_gx, (it % att_gxy) / att_gx, it / att_gxy).template as<true>(), smem_raw);
         });
-        bar.arrive();
+        op_end();
       }
+      op_begin();
       {  // ---- C6: O projection + residual ------------------------------------------------------
         const ExpertLoopParams& F = fresh(Pg);
         GemmParams o = F.o;
         o.W.w += (size_t)l * F.w_stride;
         o.gain = F.g_mlp0 + (size_t)l * F.gain_stride;
+        char* slot = F.ring + (size_t)(k * layers + l) * F.ring_stride;
+        o.X = reinterpret_cast<const bf16*>(slot + F.r_attn);
+        if (o.xsplits > 1) o.xsplit_ml = reinterpret_cast<const float*>(slot + F.r_ml);
+        o.out_bf16 = reinterpret_cast<bf16*>(slot + F.r_yb_o);
+        o.stat_out = reinterpret_cast<float*>(slot + F.r_st_o);
         const int nx = o.n_tiles * 2;
-        for_items(nx * F.m16, [&](int it) { gemm_skinny16_body<8>(o, item(it % nx, it / nx, 0), smem_raw); });
-        bar.arrive();
+        for_items(nx * F.m16, [&](int it) { gemm_skinny16_body<8>(o, item(it % nx, it / nx, 0).template as<true>(), smem_raw); });
+        op_end();
       }
+      op_begin();
       {  // ---- C7: RMS -> gate||up, fused gate -----------------------------------------------------
         const ExpertLoopParams& F = fresh(Pg);
         GemmParams g = F.gu;
         g.W.w += (size_t)l * F.w_stride;
-        for_items(g.n_tiles, [&](int it) { gemm_skinny_body<PRO_RMS, EPI_GEGLU, 0>(g, item(it, 0, 0), smem_raw); });
-        bar.arrive();
+        char* slot = F.ring + (size_t)(k * layers + l) * F.ring_stride;
+        g.X = reinterpret_cast<const bf16*>(slot + F.r_yb_o);
+        g.rowstat = reinterpret_cast<const float*>(slot + F.r_st_o);
+        g.out_bf16 = reinterpret_cast<bf16*>(slot + F.r_mid);
+        for_items(g.n_tiles, [&](int it) { gemm_skinny_body<PRO_RMS, EPI_GEGLU, 0>(g, item(it, 0, 0).template as<true>(), smem_raw); });
+        op_end();
       }
+      op_begin();
       {  // ---- C8: down + residual -----------------------------------------------------------------
         const ExpertLoopParams& F = fresh(Pg);
         GemmParams d = F.dn;
         d.W.w += (size_t)l * F.w_stride;
         d.gain = l + 1 < F.layers ? F.g_attn0 + (size_t)(l + 1) * F.gain_stride : F.g_final;
+        char* slot = F.ring + (size_t)(k * layers + l) * F.ring_stride;
+        d.X = reinterpret_cast<const bf16*>(slot + F.r_mid);
+        d.out_bf16 = reinterpret_cast<bf16*>(slot + F.r_yb_d);
+        d.stat_out = reinterpret_cast<float*>(slot + F.r_st_d);
         const int nx = d.n_tiles * 2;
-        if (F.dn_ns == 16) for_items(nx * F.m16, [&](int it) { gemm_skinny16_body<16>(d, item(it % nx, it / nx, 0), smem_raw); });
-        else for_items(nx * F.m16, [&](int it) { gemm_skinny16_body<8>(d, item(it % nx, it / nx, 0), smem_raw); });
-        bar.arrive();
+        if (F.dn_ns == 16) for_items(nx * F.m16, [&](int it) { gemm_skinny16_body<16>(d, item(it % nx, it / nx, 0).template as<true>(), smem_raw); });
+        else for_items(nx * F.m16, [&](int it) { gemm_skinny16_body<8>(d, item(it % nx, it / nx, 0).template as<true>(), smem_raw); });
+        op_end();
       }
     }
+    op_begin();
     // ---- C9: final RMS -> out-projection (+bias), Euler update x <- x + dt * v ----------------------
     {
-      const GemmParams u = fresh(Pg).outp;
-      for_items(u.n_tiles, [&](int it) { gemm_skinny_body<PRO_RMS, EPI_EULER, 0>(u, item(it, 0, 0), smem_raw); });
+      const ExpertLoopParams& F = fresh(Pg);
+      GemmParams u = F.outp;
+      char* slot = F.ring + (size_t)(k * layers + layers - 1) * F.ring_stride;
+      u.X = reinterpret_cast<const bf16*>(slot + F.r_yb_d);
+      u.rowstat = reinterpret_cast<const float*>(slot + F.r_st_d);
+      for_items(u.n_tiles, [&](int it) { gemm_skinny_body<PRO_RMS, EPI_EULER, 0>(u, item(it, 0, 0).template as<true>(), smem_raw); });
     }
-    bar.arrive();
+    op_end();
   }
 }
 
@@ -217,6 +283,8 @@ hipError_t launch_expert_loop(hipStream_t s, const ExpertLoopParams& P, ExpertLo
   if (P.emb.a.X % 32 != 0 || P.emb.a.gain == nullptr || P.emb.a.stat_parts == nullptr || P.emb.a.x != P.emb.x_rw) return hipErrorInvalidValue;
   if (!in_arena(P.emb.x_rw, (size_t)P.x_elems * 4) || !in_arena(P.stok.out, (size_t)P.stok.X * 4)) return hipErrorInvalidValue;
   if (P.stok.sd < 1 || P.stok.sd > 32) return hipErrorInvalidValue;
+  if (P.ring == nullptr || P.ring_stride % 256 != 0 || !in_arena(P.ring, P.ring_stride * (size_t)P.layers * P.steps)) return hipErrorInvalidValue;
+  if (P.r_mid >= P.ring_stride || P.r_attn >= P.ring_stride) return hipErrorInvalidValue;
   hipLaunchKernelGGL(expert_loop_params_kernel, dim3(1), dim3(64), 0, s, P, d_params);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

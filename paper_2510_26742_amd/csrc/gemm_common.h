@@ -173,13 +173,15 @@ __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16&
           cx.st(reinterpret_cast<uint2*>(p.out_bf16 + xf_index(m, col, p.ldo >> 4)), o2);
         }
       } else if (EPI == EPI_EULER) {
-        if (m >= 1) {
+        if (m >= 1 && n4 < p.n_valid) {
+          // the four x values of this lane: all read before any is written (one round trip instead of four)
+          float* xp = p.out_f32 + (size_t)(m - 1) * p.ldo + n4;
+          float xv[4];
+#pragma unroll
+          for (int j = 0; j < 4; j++) xv[j] = n4 + j < p.n_valid ? cx.ld(xp + j) : 0.f;
 #pragma unroll
           for (int j = 0; j < 4; j++) {
-            if (n4 + j < p.n_valid) {
-              float* xp = p.out_f32 + (size_t)(m - 1) * p.ldo + n4 + j;
-              cx.st(xp, cx.ld(xp) + p.dt * v[j]);
-            }
+            if (n4 + j < p.n_valid) cx.st(xp + j, xv[j] + p.dt * v[j]);
           }
         }
       } else if (EPI == EPI_QKV) {
@@ -350,7 +352,7 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmParams& p, const Cx& 
 #pragma unroll
     for (int jj = 0; jj < 8; jj++) {
       const int j = min(w + SK_WAVES * jj, p.rowstat_parts - 1);
-      sp[jj] = cx.ld(reinterpret_cast<const float2*>(p.rowstat + ((size_t)j * 64 + lane) * 2));
+      sp[jj] = cx.ld_bulk(reinterpret_cast<const float2*>(p.rowstat + ((size_t)j * 64 + lane) * 2));
     }
   }
 #pragma unroll
@@ -359,7 +361,7 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmParams& p, const Cx& 
     if (!Cx::kPersistent) wf[i] = *reinterpret_cast<const bf16x8*>(wbase + (size_t)st * 512);
 #pragma unroll
     for (int mb = 0; mb < NMB; mb++)
-      xf[mb][i] = cx.ld(reinterpret_cast<const bf16x8*>(xbase + ((size_t)min(mb_first + mb, mb_last) * XKC16 + st) * 512));
+      xf[mb][i] = cx.ld_bulk(reinterpret_cast<const bf16x8*>(xbase + ((size_t)min(mb_first + mb, mb_last) * XKC16 + st) * 512));
   }
   // operands of the epilogue, in the same round trip
   if (Cx::kPersistent) preload(std::integral_constant<int, 1>{});
@@ -477,7 +479,7 @@ __device__ __forceinline__ void gemm_skinny16_body(const GemmParams& p, const Cx
 #pragma unroll
   for (int j = 0; j < NS; j++) {
     if (!Cx::kPersistent) wf[j] = *reinterpret_cast<const bf16x8*>(wbase + (size_t)j * 1024);
-    xf[j] = cx.ld(reinterpret_cast<const bf16x8*>(xbase + (size_t)j * 1024));
+    xf[j] = cx.ld_bulk(reinterpret_cast<const bf16x8*>(xbase + (size_t)j * 1024));
   }
   // X given as attention shares over disjoint key ranges (k = 8 heads x 256, so wave w holds exactly
   // head w).  Share z carries its normalised output and (max, sum) of its exponentials; the merged
@@ -492,13 +494,13 @@ __device__ __forceinline__ void gemm_skinny16_body(const GemmParams& p, const Cx
     bf16x8 xo[3][NS];
     float2 ml[4];
     const int mrow = min(m, 63);
-    ml[0] = cx.ld(reinterpret_cast<const float2*>(p.xsplit_ml + ((size_t)w * 64 + mrow) * 2));
+    ml[0] = cx.ld_bulk(reinterpret_cast<const float2*>(p.xsplit_ml + ((size_t)w * 64 + mrow) * 2));
 #pragma unroll
     for (int z = 1; z < 4; z++) {
       if (z < nz) {
 #pragma unroll
-        for (int j = 0; j < NS; j++) xo[z - 1][j] = cx.ld(reinterpret_cast<const bf16x8*>(xbase + (size_t)z * p.xsplit_stride + (size_t)j * 1024));
-        ml[z] = cx.ld(reinterpret_cast<const float2*>(p.xsplit_ml + (((size_t)z * SK_WAVES + w) * 64 + mrow) * 2));
+        for (int j = 0; j < NS; j++) xo[z - 1][j] = cx.ld_bulk(reinterpret_cast<const bf16x8*>(xbase + (size_t)z * p.xsplit_stride + (size_t)j * 1024));
+        ml[z] = cx.ld_bulk(reinterpret_cast<const float2*>(p.xsplit_ml + (((size_t)z * SK_WAVES + w) * 64 + mrow) * 2));
       }
     }
     float mx = ml[0].x;

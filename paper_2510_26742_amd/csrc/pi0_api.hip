@@ -154,6 +154,8 @@ struct WsLayout {
   size_t stok, z, y, y_b, eq, ek, ev, eattn, eml, emid;
   size_t vstat, lstat, estat, estat_parts, pf_sink, vstat_parts, lstat_parts, progress;
   size_t esync, eparams;             // persistent denoise kernel: barrier words, parameter block
+  size_t ering, ering_slot;          // ... its ring of per-layer-step activation buffers, bytes per slot
+  unsigned r_yb_o, r_st_o, r_yb_d, r_st_d, r_q, r_k, r_v, r_attn, r_ml, r_mid;   // byte offsets inside a slot
   size_t lx8, lx8s, lmid8, lmid8s;   // MXFP8 copies of the prefix feed-forward inputs
   bool mx_ok = false;                // the prefix feed-forward shapes fit the MXFP8 kernels (multiples of 256)
   size_t total;
@@ -300,6 +302,21 @@ void ws_layout(const pi0_config& c, const Dims& d, WsLayout& w) {
   w.progress = cur.take(256);
   w.esync = cur.take((size_t)GB_WORDS * 4);
   w.eparams = cur.take(sizeof(ExpertLoopParams));
+  {  // one slot per (Euler step, expert layer): the same buffers as stok .. emid above, each 256-byte aligned
+    WsCursor sl;
+    w.r_yb_o = (unsigned)sl.take((size_t)64 * d.X * 2);
+    w.r_st_o = (unsigned)sl.take((size_t)(d.X / 16) * 64 * 2 * 4);
+    w.r_yb_d = (unsigned)sl.take((size_t)64 * d.X * 2);
+    w.r_st_d = (unsigned)sl.take((size_t)(d.X / 16) * 64 * 2 * 4);
+    w.r_q = (unsigned)sl.take((size_t)d.H * 2 * 16 * 512 * 2);
+    w.r_k = (unsigned)sl.take((size_t)2 * 16 * 512 * 2);
+    w.r_v = (unsigned)sl.take((size_t)2 * 8 * 1024 * 2);
+    w.r_attn = (unsigned)sl.take((size_t)4 * 64 * d.H * 256 * 2);
+    w.r_ml = (unsigned)sl.take((size_t)4 * d.H * 64 * 2 * 4);
+    w.r_mid = (unsigned)sl.take((size_t)64 * d.Fx * 2);
+    w.ering_slot = sl.off;
+    w.ering = cur.take(w.ering_slot * (size_t)d.steps * d.Le);
+  }
   {
     const int kmax = d.H * 256 > d.Fx ? d.H * 256 : d.Fx;
     w.epart = cur.take((size_t)ceil_div(round_up(kmax, 64), 1024) * 64 * round_up(d.X, 32) * 4);
@@ -366,6 +383,8 @@ struct pi0_ctx {
   unsigned char* ws = nullptr;
   bool loaded = false;
   bool attrs_set = false;
+  long long* loop_trace = nullptr;     // optional timeline buffer of the persistent denoise kernel (pi0_set_loop_trace)
+  int loop_trace_ops = 0;
   bool pk_ok = false;                  // the device can hold the persistent denoise kernel's 256 blocks at once
   bool graph_mode = true;
   int precision = PI0_PRECISION_BF16;   // PI0_PRECISION_MXFP8_PREFIX_MLP: prefix gate||up / down on MXFP8 operands
@@ -881,10 +900,16 @@ bool run_denoise_persistent(Run& r, int P) {
     p.ldo = d.A; p.n_valid = d.A; p.dt = -1.0f / (float)d.steps;
     E.outp = p;
   }
+  E.ring = reinterpret_cast<char*>(c->ws + w.ering);
+  E.ring_stride = w.ering_slot;
+  E.r_yb_o = w.r_yb_o; E.r_st_o = w.r_st_o; E.r_yb_d = w.r_yb_d; E.r_st_d = w.r_st_d;
+  E.r_q = w.r_q; E.r_k = w.r_k; E.r_v = w.r_v; E.r_attn = w.r_attn; E.r_ml = w.r_ml; E.r_mid = w.r_mid;
   E.sync = at<unsigned>(c, w.esync);
   E.arena = reinterpret_cast<const char*>(c->ws + w.act_begin);
   E.arena_bytes = (unsigned)arena_bytes;
   E.spin_limit = 1u << 20;
+  E.trace = c->loop_trace;
+  E.trace_ops = c->loop_trace_ops;
   r.cls = PI0_OP_MISC;
   // barrier words restart at zero (the error word, first, stays as it is)
   RUN(r, launch_fill_zero(r.s, at<unsigned>(c, w.esync) + GB_START, (size_t)(GB_WORDS - GB_START) * 4));
@@ -1336,6 +1361,17 @@ int pi0_tune(pi0_ctx* c, const char* env) {
     for (int* v : {&c->tune.pfq, &c->tune.pfa, &c->tune.pfo, &c->tune.pfd}) *v &= ~15;
     if (c->tune.rad == 7) c->tune.rad = 6;   // the read-ahead kernel exists with 1 .. 6 and 8 loads in flight
   }
+  for (auto& kv : c->graphs) (void)hipGraphExecDestroy(kv.second);
+  c->graphs.clear();
+  return PI0_OK;
+}
+
+int pi0_loop_trace_ops(const pi0_ctx* c) { return c ? 1 + c->d.steps * (3 + 5 * c->d.Le) : 0; }
+
+int pi0_set_loop_trace(pi0_ctx* c, long long* d_trace, int ops_cap) {
+  if (c == nullptr || ops_cap < 0 || (d_trace == nullptr) != (ops_cap == 0) || (reinterpret_cast<uintptr_t>(d_trace) & 7) != 0) return PI0_EINVAL;
+  c->loop_trace = d_trace;
+  c->loop_trace_ops = ops_cap;
   for (auto& kv : c->graphs) (void)hipGraphExecDestroy(kv.second);
   c->graphs.clear();
   return PI0_OK;
