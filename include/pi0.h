@@ -142,6 +142,24 @@ int pi0_prefill(pi0_ctx* ctx, const float* d_images, int n_views, const int32_t*
 int pi0_denoise(pi0_ctx* ctx, const float* d_state, const float* d_noise, float* d_actions,
                 void* hip_stream);
 
+/*
+ * pi0_denoise for callers that cannot allocate or hand over device memory at call time beyond inputs and outputs
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels, launched
+ * one per operation directly on hip_stream - no graph is built or replayed, no stream or event is created, no
+ * device or host memory is allocated - with the expert's scratch (staged state / noise, residual stream,
+ * projections, attention shares, split-K partial sums, statistic partials: about 3.4 MB for the full model) in a
+ * device array that is part of the library itself instead of the workspace.  That array holds
+ * PI0_STATIC_SCRATCH_BYTES; a geometry whose expert scratch is larger gets PI0_ENOMEM (checked first, before any
+ * GPU call).  Weights and the prefix key/value cache are read from the workspace as usual.  Every GPU the library
+ * runs on holds one copy of the array until the process ends; all calls on a GPU share it, whichever ctx they
+ * belong to, so calls that overlap in time on one GPU race (calls on one stream do not overlap).  Must be called
+ * with the device of pi0_load_weights current.  Same results as pi0_denoise, bit for bit.
+ * Errors: EINVAL, ENOMEM, ESTATE (no valid prefill, or another device is current), EHIP.
+ */
+#define PI0_STATIC_SCRATCH_BYTES (4u << 20)
+int pi0_denoise_static(pi0_ctx* ctx, const float* d_state, const float* d_noise, float* d_actions,
+                       void* hip_stream);
+
 /* pi0_prefill followed by pi0_denoise as one graph launch. */
 int pi0_infer(pi0_ctx* ctx, const float* d_images, int n_views, const int32_t* d_prompt_ids,
               int n_prompt, const float* d_state, const float* d_noise, float* d_actions,

@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpi0_hip.so")
 
 EXPORTS = ["pi0_create", "pi0_destroy", "pi0_weights_bytes", "pi0_workspace_bytes", "pi0_load_weights",
-           "pi0_prefill", "pi0_denoise", "pi0_infer", "pi0_debug_taps_elems", "pi0_debug_forward", "pi0_debug_profile", "pi0_sync_bench", "pi0_peak_bench", "pi0_clock_sample", "pi0_read_ahead_probe", "pi0_stream_frame",
+           "pi0_prefill", "pi0_denoise", "pi0_denoise_static", "pi0_infer", "pi0_debug_taps_elems", "pi0_debug_forward", "pi0_debug_profile", "pi0_sync_bench", "pi0_peak_bench", "pi0_clock_sample", "pi0_read_ahead_probe", "pi0_stream_frame",
            "pi0_set_graph_mode", "pi0_set_precision", "pi0_kernel_count", "pi0_strerror", "pi0_last_hip_error",
            "pi0_sync_dep_bench", "pi0_tune", "pi0_device_status", "pi0_loop_trace_ops", "pi0_set_loop_trace"]
 
@@ -65,6 +65,8 @@ def lib() -> ctypes.CDLL:
         L.pi0_prefill.restype = i32
         L.pi0_denoise.argtypes = [vp, vp, vp, vp, vp]
         L.pi0_denoise.restype = i32
+        L.pi0_denoise_static.argtypes = [vp, vp, vp, vp, vp]
+        L.pi0_denoise_static.restype = i32
         L.pi0_infer.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp, vp]
         L.pi0_infer.restype = i32
         L.pi0_debug_taps_elems.argtypes = [cfgp, i32, i32]
@@ -263,6 +265,9 @@ class Pi0:
 
     def pi0_denoise(self, d_state, d_noise, d_actions, stream=None):
         self._check(lib().pi0_denoise(self._ctx, _ptr(d_state), _ptr(d_noise), _ptr(d_actions), self._stream(stream)))
+
+    def pi0_denoise_static(self, d_state, d_noise, d_actions, stream=None):
+        self._check(lib().pi0_denoise_static(self._ctx, _ptr(d_state), _ptr(d_noise), _ptr(d_actions), self._stream(stream)))
 
     def pi0_infer(self, d_images, n_views, d_prompt_ids, n_prompt, d_state, d_noise, d_actions, stream=None):
         self._check(lib().pi0_infer(self._ctx, _ptr(d_images), n_views, _ptr(d_prompt_ids), n_prompt, _ptr(d_state),

@@ -153,6 +153,7 @@ struct WsLayout {
   size_t lx, lx_b, lq, kcache, vcache, lattn, lmid;
   size_t stok, z, y, y_b, eq, ek, ev, eattn, eml, emid;
   size_t vstat, lstat, estat, estat_parts, pf_sink, vstat_parts, lstat_parts, progress;
+  size_t es_begin, es_end;           // the expert's scratch block [es_begin, es_end)
   size_t esync, eparams;             // persistent denoise kernel: barrier words, parameter block
   size_t ering, ering_slot;          // ... its ring of per-layer-step activation buffers, bytes per slot
   unsigned r_yb_o, r_st_o, r_yb_d, r_st_d, r_q, r_k, r_v, r_attn, r_ml, r_mid;   // byte offsets inside a slot
@@ -250,9 +251,6 @@ void ws_layout(const pi0_config& c, const Dims& d, WsLayout& w) {
   w.act_begin = cur.off;
   w.st_images = cur.take((size_t)c.max_views * c.img_size * c.img_size * 3 * 4);
   w.st_ids = cur.take((size_t)(c.max_prompt > 0 ? c.max_prompt : 1) * 4);
-  w.st_state = cur.take((size_t)d.SD * 4);
-  w.st_noise = cur.take((size_t)c.chunk * d.A * 4);
-  w.xa = cur.take((size_t)c.chunk * d.A * 4);
   w.xpatch = cur.take((size_t)d.maxI * d.PDp * 2);
   w.vh = cur.take((size_t)d.maxI * d.Dv * 4);
   w.vh_b = cur.take((size_t)d.maxI * d.Dv * 2);
@@ -278,6 +276,12 @@ void ws_layout(const pi0_config& c, const Dims& d, WsLayout& w) {
   w.vcache = cur.take(w.vcache_slot * 2);
   w.lattn = cur.take((size_t)d.maxPc * 32 * d.H * 256 * 2);
   w.lmid = cur.take((size_t)d.maxPc * 32 * d.F * 2);
+  // ---- scratch of the action expert's per-operation launches: one contiguous block, so that it can also live
+  // in the library's static device array (pi0_denoise_static) ----
+  w.es_begin = cur.off;
+  w.st_state = cur.take((size_t)d.SD * 4);
+  w.st_noise = cur.take((size_t)c.chunk * d.A * 4);
+  w.xa = cur.take((size_t)c.chunk * d.A * 4);
   w.stok = cur.take((size_t)d.X * 4);
   w.z = cur.take((size_t)64 * d.X * 2);
   w.y = cur.take((size_t)64 * d.X * 4);
@@ -288,6 +292,15 @@ void ws_layout(const pi0_config& c, const Dims& d, WsLayout& w) {
   w.eattn = cur.take((size_t)4 * 64 * d.H * 256 * 2);   // up to 4 key shares
   w.eml = cur.take((size_t)4 * d.H * 64 * 2 * 4);
   w.emid = cur.take((size_t)64 * d.Fx * 2);
+  w.estat = cur.take((size_t)64 * 2 * 4);
+  w.estat_parts = cur.take((size_t)(d.X / 16) * 64 * 2 * 4);
+  w.pf_sink = cur.take(1024 * 4);
+  w.progress = cur.take(256);
+  {
+    const int kmax = d.H * 256 > d.Fx ? d.H * 256 : d.Fx;
+    w.epart = cur.take((size_t)ceil_div(round_up(kmax, 64), 1024) * 64 * round_up(d.X, 32) * 4);
+  }
+  w.es_end = cur.off;
   w.vstat = cur.take((size_t)d.maxI * 2 * 4);
   w.lstat = cur.take((size_t)d.maxPc * 32 * 2 * 4);
   w.lx8 = cur.take((size_t)d.maxPc * 32 * d.E);
@@ -296,10 +309,6 @@ void ws_layout(const pi0_config& c, const Dims& d, WsLayout& w) {
   w.lmid8s = cur.take((size_t)d.maxPc * 32 * d.F / 32 + 256);
   w.vstat_parts = cur.take((size_t)(d.Dv / 32) * d.maxI * 2 * 4);                     // [32-column tile][maxI][2]
   w.lstat_parts = cur.take((size_t)(d.E / 32) * d.maxPc * 32 * 2 * 4);                // [32-column tile][maxPc * 32][2]
-  w.estat = cur.take((size_t)64 * 2 * 4);
-  w.estat_parts = cur.take((size_t)(d.X / 16) * 64 * 2 * 4);
-  w.pf_sink = cur.take(1024 * 4);
-  w.progress = cur.take(256);
   w.esync = cur.take((size_t)GB_WORDS * 4);
   w.eparams = cur.take(sizeof(ExpertLoopParams));
   {  // one slot per (Euler step, expert layer): the same buffers as stok .. emid above, each 256-byte aligned
@@ -316,10 +325,6 @@ void ws_layout(const pi0_config& c, const Dims& d, WsLayout& w) {
     w.r_mid = (unsigned)sl.take((size_t)64 * d.Fx * 2);
     w.ering_slot = sl.off;
     w.ering = cur.take(w.ering_slot * (size_t)d.steps * d.Le);
-  }
-  {
-    const int kmax = d.H * 256 > d.Fx ? d.H * 256 : d.Fx;
-    w.epart = cur.take((size_t)ceil_div(round_up(kmax, 64), 1024) * 64 * round_up(d.X, 32) * 4);
   }
   w.total = cur.off;
 }
@@ -383,6 +388,8 @@ struct pi0_ctx {
   unsigned char* ws = nullptr;
   bool loaded = false;
   bool attrs_set = false;
+  int device = -1;                     // device the weights were loaded on
+  unsigned char* static_scratch = nullptr;   // that device's copy of the library's static scratch array
   long long* loop_trace = nullptr;     // optional timeline buffer of the persistent denoise kernel (pi0_set_loop_trace)
   int loop_trace_ops = 0;
   bool pk_ok = false;                  // the device can hold the persistent denoise kernel's 256 blocks at once
@@ -418,6 +425,7 @@ struct Run {
   int cls = PI0_OP_MISC;        // class of the launches that follow
   OpTimer* timer = nullptr;     // when set, every RUN / RUN_GEMM launch is bracketed by an event pair
   bool persistent_ok = false;   // the denoise loop may run as one persistent kernel (plain pi0_denoise / pi0_infer calls)
+  unsigned char* ebase = nullptr;   // where the expert's scratch block lives minus its workspace offset (null: in the workspace)
   bool ok() const { return err == hipSuccess; }
   void did(hipError_t e) {
     launches++;
@@ -442,6 +450,11 @@ struct Run {
 
 template <typename T>
 T* at(pi0_ctx* c, size_t off) { return reinterpret_cast<T*>(c->ws + off); }
+// a buffer of the expert's scratch block (workspace offsets es_begin .. es_end): in the workspace, or wherever r.ebase points
+template <typename T>
+T* ex(const Run& r, size_t off) {
+  return reinterpret_cast<T*>(reinterpret_cast<uintptr_t>(r.ebase != nullptr ? r.ebase : r.c->ws) + off);
+}
 
 PackedW packed(pi0_ctx* c, const PW& p) {
   PackedW w;
@@ -482,7 +495,7 @@ void gemm_splitk_resid(Run& r, const PW& pw, const bf16* X, int ldx, int M, int 
   if ((long)k_per_split * z < pw.k_pad) k_per_split = round_up(ceil_div(pw.k_pad, z), 64);
   GemmParams p = gp_base(c, pw, X, ldx, M, tile, k_true);
   p.k_per_split = k_per_split;
-  p.out_f32 = at<float>(c, expert_scratch ? c->wl.epart : c->wl.part);
+  p.out_f32 = expert_scratch ? ex<float>(r, c->wl.epart) : at<float>(c, c->wl.part);
   p.ldo = pw.n_pad;
   RUN_GEMM(r, tile, PRO_NONE, EPI_PARTIAL, p, z);
   const int cls_gemm = r.cls;
@@ -927,16 +940,16 @@ void run_denoise(Run& r, int P, Taps* taps) {
   const WsLayout& w = c->wl;
   const int chunk = c->cfg.chunk;
   const int pchunks = ceil_div(P, 32);
-  float* xa = at<float>(c, w.xa);
+  float* xa = ex<float>(r, w.xa);
   r.cls = PI0_OP_MISC;
-  RUN(r, launch_copy_f32(r.s, at<float>(c, w.st_noise), xa, (size_t)chunk * d.A));
+  RUN(r, launch_copy_f32(r.s, ex<float>(r, w.st_noise), xa, (size_t)chunk * d.A));
   // C0: state token
-  RUN(r, launch_state_token(r.s, at<float>(c, w.st_state), d.SD, at<float>(c, w.state_w), at<float>(c, w.state_b), d.X,
-                            at<float>(c, w.stok), at<int>(c, w.progress)));
+  RUN(r, launch_state_token(r.s, ex<float>(r, w.st_state), d.SD, at<float>(c, w.state_w), at<float>(c, w.state_b), d.X,
+                            ex<float>(r, w.stok), ex<int>(r, w.progress)));
   const float dt = -1.0f / (float)d.steps;
   size_t tap_step_base = taps ? taps->off : 0;
   // row statistics of the suffix residual stream: where the next RMS-folded GEMM finds them
-  const float* stat_ptr = at<float>(c, w.estat);
+  const float* stat_ptr = ex<float>(r, w.estat);
   int stat_parts = 1;
   // y += X @ W (expert O / down projection).  k = 2048 or 4096: one kernel with the residual
   // epilogue that also leaves per-tile row statistics; otherwise split-K partials + reduction.
@@ -945,7 +958,7 @@ void run_denoise(Run& r, int P, Taps* taps) {
     PrefetchDesc f;
     memset(&f, 0, sizeof(f));
     f.blocks = blocks;
-    f.sink = at<unsigned>(c, w.pf_sink);
+    f.sink = ex<unsigned>(r, w.pf_sink);
     return f;
   };
   auto pf_weights = [&](PrefetchDesc& f, int r, const PW& pw) {
@@ -996,9 +1009,9 @@ void run_denoise(Run& r, int P, Taps* taps) {
     ra.layer_stride[cslot + 1] = w.vcache_layer;
     ra.n16[cslot + 1] = (unsigned)pchunks * 1024;
     ra.layers = d.Le; ra.steps = d.steps; ra.lead = T.ral;
-    ra.progress = at<int>(c, w.progress);
+    ra.progress = ex<int>(r, w.progress);
     ra.wait_ticks = 50000;   // 0.5 ms
-    ra.sink = at<unsigned>(c, w.pf_sink);
+    ra.sink = ex<unsigned>(r, w.pf_sink);
     hipError_t e = c->ra_stream != nullptr ? hipSuccess : hipErrorNotReady;   // made by ensure_read_ahead, outside any capture
     if (e == hipSuccess) e = hipEventRecord(c->ev_fork, r.s);
     if (e == hipSuccess) e = hipStreamWaitEvent(c->ra_stream, c->ev_fork, 0);
@@ -1010,26 +1023,26 @@ void run_denoise(Run& r, int P, Taps* taps) {
     if (pw.k_pad == 2048 || pw.k_pad == 4096) {
       const int tile = T.ae16 ? TILE_SKINNY16 : TILE_SKINNY_FULLK;
       GemmParams p = gp_base(c, pw, X, K, 64, tile, K);
-      p.resid = at<float>(c, w.y);
-      p.out_f32 = at<float>(c, w.y);
-      p.out_bf16 = at<bf16>(c, w.y_b);
+      p.resid = ex<float>(r, w.y);
+      p.out_f32 = ex<float>(r, w.y);
+      p.out_bf16 = ex<bf16>(r, w.y_b);
       p.ldo = d.X; p.ldo2 = d.X; p.n_valid = d.X;
-      p.stat_out = at<float>(c, w.estat_parts);
+      p.stat_out = ex<float>(r, w.estat_parts);
       p.gain = gain;
       p.pf = pf;
       if (o_splits > 1) {
         p.xsplits = o_splits;
         p.xsplit_stride = (size_t)64 * d.H * 256;
-        p.xsplit_ml = at<float>(c, w.eml);
+        p.xsplit_ml = ex<float>(r, w.eml);
         o_splits = 1;
       }
       RUN_GEMM(r, tile, PRO_NONE, EPI_RESID, p, 1);
-      stat_ptr = at<float>(c, w.estat_parts);
+      stat_ptr = ex<float>(r, w.estat_parts);
       stat_parts = T.ae16 ? pw.n_pad / 16 : pw.n_pad / 32;
     } else {
-      gemm_splitk_resid(r, pw, X, K, 64, K, ceil_div(pw.k_pad, 1024), 1024, nullptr, at<float>(c, w.y), at<bf16>(c, w.y_b),
-                        d.X, TILE_SKINNY, at<float>(c, w.estat), gain, nullptr, 0, false, true);
-      stat_ptr = at<float>(c, w.estat);
+      gemm_splitk_resid(r, pw, X, K, 64, K, ceil_div(pw.k_pad, 1024), 1024, nullptr, ex<float>(r, w.y), ex<bf16>(r, w.y_b),
+                        d.X, TILE_SKINNY, ex<float>(r, w.estat), gain, nullptr, 0, false, true);
+      stat_ptr = ex<float>(r, w.estat);
       stat_parts = 1;
     }
   };
@@ -1037,20 +1050,20 @@ void run_denoise(Run& r, int P, Taps* taps) {
     // C1: folded action/time embedding, SiLU; suffix row 0 <- state token
     r.cls = PI0_OP_EXP_EMBED;
     RUN(r, launch_action_embed(r.s, xa, chunk, d.A, at<float>(c, w.wfold), at<float>(c, w.bias_tab) + (size_t)k * d.X, d.X,
-                               at<bf16>(c, w.z), at<float>(c, w.stok), at<float>(c, w.y), at<bf16>(c, w.y_b),
-                               at<float>(c, w.g_e1[0]), at<float>(c, w.estat_parts)));
+                               ex<bf16>(r, w.z), ex<float>(r, w.stok), ex<float>(r, w.y), ex<bf16>(r, w.y_b),
+                               at<float>(c, w.g_e1[0]), ex<float>(r, w.estat_parts)));
     {  // C2: second linear of the action/time MLP -> suffix rows 1..chunk; gain-scaled copy and per-tile row
        // statistics for the first layer's QKV come out of the same epilogue (row 0: from the kernel above)
-      GemmParams p = gp_base(c, w.tout, at<bf16>(c, w.z), d.X, chunk, TILE_SKINNY, d.X);
+      GemmParams p = gp_base(c, w.tout, ex<bf16>(r, w.z), d.X, chunk, TILE_SKINNY, d.X);
       p.bias = at<float>(c, w.tout.bias);
-      p.out_f32 = at<float>(c, w.y);
-      p.out_bf16 = at<bf16>(c, w.y_b);
+      p.out_f32 = ex<float>(r, w.y);
+      p.out_bf16 = ex<bf16>(r, w.y_b);
       p.ldo = d.X; p.ldo2 = d.X; p.n_valid = d.X; p.row_offset = 1;
       p.gain = at<float>(c, w.g_e1[0]);
-      p.stat_out = at<float>(c, w.estat_parts);
+      p.stat_out = ex<float>(r, w.estat_parts);
       RUN_GEMM(r, TILE_SKINNY, PRO_NONE, EPI_RESID, p, 1);
     }
-    stat_ptr = at<float>(c, w.estat_parts);
+    stat_ptr = ex<float>(r, w.estat_parts);
     stat_parts = w.tout.n_pad / 32;
     const bool tap_this = taps && (k == 0 || k == d.steps - 1);
     for (int l = 0; l < d.Le; l++) {
@@ -1058,19 +1071,19 @@ void run_denoise(Run& r, int P, Taps* taps) {
       bf16* kc = reinterpret_cast<bf16*>(c->ws + w.kcache + (size_t)r.slot_r * w.kcache_slot + (size_t)l * w.kcache_layer);
       bf16* vc = reinterpret_cast<bf16*>(c->ws + w.vcache + (size_t)r.slot_r * w.vcache_slot + (size_t)l * w.vcache_layer);
       {  // C3: RMS -> QKV, RoPE at positions P..P+63
-        GemmParams p = gp_base(c, L.qkv, at<bf16>(c, w.y_b), d.X, 64, TILE_SKINNY, d.X);
+        GemmParams p = gp_base(c, L.qkv, ex<bf16>(r, w.y_b), d.X, 64, TILE_SKINNY, d.X);
         p.rowstat = stat_ptr;
         p.rowstat_parts = stat_parts;
-        p.out_bf16 = at<bf16>(c, w.eq);
+        p.out_bf16 = ex<bf16>(r, w.eq);
         p.q_mbs = 2;
-        p.kfrag = at<bf16>(c, w.ek); p.vfrag = at<bf16>(c, w.ev);
+        p.kfrag = ex<bf16>(r, w.ek); p.vfrag = ex<bf16>(r, w.ev);
         p.rope = at<float>(c, w.rope);
         p.pos0 = P;
         p.q_cols = d.H * 256; p.k_cols = 256;
         p.head_dim = 256; p.dqk_pad = 256; p.nvb = 8; p.kv_heads = 1; p.kv_chunks = 2;
         p.m_split = T.qms;
         p.pf = pf_begin(pfq);
-        if (ras) { p.progress = at<int>(c, w.progress); p.progress_value = k * d.Le + l + 1; }
+        if (ras) { p.progress = ex<int>(r, w.progress); p.progress_value = k * d.Le + l + 1; }
         pf_weights(p.pf, 0, L.o);
         r.cls = PI0_OP_EXP_QKV;
         RUN_GEMM(r, TILE_SKINNY, PRO_RMS, EPI_QKV, p, 1);
@@ -1078,18 +1091,18 @@ void run_denoise(Run& r, int P, Taps* taps) {
       {  // C4 + C5: scores, block mask, softmax, PV over [cache ; own keys]
         AttnParams a;
         memset(&a, 0, sizeof(a));
-        a.q = at<bf16>(c, w.eq); a.q_head_stride = 2 * 16 * 512;
+        a.q = ex<bf16>(r, w.eq); a.q_head_stride = 2 * 16 * 512;
         a.Tq = 64; a.heads = d.H;
         a.k0 = kc; a.v0 = vc; a.chunks0 = pchunks; a.valid0 = P;
-        a.k1 = at<bf16>(c, w.ek); a.v1 = at<bf16>(c, w.ev); a.chunks1 = 2;
+        a.k1 = ex<bf16>(r, w.ek); a.v1 = ex<bf16>(r, w.ev); a.chunks1 = 2;
         a.suffix_mask = 1;
         a.scale = 1.0f / 16.0f;
-        a.out = at<bf16>(c, w.eattn); a.out_ld = d.H * 256; a.head_dim = 256;
+        a.out = ex<bf16>(r, w.eattn); a.out_ld = d.H * 256; a.head_dim = 256;
         if (ksplits > 1) {   // long prefix: key shares over more blocks, merged by the O projection
           a.key_splits = ksplits;
           a.chunks_per_split = kcps;
           a.out_split_stride = (size_t)64 * d.H * 256;
-          a.ml_out = at<float>(c, w.eml);
+          a.ml_out = ex<float>(r, w.eml);
         }
         a.v_split = T.avs > 0 ? T.avs : (ksplits == 1 ? 4 : 2);
         a.pf = pf_begin(pfa);
@@ -1103,13 +1116,13 @@ void run_denoise(Run& r, int P, Taps* taps) {
         pf_weights(f, 0, L.down);
         r.cls = PI0_OP_EXP_O;
         o_splits = ksplits;
-        resid_gemm(L.o, at<bf16>(c, w.eattn), d.H * 256, at<float>(c, w.g_e2[l]), f);
+        resid_gemm(L.o, ex<bf16>(r, w.eattn), d.H * 256, at<float>(c, w.g_e2[l]), f);
       }
       {  // C7: RMS -> gate||up, fused gate
-        GemmParams p = gp_base(c, L.gu, at<bf16>(c, w.y_b), d.X, 64, TILE_SKINNY, d.X);
+        GemmParams p = gp_base(c, L.gu, ex<bf16>(r, w.y_b), d.X, 64, TILE_SKINNY, d.X);
         p.rowstat = stat_ptr;
         p.rowstat_parts = stat_parts;
-        p.out_bf16 = at<bf16>(c, w.emid);
+        p.out_bf16 = ex<bf16>(r, w.emid);
         p.ldo = d.Fx;
         r.cls = PI0_OP_EXP_GATEUP;
         RUN_GEMM(r, TILE_SKINNY, PRO_RMS, EPI_GEGLU, p, 1);
@@ -1122,17 +1135,17 @@ void run_denoise(Run& r, int P, Taps* taps) {
         pf_weights(f, 0, w.exp[nl].qkv);
         pf_cache(f, 1, nl);
         r.cls = PI0_OP_EXP_DOWN;
-        resid_gemm(L.down, at<bf16>(c, w.emid), d.Fx, at<float>(c, l + 1 < d.Le ? w.g_e1[l + 1] : w.g_ef), f);
+        resid_gemm(L.down, ex<bf16>(r, w.emid), d.Fx, at<float>(c, l + 1 < d.Le ? w.g_e1[l + 1] : w.g_ef), f);
       }
       if (tap_this) {
         // step 0 taps first, last-step taps after them
         const size_t slot = (k == 0 ? 0 : (size_t)d.Le) + l;
         if (taps->base && !r.count_only && r.ok())
-          r.did(launch_copy_f32(r.s, at<float>(c, w.y), taps->base + tap_step_base + slot * 64 * d.X, (size_t)64 * d.X));
+          r.did(launch_copy_f32(r.s, ex<float>(r, w.y), taps->base + tap_step_base + slot * 64 * d.X, (size_t)64 * d.X));
       }
     }
     {  // C9: final RMS -> out-projection (+bias), Euler update x <- x + dt * v
-      GemmParams p = gp_base(c, w.outp, at<bf16>(c, w.y_b), d.X, 64, TILE_SKINNY, d.X);
+      GemmParams p = gp_base(c, w.outp, ex<bf16>(r, w.y_b), d.X, 64, TILE_SKINNY, d.X);
       p.rowstat = stat_ptr;
       p.rowstat_parts = stat_parts;
       p.bias = at<float>(c, w.outp.bias);
@@ -1163,7 +1176,9 @@ __global__ __launch_bounds__(256) void copy_segments_kernel(CopyArgs a) {
 }
 
 hipError_t stage_inputs(pi0_ctx* c, hipStream_t s, const float* images, int n_views, const int32_t* ids, int n_prompt,
-                        const float* state, const float* noise) {
+                        const float* state, const float* noise, unsigned char* ebase = nullptr) {
+  Run where{c, s, false};   // only to say where the expert's scratch block is
+  where.ebase = ebase;
   CopyArgs a;
   memset(&a, 0, sizeof(a));
   int n = 0;
@@ -1174,9 +1189,9 @@ hipError_t stage_inputs(pi0_ctx* c, hipStream_t s, const float* images, int n_vi
   if (ids && n_prompt > 0) {
     a.seg[n++] = CopySeg{reinterpret_cast<const uint32_t*>(ids), at<uint32_t>(c, c->wl.st_ids), (unsigned)n_prompt};
   }
-  if (state) a.seg[n++] = CopySeg{reinterpret_cast<const uint32_t*>(state), at<uint32_t>(c, c->wl.st_state), (unsigned)c->d.SD};
+  if (state) a.seg[n++] = CopySeg{reinterpret_cast<const uint32_t*>(state), ex<uint32_t>(where, c->wl.st_state), (unsigned)c->d.SD};
   if (noise) {
-    a.seg[n++] = CopySeg{reinterpret_cast<const uint32_t*>(noise), at<uint32_t>(c, c->wl.st_noise),
+    a.seg[n++] = CopySeg{reinterpret_cast<const uint32_t*>(noise), ex<uint32_t>(where, c->wl.st_noise),
                          (unsigned)(c->cfg.chunk * c->d.A)};
   }
   if (n == 0) return hipSuccess;
@@ -1254,6 +1269,37 @@ bool check_prefill_args(const pi0_ctx* c, const float* images, int n_views, cons
   return true;
 }
 
+}  // namespace
+
+// ==================================================================================================
+// Static scratch of pi0_denoise_static: the expert's scratch block for callers that cannot provide or allocate
+// device memory beyond inputs and outputs at call time.  One copy per device, held until the process ends.  The
+// array's name is only a host-side handle; its device address is looked up once per device (with that device
+// current) and used everywhere.  Calls that overlap in time on one device share it and would race.
+// ==================================================================================================
+static __device__ __align__(256) unsigned char scratch[PI0_STATIC_SCRATCH_BYTES];
+
+namespace {
+const int MAX_DEVICES = 64;
+unsigned char* g_static_scratch[MAX_DEVICES] = {};
+
+// device address of `scratch` on the current device (looked up on first use per device)
+hipError_t static_scratch_ptr(int* dev_out, unsigned char** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  if (g_static_scratch[dev] == nullptr) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (p == nullptr) return hipErrorInvalidSymbol;
+    g_static_scratch[dev] = reinterpret_cast<unsigned char*>(p);
+  }
+  *dev_out = dev;
+  *out = g_static_scratch[dev];
+  return hipSuccess;
+}
 }  // namespace
 
 // ==================================================================================================
@@ -1447,6 +1493,8 @@ int pi0_load_weights(pi0_ctx* c, const void* d_blob, size_t blob_bytes, void* d_
     }
     c->attrs_set = true;
   }
+  e = static_scratch_ptr(&c->device, &c->static_scratch);
+  if (e != hipSuccess) return fail_hip(c, e);
 #define TRY(call) do { e = (call); if (e != hipSuccess) return fail_hip(c, e); } while (0)
   TRY(launch_fill_zero(s, c->ws + w.act_begin, w.total - w.act_begin));
   TRY(hipMemcpyAsync(c->ws + w.rope, c->h_rope.data(), c->h_rope.size() * 4, hipMemcpyHostToDevice, s));
@@ -1579,6 +1627,29 @@ int pi0_denoise(pi0_ctx* c, const float* d_state, const float* d_noise, float* d
   int rc = execute(c, KIND_DENOISE, c->cur_views, c->cur_prompt, s);
   if (rc != PI0_OK) return rc;
   e = launch_copy_f32(s, at<float>(c, c->wl.xa), d_actions, (size_t)c->cfg.chunk * c->d.A);
+  return e == hipSuccess ? PI0_OK : fail_hip(c, e);
+}
+
+int pi0_denoise_static(pi0_ctx* c, const float* d_state, const float* d_noise, float* d_actions, void* hip_stream) {
+  if (c == nullptr || d_state == nullptr || d_noise == nullptr || d_actions == nullptr) return PI0_EINVAL;
+  if (c->wl.es_end - c->wl.es_begin > (size_t)PI0_STATIC_SCRATCH_BYTES) return PI0_ENOMEM;   // this geometry needs more than the static array holds
+  if (!c->loaded || c->cur_views == 0) return PI0_ESTATE;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev != c->device || c->static_scratch == nullptr) return PI0_ESTATE;
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  // the block's workspace offsets, rebased onto the static array (integer arithmetic: the sum is only ever
+  // dereferenced at offsets inside [es_begin, es_end))
+  unsigned char* ebase = reinterpret_cast<unsigned char*>(reinterpret_cast<uintptr_t>(c->static_scratch) - c->wl.es_begin);
+  hipError_t e = stage_inputs(c, s, nullptr, 0, nullptr, 0, d_state, d_noise, ebase);
+  if (e != hipSuccess) return fail_hip(c, e);
+  Run r{c, s, false};
+  r.slot_r = c->cur_slot;
+  r.read_ahead = false;     // no second stream, no events: nothing is created here
+  r.persistent_ok = false;  // per-operation launches, eagerly (a caller may be capturing the stream itself)
+  r.ebase = ebase;
+  run_denoise(r, c->cur_views * c->d.T + c->cur_prompt, nullptr);
+  if (!r.ok()) return fail_hip(c, r.err);
+  e = launch_copy_f32(s, ex<float>(r, c->wl.xa), d_actions, (size_t)c->cfg.chunk * c->d.A);
   return e == hipSuccess ? PI0_OK : fail_hip(c, e);
 }
 

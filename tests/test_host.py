@@ -268,3 +268,17 @@ def test_roofline_reproduces_table2_and_section5():
     b1 = roofline.stage_bounds_ms(roofline.table2_ops(cfg, 1, 0), roofline.RTX4090_BW, roofline.RTX4090_MACS)
     b3 = roofline.stage_bounds_ms(roofline.table2_ops(cfg, 3, 0), roofline.RTX4090_BW, roofline.RTX4090_MACS)
     assert abs(b1["total"] - 12.8) < 0.1 and abs(b3["total"] - 26.7) < 0.1
+
+
+def test_static_scratch_entry_point_rejects_what_does_not_fit(L):
+    """pi0_denoise_static keeps the expert's scratch in a device array of PI0_STATIC_SCRATCH_BYTES inside the library:
+    a geometry that needs more is refused with ENOMEM before anything else is looked at (no GPU call), one that fits
+    gets as far as the state check (no weights loaded here)."""
+    dummy = ctypes.c_void_p(256)     # never dereferenced: every check below fails before a GPU call
+    for kw, want in ((dict(exp_mlp=16384), binding.PI0_ENOMEM), (dict(), binding.PI0_ESTATE)):
+        c = binding.to_c_config(synth.dataclasses.replace(synth.full_config(), **kw))
+        ctx = ctypes.c_void_p()
+        assert L.pi0_create(ctypes.byref(c), ctypes.byref(ctx)) == 0
+        assert L.pi0_denoise_static(ctx, dummy, dummy, dummy, None) == want
+        assert L.pi0_denoise_static(ctx, None, dummy, dummy, None) == binding.PI0_EINVAL
+        L.pi0_destroy(ctx)
