@@ -1,0 +1,77 @@
+"""How far bf16 GEMM inputs alone move the oracle (CPU only): the evidence behind the action bars of the GPU tests.
+
+The HIP path feeds its matrix units bf16 operands (the paper runs everything in bf16, Section 8; accumulation and
+statistics stay fp32).  Here the ORACLE is run with exactly that and nothing else changed: every matrix product
+rounds both operands to bf16 first (weights are bf16 values already, so only activations, attention probabilities
+and cached keys / values move).  The arithmetic is the oracle's own - the rounding is injected through an ndarray
+subclass whose `@` rounds its operands, so no line of the oracle is touched.
+
+  N(0, 0.02) weights (the benchmark's recipe)      -> a few 1e-3 of the action RMS: the 2e-2 bar of the task has a
+                                                      factor of several in hand
+  query / key projections 2.5 x wider (std 0.05)   -> 2e-2: the softmax is sharp (logit deviation about 5) and
+                                                      amplifies input rounding; the GPU stress test that uses this
+                                                      configuration (test_sharp_attention_masks) takes 5e-2, the
+                                                      same factor 2.5 above the rounding-only figure that the 2e-2
+                                                      bar has on the benchmark's weights
+  4 x wider (std 0.08)                             -> far beyond any such bar: sharper settings test the conditioning
+                                                      of the problem, not an implementation
+"""
+import numpy as np
+import pytest
+
+from oracle import pi0_oracle as O
+from paper_2510_26742_amd import synth
+
+
+def bf16_round(x):
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    u = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) & np.uint32(0xFFFF0000)
+    return u.view(np.float32)
+
+
+class Bf16Operands(np.ndarray):
+    """float32 array whose matrix products round both operands to bf16 (round to nearest even) first."""
+
+    def __matmul__(self, other):
+        return np.matmul(bf16_round(np.asarray(self)), bf16_round(np.asarray(other))).view(Bf16Operands)
+
+    def __rmatmul__(self, other):
+        return np.matmul(bf16_round(np.asarray(other)), bf16_round(np.asarray(self))).view(Bf16Operands)
+
+
+def forward(cfg, tensors, img, st, nz, ids, rounded, monkeypatch):
+    if not rounded:
+        return O.pi0_forward(cfg, tensors, img, st, nz, ids)
+    # attention() and softmax_masked() build their results in fresh plain arrays: hand them on as the subclass,
+    # so that the products they feed (P @ V, the O projection) round their inputs too
+    att, sm = O.attention, O.softmax_masked
+    monkeypatch.setattr(O, "attention", lambda *a: att(*a).view(Bf16Operands))
+    monkeypatch.setattr(O, "softmax_masked", lambda *a: sm(*a).view(Bf16Operands))
+    out = O.pi0_forward(cfg, tensors, img.view(Bf16Operands), st.view(Bf16Operands), nz.view(Bf16Operands), ids)
+    monkeypatch.undo()
+    return np.asarray(out)
+
+
+def test_rounding_helper_is_round_to_nearest_even():
+    x = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 2.0 ** -7, 1.0 + 3 * 2.0 ** -8, -3.1415927, 0.0], dtype=np.float32)
+    want = np.array([1.0, 1.0, 1.0 + 2.0 ** -7, 1.0 + 2.0 ** -6, -3.140625, 0.0], dtype=np.float32)
+    np.testing.assert_array_equal(bf16_round(x), want)
+    a = np.arange(12, dtype=np.float32).reshape(3, 4).view(Bf16Operands) * np.float32(1.001)
+    assert isinstance(a @ np.ones((4, 2), np.float32), Bf16Operands)
+    np.testing.assert_array_equal(np.asarray(a @ np.eye(4, dtype=np.float32)), bf16_round(np.asarray(a)))
+
+
+@pytest.mark.parametrize("std, lo, hi", [(None, 5e-4, 8e-3), (0.05, 8e-3, 5e-2 / 1.5), (0.08, 5e-2, 10.0)])
+def test_oracle_moves_this_much_under_bf16_operands(std, lo, hi, monkeypatch):
+    cfg = synth.reduced_config(vocab=1024)
+    overrides = {"wq": std, "wk": std} if std else None
+    blob = synth.make_weights(cfg, seed=5, overrides=overrides)       # the GPU stress test's seed and inputs
+    tensors = synth.blob_views(cfg, blob)
+    img, st, nz = synth.make_images(cfg, 2, seed=1), synth.make_state(cfg, seed=2), synth.make_noise(cfg, seed=3)
+    ids = synth.make_prompt(cfg, 7, seed=4)
+    plain = forward(cfg, tensors, img, st, nz, ids, False, monkeypatch)
+    rounded = forward(cfg, tensors, img, st, nz, ids, True, monkeypatch)
+    rms = float(np.sqrt((plain.astype(np.float64) ** 2).mean()))
+    delta = float(np.abs(rounded - plain).max()) / rms
+    print(f"wq/wk std {std}: bf16 operands move the oracle's actions by {delta:.3e} of their RMS")
+    assert lo <= delta <= hi, delta
