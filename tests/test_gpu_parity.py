@@ -146,11 +146,12 @@ def split_taps(cfg, taps, n_views, n_prompt):
 
 
 # Key / value cache, element by element (the one tensor that crosses the prefill / denoise boundary): max |delta| over
-# a layer relative to that layer's RMS.  Derivation: a cache element is a 2048-term dot product of bf16-cast inputs
-# (independent relative errors up to 2^-9: about 1e-3 of the RMS per element, 5e-3 at the 4.5-sigma maximum over the
-# layer's elements), stored as bf16 (up to 2^-9 of an element of 4.5 RMS: 9e-3), on top of the hidden-state error that
-# 17 layers accumulate (about sqrt(17) times the first): a few 1e-2 at the last layers.
-CACHE_TOL = 5e-2
+# a layer relative to that layer's RMS.  The bar is 2.5 x what bf16 GEMM operands alone do to the ORACLE's cache
+# (tests/test_bf16_sensitivity.py, CPU: up to 5.4e-2 at the deepest layers of the full model, 1.2e-1 in the
+# sharp-attention configuration): the same factor that the task's 2e-2 action bar has over the rounding-only 4e-3 to
+# 8e-3 of the actions.
+CACHE_TOL = 0.135
+SHARP_CACHE_TOL = 0.30
 
 
 def check_against_oracle(case, n_views, n_prompt, seed_shift=0, label="", action_tol=ACTION_TOL, mxfp8=False, cos_min=COS_MIN,
@@ -287,7 +288,7 @@ def test_sharp_attention_masks():
     case = Case(synth.reduced_config(vocab=1024), seed=5, overrides={"wq": 0.05, "wk": 0.05})
     try:
         check_against_oracle(case, 2, 7, label="sharp attention 2 views + 7 prompt", action_tol=SHARP_ACTION_TOL,
-                             cache_tol=2.5 * CACHE_TOL)
+                             cache_tol=SHARP_CACHE_TOL)
     finally:
         case.close()
 
