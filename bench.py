@@ -4,8 +4,14 @@
 A "step" is one complete forward pass (vision encoder, prefix transformer, 10 Euler steps of
 the action expert) at batch 1 with inputs already resident in HBM, replayed from a HIP graph.
 Workload at N=1: full-depth pi0, 1 view, empty prompt, chunk 63 (seeded random-init bf16
-weights, synthetic inputs).  The 2- and 3-view latencies of the same metric are measured in
-the same run and reported alongside.  Prints ONE JSON line.
+weights, synthetic inputs).  The 2- and 3-view latencies of the same metric, the largest
+configuration (3 views + 48 prompt tokens from the 257152-row table) and the streaming use
+(pi0_denoise alone on a cached prefix) are measured in the same run and reported alongside,
+each view count with its own roofline fractions.  Prints ONE JSON line.
+
+Other modes (for profilers; no JSON metric line):
+  --trace-pass      warm-up, then `--steps` graph replays of pi0_infer at `--views` and nothing else
+  --counters-pass   one 1 GiB device-to-device copy (calibration point of the byte counters) and ONE eager pass
 """
 from __future__ import annotations
 
@@ -19,19 +25,21 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-
-# HBM-side bytes per launch of an operation class, where a counter run exists (2 x FETCH_SIZE + WRITE_SIZE,
-# calibrated against a copy kernel)
-PMC_TRAFFIC_BYTES = {   # profiles/counters_full_pi0_1view_eager_pass.txt
-    "exp_down": 13596672, "exp_gateup": 18720768, "exp_o": 7324672, "exp_qkv": 7132160, "exp_attn": 3123200,
-    "exp_out": 257126,
-    "llm_gateup": 152385331, "llm_down": 167919001, "llm_qkv": 21047296, "llm_o": 22289612, "vis_qkv": 38654156,
-    "vis_o": 13193216, "vis_up": 17787699, "vis_down": 32711680, "vis_proj": 12871680, "vis_patch": 5421056,
-}
+# HBM-side bytes per launch from hardware-counter runs of `bench.py --counters-pass` (2 x FETCH_SIZE + WRITE_SIZE,
+# calibrated against a copy): read from the committed profile, which records the commit it was taken at
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "traffic_full_pi0.json")
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
+
+
+def load_traffic():
+    try:
+        with open(TRAFFIC_PROFILE) as f:
+            return json.load(f)
+    except (OSError, ValueError):
+        return None
 
 
 def main() -> int:
@@ -42,15 +50,11 @@ def main() -> int:
     ap.add_argument("--reduced", action="store_true", help="reduced-depth model (parity config, not the metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--views", type=int, default=1, help="views of the headline workload")
-    ap.add_argument("--counters-pass", action="store_true",
-                    help="for hardware-counter runs: one 1 GiB device-to-device copy (calibration point) and ONE "
-                         "eager pass (no graph, no timing), then exit")
+    ap.add_argument("--prompt", type=int, default=0, help="prompt tokens (--trace-pass / --counters-pass only)")
+    ap.add_argument("--counters-pass", action="store_true")
+    ap.add_argument("--trace-pass", action="store_true")
+    ap.add_argument("--tune", type=str, default=None, help="kernel choices for tuning runs (pi0_tune)")
     args = ap.parse_args()
-    if args.counters_pass:
-        # counter collection runs one kernel at a time, so the expert's read-ahead kernel (a second stream beside
-        # the compute launches) would only wait out its bound: this pass runs without it and without warm-up blocks
-        # inside the launches, so that every launch's counters are its own traffic
-        os.environ["PI0_TUNE"] = ",".join(x for x in (os.environ.get("PI0_TUNE", ""), "ras=0,pfq=0,pfa=0,pfo=0,pfd=0") if x)
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (batch-1 latency path, no sharding); use --gpus 1",
               file=sys.stderr)
@@ -64,12 +68,13 @@ def main() -> int:
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         return 3
     dev = torch.device("cuda:0")
-    cfg = synth.reduced_config() if args.reduced else synth.full_config()
+    # the full model always carries the 257152-row prompt embedding table: the empty-prompt workloads never touch it
+    cfg = synth.reduced_config(vocab=1024) if args.reduced else synth.full_config(vocab=257152)
     t0 = time.time()
     blob = synth.make_weights(cfg, seed=0, threads=16)
     log(f"[bench] weights generated: {blob.nbytes / 1e9:.2f} GB in {time.time() - t0:.1f} s")
     stream = torch.cuda.Stream(device=dev)
-    m = binding.Pi0(cfg)
+    m = binding.Pi0(cfg, tune=args.tune)
     d_blob = torch.from_numpy(blob.view(np.int16)).to(dev)
     m.pi0_load_weights(d_blob, stream)
     stream.synchronize()
@@ -80,6 +85,12 @@ def main() -> int:
     state = torch.from_numpy(synth.make_state(cfg)).to(dev)
     noise = torch.from_numpy(synth.make_noise(cfg)).to(dev)
     actions = torch.empty((cfg.chunk, cfg.action_dim), dtype=torch.float32, device=dev)
+    images_of = {v: torch.from_numpy(synth.make_images(cfg, v)).to(dev) for v in (1, 2, 3)}
+    n_prompt_max = min(48, cfg.max_prompt)
+    prompt = torch.from_numpy(synth.make_prompt(cfg, n_prompt_max)).to(dev)
+
+    def infer(v, n_prompt=0):
+        m.pi0_infer(images_of[v], v, prompt if n_prompt else None, n_prompt, state, noise, actions, stream)
 
     if args.counters_pass:
         src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
@@ -87,25 +98,40 @@ def main() -> int:
         torch.cuda.synchronize()
         dst.copy_(src)          # reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
-        images = torch.from_numpy(synth.make_images(cfg, args.views)).to(dev)
         m.pi0_set_graph_mode(False)
-        m.pi0_infer(images, args.views, None, 0, state, noise, actions, stream)
+        infer(args.views, args.prompt)
         stream.synchronize()
-        print(json.dumps({"mode": "counters-pass", "views": args.views, "copy_bytes_each_way": 1 << 30}), flush=True)
+        m.pi0_device_status(stream)
+        print(json.dumps({"mode": "counters-pass", "views": args.views, "prompt": args.prompt, "copy_bytes_each_way": 1 << 30}),
+              flush=True)
         m.close()
         return 0
 
-    def time_views(n_views: int, steps: int, warmup: int):
-        images = torch.from_numpy(synth.make_images(cfg, n_views)).to(dev)
+    if args.trace_pass:
+        for _ in range(5):
+            infer(args.views, args.prompt)
+        stream.synchronize()
+        t_start = time.perf_counter()
+        for _ in range(args.steps):
+            infer(args.views, args.prompt)
+        stream.synchronize()
+        ms = (time.perf_counter() - t_start) * 1e3 / args.steps
+        m.pi0_device_status(stream)
+        print(json.dumps({"mode": "trace-pass", "views": args.views, "prompt": args.prompt, "replays": args.steps,
+                          "ms_per_replay_wall": round(ms, 4)}), flush=True)
+        m.close()
+        return 0
+
+    def time_infer(v: int, steps: int, warmup: int, n_prompt: int = 0):
         for _ in range(warmup):
-            m.pi0_infer(images, n_views, None, 0, state, noise, actions, stream)
+            infer(v, n_prompt)
         stream.synchronize()
         torch.cuda.synchronize()
         evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
         t_start = time.perf_counter()
         evs[0].record(stream)
         for i in range(steps):
-            m.pi0_infer(images, n_views, None, 0, state, noise, actions, stream)
+            infer(v, n_prompt)
             evs[i + 1].record(stream)
         stream.synchronize()
         torch.cuda.synchronize()
@@ -125,46 +151,116 @@ def main() -> int:
         stream.synchronize()
         return e0.elapsed_time(e1) / steps
 
+    side_steps = max(20, args.steps // 4)
     headline_views = args.views
-    wall_ms, per = time_views(headline_views, args.steps, args.warmup)
+    wall_ms, per = time_infer(headline_views, args.steps, args.warmup)
     log(f"[bench] {headline_views} view(s): {wall_ms:.3f} ms/step wall, event median {np.median(per):.3f} ms")
     views_ms = {}
     for v in (1, 2, 3):
         if v == headline_views:
             views_ms[str(v)] = float(np.median(per))
         else:
-            _, pv = time_views(v, max(20, args.steps // 4), max(5, args.warmup // 2))
+            _, pv = time_infer(v, side_steps, max(5, args.warmup // 2))
             views_ms[str(v)] = float(np.median(pv))
         log(f"[bench] {v} view(s): median {views_ms[str(v)]:.3f} ms")
 
-    # stage split of the headline workload (separate graphs for prefill and denoise)
-    images = torch.from_numpy(synth.make_images(cfg, headline_views)).to(dev)
-    prefill_ms = time_stage(lambda: m.pi0_prefill(images, headline_views, None, 0, stream), max(20, args.steps // 4), 5)
-    denoise_ms = time_stage(lambda: m.pi0_denoise(state, noise, actions, stream), max(20, args.steps // 4), 5)
-    log(f"[bench] prefill {prefill_ms:.3f} ms, denoise {denoise_ms:.3f} ms")
-
-    # per-class kernel durations, measured live with HIP event pairs on the stream the kernels run on
-    timing = m.pi0_debug_profile(images, headline_views, None, 0, state, noise, actions, passes=3, stream=stream)
-    rows = roofline.class_rooflines(roofline.class_work(cfg, headline_views, 0), timing)
-    for r in rows:
+    # stage split and per-class kernel durations at every view count: separate graphs for prefill and denoise; classes
+    # from HIP event pairs on the stream around eager launches (pi0_debug_profile, 3 passes).  The expert's operations
+    # do not appear as classes: on the timed path they are one persistent kernel (`expert_loop_kernel`), whose launch
+    # is the denoise figure.
+    prefill_ms, denoise_ms, by_views, class_rows = {}, {}, {}, {}
+    for v in (1, 2, 3):
+        prefill_ms[v] = time_stage(lambda: m.pi0_prefill(images_of[v], v, None, 0, stream), side_steps, 5)
+        denoise_ms[v] = time_stage(lambda: m.pi0_denoise(state, noise, actions, stream), side_steps, 5)
+        timing = m.pi0_debug_profile(images_of[v], v, None, 0, state, noise, actions, passes=3, stream=stream)
+        work = roofline.class_work(cfg, v, 0)
+        rows = [r for r in roofline.class_rooflines(work, timing) if not r["class"].startswith("exp_")]
+        class_rows[v] = rows
+        ops = roofline.table2_ops(cfg, v, 0, joint_vision_attention=False)
+        wbytes, ebytes = roofline.weight_bytes(ops), roofline.weight_bytes(ops, "expert")
+        bounds = roofline.stage_bounds_ms(ops, roofline.MI355X_BW, roofline.MI355X_MACS)
+        rec = {"pass_ms": round(views_ms[str(v)], 4), "prefill_ms": round(prefill_ms[v], 4), "denoise_ms": round(denoise_ms[v], 4),
+               "roofline_ms": round(bounds["total"], 4), "pass_frac_of_roofline": round(bounds["total"] / views_ms[str(v)], 4),
+               "pass_hbm_GBps": round(wbytes / (views_ms[str(v)] * 1e-3) / 1e9, 1),
+               "pass_frac_hbm": round(wbytes / (views_ms[str(v)] * 1e-3) / 8e12, 4),
+               "denoise_hbm_GBps": round(ebytes / (denoise_ms[v] * 1e-3) / 1e9, 1),
+               "denoise_frac_hbm": round(ebytes / (denoise_ms[v] * 1e-3) / 8e12, 4)}
+        for r in rows:      # the prefix GEMMs the paper's roofline calls compute-bound from two views on
+            if r["class"] in ("llm_gateup", "llm_down", "llm_qkv", "llm_o", "vis_up", "vis_down", "vis_qkv"):
+                _, fl = work[r["class"]]
+                tf = fl / (r["avg_us"] * 1e-6) / 1e12
+                rec[r["class"]] = {"avg_us": r["avg_us"], "TFLOPs": round(tf, 1), "mfma_frac": round(tf / 2500.0, 4), "bound": r["bound"]}
+        by_views[str(v)] = rec
+        log(f"[bench] {v} view(s): prefill {prefill_ms[v]:.3f} ms, denoise {denoise_ms[v]:.3f} ms; gate||up "
+            f"{rec['llm_gateup']['avg_us']:.1f} us = {rec['llm_gateup']['mfma_frac']:.3f} of the bf16 MFMA peak, down "
+            f"{rec['llm_down']['avg_us']:.1f} us = {rec['llm_down']['mfma_frac']:.3f}; denoise {rec['denoise_frac_hbm']:.3f} of the HBM peak")
+    for r in class_rows[headline_views]:
         log("[bench] class %-10s launches %5d avg %8.2f us total %9.1f us  %s" % (
             r["class"], r["launches"], r["avg_us"], r["total_us"],
             ("%s %.1f %s = %.3f of peak" % (r["bound"], r["achieved"], r["unit"], r["frac"])) if "bound" in r else ""))
-    krows = roofline.kernel_rooflines(roofline.class_work(cfg, headline_views, 0), timing, PMC_TRAFFIC_BYTES,
-                                      prefix_tokens=headline_views * cfg.tokens_per_view)
+
+    # the largest configuration: 3 views + 48 prompt tokens (816 prefix tokens), and the streaming use on its cache
+    config5 = None
+    if n_prompt_max > 0:
+        _, p5 = time_infer(3, side_steps, 5, n_prompt_max)
+        d5 = time_stage(lambda: m.pi0_denoise(state, noise, actions, stream), side_steps, 5)
+        pf5 = time_stage(lambda: m.pi0_prefill(images_of[3], 3, prompt, n_prompt_max, stream), side_steps, 5)
+        ops5 = roofline.table2_ops(cfg, 3, n_prompt_max, joint_vision_attention=False)
+        b5 = roofline.stage_bounds_ms(ops5, roofline.MI355X_BW, roofline.MI355X_MACS)
+        config5 = {"workload": f"3 views + {n_prompt_max} prompt tokens ({3 * cfg.tokens_per_view + n_prompt_max} prefix tokens), "
+                               f"{cfg.vocab}-row embedding table",
+                   "infer_ms": round(float(np.median(p5)), 4), "prefill_ms": round(pf5, 4),
+                   "denoise_only_ms": round(d5, 4), "roofline_ms": round(b5["total"], 4),
+                   "denoise_frac_hbm": round(roofline.weight_bytes(ops5, "expert") / (d5 * 1e-3) / 8e12, 4)}
+        log(f"[bench] 3 views + {n_prompt_max} prompt tokens: infer {config5['infer_ms']:.3f} ms, prefill {pf5:.3f} ms, "
+            f"streaming denoise alone {d5:.3f} ms per chunk")
+
+    # the kernel with the largest share of the pass: the persistent denoise loop, one launch per pass.  Algorithmic
+    # bytes of a launch = what its operations must move if every operand crossed HBM once (roofline.class_work, per
+    # operation of Table 2: weights + input activations + outputs) times their count; duration = the denoise call
+    # (event pair on the stream around graph replays of barrier-word clear + parameter block + loop kernel)
+    hv = headline_views
+    work = roofline.class_work(cfg, hv, 0)
+    per_layer = sum(work[k][0] for k in ("exp_qkv", "exp_attn", "exp_o", "exp_gateup", "exp_down"))
+    per_layer_fl = sum(work[k][1] for k in ("exp_qkv", "exp_attn", "exp_o", "exp_gateup", "exp_down"))
+    loop_bytes = cfg.steps * (cfg.exp_layers * per_layer + work["exp_out"][0])
+    loop_flops = cfg.steps * (cfg.exp_layers * per_layer_fl + work["exp_out"][1])
+    traffic_prof = load_traffic()
+    loop_traffic, traffic_commit = None, None
+    if traffic_prof is not None:
+        loop_traffic = traffic_prof.get("by_views", {}).get(str(hv), {}).get("expert_loop_kernel")
+        traffic_commit = traffic_prof.get("commit")
+    loop_gbps = loop_bytes / (denoise_ms[hv] * 1e-3) / 1e9
+    dominant = {"bound": "hbm", "achieved": round(loop_gbps, 1), "peak": 8000.0, "unit": "GB/s",
+                "frac": round(loop_gbps / 8000.0, 4), "traffic": loop_traffic,
+                "kernel": "expert_loop_kernel", "launches_per_pass": 1, "avg_us": round(denoise_ms[hv] * 1e3, 1),
+                "algorithmic_bytes_per_launch": int(loop_bytes), "algorithmic_flops_per_launch": int(loop_flops),
+                "units_per_launch": f"{cfg.steps} Euler steps x {cfg.exp_layers} layers x 5 operations (+ 3 per step)",
+                "traffic_profile_commit": traffic_commit}
+    log(f"[bench] expert_loop_kernel: {loop_bytes / 1e9:.3f} GB algorithmic in {denoise_ms[hv]:.3f} ms = {loop_gbps:.0f} GB/s "
+        f"= {loop_gbps / 8000.0:.3f} of the HBM peak")
+    # prefill kernels by template family (eager, event-bracketed launches)
+    timing_h = m.pi0_debug_profile(images_of[hv], hv, None, 0, state, noise, actions, passes=3, stream=stream)
+    class_traffic = (traffic_prof or {}).get("by_views", {}).get(str(hv), {}).get("classes")
+    krows = [r for r in roofline.kernel_rooflines(work, timing_h, class_traffic, prefix_tokens=hv * cfg.tokens_per_view)
+             if not any(c.startswith("exp_") for c in r["classes"])]
     for r in krows:
         log("[bench] kernel %-22s launches %5d avg %8.2f us total %9.1f us  %s %.1f %s = %.3f of peak" % (
             r["kernel"], r["launches"], r["avg_us"], r["total_us"], r["bound"], r["achieved"], r["unit"], r["frac"]))
-    dominant = krows[0]
+
+    # the per-operation launch path of the expert (pi0_tune "pdn=0"), for comparison with the persistent kernel
+    m.pi0_tune("pdn=0")
+    denoise_launch_ms = time_stage(lambda: m.pi0_denoise(state, noise, actions, stream), side_steps, 5)
+    m.pi0_tune("pdn=1")
+    m.pi0_prefill(images_of[hv], hv, None, 0, stream)
+    log(f"[bench] denoise as per-operation launches: {denoise_launch_ms:.3f} ms (persistent kernel: {denoise_ms[hv]:.3f} ms)")
 
     # reduced-precision mode (not the metric: bf16 is): prefix gate||up / down on MXFP8 operands
     mx_ms = {}
     m.pi0_set_precision("mxfp8_prefix_mlp")
     for v in (1, 2, 3):
-        imgs = torch.from_numpy(synth.make_images(cfg, v)).to(dev)
-        mx_ms[str(v)] = round(time_stage(lambda: m.pi0_infer(imgs, v, None, 0, state, noise, actions, stream),
-                                         max(20, args.steps // 4), 5), 4)
-    m.pi0_infer(images, headline_views, None, 0, state, noise, actions, stream)
+        mx_ms[str(v)] = round(time_stage(lambda: infer(v), side_steps, 5), 4)
+    infer(hv)
     stream.synchronize()
     mx_actions = actions.cpu().numpy().copy()
     m.pi0_set_precision("bf16")
@@ -176,7 +272,7 @@ def main() -> int:
     cs1 = torch.zeros(2, dtype=torch.int64, device=dev)
     binding.pi0_clock_sample(cs0, stream)
     for _ in range(50):
-        m.pi0_infer(images, headline_views, None, 0, state, noise, actions, stream)
+        infer(hv)
     binding.pi0_clock_sample(cs1, stream)
     stream.synchronize()
     clock_ghz = binding.shader_clock_ghz(cs0.cpu().tolist(), cs1.cpu().tolist())
@@ -186,29 +282,37 @@ def main() -> int:
     sp2, sd2 = torch.cuda.Stream(device=dev), torch.cuda.Stream(device=dev)
     stream_ms = {}
     for v in (1, 2, 3):
-        imgs = torch.from_numpy(synth.make_images(cfg, v)).to(dev)
-        m.pi0_prefill(imgs, v, None, 0, sp2)
+        m.pi0_prefill(images_of[v], v, None, 0, sp2)
         for _ in range(5):
-            m.pi0_stream_frame(imgs, v, None, 0, state, noise, actions, sp2, sd2)
+            m.pi0_stream_frame(images_of[v], v, None, 0, state, noise, actions, sp2, sd2)
         sp2.synchronize(); sd2.synchronize()
-        nfr = max(20, args.steps // 4)
         t_start = time.perf_counter()
-        for _ in range(nfr):
-            m.pi0_stream_frame(imgs, v, None, 0, state, noise, actions, sp2, sd2)
+        for _ in range(side_steps):
+            m.pi0_stream_frame(images_of[v], v, None, 0, state, noise, actions, sp2, sd2)
         sp2.synchronize(); sd2.synchronize()
-        stream_ms[str(v)] = round((time.perf_counter() - t_start) * 1e3 / nfr, 4)
+        stream_ms[str(v)] = round((time.perf_counter() - t_start) * 1e3 / side_steps, 4)
     log("[bench] two-stream frame interval ms by views: " + json.dumps(stream_ms))
 
-    # Table 3's experiment on this machine: 1378 dependent A+B updates under different orderings
+    # Table 3's experiment on this machine: 1378 dependent A+B updates under different orderings ...
     sx = torch.zeros((256, 1024), dtype=torch.float32, device=dev)
     sb = torch.ones((256, 1024), dtype=torch.float32, device=dev)
-    sstate = torch.zeros(2, dtype=torch.int32, device=dev)
+    sstate = torch.zeros(16384, dtype=torch.int32, device=dev)
     torch.cuda.synchronize()
     sync_ms = {}
     for mode in ("eager", "graph", "barrier", "barrier_fence", "fused"):
         binding.pi0_sync_bench(mode, 1378, 1, sx, sb, sstate, stream)          # warm-up
         sync_ms[mode] = round(binding.pi0_sync_bench(mode, 1378, 5, sx, sb, sstate, stream), 4)
     log("[bench] sync overhead, ms per 1378 updates: " + ", ".join(f"{k} {v:.3f}" for k, v in sync_ms.items()))
+    # ... and with a real dependency between blocks (every block reads 8 rows = 32 KiB that other blocks wrote in the
+    # update before): barrier kinds with no data, then data paths under the die-aware barrier
+    sx2 = torch.zeros((2, 256, 1024), dtype=torch.float32, device=dev)
+    dep_ms = {}
+    for barrier, data in (("counter", "none"), ("xcd", "none"), ("flags", "none"), ("groupadd", "none"), ("xcc", "none"),
+                          ("xcc", "bypass"), ("xcc", "wback"), ("xcc", "inv"), ("xcd", "fence")):
+        binding.pi0_sync_dep_bench(barrier, data, 8, 1378, 1, sx2, sb, sstate, stream)
+        dep_ms[f"{barrier}/{data}"] = round(binding.pi0_sync_dep_bench(barrier, data, 8, 1378, 3, sx2, sb, sstate, stream), 4)
+    log("[bench] dependent updates (fan 8), ms per 1378: " + ", ".join(f"{k} {v:.3f}" for k, v in dep_ms.items()))
+    del sx2
 
     # what this device attains on the two resources of the roofline: a streaming read of 1 GiB of random
     # words (4 x the last-level cache) and a register-resident bf16 MFMA loop
@@ -223,12 +327,12 @@ def main() -> int:
     def of_attainable(row):
         att = peak_hbm if row.get("unit") == "GB/s" else peak_mfma
         return round(row["achieved"] / att, 4) if "achieved" in row and att > 0 else None
-    for row in list(krows) + list(rows):
+    for row in list(krows) + list(class_rows[hv]) + [dominant]:
         if "achieved" in row:
             row["frac_attainable"] = of_attainable(row)
 
     # whole-pass roofline: algorithmic HBM bytes = every weight matrix once per use (Section 5.1)
-    ops = roofline.table2_ops(cfg, headline_views, 0, joint_vision_attention=False)
+    ops = roofline.table2_ops(cfg, hv, 0, joint_vision_attention=False)
     algo_bytes = roofline.weight_bytes(ops)
     ms_per_step = float(wall_ms)
     achieved = algo_bytes / (ms_per_step * 1e-3) / 1e9
@@ -248,55 +352,55 @@ def main() -> int:
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": ("reduced-depth pi0 (2/2/2 layers)" if args.reduced else "full pi0 (27/18/18 layers)")
-                   + f", {headline_views} view(s), empty prompt, chunk {cfg.chunk}, {cfg.steps} flow steps, batch 1, "
+                   + f", {hv} view(s), empty prompt, chunk {cfg.chunk}, {cfg.steps} flow steps, batch 1, "
                    "seeded N(0,0.02) bf16 weights",
-                   "n_views": headline_views, "prefix_tokens": headline_views * cfg.tokens_per_view,
-                   "kernels_per_step": m.pi0_kernel_count(headline_views, 0)},
+                   "n_views": hv, "prefix_tokens": hv * cfg.tokens_per_view,
+                   "kernels_per_step": m.pi0_kernel_count(hv, 0)},
         "latency_ms": {"median": round(float(np.median(per)), 4), "mean": round(float(per.mean()), 4),
                        "p99": round(float(np.percentile(per, 99)), 4), "min": round(float(per.min()), 4),
                        "by_views_median": {k: round(v, 4) for k, v in views_ms.items()},
-                       "prefill": round(prefill_ms, 4), "denoise": round(denoise_ms, 4)},
+                       "prefill": round(prefill_ms[hv], 4), "denoise": round(denoise_ms[hv], 4),
+                       "denoise_per_operation_launches": round(denoise_launch_ms, 4)},
         "paper_rtx4090_ms": {"1": 20.0, "2": 27.3, "3": 36.8},
+        # per view count: the pass against the Section 5.1 roofline, the prefix GEMMs against the bf16 MFMA peak,
+        # the denoise loop's weight streaming against the HBM peak
+        "roofline_by_views": by_views,
+        # 3 views + 48 prompt tokens with the 257152-row table; pi0_denoise alone on that cache (streaming use)
+        "config5": config5,
         # frame interval when the prefill of frame k overlaps the denoise of frame k-1 (pi0_stream_frame)
         "two_stream_frame_interval_ms": stream_ms,
         # pi0_set_precision(MXFP8_PREFIX_MLP): latency of the same pass with the prefix feed-forward GEMMs on MXFP8
         # operands (a different numerics contract; reported beside the metric, never as it)
         "mxfp8_prefix_mlp_ms": mx_ms,
-        # the kernel (all launches of one template family) with the largest share of the pass: algorithmic
-        # bytes of its launches / their event-timed duration (eager launches, 3 passes)
-        "roofline": {"bound": dominant["bound"], "achieved": dominant["achieved"], "peak": dominant["peak"],
-                     "unit": dominant["unit"], "frac": dominant["frac"], "traffic": dominant["traffic"],
-                     "frac_attainable": of_attainable(dominant),
-                     "kernel": dominant["kernel"], "classes": dominant["classes"],
-                     "avg_us": dominant["avg_us"], "launches_per_pass": dominant["launches"] // 3,
-                     "algorithmic_bytes_per_launch": dominant["algorithmic_bytes_per_launch"],
-                     "algorithmic_flops_per_launch": dominant["algorithmic_flops_per_launch"]},
+        "roofline": dominant,
         # measured on this device by pi0_peak_bench, beside the published peaks the `frac` fields use
         "shader_clock_GHz": round(clock_ghz, 3),
         "attainable_peaks": {"hbm_read_GBps": round(peak_hbm, 1), "mfma_bf16_TFLOPs": round(peak_mfma, 1),
                              "published": {"hbm_GBps": 8000.0, "mfma_bf16_TFLOPs": 2500.0}},
-        "roofline_kernels": krows,
-        "roofline_classes": rows,
-        # Section 5.2: ms for 1378 dependent updates; the paper's RTX 4090 figures for the same experiment
+        "roofline_kernels": [dominant] + krows,
+        "roofline_classes": class_rows[hv],
+        # Section 5.2: ms for 1378 dependent updates; the paper's RTX 4090 figures for the same experiment; and the
+        # same count of updates that really depend on other blocks' rows (barrier kind / data path)
         "sync_overhead_ms": {"mi355x": sync_ms, "extra_per_graph_node_us": round((sync_ms["graph"] - sync_ms["fused"]) / 1.378, 3),
-                             "paper_rtx4090": {"eager": 13.81, "graph": 2.61, "barrier": 1.75, "fused": 0.89}},
+                             "paper_rtx4090": {"eager": 13.81, "graph": 2.61, "barrier": 1.75, "fused": 0.89},
+                             "mi355x_dependent_fan8": dep_ms},
         # the whole pass against the paper's roofline model (weights once per use, Section 5.1)
         "roofline_pass": {"bound": "hbm", "achieved": round(achieved, 1), "peak": 8000.0, "unit": "GB/s",
                           "frac": round(achieved / 8000.0, 4), "frac_attainable": round(achieved / peak_hbm, 4),
                           "algorithmic_bytes": int(algo_bytes),
                           "model_ms": {k: round(v, 4) for k, v in bounds.items()},
-                          "denoise_hbm_GBps": round(exp_bytes / (denoise_ms * 1e-3) / 1e9, 1),
-                          "denoise_frac": round(exp_bytes / (denoise_ms * 1e-3) / 8e12, 4)},
+                          "denoise_hbm_GBps": round(exp_bytes / (denoise_ms[hv] * 1e-3) / 1e9, 1),
+                          "denoise_frac": round(exp_bytes / (denoise_ms[hv] * 1e-3) / 8e12, 4)},
     }
 
     if not args.no_cpu_baseline:
         from oracle import pi0_oracle
         tensors = synth.blob_views(cfg, blob)
-        img = synth.make_images(cfg, headline_views)
+        img = synth.make_images(cfg, hv)
         t0 = time.time()
         ref = pi0_oracle.pi0_forward(cfg, tensors, img, synth.make_state(cfg), synth.make_noise(cfg))
         cpu_s = time.time() - t0
-        m.pi0_infer(images, headline_views, None, 0, state, noise, actions, stream)
+        infer(hv)
         stream.synchronize()
         got = actions.cpu().numpy()
         rms = float(np.sqrt((ref.astype(np.float64) ** 2).mean()))
@@ -311,6 +415,7 @@ def main() -> int:
         out["parity"] = {"max_abs_delta_over_rms": round(err, 6), "tolerance": 2e-2,
                          "mxfp8_mode_vs_fp32_oracle": round(float(np.abs(mx_actions - ref).max()) / rms, 6)}
         log(f"[bench] oracle {cpu_s:.1f} s on {cores} threads; parity {err:.3e}")
+    m.pi0_device_status(stream)
     print(json.dumps(out), flush=True)
     m.close()
     return 0

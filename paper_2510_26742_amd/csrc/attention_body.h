@@ -10,7 +10,7 @@
 // MAXR: key rounds per wave over segment 0 (8 * MAXR chunks = 256 * MAXR keys); VRING: value
 // chunks in flight per wave.
 template <int DQK, int NVB, int MAXR, int VRING, class Cx>
-__device__ __forceinline__ void attention_body(const AttnParams& p, const Cx& cx, unsigned char* smem_raw) {
+__device__ __forceinline__ void attention_body(const AttnParams p, const Cx cx, unsigned char* smem_raw) {
   constexpr int S16 = DQK / 16;
   constexpr bool DUAL = MAXR == 1;             // second accumulators (register room permitting)
   constexpr int QB = (MAXR == 1 && S16 % 8 == 0) ? 8 : 1;   // Q fragments read from LDS per batch (register room permitting)

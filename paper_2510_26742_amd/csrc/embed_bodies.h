@@ -12,7 +12,7 @@ struct StateTokenArgs {
 
 // state token: out[n] = sum_j state[j] * ws[j][n] + bs[n]   (Table 2 row 1x32x1024)
 template <class Cx>
-__device__ __forceinline__ void state_token_body(const StateTokenArgs& a, const Cx& cx) {
+__device__ __forceinline__ void state_token_body(const StateTokenArgs a, const Cx cx) {
   const int tx = cx.tid();
   if (tx >= 256) return;
   const int n = cx.bx * 256 + tx;
@@ -46,7 +46,7 @@ struct ActionEmbedArgs {
 // The state row also gets its gain-scaled bf16 copy and, per 32 columns, its (sum, sum of squares) in
 // stat_parts[tile][64 rows][2] (row 0), the form the first QKV GEMM of the step reads.
 template <class Cx>
-__device__ __forceinline__ void action_embed_body(const ActionEmbedArgs& a, const Cx& cx) {
+__device__ __forceinline__ void action_embed_body(const ActionEmbedArgs a, const Cx cx) {
   const int tx = cx.tid();
   if (tx >= 256) return;
   const int n = cx.bx * 256 + tx;

@@ -149,7 +149,7 @@ __global__ __launch_bounds__(PK_THREADS) void expert_loop_kernel(const ExpertLoo
         if (a.ml_out != nullptr) a.ml_out = reinterpret_cast<float*>(slot + F.r_ml);
         const int att_gx = F.att_gx, att_gxy = F.att_gx * a.heads;
         for_items(F.att_items, [&](int it) {
-          attention_body<256, 8, 1, 8>(a, item(it % att_gx, (it % att_gxy) / att_gx, it / att_gxy).template as<true>(), smem_raw);
+          attention_body<256, 8, 1, 6>(a, item(it % att_gx, (it % att_gxy) / att_gx, it / att_gxy).template as<true>(), smem_raw);
         });
         op_end();
       }

@@ -42,6 +42,7 @@ __device__ __forceinline__ size_t xf_index(int m, int k, int kc16) {
 // Operands of the epilogue that come from memory (bias, column sums, residual / RoPE table, gain),
 // loaded ahead of time: a kernel calls epilogue_preload as early as it knows its (tile, row), so
 // that the round trip overlaps the main loop instead of following it.
+// slot j holds the operands of the tile's step I0 + j of the wave that asked for steps I0 .. I1 - 1
 struct EpiOps {
   f32x4 bias[4], colsum[4], aux[4], gain[4];
 };
@@ -58,22 +59,22 @@ __device__ __forceinline__ void epilogue_preload(const GemmParams& p, int nt, in
   for (int i = I0; i < I1; i++) {
     const int n4 = nt * 32 + 8 * i + 4 * lh;
     if (DEP != 1) {
-      if (PRO == PRO_LN) o.colsum[i] = *reinterpret_cast<const f32x4*>(p.colsum + n4);
-      if (p.bias != nullptr) o.bias[i] = *reinterpret_cast<const f32x4*>(p.bias + n4);
+      if (PRO == PRO_LN) o.colsum[i - I0] = *reinterpret_cast<const f32x4*>(p.colsum + n4);
+      if (p.bias != nullptr) o.bias[i - I0] = *reinterpret_cast<const f32x4*>(p.bias + n4);
     }
     if (EPI == EPI_RESID) {
       if (n4 < p.n_valid) {
         if (DEP != 0 && p.resid != nullptr) {
           const int rr = p.resid_mod > 0 ? (m % p.resid_mod) : m;
-          o.aux[i] = cx.ld(reinterpret_cast<const f32x4*>(p.resid + (size_t)rr * p.ldo + n4));
+          o.aux[i - I0] = cx.ld(reinterpret_cast<const f32x4*>(p.resid + (size_t)rr * p.ldo + n4));
         }
-        if (DEP != 1 && p.gain != nullptr) o.gain[i] = *reinterpret_cast<const f32x4*>(p.gain + n4);
+        if (DEP != 1 && p.gain != nullptr) o.gain[i - I0] = *reinterpret_cast<const f32x4*>(p.gain + n4);
       }
     } else if (EPI == EPI_QKV) {
       if (DEP != 1 && p.rope != nullptr && n4 < p.q_cols + p.k_cols) {
         const int nl = n4 < p.q_cols ? n4 : n4 - p.q_cols;
         const int i0 = (nl & 255) >> 1;
-        o.aux[i] = *reinterpret_cast<const f32x4*>(p.rope + ((size_t)(p.pos0 + m) * 128 + i0) * 2);
+        o.aux[i - I0] = *reinterpret_cast<const f32x4*>(p.rope + ((size_t)(p.pos0 + m) * 128 + i0) * 2);
       }
     }
   }
@@ -114,19 +115,19 @@ __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16&
 #pragma unroll
         for (int j = 0; j < 4; j++) v[j] *= rs;
       } else if (PRO == PRO_LN) {
-        const f32x4 cs = ops.colsum[i];
+        const f32x4 cs = ops.colsum[i - I0];
 #pragma unroll
         for (int j = 0; j < 4; j++) v[j] = rs * (v[j] - mu * cs[j]);
       }
       if (p.bias != nullptr) {
-        const f32x4 bb = ops.bias[i];
+        const f32x4 bb = ops.bias[i - I0];
 #pragma unroll
         for (int j = 0; j < 4; j++) v[j] += bb[j];
       }
       if (EPI == EPI_RESID) {
         if (n4 < p.n_valid) {
           if (p.resid != nullptr) {
-            const f32x4 r4 = ops.aux[i];
+            const f32x4 r4 = ops.aux[i - I0];
 #pragma unroll
             for (int j = 0; j < 4; j++) v[j] += r4[j];
           }
@@ -139,7 +140,7 @@ __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16&
             st_b += v[j] * v[j];
           }
           if (p.gain != nullptr) {
-            const f32x4 g4 = ops.gain[i];
+            const f32x4 g4 = ops.gain[i - I0];
 #pragma unroll
             for (int j = 0; j < 4; j++) v[j] *= g4[j];
           }
@@ -195,7 +196,7 @@ __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16&
             // packed head layout: row 2i = dim i, row 2i+1 = dim i + 128
             const int head = nl >> 8;
             const int i0 = (nl & 255) >> 1;          // even
-            const f32x4 c4 = ops.aux[i];   // cos i0, sin i0, cos i0+1, sin i0+1
+            const f32x4 c4 = ops.aux[i - I0];   // cos i0, sin i0, cos i0+1, sin i0+1
             const float lo0 = v[0] * c4[0] - v[1] * c4[1], hi0 = v[1] * c4[0] + v[0] * c4[1];
             const float lo1 = v[2] * c4[2] - v[3] * c4[3], hi1 = v[3] * c4[2] + v[2] * c4[3];
             const bf16x2 lo = {(bf16)lo0, (bf16)lo1};
@@ -278,8 +279,23 @@ __device__ __forceinline__ void skinny_finish(const GemmParams& p, const float* 
   if (ml < p.M) epilogue_tile<PRO, EPI, I0, I1>(p, sum, nt, ml, lh, ssum, ssq, cx.by, ops, cx);
 }
 
+// the epilogue operands of finishing wave piece fpc (a tile's four 8-feature steps are shared out over PIECES waves)
+template <int PRO, int EPI, int PIECES, int DEP, class Cx>
+__device__ __forceinline__ void skinny_preload(const GemmParams& p, int nt, int mrow, int lh, int fpc, EpiOps& ops, const Cx& cx) {
+  if constexpr (PIECES == 1) epilogue_preload<PRO, EPI, 0, 4, DEP>(p, nt, mrow, lh, ops, cx);
+  else if constexpr (PIECES == 2) {
+    if (fpc == 0) epilogue_preload<PRO, EPI, 0, 2, DEP>(p, nt, mrow, lh, ops, cx);
+    else epilogue_preload<PRO, EPI, 2, 4, DEP>(p, nt, mrow, lh, ops, cx);
+  } else {
+    if (fpc == 0) epilogue_preload<PRO, EPI, 0, 1, DEP>(p, nt, mrow, lh, ops, cx);
+    else if (fpc == 1) epilogue_preload<PRO, EPI, 1, 2, DEP>(p, nt, mrow, lh, ops, cx);
+    else if (fpc == 2) epilogue_preload<PRO, EPI, 2, 3, DEP>(p, nt, mrow, lh, ops, cx);
+    else epilogue_preload<PRO, EPI, 3, 4, DEP>(p, nt, mrow, lh, ops, cx);
+  }
+}
+
 template <int PRO, int EPI, int MS, class Cx>
-__device__ __forceinline__ void gemm_skinny_body(const GemmParams& p, const Cx& cx, unsigned char* smem_raw) {
+__device__ __forceinline__ void gemm_skinny_body(const GemmParams p, const Cx cx, unsigned char* smem_raw) {
   constexpr int NMB = MS ? 1 : 2;              // token blocks per block
   float* red = reinterpret_cast<float*>(smem_raw);                 // [8 waves][2][16][64]
   const int t = cx.tid();
@@ -321,21 +337,6 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmParams& p, const Cx& 
   EpiOps ops;
   const int fmb = w / PIECES, fpc = w % PIECES;
   const int mrow = (mb_first + fmb) * 32 + lq;   // the row this lane finishes if w < NFIN
-  auto preload = [&](auto dep) {
-    constexpr int DEP = decltype(dep)::value;
-    if (w < NFIN && mrow < p.M) {
-      if constexpr (PIECES == 1) epilogue_preload<PRO, EPI, 0, 4, DEP>(p, nt, mrow, lh, ops, cx);
-      else if constexpr (PIECES == 2) {
-        if (fpc == 0) epilogue_preload<PRO, EPI, 0, 2, DEP>(p, nt, mrow, lh, ops, cx);
-        else epilogue_preload<PRO, EPI, 2, 4, DEP>(p, nt, mrow, lh, ops, cx);
-      } else {
-        if (fpc == 0) epilogue_preload<PRO, EPI, 0, 1, DEP>(p, nt, mrow, lh, ops, cx);
-        else if (fpc == 1) epilogue_preload<PRO, EPI, 1, 2, DEP>(p, nt, mrow, lh, ops, cx);
-        else if (fpc == 2) epilogue_preload<PRO, EPI, 2, 3, DEP>(p, nt, mrow, lh, ops, cx);
-        else epilogue_preload<PRO, EPI, 3, 4, DEP>(p, nt, mrow, lh, ops, cx);
-      }
-    }
-  };
   if (Cx::kPersistent) {
     // constants first (weights, then the epilogue's vectors); the inputs are requested once they exist
 #pragma unroll
@@ -343,7 +344,7 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmParams& p, const Cx& 
       const int st = min(w * 8 + i, n16 - 1);
       wf[i] = *reinterpret_cast<const bf16x8*>(wbase + (size_t)st * 512);
     }
-    preload(std::integral_constant<int, 0>{});
+    if (w < NFIN && mrow < p.M) skinny_preload<PRO, EPI, PIECES, 0>(p, nt, mrow, lh, fpc, ops, cx);
     cx.wait_inputs();
   }
   // statistics partials: issued ahead of the operand loads (same round trip), clamped and unconditional
@@ -364,8 +365,10 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmParams& p, const Cx& 
       xf[mb][i] = cx.ld_bulk(reinterpret_cast<const bf16x8*>(xbase + ((size_t)min(mb_first + mb, mb_last) * XKC16 + st) * 512));
   }
   // operands of the epilogue, in the same round trip
-  if (Cx::kPersistent) preload(std::integral_constant<int, 1>{});
-  else preload(std::integral_constant<int, 2>{});
+  if (w < NFIN && mrow < p.M) {
+    if (Cx::kPersistent) skinny_preload<PRO, EPI, PIECES, 1>(p, nt, mrow, lh, fpc, ops, cx);
+    else skinny_preload<PRO, EPI, PIECES, 2>(p, nt, mrow, lh, fpc, ops, cx);
+  }
   f32x16 acc[NMB];
 #pragma unroll
   for (int mb = 0; mb < NMB; mb++)
@@ -439,7 +442,7 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmParams p
 // wave 0 adds the residual, writes fp32, the gain-scaled bf16 copy and per-tile row statistics.
 // Accumulator: lane -> token lane % 16, features 4 * (lane / 16) + r.
 template <int NS, class Cx>
-__device__ __forceinline__ void gemm_skinny16_body(const GemmParams& p, const Cx& cx, unsigned char* smem_raw) {
+__device__ __forceinline__ void gemm_skinny16_body(const GemmParams p, const Cx cx, unsigned char* smem_raw) {
   float (*red)[64][4] = reinterpret_cast<float (*)[64][4]>(smem_raw);   // [SK_WAVES][64][4]
   const int t = cx.tid();
   const int lane = t & 63;

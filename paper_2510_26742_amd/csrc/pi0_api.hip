@@ -778,23 +778,23 @@ void run_prefill(Run& r, int n_views, int n_prompt, Taps* taps) {
 // per-operation launches below fill them for layer 0 / step 0, plus the strides between layers.  Returns false
 // (nothing launched) when the shape or the tuning choices are outside what the kernel covers; the caller then
 // issues the per-operation launches.
-bool run_denoise_persistent(Run& r, int P) {
-  pi0_ctx* c = r.c;
+// whether the denoise loop over a prefix of P tokens runs as the persistent kernel: the device holds its blocks, the
+// tuning choices are the ones it covers, the per-layer strides are uniform
+bool persistent_feasible(const pi0_ctx* c, int P) {
   const Dims& d = c->d;
   const WsLayout& w = c->wl;
   const Tune& T = c->tune;
-  if (!T.pdn || !r.persistent_ok || !c->pk_ok || r.timer != nullptr) return false;
-  const int chunk = c->cfg.chunk;
+  if (!T.pdn || !c->pk_ok) return false;
   const int pchunks = ceil_div(P, 32);
   if (!T.ae16 || !T.qms || d.H != 8 || d.X > SK_KMAX_HOST || d.X % 256 != 0) return false;
   const int shares = pchunks > T.kcps ? ceil_div(pchunks, T.kcps) : 1;
   if (T.kcps > 8 || shares > 4 || (shares > 1 && !T.ksplit)) return false;
+  const int vs = T.avs > 0 ? T.avs : (shares == 1 ? 4 : 2);
+  if (vs != 1 && vs != 2 && vs != 4 && vs != 8) return false;
   const WsTr& L0 = w.exp[0];
   if (L0.o.k_pad != 2048 || (L0.down.k_pad != 2048 && L0.down.k_pad != 4096)) return false;
-  size_t wst = 0, gst = 0;
   if (d.Le > 1) {
-    wst = w.exp[1].qkv.w - w.exp[0].qkv.w;
-    gst = w.g_e1[1] - w.g_e1[0];
+    const size_t wst = w.exp[1].qkv.w - w.exp[0].qkv.w, gst = w.g_e1[1] - w.g_e1[0];
     for (int l = 1; l < d.Le; l++) {
       const WsTr &A = w.exp[l - 1], &B = w.exp[l];
       if (B.qkv.w - A.qkv.w != wst || B.o.w - A.o.w != wst || B.gu.w - A.gu.w != wst || B.down.w - A.down.w != wst) return false;
@@ -802,8 +802,21 @@ bool run_denoise_persistent(Run& r, int P) {
     }
     if (wst % 2 != 0 || gst % 4 != 0) return false;
   }
+  return w.total - w.act_begin < ((size_t)1 << 32);   // offsets inside the arena are 32-bit
+}
+
+bool run_denoise_persistent(Run& r, int P) {
+  pi0_ctx* c = r.c;
+  const Dims& d = c->d;
+  const WsLayout& w = c->wl;
+  const Tune& T = c->tune;
+  if (!r.persistent_ok || r.timer != nullptr || !persistent_feasible(c, P)) return false;
+  const int chunk = c->cfg.chunk;
+  const int pchunks = ceil_div(P, 32);
+  const int shares = pchunks > T.kcps ? ceil_div(pchunks, T.kcps) : 1;
+  const WsTr& L0 = w.exp[0];
+  const size_t wst = d.Le > 1 ? w.exp[1].qkv.w - w.exp[0].qkv.w : 0, gst = d.Le > 1 ? w.g_e1[1] - w.g_e1[0] : 0;
   const size_t arena_bytes = w.total - w.act_begin;
-  if (arena_bytes >= ((size_t)1 << 32)) return false;
   if (r.count_only) {
     r.launches += 3;   // barrier words cleared, parameter block written, the loop kernel
     return true;
@@ -872,7 +885,6 @@ bool run_denoise_persistent(Run& r, int P) {
       a.ml_out = at<float>(c, w.eml);
     }
     a.v_split = T.avs > 0 ? T.avs : (shares == 1 ? 4 : 2);
-    if (a.v_split != 1 && a.v_split != 2 && a.v_split != 4 && a.v_split != 8) return false;
     E.att = a;
     E.att_gx = 2 * a.v_split;
     E.att_items = E.att_gx * d.H * shares;
@@ -1219,7 +1231,11 @@ int execute(pi0_ctx* c, int kind, int n_views, int n_prompt, hipStream_t s, int 
   const int P = n_views * c->d.T + n_prompt;
   if (slot_w < 0) slot_w = c->cur_slot;
   if (slot_r < 0) slot_r = c->cur_slot;
-  if (const hipError_t e = ensure_read_ahead(c); e != hipSuccess) return fail_hip(c, e);
+  // the second stream of the read-ahead kernel exists only where the per-operation launches will use it (a stream
+  // that is never used still takes one of the process's few hardware queues from the streams that are)
+  if (kind != KIND_PREFILL && read_ahead && !persistent_feasible(c, P)) {
+    if (const hipError_t e = ensure_read_ahead(c); e != hipSuccess) return fail_hip(c, e);
+  }
   auto body = [&](Run& r) {
     if (kind == KIND_PREFILL || kind == KIND_INFER) run_prefill(r, n_views, n_prompt, nullptr);
     if (kind == KIND_DENOISE || kind == KIND_INFER) run_denoise(r, P, nullptr);
@@ -1661,8 +1677,6 @@ int pi0_infer(pi0_ctx* c, const float* d_images, int n_views, const int32_t* d_p
   hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
   c->cur_views = 0;
   hipError_t e = stage_inputs(c, s, d_images, n_views, d_prompt_ids, n_prompt, d_state, d_noise);
-  if (e != hipSuccess) return fail_hip(c, e);
-  e = ensure_read_ahead(c);
   if (e != hipSuccess) return fail_hip(c, e);
   int rc = execute(c, KIND_INFER, n_views, n_prompt, s);
   if (rc != PI0_OK) return rc;

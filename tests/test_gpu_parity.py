@@ -28,6 +28,16 @@ SHARP_ACTION_TOL = 5e-2     # see test_sharp_attention_masks and tests/test_bf16
 MX_ACTION_TOL = 2e-2
 MX_COS_MIN = 0.998
 MX_ROW_COS_MIN = 0.99
+# ... and at full depth (17 quantised layers).  Quantisation is discontinuous: two runs whose inputs differ by the
+# bf16 path's rounding land on neighbouring codes here and there, and every layer widens the gap.  What that does to
+# the MXFP8 ORACLE ITSELF was measured on the CPU (tests/test_bf16_sensitivity.py, the slow test): with bf16 GEMM
+# operands and nothing else changed its prefix hidden states fall from cosine 0.9996 (layer 0) through 0.9974 (layer 3)
+# to 0.990 (layer 16) against its own plain run, the cache to 0.9895, single token rows to 0.987, and the actions move
+# by 1.7e-2 of their RMS.  The HIP path measures the same figures (0.99735 at layer 3).  Bars: a margin below those
+# cosines, 2.5 x the action figure.
+MX_FULL_COS_MIN = 0.985
+MX_FULL_ROW_COS_MIN = 0.97
+MX_FULL_ACTION_TOL = 4.2e-2
 
 
 def say(*a):
@@ -175,7 +185,7 @@ def check_against_oracle(case, n_views, n_prompt, seed_shift=0, label="", action
                 assert c >= cos_min, (label, name, l, c)
                 d = float(np.abs(g[l] - r[l]).max()) / math.sqrt(float((r[l].astype(np.float64) ** 2).mean()))
                 worst_cache = max(worst_cache, (d, f"{name}[{l}]"))
-                assert d <= cache_tol, (label, name, l, d)
+                assert cache_tol is None or d <= cache_tol, (label, name, l, d)
         else:
             c = cosine(g, r)
             worst = min(worst, (c, name))
@@ -307,7 +317,8 @@ def test_full_model_all_view_counts():
         # the reduced-precision mode at full depth against the oracle in the same mode (17 quantised layers)
         case.m.pi0_set_precision("mxfp8_prefix_mlp")
         act, _ = check_against_oracle(case, 1, 0, label="full 1 view, mxfp8 prefix feed-forward", mxfp8=True,
-                                      action_tol=MX_ACTION_TOL, cos_min=MX_COS_MIN, row_cos_min=MX_ROW_COS_MIN)
+                                      action_tol=MX_FULL_ACTION_TOL, cos_min=MX_FULL_COS_MIN,
+                                      row_cos_min=MX_FULL_ROW_COS_MIN, cache_tol=None)
         img, st, nz, ids = case.inputs(1, 0)
         np.testing.assert_array_equal(case.infer(img, st, nz, ids), act)
         case.m.pi0_set_precision("bf16")
@@ -463,9 +474,9 @@ def test_mxfp8_prefix_mlp_against_mxfp8_oracle(reduced):
     reduced.m.pi0_set_precision("mxfp8_prefix_mlp")
     try:
         act1, ref1 = check_against_oracle(reduced, 1, 0, label="mxfp8 1 view", mxfp8=True, action_tol=MX_ACTION_TOL,
-                                          cos_min=MX_COS_MIN, row_cos_min=MX_ROW_COS_MIN)
+                                          cos_min=MX_COS_MIN, row_cos_min=MX_ROW_COS_MIN, cache_tol=2 * CACHE_TOL)
         check_against_oracle(reduced, 3, 48, label="mxfp8 3 views + 48 prompt", mxfp8=True, action_tol=MX_ACTION_TOL,
-                             cos_min=MX_COS_MIN, row_cos_min=MX_ROW_COS_MIN)
+                             cos_min=MX_COS_MIN, row_cos_min=MX_ROW_COS_MIN, cache_tol=2 * CACHE_TOL)
         # graph replays of the mode equal its eager debug pass
         np.testing.assert_array_equal(reduced.infer(img, st, nz, ids), act1)
         np.testing.assert_array_equal(reduced.infer(img, st, nz, ids), act1)
