@@ -241,9 +241,11 @@ def main() -> int:
         f"= {loop_gbps / 8000.0:.3f} of the HBM peak")
     # prefill kernels by template family (eager, event-bracketed launches)
     timing_h = m.pi0_debug_profile(images_of[hv], hv, None, 0, state, noise, actions, passes=3, stream=stream)
-    class_traffic = (traffic_prof or {}).get("by_views", {}).get(str(hv), {}).get("classes")
-    krows = [r for r in roofline.kernel_rooflines(work, timing_h, class_traffic, prefix_tokens=hv * cfg.tokens_per_view)
+    fam_traffic = (traffic_prof or {}).get("by_views", {}).get(str(hv), {}).get("families", {})
+    krows = [r for r in roofline.kernel_rooflines(work, timing_h, None, prefix_tokens=hv * cfg.tokens_per_view)
              if not any(c.startswith("exp_") for c in r["classes"])]
+    for r in krows:     # counter figure of the family: HBM-side bytes per launch, averaged over its launches of one pass
+        r["traffic"] = fam_traffic.get(r["kernel"], {}).get("bytes_per_launch")
     for r in krows:
         log("[bench] kernel %-22s launches %5d avg %8.2f us total %9.1f us  %s %.1f %s = %.3f of peak" % (
             r["kernel"], r["launches"], r["avg_us"], r["total_us"], r["bound"], r["achieved"], r["unit"], r["frac"]))

@@ -187,10 +187,12 @@ int pi0_sync_dep_bench(int barrier, int data, int fan, int n_ops, int reps, floa
 
 /*
  * Timeline of the persistent denoise kernel (Section 5.2: where the time between two software barriers goes).
- * With a buffer set, thread 0 of every block notes the 100 MHz wall clock four times per operation of the loop:
- * operation entered (its constant operands are requested next), inputs complete (the wait for the barrier of the
- * operation before is over; 0 if the block has no work item in this operation), body done, arrival announced.
- *   d_trace  device, int64 [ops_cap][256 blocks][4], 8-byte aligned; NULL with ops_cap 0 switches the timeline off
+ * With a buffer set, thread 0 of every block notes the 100 MHz wall clock per operation of the loop: [0] operation
+ * entered (its constant operands are requested next), [1] inputs complete (the wait for the barrier of the operation
+ * before is over; 0 if the block has no work item in this operation), [2] body done, [3] arrival announced, [4..7]
+ * points inside the body (0 where a body has none): GEMMs - products done, partial tiles in shared memory;
+ * attention - Q in shared memory, scores done, probabilities in shared memory, P V done.
+ *   d_trace  device, int64 [ops_cap][256 blocks][8], 8-byte aligned; NULL with ops_cap 0 switches the timeline off
  *   operations are numbered in execution order: 0 = state token; per Euler step: embed, second linear, per layer
  *   QKV, attention, O, gate||up, down; then out-projection + Euler.  pi0_loop_trace_ops gives their number.
  * Drops every captured graph.  Must not be called while work of this ctx is in flight.  Errors: EINVAL.

@@ -300,7 +300,7 @@ class Pi0:
         return int(lib().pi0_loop_trace_ops(self._ctx))
 
     def pi0_set_loop_trace(self, d_trace):
-        """d_trace: int64 CUDA tensor [ops, 256, 4] or None (off)."""
+        """d_trace: int64 CUDA tensor [ops, 256, 8] or None (off)."""
         self._check(lib().pi0_set_loop_trace(self._ctx, _ptr(d_trace), 0 if d_trace is None else int(d_trace.shape[0])))
 
     def pi0_set_graph_mode(self, enabled: bool):

@@ -118,6 +118,7 @@ __device__ __forceinline__ void attention_body(const AttnParams p, const Cx cx, 
     }
   }
   __syncthreads();
+  cx.mark(1);   // Q and the second segment's keys are in LDS
 
   // ---- phase 1: scores of this wave's chunks ------------------------------------------------
   float sv[MAXR][16];
@@ -201,6 +202,7 @@ __device__ __forceinline__ void attention_body(const AttnParams p, const Cx cx, 
   m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32, 64));
   if (lh == 0) mw[w * 32 + lq] = m_loc;
   __syncthreads();
+  cx.mark(2);   // scores done
   float m_all = NEG_BIG;
 #pragma unroll
   for (int i = 0; i < ATT_WAVES; i++) m_all = fmaxf(m_all, mw[i * 32 + lq]);
@@ -229,6 +231,7 @@ __device__ __forceinline__ void attention_body(const AttnParams p, const Cx cx, 
   l_loc += __shfl_xor(l_loc, 32, 64);
   if (lh == 0) lw[w * 32 + lq] = l_loc;
   __syncthreads();
+  cx.mark(3);   // probabilities in LDS
   if (!pv_wave) return;
 
   // ---- phase 2: this wave's 32-wide slice of the head dimension over all chunks --------------
@@ -279,6 +282,7 @@ __device__ __forceinline__ void attention_body(const AttnParams p, const Cx cx, 
 #pragma unroll
     for (int e = 0; e < 16; e++) o[e] += o1[e];
   }
+  cx.mark(4);   // P V done
   float l_all = 0.f;
 #pragma unroll
   for (int i = 0; i < ATT_WAVES; i++) l_all += lw[i * 32 + lq];

@@ -33,6 +33,7 @@ struct LaunchCtx {
   template <class T>
   __device__ __forceinline__ void st(T* p, const T& v) const { *p = v; }
   __device__ __forceinline__ void wait_inputs() const {}
+  __device__ __forceinline__ void mark(int) const {}
   __device__ __forceinline__ int tid() const { return (int)threadIdx.x; }
 };
 
@@ -176,6 +177,10 @@ struct PersistCtxT {
     else return ld(p);
   }
   __device__ __forceinline__ void wait_inputs() const { bar->wait(); }
+  // timeline sample k (1 .. 4) of the current operation, by thread 0, when a timeline is being recorded
+  __device__ __forceinline__ void mark(int k) const {
+    if (bar->trace != nullptr && thread == 0) bar->trace[2 + k] = (long long)wall_clock64();
+  }
   template <bool B>
   __device__ __forceinline__ PersistCtxT<B> as() const {
     PersistCtxT<B> c;

@@ -44,8 +44,9 @@ struct ExpertLoopParams {
   const char* arena;              // every buffer written by one block and read by another lies in [arena, arena + arena_bytes)
   unsigned arena_bytes;
   unsigned spin_limit;            // bound of one barrier wait, in polls
-  // optional timeline for measurements: [operation][block][4] wall-clock samples (100 MHz) taken by thread 0:
-  // operation entered, its inputs complete (wait over), body done, arrival announced; null = off
+  // optional timeline for measurements: [operation][block][8] wall-clock samples (100 MHz) taken by thread 0:
+  // operation entered, its inputs complete (wait over), body done, arrival announced, four points inside the body;
+  // null = off
   long long* trace;
   int trace_ops;                  // capacity in operations
 };

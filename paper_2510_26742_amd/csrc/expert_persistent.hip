@@ -56,18 +56,19 @@ __global__ __launch_bounds__(PK_THREADS) void expert_loop_kernel(const ExpertLoo
   long long* const trace = P.trace;
   const int trace_ops = P.trace_ops;
   int opi = 0;
-  // timeline: sample 0 at the start of an operation, 1 by the barrier when the wait ends, 2 after the body, 3 after arrive
+  // timeline, 8 samples per (operation, block): 0 at the start of an operation, 1 by the barrier when the wait ends,
+  // 2 after the body, 3 after arrive, 4 .. 7 by the body itself (cx.mark)
   auto op_begin = [&]() {
     if (trace != nullptr && opi < trace_ops) {
-      long long* slot = trace + ((size_t)opi * gridDim.x + blockIdx.x) * 4;
+      long long* slot = trace + ((size_t)opi * gridDim.x + blockIdx.x) * 8;
       bar.trace = slot + 1;
-      if (threadIdx.x == 0) { slot[0] = (long long)wall_clock64(); slot[1] = 0; }
+      if (threadIdx.x == 0) { slot[0] = (long long)wall_clock64(); slot[1] = slot[4] = slot[5] = slot[6] = slot[7] = 0; }
     } else {
       bar.trace = nullptr;
     }
   };
   auto op_end = [&]() {
-    long long* slot = trace != nullptr && opi < trace_ops ? trace + ((size_t)opi * gridDim.x + blockIdx.x) * 4 : nullptr;
+    long long* slot = trace != nullptr && opi < trace_ops ? trace + ((size_t)opi * gridDim.x + blockIdx.x) * 8 : nullptr;
     if (slot != nullptr && threadIdx.x == 0) slot[2] = (long long)wall_clock64();
     bar.trace = nullptr;
     bar.arrive();
@@ -177,7 +178,10 @@ __global__ __launch_bounds__(PK_THREADS) void expert_loop_kernel(const ExpertLoo
         g.X = reinterpret_cast<const bf16*>(slot + F.r_yb_o);
         g.rowstat = reinterpret_cast<const float*>(slot + F.r_st_o);
         g.out_bf16 = reinterpret_cast<bf16*>(slot + F.r_mid);
-        for_items(g.n_tiles, [&](int it) { gemm_skinny_body<PRO_RMS, EPI_GEGLU, 0>(g, item(it, 0, 0).template as<true>(), smem_raw); });
+        // two feature tiles x one token block per item: the same sums as one tile x both token blocks, half the
+        // activation bytes per block behind the wait
+        const int pairs = g.n_tiles / 2;
+        for_items(pairs * 2, [&](int it) { gemm_skinny_body<PRO_RMS, EPI_GEGLU, 2>(g, item(it % pairs, 0, it / pairs).template as<true>(), smem_raw); });
         op_end();
       }
       op_begin();
@@ -251,6 +255,7 @@ hipError_t launch_expert_loop(hipStream_t s, const ExpertLoopParams& P, ExpertLo
   for (const GemmParams* g : sk) {
     if (g->k_per_split != g->W.k_pad || g->W.k_pad > SK_KMAX || g->m_tiles != 1) return hipErrorInvalidValue;
   }
+  if (P.gu.n_tiles % 2 != 0 || P.gu.M <= 32) return hipErrorInvalidValue;   // gate||up: pairs of feature tiles, two token blocks
   if (P.qkv.rowstat == nullptr || P.gu.rowstat == nullptr || P.outp.rowstat == nullptr) return hipErrorInvalidValue;
   if (P.parts_first < 1 || P.parts_first > 8 * SK_WAVES || P.parts_rest < 1 || P.parts_rest > 8 * SK_WAVES) return hipErrorInvalidValue;
   if (P.gu.rowstat_parts < 1 || P.gu.rowstat_parts > 8 * SK_WAVES || P.outp.rowstat_parts < 1 || P.outp.rowstat_parts > 8 * SK_WAVES)

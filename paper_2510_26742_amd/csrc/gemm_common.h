@@ -263,7 +263,7 @@ __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16&
 // Steps I0 .. I1-1 of one token block's tile: the 8 waves' partial tiles [wave][token block][step][lane][4] are
 // added in wave order, then the epilogue runs on those steps.
 template <int PRO, int EPI, int I0, int I1, class Cx>
-__device__ __forceinline__ void skinny_finish(const GemmParams& p, const float* red, int mb, int lane, int nt, int ml, int lh,
+__device__ __forceinline__ void skinny_finish(const GemmParams& p, const float* red, int mb /* slot */, int lane, int nt, int ml, int lh,
                                               float ssum, float ssq, const EpiOps& ops, const Cx& cx) {
   f32x16 sum;
 #pragma unroll
@@ -296,8 +296,13 @@ __device__ __forceinline__ void skinny_preload(const GemmParams& p, int nt, int 
 
 template <int PRO, int EPI, int MS, class Cx>
 __device__ __forceinline__ void gemm_skinny_body(const GemmParams p, const Cx cx, unsigned char* smem_raw) {
-  constexpr int NMB = MS ? 1 : 2;              // token blocks per block
-  float* red = reinterpret_cast<float*>(smem_raw);                 // [8 waves][2][16][64]
+  // MS = 0: one feature tile, both token blocks; 1: one feature tile, one token block (cx.bz); 2: two adjacent feature
+  // tiles (2 cx.bx, 2 cx.bx + 1), one token block (cx.bz) - half the activation bytes of MS = 0 behind the wait of a
+  // persistent kernel, where the weights have been requested before it.  A "slot" is a (token block, tile) of the block.
+  constexpr int NMB = MS == 0 ? 2 : 1;         // token blocks per block
+  constexpr int NTL = MS == 2 ? 2 : 1;         // feature tiles per block
+  constexpr int NSLOT = NMB * NTL;
+  float* red = reinterpret_cast<float*>(smem_raw);                 // [8 waves][2 slots][16][64]
   const int t = cx.tid();
   const int lane = t & 63;
   const int w = t >> 6;
@@ -311,7 +316,7 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmParams p, const Cx cx
     if (p.progress != nullptr && t == 0 && cx.bx == 0 && cx.by == 0 && cx.bz == 0)
       __hip_atomic_store(p.progress, p.progress_value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
-  const int nt = cx.bx;
+  const int nt = NTL * cx.bx;   // first feature tile of the block
   const int k_pad = p.W.k_pad;
   const int kbeg = cx.by * p.k_per_split;
   const int kend = min(kbeg + p.k_per_split, k_pad);
@@ -322,8 +327,8 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmParams p, const Cx cx
   // row statistics of the input: parts partial sums per row (1, or one per 32-column tile of the
   // producer); wave w adds parts w, w+8, ... for row `lane`, the epilogue adds the 8 wave sums
   float* sstat8 = red + SK_WAVES * 2 * 16 * 64 + 128;   // [8 waves][64][2]
-  bf16x8 wf[8], xf[NMB][8];
-  const bf16* wbase = p.W.w + ((size_t)nt * KC16 + (kbeg >> 4)) * 512 + lane * 8;
+  bf16x8 wf[NTL][8], xf[NMB][8];
+  const bf16* wbase = p.W.w + ((size_t)nt * KC16 + (kbeg >> 4)) * 512 + lane * 8;   // tile j: + j * KC16 * 512
   const bf16* xbase = p.X + (size_t)(kbeg >> 4) * 512 + lane * 8;
   const int mb_last = p.M > 32 ? 1 : 0;        // last token block (clamps when M <= 32)
   const int mb_first = MS ? min(cx.bz, mb_last) : 0;   // global index of local token block 0
@@ -332,19 +337,22 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmParams p, const Cx cx
   // epilogue arithmetic are the tail of the launch, and one wave alone took 3.8 k cycles over them for the QKV
   // epilogue (2.2 k for GeGLU)
   constexpr int PIECES = EPI == EPI_QKV ? 4 : EPI == EPI_GEGLU ? 2 : 1;
-  constexpr int NFIN = NMB * PIECES;
+  constexpr int NFIN = NSLOT * PIECES;
   static_assert(NFIN <= SK_WAVES, "finishing waves");
   EpiOps ops;
-  const int fmb = w / PIECES, fpc = w % PIECES;
+  const int fslot = w / PIECES, fpc = w % PIECES;   // finishing wave f: slot f / PIECES, piece f % PIECES
+  const int fmb = NTL == 1 ? fslot : 0;             // its token block (local) ...
+  const int fnt = nt + (NTL == 1 ? 0 : fslot);      // ... and feature tile
   const int mrow = (mb_first + fmb) * 32 + lq;   // the row this lane finishes if w < NFIN
   if (Cx::kPersistent) {
     // constants first (weights, then the epilogue's vectors); the inputs are requested once they exist
 #pragma unroll
     for (int i = 0; i < 8; i++) {
       const int st = min(w * 8 + i, n16 - 1);
-      wf[i] = *reinterpret_cast<const bf16x8*>(wbase + (size_t)st * 512);
+#pragma unroll
+      for (int j = 0; j < NTL; j++) wf[j][i] = *reinterpret_cast<const bf16x8*>(wbase + ((size_t)j * KC16 + st) * 512);
     }
-    if (w < NFIN && mrow < p.M) skinny_preload<PRO, EPI, PIECES, 0>(p, nt, mrow, lh, fpc, ops, cx);
+    if (w < NFIN && mrow < p.M) skinny_preload<PRO, EPI, PIECES, 0>(p, fnt, mrow, lh, fpc, ops, cx);
     cx.wait_inputs();
   }
   // statistics partials: issued ahead of the operand loads (same round trip), clamped and unconditional
@@ -359,35 +367,40 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmParams p, const Cx cx
 #pragma unroll
   for (int i = 0; i < 8; i++) {
     const int st = min(w * 8 + i, n16 - 1);    // clamped: steps beyond the range are never used
-    if (!Cx::kPersistent) wf[i] = *reinterpret_cast<const bf16x8*>(wbase + (size_t)st * 512);
+    if (!Cx::kPersistent) {
+#pragma unroll
+      for (int j = 0; j < NTL; j++) wf[j][i] = *reinterpret_cast<const bf16x8*>(wbase + ((size_t)j * KC16 + st) * 512);
+    }
 #pragma unroll
     for (int mb = 0; mb < NMB; mb++)
       xf[mb][i] = cx.ld_bulk(reinterpret_cast<const bf16x8*>(xbase + ((size_t)min(mb_first + mb, mb_last) * XKC16 + st) * 512));
   }
   // operands of the epilogue, in the same round trip
   if (w < NFIN && mrow < p.M) {
-    if (Cx::kPersistent) skinny_preload<PRO, EPI, PIECES, 1>(p, nt, mrow, lh, fpc, ops, cx);
-    else skinny_preload<PRO, EPI, PIECES, 2>(p, nt, mrow, lh, fpc, ops, cx);
+    if (Cx::kPersistent) skinny_preload<PRO, EPI, PIECES, 1>(p, fnt, mrow, lh, fpc, ops, cx);
+    else skinny_preload<PRO, EPI, PIECES, 2>(p, fnt, mrow, lh, fpc, ops, cx);
   }
-  f32x16 acc[NMB];
+  f32x16 acc[NSLOT];   // slot = token block (NTL == 1) or feature tile (NTL == 2)
 #pragma unroll
-  for (int mb = 0; mb < NMB; mb++)
+  for (int sl = 0; sl < NSLOT; sl++)
 #pragma unroll
-    for (int r = 0; r < 16; r++) acc[mb][r] = 0.f;
+    for (int r = 0; r < 16; r++) acc[sl][r] = 0.f;
 #pragma unroll
   for (int i = 0; i < 8; i++) {
     if (w * 8 + i < n16) {
 #pragma unroll
-      for (int mb = 0; mb < NMB; mb++) acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[mb][i], acc[mb], 0, 0, 0);
+      for (int sl = 0; sl < NSLOT; sl++)
+        acc[sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[NTL == 1 ? 0 : sl][i], xf[NTL == 1 ? sl : 0][i], acc[sl], 0, 0, 0);
     }
   }
 #pragma unroll
-  for (int mb = 0; mb < NMB; mb++)
+  for (int sl = 0; sl < NSLOT; sl++)
 #pragma unroll
-    for (int q = 0; q < 4; q++) {   // 16-byte pieces: [wave][token block][q][lane][4]
-      const f32x4 v4 = {acc[mb][4 * q], acc[mb][4 * q + 1], acc[mb][4 * q + 2], acc[mb][4 * q + 3]};
-      *reinterpret_cast<f32x4*>(red + ((((size_t)w * 2 + mb) * 4 + q) * 64 + lane) * 4) = v4;
+    for (int q = 0; q < 4; q++) {   // 16-byte pieces: [wave][slot][q][lane][4]
+      const f32x4 v4 = {acc[sl][4 * q], acc[sl][4 * q + 1], acc[sl][4 * q + 2], acc[sl][4 * q + 3]};
+      *reinterpret_cast<f32x4*>(red + ((((size_t)w * 2 + sl) * 4 + q) * 64 + lane) * 4) = v4;
     }
+  cx.mark(1);   // operands arrived, products done
   if (PRO != PRO_NONE) {
     float pa = 0.f, pb = 0.f;
 #pragma unroll
@@ -401,6 +414,7 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmParams p, const Cx cx
     sstat8[(w * 64 + lane) * 2 + 1] = pb;
   }
   __syncthreads();
+  cx.mark(2);   // partial tiles of all waves in LDS
   if (w >= NFIN) return;
   if (MS && cx.bz > mb_last) return;   // M <= 32: the second block of a split launch has nothing to store
   const int ml = mrow;
@@ -412,15 +426,15 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmParams p, const Cx cx
       ssq += sstat8[(ww * 64 + ml) * 2 + 1];
     }
   }
-  if constexpr (PIECES == 1) skinny_finish<PRO, EPI, 0, 4>(p, red, fmb, lane, nt, ml, lh, ssum, ssq, ops, cx);
+  if constexpr (PIECES == 1) skinny_finish<PRO, EPI, 0, 4>(p, red, fslot, lane, fnt, ml, lh, ssum, ssq, ops, cx);
   else if constexpr (PIECES == 2) {
-    if (fpc == 0) skinny_finish<PRO, EPI, 0, 2>(p, red, fmb, lane, nt, ml, lh, ssum, ssq, ops, cx);
-    else skinny_finish<PRO, EPI, 2, 4>(p, red, fmb, lane, nt, ml, lh, ssum, ssq, ops, cx);
+    if (fpc == 0) skinny_finish<PRO, EPI, 0, 2>(p, red, fslot, lane, fnt, ml, lh, ssum, ssq, ops, cx);
+    else skinny_finish<PRO, EPI, 2, 4>(p, red, fslot, lane, fnt, ml, lh, ssum, ssq, ops, cx);
   } else {
-    if (fpc == 0) skinny_finish<PRO, EPI, 0, 1>(p, red, fmb, lane, nt, ml, lh, ssum, ssq, ops, cx);
-    else if (fpc == 1) skinny_finish<PRO, EPI, 1, 2>(p, red, fmb, lane, nt, ml, lh, ssum, ssq, ops, cx);
-    else if (fpc == 2) skinny_finish<PRO, EPI, 2, 3>(p, red, fmb, lane, nt, ml, lh, ssum, ssq, ops, cx);
-    else skinny_finish<PRO, EPI, 3, 4>(p, red, fmb, lane, nt, ml, lh, ssum, ssq, ops, cx);
+    if (fpc == 0) skinny_finish<PRO, EPI, 0, 1>(p, red, fslot, lane, fnt, ml, lh, ssum, ssq, ops, cx);
+    else if (fpc == 1) skinny_finish<PRO, EPI, 1, 2>(p, red, fslot, lane, fnt, ml, lh, ssum, ssq, ops, cx);
+    else if (fpc == 2) skinny_finish<PRO, EPI, 2, 3>(p, red, fslot, lane, fnt, ml, lh, ssum, ssq, ops, cx);
+    else skinny_finish<PRO, EPI, 3, 4>(p, red, fslot, lane, fnt, ml, lh, ssum, ssq, ops, cx);
   }
 }
 
