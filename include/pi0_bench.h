@@ -211,6 +211,24 @@ int pi0_set_loop_trace(pi0_ctx* ctx, long long* d_trace, int ops_cap);
  */
 int pi0_tune(pi0_ctx* ctx, const char* spec);
 
+/* Attention kernels on operands in natural order (Table 2: the attention rows of the vision encoder, the prefix and
+ * the action expert).  A test entry: it allocates and frees staging buffers and synchronises the stream.
+ * All pointers are device memory, fp32; values are rounded to bf16 on entry.
+ *   d_q  [heads][Tq][head_dim]        d_k0, d_v0 [kv_heads][n0][head_dim]      d_k1, d_v1 [1][n1][head_dim] or NULL
+ *   d_out [shares][Tq][heads * head_dim]            d_ml [shares][heads][ceil32(Tq)][2] (only written if shares > 1)
+ * kv_heads is heads or 1 (shared head); head_dim is 256 or 68 .. 80; n1 is 0 or 64 (needs kv_heads == 1, head_dim
+ * 256).  view_tokens > 0: query row m sees the keys of its own view only (needs n0 == Tq).  suffix_mask = 1: row 0
+ * sees all of segment 0 and key 0 of segment 1, the other rows see everything.  chunks_per_share > 0 and
+ * ceil(n0 / 32) > chunks_per_share: the keys of segment 0 are shared out over shares = ceil(ceil(n0 / 32) /
+ * chunks_per_share) blocks (segment 1 goes with the last); share z returns its own normalised output and, in d_ml,
+ * (row maximum of the scaled logits, sum of exponentials relative to it), which the consumer merges as
+ * sum_z c_z out_z, c_z = l_z exp(m_z - max m) / sum.  v_split: 0, or 2 / 4 / 8 blocks per (query tile, head) with a
+ * part of the value slices each (head_dim 256).  Unsupported combinations return PI0_EINVAL. */
+int pi0_attention_probe(int heads, int kv_heads, int head_dim, int Tq, int n0, int n1, int view_tokens,
+                        int suffix_mask, int chunks_per_share, int v_split, float scale, const float* d_q,
+                        const float* d_k0, const float* d_v0, const float* d_k1, const float* d_v1, float* d_out,
+                        float* d_ml, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libpi0_hip.so")
 EXPORTS = ["pi0_create", "pi0_destroy", "pi0_weights_bytes", "pi0_workspace_bytes", "pi0_load_weights",
            "pi0_prefill", "pi0_denoise", "pi0_denoise_static", "pi0_infer", "pi0_debug_taps_elems", "pi0_debug_forward", "pi0_debug_profile", "pi0_sync_bench", "pi0_peak_bench", "pi0_clock_sample", "pi0_read_ahead_probe", "pi0_stream_frame",
            "pi0_set_graph_mode", "pi0_set_precision", "pi0_kernel_count", "pi0_strerror", "pi0_last_hip_error",
-           "pi0_sync_dep_bench", "pi0_tune", "pi0_device_status", "pi0_loop_trace_ops", "pi0_set_loop_trace"]
+           "pi0_sync_dep_bench", "pi0_tune", "pi0_device_status", "pi0_loop_trace_ops", "pi0_set_loop_trace", "pi0_attention_probe"]
 
 # enum pi0_op_class, in order
 OP_CLASSES = ["misc", "vis_patch", "vis_qkv", "vis_attn", "vis_o", "vis_up", "vis_down", "vis_proj", "reduce",
@@ -82,6 +82,8 @@ def lib() -> ctypes.CDLL:
         L.pi0_sync_bench.restype = i32
         L.pi0_sync_dep_bench.argtypes = [i32, i32, i32, i32, i32, vp, i32, vp, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.pi0_sync_dep_bench.restype = i32
+        L.pi0_attention_probe.argtypes = [i32] * 10 + [ctypes.c_float] + [vp] * 8
+        L.pi0_attention_probe.restype = i32
         L.pi0_device_status.argtypes = [vp, vp]
         L.pi0_device_status.restype = i32
         L.pi0_loop_trace_ops.argtypes = [vp]
@@ -164,6 +166,28 @@ def pi0_sync_dep_bench(barrier: str, data: str, fan: int, n_ops: int, reps: int,
     if rc != PI0_OK:
         raise Pi0Error(rc)
     return float(ms.value)
+
+
+def pi0_attention_probe(q, k0, v0, k1=None, v1=None, *, view_tokens=0, suffix_mask=False, chunks_per_share=0, v_split=0,
+                        scale=None, stream=None):
+    """Attention kernels of the pass on fp32 device tensors in natural order: q [H, Tq, d], k0 / v0 [Hk, n0, d],
+    k1 / v1 [1, 64, d] or None.  Returns (out [shares, Tq, H * d], ml [shares, H, ceil32(Tq), 2] or None)."""
+    import torch
+    H, Tq, d = q.shape
+    Hk, n0, _ = k0.shape
+    n1 = 0 if k1 is None else int(k1.shape[1])
+    c0 = (n0 + 31) // 32
+    shares = -(-c0 // chunks_per_share) if chunks_per_share > 0 and c0 > chunks_per_share else 1
+    out = torch.empty((shares, Tq, H * d), dtype=torch.float32, device=q.device)
+    ml = torch.empty((shares, H, (Tq + 31) // 32 * 32, 2), dtype=torch.float32, device=q.device) if shares > 1 else None
+    ts = [t.contiguous() if t is not None else None for t in (q, k0, v0, k1, v1)]
+    s = None if stream is None else int(stream.cuda_stream)
+    rc = lib().pi0_attention_probe(H, Hk, d, Tq, n0, n1, int(view_tokens), int(bool(suffix_mask)), int(chunks_per_share),
+                                   int(v_split), float(d ** -0.5 if scale is None else scale),
+                                   *[None if t is None else _ptr(t) for t in ts], _ptr(out), None if ml is None else _ptr(ml), s)
+    if rc != PI0_OK:
+        raise Pi0Error(rc)
+    return out, ml
 
 
 def pi0_clock_sample(d_out, stream=None):

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpi0_hip.so")
-SOURCES = ["gemm.hip", "attention.hip", "pack_misc.hip", "pi0_api.hip", "sync_bench.hip", "sync_dep_bench.hip", "expert_persistent.hip", "peak_bench.hip", "gemm_mx.hip"]
+SOURCES = ["gemm.hip", "attention.hip", "pack_misc.hip", "pi0_api.hip", "sync_bench.hip", "sync_dep_bench.hip", "expert_persistent.hip", "attention_probe.hip", "peak_bench.hip", "gemm_mx.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function"]
