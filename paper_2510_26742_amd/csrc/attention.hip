@@ -24,25 +24,25 @@
 
 #include "attention_body.h"
 
-template <int DQK, int NVB, int MAXR, int VRING>
+template <int DQK, int NVB, int MAXR, int VRING, int CPW>
 __global__ __launch_bounds__(512) void attention_kernel(AttnParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  attention_body<DQK, NVB, MAXR, VRING>(p, LaunchCtx::from_block_idx(), smem_raw);
+  attention_body<DQK, NVB, MAXR, VRING, CPW>(p, LaunchCtx::from_block_idx(), smem_raw);
 }
 
 template <int DQK>
 static int attn_smem(int ntot) { return 3 * (DQK / 16) * 1024 + 2 * ATT_WAVES * 32 * 4 + ntot * 2048; }
 
 #define ATTN_VARIANTS(X) \
-  X(256, 8, 1, 8)        \
-  X(256, 8, 2, 8)        \
-  X(256, 8, 4, 8)        \
-  X(80, 3, 1, 8)
+  X(256, 8, 1, 8, 10)    \
+  X(256, 8, 2, 8, 0)     \
+  X(256, 8, 4, 8, 0)     \
+  X(80, 3, 1, 8, 0)
 
 hipError_t attention_init_attributes() {
-#define X(DQK, NVB, MAXR, VRING)                                                                              \
+#define X(DQK, NVB, MAXR, VRING, CPW)                                                                              \
   {                                                                                                           \
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_kernel<DQK, NVB, MAXR, VRING>), \
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_kernel<DQK, NVB, MAXR, VRING, CPW>), \
                                        hipFuncAttributeMaxDynamicSharedMemorySize, attn_smem<DQK>(8 * MAXR + 2)); \
     if (e != hipSuccess) return e;                                                                            \
   }
@@ -87,12 +87,12 @@ hipError_t launch_attention(hipStream_t s, const AttnParams& p) {
     grid.y += d.blocks / grid.x;
   }
   if (p.head_dim == 256) {
-    if (n0 <= 8) attention_kernel<256, 8, 1, 8><<<grid, dim3(512), attn_smem<256>(ntot), s>>>(p);
-    else if (n0 <= 16) attention_kernel<256, 8, 2, 8><<<grid, dim3(512), attn_smem<256>(ntot), s>>>(p);
-    else attention_kernel<256, 8, 4, 8><<<grid, dim3(512), attn_smem<256>(ntot), s>>>(p);
+    if (n0 <= 8) attention_kernel<256, 8, 1, 8, 10><<<grid, dim3(512), attn_smem<256>(ntot), s>>>(p);
+    else if (n0 <= 16) attention_kernel<256, 8, 2, 8, 0><<<grid, dim3(512), attn_smem<256>(ntot), s>>>(p);
+    else attention_kernel<256, 8, 4, 8, 0><<<grid, dim3(512), attn_smem<256>(ntot), s>>>(p);
   } else if (p.head_dim <= 80 && p.head_dim > 64) {
     if (n0 > 8 || p.chunks1 != 0) return hipErrorInvalidValue;
-    attention_kernel<80, 3, 1, 8><<<grid, dim3(512), attn_smem<80>(ntot), s>>>(p);
+    attention_kernel<80, 3, 1, 8, 0><<<grid, dim3(512), attn_smem<80>(ntot), s>>>(p);
   } else {
     return hipErrorInvalidValue;
   }

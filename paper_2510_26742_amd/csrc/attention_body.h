@@ -9,9 +9,16 @@
 
 // MAXR: key rounds per wave over segment 0 (8 * MAXR chunks = 256 * MAXR keys); VRING: value
 // chunks in flight per wave.
-template <int DQK, int NVB, int MAXR, int VRING, class Cx>
+// CPW > 0 (needs MAXR == 1 and NVB == 8): phase 2 is shared out over all 8 waves instead of one wave per value slice.
+// With nslice value slices in the block, the waves form G = 8 / nslice groups; wave (slice, group g) multiplies the
+// chunks g, g + G, ... of [segment 0 ; segment 1] (at most CPW of them, held in registers: no ring, no second round
+// trip), the G partial outputs of a slice meet in LDS and are added in group order.  The dependent chain of a wave
+// drops from 2 x (all chunks) to 2 x CPW products.
+template <int DQK, int NVB, int MAXR, int VRING, int CPW, class Cx>
 __device__ __forceinline__ void attention_body(const AttnParams p, const Cx cx, unsigned char* smem_raw) {
   constexpr int S16 = DQK / 16;
+  constexpr bool PVG = CPW > 0;
+  static_assert(!PVG || (MAXR == 1 && NVB == ATT_WAVES), "chunk groups: one key round, 8 value slices");
   constexpr bool DUAL = MAXR == 1;             // second accumulators (register room permitting)
   constexpr int QB = (MAXR == 1 && S16 % 8 == 0) ? 8 : 1;   // Q fragments read from LDS per batch (register room permitting)
   constexpr int NPQ = 32 * DQK / 8;            // 16-byte pieces of the Q tile
@@ -41,7 +48,9 @@ __device__ __forceinline__ void attention_body(const AttnParams p, const Cx cx, 
   const int tile = cx.bx / vs;
   const int vpart = cx.bx - tile * vs;
   const int nslice = NVB / vs;                 // value slices (waves of phase 2) of this block
-  const int slice = vpart * nslice + w;        // the slice wave w < nslice accumulates
+  const int pv_groups = PVG ? ATT_WAVES / nslice : 1;   // G
+  const int pv_g = PVG ? w / nslice : 0;                // this wave's group
+  const int slice = vpart * nslice + (PVG ? w - pv_g * nslice : w);   // the slice this wave accumulates
   const int head = cx.by;
   const int row = tile * 32 + lq;
   const bool row_ok = row < p.Tq;
@@ -69,14 +78,21 @@ __device__ __forceinline__ void attention_body(const AttnParams p, const Cx cx, 
   bf16x8 qreg[QP];
   bf16x8 k1reg[KP1];
   bf16x8 kf[S16];
-  bf16x8 vf[VRING * 2];      // ring over the chunks of segment 0
-  bf16x8 vs1[4];             // the (at most two) chunks of segment 1
-  const bool pv_wave = w < nslice;
+  bf16x8 vf[PVG ? CPW * 2 : VRING * 2];      // ring over the chunks of segment 0 (chunk groups: this wave's chunks)
+  bf16x8 vs1[PVG ? 1 : 4];                   // the (at most two) chunks of segment 1 (chunk groups: they are in vf)
+  const bool pv_wave = PVG ? true : w < nslice;
   auto load_seg0 = [&]() {
     const bf16* kp0 = kbase0 + (size_t)min(w, n0 - 1) * S16 * 512;
 #pragma unroll
     for (int s = 0; s < S16; s++) kf[s] = *reinterpret_cast<const bf16x8*>(kp0 + (size_t)s * 512);
-    if (pv_wave) {
+    if (PVG) {
+#pragma unroll
+      for (int j = 0; j < (PVG ? CPW : 0); j++) {   // chunks beyond segment 0: a valid address, replaced or unused later
+        const bf16* vp = vslice0 + (size_t)min(pv_g + j * pv_groups, n0 - 1) * NVB * 1024;
+        vf[2 * j] = *reinterpret_cast<const bf16x8*>(vp);
+        vf[2 * j + 1] = *reinterpret_cast<const bf16x8*>(vp + 512);
+      }
+    } else if (pv_wave) {
 #pragma unroll
       for (int c = 0; c < VRING; c++) {
         const bf16* vp = vslice0 + (size_t)min(c, n0 - 1) * NVB * 1024;
@@ -95,7 +111,7 @@ __device__ __forceinline__ void attention_body(const AttnParams p, const Cx cx, 
 #pragma unroll
     for (int i = 0; i < KP1; i++)
       k1reg[i] = cx.ld_bulk(reinterpret_cast<const bf16x8*>(p.k1 + (size_t)min(t + i * 512, n1 * S16 * 64 - 1) * 8));
-    if (pv_wave) {
+    if (!PVG && pv_wave) {
 #pragma unroll
       for (int c = 0; c < 2; c++) {
         const bf16* vp = p.v1 + (size_t)min(c, n1 - 1) * NVB * 1024 + slice * 1024 + lane * 8;
@@ -105,6 +121,17 @@ __device__ __forceinline__ void attention_body(const AttnParams p, const Cx cx, 
     }
   }
   if (!Cx::kPersistent) load_seg0();
+  if (PVG && n1 > 0) {   // this wave's chunks that fall into segment 1 (after load_seg0, whose placeholders they replace)
+#pragma unroll
+    for (int j = 0; j < (PVG ? CPW : 0); j++) {
+      const int c = pv_g + j * pv_groups - n0;
+      if (c >= 0 && c < n1) {
+        const bf16* vp = p.v1 + (size_t)c * NVB * 1024 + slice * 1024 + lane * 8;
+        vf[2 * j] = cx.ld_bulk(reinterpret_cast<const bf16x8*>(vp));
+        vf[2 * j + 1] = cx.ld_bulk(reinterpret_cast<const bf16x8*>(vp + 512));
+      }
+    }
+  }
 #pragma unroll
   for (int i = 0; i < QP; i++) {
     const int pc = t + i * 512;
@@ -243,38 +270,56 @@ __device__ __forceinline__ void attention_body(const AttnParams p, const Cx cx, 
   // fragments of the next round are requested (whole round, one uniform branch) as the registers
   // of this round are consumed.  Then the chunks of segment 1, whose value fragments came with Q.
   const bf16x8 zero8v = {(bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f};
-  for (int c0 = 0; c0 < n0; c0 += VRING) {
-    bf16x8 bp[2 * VRING];
+  if (PVG) {
+    const int ntot = n0 + n1;
+    bf16x8 bpg[PVG ? 2 * CPW : 1];   // the probability fragments of this wave's chunks, read together (clamped, unconditional)
 #pragma unroll
-    for (int cc = 0; cc < VRING; cc++) {
-      const int c = min(c0 + cc, n0 - 1);
-#pragma unroll
-      for (int s2 = 0; s2 < 2; s2++)
-        bp[2 * cc + s2] = *reinterpret_cast<const bf16x8*>(pf + ((size_t)(c * 2 + s2) * 64 + lane) * 8);
+    for (int j = 0; j < (PVG ? CPW : 0); j++) {
+      const int c = min(pv_g + j * pv_groups, ntot - 1);
+      bpg[2 * j] = *reinterpret_cast<const bf16x8*>(pf + ((size_t)(c * 2) * 64 + lane) * 8);
+      bpg[2 * j + 1] = *reinterpret_cast<const bf16x8*>(pf + ((size_t)(c * 2 + 1) * 64 + lane) * 8);
     }
-    const bool more_round = c0 + VRING < n0;
 #pragma unroll
-    for (int cc = 0; cc < VRING; cc++) {
-      const bool live = c0 + cc < n0;
-#pragma unroll
-      for (int s2 = 0; s2 < 2; s2++) {
-        const bf16x8 a = vf[2 * cc + s2];
-        if (more_round) vf[2 * cc + s2] = *reinterpret_cast<const bf16x8*>(vslice0 + (size_t)min(c0 + cc + VRING, n0 - 1) * NVB * 1024 + (size_t)s2 * 512);
-        if (DUAL && s2) o1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, live ? bp[2 * cc + s2] : zero8v, o1, 0, 0, 0);
-        else o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, live ? bp[2 * cc + s2] : zero8v, o, 0, 0, 0);
+    for (int j = 0; j < (PVG ? CPW : 0); j++) {
+      if (pv_g + j * pv_groups < ntot) {   // uniform per wave
+        o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[2 * j], bpg[2 * j], o, 0, 0, 0);
+        o1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[2 * j + 1], bpg[2 * j + 1], o1, 0, 0, 0);
       }
     }
-  }
-  if (n1 > 0) {
-#pragma unroll
-    for (int cc = 0; cc < 2; cc++) {
-      const bool live = cc < n1;
-      const int c = n0 + min(cc, n1 - 1);
-#pragma unroll
-      for (int s2 = 0; s2 < 2; s2++) {
-        const bf16x8 bpv = *reinterpret_cast<const bf16x8*>(pf + ((size_t)(c * 2 + s2) * 64 + lane) * 8);
-        if (DUAL && s2) o1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vs1[2 * cc + s2], live ? bpv : zero8v, o1, 0, 0, 0);
-        else o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vs1[2 * cc + s2], live ? bpv : zero8v, o, 0, 0, 0);
+  } else {
+    for (int c0 = 0; c0 < n0; c0 += VRING) {
+      bf16x8 bp[2 * VRING];
+  #pragma unroll
+      for (int cc = 0; cc < VRING; cc++) {
+        const int c = min(c0 + cc, n0 - 1);
+  #pragma unroll
+        for (int s2 = 0; s2 < 2; s2++)
+          bp[2 * cc + s2] = *reinterpret_cast<const bf16x8*>(pf + ((size_t)(c * 2 + s2) * 64 + lane) * 8);
+      }
+      const bool more_round = c0 + VRING < n0;
+  #pragma unroll
+      for (int cc = 0; cc < VRING; cc++) {
+        const bool live = c0 + cc < n0;
+  #pragma unroll
+        for (int s2 = 0; s2 < 2; s2++) {
+          const bf16x8 a = vf[2 * cc + s2];
+          if (more_round) vf[2 * cc + s2] = *reinterpret_cast<const bf16x8*>(vslice0 + (size_t)min(c0 + cc + VRING, n0 - 1) * NVB * 1024 + (size_t)s2 * 512);
+          if (DUAL && s2) o1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, live ? bp[2 * cc + s2] : zero8v, o1, 0, 0, 0);
+          else o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, live ? bp[2 * cc + s2] : zero8v, o, 0, 0, 0);
+        }
+      }
+    }
+    if (n1 > 0) {
+  #pragma unroll
+      for (int cc = 0; cc < 2; cc++) {
+        const bool live = cc < n1;
+        const int c = n0 + min(cc, n1 - 1);
+  #pragma unroll
+        for (int s2 = 0; s2 < 2; s2++) {
+          const bf16x8 bpv = *reinterpret_cast<const bf16x8*>(pf + ((size_t)(c * 2 + s2) * 64 + lane) * 8);
+          if (DUAL && s2) o1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vs1[2 * cc + s2], live ? bpv : zero8v, o1, 0, 0, 0);
+          else o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vs1[2 * cc + s2], live ? bpv : zero8v, o, 0, 0, 0);
+        }
       }
     }
   }
@@ -287,6 +332,30 @@ __device__ __forceinline__ void attention_body(const AttnParams p, const Cx cx, 
 #pragma unroll
   for (int i = 0; i < ATT_WAVES; i++) l_all += lw[i * 32 + lq];
   const float inv = 1.0f / l_all;
+  if (PVG && pv_groups > 1) {
+    // the groups' partial outputs meet in LDS (over Q and the keys of segment 1, which phase 1 is done with):
+    // [wave][4][64][4] floats; wave (slice, g) then finishes the pieces i = g, g + G, .. of its slice
+    float* red = reinterpret_cast<float*>(smem_raw);
+    static_assert(3 * S16 * 1024 >= ATT_WAVES * 4096 || !PVG, "partial outputs fit over Q and the keys of segment 1");
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      const f32x4 v4 = {o[4 * i], o[4 * i + 1], o[4 * i + 2], o[4 * i + 3]};
+      *reinterpret_cast<f32x4*>(red + (((size_t)w * 4 + i) * 64 + lane) * 4) = v4;
+    }
+    __syncthreads();
+    const int sl = w - pv_g * nslice;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      if ((i % pv_groups) == pv_g % 4 && pv_g < 4) {   // uniform per wave
+        f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+        for (int gg = 0; gg < pv_groups; gg++) {
+          const f32x4 v4 = *reinterpret_cast<const f32x4*>(red + (((size_t)(gg * nslice + sl) * 4 + i) * 64 + lane) * 4);
+          sum[0] += v4[0]; sum[1] += v4[1]; sum[2] += v4[2]; sum[3] += v4[3];
+        }
+        o[4 * i] = sum[0]; o[4 * i + 1] = sum[1]; o[4 * i + 2] = sum[2]; o[4 * i + 3] = sum[3];
+      }
+    }
+  }
   if (!row_ok) return;
   if (p.ml_out != nullptr && w == 0 && lh == 0 && vpart == 0) {   // (row maximum, sum) of this share, for the consumer's merge
     float* dst = p.ml_out + ((((size_t)cx.bz * p.heads + head) * ((p.Tq + 31) >> 5) * 32) + row) * 2;
@@ -295,6 +364,7 @@ __device__ __forceinline__ void attention_body(const AttnParams p, const Cx cx, 
   bf16* outp = p.out + (size_t)cx.bz * p.out_split_stride;
 #pragma unroll
   for (int i = 0; i < 4; i++) {
+    if (PVG && pv_groups > 1 && !((i % pv_groups) == pv_g % 4 && pv_g < 4)) continue;   // another wave's piece
     const int d = slice * 32 + 8 * i + 4 * lh;
     if (d < p.head_dim) {
       const bf16x4 ob = {(bf16)(o[4 * i] * inv), (bf16)(o[4 * i + 1] * inv), (bf16)(o[4 * i + 2] * inv),

@@ -150,7 +150,7 @@ __global__ __launch_bounds__(PK_THREADS) void expert_loop_kernel(const ExpertLoo
         if (a.ml_out != nullptr) a.ml_out = reinterpret_cast<float*>(slot + F.r_ml);
         const int att_gx = F.att_gx, att_gxy = F.att_gx * a.heads;
         for_items(F.att_items, [&](int it) {
-          attention_body<256, 8, 1, 6>(a, item(it % att_gx, (it % att_gxy) / att_gx, it / att_gxy).template as<true>(), smem_raw);
+          attention_body<256, 8, 1, 6, 5>(a, item(it % att_gx, (it % att_gxy) / att_gx, it / att_gxy).template as<true>(), smem_raw);
         });
         op_end();
       }
@@ -282,7 +282,9 @@ hipError_t launch_expert_loop(hipStream_t s, const ExpertLoopParams& P, ExpertLo
                                                         shares * a.chunks_per_split < a.chunks0)))
     return hipErrorInvalidValue;
   const int vs = a.v_split > 1 ? a.v_split : 1;
-  if (vs != 1 && vs != 2 && vs != 4 && vs != 8) return hipErrorInvalidValue;
+  // value slices in groups of waves: at most 5 chunks of [segment 0 ; segment 1] per wave
+  if (vs != 2 && vs != 4 && vs != 8) return hipErrorInvalidValue;
+  if ((n0 + 2 + vs - 1) / vs > 5) return hipErrorInvalidValue;
   if (P.att_gx != 2 * vs || P.att_items != 2 * vs * a.heads * shares || a.pf.blocks != 0) return hipErrorInvalidValue;
   if (!in_arena(a.q, 2) || !in_arena(a.k1, 2) || !in_arena(a.v1, 2) || !in_arena(a.out, 2)) return hipErrorInvalidValue;
   if (P.emb.a.X % 32 != 0 || P.emb.a.gain == nullptr || P.emb.a.stat_parts == nullptr || P.emb.a.x != P.emb.x_rw) return hipErrorInvalidValue;
