@@ -63,8 +63,14 @@ __global__ __launch_bounds__(PEAK_THREADS) void peak_mfma_kernel(int iters, unsi
 }
 
 // the shader's cycle counter (moves with the clock the power management currently grants) and the constant
-// 100 MHz counter, read back to back by one lane
+// 100 MHz counter, read back to back by one lane.  The cycle counters of the eight dies do not start together
+// (two samples taken on different dies gave "3.2 GHz"), and a one-block launch lands on any die: so the launch has
+// 256 one-wave blocks and only those on die 0, shader engine 0 write the pair (several may: they differ by well
+// under a microsecond).
 __global__ void clock_pair_kernel(long long* out) {
+  const unsigned xcc = (unsigned)__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 7u;    // XCC_ID, bits 3:0
+  const unsigned se = (unsigned)__builtin_amdgcn_s_getreg(4 | (13 << 6) | (2 << 11)) & 7u;     // HW_ID, SE_ID bits 15:13
+  if (xcc != 0u || se != 0u || threadIdx.x != 0) return;
   out[0] = (long long)__builtin_amdgcn_s_memtime();
   out[1] = (long long)wall_clock64();
 }
@@ -73,7 +79,7 @@ __global__ void clock_pair_kernel(long long* out) {
 
 extern "C" int pi0_clock_sample(long long* d_out, void* hip_stream) {
   if (d_out == nullptr || (reinterpret_cast<uintptr_t>(d_out) & 7) != 0) return PI0_EINVAL;
-  clock_pair_kernel<<<1, 1, 0, reinterpret_cast<hipStream_t>(hip_stream)>>>(d_out);
+  clock_pair_kernel<<<256, 64, 0, reinterpret_cast<hipStream_t>(hip_stream)>>>(d_out);
   return hipGetLastError() == hipSuccess ? PI0_OK : PI0_EHIP;
 }
 

@@ -790,7 +790,8 @@ bool persistent_feasible(const pi0_ctx* c, int P) {
   const int shares = pchunks > T.kcps ? ceil_div(pchunks, T.kcps) : 1;
   if (T.kcps > 8 || shares > 4 || (shares > 1 && !T.ksplit)) return false;
   const int vs = T.avs > 0 ? T.avs : (shares == 1 ? 4 : 2);
-  if (vs != 1 && vs != 2 && vs != 4 && vs != 8) return false;
+  if (vs != 2 && vs != 4 && vs != 8) return false;   // the kernel's attention keeps at most 5 chunks per wave
+  if (ceil_div((shares > 1 ? T.kcps : pchunks) + 2, vs) > 5) return false;
   const WsTr& L0 = w.exp[0];
   if (L0.o.k_pad != 2048 || (L0.down.k_pad != 2048 && L0.down.k_pad != 4096)) return false;
   if (d.Le > 1) {
