@@ -176,6 +176,10 @@ int pi0_infer(pi0_ctx* ctx, const float* d_images, int n_views, const int32_t* d
  * with events owned by ctx: use the same two (distinct, non-NULL) streams for every frame, and
  * enqueue the priming prefill on stream_prefill.  The results are valid once both streams are
  * synchronised.  Errors as pi0_infer; ESTATE if there is no valid prefill to denoise against.
+ * How far the two streams overlap depends on the hardware queues the runtime gives them: a process has few (4 by
+ * default), handed out in order of first use, and not every pair of queues runs kernels side by side equally well
+ * (measured: the same frames 9.1 or 10.3 ms apart).  Create and first use the two streams early in the process,
+ * before streams that other code or this library (the read-ahead stream of the per-operation denoise) creates.
  */
 int pi0_stream_frame(pi0_ctx* ctx, const float* d_images, int n_views, const int32_t* d_prompt_ids,
                      int n_prompt, const float* d_state, const float* d_noise, float* d_actions,

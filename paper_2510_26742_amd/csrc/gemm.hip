@@ -292,8 +292,20 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_entry_kernel(GemmParams p)
   const int w = t >> 6;
   const int lq = lane & 31;
   const int lh = lane >> 5;
-  const int nt0 = blockIdx.x * NT;
-  const int m0 = blockIdx.y * 64;
+  // die-aware order: consecutive block ids go to different dies (an L2 each), so the token blocks that share one
+  // weight panel are given ids with equal (id % 8) and fetch it from memory once
+  // (measured: vision QKV, 8 MB of weights, 10.8 -> 10.1 us and 3.7 x -> 1 x of its bytes from memory; the O projections
+  // with one feature tile per block lose 0.3 us, so they keep the plain two-dimensional grid)
+  int nb = (int)blockIdx.x, mt = (int)blockIdx.y;
+  if (NT > 1) {
+    const int nblocks_n = (p.n_tiles + NT - 1) / NT;
+    const int slot = (int)blockIdx.x >> 3;
+    nb = ((int)blockIdx.x & 7) + 8 * (slot / p.m_tiles);
+    mt = slot % p.m_tiles;
+    if (nb >= nblocks_n) return;
+  }
+  const int nt0 = nb * NT;
+  const int m0 = mt * 64;
   const int KC16 = p.W.k_pad >> 4;
   const int XKC16 = p.ldx >> 4;
   const int spw = (KC16 + SK_WAVES - 1) / SK_WAVES;        // host picks the instantiation with spw <= EN_SPW
@@ -589,7 +601,7 @@ hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmPara
     if (epi == EPI_RESID && (p.out_f32 == nullptr || p.out_bf16 == nullptr)) return hipErrorInvalidValue;
 #define X(PRO, EPI, NT, SPW)                                                                                   \
   if (pro == PRO && epi == EPI && spw <= SPW) {                                                                \
-    gemm_entry_kernel<PRO, EPI, NT, SPW><<<dim3((p.n_tiles + NT - 1) / NT, p.m_tiles), dim3(64 * SK_WAVES),    \
+    gemm_entry_kernel<PRO, EPI, NT, SPW><<<NT > 1 ? dim3(8 * (((p.n_tiles + NT - 1) / NT + 7) / 8) * p.m_tiles) : dim3(p.n_tiles, p.m_tiles), dim3(64 * SK_WAVES), \
                                            entry_smem_bytes(NT), s>>>(p);                                      \
     return hipGetLastError();                                                                                  \
   }
