@@ -53,6 +53,8 @@ def main() -> int:
     ap.add_argument("--prompt", type=int, default=0, help="prompt tokens (--trace-pass / --counters-pass only)")
     ap.add_argument("--counters-pass", action="store_true")
     ap.add_argument("--trace-pass", action="store_true")
+    ap.add_argument("--loop-timeline", action="store_true",
+                    help="in-kernel timeline of the persistent denoise loop (pi0_set_loop_trace), as text")
     ap.add_argument("--tune", type=str, default=None, help="kernel choices for tuning runs (pi0_tune)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -128,6 +130,71 @@ def main() -> int:
         m.pi0_device_status(stream)
         print(json.dumps({"mode": "trace-pass", "views": args.views, "prompt": args.prompt, "replays": args.steps,
                           "ms_per_replay_wall": round(ms, 4)}), flush=True)
+        m.close()
+        return 0
+
+    if args.loop_timeline:
+        # Wall-clock samples (100 MHz) that thread 0 of every block takes per operation of the persistent loop: entry,
+        # end of the wait for the barrier before, up to four marks inside the body, last store issued, end of arrive.
+        m.pi0_prefill(images_of[args.views], args.views, prompt if args.prompt else None, args.prompt, stream)
+
+        def denoise_ms(n=30):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            for _ in range(5):
+                m.pi0_denoise(state, noise, actions, stream)
+            with torch.cuda.stream(stream):
+                e0.record(stream)
+                for _ in range(n):
+                    m.pi0_denoise(state, noise, actions, stream)
+                e1.record(stream)
+            stream.synchronize()
+            return e0.elapsed_time(e1) / n
+        plain_ms = denoise_ms()
+        nops = m.pi0_loop_trace_ops()
+        tr = torch.zeros((nops, 256, 8), dtype=torch.int64, device=dev)
+        m.pi0_set_loop_trace(tr)
+        traced_ms = denoise_ms()
+        m.pi0_device_status(stream)
+        t = tr.cpu().numpy().astype(np.int64)
+        per_step = 3 + 5 * cfg.exp_layers
+        names = ["state"] + (["embed", "time2"] + ["qkv", "attn", "o", "gateup", "down"] * cfg.exp_layers + ["out"]) * cfg.steps
+        assert len(names) == nops
+        lo, hi = 1 + 4 * per_step, 1 + 6 * per_step          # Euler steps 4 and 5: steady state
+        rows = {}
+        for i in range(lo, hi):
+            a, nxt = t[i], t[i + 1]
+            work = a[:, 1] > 0
+            enter, waited, done, arr = a[:, 0], a[:, 1], a[:, 2], a[:, 3]
+            nwork = nxt[:, 1] > 0
+            d = {"items": int(work.sum()),
+                 "wait": float(np.median((waited - enter)[work])) * 10, "body": float(np.median((done - waited)[work])) * 10,
+                 "body_max": float((done - waited)[work].max()) * 10, "arrive": float(np.median((arr - done)[work])) * 10,
+                 "span": float(arr[work].max() - waited[work].min()) * 10,
+                 "barrier": float(nxt[:, 1][nwork].min() - arr[work].max()) * 10,
+                 "marks": [float(np.median((a[:, k] - waited)[work & (a[:, k] > 0)])) * 10 if (work & (a[:, k] > 0)).any() else 0.0
+                           for k in range(4, 8)]}
+            rows.setdefault(names[i], []).append(d)
+        print(f"persistent denoise loop, full pi0, {args.views} view(s), {args.prompt} prompt tokens; pi0_denoise {plain_ms:.3f} ms "
+              f"({traced_ms:.3f} ms while recording); averages over Euler steps 4 and 5, nanoseconds")
+        print("items  = blocks with a work item in the operation (of 256)")
+        print("wait   = median time a working block spends between its previous arrive and the end of the barrier wait")
+        print("body   = end of wait -> last store issued (median / max over working blocks)")
+        print("arrive = last store issued -> arrival counted (stores acknowledged, block barrier, atomic)")
+        print("span   = first working block released -> last working block arrived")
+        print("next   = last working block arrived -> first working block of the NEXT operation released (barrier latency)")
+        print("marks  = medians of the in-body samples relative to the end of the wait (GEMMs: activations in registers and")
+        print("         products done; all waves' partial tiles in LDS.  attention: Q in LDS; scores; probabilities; P V)")
+        print(f"{'op':7s} {'items':>5s} {'wait':>7s} {'body':>7s} {'max':>7s} {'arrive':>7s} {'span':>7s} {'next':>7s}   marks")
+        total = 0.0
+        for nm, lst in rows.items():
+            f = lambda k: float(np.mean([x[k] for x in lst]))
+            mk = [float(np.mean([x["marks"][j] for x in lst])) for j in range(4)]
+            total += (f("span") + f("barrier")) * len(lst)
+            print(f"{nm:7s} {f('items'):5.0f} {f('wait'):7.0f} {f('body'):7.0f} {f('body_max'):7.0f} {f('arrive'):7.0f} {f('span'):7.0f} "
+                  f"{f('barrier'):7.0f}   " + " ".join(f"{x:6.0f}" for x in mk if x > 0))
+        print(f"sum of span + next over the operations of one Euler step: {total / 2e3:.1f} us "
+              f"({total / 2e3 / cfg.exp_layers:.2f} us per layer incl. the step's three own operations)")
+        print(f"kernel span (first entry -> last arrive): {(t[-1][:, 3].max() - t[0][:, 0].min()) * 10 / 1e6:.3f} ms")
         m.close()
         return 0
 

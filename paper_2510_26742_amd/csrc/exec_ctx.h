@@ -53,7 +53,8 @@ enum {
   GB_MEMBERS = 64,     // + 32 x: blocks resident on die x
   GB_COUNT = 320,      // + 32 x: arrivals on die x (monotonic)
   GB_DONE = 576,       // + 32 y + x: last epoch that die x completed, as told to die y (one cache line per reading die)
-  GB_WORDS = 832
+  GB_SINK = 832,       // never read: where a read-ahead block would store its folded loads (keeps the loads alive)
+  GB_WORDS = 864
 };
 
 struct GridBarrier {

@@ -16,6 +16,7 @@ struct ExpertLoopParams {
   const float* noise;             // [x_elems] initial x (staged input, constant during the kernel)
   int x_elems;
   int layers, steps;
+  int read_ahead;                 // bit i set: blocks without an attention item read ahead range i of {gate||up, down, next QKV, next O}; 16: blocks without a QKV item read this layer's O
   size_t w_stride;                // elements between consecutive layers, the same for the four packed matrices
   size_t kcache_stride, vcache_stride;   // elements between consecutive layers of the prefix cache
   const float* g_attn0;           // gain vector of layer 0's attention norm; layer l at + l * gain_stride

@@ -21,6 +21,32 @@ namespace {
 
 constexpr int PK_THREADS = 512;
 
+// Reading ahead inside the loop.  The expert's weights (623 MB) cycle through the 256 MB memory-side cache once per Euler
+// step, so an operation's weight request - issued when the operation before ends - goes all the way to HBM (the same loop
+// run on one layer's weights throughout, i.e. from that cache, is 0.46 ms faster).  The attention has 64 items for 256
+// blocks: the blocks without one use the time to read the weights that the following operations will ask for, which puts
+// them into the memory-side cache.  Part `part` of `nparts` of [base, base + bytes): 16 bytes per lane, 8 loads in flight
+// (4 finish too late, 16 disturb the working blocks' loads more than they gain: same-box A/B 5.47 / 5.42 / 5.48 ms);
+// the values are folded into a word that is stored only if it equals a constant, so no result depends on them.
+__device__ __forceinline__ unsigned read_ahead_part(const void* base, size_t bytes, int part, int nparts, int tid, unsigned fold) {
+  const size_t n16 = bytes >> 4;
+  const size_t per = (n16 + (size_t)nparts - 1) / (size_t)nparts;
+  const size_t beg = (size_t)part * per;
+  const size_t end = beg + per < n16 ? beg + per : n16;
+  const u32x4_t* p = reinterpret_cast<const u32x4_t*>(base);
+  for (size_t i = beg + (size_t)tid; i < end; i += 8 * PK_THREADS) {
+    u32x4_t v[8];
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+      const size_t idx = i + (size_t)j * PK_THREADS;
+      v[j] = p[idx < end ? idx : end - 1];   // clamped, unconditional
+    }
+#pragma unroll
+    for (int j = 0; j < 8; j++) fold ^= v[j][0] ^ v[j][1] ^ v[j][2] ^ v[j][3];
+  }
+  return fold;
+}
+
 template <class F>
 __device__ __forceinline__ void for_items(int n_items, F&& f) {
   bool first = true;
@@ -134,6 +160,18 @@ __global__ __launch_bounds__(PK_THREADS) void expert_loop_kernel(const ExpertLoo
             gemm_skinny_body<PRO_RMS, EPI_QKV, 1>(q, item(it % q.n_tiles, 0, it / q.n_tiles).template as<true>(), smem_raw);
           });
         }
+        if ((int)blockIdx.x >= q.n_tiles * 2 && (F.read_ahead & 48)) {   // no item: what the attention and O of this layer read
+          const int tid = item(0, 0, 0).thread;
+          const int part = (int)blockIdx.x - q.n_tiles * 2, nparts = (int)gridDim.x - q.n_tiles * 2;
+          unsigned fold = 0;
+          if (F.read_ahead & 32) {   // this layer's slices of the prefix cache
+            const size_t cache_bytes = (size_t)F.att.chunks0 * 32 * 256 * 2;
+            fold = read_ahead_part(F.att.k0 + (size_t)l * F.kcache_stride, cache_bytes, part, nparts, tid, fold);
+            fold = read_ahead_part(F.att.v0 + (size_t)l * F.vcache_stride, cache_bytes, part, nparts, tid, fold);
+          }
+          if (F.read_ahead & 16) fold = read_ahead_part(F.o.W.w + (size_t)l * F.w_stride, (size_t)F.o.n_tiles * 64 * F.o.W.k_pad, part, nparts, tid, fold);
+          if (fold == 0x9e3779b9u) F.sync[GB_SINK] = fold;
+        }
         op_end();
       }
       op_begin();
@@ -152,6 +190,17 @@ __global__ __launch_bounds__(PK_THREADS) void expert_loop_kernel(const ExpertLoo
         for_items(F.att_items, [&](int it) {
           attention_body<256, 8, 1, 6, 5>(a, item(it % att_gx, (it % att_gxy) / att_gx, it / att_gxy).template as<true>(), smem_raw);
         });
+        if ((int)blockIdx.x >= F.att_items && F.read_ahead != 0) {   // no item: read ahead (constants only, no wait needed)
+          const int part = (int)blockIdx.x - F.att_items, nparts = (int)gridDim.x - F.att_items;
+          const int ln = l + 1 < layers ? l + 1 : 0;
+          const int tid = item(0, 0, 0).thread;
+          unsigned fold = 0;
+          if (F.read_ahead & 1) fold = read_ahead_part(F.gu.W.w + (size_t)l * F.w_stride, (size_t)F.gu.n_tiles * 64 * F.gu.W.k_pad, part, nparts, tid, fold);
+          if (F.read_ahead & 2) fold = read_ahead_part(F.dn.W.w + (size_t)l * F.w_stride, (size_t)F.dn.n_tiles * 64 * F.dn.W.k_pad, part, nparts, tid, fold);
+          if (F.read_ahead & 4) fold = read_ahead_part(F.qkv.W.w + (size_t)ln * F.w_stride, (size_t)F.qkv.n_tiles * 64 * F.qkv.W.k_pad, part, nparts, tid, fold);
+          if (F.read_ahead & 8) fold = read_ahead_part(F.o.W.w + (size_t)ln * F.w_stride, (size_t)F.o.n_tiles * 64 * F.o.W.k_pad, part, nparts, tid, fold);
+          if (fold == 0x9e3779b9u) F.sync[GB_SINK] = fold;
+        }
         op_end();
       }
       op_begin();
@@ -255,6 +304,7 @@ hipError_t launch_expert_loop(hipStream_t s, const ExpertLoopParams& P, ExpertLo
   for (const GemmParams* g : sk) {
     if (g->k_per_split != g->W.k_pad || g->W.k_pad > SK_KMAX || g->m_tiles != 1) return hipErrorInvalidValue;
   }
+  if (P.read_ahead < 0 || P.read_ahead > 63) return hipErrorInvalidValue;
   if (P.gu.n_tiles % 2 != 0 || P.gu.M <= 32) return hipErrorInvalidValue;   // gate||up: pairs of feature tiles, two token blocks
   if (P.qkv.rowstat == nullptr || P.gu.rowstat == nullptr || P.outp.rowstat == nullptr) return hipErrorInvalidValue;
   if (P.parts_first < 1 || P.parts_first > 8 * SK_WAVES || P.parts_rest < 1 || P.parts_rest > 8 * SK_WAVES) return hipErrorInvalidValue;

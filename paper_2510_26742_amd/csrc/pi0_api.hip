@@ -377,6 +377,9 @@ struct Tune {
   int ras = 256, ral = 1, rat = 256, rad = 6;
   // the whole denoise loop as one persistent kernel with grid barriers (1) or one launch per operation (0)
   int pdn = 1;
+  // ... in which the blocks without an attention item read ahead (bits: gate||up, down, next layer's QKV, next layer's O; 16: this layer's O by the blocks
+  // without a QKV item)
+  int pra = 39;
 };
 
 struct pi0_ctx {
@@ -835,6 +838,7 @@ bool run_denoise_persistent(Run& r, int P) {
   E.layers = d.Le;
   E.steps = d.steps;
   E.w_stride = wst / 2;
+  E.read_ahead = T.pra;
   E.kcache_stride = w.kcache_layer / 2;
   E.vcache_stride = w.vcache_layer / 2;
   E.g_attn0 = at<float>(c, w.g_e1[0]);
@@ -1412,7 +1416,7 @@ int pi0_tune(pi0_ctx* c, const char* env) {
         {"zld", &c->tune.zld, 1, Z_MAX}, {"zvd", &c->tune.zvd, 1, Z_MAX},
         {"pfq", &c->tune.pfq, 0, 1024}, {"pfa", &c->tune.pfa, 0, 1024}, {"pfo", &c->tune.pfo, 0, 1024},
         {"pfd", &c->tune.pfd, 0, 1024}, {"ae16", &c->tune.ae16, 0, 1}, {"ksplit", &c->tune.ksplit, 0, 1}, {"kcps", &c->tune.kcps, 2, 16}, {"qms", &c->tune.qms, 0, 1},
-        {"fko", &c->tune.fko, 0, 1}, {"fkl", &c->tune.fkl, 0, 1}, {"ras", &c->tune.ras, 0, 4096}, {"ral", &c->tune.ral, 1, 8}, {"rat", &c->tune.rat, 64, 256}, {"rad", &c->tune.rad, 1, 8 /* 7: no such variant, see below */}, {"avs", &c->tune.avs, 1, 8}, {"pdn", &c->tune.pdn, 0, 1}};
+        {"fko", &c->tune.fko, 0, 1}, {"fkl", &c->tune.fkl, 0, 1}, {"ras", &c->tune.ras, 0, 4096}, {"ral", &c->tune.ral, 1, 8}, {"rat", &c->tune.rat, 64, 256}, {"rad", &c->tune.rad, 1, 8 /* 7: no such variant, see below */}, {"avs", &c->tune.avs, 1, 8}, {"pdn", &c->tune.pdn, 0, 1}, {"pra", &c->tune.pra, 0, 63}};
     for (auto& k : keys) {
       const char* f = strstr(env, k.key);
       while (f != nullptr && !((f == env || f[-1] == ',') && f[strlen(k.key)] == '=')) f = strstr(f + 1, k.key);
