@@ -54,18 +54,20 @@ __device__ __forceinline__ void action_embed_body(const ActionEmbedArgs a, const
   const int X = a.X, A = a.A, chunk = a.chunk;
   if (n >= X) return;
   if (r < chunk) {
-    // loads in batches of 8 (independent), accumulated in index order
+    // all loads of (up to) 32 terms issued together - the x values cross blocks, i.e. come from memory, and a batch
+    // that waits for the one before costs a round trip each (4 batches of 8: 3.9 us per operation) - then accumulated
+    // in index order
     float acc = a.bias_k[n];
-    for (int j0 = 0; j0 < A; j0 += 8) {
-      float wv[8], xv[8];
+    for (int j0 = 0; j0 < A; j0 += 32) {
+      float wv[32], xv[32];
 #pragma unroll
-      for (int u = 0; u < 8; u++) {
+      for (int u = 0; u < 32; u++) {
         const int j = min(j0 + u, A - 1);
-        wv[u] = a.wfold[(size_t)j * X + n];
         xv[u] = cx.ld(a.x + (size_t)r * A + j);
+        wv[u] = a.wfold[(size_t)j * X + n];
       }
 #pragma unroll
-      for (int u = 0; u < 8; u++) {
+      for (int u = 0; u < 32; u++) {
         if (j0 + u < A) acc += xv[u] * wv[u];
       }
     }

@@ -136,7 +136,7 @@ __global__ __launch_bounds__(PK_THREADS) void expert_loop_kernel(const ExpertLoo
     // ---- C2: second linear of the action/time MLP -> suffix rows 1 .. chunk --------------------------
     {
       const GemmParams t = fresh(Pg).tout;
-      for_items(t.n_tiles, [&](int it) { gemm_skinny_body<PRO_NONE, EPI_RESID, 0>(t, item(it, 0, 0), smem_raw); });
+      for_items(t.n_tiles * 2, [&](int it) { gemm_skinny_body<PRO_NONE, EPI_RESID, 1>(t, item(it % t.n_tiles, 0, it / t.n_tiles), smem_raw); });
     }
     op_end();
     for (int l = 0; l < layers; l++) {
@@ -257,7 +257,8 @@ __global__ __launch_bounds__(PK_THREADS) void expert_loop_kernel(const ExpertLoo
       char* slot = F.ring + (size_t)(k * layers + layers - 1) * F.ring_stride;
       u.X = reinterpret_cast<const bf16*>(slot + F.r_yb_d);
       u.rowstat = reinterpret_cast<const float*>(slot + F.r_st_d);
-      for_items(u.n_tiles, [&](int it) { gemm_skinny_body<PRO_RMS, EPI_EULER, 0>(u, item(it, 0, 0).template as<true>(), smem_raw); });
+      // one item per (feature tile, token block): half the activation bytes per block
+      for_items(u.n_tiles * 2, [&](int it) { gemm_skinny_body<PRO_RMS, EPI_EULER, 1>(u, item(it % u.n_tiles, 0, it / u.n_tiles).template as<true>(), smem_raw); });
     }
     op_end();
   }

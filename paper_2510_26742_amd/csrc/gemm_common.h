@@ -76,6 +76,18 @@ __device__ __forceinline__ void epilogue_preload(const GemmParams& p, int nt, in
         const int i0 = (nl & 255) >> 1;
         o.aux[i - I0] = *reinterpret_cast<const f32x4*>(p.rope + ((size_t)(p.pos0 + m) * 128 + i0) * 2);
       }
+    } else if (EPI == EPI_EULER) {
+      // the x values this lane updates, with the other inputs (read inside the epilogue they cost one round trip per
+      // step of the tile, each behind the stores of the step before: 4.7 of the out-projection's 7.2 us)
+      if (DEP != 0 && m >= 1 && n4 < p.n_valid) {
+        const float* xp = p.out_f32 + (size_t)(m - 1) * p.ldo + n4;
+        f32x4 xv = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+          if (n4 + j < p.n_valid) xv[j] = cx.ld(xp + j);
+        }
+        o.aux[i - I0] = xv;
+      }
     }
   }
 }
@@ -175,11 +187,8 @@ __device__ __forceinline__ void epilogue_tile(const GemmParams& p, const f32x16&
         }
       } else if (EPI == EPI_EULER) {
         if (m >= 1 && n4 < p.n_valid) {
-          // the four x values of this lane: all read before any is written (one round trip instead of four)
           float* xp = p.out_f32 + (size_t)(m - 1) * p.ldo + n4;
-          float xv[4];
-#pragma unroll
-          for (int j = 0; j < 4; j++) xv[j] = n4 + j < p.n_valid ? cx.ld(xp + j) : 0.f;
+          const f32x4 xv = ops.aux[i - I0];   // x before the update, fetched with the other inputs
 #pragma unroll
           for (int j = 0; j < 4; j++) {
             if (n4 + j < p.n_valid) cx.st(xp + j, xv[j] + p.dt * v[j]);
