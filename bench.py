@@ -398,8 +398,11 @@ def main() -> int:
     torch.cuda.synchronize()
     peak_hbm = binding.pi0_peak_bench("hbm_read", pbuf, pbuf.numel() * 4, 0, 20, psink, stream)
     peak_mfma = binding.pi0_peak_bench("mfma_bf16", None, 0, 4096, 20, psink, stream)
+    # ... and what the caches deliver to the compute units when the 32 blocks of a die share 1 MiB (L2 hits)
+    peak_cache = binding.pi0_peak_bench("cache_read", pbuf, 8 << 20, 64, 5, psink, stream)
     del pbuf
-    log(f"[bench] attainable peaks on this device: HBM read {peak_hbm:.0f} GB/s, bf16 MFMA {peak_mfma:.0f} TFLOP/s")
+    log(f"[bench] attainable peaks on this device: HBM read {peak_hbm:.0f} GB/s, bf16 MFMA {peak_mfma:.0f} TFLOP/s, "
+        f"L2 hits into the compute units {peak_cache:.0f} GB/s")
 
     def of_attainable(row):
         att = peak_hbm if row.get("unit") == "GB/s" else peak_mfma
@@ -453,6 +456,7 @@ def main() -> int:
         # measured on this device by pi0_peak_bench, beside the published peaks the `frac` fields use
         "shader_clock_GHz": round(clock_ghz, 3),
         "attainable_peaks": {"hbm_read_GBps": round(peak_hbm, 1), "mfma_bf16_TFLOPs": round(peak_mfma, 1),
+                             "l2_hit_read_GBps": round(peak_cache, 1),
                              "published": {"hbm_GBps": 8000.0, "mfma_bf16_TFLOPs": 2500.0}},
         "roofline_kernels": [dominant] + krows,
         "roofline_classes": class_rows[hv],

@@ -90,11 +90,17 @@ int pi0_sync_bench(int mode, int n_ops, int reps, float* d_x, const float* d_b, 
  *                       2 waves per SIMD on 256 compute units' worth of blocks, operands and
  *                       accumulators in registers, non-zero operands; *h_result = TFLOP/s.
  *                       d_buf / bytes unused.
+ *   PI0_PEAK_CACHE_READ 256 blocks of 512 threads (one per compute unit, the shape of the pass's own kernels); block b
+ *                       reads the slice (b mod 8) of d_buf - `bytes` / 8 bytes each, so the blocks of one die share
+ *                       a slice under round-robin dispatch - `iters` (1 .. 2^20) times with 16-byte loads, 8 in flight
+ *                       per lane; *h_result = GB/s delivered to the compute units.  With slices that fit a die's L2
+ *                       (4 MB) this is the rate of L2 hits, with larger ones that of the memory-side cache.
+ *                       bytes: a multiple of 128, at least 65536.
  * One untimed launch, then `reps` (1 .. 1000) launches timed with HIP events on hip_stream; the call
  * synchronises the stream.  d_sink: device, one uint32 the kernels may write (never read back).
  * h_result: HOST.  Nothing is allocated on the device.  Errors: EINVAL, EHIP.
  */
-enum pi0_peak_kind { PI0_PEAK_HBM_READ = 0, PI0_PEAK_MFMA_BF16 = 1 };
+enum pi0_peak_kind { PI0_PEAK_HBM_READ = 0, PI0_PEAK_MFMA_BF16 = 1, PI0_PEAK_CACHE_READ = 2 };
 int pi0_peak_bench(int kind, const void* d_buf, size_t bytes, int iters, int reps, unsigned* d_sink,
                    double* h_result, void* hip_stream);
 

@@ -217,7 +217,7 @@ def shader_clock_ghz(sample0, sample1) -> float:
     return cyc / (ticks * 10.0) if ticks > 0 else float("nan")
 
 
-PEAK_KINDS = {"hbm_read": 0, "mfma_bf16": 1}
+PEAK_KINDS = {"hbm_read": 0, "mfma_bf16": 1, "cache_read": 2}
 PRECISIONS = {"bf16": 0, "mxfp8_prefix_mlp": 1}
 
 

@@ -34,6 +34,28 @@ __global__ __launch_bounds__(PEAK_THREADS) void peak_read_kernel(const u32x4* bu
   if (fold == NEVER) sink[0] = fold;
 }
 
+// What the caches deliver to the compute units: every block reads one of eight slices over and over (the blocks of
+// a die share a slice), 8 loads of 16 bytes in flight per lane.
+__global__ __launch_bounds__(512) void peak_cache_kernel(const u32x4* buf, size_t n16_slice, int iters, unsigned* sink) {
+  const u32x4* p = buf + (size_t)(blockIdx.x & 7) * n16_slice;
+  u32x4 f = {0u, 0u, 0u, 0u};
+  for (int it = 0; it < iters; it++) {
+    for (size_t i = threadIdx.x; i < n16_slice; i += 8 * 512) {
+      u32x4 v[8];
+#pragma unroll
+      for (int j = 0; j < 8; j++) {
+        const size_t idx = i + (size_t)j * 512;
+        v[j] = p[idx < n16_slice ? idx : n16_slice - 1];
+      }
+#pragma unroll
+      for (int j = 0; j < 8; j++) f ^= v[j];
+    }
+    asm volatile("" ::: "memory");   // the next pass reads again
+  }
+  const unsigned fold = f[0] ^ f[1] ^ f[2] ^ f[3];
+  if (fold == NEVER) sink[0] = fold;
+}
+
 // Operands and accumulators never leave the registers.  The operands are small non-zero values
 // that differ per lane (a matrix pipe fed with zeros draws less power and clocks higher than one
 // fed with data).
@@ -90,6 +112,9 @@ extern "C" int pi0_peak_bench(int kind, const void* d_buf, size_t bytes, int ite
     if (d_buf == nullptr || bytes < 16 || (bytes & 15) != 0 || (reinterpret_cast<uintptr_t>(d_buf) & 15) != 0) return PI0_EINVAL;
   } else if (kind == PI0_PEAK_MFMA_BF16) {
     if (iters < 1 || iters > (1 << 22)) return PI0_EINVAL;
+  } else if (kind == PI0_PEAK_CACHE_READ) {
+    if (d_buf == nullptr || bytes < 65536 || (bytes & 127) != 0 || (reinterpret_cast<uintptr_t>(d_buf) & 15) != 0) return PI0_EINVAL;
+    if (iters < 1 || iters > (1 << 20)) return PI0_EINVAL;
   } else {
     return PI0_EINVAL;
   }
@@ -104,6 +129,8 @@ extern "C" int pi0_peak_bench(int kind, const void* d_buf, size_t bytes, int ite
       if (e != hipSuccess) break;
       if (kind == PI0_PEAK_HBM_READ)
         peak_read_kernel<<<dim3(READ_BLOCKS), dim3(PEAK_THREADS), 0, s>>>(reinterpret_cast<const u32x4*>(d_buf), bytes / 16, d_sink);
+      else if (kind == PI0_PEAK_CACHE_READ)
+        peak_cache_kernel<<<dim3(256), dim3(512), 0, s>>>(reinterpret_cast<const u32x4*>(d_buf), bytes / 128, iters, d_sink);
       else
         peak_mfma_kernel<<<dim3(MFMA_BLOCKS), dim3(PEAK_THREADS), 0, s>>>(iters, d_sink);
       e = hipGetLastError();
@@ -118,6 +145,8 @@ extern "C" int pi0_peak_bench(int kind, const void* d_buf, size_t bytes, int ite
         e = hipErrorUnknown;
       } else if (kind == PI0_PEAK_HBM_READ) {
         *h_result = (double)bytes / sec * 1e-9;                                  // GB/s
+      } else if (kind == PI0_PEAK_CACHE_READ) {
+        *h_result = 256.0 * (double)iters * (double)(bytes / 8) / sec * 1e-9;    // GB/s into the compute units
       } else {
         const double flops = (double)MFMA_BLOCKS * (PEAK_THREADS / 64) * (double)iters * MFMA_ACC * (2.0 * 32 * 32 * 16);
         *h_result = flops / sec * 1e-12;                                         // TFLOP/s

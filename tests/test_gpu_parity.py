@@ -398,6 +398,14 @@ def test_attainable_peak_microbenchmarks():
     say(f"[peak] HBM read {gbps:.0f} GB/s, bf16 MFMA {tflops:.0f} TFLOP/s")
     assert 1500.0 < gbps < 8000.0
     assert 500.0 < tflops < 2600.0
+    say("[gpu] pi0_peak_bench cache_read")
+    l2 = binding.pi0_peak_bench("cache_read", buf, 8 << 20, 32, 5, sink, stream)    # 1 MiB per die, shared by its 32 blocks
+    say(f"[peak] L2 hits into the compute units {l2:.0f} GB/s")
+    assert 4000.0 < l2 < 256 * 64 * 3.0        # above HBM's rate, below 64 B/clk per compute unit at 3 GHz
+    with pytest.raises(binding.Pi0Error):
+        binding.pi0_peak_bench("cache_read", buf, 8 << 20, 0, 1, sink, stream)
+    with pytest.raises(binding.Pi0Error):
+        binding.pi0_peak_bench("cache_read", buf, 1000, 4, 1, sink, stream)
     assert torch.equal(buf.cpu(), host)
     with pytest.raises(binding.Pi0Error):
         binding.pi0_peak_bench("hbm_read", buf, n * 4 + 4, 0, 1, sink, stream)

@@ -160,7 +160,11 @@ def test_peak_bench_rejects_bad_arguments(L):
     fake = 0x10000
     out = ctypes.c_double(0.0)
     r = ctypes.byref(out)
-    assert L.pi0_peak_bench(2, fake, 1 << 20, 16, 1, fake, r, None) == binding.PI0_EINVAL          # unknown kind
+    assert L.pi0_peak_bench(3, fake, 1 << 20, 16, 1, fake, r, None) == binding.PI0_EINVAL          # unknown kind
+    assert L.pi0_peak_bench(2, None, 1 << 20, 16, 1, fake, r, None) == binding.PI0_EINVAL          # cache read: no buffer
+    assert L.pi0_peak_bench(2, fake, 1 << 15, 16, 1, fake, r, None) == binding.PI0_EINVAL          # slices too small
+    assert L.pi0_peak_bench(2, fake, (1 << 20) + 64, 16, 1, fake, r, None) == binding.PI0_EINVAL   # not 8 equal slices of 16-byte words
+    assert L.pi0_peak_bench(2, fake, 1 << 20, 0, 1, fake, r, None) == binding.PI0_EINVAL           # no passes
     assert L.pi0_peak_bench(0, None, 1 << 20, 0, 1, fake, r, None) == binding.PI0_EINVAL            # no buffer
     assert L.pi0_peak_bench(0, fake, 0, 0, 1, fake, r, None) == binding.PI0_EINVAL                  # nothing to read
     assert L.pi0_peak_bench(0, fake, (1 << 20) + 8, 0, 1, fake, r, None) == binding.PI0_EINVAL      # not whole 16-byte words
@@ -170,7 +174,7 @@ def test_peak_bench_rejects_bad_arguments(L):
     assert L.pi0_peak_bench(1, None, 0, 16, 0, fake, r, None) == binding.PI0_EINVAL                 # no repetitions
     assert L.pi0_peak_bench(1, None, 0, 16, 1, None, r, None) == binding.PI0_EINVAL                 # no sink
     assert L.pi0_peak_bench(1, None, 0, 16, 1, fake, None, None) == binding.PI0_EINVAL              # no result
-    assert binding.PEAK_KINDS == {"hbm_read": 0, "mfma_bf16": 1}
+    assert binding.PEAK_KINDS == {"hbm_read": 0, "mfma_bf16": 1, "cache_read": 2}
 
 
 def test_clock_sample_rejects_bad_arguments(L):
