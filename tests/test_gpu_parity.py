@@ -602,14 +602,14 @@ def test_persistent_denoise_loop_equals_per_operation_launches():
 def test_reading_ahead_changes_no_bit():
     """The expert's read-ahead kernel and the warm-up blocks only load: the actions of a pass with either of them,
     with neither, and with another shape of the read-ahead kernel are the same bits (graph replay and eager), and the
-    persistent loop gives the bits of the per-operation launches.  The number of blocks that share the value slices of the
+    persistent loop gives the bits of the per-operation launches, whatever its idle blocks read ahead (pra).  The number of blocks that share the value slices of the
     expert attention fixes how the second product is shared out over a block's waves, i.e. the order of an fp32 sum:
     for each such number the persistent loop and the launches agree bit for bit, and between the numbers the actions
     differ by rounding only."""
     import os
     outs = {}
     for tune in ("", "pdn=0", "pdn=0,ras=0", "pdn=0,ras=0,pfq=0,pfa=0,pfo=0,pfd=0", "pdn=0,ras=128,rat=128,rad=3,ral=2", "pdn=0,avs=1",
-                 "pdn=0,avs=8", "avs=1", "avs=8", "pdn=0,avs=2", "avs=2"):
+                 "pdn=0,avs=8", "avs=1", "avs=8", "pdn=0,avs=2", "avs=2", "pra=0", "pra=63"):
         if tune:
             os.environ["PI0_TUNE"] = tune
         try:
