@@ -286,3 +286,19 @@ def test_static_scratch_entry_point_rejects_what_does_not_fit(L):
         assert L.pi0_denoise_static(ctx, dummy, dummy, dummy, None) == want
         assert L.pi0_denoise_static(ctx, None, dummy, dummy, None) == binding.PI0_EINVAL
         L.pi0_destroy(ctx)
+
+
+def test_traffic_profile_is_what_bench_reads():
+    """bench.py takes `traffic` from profiles/traffic_full_pi0.json: per view count the dominant kernel's HBM-side bytes per
+    launch and a table by kernel family, with the commit and the calibration it was taken at."""
+    import json
+    t = json.load(open(os.path.join(ROOT, "profiles", "traffic_full_pi0.json")))
+    assert re.fullmatch(r"[0-9a-f]{7,40}", t["commit"])
+    assert 1.5 < t["calibration"]["fetch_factor"] < 2.5 and 0.8 < t["calibration"]["write_factor"] < 1.2
+    algorithmic = 6.9e9            # the expert's weights, 10 times (roofline.class_work gives the exact figure)
+    for v in ("1", "2", "3"):
+        row = t["by_views"][v]
+        assert algorithmic < row["expert_loop_kernel"] < 4 * algorithmic
+        assert row["families"]["expert_loop_kernel"]["launches"] == 1
+        for fam in ("gemm_kernel", "attention_kernel", "splitk_reduce_kernel"):
+            assert row["families"][fam]["bytes_per_launch"] > 0
