@@ -176,6 +176,8 @@ int pi0_infer(pi0_ctx* ctx, const float* d_images, int n_views, const int32_t* d
  * with events owned by ctx: use the same two (distinct, non-NULL) streams for every frame, and
  * enqueue the priming prefill on stream_prefill.  The results are valid once both streams are
  * synchronised.  Errors as pi0_infer; ESTATE if there is no valid prefill to denoise against.
+ * The denoise runs as the persistent kernel on a part of the compute units (96 .. 160 blocks, by prefix size), the
+ * prefill on the rest; the same bounded waits and pi0_device_status apply.
  * How far the two streams overlap depends on the hardware queues the runtime gives them: a process has few (4 by
  * default), handed out in order of first use, and not every pair of queues runs kernels side by side equally well
  * (measured: the same frames 9.1 or 10.3 ms apart).  Create and first use the two streams early in the process,

@@ -214,7 +214,8 @@ int pi0_set_loop_trace(pi0_ctx* ctx, long long* d_trace, int ops_cap);
  * warm-up block counts (pfq, pfa, pfo, pfd), switches (ae16, qms, ksplit, kcps, avs, fko, fkl), pdn (1: the denoise loop as
  * one persistent kernel, 0: one launch per operation) and pra (what the persistent kernel's blocks without a work item read
  * ahead: 1 gate||up, 2 down, 4 next layer's QKV, 8 next layer's O weights during the attention; 16 this layer's O weights,
- * 32 this layer's prefix keys / values during QKV).
+ * 32 this layer's prefix keys / values during QKV) and psb (blocks of the persistent kernel inside a two-stream frame;
+ * 0: per-operation launches there, -1: chosen from the prefix size).
  * Drops every captured graph, so the next call of a shape captures again.  Must not be called while work of this
  * ctx is in flight.  The library itself never reads the environment.  Errors: EINVAL (null).
  */

@@ -380,6 +380,9 @@ struct Tune {
   // ... in which the blocks without an attention item read ahead (bits: gate||up, down, next layer's QKV, next layer's O; 16: this layer's O by the blocks
   // without a QKV item)
   int pra = 39;
+  // two-stream frames: blocks of the persistent loop beside the prefill (0: per-operation launches).  A resident block
+  // of the loop holds a whole compute unit, so its grid decides how the chip is shared between the two streams
+  int psb = -1;           // -1: from the number of prefix tokens (frame_loop_blocks)
 };
 
 struct pi0_ctx {
@@ -428,6 +431,7 @@ struct Run {
   int cls = PI0_OP_MISC;        // class of the launches that follow
   OpTimer* timer = nullptr;     // when set, every RUN / RUN_GEMM launch is bracketed by an event pair
   bool persistent_ok = false;   // the denoise loop may run as one persistent kernel (plain pi0_denoise / pi0_infer calls)
+  int persist_blocks = 0;       // its grid (0: one block per compute unit)
   unsigned char* ebase = nullptr;   // where the expert's scratch block lives minus its workspace offset (null: in the workspace)
   bool ok() const { return err == hipSuccess; }
   void did(hipError_t e) {
@@ -944,7 +948,7 @@ bool run_denoise_persistent(Run& r, int P) {
   // barrier words restart at zero (the error word, first, stays as it is)
   RUN(r, launch_fill_zero(r.s, at<unsigned>(c, w.esync) + GB_START, (size_t)(GB_WORDS - GB_START) * 4));
   if (r.ok()) {
-    r.did(launch_expert_loop(r.s, E, at<ExpertLoopParams>(c, w.eparams), PK_BLOCKS));
+    r.did(launch_expert_loop(r.s, E, at<ExpertLoopParams>(c, w.eparams), r.persist_blocks > 0 ? r.persist_blocks : PK_BLOCKS));
     r.launches++;   // two launches: parameter block, loop kernel
   }
   return true;
@@ -1231,6 +1235,12 @@ hipError_t ensure_read_ahead(pi0_ctx* c) {
   return e;
 }
 
+// grid of the persistent denoise loop inside a two-stream frame (0: per-operation launches)
+int frame_loop_blocks(const pi0_ctx* c, int P) {
+  if (c->tune.psb >= 0) return c->tune.psb;
+  return P <= 256 ? 160 : P <= 512 ? 128 : P <= 768 ? 96 : 128;   // measured optima at 256 / 512 / 768 / 816 prefix tokens
+}
+
 // Runs `kind` either through a cached graph or eagerly.
 int execute(pi0_ctx* c, int kind, int n_views, int n_prompt, hipStream_t s, int slot_w = -1, int slot_r = -1, bool read_ahead = true) {
   const int P = n_views * c->d.T + n_prompt;
@@ -1250,7 +1260,9 @@ int execute(pi0_ctx* c, int kind, int n_views, int n_prompt, hipStream_t s, int 
     r.slot_w = slot_w;
     r.slot_r = slot_r;
     r.read_ahead = read_ahead;
-    r.persistent_ok = read_ahead;   // two-stream frames keep the per-operation launches: the prefill's blocks need the compute units too
+    // two-stream frames: per-operation launches, or the loop on a part of the chip (the prefill's blocks need compute units too)
+    r.persist_blocks = read_ahead ? 0 : frame_loop_blocks(c, P);
+    r.persistent_ok = read_ahead || r.persist_blocks > 0;
     body(r);
     return r.ok() ? PI0_OK : fail_hip(c, r.err);
   }
@@ -1264,7 +1276,9 @@ int execute(pi0_ctx* c, int kind, int n_views, int n_prompt, hipStream_t s, int 
     r.slot_w = slot_w;
     r.slot_r = slot_r;
     r.read_ahead = read_ahead;
-    r.persistent_ok = read_ahead;   // two-stream frames keep the per-operation launches: the prefill's blocks need the compute units too
+    // two-stream frames: per-operation launches, or the loop on a part of the chip (the prefill's blocks need compute units too)
+    r.persist_blocks = read_ahead ? 0 : frame_loop_blocks(c, P);
+    r.persistent_ok = read_ahead || r.persist_blocks > 0;
     body(r);
     hipGraph_t g = nullptr;
     e = hipStreamEndCapture(s, &g);
@@ -1416,7 +1430,7 @@ int pi0_tune(pi0_ctx* c, const char* env) {
         {"zld", &c->tune.zld, 1, Z_MAX}, {"zvd", &c->tune.zvd, 1, Z_MAX},
         {"pfq", &c->tune.pfq, 0, 1024}, {"pfa", &c->tune.pfa, 0, 1024}, {"pfo", &c->tune.pfo, 0, 1024},
         {"pfd", &c->tune.pfd, 0, 1024}, {"ae16", &c->tune.ae16, 0, 1}, {"ksplit", &c->tune.ksplit, 0, 1}, {"kcps", &c->tune.kcps, 2, 16}, {"qms", &c->tune.qms, 0, 1},
-        {"fko", &c->tune.fko, 0, 1}, {"fkl", &c->tune.fkl, 0, 1}, {"ras", &c->tune.ras, 0, 4096}, {"ral", &c->tune.ral, 1, 8}, {"rat", &c->tune.rat, 64, 256}, {"rad", &c->tune.rad, 1, 8 /* 7: no such variant, see below */}, {"avs", &c->tune.avs, 1, 8}, {"pdn", &c->tune.pdn, 0, 1}, {"pra", &c->tune.pra, 0, 63}};
+        {"fko", &c->tune.fko, 0, 1}, {"fkl", &c->tune.fkl, 0, 1}, {"ras", &c->tune.ras, 0, 4096}, {"ral", &c->tune.ral, 1, 8}, {"rat", &c->tune.rat, 64, 256}, {"rad", &c->tune.rad, 1, 8 /* 7: no such variant, see below */}, {"avs", &c->tune.avs, 1, 8}, {"pdn", &c->tune.pdn, 0, 1}, {"pra", &c->tune.pra, 0, 63}, {"psb", &c->tune.psb, -1, 256}};
     for (auto& k : keys) {
       const char* f = strstr(env, k.key);
       while (f != nullptr && !((f == env || f[-1] == ',') && f[strlen(k.key)] == '=')) f = strstr(f + 1, k.key);
@@ -1723,10 +1737,12 @@ int pi0_stream_frame(pi0_ctx* c, const float* d_images, int n_views, const int32
   if (e == hipSuccess) e = hipStreamWaitEvent(sd, c->ev_prefill[cur], 0);
   if (e == hipSuccess) e = stage_inputs(c, sd, nullptr, 0, nullptr, 0, d_state, d_noise);
   if (e != hipSuccess) return fail_hip(c, e);
-  // no reading ahead here.  The read-ahead kernel keeps a wave on every SIMD for the whole loop, and the prefill that
-  // runs beside this denoise has kernels whose waves take a SIMD's whole register file (they would wait for the loop's
-  // end; measured with it: frame interval +0.8 .. +1.2 ms); warm-up blocks inside the launches cost +0.2 .. +0.3 ms:
-  // the prefill already keeps the memory busy, and the expert's cold starts hide behind it
+  // The denoise of a frame is the persistent loop on a part of the chip (frame_loop_blocks): a resident block of the
+  // loop holds a whole compute unit, so its grid is what shares the chip between the two streams - the prefill's blocks
+  // run on the compute units it leaves (measured at 1 view: 7.8 ms per frame with 160 blocks, 8.5 with 128, 9.1 as
+  // per-operation launches).  With psb=0 it is per-operation launches without any reading ahead: the read-ahead kernel
+  // keeps a wave on every SIMD for the whole loop, and the prefill's kernels have waves that take a SIMD's whole register
+  // file (they would wait for the loop's end: +0.8 .. +1.2 ms); warm-up blocks inside the launches cost +0.2 .. +0.3 ms.
   rc = execute(c, KIND_DENOISE, c->cur_views, c->cur_prompt, sd, cur, cur, false);
   if (rc != PI0_OK) return rc;
   e = launch_copy_f32(sd, at<float>(c, c->wl.xa), d_actions, (size_t)c->cfg.chunk * c->d.A);

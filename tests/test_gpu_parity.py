@@ -527,17 +527,21 @@ def test_two_stream_frames_match_sequential(reduced):
         m.pi0_denoise(d_st, d_nz, out, reduced.stream)
         reduced.stream.synchronize()
         ref.append(out.cpu().numpy())
-    for rounds in range(2):      # second round replays the captured graphs
+    # the denoise of a frame: the persistent loop on a part of the chip (default grid, and an odd one), or per-operation
+    # launches (psb=0); the second round of each replays the captured graphs
+    for tune in ("psb=-1", "psb=-1", "psb=0", "psb=0", "psb=72", "psb=-1"):
+        m.pi0_tune(tune)
         outs = [torch.empty((cfg.chunk, cfg.action_dim), dtype=torch.float32, device=dev) for _ in views[1:]]
-        say(f"[gpu] pi0_stream_frame round {rounds}")
+        say(f"[gpu] pi0_stream_frame {tune}")
         m.pi0_prefill(dev_frames[0][0], views[0], None, 0, sp)
         for k in range(1, len(views)):
             d_img, d_st, d_nz, _ = dev_frames[k]
             m.pi0_stream_frame(d_img, views[k], None, 0, d_st, d_nz, outs[k - 1], sp, sd)
         sp.synchronize()
         sd.synchronize()
+        m.pi0_device_status(sd)      # no bounded wait of the loop ran out
         for k, (o, r) in enumerate(zip(outs, ref)):
-            np.testing.assert_array_equal(o.cpu().numpy(), r, err_msg=f"frame {k + 1}")
+            np.testing.assert_array_equal(o.cpu().numpy(), r, err_msg=f"{tune} frame {k + 1}")
     # one streamed frame against the oracle itself: the chunk of frame 3 belongs to frame 2's images
     k = 3
     say("[oracle] streamed frame")
