@@ -53,6 +53,7 @@ def main() -> int:
     ap.add_argument("--prompt", type=int, default=0, help="prompt tokens (--trace-pass / --counters-pass only)")
     ap.add_argument("--counters-pass", action="store_true")
     ap.add_argument("--trace-pass", action="store_true")
+    ap.add_argument("--frames-pass", action="store_true", help="two-stream frames only (pi0_stream_frame), for a kernel trace")
     ap.add_argument("--loop-timeline", action="store_true",
                     help="in-kernel timeline of the persistent denoise loop (pi0_set_loop_trace), as text")
     ap.add_argument("--tune", type=str, default=None, help="kernel choices for tuning runs (pi0_tune)")
@@ -115,6 +116,24 @@ def main() -> int:
         m.pi0_device_status(stream)
         print(json.dumps({"mode": "counters-pass", "views": args.views, "prompt": args.prompt, "copy_bytes_each_way": 1 << 30}),
               flush=True)
+        m.close()
+        return 0
+
+    if args.frames_pass:
+        v, npr = args.views, args.prompt
+        pr = prompt if npr else None
+        m.pi0_prefill(images_of[v], v, pr, npr, sp2)
+        for _ in range(5):
+            m.pi0_stream_frame(images_of[v], v, pr, npr, state, noise, actions, sp2, sd2)
+        sp2.synchronize(); sd2.synchronize()
+        t_start = time.perf_counter()
+        for _ in range(args.steps):
+            m.pi0_stream_frame(images_of[v], v, pr, npr, state, noise, actions, sp2, sd2)
+        sp2.synchronize(); sd2.synchronize()
+        ms = (time.perf_counter() - t_start) * 1e3 / args.steps
+        m.pi0_device_status(sd2)
+        print(json.dumps({"mode": "frames-pass", "views": v, "prompt": npr, "frames": args.steps,
+                          "ms_per_frame_wall": round(ms, 4)}), flush=True)
         m.close()
         return 0
 
