@@ -30,6 +30,15 @@ __global__ __launch_bounds__(512) void attention_kernel(AttnParams p) {
   attention_body<DQK, NVB, MAXR, VRING, CPW>(p, LaunchCtx::from_block_idx(), smem_raw);
 }
 
+// The vision case cut for two resident blocks per compute unit (4 waves per SIMD: at most 128 registers, which a value
+// ring of 2 chunks gives without spilling): the 384 blocks of 3 views then run in one round instead of one and a half,
+// and a block's shorter ring is covered by its neighbour.  Same order of every sum, so the same bits.
+template <int VRING>
+__global__ __launch_bounds__(512, 4) void attention_vision2_kernel(AttnParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  attention_body<80, 3, 1, VRING, 0>(p, LaunchCtx::from_block_idx(), smem_raw);
+}
+
 template <int DQK>
 static int attn_smem(int ntot) { return 3 * (DQK / 16) * 1024 + 2 * ATT_WAVES * 32 * 4 + ntot * 2048; }
 
@@ -48,7 +57,8 @@ hipError_t attention_init_attributes() {
   }
   ATTN_VARIANTS(X)
 #undef X
-  return hipSuccess;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_vision2_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             attn_smem<80>(8));
 }
 
 hipError_t launch_attention(hipStream_t s, const AttnParams& p) {
@@ -92,7 +102,8 @@ hipError_t launch_attention(hipStream_t s, const AttnParams& p) {
     else attention_kernel<256, 8, 4, 8, 0><<<grid, dim3(512), attn_smem<256>(ntot), s>>>(p);
   } else if (p.head_dim <= 80 && p.head_dim > 64) {
     if (n0 > 8 || p.chunks1 != 0) return hipErrorInvalidValue;
-    attention_kernel<80, 3, 1, 8, 0><<<grid, dim3(512), attn_smem<80>(ntot), s>>>(p);
+    if (grid.x * grid.y > 256 && p.pf.blocks == 0) attention_vision2_kernel<2><<<grid, dim3(512), attn_smem<80>(ntot), s>>>(p);
+    else attention_kernel<80, 3, 1, 8, 0><<<grid, dim3(512), attn_smem<80>(ntot), s>>>(p);
   } else {
     return hipErrorInvalidValue;
   }
