@@ -25,8 +25,10 @@
 // NT > 1: every wave owns NT adjacent feature tiles, so that an activation fragment read from LDS
 // feeds NT MFMAs (with NT = 1 and 32-feature wave tiles the LDS read rate, one 1 KiB fragment per
 // MFMA per wave, is exactly the LDS peak, and the matrix pipe cannot be kept busy).
-template <int MB, int WN, int D, int PRO, int EPI, int NT = 1>
-__global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_kernel(GemmParams p) {
+// OCC = 2: cut for two resident blocks per compute unit (two waves per SIMD, at most 256 registers): launches with a
+// few more blocks than compute units then run in one round, and a block's cold start and epilogue overlap its neighbour's loop.
+template <int MB, int WN, int D, int PRO, int EPI, int NT = 1, int OCC = 1>
+__global__ __launch_bounds__(64 * WN) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) void gemm_kernel(GemmParams p) {
   constexpr int ROWS = MB * 32;
   constexpr int NFR = MB * 4;             // fragments per chunk
   constexpr int NP = NFR / WN;            // fragments staged per wave per chunk
@@ -459,24 +461,25 @@ int gemm_rows_per_tile(int tile) {
     case TILE_ENTRY: return 64;
     case TILE_SQ128: return 128;
     case TILE_T192: return 192;
+    case TILE_MID2: return 64;
     default: return -1;
   }
 }
 
-template <int MB, int WN, int D, int PRO, int EPI, int NT>
+template <int MB, int WN, int D, int PRO, int EPI, int NT, int OCC = 1>
 static hipError_t launch_one(hipStream_t s, const GemmParams& p, int z) {
   if (p.n_tiles % NT != 0) return hipErrorInvalidValue;
   const int nblocks_n = (p.n_tiles + WN * NT - 1) / (WN * NT);
   dim3 grid(8 * ((nblocks_n + 7) / 8) * p.m_tiles, z, 1);
   dim3 block(64 * WN, 1, 1);
   constexpr int smem = smem_bytes_for<MB, WN>();
-  gemm_kernel<MB, WN, D, PRO, EPI, NT><<<grid, block, smem, s>>>(p);
+  gemm_kernel<MB, WN, D, PRO, EPI, NT, OCC><<<grid, block, smem, s>>>(p);
   return hipGetLastError();
 }
 
-template <int MB, int WN, int D, int PRO, int EPI, int NT>
+template <int MB, int WN, int D, int PRO, int EPI, int NT, int OCC = 1>
 static hipError_t set_attr() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<MB, WN, D, PRO, EPI, NT>),
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<MB, WN, D, PRO, EPI, NT, OCC>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes_for<MB, WN>());
 }
 
@@ -500,6 +503,16 @@ static hipError_t set_attr() {
   X(TILE_WIDE128, 4, 4, 3, PRO_NONE, EPI_PARTIAL, 2) \
   X(TILE_T192, 6, 4, 3, PRO_RMS, EPI_GEGLU, 2)   \
   X(TILE_T192, 6, 4, 2, PRO_NONE, EPI_PARTIAL, 2)
+
+// ... and those cut for two resident blocks per compute unit: 64 x 128 tiles, 6 stages
+#define TALL_EPIS2(X, T, MB, WN, D)    \
+  X(T, MB, WN, D, PRO_NONE, EPI_RESID, 1, 2)   \
+  X(T, MB, WN, D, PRO_NONE, EPI_PARTIAL, 1, 2) \
+  X(T, MB, WN, D, PRO_LN, EPI_QKV, 1, 2)       \
+  X(T, MB, WN, D, PRO_LN, EPI_BF16, 1, 2)      \
+  X(T, MB, WN, D, PRO_LN, EPI_RESID, 1, 2)     \
+  X(T, MB, WN, D, PRO_RMS, EPI_QKV, 1, 2)
+#define GEMM_VARIANTS2(X) TALL_EPIS2(X, TILE_MID2, 2, 4, 6)
 
 // X(PRO, EPI, feature tiles per block, k16 steps per wave), ascending steps: vision O (k = 1152), prefix O
 // (k = 2048), vision QKV (k = 1152, 64 x 64 tiles)
@@ -545,6 +558,13 @@ hipError_t gemm_init_attributes() {
   }
   GEMM_VARIANTS(X)
 #undef X
+#define X(T, MB, WN, D, PRO, EPI, NT, OCC)                            \
+  {                                                                   \
+    hipError_t e = set_attr<MB, WN, D, PRO, EPI, NT, OCC>();          \
+    if (e != hipSuccess) return e;                                    \
+  }
+  GEMM_VARIANTS2(X)
+#undef X
   return hipSuccess;
 }
 
@@ -572,7 +592,7 @@ hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmPara
   if (pro != PRO_NONE && (z_splits != 1 || p.rowstat == nullptr)) return hipErrorInvalidValue;
   if (epi != EPI_PARTIAL && z_splits != 1) return hipErrorInvalidValue;
   if (p.m_tiles < 1) return hipErrorInvalidValue;
-  if (tile == TILE_BIG || tile == TILE_MID || tile == TILE_SMALL || tile == TILE_WIDE || tile == TILE_WIDE128 || tile == TILE_T192 || tile == TILE_ENTRY) {
+  if (tile == TILE_BIG || tile == TILE_MID || tile == TILE_SMALL || tile == TILE_WIDE || tile == TILE_WIDE128 || tile == TILE_T192 || tile == TILE_ENTRY || tile == TILE_MID2) {
     // partial row statistics: planes of stat_rows rows, every row a block touches inside a plane
     if (pro != PRO_NONE && p.rowstat_parts > 1 && (p.stat_rows < p.M || p.rowstat_parts > STAT_PARTS_MAX)) return hipErrorInvalidValue;
     if (epi == EPI_RESID && p.stat_out != nullptr && p.stat_rows < p.M + p.row_offset) return hipErrorInvalidValue;
@@ -641,6 +661,13 @@ hipError_t launch_gemm(hipStream_t s, int tile, int pro, int epi, const GemmPara
     return launch_one<MB, WN, D, PRO, EPI, NT>(s, p, z_splits);                 \
   }
   GEMM_VARIANTS(X)
+#undef X
+#define X(T, MB, WN, D, PRO, EPI, NT, OCC)                                     \
+  if (tile == T && pro == PRO && epi == EPI) {                                  \
+    if (p.m_tiles * MB * 32 < p.M) return hipErrorInvalidValue;                 \
+    return launch_one<MB, WN, D, PRO, EPI, NT, OCC>(s, p, z_splits);            \
+  }
+  GEMM_VARIANTS2(X)
 #undef X
   return hipErrorInvalidValue;
 }

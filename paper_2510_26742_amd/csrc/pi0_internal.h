@@ -172,7 +172,8 @@ enum GemmTile {
   TILE_WIDE128 = 7,       // 128 tokens x 256 features per block, 3 stages
   TILE_ENTRY = 8,         // 64 tokens x 32 / 64 features per block, k <= 2048 split over 8 waves, every load issued at entry
   TILE_SQ128 = 9,         // 128 tokens x 128 features per block (4 waves), 5 stages: the mid-size GEMMs at three views
-  TILE_T192 = 10          // 192 tokens x 256 features per block, 2 stages: 768 tokens in four tiles
+  TILE_T192 = 10,         // 192 tokens x 256 features per block, 2 stages: 768 tokens in four tiles
+  TILE_MID2 = 11          // 64 tokens x 128 features as TILE_MID, cut for two resident blocks per compute unit
 };
 
 // ------------------------------------------------------------------------------------------

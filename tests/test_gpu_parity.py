@@ -654,6 +654,7 @@ def test_reading_ahead_changes_no_bit():
     "lgu=7,ld=6,zld=8",                                                                # ... and the other way round
     "lgu=10,ld=10,zld=8",                                                              # 192-token tiles (768 tokens in four)
     "vis=9,vqkv=9,vup=9,lqkv=9,vo=9,vd=9,lo=9,zvo=2,zvd=3,zlo=2,fko=0,fkl=0",          # 128x128 tiles everywhere they exist
+    "vqkv=11,vup=11,lqkv=11,vo=11,vd=11,lo=11,fko=0,fkl=0",                            # 64x128 tiles cut for two resident blocks per compute unit
     "fko=1,fkl=1",                                                                     # O projections over the whole k range, residual epilogue in the GEMM
     "fko=0,fkl=0",                                                                     # ... and as split-K partial GEMMs + reduction
     "ras=64,ral=2,rat=128,rad=8",                                                      # expert read-ahead kernel: other shape, two layers ahead
